@@ -1,0 +1,141 @@
+"""Layer lists and shapes of the benchmark stages.
+
+A stage model is a run of consecutive layers (Sec. 3.2); a mini-batch is split
+into M micro-batches of size B.  Micro-batch m holds samples [m*B, (m+1)*B).
+
+Layer dictionaries (keys are plain ints/floats/bools):
+  conv2d       cin cout k stride pad groups bias
+  batchnorm2d  c eps
+  relu / relu6 / gelu / res_begin / res_add / global_avgpool / maxpool2x2 / softmax_ce
+  linear       cin cout bias
+  layernorm    d eps
+  mha          d heads
+"""
+from dataclasses import dataclass, field
+from typing import List, Tuple
+
+
+def conv(cin, cout, k, stride=1, pad=0, groups=1, bias=False):
+    return dict(kind="conv2d", cin=cin, cout=cout, k=k, stride=stride, pad=pad,
+                groups=groups, bias=bool(bias))
+
+
+def bn(c, eps=1e-5):
+    return dict(kind="batchnorm2d", c=c, eps=eps)
+
+
+def simple(kind):
+    return dict(kind=kind)
+
+
+def linear(cin, cout, bias=True):
+    return dict(kind="linear", cin=cin, cout=cout, bias=bool(bias))
+
+
+def irb(cin, cout, stride, expand):
+    """MobileNetV2 inverted-residual block: 1x1 expand, BN, ReLU6, 3x3 depthwise,
+    BN, ReLU6, 1x1 project, BN, residual add iff stride 1 and cin == cout.
+    The expansion conv is absent when expand == 1."""
+    hid = cin * expand
+    res = stride == 1 and cin == cout
+    L = []
+    if res:
+        L.append(simple("res_begin"))
+    if expand != 1:
+        L += [conv(cin, hid, 1), bn(hid), simple("relu6")]
+    L += [conv(hid, hid, 3, stride, 1, groups=hid), bn(hid), simple("relu6")]
+    L += [conv(hid, cout, 1), bn(cout)]
+    if res:
+        L.append(simple("res_add"))
+    return L
+
+
+# (t, c, n, s): expansion, output channels, repeats, stride of the first repeat
+MBV2_SCHEDULE = [(1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2),
+                 (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1)]
+
+
+def mobilenetv2_layers(num_classes=1000, schedule=MBV2_SCHEDULE, stem=32, last=1280):
+    L = [conv(3, stem, 3, 2, 1), bn(stem), simple("relu6")]
+    cin = stem
+    for t, c, n, s in schedule:
+        for i in range(n):
+            L += irb(cin, c, s if i == 0 else 1, t)
+            cin = c
+    L += [conv(cin, last, 1), bn(last), simple("relu6"), simple("global_avgpool"),
+          linear(last, num_classes), simple("softmax_ce")]
+    return L
+
+
+def encoder_layer(d, heads, ffn, eps=1e-5):
+    """Post-LN encoder layer: h = LN(x + MHA(x)); y = LN(h + W2 GELU(W1 h + b1) + b2)."""
+    return [simple("res_begin"), dict(kind="mha", d=d, heads=heads), simple("res_add"),
+            dict(kind="layernorm", d=d, eps=eps),
+            simple("res_begin"), linear(d, ffn), simple("gelu"), linear(ffn, d),
+            simple("res_add"), dict(kind="layernorm", d=d, eps=eps)]
+
+
+def vgg_layers(cin, c):
+    return [conv(cin, c, 3, 1, 1, bias=True), simple("relu"),
+            conv(c, c, 3, 1, 1, bias=True), simple("relu"),
+            conv(c, c, 3, 1, 1, bias=True), simple("relu"), simple("maxpool2x2")]
+
+
+@dataclass
+class StageConfig:
+    name: str
+    layers: List[dict]
+    B: int
+    M: int
+    in_shape: Tuple[int, ...]      # per-sample logical shape: (C,H,W) or (S,D)
+    dtype: str                     # "f32" | "bf16"  (bf16 = bf16 operands, fp32 accumulate/master)
+    layout: str                    # boundary layout: "nchw" | "nhwc" | "bsd"
+    needs_input_grad: bool
+    seed: int
+    lr: float = 0.01
+    momentum: float = 0.9
+    init: str = "kaiming"          # "kaiming" | "normal0.02"
+    note: str = ""
+
+    @property
+    def loss_tail(self):
+        return self.layers[-1]["kind"] == "softmax_ce"
+
+
+def cfg1(B=4, M=2, hw=16, seed=1001):
+    L = irb(32, 32, 1, 6) + irb(32, 32, 1, 6) + [simple("global_avgpool"), linear(32, 10),
+                                               simple("softmax_ce")]
+    return StageConfig("cfg1_tiny_cnn", L, B, M, (32, hw, hw), "f32", "nchw", True, seed)
+
+
+def cfg2(B=32, M=4, hw=56, seed=1002):
+    L = irb(24, 32, 2, 6) + irb(32, 32, 1, 6) + irb(32, 32, 1, 6)
+    return StageConfig("cfg2_mbv2_stage", L, B, M, (24, hw, hw), "f32", "nchw", True, seed)
+
+
+def cfg3(B=8, M=8, hw=224, seed=1003, num_classes=1000):
+    return StageConfig("cfg3_mbv2_full", mobilenetv2_layers(num_classes), B, M, (3, hw, hw),
+                       "f32", "nchw", False, seed)
+
+
+def cfg4(B=32, M=4, hw=56, cin=128, c=256, seed=1004):
+    return StageConfig("cfg4_vgg_bf16", vgg_layers(cin, c), B, M, (cin, hw, hw), "bf16",
+                       "nhwc", True, seed)
+
+
+def cfg5(B=32, M=4, S=128, d=512, heads=8, ffn=2048, nlayers=6, seed=1005):
+    L = []
+    for _ in range(nlayers):
+        L += encoder_layer(d, heads, ffn)
+    return StageConfig("cfg5_bert_small_bf16", L, B, M, (S, d), "bf16", "bsd", True, seed,
+                       init="normal0.02")
+
+
+CONFIGS = {
+    "cfg1": cfg1, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4, "cfg5": cfg5,
+}
+
+
+def get_config(name, **kw):
+    """Full-size config by name ("cfg1".."cfg5"); keyword overrides shrink it for tests."""
+    return CONFIGS[name](**kw)
