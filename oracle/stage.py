@@ -62,6 +62,8 @@ class OracleStage:
         self.G = np.zeros(off, F)
         self.V = np.zeros(off, F)
         self.stash = {}
+        self.keep_acts = False     # tests may ask for every layer's output (logical layout)
+        self.acts = {}
         self.loss_tail = self.layers[-1]["kind"] == "softmax_ce"
         # BatchNorm running statistics (tracked, never scored)
         self.running = {i: [np.zeros(l["c"], F), np.ones(l["c"], F)]
@@ -99,7 +101,10 @@ class OracleStage:
         res = []
         loss = None
         logits = None
+        trace = []
         for i, l in enumerate(self.layers):
+            if i > 0 and self.keep_acts:
+                trace.append(a)
             k = l["kind"]
             P = self._p(self.W, i)
             if k == "conv2d":
@@ -151,6 +156,9 @@ class OracleStage:
             else:
                 raise ValueError(k)
         self.stash[mb] = saved
+        if self.keep_acts:
+            trace.append(a)
+            self.acts[mb] = trace          # trace[i] = output of layer i
         if self.loss_tail:
             return logits, loss
         return self._to_boundary(a), None

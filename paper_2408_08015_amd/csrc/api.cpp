@@ -1,0 +1,277 @@
+// C ABI of the stage-training library (see include/asteroid.h): argument checks, the
+// 1F1B call discipline (Sec. 3.2), allocation in create, and the flat-vector accessors.
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+#include "kernels_bf16.h"
+#include "stage.h"
+
+struct asteroid_stage {
+  ast::Stage s;
+};
+
+namespace {
+thread_local std::string g_err;
+
+ast_status fail(ast_status code, const std::string& msg) {
+  g_err = msg;
+  return code;
+}
+ast_status hip_fail(hipError_t e, const char* what) {
+  g_err = std::string(what) + ": " + hipGetErrorString(e);
+  return e == hipErrorOutOfMemory ? AST_ENOMEM : AST_EHIP;
+}
+#define HIPCHK(call, what)                        \
+  do {                                            \
+    hipError_t e_ = (call);                       \
+    if (e_ != hipSuccess) return hip_fail(e_, what); \
+  } while (0)
+
+void free_stage(ast::Stage& s) {
+  if (s.W) (void)hipFree(s.W);
+  if (s.G) (void)hipFree(s.G);
+  if (s.V) (void)hipFree(s.V);
+  if (s.shadow) (void)hipFree(s.shadow);
+  if (s.running) (void)hipFree(s.running);
+  if (s.ws) (void)hipFree(s.ws);
+  for (char* p : s.slots)
+    if (p) (void)hipFree(p);
+  s.slots.clear();
+  s.W = s.G = s.V = nullptr;
+  s.shadow = nullptr;
+  s.running = nullptr;
+  s.ws = nullptr;
+}
+
+// initial parameter values: 0, with BatchNorm / LayerNorm gamma at 1
+std::vector<float> initial_params(const ast::Stage& s) {
+  std::vector<float> w(s.nparams, 0.f);
+  for (const ast::Op& op : s.ops)
+    if (op.kind == ast::OP_BN || op.kind == ast::OP_LAYERNORM)
+      for (int c = 0; c < op.cin; ++c) w[op.w_off + c] = 1.f;
+  return w;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+}  // namespace
+
+extern "C" {
+
+const char* asteroid_last_error(void) { return g_err.c_str(); }
+
+int32_t asteroid_kp(int32_t P, int32_t p) {
+  if (P <= 0 || p < 0 || p >= P) return -1;
+  return 2 * (P - p) - 1;
+}
+
+ast_status asteroid_stage_create(const ast_layer* layers, int32_t n_layers, const ast_stage_cfg* cfg,
+                                 void* hip_stream, asteroid_stage** out) {
+  if (out) *out = nullptr;
+  if (!layers || n_layers <= 0 || !cfg || !out) return fail(AST_EINVAL, "create: NULL argument or no layers");
+  if (cfg->K > cfg->M) return fail(AST_EINVAL, "create: K must not exceed M");
+  asteroid_stage* h = new (std::nothrow) asteroid_stage();
+  if (!h) return fail(AST_ENOMEM, "create: host allocation failed");
+  ast::Stage& s = h->s;
+  s.cfg = *cfg;
+  s.layers.assign(layers, layers + n_layers);
+  s.stream = static_cast<hipStream_t>(hip_stream);
+  std::string err;
+  ast_status r = ast::build_plan(s, err);
+  if (r != AST_OK) {
+    delete h;
+    return fail(r, "create: " + err);
+  }
+  auto bail = [&](hipError_t e, const char* what) {
+    ast_status st = hip_fail(e, what);
+    free_stage(s);
+    delete h;
+    return st;
+  };
+  hipError_t e;
+  const size_t pbytes = (s.nparams + 4) * sizeof(float);
+  if ((e = hipMalloc((void**)&s.W, pbytes)) != hipSuccess) return bail(e, "create: hipMalloc(W)");
+  if ((e = hipMalloc((void**)&s.G, pbytes)) != hipSuccess) return bail(e, "create: hipMalloc(G)");
+  if ((e = hipMalloc((void**)&s.V, pbytes)) != hipSuccess) return bail(e, "create: hipMalloc(V)");
+  if (s.shadow_elems && (e = hipMalloc((void**)&s.shadow, s.shadow_elems * 2 + 16)) != hipSuccess)
+    return bail(e, "create: hipMalloc(weight copies)");
+  if (s.running_floats && (e = hipMalloc((void**)&s.running, s.running_floats * sizeof(float))) != hipSuccess)
+    return bail(e, "create: hipMalloc(running stats)");
+  if ((e = hipMalloc((void**)&s.ws, s.ws_bytes)) != hipSuccess) return bail(e, "create: hipMalloc(workspace)");
+  s.slots.assign(cfg->K, nullptr);
+  for (int k = 0; k < cfg->K; ++k)
+    if ((e = hipMalloc((void**)&s.slots[k], s.slot_bytes)) != hipSuccess) return bail(e, "create: hipMalloc(stash)");
+  if ((e = hipMemset(s.G, 0, pbytes)) != hipSuccess) return bail(e, "create: memset");
+  if ((e = hipMemset(s.V, 0, pbytes)) != hipSuccess) return bail(e, "create: memset");
+  if ((e = hipMemset(s.ws, 0, s.ws_bytes)) != hipSuccess) return bail(e, "create: memset");
+  if (s.running) {
+    std::vector<float> rs(s.running_floats, 0.f);
+    for (const ast::Op& op : s.ops)
+      if (op.kind == ast::OP_BN)
+        for (int c = 0; c < op.cin; ++c) rs[op.run_off + op.cin + c] = 1.f;
+    if ((e = hipMemcpy(s.running, rs.data(), rs.size() * sizeof(float), hipMemcpyHostToDevice)) != hipSuccess)
+      return bail(e, "create: memcpy");
+  }
+  std::vector<float> w0 = initial_params(s);
+  w0.resize(s.nparams + 4, 0.f);
+  if ((e = hipMemcpy(s.W, w0.data(), pbytes, hipMemcpyHostToDevice)) != hipSuccess) return bail(e, "create: memcpy");
+  s.mb_slot.assign(cfg->M, -1);
+  for (int k = cfg->K - 1; k >= 0; --k) s.free_slots.push_back(k);
+  r = ast::refresh_shadow(s, err);
+  if (r == AST_OK && (e = hipStreamSynchronize(s.stream)) != hipSuccess) return bail(e, "create: sync");
+  if (r != AST_OK) {
+    free_stage(s);
+    delete h;
+    return fail(r, "create: " + err);
+  }
+  *out = h;
+  return AST_OK;
+}
+
+ast_status asteroid_stage_forward(asteroid_stage* h, int32_t mb, const void* x_dev, const int32_t* labels_dev,
+                                  void* y_dev, float* loss_dev) {
+  if (!h) return fail(AST_EINVAL, "forward: NULL stage");
+  ast::Stage& s = h->s;
+  if (mb < 0 || mb >= s.cfg.M) return fail(AST_ESTATE, "forward: micro-batch index outside [0, M)");
+  if (mb != s.next_fwd) return fail(AST_ESTATE, "forward: micro-batches are forwarded in order, once per round");
+  if (s.next_fwd - s.next_bwd >= s.cfg.K) return fail(AST_ESTATE, "forward: K forwarded micro-batches await their backward");
+  if (!x_dev) return fail(AST_EINVAL, "forward: x_dev is NULL");
+  if (!aligned16(x_dev) || !aligned16(y_dev)) return fail(AST_EINVAL, "forward: buffers must be 16-byte aligned");
+  if (s.loss_tail && !labels_dev) return fail(AST_EINVAL, "forward: labels_dev required for a SOFTMAX_CE tail");
+  if (!s.loss_tail && !y_dev) return fail(AST_EINVAL, "forward: y_dev is NULL");
+  int slot = s.free_slots.back();
+  std::string err;
+  ast_status r = ast::run_forward(s, slot, x_dev, labels_dev, y_dev, loss_dev, err);
+  if (r != AST_OK) return fail(r, err);
+  s.free_slots.pop_back();
+  s.mb_slot[mb] = slot;
+  s.next_fwd++;
+  return AST_OK;
+}
+
+ast_status asteroid_stage_backward(asteroid_stage* h, int32_t mb, const void* dy_dev, void* dx_dev) {
+  if (!h) return fail(AST_EINVAL, "backward: NULL stage");
+  ast::Stage& s = h->s;
+  if (mb < 0 || mb >= s.cfg.M) return fail(AST_ESTATE, "backward: micro-batch index outside [0, M)");
+  if (mb >= s.next_fwd) return fail(AST_ESTATE, "backward: micro-batch was not forwarded");
+  if (mb != s.next_bwd) return fail(AST_ESTATE, "backward: backwards run in micro-batch order, once each");
+  if (!s.loss_tail && !dy_dev) return fail(AST_EINVAL, "backward: dy_dev is NULL");
+  if (s.loss_tail && dy_dev) return fail(AST_EINVAL, "backward: dy_dev must be NULL for a SOFTMAX_CE tail");
+  if (s.cfg.needs_input_grad && !dx_dev) return fail(AST_EINVAL, "backward: dx_dev is NULL");
+  if (!s.cfg.needs_input_grad && dx_dev) return fail(AST_EINVAL, "backward: dx_dev must be NULL when needs_input_grad == 0");
+  if (!aligned16(dy_dev) || !aligned16(dx_dev)) return fail(AST_EINVAL, "backward: buffers must be 16-byte aligned");
+  int slot = s.mb_slot[mb];
+  std::string err;
+  ast_status r = ast::run_backward(s, slot, dy_dev, dx_dev, err);
+  if (r != AST_OK) return fail(r, err);
+  s.mb_slot[mb] = -1;
+  s.free_slots.push_back(slot);  // the backward releases the stash
+  s.next_bwd++;
+  return AST_OK;
+}
+
+ast_status asteroid_stage_step(asteroid_stage* h, float lr, float momentum) {
+  if (!h) return fail(AST_EINVAL, "step: NULL stage");
+  ast::Stage& s = h->s;
+  if (s.next_bwd != s.cfg.M) return fail(AST_ESTATE, "step: not all M micro-batches have been forwarded and backwarded");
+  std::string err;
+  ast_status r = ast::run_step(s, lr, momentum, err);
+  if (r != AST_OK) return fail(r, err);
+  s.next_fwd = s.next_bwd = 0;
+  return AST_OK;
+}
+
+void asteroid_stage_destroy(asteroid_stage* h) {
+  if (!h) return;
+  (void)hipStreamSynchronize(h->s.stream);
+  free_stage(h->s);
+  delete h;
+}
+
+size_t asteroid_stage_num_params(const asteroid_stage* h) { return h ? h->s.nparams : 0; }
+
+static ast_status copy_flat(asteroid_stage* h, float* dev, float* host_out, const float* host_in, const char* what) {
+  if (!h || (!host_out && !host_in)) return fail(AST_EINVAL, std::string(what) + ": NULL argument");
+  ast::Stage& s = h->s;
+  HIPCHK(hipStreamSynchronize(s.stream), what);
+  if (host_in) HIPCHK(hipMemcpy(dev, host_in, s.nparams * sizeof(float), hipMemcpyHostToDevice), what);
+  else HIPCHK(hipMemcpy(host_out, dev, s.nparams * sizeof(float), hipMemcpyDeviceToHost), what);
+  return AST_OK;
+}
+
+ast_status asteroid_stage_set_params(asteroid_stage* h, const float* host_flat) {
+  ast_status r = copy_flat(h, h ? h->s.W : nullptr, nullptr, host_flat, "set_params");
+  if (r != AST_OK) return r;
+  std::string err;
+  r = ast::refresh_shadow(h->s, err);
+  if (r != AST_OK) return fail(r, err);
+  HIPCHK(hipStreamSynchronize(h->s.stream), "set_params");
+  return AST_OK;
+}
+ast_status asteroid_stage_get_params(asteroid_stage* h, float* host_flat) {
+  return copy_flat(h, h ? h->s.W : nullptr, host_flat, nullptr, "get_params");
+}
+ast_status asteroid_stage_get_grads(asteroid_stage* h, float* host_flat) {
+  return copy_flat(h, h ? h->s.G : nullptr, host_flat, nullptr, "get_grads");
+}
+ast_status asteroid_stage_set_velocity(asteroid_stage* h, const float* host_flat) {
+  return copy_flat(h, h ? h->s.V : nullptr, nullptr, host_flat, "set_velocity");
+}
+ast_status asteroid_stage_get_velocity(asteroid_stage* h, float* host_flat) {
+  return copy_flat(h, h ? h->s.V : nullptr, host_flat, nullptr, "get_velocity");
+}
+
+ast_status asteroid_stage_memory(const asteroid_stage* h, size_t* mod, size_t* opt, size_t* act_per_mb,
+                                 size_t* workspace) {
+  if (!h) return fail(AST_EINVAL, "memory: NULL stage");
+  const ast::Stage& s = h->s;
+  if (mod) *mod = 2 * s.nparams * sizeof(float) + s.shadow_elems * 2;
+  if (opt) *opt = s.nparams * sizeof(float);
+  if (act_per_mb) *act_per_mb = s.slot_bytes;
+  if (workspace) *workspace = s.ws_bytes;
+  return AST_OK;
+}
+
+ast_status asteroid_stage_plan_memory(const ast_layer* layers, int32_t n_layers, const ast_stage_cfg* cfg,
+                                      size_t* mod, size_t* opt, size_t* act_per_mb, size_t* workspace) {
+  if (!layers || n_layers <= 0 || !cfg) return fail(AST_EINVAL, "plan_memory: NULL argument or no layers");
+  if (cfg->K > cfg->M) return fail(AST_EINVAL, "plan_memory: K must not exceed M");
+  asteroid_stage tmp;
+  tmp.s.cfg = *cfg;
+  tmp.s.layers.assign(layers, layers + n_layers);
+  std::string err;
+  ast_status r = ast::build_plan(tmp.s, err);
+  if (r != AST_OK) return fail(r, "plan_memory: " + err);
+  return asteroid_stage_memory(&tmp, mod, opt, act_per_mb, workspace);
+}
+
+ast_status asteroid_stage_debug_activation(asteroid_stage* h, int32_t mb, int32_t layer, float* host_out,
+                                           size_t* n_out) {
+  if (!h) return fail(AST_EINVAL, "debug_activation: NULL stage");
+  ast::Stage& s = h->s;
+  if (layer < 0 || layer >= (int)s.layers.size() || s.layer_act[layer] < 0)
+    return fail(AST_EINVAL, "debug_activation: layer has no materialised output");
+  if (mb < 0 || mb >= s.cfg.M || s.mb_slot[mb] < 0) return fail(AST_ESTATE, "debug_activation: micro-batch has no live stash");
+  int id = s.layer_act[layer];
+  const ast::Act& A = s.acts[id];
+  if (id == s.final_act && !s.loss_tail) return fail(AST_EINVAL, "debug_activation: the stage output lives in the caller's buffer");
+  if (n_out) *n_out = A.elems;
+  if (!host_out) return AST_OK;
+  HIPCHK(hipStreamSynchronize(s.stream), "debug_activation");
+  const char* src = s.slots[s.mb_slot[mb]] + A.slot_off;
+  if (A.esize == 4) {
+    HIPCHK(hipMemcpy(host_out, src, A.bytes, hipMemcpyDeviceToHost), "debug_activation");
+  } else {
+    std::vector<unsigned short> tmp(A.elems);
+    HIPCHK(hipMemcpy(tmp.data(), src, A.bytes, hipMemcpyDeviceToHost), "debug_activation");
+    for (size_t i = 0; i < A.elems; ++i) {
+      uint32_t u = ((uint32_t)tmp[i]) << 16;
+      std::memcpy(&host_out[i], &u, 4);
+    }
+  }
+  return AST_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,324 @@
+// Plan execution: forward, backward and optimizer step of a stage, as kernel launches
+// on the stage's stream.  No allocation, no host synchronisation.
+#include "kernels.h"
+#include "kernels_bf16.h"
+#include "stage.h"
+
+namespace ast {
+
+namespace {
+
+struct Ctx {
+  Stage& s;
+  char* slot;
+  int final_act;
+  int launches = 0;
+};
+
+inline int final_act_of(const Stage& s) { return s.final_act; }
+
+inline void* act_ptr(Ctx& c, int id) {
+  if (id == c.final_act && !c.s.loss_tail && id != 0) return c.s.cur_y;
+  return c.slot + c.s.acts[id].slot_off;
+}
+inline void* grad_ptr(Ctx& c, int id) {
+  while (c.s.acts[id].grad_alias >= 0) id = c.s.acts[id].grad_alias;
+  if (id == 0) return c.s.cur_dx;  // may be NULL: the input gradient is not wanted
+  if (id == c.final_act && !c.s.loss_tail) return const_cast<void*>(c.s.cur_dy);  // id != 0 here
+  return c.s.ws + c.s.acts[id].grad_off;
+}
+inline char* scratch(Ctx& c) { return c.s.ws + c.s.scratch_off; }
+inline float* scratch2(Ctx& c) { return reinterpret_cast<float*>(c.s.ws + c.s.scratch2_off); }
+inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+typedef const float* cf;
+typedef const bf16_t* cb;
+
+void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
+  Stage& s = c.s;
+  hipStream_t st = s.stream;
+  const Act& I = s.acts[op.in];
+  const int HW = I.h * I.w;
+  switch (op.kind) {
+    case OP_CONV_PW:
+      pw_conv_f32(st, s.W + op.w_off, op.cin, 1, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out),
+                  op.has_bias ? s.W + op.b_off : nullptr, nullptr, I.n, op.cin, op.cout, HW);
+      break;
+    case OP_CONV_DW:
+      dw3x3_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, (float*)act_ptr(c, op.out), I.n, I.c, I.h,
+                    I.w, op.stride);
+      break;
+    case OP_CONV_DIRECT:
+      conv_direct_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, op.has_bias ? s.W + op.b_off : nullptr,
+                          (float*)act_ptr(c, op.out), I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride,
+                          op.pad, op.groups);
+      break;
+    case OP_CONV_IGEMM:
+      conv_bf16_fwd(st, (cb)act_ptr(c, op.in), s.shadow + op.sh_off, op.has_bias ? s.W + op.b_off : nullptr,
+                    (bf16_t*)act_ptr(c, op.out), I.n, I.h, I.w, op.cin, op.cout, op.k, op.act);
+      break;
+    case OP_BN: {
+      float* aux = reinterpret_cast<float*>(c.slot + op.aux_off);
+      bn_stats_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, s.W + op.b_off, aux, aux + 2 * I.c,
+                   s.running + op.run_off, reinterpret_cast<double*>(scratch(c)), I.n, I.c, HW, op.eps);
+      bn_apply_f32(st, (cf)act_ptr(c, op.in), aux + 2 * I.c, op.skip >= 0 ? (cf)act_ptr(c, op.skip) : nullptr,
+                   (float*)act_ptr(c, op.out), I.n, I.c, HW, op.act);
+      break;
+    }
+    case OP_ACT:
+      if (s.bf16) act_fwd_bf16(st, (cb)act_ptr(c, op.in), (bf16_t*)act_ptr(c, op.out), I.elems, op.act);
+      else act_fwd_f32(st, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out), I.elems, op.act);
+      break;
+    case OP_RES_BEGIN:
+      break;
+    case OP_RES_ADD:
+      if (s.bf16) add_bf16(st, (cb)act_ptr(c, op.in), (cb)act_ptr(c, op.skip), (bf16_t*)act_ptr(c, op.out), I.elems);
+      else add_f32(st, (cf)act_ptr(c, op.in), (cf)act_ptr(c, op.skip), (float*)act_ptr(c, op.out), I.elems);
+      break;
+    case OP_GAP:
+      gap_fwd_f32(st, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out), I.n * I.c, HW);
+      break;
+    case OP_MAXPOOL:
+      if (s.bf16) maxpool_fwd_bf16(st, (cb)act_ptr(c, op.in), (bf16_t*)act_ptr(c, op.out), I.n, I.h, I.w, I.c);
+      else maxpool_fwd_f32(st, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out), I.n * I.c, I.h, I.w);
+      break;
+    case OP_LINEAR:
+      if (s.bf16) {
+        linear_bf16_fwd(st, (cb)act_ptr(c, op.in), s.shadow + op.sh_off, op.has_bias ? s.W + op.b_off : nullptr,
+                        (bf16_t*)act_ptr(c, op.out), op.act == 3 ? (bf16_t*)act_ptr(c, op.skip) : nullptr,
+                        (size_t)I.n * I.h * I.w, op.cin, op.cout, op.act);
+      } else {
+        linear_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, op.has_bias ? s.W + op.b_off : nullptr,
+                       (float*)act_ptr(c, op.out), I.n, op.cin, op.cout);
+      }
+      break;
+    case OP_SOFTMAX_CE: {
+      float* p = reinterpret_cast<float*>(c.slot + op.aux_off);
+      float* row_loss = p + (size_t)I.n * I.c;
+      int32_t* lab = reinterpret_cast<int32_t*>(row_loss + I.n);
+      copy_bytes(st, labels, lab, sizeof(int32_t) * I.n);
+      softmax_ce_fwd_f32(st, (cf)act_ptr(c, op.in), lab, p, row_loss, loss, I.n, I.c,
+                         1.f / ((float)s.cfg.M * (float)s.cfg.B));
+      if (s.cur_y) copy_bytes(st, act_ptr(c, op.in), s.cur_y, I.bytes);
+      break;
+    }
+    case OP_LAYERNORM:
+      layernorm_fwd_bf16(st, (cb)act_ptr(c, op.in), s.W + op.w_off, s.W + op.b_off, (bf16_t*)act_ptr(c, op.out),
+                         reinterpret_cast<float*>(c.slot + op.aux_off), (size_t)I.n * I.h, I.c, op.eps);
+      break;
+    case OP_MHA: {
+      const int D = op.cin;
+      const size_t R = (size_t)I.n * I.h;
+      bf16_t* qkv = reinterpret_cast<bf16_t*>(c.slot + op.aux_off);
+      bf16_t* o = qkv + R * 3 * D;
+      float* lse = reinterpret_cast<float*>(o + R * D);
+      const float* bq = s.W + op.w_off + (size_t)3 * D * D;
+      const float* bo = bq + 3 * D + (size_t)D * D;
+      linear_bf16_fwd(st, (cb)act_ptr(c, op.in), s.shadow + op.sh_off, bq, qkv, nullptr, R, D, 3 * D, 0);
+      attention_fwd_bf16(st, qkv, o, lse, I.n, I.h, D, op.heads);
+      linear_bf16_fwd(st, o, s.shadow + op.sh_off + (size_t)3 * D * D, bo, (bf16_t*)act_ptr(c, op.out), nullptr,
+                      R, D, D, 0);
+      break;
+    }
+  }
+}
+
+void bwd_op(Ctx& c, const Op& op) {
+  Stage& s = c.s;
+  hipStream_t st = s.stream;
+  const Act& I = s.acts[op.in];
+  const int HW = I.h * I.w;
+  void* gin = grad_ptr(c, op.in);  // NULL: not wanted
+  switch (op.kind) {
+    case OP_CONV_PW: {
+      cf g = (cf)grad_ptr(c, op.out);
+      if (gin)
+        pw_conv_f32(st, s.W + op.w_off, 1, op.cin, g, (float*)gin, nullptr,
+                    op.dgrad_add >= 0 ? (cf)grad_ptr(c, op.dgrad_add) : nullptr, I.n, op.cout, op.cin, HW);
+      pw_wgrad_f32(st, g, (cf)act_ptr(c, op.in), reinterpret_cast<float*>(scratch(c)), s.G + op.w_off, I.n,
+                   op.cin, op.cout, HW);
+      if (op.has_bias) channel_sum_acc_f32(st, g, s.G + op.b_off, I.n, op.cout, HW);
+      break;
+    }
+    case OP_CONV_DW: {
+      cf g = (cf)grad_ptr(c, op.out);
+      if (gin) dw3x3_dgrad_f32(st, g, s.W + op.w_off, (float*)gin, I.n, I.c, I.h, I.w, op.stride);
+      dw3x3_wgrad_f32(st, g, (cf)act_ptr(c, op.in), reinterpret_cast<float*>(scratch(c)), s.G + op.w_off, I.n,
+                      I.c, I.h, I.w, op.stride);
+      break;
+    }
+    case OP_CONV_DIRECT: {
+      cf g = (cf)grad_ptr(c, op.out);
+      const Act& O = s.acts[op.out];
+      if (gin)
+        conv_direct_dgrad_f32(st, g, s.W + op.w_off, (float*)gin, I.n, op.cin, I.h, I.w, op.cout, op.k,
+                              op.stride, op.pad, op.groups);
+      conv_direct_wgrad_f32(st, g, (cf)act_ptr(c, op.in), s.G + op.w_off, I.n, op.cin, I.h, I.w, op.cout,
+                            op.k, op.stride, op.pad, op.groups);
+      if (op.has_bias) channel_sum_acc_f32(st, g, s.G + op.b_off, I.n, op.cout, O.h * O.w);
+      break;
+    }
+    case OP_CONV_IGEMM: {
+      const Act& O = s.acts[op.out];
+      cb g = (cb)grad_ptr(c, op.out);
+      char* sc = scratch(c);
+      if (op.act) {  // mask by the ReLU output
+        bf16_t* gm = reinterpret_cast<bf16_t*>(sc);
+        act_bwd_bf16(st, g, (cb)act_ptr(c, op.out), gm, O.elems, op.act);
+        g = gm;
+        sc += align256(O.bytes);
+      }
+      if (gin) conv_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin, I.n, I.h, I.w, op.cin, op.cout, op.k);
+      conv_bf16_wgrad(st, g, (cb)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr, sc,
+                      I.n, I.h, I.w, op.cin, op.cout, op.k);
+      break;
+    }
+    case OP_BN: {
+      float* aux = reinterpret_cast<float*>(c.slot + op.aux_off);
+      bn_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), aux, aux + 2 * I.c, s.W + op.w_off,
+                 (float*)gin, s.G + op.w_off, s.G + op.b_off, reinterpret_cast<double*>(scratch(c)),
+                 scratch2(c), I.n, I.c, HW, op.act);
+      break;
+    }
+    case OP_ACT:
+      if (!gin) break;
+      if (s.bf16)
+        act_bwd_bf16(st, (cb)grad_ptr(c, op.out), op.act == 3 ? (cb)act_ptr(c, op.in) : (cb)act_ptr(c, op.out),
+                     (bf16_t*)gin, I.elems, op.act);
+      else
+        act_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), (float*)gin, I.elems, op.act);
+      break;
+    case OP_RES_BEGIN:
+      if (op.noop_bwd || !gin || op.skip < 0) break;
+      if (s.bf16) add_bf16(st, (cb)gin, (cb)grad_ptr(c, op.skip), (bf16_t*)gin, I.elems);
+      else add_f32(st, (cf)gin, (cf)grad_ptr(c, op.skip), (float*)gin, I.elems);
+      break;
+    case OP_RES_ADD:
+      if (gin && gin != grad_ptr(c, op.out)) copy_bytes(st, grad_ptr(c, op.out), gin, I.bytes);
+      break;
+    case OP_GAP:
+      if (gin) gap_bwd_f32(st, (cf)grad_ptr(c, op.out), (float*)gin, I.n * I.c, HW);
+      break;
+    case OP_MAXPOOL:
+      if (!gin) break;
+      if (s.bf16) maxpool_bwd_bf16(st, (cb)grad_ptr(c, op.out), (cb)act_ptr(c, op.in), (bf16_t*)gin, I.n, I.h, I.w, I.c);
+      else maxpool_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), (float*)gin, I.n * I.c, I.h, I.w);
+      break;
+    case OP_LINEAR:
+      if (s.bf16) {
+        const Act& O = s.acts[op.out];
+        const size_t R = (size_t)I.n * I.h * I.w;
+        cb g = (cb)grad_ptr(c, op.out);
+        char* sc = scratch(c);
+        if (op.act == 3) {
+          bf16_t* gp = reinterpret_cast<bf16_t*>(sc);
+          act_bwd_bf16(st, g, (cb)act_ptr(c, op.skip), gp, O.elems, 3);
+          g = gp;
+          sc += align256(O.bytes);
+        }
+        if (gin) linear_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin, R, op.cin, op.cout);
+        linear_bf16_wgrad(st, g, (cb)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr,
+                          sc, R, op.cin, op.cout);
+      } else {
+        cf g = (cf)grad_ptr(c, op.out);
+        if (gin) linear_dgrad_f32(st, g, s.W + op.w_off, (float*)gin, I.n, op.cin, op.cout);
+        linear_wgrad_f32(st, g, (cf)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr,
+                         I.n, op.cin, op.cout);
+      }
+      break;
+    case OP_SOFTMAX_CE: {
+      float* p = reinterpret_cast<float*>(c.slot + op.aux_off);
+      int32_t* lab = reinterpret_cast<int32_t*>(p + (size_t)I.n * I.c + I.n);
+      softmax_ce_bwd_f32(st, p, lab, (float*)gin, I.n, I.c, 1.f / ((float)s.cfg.M * (float)s.cfg.B));
+      break;
+    }
+    case OP_LAYERNORM:
+      layernorm_bwd_bf16(st, (cb)grad_ptr(c, op.out), (cb)act_ptr(c, op.in),
+                         reinterpret_cast<float*>(c.slot + op.aux_off), s.W + op.w_off, (bf16_t*)gin,
+                         s.G + op.w_off, s.G + op.b_off, scratch(c), (size_t)I.n * I.h, I.c);
+      break;
+    case OP_MHA: {
+      const int D = op.cin;
+      const size_t R = (size_t)I.n * I.h;
+      bf16_t* qkv = reinterpret_cast<bf16_t*>(c.slot + op.aux_off);
+      bf16_t* o = qkv + R * 3 * D;
+      float* lse = reinterpret_cast<float*>(o + R * D);
+      float* Gq = s.G + op.w_off;
+      float* Gbq = Gq + (size_t)3 * D * D;
+      float* Go = Gbq + 3 * D;
+      float* Gbo = Go + (size_t)D * D;
+      char* sc = scratch(c);
+      bf16_t* d_o = reinterpret_cast<bf16_t*>(sc);
+      bf16_t* dqkv = d_o + R * D;
+      char* lw = sc + align256(R * 4 * D * sizeof(bf16_t));
+      cb g = (cb)grad_ptr(c, op.out);
+      linear_bf16_dgrad(st, g, s.shadow + op.sh2_off + (size_t)3 * D * D, d_o, R, D, D);
+      linear_bf16_wgrad(st, g, o, Go, Gbo, lw, R, D, D);
+      attention_bwd_bf16(st, qkv, o, d_o, lse, dqkv, I.n, I.h, D, op.heads);
+      if (gin) linear_bf16_dgrad(st, dqkv, s.shadow + op.sh2_off, (bf16_t*)gin, R, D, 3 * D);
+      linear_bf16_wgrad(st, dqkv, (cb)act_ptr(c, op.in), Gq, Gbq, lw, R, D, 3 * D);
+      break;
+    }
+  }
+}
+
+ast_status check_launch(std::string& err, const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    err = std::string(what) + ": " + hipGetErrorString(e);
+    return AST_EHIP;
+  }
+  return AST_OK;
+}
+
+}  // namespace
+
+ast_status run_forward(Stage& s, int slot, const void* x, const int32_t* labels, void* y, float* loss,
+                       std::string& err) {
+  Ctx c{s, s.slots[slot], final_act_of(s)};
+  s.cur_y = y;
+  s.cur_dy = nullptr;
+  s.cur_dx = nullptr;
+  copy_bytes(s.stream, x, c.slot + s.acts[0].slot_off, s.acts[0].bytes);
+  for (const Op& op : s.ops) fwd_op(c, op, labels, loss);
+  return check_launch(err, "forward");
+}
+
+ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, std::string& err) {
+  Ctx c{s, s.slots[slot], final_act_of(s)};
+  s.cur_y = nullptr;
+  s.cur_dy = dy;
+  s.cur_dx = dx;
+  for (int j = (int)s.ops.size() - 1; j >= 0; --j) bwd_op(c, s.ops[j]);
+  return check_launch(err, "backward");
+}
+
+ast_status refresh_shadow(Stage& s, std::string& err) {
+  if (!s.bf16) return AST_OK;
+  for (const Op& op : s.ops) {
+    if (op.kind == OP_CONV_IGEMM) {
+      conv_weight_shadow_bf16(s.stream, s.W + op.w_off, s.shadow + op.sh_off, s.shadow + op.sh2_off, op.cout,
+                              op.cin, op.k);
+    } else if (op.kind == OP_LINEAR) {
+      linear_weight_shadow_bf16(s.stream, s.W + op.w_off, s.shadow + op.sh_off, s.shadow + op.sh2_off, op.cout,
+                                op.cin);
+    } else if (op.kind == OP_MHA) {
+      const int D = op.cin;
+      const float* wq = s.W + op.w_off;
+      const float* wo = wq + (size_t)3 * D * D + 3 * D;
+      linear_weight_shadow_bf16(s.stream, wq, s.shadow + op.sh_off, s.shadow + op.sh2_off, 3 * D, D);
+      linear_weight_shadow_bf16(s.stream, wo, s.shadow + op.sh_off + (size_t)3 * D * D,
+                                s.shadow + op.sh2_off + (size_t)3 * D * D, D, D);
+    }
+  }
+  return check_launch(err, "weight copy refresh");
+}
+
+ast_status run_step(Stage& s, float lr, float mu, std::string& err) {
+  sgd_momentum_f32(s.stream, s.W, s.G, s.V, s.nparams, lr, mu);
+  ast_status r = check_launch(err, "step");
+  if (r != AST_OK) return r;
+  return refresh_shadow(s, err);
+}
+
+}  // namespace ast

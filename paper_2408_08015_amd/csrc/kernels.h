@@ -1,0 +1,92 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher enqueues on `st` and
+// returns immediately; none allocates.  Shapes are validated by the stage runtime
+// before any launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ast {
+
+typedef unsigned short bf16_t;
+
+// ------------------------------------------------------------------ fp32, NCHW
+// Pointwise (1x1) convolution as a per-pixel matrix product on the fp32 matrix cores:
+//   Y[n][m][p] = sum_k A[m][k] * X[n][k][p] (+ bias[m]) (+ add[n][m][p])
+// A[m][k] = W[m*lda_m + k*lda_k], so the same kernel serves the forward pass
+// (A = W[Cout][Cin]) and the input gradient (A = W^T).
+void pw_conv_f32(hipStream_t st, const float* W, int lda_m, int lda_k, const float* X, float* Y,
+                 const float* bias, const float* add, int N, int Kdim, int Mdim, int HW);
+// Weight gradient of the pointwise convolution, split over pixel chunks:
+//   part[chunk][co][ci] = sum_{p in chunk} g[n][co][p] * x[n][ci][p];  then G += sum_chunk part.
+// `part` must hold pw_wgrad_f32_ws(N,Cin,Cout,HW) floats.
+size_t pw_wgrad_f32_ws(int N, int Cin, int Cout, int HW);
+void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, float* G, int N,
+                  int Cin, int Cout, int HW);
+
+// Depthwise 3x3 convolution, pad 1, stride 1 or 2, weights [C][3][3].
+void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int N, int C, int H,
+                   int W, int stride);
+void dw3x3_dgrad_f32(hipStream_t st, const float* g, const float* w, float* dx, int N, int C, int H,
+                     int W, int stride);
+size_t dw3x3_wgrad_f32_ws(int N, int C, int H, int W, int stride);
+void dw3x3_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, float* G, int N,
+                     int C, int H, int W, int stride);
+
+// Generic direct convolution (any k, stride, pad, groups); the fallback for shapes the
+// specialised kernels do not cover (e.g. a 3-channel stem).
+void conv_direct_fwd_f32(hipStream_t st, const float* x, const float* w, const float* bias, float* y,
+                         int N, int Cin, int H, int W, int Cout, int k, int stride, int pad,
+                         int groups);
+void conv_direct_dgrad_f32(hipStream_t st, const float* g, const float* w, float* dx, int N, int Cin,
+                           int H, int W, int Cout, int k, int stride, int pad, int groups);
+void conv_direct_wgrad_f32(hipStream_t st, const float* g, const float* x, float* G, int N, int Cin,
+                           int H, int W, int Cout, int k, int stride, int pad, int groups);
+// G[c] += sum_{n,p} g[n][c][p]
+void channel_sum_acc_f32(hipStream_t st, const float* g, float* G, int N, int C, int HW);
+
+// BatchNorm2d, training mode.  `ws` holds bn_ws_doubles(C, N*HW) doubles.
+size_t bn_ws_doubles(int C, size_t per_channel);
+// mean/istd -> stat[0..C) / stat[C..2C); running[0..C) mean, running[C..2C) var updated in place.
+void bn_stats_f32(hipStream_t st, const float* x, const float* gamma, const float* beta, float* stat,
+                  float* scale_shift, float* running, double* ws, int N, int C, int HW, float eps);
+// y = act(x*scale[c] + shift[c]) (+ skip)
+void bn_apply_f32(hipStream_t st, const float* x, const float* scale_shift, const float* skip,
+                  float* y, int N, int C, int HW, int act);
+// Backward: g' = g * act'(x*scale+shift); dbeta += sum g'; dgamma += sum g'*xhat;
+// dx = gamma*istd*(g' - mean(g') - xhat*mean(g'*xhat)).
+void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* stat,
+                const float* scale_shift, const float* gamma, float* dx, float* Ggamma, float* Gbeta,
+                double* ws, float* coef, int N, int C, int HW, int act);
+
+// Elementwise
+void act_fwd_f32(hipStream_t st, const float* x, float* y, size_t n, int act);
+void act_bwd_f32(hipStream_t st, const float* g, const float* x, float* dx, size_t n, int act);
+void add_f32(hipStream_t st, const float* a, const float* b, float* y, size_t n);
+void copy_bytes(hipStream_t st, const void* src, void* dst, size_t bytes);
+void fill_zero(hipStream_t st, void* dst, size_t bytes);
+
+// Pooling
+void gap_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int HW);
+void gap_bwd_f32(hipStream_t st, const float* g, float* dx, int NC, int HW);
+void maxpool_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int H, int W);
+void maxpool_bwd_f32(hipStream_t st, const float* g, const float* x, float* dx, int NC, int H, int W);
+
+// Linear on [R][Cin] rows, fp32.
+void linear_fwd_f32(hipStream_t st, const float* x, const float* W, const float* b, float* y, int R,
+                    int Cin, int Cout);
+void linear_dgrad_f32(hipStream_t st, const float* g, const float* W, float* dx, int R, int Cin,
+                      int Cout);
+void linear_wgrad_f32(hipStream_t st, const float* g, const float* x, float* GW, float* Gb, int R,
+                      int Cin, int Cout);
+
+// Softmax cross-entropy over [R][C] logits; p is stashed; loss = sum_r(-log p[r][label])*inv_denom.
+void softmax_ce_fwd_f32(hipStream_t st, const float* z, const int32_t* labels, float* p,
+                        float* row_loss, float* loss_out, int R, int C, float inv_denom);
+void softmax_ce_bwd_f32(hipStream_t st, const float* p, const int32_t* labels, float* dz, int R,
+                        int C, float inv_denom);
+
+// Momentum SGD over the flat arenas: v = mu*v + g; w -= lr*v; g = 0.
+void sgd_momentum_f32(hipStream_t st, float* w, float* g, float* v, size_t n, float lr, float mu);
+
+}  // namespace ast

@@ -1,0 +1,72 @@
+// Host-side launchers of the bf16-operand / fp32-accumulate kernels (NHWC images and
+// [rows][features] token matrices).  All matrix products run on the gfx950 matrix cores
+// (v_mfma_f32_32x32x16_bf16) from LDS-staged tiles.  None of the launchers allocates.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ast {
+
+typedef unsigned short bf16_t;
+
+// ---- weight copies (refreshed by the optimizer step from the fp32 master weights)
+// conv: master [Cout][Cin][k][k] -> fwd operand [Cout][tap][Cin] and input-gradient operand
+// [Cin][tap'][Cout] with tap' the point-reflected tap.
+void conv_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh_fwd, bf16_t* sh_dgrad, int Cout,
+                             int Cin, int k);
+// linear: master [Cout][Cin] -> copy [Cout][Cin] and transpose [Cin][Cout]
+void linear_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh, bf16_t* sh_t, int Cout,
+                               int Cin);
+
+// ---- dense 'same' convolution, stride 1, NHWC, k in {1,3}
+size_t conv_bf16_ws_bytes(int N, int H, int W, int Cin, int Cout, int k);
+// y = act(conv(x) + bias)
+void conv_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh_fwd, const float* bias, bf16_t* y,
+                   int N, int H, int W, int Cin, int Cout, int k, int act);
+// dx = conv^T(g)
+void conv_bf16_dgrad(hipStream_t st, const bf16_t* g, const bf16_t* sh_dgrad, bf16_t* dx, int N, int H,
+                     int W, int Cin, int Cout, int k);
+// GW[Cout][Cin][k][k] += sum_pixels g x ; Gb[Cout] += sum_pixels g.  `ws` holds
+// conv_bf16_ws_bytes().
+void conv_bf16_wgrad(hipStream_t st, const bf16_t* g, const bf16_t* x, float* GW, float* Gb, void* ws,
+                     int N, int H, int W, int Cin, int Cout, int k);
+
+// ---- linear on [R][Cin] rows
+size_t linear_bf16_ws_bytes(size_t R, int Cin, int Cout);
+// y = act(x W^T + b) (+ add); with act == GELU the pre-activation goes to `pre` as well
+void linear_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh, const float* bias, bf16_t* y,
+                     bf16_t* pre, size_t R, int Cin, int Cout, int act);
+void linear_bf16_dgrad(hipStream_t st, const bf16_t* g, const bf16_t* sh_t, bf16_t* dx, size_t R,
+                       int Cin, int Cout);
+void linear_bf16_wgrad(hipStream_t st, const bf16_t* g, const bf16_t* x, float* GW, float* Gb, void* ws,
+                       size_t R, int Cin, int Cout);
+
+// ---- elementwise on bf16
+// g' = g * act'(.) : ReLU masks by the OUTPUT y (> 0), GELU uses the stashed pre-activation.
+void act_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* ref, bf16_t* out, size_t n, int act);
+void act_fwd_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, size_t n, int act);
+void add_bf16(hipStream_t st, const bf16_t* a, const bf16_t* b, bf16_t* y, size_t n);
+void maxpool_fwd_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, int N, int H, int W, int C);
+void maxpool_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, bf16_t* dx, int N, int H, int W,
+                      int C);
+
+// ---- LayerNorm over the last dimension of [R][D]
+size_t layernorm_bf16_ws_bytes(size_t R, int D);
+void layernorm_fwd_bf16(hipStream_t st, const bf16_t* x, const float* gamma, const float* beta,
+                        bf16_t* y, float* stat /*[2][R]*/, size_t R, int D, float eps);
+void layernorm_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, const float* stat,
+                        const float* gamma, bf16_t* dx, float* Ggamma, float* Gbeta, void* ws, size_t R,
+                        int D);
+
+// ---- self-attention core on packed qkv [B][S][3D] (head size 64): o [B][S][D], lse [B][H][S]
+size_t mha_bf16_ws_bytes(int B, int S, int D, int heads);
+void attention_fwd_bf16(hipStream_t st, const bf16_t* qkv, bf16_t* o, float* lse, int B, int S, int D,
+                        int heads);
+void attention_bwd_bf16(hipStream_t st, const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o,
+                        const float* lse, bf16_t* dqkv, int B, int S, int D, int heads);
+
+// bf16 <-> fp32 conversion of flat buffers
+void f32_to_bf16(hipStream_t st, const float* src, bf16_t* dst, size_t n);
+
+}  // namespace ast

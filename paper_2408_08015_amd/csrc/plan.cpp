@@ -1,0 +1,297 @@
+// Plan construction: shape inference over the layer list, operator fusion, and the
+// layout of the flat arenas, the stash slot and the workspace.  Host code only.
+#include <algorithm>
+#include <cstdio>
+
+#include "kernels.h"
+#include "kernels_bf16.h"
+#include "stage.h"
+
+namespace ast {
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static std::string fmt(const char* f, int a = 0, int b = 0, int c = 0) {
+  char buf[256];
+  snprintf(buf, sizeof buf, f, a, b, c);
+  return buf;
+}
+
+static int new_act(Stage& s, int n, int c, int h, int w, int rank, int layer, int esize) {
+  Act a;
+  a.n = n; a.c = c; a.h = h; a.w = w; a.rank = rank; a.layer = layer; a.esize = esize;
+  a.elems = (size_t)n * c * h * w;
+  a.bytes = a.elems * esize;
+  s.acts.push_back(a);
+  return (int)s.acts.size() - 1;
+}
+
+ast_status build_plan(Stage& s, std::string& err) {
+  const ast_stage_cfg& cfg = s.cfg;
+  const int B = cfg.B;
+  const int nl = (int)s.layers.size();
+  s.bf16 = cfg.dtype == AST_BF16_F32ACC;
+  const int es = s.bf16 ? 2 : 4;
+  if (B <= 0 || cfg.M <= 0 || cfg.K <= 0) { err = "B, M, K must be positive"; return AST_EINVAL; }
+  if (cfg.dtype != AST_F32 && cfg.dtype != AST_BF16_F32ACC) { err = "unknown dtype"; return AST_EINVAL; }
+  if (!s.bf16 && cfg.layout == AST_NHWC) { err = "fp32 stages use NCHW or BSD"; return AST_EUNSUPPORTED; }
+  if (s.bf16 && cfg.layout == AST_NCHW) { err = "bf16 stages use NHWC or BSD"; return AST_EUNSUPPORTED; }
+
+  int cur;
+  if (cfg.layout == AST_BSD) {
+    if (cfg.in_shape[0] <= 0 || cfg.in_shape[1] <= 0) { err = "bad in_shape"; return AST_EINVAL; }
+    cur = new_act(s, B, cfg.in_shape[1], cfg.in_shape[0], 1, 3, -1, es);
+  } else if (cfg.layout == AST_NCHW || cfg.layout == AST_NHWC) {
+    if (cfg.in_shape[0] <= 0 || cfg.in_shape[1] <= 0 || cfg.in_shape[2] <= 0) { err = "bad in_shape"; return AST_EINVAL; }
+    cur = new_act(s, B, cfg.in_shape[0], cfg.in_shape[1], cfg.in_shape[2], 4, -1, es);
+  } else { err = "unknown layout"; return AST_EINVAL; }
+
+  s.layer_act.assign(nl, -1);
+  std::vector<int> res_stack;      // activation ids of open RES_BEGINs
+  std::vector<int> res_op_stack;   // op indices of those RES_BEGINs
+  size_t poff = 0, aux = 0, run = 0, shadow = 0;
+  auto take_aux = [&](Op& op, size_t bytes) { op.aux_off = aux; op.aux_bytes = bytes; aux = align_up(aux + bytes, 256); };
+
+  for (int i = 0; i < nl; ++i) {
+    const ast_layer& L = s.layers[i];
+    const Act A = s.acts[cur];
+    Op op;
+    op.layer = i;
+    op.in = cur;
+    switch (L.kind) {
+      case AST_CONV2D: {
+        int Cin = L.p[0], Cout = L.p[1], k = L.p[2], st = L.p[3], pad = L.p[4], g = L.p[5], hb = L.p[6];
+        if (A.rank != 4) { err = fmt("layer %d: conv2d needs an image tensor", i); return AST_EINVAL; }
+        if (Cin != A.c || Cout <= 0 || k <= 0 || st <= 0 || pad < 0 || g <= 0 || Cin % g || Cout % g) {
+          err = fmt("layer %d: conv2d parameters do not match input (C=%d)", i, A.c); return AST_EINVAL; }
+        int Ho = (A.h + 2 * pad - k) / st + 1, Wo = (A.w + 2 * pad - k) / st + 1;
+        if (A.h + 2 * pad < k || A.w + 2 * pad < k || Ho <= 0 || Wo <= 0) { err = fmt("layer %d: conv2d output is empty", i); return AST_EINVAL; }
+        op.cin = Cin; op.cout = Cout; op.k = k; op.stride = st; op.pad = pad; op.groups = g; op.has_bias = hb ? 1 : 0;
+        op.w_off = poff; poff += (size_t)Cout * (Cin / g) * k * k;
+        if (hb) { op.b_off = poff; poff += Cout; }
+        if (s.bf16) {
+          if (!(g == 1 && (k == 1 || k == 3) && st == 1 && pad == (k - 1) / 2 && Cin % 8 == 0 && Cout % 8 == 0)) {
+            err = fmt("layer %d: bf16 conv2d supports dense 1x1/3x3 stride 1 'same' with channels %% 8 == 0", i);
+            return AST_EUNSUPPORTED; }
+          op.kind = OP_CONV_IGEMM;
+          op.sh_off = shadow; shadow += (size_t)Cout * k * k * Cin;   // [Cout][tap][Cin]
+          op.sh2_off = shadow; shadow += (size_t)Cout * k * k * Cin;  // [Cin][tap flipped][Cout]
+          if (i + 1 < nl && s.layers[i + 1].kind == AST_RELU) { op.act = 1; ++i; }
+        } else if (k == 1 && st == 1 && pad == 0 && g == 1) {
+          op.kind = OP_CONV_PW;
+        } else if (k == 3 && pad == 1 && g == Cin && Cin == Cout && (st == 1 || st == 2) && !hb) {
+          op.kind = OP_CONV_DW;
+        } else {
+          op.kind = OP_CONV_DIRECT;
+        }
+        op.out = cur = new_act(s, B, Cout, Ho, Wo, 4, i, es);
+        break;
+      }
+      case AST_BATCHNORM2D: {
+        if (s.bf16) { err = fmt("layer %d: BatchNorm is fp32-only", i); return AST_EUNSUPPORTED; }
+        if (A.rank != 4 || L.p[0] != A.c) { err = fmt("layer %d: batchnorm channels %d != %d", i, L.p[0], A.c); return AST_EINVAL; }
+        op.kind = OP_BN; op.cin = op.cout = A.c; op.eps = L.eps;
+        op.w_off = poff; poff += A.c; op.b_off = poff; poff += A.c; op.has_bias = 1;
+        op.run_off = run; run += 2 * (size_t)A.c;
+        take_aux(op, 4 * sizeof(float) * A.c);  // mean, istd, scale, shift
+        if (i + 1 < nl && (s.layers[i + 1].kind == AST_RELU || s.layers[i + 1].kind == AST_RELU6)) {
+          op.act = s.layers[i + 1].kind == AST_RELU ? 1 : 2; ++i;
+        }
+        if (i + 1 < nl && s.layers[i + 1].kind == AST_RES_ADD && !res_stack.empty()) {
+          const Act& K = s.acts[res_stack.back()];
+          if (K.elems != A.elems || K.c != A.c) { err = fmt("layer %d: residual shapes differ", i + 1); return AST_EINVAL; }
+          op.skip = res_stack.back();
+          s.ops[res_op_stack.back()].skip = -2;  // patched below once `out` is known
+          ++i;
+        }
+        op.out = cur = new_act(s, B, A.c, A.h, A.w, 4, i, es);
+        if (op.skip >= 0) {
+          s.ops[res_op_stack.back()].skip = cur;
+          res_stack.pop_back(); res_op_stack.pop_back();
+        }
+        break;
+      }
+      case AST_RELU: case AST_RELU6: case AST_GELU: {
+        op.kind = OP_ACT;
+        op.act = L.kind == AST_RELU ? 1 : (L.kind == AST_RELU6 ? 2 : 3);
+        if (!s.bf16 && op.act == 3) { err = fmt("layer %d: GELU is bf16-only", i); return AST_EUNSUPPORTED; }
+        op.out = cur = new_act(s, A.n, A.c, A.h, A.w, A.rank, i, es);
+        break;
+      }
+      case AST_RES_BEGIN: {
+        op.kind = OP_RES_BEGIN; op.out = cur; op.skip = -1;
+        res_stack.push_back(cur);
+        res_op_stack.push_back((int)s.ops.size());
+        s.layer_act[i] = -1;
+        s.ops.push_back(op);
+        continue;
+      }
+      case AST_RES_ADD: {
+        if (res_stack.empty()) { err = fmt("layer %d: RES_ADD without RES_BEGIN", i); return AST_EINVAL; }
+        const Act& K = s.acts[res_stack.back()];
+        if (K.elems != A.elems || K.c != A.c || K.rank != A.rank) { err = fmt("layer %d: residual shapes differ", i); return AST_EINVAL; }
+        op.kind = OP_RES_ADD; op.skip = res_stack.back();
+        op.out = cur = new_act(s, A.n, A.c, A.h, A.w, A.rank, i, es);
+        s.ops[res_op_stack.back()].skip = cur;
+        res_stack.pop_back(); res_op_stack.pop_back();
+        break;
+      }
+      case AST_GLOBAL_AVGPOOL: {
+        if (s.bf16 || A.rank != 4) { err = fmt("layer %d: global avg-pool needs an fp32 image tensor", i); return AST_EUNSUPPORTED; }
+        op.kind = OP_GAP;
+        op.out = cur = new_act(s, B, A.c, 1, 1, 2, i, es);
+        break;
+      }
+      case AST_MAXPOOL2X2: {
+        if (A.rank != 4 || A.h < 2 || A.w < 2) { err = fmt("layer %d: maxpool needs an image of at least 2x2", i); return AST_EINVAL; }
+        if (s.bf16 && A.c % 8) { err = fmt("layer %d: bf16 maxpool needs channels %% 8 == 0", i); return AST_EUNSUPPORTED; }
+        op.kind = OP_MAXPOOL;
+        op.out = cur = new_act(s, B, A.c, A.h / 2, A.w / 2, 4, i, es);
+        break;
+      }
+      case AST_LINEAR: {
+        int Cin = L.p[0], Cout = L.p[1], hb = L.p[2];
+        if (A.rank == 4 || Cin != A.c || Cout <= 0) { err = fmt("layer %d: linear in=%d does not match input %d", i, Cin, A.c); return AST_EINVAL; }
+        if (!s.bf16 && A.rank != 2) { err = fmt("layer %d: fp32 linear works on [B][C] vectors", i); return AST_EUNSUPPORTED; }
+        if (s.bf16 && (Cin % 8 || Cout % 8)) { err = fmt("layer %d: bf16 linear needs features %% 8 == 0", i); return AST_EUNSUPPORTED; }
+        op.kind = OP_LINEAR; op.cin = Cin; op.cout = Cout; op.has_bias = hb ? 1 : 0;
+        op.w_off = poff; poff += (size_t)Cout * Cin;
+        if (hb) { op.b_off = poff; poff += Cout; }
+        if (s.bf16) {
+          op.sh_off = shadow; shadow += (size_t)Cout * Cin;   // W  [Cout][Cin]
+          op.sh2_off = shadow; shadow += (size_t)Cout * Cin;  // W^T [Cin][Cout]
+          if (i + 1 < nl && s.layers[i + 1].kind == AST_GELU) {
+            // pre-activation is stashed for the backward; output = GELU(pre)
+            op.act = 3;
+            op.skip = new_act(s, A.n, Cout, A.h, A.w, A.rank, i, es);  // pre-activation
+            s.layer_act[i] = op.skip;
+            ++i;
+          }
+        }
+        op.out = cur = new_act(s, A.n, Cout, A.h, A.w, A.rank, i, es);
+        break;
+      }
+      case AST_SOFTMAX_CE: {
+        if (i != nl - 1) { err = "SOFTMAX_CE must be the last layer"; return AST_EINVAL; }
+        if (s.bf16 || A.rank != 2) { err = "SOFTMAX_CE needs fp32 [B][classes] logits"; return AST_EUNSUPPORTED; }
+        op.kind = OP_SOFTMAX_CE; op.cout = A.c;
+        s.loss_tail = true; s.n_classes = A.c;
+        take_aux(op, sizeof(float) * ((size_t)B * A.c + B) + sizeof(int32_t) * B);  // p, row loss, labels
+        op.out = cur;  // no new activation: the loss is a scalar
+        s.layer_act[i] = -1;
+        s.ops.push_back(op);
+        continue;
+      }
+      case AST_LAYERNORM: {
+        if (!s.bf16 || A.rank == 4 || L.p[0] != A.c) { err = fmt("layer %d: layernorm needs bf16 rows with D=%d", i, A.c); return s.bf16 ? AST_EINVAL : AST_EUNSUPPORTED; }
+        if (A.c % 8 || A.c > 8192) { err = fmt("layer %d: layernorm needs D %% 8 == 0 and D <= 8192", i); return AST_EUNSUPPORTED; }
+        op.kind = OP_LAYERNORM; op.cin = op.cout = A.c; op.eps = L.eps;
+        op.w_off = poff; poff += A.c; op.b_off = poff; poff += A.c; op.has_bias = 1;
+        take_aux(op, 2 * sizeof(float) * (size_t)A.n * A.h);  // mean, istd per row
+        op.out = cur = new_act(s, A.n, A.c, A.h, A.w, A.rank, i, es);
+        break;
+      }
+      case AST_MHA: {
+        int D = L.p[0], H = L.p[1];
+        if (!s.bf16 || A.rank != 3) { err = fmt("layer %d: MHA needs bf16 token input", i); return AST_EUNSUPPORTED; }
+        if (D != A.c || H <= 0 || D % H) { err = fmt("layer %d: MHA D=%d heads=%d do not match input", i, D, H); return AST_EINVAL; }
+        if (D / H != 64 || A.h % 32 || A.h > 256) { err = fmt("layer %d: MHA kernels cover head size 64 and S %% 32 == 0, S <= 256", i); return AST_EUNSUPPORTED; }
+        op.kind = OP_MHA; op.cin = op.cout = D; op.heads = H; op.has_bias = 1;
+        op.w_off = poff; poff += (size_t)3 * D * D + 3 * D + (size_t)D * D + D;
+        op.sh_off = shadow; shadow += (size_t)4 * D * D;   // W_qkv [3D][D], W_o [D][D]
+        op.sh2_off = shadow; shadow += (size_t)4 * D * D;  // W_qkv^T [D][3D], W_o^T [D][D]
+        // per-slot: qkv [rows][3D] bf16, o [rows][D] bf16, lse [B][H][S] fp32
+        take_aux(op, (size_t)A.n * A.h * 4 * D * 2 + (size_t)A.n * H * A.h * 4);
+        op.out = cur = new_act(s, A.n, D, A.h, 1, 3, i, es);
+        break;
+      }
+      default:
+        err = fmt("layer %d: unknown layer kind %d", i, L.kind);
+        return AST_EINVAL;
+    }
+    s.layer_act[i] = cur;
+    s.ops.push_back(op);
+  }
+  if (!res_stack.empty()) { err = "RES_BEGIN without RES_ADD"; return AST_EINVAL; }
+  if (s.ops.empty()) { err = "empty stage"; return AST_EINVAL; }
+  s.nparams = poff;
+  s.running_floats = run;
+  s.shadow_elems = shadow;
+
+  // Fuse the skip-gradient add of a residual block into the input-gradient kernel of the
+  // pointwise conv that opens the block: dx = W^T g + g_skip.
+  for (size_t j = 0; j + 1 < s.ops.size(); ++j) {
+    Op& rb = s.ops[j];
+    Op& nx = s.ops[j + 1];
+    if (rb.kind == OP_RES_BEGIN && nx.kind == OP_CONV_PW && nx.in == rb.in && rb.skip >= 0) {
+      nx.dgrad_add = rb.skip;
+      rb.noop_bwd = true;
+    }
+  }
+
+  // Stash slot: every activation (the stage input is copied in; the final output goes to
+  // the caller's buffer) followed by the per-op extras.
+  size_t off = 0;
+  const int final_act = cur;
+  s.final_act = cur;
+  for (size_t a = 0; a < s.acts.size(); ++a) {
+    if ((int)a == final_act && !s.loss_tail && a != 0) continue;
+    s.acts[a].slot_off = off;
+    off = align_up(off + s.acts[a].bytes, 256);
+  }
+  for (Op& op : s.ops) op.aux_off += off;
+  s.slot_bytes = align_up(off + aux, 256);
+
+  // Gradient workspace: one buffer per activation except the stage input (caller's dx)
+  // and the final output (caller's dy).
+  size_t goff = 0;
+  for (size_t a = 0; a < s.acts.size(); ++a) {
+    if (a == 0) continue;
+    if ((int)a == final_act && !s.loss_tail) continue;
+    s.acts[a].grad_off = goff;
+    goff = align_up(goff + s.acts[a].bytes, 256);
+  }
+  // RES_ADD passes its output gradient through unchanged: share the buffer.
+  for (Op& op : s.ops)
+    if (op.kind == OP_RES_ADD) s.acts[op.in].grad_alias = op.out;
+  s.grad_bytes = goff;
+
+  // Scratch: reduction partials (max over ops) and small coefficient vectors.
+  size_t sc = 0, sc2 = 0;
+  for (const Op& op : s.ops) {
+    const Act& I = s.acts[op.in];
+    size_t need = 0, need2 = 0;
+    switch (op.kind) {
+      case OP_CONV_PW: need = pw_wgrad_f32_ws(I.n, op.cin, op.cout, I.h * I.w) * sizeof(float); break;
+      case OP_CONV_DW: need = dw3x3_wgrad_f32_ws(I.n, I.c, I.h, I.w, op.stride) * sizeof(float); break;
+      case OP_BN:
+        need = bn_ws_doubles(I.c, (size_t)I.n * I.h * I.w) * sizeof(double);
+        need2 = 3 * sizeof(float) * I.c;
+        break;
+      case OP_CONV_IGEMM:  // masked upstream gradient + split-K partials
+        need = align_up(s.acts[op.out].bytes, 256) + conv_bf16_ws_bytes(I.n, I.h, I.w, op.cin, op.cout, op.k);
+        break;
+      case OP_LINEAR:
+        if (s.bf16)
+          need = align_up(s.acts[op.out].bytes, 256) + linear_bf16_ws_bytes((size_t)I.n * I.h * I.w, op.cin, op.cout);
+        break;
+      case OP_LAYERNORM: need = layernorm_bf16_ws_bytes((size_t)I.n * I.h, I.c); break;
+      case OP_MHA:  // d_o and dqkv, then the split-K partials of the two projections
+        need = align_up((size_t)I.n * I.h * 4 * op.cin * 2, 256) +
+               std::max(linear_bf16_ws_bytes((size_t)I.n * I.h, op.cin, 3 * op.cin),
+                        mha_bf16_ws_bytes(I.n, I.h, op.cin, op.heads));
+        break;
+      default: break;
+    }
+    sc = std::max(sc, need);
+    sc2 = std::max(sc2, need2);
+  }
+  s.scratch_off = align_up(goff, 256);
+  s.scratch_bytes = align_up(sc, 256);
+  s.scratch2_off = s.scratch_off + s.scratch_bytes;
+  s.scratch2_bytes = align_up(sc2, 256);
+  s.ws_bytes = s.scratch2_off + s.scratch2_bytes + 256;
+  return AST_OK;
+}
+
+}  // namespace ast

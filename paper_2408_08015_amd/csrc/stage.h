@@ -1,0 +1,109 @@
+// Stage runtime: turns the layer list of a stage model into an execution plan of
+// fused operators over flat arenas (parameters W, accumulated gradients G, velocity V),
+// a ring of K activation stashes and one gradient/scratch workspace, and enforces the
+// one-forward-one-backward call discipline (Sec. 3.2; memory model Eq. (3)).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/asteroid.h"
+
+namespace ast {
+
+enum OpKind {
+  OP_CONV_PW,      // fp32 1x1 dense conv (matrix cores)
+  OP_CONV_DW,      // fp32 depthwise 3x3
+  OP_CONV_DIRECT,  // fp32 generic conv
+  OP_CONV_IGEMM,   // bf16 NHWC implicit-GEMM conv (+bias, +ReLU)
+  OP_BN,           // BatchNorm (+ReLU/ReLU6) (+residual add)
+  OP_ACT,          // standalone ReLU / ReLU6 / GELU
+  OP_RES_BEGIN,
+  OP_RES_ADD,
+  OP_GAP,
+  OP_MAXPOOL,
+  OP_LINEAR,       // fp32 rows (vectors) or bf16 token GEMM (+GELU)
+  OP_SOFTMAX_CE,
+  OP_LAYERNORM,    // (+ residual add fused in front)
+  OP_MHA
+};
+
+struct Act {
+  int n = 0, c = 0, h = 1, w = 1;  // logical dims; tokens: h = S, c = D; vectors: h = w = 1
+  int rank = 4;                    // 4 image, 3 tokens, 2 vectors
+  int esize = 4;                   // bytes per element (4 fp32, 2 bf16)
+  size_t elems = 0, bytes = 0;
+  size_t slot_off = 0;             // byte offset inside a stash slot
+  size_t grad_off = 0;             // byte offset inside the gradient workspace
+  int grad_alias = -1;             // gradient buffer shared with this activation's
+  int layer = -1;                  // layer index whose output this is (-1: stage input)
+};
+
+struct Op {
+  OpKind kind;
+  int layer = -1;         // first layer index covered by this op
+  int in = -1, out = -1;  // activation ids
+  int skip = -1;          // residual partner: skip input (BN/LN/RES_ADD) or, for RES_BEGIN /
+                          // a fused dgrad add, the activation whose gradient is the skip gradient
+  int act = 0;            // fused activation code
+  size_t w_off = 0, b_off = 0;  // offsets (floats) into the flat arenas; b_off valid iff has_bias
+  int has_bias = 0;
+  int cin = 0, cout = 0, k = 1, stride = 1, pad = 0, groups = 1;
+  int heads = 0;
+  float eps = 1e-5f;
+  size_t aux_off = 0, aux_bytes = 0;  // per-slot extras (statistics, probabilities, ...)
+  size_t run_off = 0;                 // BatchNorm running statistics (floats, persistent)
+  int dgrad_add = -1;                 // pointwise conv: add this activation's gradient to dx
+  bool noop_bwd = false;              // RES_BEGIN whose add was fused into the next dgrad
+  size_t sh_off = 0, sh2_off = 0;     // bf16 weight copies (elements) in the shadow arena
+};
+
+struct Stage {
+  ast_stage_cfg cfg;
+  std::vector<ast_layer> layers;
+  std::vector<Act> acts;
+  std::vector<Op> ops;
+  std::vector<int> layer_act;  // layer -> activation id holding its output (-1 if fused away)
+  hipStream_t stream = nullptr;
+  bool bf16 = false;
+  bool loss_tail = false;
+  int final_act = 0;  // activation id of the stage output (logits for a loss tail)
+  int n_classes = 0;
+
+  size_t nparams = 0;
+  float *W = nullptr, *G = nullptr, *V = nullptr;  // flat arenas (device)
+  unsigned short* shadow = nullptr;                // bf16 weight copies
+  size_t shadow_elems = 0;
+  float* running = nullptr;  // BatchNorm running mean/var
+  size_t running_floats = 0;
+
+  size_t slot_bytes = 0;
+  std::vector<char*> slots;  // K stash slots
+  char* ws = nullptr;        // workspace: activation gradients + scratch
+  size_t ws_bytes = 0, grad_bytes = 0;
+  size_t scratch_off = 0, scratch_bytes = 0;  // reduction partials
+  size_t scratch2_off = 0, scratch2_bytes = 0;  // small coefficient vectors
+
+  // 1F1B state
+  int next_fwd = 0, next_bwd = 0;
+  std::vector<int> mb_slot;
+  std::vector<int> free_slots;
+
+  // per-call boundary pointers
+  const void* cur_dy = nullptr;
+  void* cur_dx = nullptr;
+  void* cur_y = nullptr;
+
+};
+
+// plan.cpp
+ast_status build_plan(Stage& s, std::string& err);
+// exec.cpp
+ast_status run_forward(Stage& s, int slot, const void* x, const int32_t* labels, void* y, float* loss,
+                       std::string& err);
+ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, std::string& err);
+ast_status run_step(Stage& s, float lr, float mu, std::string& err);
+ast_status refresh_shadow(Stage& s, std::string& err);
+
+}  // namespace ast

@@ -345,9 +345,9 @@ def test_mobilenetv2_schedule():
 
 
 # ----------------------------------------------------------------- independent library cross-check
-def torch_stage(cfg, params, x, target):
-    """The same layer list through PyTorch CPU float64 functional ops + autograd."""
-    t = lambda a: torch.tensor(np.asarray(a, np.float64))
+def torch_stage(cfg, params, x, target, dtype=torch.float64):
+    """The same layer list through PyTorch CPU functional ops + autograd (float64 by default)."""
+    t = lambda a: torch.tensor(np.asarray(a, np.float64)).to(dtype)
     W = t(params).requires_grad_(True)
     xs = t(x).requires_grad_(True)
     off = 0
@@ -415,7 +415,7 @@ def torch_stage(cfg, params, x, target):
             total = total + (a * t(target[m * B:(m + 1) * B])).sum()
         outs.append(a.detach().numpy())
     total.backward()
-    return outs, W.grad.numpy(), xs.grad.numpy(), float(total.detach())
+    return outs, W.grad.double().numpy(), xs.grad.double().numpy(), float(total.detach())
 
 
 @pytest.mark.parametrize("cfg", [
