@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Stage-training benchmark on one MI355X.
+
+A step is one HPP-Round of the stage (Sec. 3.2): M micro-batches through forward and
+backward in 1F1B order (K = 1), in-place gradient accumulation, one momentum-SGD update.
+Inputs are synthetic, seeded, and resident in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+
+Prints ONE JSON line: stage train samples/sec, the roofline figures of the dominant
+kernel (timed live with HIP events on the stage's stream during the timed steps) and
+the CPU oracle's rate on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def dominant_kernel(cfg):
+    """(kernel-name filter, bound, algorithmic units per launch averaged over one round's
+    launches, unit).  The dominant kernel of each workload was read off a rocprofv3
+    kernel trace of this same command (summaries under profiles/)."""
+    from asteroid_workloads import gen
+    if cfg.name.startswith("cfg4") or cfg.name.startswith("cfg5"):
+        return None
+    # fp32 MobileNetV2-style stages: BatchNorm backward apply kernel
+    #   per element: read g, read x, write dx  = 12 bytes
+    total, launches = 0, 0
+    shape = tuple(cfg.in_shape)
+    for L in cfg.layers:
+        if L["kind"] == "batchnorm2d":
+            c, h, w = shape
+            total += 12 * cfg.B * c * h * w
+            launches += 1
+        shape = gen.out_shape([L], shape)
+    return "bn_bwd_apply_kernel", "hbm", total / max(launches, 1), "GB/s"
+
+
+def run(args):
+    import numpy as np
+    import torch
+    import paper_2408_08015_amd as A
+    from asteroid_workloads import get_config, gen
+
+    cfg = get_config(args.workload)
+    inp = gen.make_inputs(cfg)
+    dev = torch.device("cuda:0")
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    stream = torch.cuda.current_stream()
+    st = A.Stage(cfg.layers, cfg.B, cfg.M, 1, cfg.in_shape, cfg.dtype, cfg.layout, cfg.needs_input_grad,
+                 stream=stream.cuda_stream)
+    st.set_params(inp["params"])
+    B, M = cfg.B, cfg.M
+    x = torch.from_numpy(inp["x"]).to(dev).to(tdt).contiguous()
+    if cfg.loss_tail:
+        labels = torch.from_numpy(inp["labels"]).to(dev)
+        y = torch.zeros((B * M, gen.out_shape(cfg.layers, cfg.in_shape)[0]), device=dev)
+        dy = None
+    else:
+        labels = None
+        dy = torch.from_numpy(inp["dy"]).to(dev).to(tdt).contiguous()
+        y = torch.zeros_like(dy)
+    dx = torch.zeros_like(x) if cfg.needs_input_grad else None
+    loss = torch.zeros(M, device=dev)
+    # one separately allocated buffer per micro-batch (16-byte aligned, as the ABI requires)
+    mbs = lambda t: [t[m * B:(m + 1) * B].clone() if t is not None else None for m in range(M)]
+    xs, ys, dys, dxs, labs = mbs(x), mbs(y), mbs(dy), mbs(dx), mbs(labels)
+    loss = torch.zeros(M * 4, device=dev)
+    ls = [loss[4 * m:4 * m + 1] if cfg.loss_tail else None for m in range(M)]
+
+    def one_round():
+        # K = 1: F0 B0 F1 B1 ... then the update
+        for m in range(M):
+            st.forward(m, xs[m], labs[m], ys[m], ls[m])
+            st.backward(m, dys[m], dxs[m])
+        st.step(cfg.lr, cfg.momentum)
+
+    for _ in range(args.warmup):
+        one_round()
+    torch.cuda.synchronize()
+
+    dom = dominant_kernel(cfg)
+    filt = "" if args.profile_all else (dom[0] if dom else None)
+    if filt is not None:
+        st.profile_begin(filt, max_launches=args.steps * (20000 if args.profile_all else 512))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_round()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = st.profile_end() if filt is not None else {}
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = M * B / (ms_per_step * 1e-3)
+    roofline = None
+    if dom:
+        name, bound, units, unit = dom
+        hits = {k: v for k, v in prof.items() if name in k}
+        n = sum(v[0] for v in hits.values())
+        ms = sum(v[1] for v in hits.values())
+        if n:
+            avg_s = ms * 1e-3 / n
+            achieved = units / avg_s / 1e9
+            peak = HBM_PEAK_GBS if bound == "hbm" else MFMA_PEAK_TFLOPS[cfg.dtype] * 1e3
+            roofline = {"bound": bound, "kernel": name, "achieved": round(achieved, 1), "peak": peak,
+                        "unit": unit, "frac": round(achieved / peak, 4), "traffic": None,
+                        "launches": n, "avg_us": round(avg_s * 1e6, 2)}
+    if args.profile_all:
+        tot = sum(v[1] for v in prof.values())
+        print("per-kernel HIP-event times over %d steps (sum %.3f ms/step):" % (args.steps, tot / args.steps),
+              file=sys.stderr)
+        for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1]):
+            print("  %-48s launches/step %6.1f  us/launch %9.2f  ms/step %8.4f  %5.1f%%" %
+                  (k, v[0] / args.steps, v[1] * 1e3 / v[0], v[1] / args.steps, 100 * v[1] / tot), file=sys.stderr)
+    mem = st.memory()
+    st.close()
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, inp)
+
+    out = {
+        "metric": "stage train samples/sec (fwd+bwd+SGD, M micro-batches)",
+        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == "f32" else "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %s, B=%d x M=%d, in %s %s" % (args.workload, cfg.name, B, M,
+                                                                 "x".join(map(str, cfg.in_shape)), cfg.layout),
+                   "K": 1, "lr": cfg.lr, "momentum": cfg.momentum,
+                   "stage_bytes": {"mod": mem[0], "opt": mem[1], "act_per_mb": mem[2], "workspace": mem[3]}},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(cfg, inp):
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload."""
+    from oracle import OracleStage, run_round
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    # sample: as many whole micro-batches as fit the time budget (at least one), then one update
+    M, B = cfg.M, cfg.B
+    st = OracleStage(cfg.layers, B, M, cfg.in_shape, cfg.layout, cfg.needs_input_grad,
+                     storage="bf16" if cfg.dtype == "bf16" else "f64")
+    st.set_params(inp["params"])
+    target = inp["labels"] if cfg.loss_tail else inp["dy"]
+    t0 = time.perf_counter()
+    done = 0
+    for m in range(M):
+        sl = slice(m * B, (m + 1) * B)
+        st.forward(m, inp["x"][sl], target[sl] if cfg.loss_tail else None)
+        st.backward(m, None if cfg.loss_tail else target[sl])
+        done += 1
+        if time.perf_counter() - t0 > 20.0:
+            break
+    st.stash.clear()
+    st.step(cfg.lr, cfg.momentum)
+    dt = time.perf_counter() - t0
+    return {"value": round(done * B / dt, 2), "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d of %d micro-batches (B=%d) forward+backward, then one update; numpy float64" % (done, M, B),
+            "seconds": round(dt, 2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--profile-all", action="store_true", help="time every kernel, table on stderr")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    run(args)
+
+
+if __name__ == "__main__":
+    main()

@@ -12,7 +12,8 @@
  * Micro-batch Scheduling"; memory model Eq. (3)).
  *
  * Pointer conventions: every `*_dev` argument is DEVICE memory owned by the
- * caller; every `host_*` argument is HOST memory owned by the caller.  The library
+ * caller and must be 16-byte aligned (AST_EINVAL otherwise); every `host_*`
+ * argument is HOST memory owned by the caller.  The library
  * owns parameters, accumulated gradients, optimizer state, reduced-precision
  * weight copies, the activation stash and its workspace; all are allocated in
  * asteroid_stage_create and none in forward/backward/step.
@@ -162,6 +163,19 @@ ast_status asteroid_stage_plan_memory(const ast_layer* layers, int32_t n_layers,
  * output is fused away or is the stage output (that one is in the caller's y buffer). */
 ast_status asteroid_stage_debug_activation(asteroid_stage* s, int32_t mb, int32_t layer,
                                            float* host_out, size_t* n_out);
+
+/* Per-kernel timing with HIP events on the stage's stream (for roofline reports).
+ * profile_begin: from now on, every kernel launch of this stage made by the calling
+ * thread whose kernel name contains `filter` (NULL or "" = every kernel) is bracketed by
+ * an event pair, up to `max_launches` launches (the pool is created here, not in the hot
+ * calls).  profile_end: waits for the stream, then aggregates the elapsed times by kernel
+ * name and stops recording.  profile_entry(i): name (copied, NUL-terminated, at most
+ * name_cap bytes), launch count and summed milliseconds of the i-th aggregated kernel;
+ * AST_EINVAL once i is past the last entry. */
+ast_status asteroid_stage_profile_begin(asteroid_stage* s, const char* filter, int32_t max_launches);
+ast_status asteroid_stage_profile_end(asteroid_stage* s);
+ast_status asteroid_stage_profile_entry(asteroid_stage* s, int32_t i, char* name_out, size_t name_cap,
+                                        int32_t* launches, double* total_ms);
 
 /* Thread-local message of the last failing call on this thread ("" if none). */
 const char* asteroid_last_error(void);

@@ -11,6 +11,16 @@ W = W - lr*v, G = 0; a loss tail divides by M*B so G is the gradient of the
 mini-batch mean loss; a stage fed an upstream gradient applies no scaling;
 BatchNorm statistics are those of the micro-batch.
 
+Stages whose tensors are bf16 ("bf16 compute, fp32 accumulation, fp32 master
+weights"): with storage="bf16" the oracle applies exactly the roundings that this
+arithmetic type prescribes and nothing else -- the weight matrices are rounded to bf16
+when used as operands (the fp32 master copy is what the update changes), and every
+layer's output activation is rounded to bf16 (round-to-nearest-even); all sums stay in
+fp64 and rounding passes gradients through unchanged.  This puts the decisions that a
+float comparison takes (ReLU masks, max-pool arg-max) in the kernel's precision on both
+sides, which a comparison of a bf16 stage needs: a pure fp64 run picks a different
+arg-max wherever two window entries agree to 8 bits.
+
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import this.
 It imports nothing from the HIP package.
 """
@@ -19,6 +29,14 @@ import numpy as np
 from . import layers as L
 
 F = np.float64
+
+
+def round_bf16(a):
+    """fp64 -> nearest fp32 -> nearest bf16 (ties to even), returned as fp64."""
+    a32 = np.ascontiguousarray(a, dtype=np.float32)
+    u = a32.view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return r.astype(np.uint32).view(np.float32).reshape(a32.shape).astype(F)
 
 
 def _param_shapes(layer):
@@ -42,7 +60,9 @@ def _param_shapes(layer):
 class OracleStage:
     """Same logical calls as the C ABI (create / forward / backward / step), on host fp64."""
 
-    def __init__(self, layers, B, M, in_shape, layout="nchw", needs_input_grad=True):
+    def __init__(self, layers, B, M, in_shape, layout="nchw", needs_input_grad=True, storage="f64"):
+        assert storage in ("f64", "bf16")
+        self.storage = storage
         self.layers = [dict(l) for l in layers]
         self.B, self.M = B, M
         self.in_shape = tuple(in_shape)
@@ -59,6 +79,7 @@ class OracleStage:
             self.offsets.append(o)
         self.nparams = off
         self.W = np.zeros(off, F)
+        self.Wop = self.W
         self.G = np.zeros(off, F)
         self.V = np.zeros(off, F)
         self.stash = {}
@@ -73,6 +94,20 @@ class OracleStage:
     def set_params(self, flat):
         assert flat.size == self.nparams
         self.W = np.asarray(flat, F).copy()
+        self._refresh_operands()
+
+    def _refresh_operands(self):
+        """Weights as the layers see them: the master copy, or (bf16 storage) its weight
+        matrices rounded to bf16; biases and normalisation parameters stay as they are."""
+        if self.storage != "bf16":
+            self.Wop = self.W
+            return
+        self.Wop = self.W.copy()
+        for i, l in enumerate(self.layers):
+            mats = {"conv2d": [0], "linear": [0], "mha": [0, 2]}.get(l["kind"], [])
+            for t in mats:
+                o, n = self.offsets[i][t], int(np.prod(self.shapes[i][t]))
+                self.Wop[o:o + n] = round_bf16(self.W[o:o + n])
 
     def set_velocity(self, flat):
         self.V = np.asarray(flat, F).copy()
@@ -106,7 +141,7 @@ class OracleStage:
             if i > 0 and self.keep_acts:
                 trace.append(a)
             k = l["kind"]
-            P = self._p(self.W, i)
+            P = self._p(self.Wop, i)
             if k == "conv2d":
                 saved.append(a)
                 a = L.conv2d_fwd(a, P[0], P[1] if l["bias"] else None, l["stride"], l["pad"], l["groups"])
@@ -155,6 +190,8 @@ class OracleStage:
                 saved.append((p, np.asarray(labels)))
             else:
                 raise ValueError(k)
+            if self.storage == "bf16" and k not in ("softmax_ce", "res_begin"):
+                a = round_bf16(a)
         self.stash[mb] = saved
         if self.keep_acts:
             trace.append(a)
@@ -171,7 +208,7 @@ class OracleStage:
         for i in range(len(self.layers) - 1, -1, -1):
             l = self.layers[i]
             k = l["kind"]
-            P = self._p(self.W, i)
+            P = self._p(self.Wop, i)
             sv = saved[i]
             if k == "softmax_ce":
                 g = L.softmax_ce_bwd(sv[0], sv[1], self.M * self.B)
@@ -211,6 +248,7 @@ class OracleStage:
         assert not self.stash
         self.V = momentum * self.V + self.G
         self.W = self.W - lr * self.V
+        self._refresh_operands()
         self.G = np.zeros_like(self.G)
 
 

@@ -58,6 +58,9 @@ def load_library():
     lib.asteroid_stage_memory.argtypes = [vp, szp, szp, szp, szp]
     lib.asteroid_stage_plan_memory.argtypes = [C.POINTER(ast_layer), i32, C.POINTER(ast_stage_cfg), szp, szp, szp, szp]
     lib.asteroid_stage_debug_activation.argtypes = [vp, i32, i32, f32p, szp]
+    lib.asteroid_stage_profile_begin.argtypes = [vp, C.c_char_p, i32]
+    lib.asteroid_stage_profile_end.argtypes = [vp]
+    lib.asteroid_stage_profile_entry.argtypes = [vp, i32, C.c_char_p, C.c_size_t, C.POINTER(i32), C.POINTER(C.c_double)]
     lib.asteroid_last_error.restype = C.c_char_p
     lib.asteroid_kp.argtypes = [i32, i32]
     lib.asteroid_kp.restype = i32
@@ -188,6 +191,20 @@ class Stage:
         out = [C.c_size_t() for _ in range(4)]
         _check(self.lib, self.lib.asteroid_stage_memory(self.h, *[C.byref(o) for o in out]))
         return tuple(o.value for o in out)
+
+    def profile_begin(self, kernel_filter="", max_launches=4096):
+        _check(self.lib, self.lib.asteroid_stage_profile_begin(self.h, kernel_filter.encode(), max_launches))
+
+    def profile_end(self):
+        """{kernel name: (launches, total_ms)} of the launches recorded since profile_begin."""
+        _check(self.lib, self.lib.asteroid_stage_profile_end(self.h))
+        out, i = {}, 0
+        buf = C.create_string_buffer(256)
+        n, ms = C.c_int32(), C.c_double()
+        while self.lib.asteroid_stage_profile_entry(self.h, i, buf, 256, C.byref(n), C.byref(ms)) == 0:
+            out[buf.value.decode()] = (n.value, ms.value)
+            i += 1
+        return out
 
     def debug_activation(self, mb, layer):
         n = C.c_size_t()

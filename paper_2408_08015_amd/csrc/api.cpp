@@ -7,11 +7,33 @@
 
 #include "kernels.h"
 #include "kernels_bf16.h"
+#include "prof.h"
 #include "stage.h"
+
+namespace ast {
+thread_local Profiler* g_prof = nullptr;
+}
+
+struct ProfEntry {
+  std::string name;
+  int launches = 0;
+  double ms = 0;
+};
 
 struct asteroid_stage {
   ast::Stage s;
+  ast::Profiler prof;
+  bool prof_on = false;
+  std::vector<ProfEntry> prof_result;
 };
+
+namespace {
+// activates the stage's profiler on this thread for the duration of one hot call
+struct ProfGuard {
+  explicit ProfGuard(asteroid_stage* h) { ast::g_prof = h->prof_on ? &h->prof : nullptr; }
+  ~ProfGuard() { ast::g_prof = nullptr; }
+};
+}  // namespace
 
 namespace {
 thread_local std::string g_err;
@@ -138,11 +160,12 @@ ast_status asteroid_stage_forward(asteroid_stage* h, int32_t mb, const void* x_d
   if (mb != s.next_fwd) return fail(AST_ESTATE, "forward: micro-batches are forwarded in order, once per round");
   if (s.next_fwd - s.next_bwd >= s.cfg.K) return fail(AST_ESTATE, "forward: K forwarded micro-batches await their backward");
   if (!x_dev) return fail(AST_EINVAL, "forward: x_dev is NULL");
-  if (!aligned16(x_dev) || !aligned16(y_dev)) return fail(AST_EINVAL, "forward: buffers must be 16-byte aligned");
+  if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(labels_dev)) return fail(AST_EINVAL, "forward: buffers must be 16-byte aligned");
   if (s.loss_tail && !labels_dev) return fail(AST_EINVAL, "forward: labels_dev required for a SOFTMAX_CE tail");
   if (!s.loss_tail && !y_dev) return fail(AST_EINVAL, "forward: y_dev is NULL");
   int slot = s.free_slots.back();
   std::string err;
+  ProfGuard pg(h);
   ast_status r = ast::run_forward(s, slot, x_dev, labels_dev, y_dev, loss_dev, err);
   if (r != AST_OK) return fail(r, err);
   s.free_slots.pop_back();
@@ -164,6 +187,7 @@ ast_status asteroid_stage_backward(asteroid_stage* h, int32_t mb, const void* dy
   if (!aligned16(dy_dev) || !aligned16(dx_dev)) return fail(AST_EINVAL, "backward: buffers must be 16-byte aligned");
   int slot = s.mb_slot[mb];
   std::string err;
+  ProfGuard pg(h);
   ast_status r = ast::run_backward(s, slot, dy_dev, dx_dev, err);
   if (r != AST_OK) return fail(r, err);
   s.mb_slot[mb] = -1;
@@ -177,6 +201,7 @@ ast_status asteroid_stage_step(asteroid_stage* h, float lr, float momentum) {
   ast::Stage& s = h->s;
   if (s.next_bwd != s.cfg.M) return fail(AST_ESTATE, "step: not all M micro-batches have been forwarded and backwarded");
   std::string err;
+  ProfGuard pg(h);
   ast_status r = ast::run_step(s, lr, momentum, err);
   if (r != AST_OK) return fail(r, err);
   s.next_fwd = s.next_bwd = 0;
@@ -186,6 +211,7 @@ ast_status asteroid_stage_step(asteroid_stage* h, float lr, float momentum) {
 void asteroid_stage_destroy(asteroid_stage* h) {
   if (!h) return;
   (void)hipStreamSynchronize(h->s.stream);
+  for (hipEvent_t e : h->prof.events) (void)hipEventDestroy(e);
   free_stage(h->s);
   delete h;
 }
@@ -271,6 +297,60 @@ ast_status asteroid_stage_debug_activation(asteroid_stage* h, int32_t mb, int32_
       std::memcpy(&host_out[i], &u, 4);
     }
   }
+  return AST_OK;
+}
+
+ast_status asteroid_stage_profile_begin(asteroid_stage* h, const char* filter, int32_t max_launches) {
+  if (!h || max_launches <= 0) return fail(AST_EINVAL, "profile_begin: bad argument");
+  ast::Profiler& p = h->prof;
+  p.filter = filter ? filter : "";
+  while (p.events.size() < (size_t)max_launches * 2) {
+    hipEvent_t e;
+    HIPCHK(hipEventCreate(&e), "profile_begin");
+    p.events.push_back(e);
+  }
+  p.used = 0;
+  p.names.clear();
+  h->prof_result.clear();
+  h->prof_on = true;
+  return AST_OK;
+}
+
+ast_status asteroid_stage_profile_end(asteroid_stage* h) {
+  if (!h) return fail(AST_EINVAL, "profile_end: NULL stage");
+  h->prof_on = false;
+  HIPCHK(hipStreamSynchronize(h->s.stream), "profile_end");
+  ast::Profiler& p = h->prof;
+  h->prof_result.clear();
+  for (size_t i = 0; i < p.used; ++i) {
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, p.events[2 * i], p.events[2 * i + 1]), "profile_end");
+    ProfEntry* e = nullptr;
+    for (ProfEntry& q : h->prof_result)
+      if (q.name == p.names[i]) { e = &q; break; }
+    if (!e) {
+      h->prof_result.push_back(ProfEntry());
+      e = &h->prof_result.back();
+      e->name = p.names[i];
+    }
+    e->launches++;
+    e->ms += ms;
+  }
+  p.used = 0;
+  p.names.clear();
+  return AST_OK;
+}
+
+ast_status asteroid_stage_profile_entry(asteroid_stage* h, int32_t i, char* name_out, size_t name_cap,
+                                        int32_t* launches, double* total_ms) {
+  if (!h || i < 0 || i >= (int)h->prof_result.size()) return fail(AST_EINVAL, "profile_entry: index past the last entry");
+  const ProfEntry& e = h->prof_result[i];
+  if (name_out && name_cap) {
+    std::strncpy(name_out, e.name.c_str(), name_cap - 1);
+    name_out[name_cap - 1] = 0;
+  }
+  if (launches) *launches = e.launches;
+  if (total_ms) *total_ms = e.ms;
   return AST_OK;
 }
 

@@ -1,0 +1,385 @@
+// Self-attention core (no mask, head size 64, S % 32 == 0, S <= 256) on packed
+// qkv [B][S][3D]: forward with online softmax, and backward as two kernels
+// (dK/dV parallel over keys, dQ parallel over queries).  The S x S score matrix never
+// leaves the chip: bytes moved are Q, K, V, O (+ dO, dQ, dK, dV) only.
+//
+// Every product is computed in the orientation that keeps the softmax reductions inside
+// a lane.  With MFMA 32x32x16 the accumulator of lane l holds column l%32 and 16 rows
+// (register r -> row 8*(r/4) + 4*(l/32) + r%4).  The forward computes S^T = K Q^T, so a
+// lane owns one query and its registers run over keys: the row max / row sum need one
+// cross-half shuffle, and the probabilities are already laid out as the B operand of
+// O^T = V^T P^T (slot (g, e) of MFMA u <-> key 16u + 8*(e/4) + 4g + e%4; the V^T operand is
+// read from a transposed LDS copy with the same slot order).  The backward kernels use
+// the same trick with the roles of queries and keys chosen per product.
+#include "device_utils.h"
+#include "kernels_bf16.h"
+#include "prof.h"
+
+namespace ast {
+
+namespace {
+
+constexpr int HD = 64;        // head size
+constexpr int RS = HD + 8;    // LDS row stride of [row][d] copies (elements)
+
+__device__ __forceinline__ bf16x8 ld_frag(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+__device__ __forceinline__ bf16x8 pack_frag(const float* f) {
+  uint4 v;
+  uint32_t* w = reinterpret_cast<uint32_t*>(&v);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) w[k] = (uint32_t)f2bf(f[2 * k]) | ((uint32_t)f2bf(f[2 * k + 1]) << 16);
+  return __builtin_bit_cast(bf16x8, v);
+}
+// two 8-byte reads -> one operand fragment (slots e = 0..3 and 4..7)
+__device__ __forceinline__ bf16x8 ld_frag_2x4(const bf16_t* p0, const bf16_t* p1) {
+  uint4 v;
+  uint2 a = *reinterpret_cast<const uint2*>(p0);
+  uint2 b = *reinterpret_cast<const uint2*>(p1);
+  v.x = a.x; v.y = a.y; v.z = b.x; v.w = b.y;
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// copy S rows of 64 bf16 (row stride `ld` elements in global memory) into LDS [S][RS]
+__device__ __forceinline__ void stage_rows(bf16_t* dst, const bf16_t* src, long ld, int S) {
+  for (int c = threadIdx.x; c < S * 8; c += blockDim.x) {
+    int row = c >> 3, part = c & 7;
+    *reinterpret_cast<uint4*>(dst + row * RS + part * 8) =
+        *reinterpret_cast<const uint4*>(src + (long)row * ld + part * 8);
+  }
+}
+// transposed copy into LDS [64][S + 8]: tasks of 4 rows x 8 columns
+__device__ __forceinline__ void stage_rows_T(bf16_t* dst, const bf16_t* src, long ld, int S) {
+  const int TS = S + 8;
+  for (int t = threadIdx.x; t < (S / 4) * 8; t += blockDim.x) {
+    int rq = t >> 3, cg = t & 7;
+    uint4 v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) v[r] = *reinterpret_cast<const uint4*>(src + (long)(rq * 4 + r) * ld + cg * 8);
+    const uint32_t* r0 = reinterpret_cast<const uint32_t*>(&v[0]);
+    const uint32_t* r1 = reinterpret_cast<const uint32_t*>(&v[1]);
+    const uint32_t* r2 = reinterpret_cast<const uint32_t*>(&v[2]);
+    const uint32_t* r3 = reinterpret_cast<const uint32_t*>(&v[3]);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      uint2 lo, hi;
+      lo.x = (r0[w] & 0xffffu) | (r1[w] << 16);
+      lo.y = (r2[w] & 0xffffu) | (r3[w] << 16);
+      hi.x = (r0[w] >> 16) | (r1[w] & 0xffff0000u);
+      hi.y = (r2[w] >> 16) | (r3[w] & 0xffff0000u);
+      *reinterpret_cast<uint2*>(dst + (cg * 8 + 2 * w) * TS + rq * 4) = lo;
+      *reinterpret_cast<uint2*>(dst + (cg * 8 + 2 * w + 1) * TS + rq * 4) = hi;
+    }
+  }
+}
+
+// row index held by accumulator register r of a lane in half g
+__device__ __forceinline__ int acc_row(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
+
+// ------------------------------------------------------------------ forward
+__global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __restrict__ qkv,
+                                                            bf16_t* __restrict__ o, float* __restrict__ lse,
+                                                            int S, int D, int H) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* sK = reinterpret_cast<bf16_t*>(smem);  // [S][RS]
+  bf16_t* sVt = sK + S * RS;                     // [64][S+8]
+  const int TS = S + 8;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, g = lane >> 5;
+  const long ld = 3L * D;
+  const bf16_t* base = qkv + (long)b * S * ld + h * HD;
+  stage_rows(sK, base + D, ld, S);
+  stage_rows_T(sVt, base + 2 * D, ld, S);
+  __syncthreads();
+  const int q0 = blockIdx.x * 128 + wave * 32;
+  if (q0 >= S) return;
+  const int q = q0 + col;
+
+  bf16x8 qf[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) qf[t] = ld_frag(base + (long)q * ld + 16 * t + 8 * g);
+
+  floatx16 oacc[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float scale = 0.125f;  // 1/sqrt(64)
+
+  for (int kt = 0; kt < S / 32; ++kt) {
+    floatx16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(sK + (kt * 32 + col) * RS + 16 * t + 8 * g), qf[t], s, 0, 0, 0);
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s[r] *= scale;
+      tmax = fmaxf(tmax, s[r]);
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m_run, tmax);
+    const float alpha = __expf(m_run - m_new);
+    float p[16], rs = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      p[r] = __expf(s[r] - m_new);
+      rs += p[r];
+    }
+    rs += __shfl_xor(rs, 32, 64);
+    l_run = l_run * alpha + rs;
+    m_run = m_new;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      bf16x8 pf = pack_frag(p + 8 * u);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) {
+        const bf16_t* vp = sVt + (dt * 32 + col) * TS + kt * 32 + 16 * u + 4 * g;
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_2x4(vp, vp + 8), pf, oacc[dt], 0, 0, 0);
+      }
+    }
+  }
+  const float inv = 1.f / l_run;
+  bf16_t* orow = o + ((long)b * S + q) * D + h * HD;
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      uint2 v;
+      v.x = (uint32_t)f2bf(oacc[dt][4 * r4] * inv) | ((uint32_t)f2bf(oacc[dt][4 * r4 + 1] * inv) << 16);
+      v.y = (uint32_t)f2bf(oacc[dt][4 * r4 + 2] * inv) | ((uint32_t)f2bf(oacc[dt][4 * r4 + 3] * inv) << 16);
+      *reinterpret_cast<uint2*>(orow + dt * 32 + 8 * r4 + 4 * g) = v;
+    }
+  if (g == 0) lse[((long)b * H + h) * S + q] = m_run + __logf(l_run);
+}
+
+// ------------------------------------------------------------------ backward helpers
+// Dsum[b][h][q] = sum_d dO[q][d] * O[q][d]
+__global__ void attn_dsum_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
+                                 float* __restrict__ dsum, int S, int D, int H, long total) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;  // (b, q, h)
+  if (i >= total) return;
+  int h = (int)(i % H);
+  long bq = i / H;
+  int q = (int)(bq % S);
+  long b = bq / S;
+  const bf16_t* po = o + bq * D + h * HD;
+  const bf16_t* pd = d_o + bq * D + h * HD;
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    uint4 a = *reinterpret_cast<const uint4*>(po + c * 8);
+    uint4 d = *reinterpret_cast<const uint4*>(pd + c * 8);
+    const uint32_t* aw = reinterpret_cast<const uint32_t*>(&a);
+    const uint32_t* dw = reinterpret_cast<const uint32_t*>(&d);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      s += __uint_as_float(aw[k] << 16) * __uint_as_float(dw[k] << 16);
+      s += __uint_as_float(aw[k] & 0xffff0000u) * __uint_as_float(dw[k] & 0xffff0000u);
+    }
+  }
+  dsum[(b * H + h) * S + q] = s;
+}
+
+// dK, dV: a wavefront owns 32 keys (lane = key), loops over query tiles.
+__global__ __launch_bounds__(256) void attention_bwd_dkv_kernel(const bf16_t* __restrict__ qkv,
+                                                                const bf16_t* __restrict__ d_o,
+                                                                const float* __restrict__ lse,
+                                                                const float* __restrict__ dsum,
+                                                                bf16_t* __restrict__ dqkv, int S, int D, int H) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int TS = S + 8;
+  bf16_t* sQ = reinterpret_cast<bf16_t*>(smem);  // [S][RS]
+  bf16_t* sdO = sQ + S * RS;                     // [S][RS]
+  bf16_t* sQt = sdO + S * RS;                    // [64][TS]
+  bf16_t* sdOt = sQt + HD * TS;                  // [64][TS]
+  float* sL = reinterpret_cast<float*>(sdOt + HD * TS);  // [S] lse, then [S] dsum
+  float* sD = sL + S;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, g = lane >> 5;
+  const long ld = 3L * D;
+  const bf16_t* base = qkv + (long)b * S * ld + h * HD;
+  const bf16_t* dobase = d_o + (long)b * S * D + h * HD;
+  stage_rows(sQ, base, ld, S);
+  stage_rows(sdO, dobase, D, S);
+  stage_rows_T(sQt, base, ld, S);
+  stage_rows_T(sdOt, dobase, D, S);
+  for (int i = threadIdx.x; i < S; i += blockDim.x) {
+    sL[i] = lse[((long)b * H + h) * S + i];
+    sD[i] = dsum[((long)b * H + h) * S + i];
+  }
+  __syncthreads();
+  const int k0 = blockIdx.x * 128 + wave * 32;
+  if (k0 >= S) return;
+  const int key = k0 + col;
+  bf16x8 kf[4], vf[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    kf[t] = ld_frag(base + D + (long)key * ld + 16 * t + 8 * g);
+    vf[t] = ld_frag(base + 2 * D + (long)key * ld + 16 * t + 8 * g);
+  }
+  floatx16 dk[2], dv[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
+  const float scale = 0.125f;
+
+  for (int qt = 0; qt < S / 32; ++qt) {
+    floatx16 s, dp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(sQ + (qt * 32 + col) * RS + 16 * t + 8 * g), kf[t], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(sdO + (qt * 32 + col) * RS + 16 * t + 8 * g), vf[t], dp, 0, 0, 0);
+    }
+    float p[16], ds[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      int qq = qt * 32 + acc_row(r, g);
+      p[r] = __expf(s[r] * scale - sL[qq]);
+      ds[r] = p[r] * (dp[r] - sD[qq]);
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      bf16x8 pf = pack_frag(p + 8 * u), dsf = pack_frag(ds + 8 * u);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) {
+        const int off = (dt * 32 + col) * TS + qt * 32 + 16 * u + 4 * g;
+        dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_2x4(sdOt + off, sdOt + off + 8), pf, dv[dt], 0, 0, 0);
+        dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_2x4(sQt + off, sQt + off + 8), dsf, dk[dt], 0, 0, 0);
+      }
+    }
+  }
+  bf16_t* krow = dqkv + ((long)b * S + key) * ld + D + h * HD;
+  bf16_t* vrow = krow + D;
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      uint2 a, c;
+      a.x = (uint32_t)f2bf(dk[dt][4 * r4] * scale) | ((uint32_t)f2bf(dk[dt][4 * r4 + 1] * scale) << 16);
+      a.y = (uint32_t)f2bf(dk[dt][4 * r4 + 2] * scale) | ((uint32_t)f2bf(dk[dt][4 * r4 + 3] * scale) << 16);
+      c.x = (uint32_t)f2bf(dv[dt][4 * r4]) | ((uint32_t)f2bf(dv[dt][4 * r4 + 1]) << 16);
+      c.y = (uint32_t)f2bf(dv[dt][4 * r4 + 2]) | ((uint32_t)f2bf(dv[dt][4 * r4 + 3]) << 16);
+      *reinterpret_cast<uint2*>(krow + dt * 32 + 8 * r4 + 4 * g) = a;
+      *reinterpret_cast<uint2*>(vrow + dt * 32 + 8 * r4 + 4 * g) = c;
+    }
+}
+
+// dQ: a wavefront owns 32 queries (lane = query), loops over key tiles.
+__global__ __launch_bounds__(256) void attention_bwd_dq_kernel(const bf16_t* __restrict__ qkv,
+                                                               const bf16_t* __restrict__ d_o,
+                                                               const float* __restrict__ lse,
+                                                               const float* __restrict__ dsum,
+                                                               bf16_t* __restrict__ dqkv, int S, int D, int H) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int TS = S + 8;
+  bf16_t* sK = reinterpret_cast<bf16_t*>(smem);  // [S][RS]
+  bf16_t* sV = sK + S * RS;                      // [S][RS]
+  bf16_t* sKt = sV + S * RS;                     // [64][TS]
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, g = lane >> 5;
+  const long ld = 3L * D;
+  const bf16_t* base = qkv + (long)b * S * ld + h * HD;
+  stage_rows(sK, base + D, ld, S);
+  stage_rows(sV, base + 2 * D, ld, S);
+  stage_rows_T(sKt, base + D, ld, S);
+  __syncthreads();
+  const int q0 = blockIdx.x * 128 + wave * 32;
+  if (q0 >= S) return;
+  const int q = q0 + col;
+  bf16x8 qf[4], dof[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    qf[t] = ld_frag(base + (long)q * ld + 16 * t + 8 * g);
+    dof[t] = ld_frag(d_o + ((long)b * S + q) * D + h * HD + 16 * t + 8 * g);
+  }
+  const float lq = lse[((long)b * H + h) * S + q];
+  const float dq_sum = dsum[((long)b * H + h) * S + q];
+  floatx16 dq[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[dt][r] = 0.f;
+  const float scale = 0.125f;
+  for (int kt = 0; kt < S / 32; ++kt) {
+    floatx16 s, dp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(sK + (kt * 32 + col) * RS + 16 * t + 8 * g), qf[t], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(sV + (kt * 32 + col) * RS + 16 * t + 8 * g), dof[t], dp, 0, 0, 0);
+    }
+    float ds[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) ds[r] = __expf(s[r] * scale - lq) * (dp[r] - dq_sum);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      bf16x8 dsf = pack_frag(ds + 8 * u);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) {
+        const int off = (dt * 32 + col) * TS + kt * 32 + 16 * u + 4 * g;
+        dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_2x4(sKt + off, sKt + off + 8), dsf, dq[dt], 0, 0, 0);
+      }
+    }
+  }
+  bf16_t* qrow = dqkv + ((long)b * S + q) * ld + h * HD;
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      uint2 a;
+      a.x = (uint32_t)f2bf(dq[dt][4 * r4] * scale) | ((uint32_t)f2bf(dq[dt][4 * r4 + 1] * scale) << 16);
+      a.y = (uint32_t)f2bf(dq[dt][4 * r4 + 2] * scale) | ((uint32_t)f2bf(dq[dt][4 * r4 + 3] * scale) << 16);
+      *reinterpret_cast<uint2*>(qrow + dt * 32 + 8 * r4 + 4 * g) = a;
+    }
+}
+
+size_t lds_fwd(int S) { return ((size_t)S * RS + (size_t)HD * (S + 8)) * 2; }
+size_t lds_dkv(int S) { return ((size_t)2 * S * RS + (size_t)2 * HD * (S + 8)) * 2 + (size_t)2 * S * 4; }
+size_t lds_dq(int S) { return ((size_t)2 * S * RS + (size_t)HD * (S + 8)) * 2; }
+
+// kernels may need more than the default 64 KiB of dynamic LDS (S = 256)
+void allow_lds(const void* fn, size_t bytes) {
+  (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+}  // namespace
+
+size_t mha_bf16_ws_bytes(int B, int S, int D, int heads) {
+  (void)D;
+  return (size_t)B * heads * S * sizeof(float) + 256;  // Dsum
+}
+
+void attention_fwd_bf16(hipStream_t st, const bf16_t* qkv, bf16_t* o, float* lse, int B, int S, int D, int heads) {
+  size_t lds = lds_fwd(S);
+  allow_lds((const void*)attention_fwd_kernel, lds);
+  KLAUNCH(attention_fwd_kernel, dim3((S + 127) / 128, heads, B), dim3(256), lds, st, qkv, o, lse, S, D, heads);
+}
+
+void attention_bwd_bf16(hipStream_t st, const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o, const float* lse,
+                        bf16_t* dqkv, float* dsum, int B, int S, int D, int heads) {
+  long total = (long)B * S * heads;
+  KLAUNCH(attn_dsum_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, o, d_o, dsum, S, D, heads, total);
+  size_t l1 = lds_dkv(S), l2 = lds_dq(S);
+  allow_lds((const void*)attention_bwd_dkv_kernel, l1);
+  allow_lds((const void*)attention_bwd_dq_kernel, l2);
+  dim3 grid((S + 127) / 128, heads, B);
+  KLAUNCH(attention_bwd_dkv_kernel, grid, dim3(256), l1, st, qkv, d_o, lse, dsum, dqkv, S, D, heads);
+  KLAUNCH(attention_bwd_dq_kernel, grid, dim3(256), l2, st, qkv, d_o, lse, dsum, dqkv, S, D, heads);
+}
+
+}  // namespace ast

@@ -250,11 +250,12 @@ void bwd_op(Ctx& c, const Op& op) {
       char* sc = scratch(c);
       bf16_t* d_o = reinterpret_cast<bf16_t*>(sc);
       bf16_t* dqkv = d_o + R * D;
-      char* lw = sc + align256(R * 4 * D * sizeof(bf16_t));
+      float* dsum = reinterpret_cast<float*>(sc + align256(R * 4 * D * sizeof(bf16_t)));
+      char* lw = reinterpret_cast<char*>(dsum) + align256(mha_bf16_ws_bytes(I.n, I.h, D, op.heads));
       cb g = (cb)grad_ptr(c, op.out);
       linear_bf16_dgrad(st, g, s.shadow + op.sh2_off + (size_t)3 * D * D, d_o, R, D, D);
       linear_bf16_wgrad(st, g, o, Go, Gbo, lw, R, D, D);
-      attention_bwd_bf16(st, qkv, o, d_o, lse, dqkv, I.n, I.h, D, op.heads);
+      attention_bwd_bf16(st, qkv, o, d_o, lse, dqkv, dsum, I.n, I.h, D, op.heads);
       if (gin) linear_bf16_dgrad(st, dqkv, s.shadow + op.sh2_off, (bf16_t*)gin, R, D, 3 * D);
       linear_bf16_wgrad(st, dqkv, (cb)act_ptr(c, op.in), Gq, Gbq, lw, R, D, 3 * D);
       break;

@@ -59,12 +59,14 @@ void layernorm_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, const 
                         const float* gamma, bf16_t* dx, float* Ggamma, float* Gbeta, void* ws, size_t R,
                         int D);
 
-// ---- self-attention core on packed qkv [B][S][3D] (head size 64): o [B][S][D], lse [B][H][S]
+// ---- self-attention core on packed qkv [B][S][3D] (head size 64, S % 32 == 0, S <= 256):
+// o [B][S][D], lse [B][H][S]
 size_t mha_bf16_ws_bytes(int B, int S, int D, int heads);
 void attention_fwd_bf16(hipStream_t st, const bf16_t* qkv, bf16_t* o, float* lse, int B, int S, int D,
                         int heads);
+// `dsum` is scratch of mha_bf16_ws_bytes() bytes
 void attention_bwd_bf16(hipStream_t st, const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o,
-                        const float* lse, bf16_t* dqkv, int B, int S, int D, int heads);
+                        const float* lse, bf16_t* dqkv, float* dsum, int B, int S, int D, int heads);
 
 // bf16 <-> fp32 conversion of flat buffers
 void f32_to_bf16(hipStream_t st, const float* src, bf16_t* dst, size_t n);

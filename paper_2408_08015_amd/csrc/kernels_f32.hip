@@ -8,6 +8,7 @@
 // loaded straight from global memory, the small weight matrix is staged in LDS).
 #include "device_utils.h"
 #include "kernels.h"
+#include "prof.h"
 
 namespace ast {
 
@@ -100,7 +101,7 @@ void pw_conv_f32(hipStream_t st, const float* W, int lda_m, int lda_k, const flo
   int mt = cdiv(Mdim, 32);
   dim3 block(256);
 #define PW_LAUNCH(NT)                                                                         \
-  hipLaunchKernelGGL(pw_conv_f32_kernel<NT>, dim3(cdiv(NQ, 128), cdiv(mt, NT)), block, 0, st, W, \
+  KLAUNCH(pw_conv_f32_kernel<NT>, dim3(cdiv(NQ, 128), cdiv(mt, NT)), block, 0, st, W, \
                      lda_m, lda_k, X, Y, bias, add, NQ, HW, Kdim, Mdim)
   if (mt == 1) PW_LAUNCH(1);
   else if (mt == 2) PW_LAUNCH(2);
@@ -191,9 +192,9 @@ void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, f
   dim3 grid(chunks, cdiv(Cin, 32), cdiv(cdiv(Cout, 32), 4));
   // the vector path needs every chunk start to be a multiple of 8 pixels and aligned rows
   int vec = (HW % 4 == 0) ? 1 : 0;
-  hipLaunchKernelGGL(pw_wgrad_f32_kernel, grid, dim3(256), 0, st, g, x, part, Cin, Cout, HW, cps, vec);
+  KLAUNCH(pw_wgrad_f32_kernel, grid, dim3(256), 0, st, g, x, part, Cin, Cout, HW, cps, vec);
   size_t n = (size_t)Cin * Cout;
-  hipLaunchKernelGGL(reduce_parts_acc_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, part, G, n, chunks);
+  KLAUNCH(reduce_parts_acc_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, part, G, n, chunks);
 }
 
 // ============================================================== depthwise 3x3
@@ -321,14 +322,14 @@ void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int
                    int W, int stride) {
   int Ho = conv_out(H, 3, stride, 1), Wo = conv_out(W, 3, stride, 1);
   size_t total = (size_t)N * C * Ho * Wo;
-  hipLaunchKernelGGL(dw3x3_fwd_f32_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, x, w, y, C, H, W,
+  KLAUNCH(dw3x3_fwd_f32_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, x, w, y, C, H, W,
                      Ho, Wo, stride, total);
 }
 void dw3x3_dgrad_f32(hipStream_t st, const float* g, const float* w, float* dx, int N, int C, int H,
                      int W, int stride) {
   int Ho = conv_out(H, 3, stride, 1), Wo = conv_out(W, 3, stride, 1);
   size_t total = (size_t)N * C * H * W;
-  hipLaunchKernelGGL(dw3x3_dgrad_f32_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, w, dx, C, H,
+  KLAUNCH(dw3x3_dgrad_f32_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, w, dx, C, H,
                      W, Ho, Wo, stride, total);
 }
 size_t dw3x3_wgrad_f32_ws(int N, int C, int H, int W, int stride) {
@@ -339,9 +340,9 @@ void dw3x3_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part
                      int C, int H, int W, int stride) {
   int Ho = conv_out(H, 3, stride, 1), Wo = conv_out(W, 3, stride, 1);
   int S = dw_split(N, C, Ho, Wo);
-  hipLaunchKernelGGL(dw3x3_wgrad_f32_kernel, dim3(C, S), dim3(256), 0, st, g, x, part, N, C, H, W, Ho,
+  KLAUNCH(dw3x3_wgrad_f32_kernel, dim3(C, S), dim3(256), 0, st, g, x, part, N, C, H, W, Ho,
                      Wo, stride, S);
-  hipLaunchKernelGGL(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 256)), dim3(256), 0, st, part, G, C, S);
+  KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 256)), dim3(256), 0, st, part, G, C, S);
 }
 
 // ============================================================== generic direct conv
@@ -445,21 +446,21 @@ void conv_direct_fwd_f32(hipStream_t st, const float* x, const float* w, const f
                          int groups) {
   int Ho = conv_out(H, k, stride, pad), Wo = conv_out(W, k, stride, pad);
   size_t total = (size_t)N * Cout * Ho * Wo;
-  hipLaunchKernelGGL(conv_direct_fwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, x, w, bias, y,
+  KLAUNCH(conv_direct_fwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, x, w, bias, y,
                      Cin, H, W, Cout, Ho, Wo, k, stride, pad, groups, total);
 }
 void conv_direct_dgrad_f32(hipStream_t st, const float* g, const float* w, float* dx, int N, int Cin,
                            int H, int W, int Cout, int k, int stride, int pad, int groups) {
   int Ho = conv_out(H, k, stride, pad), Wo = conv_out(W, k, stride, pad);
   size_t total = (size_t)N * Cin * H * W;
-  hipLaunchKernelGGL(conv_direct_dgrad_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, w, dx, Cin,
+  KLAUNCH(conv_direct_dgrad_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, w, dx, Cin,
                      H, W, Cout, Ho, Wo, k, stride, pad, groups, total);
 }
 void conv_direct_wgrad_f32(hipStream_t st, const float* g, const float* x, float* G, int N, int Cin,
                            int H, int W, int Cout, int k, int stride, int pad, int groups) {
   int Ho = conv_out(H, k, stride, pad), Wo = conv_out(W, k, stride, pad);
   int nw = Cout * (Cin / groups) * k * k;
-  hipLaunchKernelGGL(conv_direct_wgrad_kernel, dim3(nw), dim3(256), 0, st, g, x, G, N, Cin, H, W, Cout,
+  KLAUNCH(conv_direct_wgrad_kernel, dim3(nw), dim3(256), 0, st, g, x, G, N, Cin, H, W, Cout,
                      Ho, Wo, k, stride, pad, groups);
 }
 
@@ -479,7 +480,7 @@ __global__ __launch_bounds__(256) void channel_sum_acc_kernel(const float* __res
   if (threadIdx.x == 0) G[c] += s;
 }
 void channel_sum_acc_f32(hipStream_t st, const float* g, float* G, int N, int C, int HW) {
-  hipLaunchKernelGGL(channel_sum_acc_kernel, dim3(C), dim3(256), 0, st, g, G, N, C, HW);
+  KLAUNCH(channel_sum_acc_kernel, dim3(C), dim3(256), 0, st, g, G, N, C, HW);
 }
 
 // ============================================================== BatchNorm
@@ -567,10 +568,10 @@ void bn_stats_f32(hipStream_t st, const float* x, const float* gamma, const floa
   size_t per = (size_t)N * HW;
   int S = bn_split(C, per);
   if (HW % 4 == 0)
-    hipLaunchKernelGGL(bn_stats_partial_kernel<true>, dim3(C, S), dim3(256), 0, st, x, ws, N, C, HW, S);
+    KLAUNCH(bn_stats_partial_kernel<true>, dim3(C, S), dim3(256), 0, st, x, ws, N, C, HW, S);
   else
-    hipLaunchKernelGGL(bn_stats_partial_kernel<false>, dim3(C, S), dim3(256), 0, st, x, ws, N, C, HW, S);
-  hipLaunchKernelGGL(bn_stats_final_kernel, dim3(cdiv(C, 128)), dim3(128), 0, st, ws, gamma, beta, stat,
+    KLAUNCH(bn_stats_partial_kernel<false>, dim3(C, S), dim3(256), 0, st, x, ws, N, C, HW, S);
+  KLAUNCH(bn_stats_final_kernel, dim3(cdiv(C, 128)), dim3(128), 0, st, ws, gamma, beta, stat,
                      scale_shift, running, C, S, (double)per, eps);
 }
 
@@ -609,10 +610,10 @@ void bn_apply_f32(hipStream_t st, const float* x, const float* ss, const float* 
                   int C, int HW, int act) {
   size_t total = (size_t)N * C * HW;
   if (HW % 4 == 0)
-    hipLaunchKernelGGL(bn_apply_kernel<true>, dim3(cdiv(total / 4, 256)), dim3(256), 0, st, x, ss, skip,
+    KLAUNCH(bn_apply_kernel<true>, dim3(cdiv(total / 4, 256)), dim3(256), 0, st, x, ss, skip,
                        y, C, HW, act, total);
   else
-    hipLaunchKernelGGL(bn_apply_kernel<false>, dim3(cdiv(total, 256)), dim3(256), 0, st, x, ss, skip, y,
+    KLAUNCH(bn_apply_kernel<false>, dim3(cdiv(total, 256)), dim3(256), 0, st, x, ss, skip, y,
                        C, HW, act, total);
 }
 
@@ -715,19 +716,19 @@ void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* sta
   int S = bn_split(C, per);
   bool vec = HW % 4 == 0;
   if (vec)
-    hipLaunchKernelGGL(bn_bwd_partial_kernel<true>, dim3(C, S), dim3(256), 0, st, g, x, stat, ss, ws, N,
+    KLAUNCH(bn_bwd_partial_kernel<true>, dim3(C, S), dim3(256), 0, st, g, x, stat, ss, ws, N,
                        C, HW, S, act);
   else
-    hipLaunchKernelGGL(bn_bwd_partial_kernel<false>, dim3(C, S), dim3(256), 0, st, g, x, stat, ss, ws, N,
+    KLAUNCH(bn_bwd_partial_kernel<false>, dim3(C, S), dim3(256), 0, st, g, x, stat, ss, ws, N,
                        C, HW, S, act);
-  hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(cdiv(C, 128)), dim3(128), 0, st, ws, stat, gamma, Ggamma,
+  KLAUNCH(bn_bwd_final_kernel, dim3(cdiv(C, 128)), dim3(128), 0, st, ws, stat, gamma, Ggamma,
                      Gbeta, coef, C, S, (double)per);
   if (!dx) return;  // the input gradient is not wanted
   if (vec)
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<true>, dim3(cdiv(total / 4, 256)), dim3(256), 0, st, g, x,
+    KLAUNCH(bn_bwd_apply_kernel<true>, dim3(cdiv(total / 4, 256)), dim3(256), 0, st, g, x,
                        stat, ss, coef, dx, C, HW, act, total);
   else
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<false>, dim3(cdiv(total, 256)), dim3(256), 0, st, g, x, stat,
+    KLAUNCH(bn_bwd_apply_kernel<false>, dim3(cdiv(total, 256)), dim3(256), 0, st, g, x, stat,
                        ss, coef, dx, C, HW, act, total);
 }
 
@@ -763,26 +764,26 @@ __global__ void zero16_kernel(uint4* __restrict__ d, size_t n16, unsigned char* 
   if (i < 16 && t < bytes) db[t] = 0;
 }
 void act_fwd_f32(hipStream_t st, const float* x, float* y, size_t n, int act) {
-  hipLaunchKernelGGL(act_fwd_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, x, y, n, act);
+  KLAUNCH(act_fwd_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, x, y, n, act);
 }
 void act_bwd_f32(hipStream_t st, const float* g, const float* x, float* dx, size_t n, int act) {
-  hipLaunchKernelGGL(act_bwd_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, g, x, dx, n, act);
+  KLAUNCH(act_bwd_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, g, x, dx, n, act);
 }
 void add_f32(hipStream_t st, const float* a, const float* b, float* y, size_t n) {
-  hipLaunchKernelGGL(add_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, a, b, y, n);
+  KLAUNCH(add_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, a, b, y, n);
 }
 void copy_bytes(hipStream_t st, const void* src, void* dst, size_t bytes) {
   if (!bytes) return;
   size_t n16 = bytes / 16;
   size_t threads = n16 > 16 ? n16 : 16;
-  hipLaunchKernelGGL(copy16_kernel, dim3(cdiv(threads, 256)), dim3(256), 0, st, (const uint4*)src,
+  KLAUNCH(copy16_kernel, dim3(cdiv(threads, 256)), dim3(256), 0, st, (const uint4*)src,
                      (uint4*)dst, n16, (const unsigned char*)src, (unsigned char*)dst, n16 * 16, bytes);
 }
 void fill_zero(hipStream_t st, void* dst, size_t bytes) {
   if (!bytes) return;
   size_t n16 = bytes / 16;
   size_t threads = n16 > 16 ? n16 : 16;
-  hipLaunchKernelGGL(zero16_kernel, dim3(cdiv(threads, 256)), dim3(256), 0, st, (uint4*)dst, n16,
+  KLAUNCH(zero16_kernel, dim3(cdiv(threads, 256)), dim3(256), 0, st, (uint4*)dst, n16,
                      (unsigned char*)dst, n16 * 16, bytes);
 }
 
@@ -804,11 +805,11 @@ __global__ void gap_bwd_kernel(const float* __restrict__ g, float* __restrict__ 
   if (i < total) dx[i] = g[i / HW] / (float)HW;
 }
 void gap_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int HW) {
-  hipLaunchKernelGGL(gap_fwd_kernel, dim3(cdiv(NC, 4)), dim3(256), 0, st, x, y, NC, HW);
+  KLAUNCH(gap_fwd_kernel, dim3(cdiv(NC, 4)), dim3(256), 0, st, x, y, NC, HW);
 }
 void gap_bwd_f32(hipStream_t st, const float* g, float* dx, int NC, int HW) {
   size_t total = (size_t)NC * HW;
-  hipLaunchKernelGGL(gap_bwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, dx, total, HW);
+  KLAUNCH(gap_bwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, dx, total, HW);
 }
 
 __device__ __forceinline__ int first_argmax4(float a, float b, float c, float d) {
@@ -850,13 +851,13 @@ __global__ void maxpool_bwd_kernel(const float* __restrict__ g, const float* __r
 void maxpool_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int H, int W) {
   int Ho = H / 2, Wo = W / 2;
   size_t total = (size_t)NC * Ho * Wo;
-  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, x, y, H, W, Ho, Wo,
+  KLAUNCH(maxpool_fwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, x, y, H, W, Ho, Wo,
                      total);
 }
 void maxpool_bwd_f32(hipStream_t st, const float* g, const float* x, float* dx, int NC, int H, int W) {
   int Ho = H / 2, Wo = W / 2;
   size_t total = (size_t)NC * H * W;
-  hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, x, dx, H, W, Ho,
+  KLAUNCH(maxpool_bwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, x, dx, H, W, Ho,
                      Wo, total);
 }
 
@@ -915,16 +916,16 @@ __global__ void linear_wgrad_kernel(const float* __restrict__ g, const float* __
 }
 void linear_fwd_f32(hipStream_t st, const float* x, const float* W, const float* b, float* y, int R,
                     int Cin, int Cout) {
-  hipLaunchKernelGGL(linear_fwd_kernel, dim3(cdiv(Cout, 4)), dim3(256), 0, st, x, W, b, y, R, Cin, Cout);
+  KLAUNCH(linear_fwd_kernel, dim3(cdiv(Cout, 4)), dim3(256), 0, st, x, W, b, y, R, Cin, Cout);
 }
 void linear_dgrad_f32(hipStream_t st, const float* g, const float* W, float* dx, int R, int Cin,
                       int Cout) {
-  hipLaunchKernelGGL(linear_dgrad_kernel, dim3(cdiv((long)R * Cin, 256)), dim3(256), 0, st, g, W, dx, R,
+  KLAUNCH(linear_dgrad_kernel, dim3(cdiv((long)R * Cin, 256)), dim3(256), 0, st, g, W, dx, R,
                      Cin, Cout);
 }
 void linear_wgrad_f32(hipStream_t st, const float* g, const float* x, float* GW, float* Gb, int R,
                       int Cin, int Cout) {
-  hipLaunchKernelGGL(linear_wgrad_kernel, dim3(cdiv((long)Cout * Cin, 256)), dim3(256), 0, st, g, x, GW,
+  KLAUNCH(linear_wgrad_kernel, dim3(cdiv((long)Cout * Cin, 256)), dim3(256), 0, st, g, x, GW,
                      Gb, R, Cin, Cout);
 }
 
@@ -971,13 +972,13 @@ __global__ void softmax_ce_bwd_kernel(const float* __restrict__ p, const int32_t
 }
 void softmax_ce_fwd_f32(hipStream_t st, const float* z, const int32_t* labels, float* p,
                         float* row_loss, float* loss_out, int R, int C, float inv_denom) {
-  hipLaunchKernelGGL(softmax_ce_fwd_kernel, dim3(R), dim3(256), 0, st, z, labels, p, row_loss, C);
+  KLAUNCH(softmax_ce_fwd_kernel, dim3(R), dim3(256), 0, st, z, labels, p, row_loss, C);
   if (loss_out)
-    hipLaunchKernelGGL(loss_sum_kernel, dim3(1), dim3(64), 0, st, row_loss, loss_out, R, inv_denom);
+    KLAUNCH(loss_sum_kernel, dim3(1), dim3(64), 0, st, row_loss, loss_out, R, inv_denom);
 }
 void softmax_ce_bwd_f32(hipStream_t st, const float* p, const int32_t* labels, float* dz, int R, int C,
                         float inv_denom) {
-  hipLaunchKernelGGL(softmax_ce_bwd_kernel, dim3(cdiv((long)R * C, 256)), dim3(256), 0, st, p, labels,
+  KLAUNCH(softmax_ce_bwd_kernel, dim3(cdiv((long)R * C, 256)), dim3(256), 0, st, p, labels,
                      dz, R, C, inv_denom);
 }
 
@@ -1005,7 +1006,7 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ w, float* 
 }
 void sgd_momentum_f32(hipStream_t st, float* w, float* g, float* v, size_t n, float lr, float mu) {
   if (!n) return;
-  hipLaunchKernelGGL(sgd_kernel, dim3(cdiv(cdiv(n, 4), 256)), dim3(256), 0, st, w, g, v, n, lr, mu);
+  KLAUNCH(sgd_kernel, dim3(cdiv(cdiv(n, 4), 256)), dim3(256), 0, st, w, g, v, n, lr, mu);
 }
 
 }  // namespace ast

@@ -184,7 +184,7 @@ ast_status build_plan(Stage& s, std::string& err) {
       }
       case AST_LAYERNORM: {
         if (!s.bf16 || A.rank == 4 || L.p[0] != A.c) { err = fmt("layer %d: layernorm needs bf16 rows with D=%d", i, A.c); return s.bf16 ? AST_EINVAL : AST_EUNSUPPORTED; }
-        if (A.c % 8 || A.c > 8192) { err = fmt("layer %d: layernorm needs D %% 8 == 0 and D <= 8192", i); return AST_EUNSUPPORTED; }
+        if (A.c % 8 || A.c > 1024) { err = fmt("layer %d: layernorm needs D %% 8 == 0 and D <= 1024", i); return AST_EUNSUPPORTED; }
         op.kind = OP_LAYERNORM; op.cin = op.cout = A.c; op.eps = L.eps;
         op.w_off = poff; poff += A.c; op.b_off = poff; poff += A.c; op.has_bias = 1;
         take_aux(op, 2 * sizeof(float) * (size_t)A.n * A.h);  // mean, istd per row
@@ -278,8 +278,8 @@ ast_status build_plan(Stage& s, std::string& err) {
       case OP_LAYERNORM: need = layernorm_bf16_ws_bytes((size_t)I.n * I.h, I.c); break;
       case OP_MHA:  // d_o and dqkv, then the split-K partials of the two projections
         need = align_up((size_t)I.n * I.h * 4 * op.cin * 2, 256) +
-               std::max(linear_bf16_ws_bytes((size_t)I.n * I.h, op.cin, 3 * op.cin),
-                        mha_bf16_ws_bytes(I.n, I.h, op.cin, op.heads));
+               align_up(mha_bf16_ws_bytes(I.n, I.h, op.cin, op.heads), 256) +
+               linear_bf16_ws_bytes((size_t)I.n * I.h, op.cin, 3 * op.cin);
         break;
       default: break;
     }

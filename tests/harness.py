@@ -26,7 +26,8 @@ def split_params(layers, flat):
 
 def run_oracle(cfg, inp, K=1, rounds=2, keep_acts=False):
     from oracle import OracleStage, run_round
-    st = OracleStage(cfg.layers, cfg.B, cfg.M, cfg.in_shape, cfg.layout, cfg.needs_input_grad)
+    st = OracleStage(cfg.layers, cfg.B, cfg.M, cfg.in_shape, cfg.layout, cfg.needs_input_grad,
+                     storage="bf16" if cfg.dtype == "bf16" else "f64")
     st.keep_acts = keep_acts
     st.set_params(inp["params"])
     target = inp["labels"] if cfg.loss_tail else inp["dy"]
@@ -62,13 +63,15 @@ def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None):
         dy = torch.from_numpy(inp["dy"]).to(dev).to(tdt).contiguous()
         y = torch.zeros_like(dy)
     dx = torch.zeros_like(x) if cfg.needs_input_grad else None
-    losses = torch.zeros(M, device=dev, dtype=torch.float32)
+    losses = torch.zeros(M * 4, device=dev, dtype=torch.float32)
     res, dbg = [], {}
+    # one separately allocated (hence aligned) buffer per micro-batch, as a pipeline would hold
+    mbs = lambda t: None if t is None else [t[m * B:(m + 1) * B].clone() for m in range(M)]
+    xs, ys, dys, dxs, labs = mbs(x), mbs(y), mbs(dy), mbs(dx), mbs(labels)
 
     def fwd(m, r):
-        sl = slice(m * B, (m + 1) * B)
-        st.forward(m, x[sl], labels[sl] if labels is not None else None, y[sl],
-                   losses[m:m + 1] if cfg.loss_tail else None)
+        st.forward(m, xs[m], labs[m] if labs is not None else None, ys[m],
+                   losses[4 * m:4 * m + 1] if cfg.loss_tail else None)
         if debug_layers and r == 0 and m == 0:
             for li in debug_layers:
                 try:
@@ -80,16 +83,17 @@ def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None):
         for m in range(min(K, M)):
             fwd(m, r)
         for m in range(M):
-            sl = slice(m * B, (m + 1) * B)
-            st.backward(m, dy[sl] if dy is not None else None, dx[sl] if dx is not None else None)
+            st.backward(m, dys[m] if dys is not None else None, dxs[m] if dxs is not None else None)
             if m + K < M:
                 fwd(m + K, r)
         torch.cuda.synchronize()
         G = st.get_grads()
         st.step(cfg.lr, cfg.momentum)
         torch.cuda.synchronize()
-        res.append(dict(y=y.float().cpu().numpy(), loss=float(losses.sum().item()) if cfg.loss_tail else None,
-                        dx=dx.float().cpu().numpy() if dx is not None else None, G=G, W=st.get_params()))
+        res.append(dict(y=torch.cat(ys).float().cpu().numpy(),
+                        loss=float(losses.double().sum().item()) if cfg.loss_tail else None,
+                        dx=torch.cat(dxs).float().cpu().numpy() if dxs is not None else None, G=G,
+                        W=st.get_params()))
     mem = st.memory()
     st.close()
     return res, dbg, mem
@@ -109,4 +113,91 @@ def score(cfg, hip, ora):
         out["r%d.G" % r] = max(gw, key=lambda t: t[1])
         out["r%d.W" % r] = max(ww, key=lambda t: t[1])
         out["r%d.G_all" % r] = gw
+    return out
+
+
+# ---------------------------------------------------------------- stored expected values
+def golden_path(name):
+    import os
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "%s_full.npz" % name)
+
+
+def golden_velocity(cfg, n):
+    """The seeded initial velocity used by tests/golden/make_golden.py."""
+    rng = np.random.Generator(np.random.PCG64(cfg.seed + 7))
+    return (rng.standard_normal(n) * 0.05).astype(np.float32)
+
+
+def run_hip_one_round(cfg, inp, v0=None, K=1):
+    """One HPP-Round on the GPU at the launch configuration bench.py times (K = 1 by default).
+    Returns y, loss, dx, G (before the update), W (after it) as numpy arrays."""
+    import torch
+    import paper_2408_08015_amd as A
+    dev = torch.device("cuda:0")
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    st = A.Stage(cfg.layers, cfg.B, cfg.M, K, cfg.in_shape, cfg.dtype, cfg.layout, cfg.needs_input_grad,
+                 stream=torch.cuda.current_stream().cuda_stream)
+    st.set_params(inp["params"])
+    if v0 is not None:
+        st.set_velocity(v0)
+    x = torch.from_numpy(inp["x"]).to(dev).to(tdt).contiguous()
+    B, M = cfg.B, cfg.M
+    if cfg.loss_tail:
+        labels = torch.from_numpy(inp["labels"]).to(dev)
+        y = torch.zeros((B * M, gen.out_shape(cfg.layers, cfg.in_shape)[0]), device=dev)
+        dy = None
+    else:
+        labels = None
+        dy = torch.from_numpy(inp["dy"]).to(dev).to(tdt).contiguous()
+        y = torch.zeros_like(dy)
+    dx = torch.zeros_like(x) if cfg.needs_input_grad else None
+    losses = torch.zeros(M * 4, device=dev)
+    mbs = lambda t: None if t is None else [t[m * B:(m + 1) * B].clone() for m in range(M)]
+    xs, ys, dys, dxs, labs = mbs(x), mbs(y), mbs(dy), mbs(dx), mbs(labels)
+
+    def fwd(m):
+        st.forward(m, xs[m], labs[m] if labs is not None else None, ys[m],
+                   losses[4 * m:4 * m + 1] if cfg.loss_tail else None)
+
+    for m in range(min(K, M)):
+        fwd(m)
+    for m in range(M):
+        st.backward(m, dys[m] if dys is not None else None, dxs[m] if dxs is not None else None)
+        if m + K < M:
+            fwd(m + K)
+    torch.cuda.synchronize()
+    G = st.get_grads()
+    st.step(cfg.lr, cfg.momentum)
+    torch.cuda.synchronize()
+    out = dict(y=torch.cat(ys).float().cpu().numpy(), loss=float(losses.double().sum().item()),
+               dx=torch.cat(dxs).float().cpu().numpy() if dxs is not None else None, G=G, W=st.get_params(),
+               V=st.get_velocity())
+    st.close()
+    return out
+
+
+def score_golden(cfg, hip, gold):
+    """rel-L2 on the stored samples: y, dx, loss, and per parameter tensor G and W.
+    A tensor whose oracle gradient is (numerically) zero is scored against the floor
+    1e-2 * rms(G) instead of its own norm."""
+    out = {"y": rel_l2(hip["y"].ravel()[gold["y_idx"]], gold["y"])}
+    if cfg.needs_input_grad:
+        out["dx"] = rel_l2(hip["dx"].ravel()[gold["dx_idx"]], gold["dx"])
+    if cfg.loss_tail:
+        out["loss"] = abs(hip["loss"] - float(gold["loss"])) / abs(float(gold["loss"]))
+    g_rms = float(gold["G_rms"])
+    gs, ws = [], []
+    for name, hv in split_params(cfg.layers, hip["G"]):
+        idx = gold["idx/" + name]
+        ref = gold["G/" + name].astype(np.float64)
+        err = np.linalg.norm(hv[idx] - ref)
+        floor = 1e-2 * g_rms * np.sqrt(idx.size)
+        gs.append((name, float(err / max(np.linalg.norm(ref), floor))))
+    for name, hv in split_params(cfg.layers, hip["W"]):
+        idx = gold["idx/" + name]
+        ws.append((name, rel_l2(hv[idx], gold["W/" + name])))
+    out["G"] = max(gs, key=lambda t: t[1])
+    out["W"] = max(ws, key=lambda t: t[1])
+    out["G_all"] = gs
+    out["G_median"] = float(np.median([e for _, e in gs]))
     return out

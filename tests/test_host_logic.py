@@ -1,0 +1,116 @@
+"""CPU-only checks: the C-ABI library loads and exports every declared symbol, host-side
+planning (shape inference, Eq. (3) byte counts, argument errors), the warm-up depth
+formula, and the seeded generators."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from asteroid_workloads import configs as C
+from asteroid_workloads import gen, get_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2408_08015_amd as A
+    A.load_library()
+    return A
+
+
+def test_library_exports_every_declared_symbol(A):
+    hdr = open(os.path.join(ROOT, "include", "asteroid.h")).read()
+    names = sorted(set(re.findall(r"\b(asteroid_[a-z_0-9]+)\s*\(", hdr)))
+    assert "asteroid_stage_create" in names and "asteroid_stage_step" in names and len(names) >= 15
+    lib = ctypes.CDLL(A.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_kp_matches_the_papers_example(A):
+    # Sec. 3.2: K_p = 2(P - p) - 1; the paper's 3-stage pipeline has K_0 = 5, K_1 = 3, K_2 = 1
+    assert [A.kp(3, p) for p in range(3)] == [5, 3, 1]
+    assert A.kp(1, 0) == 1
+    assert A.kp(3, 3) == -1 and A.kp(0, 0) == -1 and A.kp(2, -1) == -1
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_plan_memory_follows_eq3(A, name):
+    """Eq. (3): Mem = MOD + OPT + K * ACT.  MOD = fp32 params + fp32 accumulated gradients
+    (+ bf16 weight copies), OPT = fp32 velocity, ACT independent of K and M."""
+    cfg = get_config(name)
+    n = gen.num_params(cfg.layers)
+    args = (cfg.layers, cfg.B, cfg.M)
+    m1 = A.plan_memory(*args, 1, cfg.in_shape, cfg.dtype, cfg.layout, cfg.needs_input_grad)
+    m3 = A.plan_memory(*args, cfg.M, cfg.in_shape, cfg.dtype, cfg.layout, cfg.needs_input_grad)
+    assert m1 == m3                               # per-micro-batch stash does not depend on K
+    mod, opt, act, ws = m1
+    assert opt == 4 * n
+    if cfg.dtype == "f32":
+        assert mod == 8 * n
+    else:
+        assert mod > 8 * n and mod <= 8 * n + 2 * 2 * n + 64   # two bf16 layouts of each matrix
+    # the stash holds at least the stage input and every conv / linear input
+    x_bytes = int(np.prod(cfg.in_shape)) * cfg.B * (2 if cfg.dtype == "bf16" else 4)
+    assert act >= x_bytes
+    # a bigger micro-batch needs a proportionally bigger stash (activations dominate)
+    big = A.plan_memory(cfg.layers, 2 * cfg.B, cfg.M, 1, cfg.in_shape, cfg.dtype, cfg.layout, cfg.needs_input_grad)
+    assert 1.8 * act < big[2] < 2.2 * act
+
+
+def test_plan_errors(A):
+    ok = C.cfg1()
+    with pytest.raises(A.AsteroidError) as e:
+        A.plan_memory(ok.layers, 4, 2, 3, ok.in_shape)           # K > M
+    assert e.value.status == -1
+    with pytest.raises(A.AsteroidError) as e:
+        A.plan_memory(ok.layers, 4, 2, 1, (16, 8, 8))            # channel mismatch
+    assert e.value.status == -1
+    with pytest.raises(A.AsteroidError) as e:
+        A.plan_memory([dict(kind="res_add")], 4, 2, 1, (16, 8, 8))
+    assert e.value.status == -1
+    with pytest.raises(A.AsteroidError) as e:
+        A.plan_memory([dict(kind="res_begin"), dict(kind="relu")], 4, 2, 1, (16, 8, 8))
+    assert e.value.status == -1
+    with pytest.raises(A.AsteroidError) as e:                     # loss tail must be last
+        A.plan_memory([dict(kind="global_avgpool"), dict(kind="softmax_ce"), dict(kind="relu")], 4, 2, 1, (16, 8, 8))
+    assert e.value.status == -1
+    with pytest.raises(A.AsteroidError) as e:                     # fp32 stages are NCHW
+        A.plan_memory(ok.layers, 4, 2, 1, ok.in_shape, "f32", "nhwc")
+    assert e.value.status == -5
+    with pytest.raises(A.AsteroidError) as e:                     # bf16 BatchNorm is not covered
+        A.plan_memory(ok.layers, 4, 2, 1, ok.in_shape, "bf16", "nhwc")
+    assert e.value.status == -5
+    with pytest.raises(A.AsteroidError):
+        A.plan_memory(ok.layers, 0, 2, 1, ok.in_shape)
+
+
+def test_generators_are_seeded_and_ordered():
+    cfg = C.cfg1()
+    a, b = gen.make_inputs(cfg), gen.make_inputs(cfg)
+    for k in a:
+        assert np.array_equal(a[k], b[k])
+    rng = np.random.Generator(np.random.PCG64(cfg.seed))
+    x = rng.standard_normal((8, 32, 16, 16)).astype(np.float32)
+    assert np.array_equal(a["x"], x)                       # x is drawn first
+    lab = rng.integers(0, 10, size=8).astype(np.int32)
+    assert np.array_equal(a["labels"], lab)                # then the labels
+    assert a["params"].size == 30026
+    assert [gen.num_params(get_config(n).layers) for n in ("cfg2", "cfg3", "cfg4", "cfg5")] == \
+        [39696, 3504872, 1475328, 18914304]
+
+
+def test_bf16_rounding_helper():
+    v = np.array([1.0, 1.00390625, 1.01171875, -3.14159, 65504.0, 1e-40], np.float32)
+    r = gen.round_to_bf16(v)
+    assert np.all((r.view(np.uint32) & 0xFFFF) == 0)
+    assert r[0] == 1.0
+    assert r[1] == 1.0            # 1 + 2^-8 is a tie: rounds to even (1.0)
+    assert r[2] == np.float32(1.015625)   # 1 + 3*2^-8 ties to the even neighbour 1 + 2^-6
+    assert abs(r[3] + 3.140625) < 1e-6
+    c4 = get_config("cfg4", B=1, M=1, hw=4, cin=8, c=8)
+    inp = gen.make_inputs(c4)
+    assert np.array_equal(gen.round_to_bf16(inp["x"]), inp["x"]) and inp["x"].shape == (1, 4, 4, 8)

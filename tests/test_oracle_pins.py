@@ -345,9 +345,12 @@ def test_mobilenetv2_schedule():
 
 
 # ----------------------------------------------------------------- independent library cross-check
-def torch_stage(cfg, params, x, target, dtype=torch.float64):
-    """The same layer list through PyTorch CPU functional ops + autograd (float64 by default)."""
+def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False):
+    """The same layer list through PyTorch CPU functional ops + autograd (float64 by default).
+    bf16_storage: weight matrices and every layer output pass through the library's own
+    bf16 cast (round to nearest even) with a straight-through gradient."""
     t = lambda a: torch.tensor(np.asarray(a, np.float64)).to(dtype)
+    rb = (lambda v: v + (v.float().bfloat16().to(dtype) - v).detach()) if bf16_storage else (lambda v: v)
     W = t(params).requires_grad_(True)
     xs = t(x).requires_grad_(True)
     off = 0
@@ -371,7 +374,7 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64):
         for l in cfg.layers:
             k = l["kind"]
             if k == "conv2d":
-                w = take((l["cout"], l["cin"] // l["groups"], l["k"], l["k"]))
+                w = rb(take((l["cout"], l["cin"] // l["groups"], l["k"], l["k"])))
                 b = take((l["cout"],)) if l["bias"] else None
                 a = TF.conv2d(a, w, b, l["stride"], l["pad"], 1, l["groups"])
             elif k == "batchnorm2d":
@@ -395,12 +398,12 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64):
             elif k == "maxpool2x2":
                 a = TF.max_pool2d(a, 2, 2)
             elif k == "linear":
-                w = take((l["cout"], l["cin"]))
+                w = rb(take((l["cout"], l["cin"])))
                 b = take((l["cout"],)) if l["bias"] else None
                 a = TF.linear(a, w, b)
             elif k == "mha":
                 d = l["d"]
-                wq, bq, wo, bo = take((3 * d, d)), take((3 * d,)), take((d, d)), take((d,))
+                wq, bq, wo, bo = rb(take((3 * d, d))), take((3 * d,)), rb(take((d, d))), take((d,))
                 at = a.transpose(0, 1)        # (S, N, D)
                 o, _ = TF.multi_head_attention_forward(
                     at, at, at, d, l["heads"], wq, bq, None, None, False, 0.0, wo, bo,
@@ -409,6 +412,8 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64):
             elif k == "softmax_ce":
                 lab = torch.tensor(target[m * B:(m + 1) * B].astype(np.int64))
                 total = total + TF.cross_entropy(a, lab, reduction="sum") / (M * B)
+            if k not in ("softmax_ce", "res_begin"):
+                a = rb(a)
         if not cfg.loss_tail:
             if cfg.layout == "nhwc":
                 a = a.permute(0, 2, 3, 1)
@@ -437,3 +442,36 @@ def test_stage_matches_torch_float64_autograd(cfg):
         np.testing.assert_allclose(np.concatenate(dxs), t_dx, rtol=1e-8, atol=1e-10)
     if cfg.loss_tail:
         assert abs(loss - t_loss) < 1e-10
+
+
+@pytest.mark.parametrize("cfg", [
+    C.cfg4(B=2, M=2, hw=6, cin=4, c=6),
+    C.cfg5(B=2, M=2, S=7, d=16, heads=2, ffn=24, nlayers=2),
+], ids=lambda c: c.name)
+def test_bf16_storage_mode_matches_torch_with_library_bf16_casts(cfg):
+    """storage="bf16": the prescribed roundings (weight matrices, layer outputs) checked against
+    PyTorch float64 autograd with torch's own bfloat16 casts at the same points."""
+    inp = gen.make_inputs(cfg, randomize_affine=True)
+    st = OracleStage(cfg.layers, cfg.B, cfg.M, cfg.in_shape, cfg.layout, cfg.needs_input_grad, storage="bf16")
+    st.set_params(inp["params"])
+    ys, _, dxs = run_round(st, inp["x"], inp["dy"])
+    t_out, t_G, t_dx, _ = torch_stage(cfg, inp["params"], inp["x"], inp["dy"], bf16_storage=True)
+    y = np.concatenate(ys)
+    assert np.array_equal(gen.round_to_bf16(y.astype(np.float32)).astype(np.float64), y)   # outputs are bf16 values
+    np.testing.assert_allclose(y, np.concatenate(t_out), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(st.G, t_G, rtol=1e-8, atol=1e-10)
+    np.testing.assert_allclose(np.concatenate(dxs), t_dx, rtol=1e-8, atol=1e-10)
+    # and it is a small perturbation of the unrounded computation
+    pure = OracleStage(cfg.layers, cfg.B, cfg.M, cfg.in_shape, cfg.layout, cfg.needs_input_grad)
+    pure.set_params(inp["params"])
+    yp, _, _ = run_round(pure, inp["x"], inp["dy"])
+    assert np.linalg.norm(y - np.concatenate(yp)) <= 2e-2 * np.linalg.norm(np.concatenate(yp))
+
+
+def test_round_bf16_helper():
+    from oracle.stage import round_bf16
+    v = np.array([1.0, 1.00390625, 1.01171875, -3.14159, 0.1, 3.0e38])
+    r = round_bf16(v)
+    assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.015625      # ties go to the even mantissa
+    assert r[3] == -3.140625 and abs(r[4] - 0.10009765625) < 1e-15
+    assert np.array_equal(round_bf16(r), r)
