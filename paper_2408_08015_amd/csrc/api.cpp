@@ -282,7 +282,7 @@ ast_status asteroid_stage_debug_activation(asteroid_stage* h, int32_t mb, int32_
   if (mb < 0 || mb >= s.cfg.M || s.mb_slot[mb] < 0) return fail(AST_ESTATE, "debug_activation: micro-batch has no live stash");
   int id = s.layer_act[layer];
   const ast::Act& A = s.acts[id];
-  if (id == s.final_act && !s.loss_tail) return fail(AST_EINVAL, "debug_activation: the stage output lives in the caller's buffer");
+  if (id == s.final_act && !s.loss_tail && !s.final_in_slot) return fail(AST_EINVAL, "debug_activation: the stage output lives in the caller's buffer");
   if (n_out) *n_out = A.elems;
   if (!host_out) return AST_OK;
   HIPCHK(hipStreamSynchronize(s.stream), "debug_activation");

@@ -18,7 +18,7 @@ struct Ctx {
 inline int final_act_of(const Stage& s) { return s.final_act; }
 
 inline void* act_ptr(Ctx& c, int id) {
-  if (id == c.final_act && !c.s.loss_tail && id != 0) return c.s.cur_y;
+  if (id == c.final_act && !c.s.loss_tail && id != 0 && !c.s.final_in_slot) return c.s.cur_y;
   return c.slot + c.s.acts[id].slot_off;
 }
 inline void* grad_ptr(Ctx& c, int id) {
@@ -282,6 +282,8 @@ ast_status run_forward(Stage& s, int slot, const void* x, const int32_t* labels,
   s.cur_dx = nullptr;
   copy_bytes(s.stream, x, c.slot + s.acts[0].slot_off, s.acts[0].bytes);
   for (const Op& op : s.ops) fwd_op(c, op, labels, loss);
+  if (s.final_in_slot && !s.loss_tail)
+    copy_bytes(s.stream, c.slot + s.acts[s.final_act].slot_off, y, s.acts[s.final_act].bytes);
   return check_launch(err, "forward");
 }
 

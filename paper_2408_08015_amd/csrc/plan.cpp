@@ -234,8 +234,13 @@ ast_status build_plan(Stage& s, std::string& err) {
   size_t off = 0;
   const int final_act = cur;
   s.final_act = cur;
+  // An op that masks its upstream gradient by its own OUTPUT needs that output in the backward.
+  for (const Op& op : s.ops)
+    if (op.out == cur && op.kind != OP_RES_BEGIN && op.kind != OP_SOFTMAX_CE &&
+        ((op.kind == OP_CONV_IGEMM && op.act) || (op.kind == OP_ACT && s.bf16 && op.act != 3)))
+      s.final_in_slot = true;
   for (size_t a = 0; a < s.acts.size(); ++a) {
-    if ((int)a == final_act && !s.loss_tail && a != 0) continue;
+    if ((int)a == final_act && !s.loss_tail && a != 0 && !s.final_in_slot) continue;
     s.acts[a].slot_off = off;
     off = align_up(off + s.acts[a].bytes, 256);
   }

@@ -69,6 +69,8 @@ struct Stage {
   bool bf16 = false;
   bool loss_tail = false;
   int final_act = 0;  // activation id of the stage output (logits for a loss tail)
+  bool final_in_slot = false;  // the backward reads the stage output (a fused ReLU mask): it is
+                               // produced in the stash and copied to the caller's buffer
   int n_classes = 0;
 
   size_t nparams = 0;

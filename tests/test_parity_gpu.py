@@ -255,3 +255,84 @@ def test_cfg3_full_golden(A):
     # Derived bar: PyTorch CPU fp32 deviates by 9e-3 (median over tensors) and 1.7e-2 (max).
     sc = golden_check("cfg3", 1e-4, None, 5e-2, 5e-2)
     assert sc["G_median"] <= 2e-2
+
+
+# ------------------------------------------------------------------ bf16 operands / fp32 accumulation
+TOL_BF16 = 2e-2
+
+
+def one_bf16(layers, in_shape, layout, B=2, M=2, name="op16", seed=9):
+    return StageConfig(name, layers, B, M, in_shape, "bf16", layout, True, seed, init="kaiming")
+
+
+def enc(d, heads, ffn):
+    return C.encoder_layer(d, heads, ffn)
+
+
+@pytest.mark.parametrize("cin,cout,k,hw,B", [
+    (16, 24, 3, 12, 2),       # smaller than one tile in N, ragged in M
+    (128, 256, 3, 14, 2),     # cfg-4 channel counts: two N tiles, K = 1152 (36 K-tiles)
+    (64, 136, 1, 9, 3),       # 1x1, ragged N tile
+    (8, 8, 3, 5, 1),          # K = 72: a ragged last K-tile
+])
+def test_bf16_conv(A, cin, cout, k, hw, B):
+    L = [conv(cin, cout, k, 1, (k - 1) // 2, bias=True), simple("relu")]
+    check(one_bf16(L, (cin, hw, hw), "nhwc", B=B), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+
+
+def test_bf16_conv_without_relu_and_maxpool(A):
+    check(one_bf16([conv(16, 16, 3, 1, 1, bias=False)], (16, 6, 6), "nhwc"), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+    L = [conv(8, 16, 3, 1, 1, bias=True), simple("relu"), simple("maxpool2x2")]
+    check(one_bf16(L, (8, 9, 7), "nhwc", B=3), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)   # odd H, W: uncovered edge
+
+
+@pytest.mark.parametrize("rows_s,cin,cout,gelu", [(64, 128, 256, True), (40, 512, 136, False), (128, 2048, 512, False), (24, 8, 8, True)])
+def test_bf16_linear(A, rows_s, cin, cout, gelu):
+    L = [linear(cin, cout)] + ([simple("gelu")] if gelu else [])
+    cfg = one_bf16(L, (rows_s, cin), "bsd", B=3)
+    cfg.init = "normal0.02" if cin > 64 else "kaiming"
+    check(cfg, tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+
+
+@pytest.mark.parametrize("S,d", [(32, 64), (128, 512), (96, 1024)])
+def test_bf16_layernorm(A, S, d):
+    check(one_bf16([dict(kind="layernorm", d=d, eps=1e-5)], (S, d), "bsd", B=3), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+
+
+@pytest.mark.parametrize("S,d,heads", [(32, 64, 1), (128, 512, 8), (96, 128, 2), (256, 128, 2)])
+def test_bf16_mha(A, S, d, heads):
+    cfg = one_bf16([dict(kind="mha", d=d, heads=heads)], (S, d), "bsd", B=2)
+    check(cfg, tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+
+
+def test_bf16_standalone_ops(A):
+    L = [simple("res_begin"), linear(64, 64), simple("relu"), simple("res_add"), simple("gelu")]
+    check(one_bf16(L, (16, 64), "bsd"), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+
+
+def test_cfg4_small(A):
+    check(C.cfg4(B=2, M=3, hw=12, cin=16, c=24), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+    check(C.cfg4(B=3, M=2, hw=10, cin=128, c=256), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+
+
+def test_cfg5_small(A):
+    check(C.cfg5(B=2, M=2, S=64, d=128, heads=2, ffn=256, nlayers=2), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+    check(C.cfg5(B=1, M=3, S=32, d=512, heads=8, ffn=2048, nlayers=1), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+
+
+def test_bf16_determinism_and_K(A):
+    cfg = C.cfg5(B=2, M=3, S=32, d=128, heads=2, ffn=256, nlayers=1)
+    inp = gen.make_inputs(cfg, randomize_affine=True)
+    r1, _, _ = harness.run_hip(cfg, inp, K=1, rounds=1)
+    r3, _, _ = harness.run_hip(cfg, inp, K=3, rounds=1)
+    r1b, _, _ = harness.run_hip(cfg, inp, K=1, rounds=1)
+    for k in ("y", "dx", "G", "W"):
+        assert np.array_equal(r1[0][k], r3[0][k]) and np.array_equal(r1[0][k], r1b[0][k]), k
+
+
+def test_cfg4_full_golden(A):
+    golden_check("cfg4", TOL_BF16, TOL_BF16, TOL_BF16, TOL_BF16)
+
+
+def test_cfg5_full_golden(A):
+    golden_check("cfg5", TOL_BF16, TOL_BF16, TOL_BF16, TOL_BF16)
