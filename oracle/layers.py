@@ -39,7 +39,8 @@ def conv2d_fwd(x, w, b, stride, pad, groups):
     wg = w.reshape(groups, og, cg, k, k)
     for u, v, win in _taps(x, k, stride, pad, ho, wo):
         xs = np.ascontiguousarray(win).reshape(n, groups, cg, ho * wo)
-        y += np.matmul(wg[:, :, :, u, v], xs)          # (G,og,cg) @ (n,G,cg,P)
+        wt = np.ascontiguousarray(wg[:, :, :, u, v])   # contiguous: lets matmul use the BLAS gemm
+        y += np.matmul(wt, xs)                         # (G,og,cg) @ (n,G,cg,P)
     y = y.reshape(n, cout, ho, wo)
     if b is not None:
         y = y + b.reshape(1, cout, 1, 1)
@@ -60,7 +61,8 @@ def conv2d_bwd(x, w, g, stride, pad, groups, has_bias):
     for u, v, win in _taps(x, k, stride, pad, ho, wo):
         xs = np.ascontiguousarray(win).reshape(n, groups, cg, ho * wo)
         dw[:, :, :, u, v] = np.matmul(gg, xs.transpose(0, 1, 3, 2)).sum(axis=0)
-        dxs = np.matmul(wg[:, :, :, u, v].transpose(0, 2, 1), gg)      # (n,G,cg,P)
+        wt = np.ascontiguousarray(wg[:, :, :, u, v])
+        dxs = np.matmul(wt.transpose(0, 2, 1), gg)                     # (n,G,cg,P)
         dxp[:, :, u:u + stride * (ho - 1) + 1:stride, v:v + stride * (wo - 1) + 1:stride] += \
             dxs.reshape(n, cin, ho, wo)
     dx = dxp[:, :, pad:pad + h, pad:pad + wd]

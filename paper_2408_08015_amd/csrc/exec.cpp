@@ -59,10 +59,9 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       break;
     case OP_BN: {
       float* aux = reinterpret_cast<float*>(c.slot + op.aux_off);
-      bn_stats_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, s.W + op.b_off, aux, aux + 2 * I.c,
-                   s.running + op.run_off, reinterpret_cast<double*>(scratch(c)), I.n, I.c, HW, op.eps);
-      bn_apply_f32(st, (cf)act_ptr(c, op.in), aux + 2 * I.c, op.skip >= 0 ? (cf)act_ptr(c, op.skip) : nullptr,
-                   (float*)act_ptr(c, op.out), I.n, I.c, HW, op.act);
+      bn_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, s.W + op.b_off,
+                 op.skip >= 0 ? (cf)act_ptr(c, op.skip) : nullptr, (float*)act_ptr(c, op.out), aux, aux + 2 * I.c,
+                 s.running + op.run_off, reinterpret_cast<double*>(scratch(c)), I.n, I.c, HW, op.eps, op.act);
       break;
     }
     case OP_ACT:
@@ -142,9 +141,8 @@ void bwd_op(Ctx& c, const Op& op) {
     }
     case OP_CONV_DW: {
       cf g = (cf)grad_ptr(c, op.out);
-      if (gin) dw3x3_dgrad_f32(st, g, s.W + op.w_off, (float*)gin, I.n, I.c, I.h, I.w, op.stride);
-      dw3x3_wgrad_f32(st, g, (cf)act_ptr(c, op.in), reinterpret_cast<float*>(scratch(c)), s.G + op.w_off, I.n,
-                      I.c, I.h, I.w, op.stride);
+      dw3x3_bwd_f32(st, g, (cf)act_ptr(c, op.in), s.W + op.w_off, (float*)gin, reinterpret_cast<float*>(scratch(c)),
+                    s.G + op.w_off, I.n, I.c, I.h, I.w, op.stride);
       break;
     }
     case OP_CONV_DIRECT: {
@@ -176,8 +174,8 @@ void bwd_op(Ctx& c, const Op& op) {
     case OP_BN: {
       float* aux = reinterpret_cast<float*>(c.slot + op.aux_off);
       bn_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), aux, aux + 2 * I.c, s.W + op.w_off,
-                 (float*)gin, s.G + op.w_off, s.G + op.b_off, reinterpret_cast<double*>(scratch(c)),
-                 scratch2(c), I.n, I.c, HW, op.act);
+                 (float*)gin, s.G + op.w_off, s.G + op.b_off, reinterpret_cast<double*>(scratch(c)), I.n, I.c, HW,
+                 op.act);
       break;
     }
     case OP_ACT:

@@ -27,11 +27,11 @@ void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, f
 // Depthwise 3x3 convolution, pad 1, stride 1 or 2, weights [C][3][3].
 void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int N, int C, int H,
                    int W, int stride);
-void dw3x3_dgrad_f32(hipStream_t st, const float* g, const float* w, float* dx, int N, int C, int H,
-                     int W, int stride);
-size_t dw3x3_wgrad_f32_ws(int N, int C, int H, int W, int stride);
-void dw3x3_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, float* G, int N,
-                     int C, int H, int W, int stride);
+// Backward of the depthwise conv from one read of g and x: dx (skipped if NULL) and
+// G[C][3][3] += weight gradient.  `part` holds dw3x3_bwd_f32_ws(N, C) floats.
+size_t dw3x3_bwd_f32_ws(int N, int C);
+void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part,
+                   float* G, int N, int C, int H, int W, int stride);
 
 // Generic direct convolution (any k, stride, pad, groups); the fallback for shapes the
 // specialised kernels do not cover (e.g. a 3-channel stem).
@@ -47,17 +47,17 @@ void channel_sum_acc_f32(hipStream_t st, const float* g, float* G, int N, int C,
 
 // BatchNorm2d, training mode.  `ws` holds bn_ws_doubles(C, N*HW) doubles.
 size_t bn_ws_doubles(int C, size_t per_channel);
-// mean/istd -> stat[0..C) / stat[C..2C); running[0..C) mean, running[C..2C) var updated in place.
-void bn_stats_f32(hipStream_t st, const float* x, const float* gamma, const float* beta, float* stat,
-                  float* scale_shift, float* running, double* ws, int N, int C, int HW, float eps);
-// y = act(x*scale[c] + shift[c]) (+ skip)
-void bn_apply_f32(hipStream_t st, const float* x, const float* scale_shift, const float* skip,
-                  float* y, int N, int C, int HW, int act);
+// Forward: batch statistics of x, then y = act(x*scale[c] + shift[c]) (+ skip).
+// mean/istd -> stat[0..C) / stat[C..2C); scale/shift -> scale_shift[0..2C);
+// running[0..C) mean, running[C..2C) var updated in place (momentum 0.1, unbiased variance).
+void bn_fwd_f32(hipStream_t st, const float* x, const float* gamma, const float* beta, const float* skip,
+                float* y, float* stat, float* scale_shift, float* running, double* ws, int N, int C, int HW,
+                float eps, int act);
 // Backward: g' = g * act'(x*scale+shift); dbeta += sum g'; dgamma += sum g'*xhat;
-// dx = gamma*istd*(g' - mean(g') - xhat*mean(g'*xhat)).
-void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* stat,
-                const float* scale_shift, const float* gamma, float* dx, float* Ggamma, float* Gbeta,
-                double* ws, float* coef, int N, int C, int HW, int act);
+// dx = gamma*istd*(g' - mean(g') - xhat*mean(g'*xhat)); dx may be NULL (not wanted).
+void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* scale_shift,
+                const float* gamma, float* dx, float* Ggamma, float* Gbeta, double* ws, int N, int C, int HW,
+                int act);
 
 // Elementwise
 void act_fwd_f32(hipStream_t st, const float* x, float* y, size_t n, int act);

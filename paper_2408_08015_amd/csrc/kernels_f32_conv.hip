@@ -1,0 +1,562 @@
+// fp32 NCHW convolution kernels of the MobileNetV2-style stages.
+//
+// Pointwise (1x1) convolution = per-pixel matrix product on the fp32 matrix cores
+// (v_mfma_f32_32x32x2f32).  In NCHW a channel plane is contiguous, so pixels go on the MFMA
+// N dimension: lane l supplies B[k = l/32][pixel = l%32] with one coalesced global load,
+// the small weight matrix comes from LDS as A[m = l%32][k = l/32], and accumulator
+// register r of lane l is D[8*(r/4) + 4*(l/32) + r%4][l%32].  At these shapes the kernels
+// are HBM / latency bound, so the launch shapes are chosen for wavefront count first.
+//
+// Depthwise 3x3: a block stages whole (n, c) planes (they are contiguous) with a zero halo
+// in LDS; the backward kernel produces the input gradient and the nine weight-gradient
+// sums of each plane from one read of g and x.
+#include "device_utils.h"
+#include "kernels.h"
+#include "prof.h"
+
+namespace ast {
+
+static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+static inline int conv_out(int H, int k, int stride, int pad) { return (H + 2 * pad - k) / stride + 1; }
+
+// ============================================================== pointwise conv (fwd / dgrad)
+// Block = 4 wavefronts; wavefront w owns pixels [128*bx + 32*w, +32) of the flattened
+// (n, p) index and NT 32-row tiles of output channels.  MFMA 32x32x2: lane l supplies
+// A[m = l%32][k = l/32] and B[k = l/32][q = l%32]; accumulator register r of lane l is
+// D[8*(r/4) + 4*(l/32) + r%4][l%32].
+template <int NT>
+__global__ __launch_bounds__(256) void pw_conv_f32_kernel(
+    const float* __restrict__ W, int lda_m, int lda_k, const float* __restrict__ X,
+    float* __restrict__ Y, const float* __restrict__ bias, const float* __restrict__ add, long NQ,
+    int HW, int Kdim, int Mdim) {
+  constexpr int KC = 32;
+  constexpr int MT = 32 * NT;
+  __shared__ float sW[KC][MT + 1];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int m_base = blockIdx.y * MT;
+  const long q = (long)blockIdx.x * 128 + wave * 32 + col;
+  const bool qv = q < NQ;
+  long n = 0;
+  int p = 0;
+  if (qv) {
+    n = q / HW;
+    p = (int)(q - n * HW);
+  }
+  const float* xq = X + (size_t)n * Kdim * HW + p;
+  floatx16 acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+  for (int k0 = 0; k0 < Kdim; k0 += KC) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < KC * MT; idx += 256) {
+      int kk, mm;
+      if (lda_k == 1) {  // k contiguous in memory
+        kk = idx % KC;
+        mm = idx / KC;
+      } else {
+        mm = idx % MT;
+        kk = idx / MT;
+      }
+      int m = m_base + mm, k = k0 + kk;
+      float v = 0.f;
+      if (m < Mdim && k < Kdim) v = W[(size_t)m * lda_m + (size_t)k * lda_k];
+      sW[kk][mm] = v;
+    }
+    __syncthreads();
+    float b[KC / 2];
+#pragma unroll
+    for (int j = 0; j < KC / 2; ++j) {
+      int k = k0 + 2 * j + half;
+      b[j] = (qv && k < Kdim) ? xq[(size_t)k * HW] : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < KC / 2; ++j) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        float a = sW[2 * j + half][t * 32 + col];
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j], acc[t], 0, 0, 0);
+      }
+    }
+  }
+  if (!qv) return;
+  float* yq = Y + (size_t)n * Mdim * HW + p;
+  const float* aq = add ? add + (size_t)n * Mdim * HW + p : nullptr;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      int m = m_base + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (m < Mdim) {
+        float v = acc[t][r];
+        if (bias) v += bias[m];
+        if (aq) v += aq[(size_t)m * HW];
+        yq[(size_t)m * HW] = v;
+      }
+    }
+  }
+}
+
+// Large images: a wavefront owns 128 pixels; every lane loads four consecutive pixels
+// (16 bytes) per input channel and feeds four MFMA column tiles (column j of tile t is
+// pixel 4j + t), so each output row is stored as 16 bytes per lane.  Four times the bytes
+// per memory instruction of the kernel above; needs HW % 4 == 0.
+__global__ __launch_bounds__(256) void pw_conv_f32_px4_kernel(
+    const float* __restrict__ W, int lda_m, int lda_k, const float* __restrict__ X,
+    float* __restrict__ Y, const float* __restrict__ bias, const float* __restrict__ add, long NQ,
+    int HW, int Kdim, int Mdim) {
+  constexpr int KC = 32;
+  __shared__ float sW[KC][33];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int m_base = blockIdx.y * 32;
+  const long q = (long)blockIdx.x * 512 + wave * 128 + col * 4;
+  const bool qv = q < NQ;  // NQ % 4 == 0: the four pixels are valid together
+  long n = 0;
+  int p = 0;
+  if (qv) {
+    n = q / HW;
+    p = (int)(q - n * HW);
+  }
+  const float* xq = X + (size_t)n * Kdim * HW + p;
+  floatx16 acc[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+  for (int k0 = 0; k0 < Kdim; k0 += KC) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < KC * 32; idx += 256) {
+      int kk, mm;
+      if (lda_k == 1) {
+        kk = idx % KC;
+        mm = idx / KC;
+      } else {
+        mm = idx % 32;
+        kk = idx / 32;
+      }
+      int m = m_base + mm, k = k0 + kk;
+      float v = 0.f;
+      if (m < Mdim && k < Kdim) v = W[(size_t)m * lda_m + (size_t)k * lda_k];
+      sW[kk][mm] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int jj = 0; jj < KC / 2; jj += 8) {
+      float4 b[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        int k = k0 + 2 * (jj + j) + half;
+        b[j] = (qv && k < Kdim) ? *reinterpret_cast<const float4*>(xq + (size_t)k * HW)
+                                : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float a = sW[2 * (jj + j) + half][col];
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j].x, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j].y, acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j].z, acc[2], 0, 0, 0);
+        acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j].w, acc[3], 0, 0, 0);
+      }
+    }
+  }
+  if (!qv) return;
+  float* yq = Y + (size_t)n * Mdim * HW + p;
+  const float* aq = add ? add + (size_t)n * Mdim * HW + p : nullptr;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
+    if (m < Mdim) {
+      float4 v = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+      if (bias) {
+        const float bv = bias[m];
+        v.x += bv; v.y += bv; v.z += bv; v.w += bv;
+      }
+      if (aq) {
+        const float4 k = *reinterpret_cast<const float4*>(aq + (size_t)m * HW);
+        v.x += k.x; v.y += k.y; v.z += k.z; v.w += k.w;
+      }
+      *reinterpret_cast<float4*>(yq + (size_t)m * HW) = v;
+    }
+  }
+}
+
+void pw_conv_f32(hipStream_t st, const float* W, int lda_m, int lda_k, const float* X, float* Y,
+                 const float* bias, const float* add, int N, int Kdim, int Mdim, int HW) {
+  long NQ = (long)N * HW;
+  int mt = cdiv(Mdim, 32);
+  // 128-pixel wavefronts when they still fill the chip (measured: 26 % faster at 56x56x32,
+  // slower when fewer than ~500 blocks remain)
+  if (HW % 4 == 0 && (long)cdiv(NQ, 512) * mt >= 512) {
+    KLAUNCH(pw_conv_f32_px4_kernel, dim3(cdiv(NQ, 512), mt), dim3(256), 0, st, W, lda_m, lda_k, X, Y, bias, add, NQ,
+            HW, Kdim, Mdim);
+    return;
+  }
+  KLAUNCH(pw_conv_f32_kernel<1>, dim3(cdiv(NQ, 128), mt), dim3(256), 0, st, W, lda_m, lda_k, X, Y, bias, add, NQ, HW,
+          Kdim, Mdim);
+}
+
+// ============================================================== pointwise conv wgrad
+// Block = one 32(co) x 32(ci) tile of dW over 4*pxw pixels of one sample; each wavefront
+// contracts pxw pixels (lane (m = l%32, h = l/32) loads eight consecutive pixels of row m
+// and feeds eight MFMAs; both operands use the same pixel per slot), the four accumulators
+// are added through LDS and written as one partial.  A second kernel adds the partials in a
+// fixed order and performs G += (in-place gradient accumulation).
+template <bool VEC>
+__global__ __launch_bounds__(256) void pw_wgrad_f32_kernel(const float* __restrict__ g,
+                                                           const float* __restrict__ x,
+                                                           float* __restrict__ part, int Cin, int Cout,
+                                                           int HW, int cps, int pxw) {
+  __shared__ float sR[4][16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = lane & 31, half = lane >> 5;
+  const int chunk = blockIdx.x;
+  const int n = chunk / cps;
+  const int p0 = ((chunk - n * cps) * 4 + wave) * pxw;
+  const int p1 = min(p0 + pxw, HW);
+  const int ci_base = blockIdx.y * 32, co_base = blockIdx.z * 32;
+  const bool av = co_base + row < Cout, bv = ci_base + row < Cin;
+  const float* ga = g + ((size_t)n * Cout + (av ? co_base + row : 0)) * HW;
+  const float* xb = x + ((size_t)n * Cin + (bv ? ci_base + row : 0)) * HW;
+  floatx16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  if (VEC) {  // HW % 4 == 0: aligned 16-byte loads, 16 pixels per fragment, two fragments in flight
+    struct Frag { float4 a0, a1, b0, b1; };
+    auto ld = [&](int p, Frag& f) {
+      const int pp = p + 8 * half;
+      f.a0 = f.a1 = f.b0 = f.b1 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (pp < p1) {
+        if (av) f.a0 = *reinterpret_cast<const float4*>(ga + pp);
+        if (bv) f.b0 = *reinterpret_cast<const float4*>(xb + pp);
+      }
+      if (pp + 4 < p1) {
+        if (av) f.a1 = *reinterpret_cast<const float4*>(ga + pp + 4);
+        if (bv) f.b1 = *reinterpret_cast<const float4*>(xb + pp + 4);
+      }
+    };
+    auto mma = [&](const Frag& f) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.x, f.b0.x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.y, f.b0.y, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.z, f.b0.z, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.w, f.b0.w, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.x, f.b1.x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.y, f.b1.y, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.z, f.b1.z, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.w, f.b1.w, acc, 0, 0, 0);
+    };
+    Frag f0, f1, f2, f3;
+    for (int p = p0; p < p1; p += 64) {  // four fragments issued before the first MFMA
+      ld(p, f0);
+      ld(p + 16, f1);
+      ld(p + 32, f2);
+      ld(p + 48, f3);
+      mma(f0);
+      mma(f1);
+      mma(f2);
+      mma(f3);
+    }
+  } else {
+    for (int p = p0; p < p1; p += 2) {
+      const int pp = p + half;
+      float a = (av && pp < p1) ? ga[pp] : 0.f;
+      float b = (bv && pp < p1) ? xb[pp] : 0.f;
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sR[wave][r][lane] = acc[r];
+  __syncthreads();
+  float* out = part + (size_t)chunk * Cout * Cin;
+  const int ci = ci_base + row;
+  if (ci < Cin) {
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int r = 4 * wave + rr;
+      const int co = co_base + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (co < Cout)
+        out[(size_t)co * Cin + ci] = (sR[0][r][lane] + sR[1][r][lane]) + (sR[2][r][lane] + sR[3][r][lane]);
+    }
+  }
+}
+
+// G[i] += sum_c part[c][i]: 64 outputs per block, four interleaved part lanes, fixed order
+__global__ __launch_bounds__(256) void reduce_parts_acc_kernel(const float* __restrict__ part,
+                                                               float* __restrict__ G, size_t n, int parts) {
+  __shared__ float sh[4][64];
+  const int o = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const size_t i = (size_t)blockIdx.x * 64 + o;
+  float s = 0.f;
+  if (i < n) {
+    int c = q;
+    for (; c + 28 < parts; c += 32) {  // eight independent loads in flight
+      float v0 = part[(size_t)c * n + i], v1 = part[(size_t)(c + 4) * n + i];
+      float v2 = part[(size_t)(c + 8) * n + i], v3 = part[(size_t)(c + 12) * n + i];
+      float v4 = part[(size_t)(c + 16) * n + i], v5 = part[(size_t)(c + 20) * n + i];
+      float v6 = part[(size_t)(c + 24) * n + i], v7 = part[(size_t)(c + 28) * n + i];
+      s += ((v0 + v1) + (v2 + v3)) + ((v4 + v5) + (v6 + v7));
+    }
+    for (; c < parts; c += 4) s += part[(size_t)c * n + i];
+  }
+  sh[q][o] = s;
+  __syncthreads();
+  if (q == 0 && i < n) G[i] += (sh[0][o] + sh[1][o]) + (sh[2][o] + sh[3][o]);
+}
+
+// pixels per wavefront: the largest of {256,128,64,32} that still gives >= 768 blocks
+static int wg_pxw(int N, int Cin, int Cout, int HW) {
+  long tiles = (long)cdiv(Cin, 32) * cdiv(Cout, 32);
+  const int cand[4] = {256, 128, 64, 32};
+  for (int c : cand)
+    if ((long)N * cdiv(HW, 4 * c) * tiles >= 768) return c;
+  return 32;
+}
+size_t pw_wgrad_f32_ws(int N, int Cin, int Cout, int HW) {
+  int pxw = wg_pxw(N, Cin, Cout, HW);
+  return (size_t)N * cdiv(HW, 4 * pxw) * Cin * Cout;
+}
+void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, float* G, int N,
+                  int Cin, int Cout, int HW) {
+  int pxw = wg_pxw(N, Cin, Cout, HW);
+  int cps = cdiv(HW, 4 * pxw);
+  int chunks = N * cps;
+  dim3 grid(chunks, cdiv(Cin, 32), cdiv(Cout, 32));
+  if (HW % 4 == 0)
+    KLAUNCH(pw_wgrad_f32_kernel<true>, grid, dim3(256), 0, st, g, x, part, Cin, Cout, HW, cps, pxw);
+  else
+    KLAUNCH(pw_wgrad_f32_kernel<false>, grid, dim3(256), 0, st, g, x, part, Cin, Cout, HW, cps, pxw);
+  size_t n = (size_t)Cin * Cout;
+  KLAUNCH(reduce_parts_acc_kernel, dim3(cdiv(n, 64)), dim3(256), 0, st, part, G, n, chunks);
+}
+
+// ============================================================== depthwise 3x3 (pad 1, stride 1 or 2)
+struct DwGeom {
+  int C, H, W, Ho, Wo, stride, ppb, NC;
+};
+
+// planes per block: about 4096 input elements per block, a power of two in [1, 16]
+static int dw_ppb(int H, int W) {
+  int p = 4096 / (H * W);
+  int r = 1;
+  while (r * 2 <= p && r < 16) r *= 2;
+  return r;
+}
+
+// Zero `count` floats of LDS (all 256 threads), then barrier.
+__device__ __forceinline__ void dw_zero(float* dst, int count) {
+  for (int i = threadIdx.x; i < count; i += 256) dst[i] = 0.f;
+  __syncthreads();
+}
+// Copy one h x w plane into an LDS plane of (h+2) x (w+2) (halo already zero) with the tpp
+// threads of the plane's group (t = index in the group).  Four loads are issued before
+// the first LDS write so the memory latency is paid once per four elements, not per element.
+__device__ __forceinline__ void dw_stage_plane(float* dst, const float* __restrict__ src, int h, int w, int t,
+                                               int tpp) {
+  const int pw = w + 2;
+  if ((w & 3) == 0) {
+    const int nq = (h * w) >> 2, qpr = w >> 2;
+    const float4* s4 = reinterpret_cast<const float4*>(src);
+    for (int q0 = t; q0 < nq; q0 += 4 * tpp) {
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        int q = q0 + u * tpp;
+        v[u] = q < nq ? s4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        int q = q0 + u * tpp;
+        if (q < nq) {
+          int i = q / qpr, j = (q - i * qpr) * 4;
+          float* d = dst + (i + 1) * pw + j + 1;
+          d[0] = v[u].x; d[1] = v[u].y; d[2] = v[u].z; d[3] = v[u].w;
+        }
+      }
+    }
+  } else {
+    const int ne = h * w;
+    for (int e0 = t; e0 < ne; e0 += 4 * tpp) {
+      float v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        int e = e0 + u * tpp;
+        v[u] = e < ne ? src[e] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        int e = e0 + u * tpp;
+        if (e < ne) {
+          int i = e / w, j = e - i * w;
+          dst[(i + 1) * pw + j + 1] = v[u];
+        }
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void dw3x3_fwd_f32_kernel(const float* __restrict__ x,
+                                                            const float* __restrict__ w,
+                                                            float* __restrict__ y, DwGeom gm) {
+  extern __shared__ float sm[];
+  const int PW = gm.W + 2, PSZ = (gm.H + 2) * PW;
+  float* sx = sm;
+  float* sw = sm + gm.ppb * PSZ;  // [ppb][9]
+  const int plane0 = blockIdx.x * gm.ppb;
+  const int np = min(gm.ppb, gm.NC - plane0);
+  const int tpp = 256 / gm.ppb;
+  const int pl = threadIdx.x / tpp, t = threadIdx.x - pl * tpp;
+  dw_zero(sx, gm.ppb * PSZ);
+  if (pl < np) dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
+  for (int i = threadIdx.x; i < np * 9; i += 256) sw[i] = w[((plane0 + i / 9) % gm.C) * 9 + i % 9];
+  __syncthreads();
+  if (pl >= np) return;
+  const float* wc = sw + pl * 9;
+  const float w0 = wc[0], w1 = wc[1], w2 = wc[2], w3 = wc[3], w4 = wc[4], w5 = wc[5], w6 = wc[6], w7 = wc[7], w8 = wc[8];
+  const float* sp = sx + pl * PSZ;
+  float* yp = y + (size_t)(plane0 + pl) * gm.Ho * gm.Wo;
+  const int s = gm.stride;
+  for (int o = t; o < gm.Ho * gm.Wo; o += tpp) {
+    int i = o / gm.Wo, j = o - i * gm.Wo;
+    const float* b = sp + (i * s) * PW + j * s;
+    float acc = w0 * b[0] + w1 * b[1] + w2 * b[2];
+    acc += w3 * b[PW] + w4 * b[PW + 1] + w5 * b[PW + 2];
+    acc += w6 * b[2 * PW] + w7 * b[2 * PW + 1] + w8 * b[2 * PW + 2];
+    yp[o] = acc;
+  }
+}
+
+// Input gradient (if dx) and the nine weight-gradient sums of every plane:
+//   dx[i][j] = sum_{u,v} w[u][v] g[(i+1-u)/s][(j+1-v)/s]   (terms with a non-integer index drop)
+//   part[plane][u*3+v] = sum_{i,j} g[i][j] x[i*s-1+u][j*s-1+v]
+__global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restrict__ g,
+                                                            const float* __restrict__ x,
+                                                            const float* __restrict__ w,
+                                                            float* __restrict__ dx, float* __restrict__ part,
+                                                            DwGeom gm) {
+  extern __shared__ float sm[];
+  const int PW = gm.W + 2, PSZ = (gm.H + 2) * PW;
+  const int GW = gm.Wo + 2, GSZ = (gm.Ho + 2) * GW;
+  float* sx = sm;
+  float* sg = sx + gm.ppb * PSZ;
+  float* sw = sg + gm.ppb * GSZ;  // [ppb][9]
+  float* sred = sw + gm.ppb * 9;  // [4 waves][9]
+  const int plane0 = blockIdx.x * gm.ppb;
+  const int np = min(gm.ppb, gm.NC - plane0);
+  const int tpp = 256 / gm.ppb;
+  const int pl = threadIdx.x / tpp, t = threadIdx.x - pl * tpp;
+  const bool live = pl < np;
+  dw_zero(sx, gm.ppb * (PSZ + GSZ));  // sx and sg are adjacent
+  if (live) {
+    dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
+    dw_stage_plane(sg + pl * GSZ, g + (size_t)(plane0 + pl) * gm.Ho * gm.Wo, gm.Ho, gm.Wo, t, tpp);
+  }
+  for (int i = threadIdx.x; i < np * 9; i += 256) sw[i] = w[((plane0 + i / 9) % gm.C) * 9 + i % 9];
+  __syncthreads();
+  const int s = gm.stride;
+  float acc[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) acc[k] = 0.f;
+  if (live) {
+    const float* wc = sw + pl * 9;
+    const float* gp = sg + pl * GSZ;
+    const float* xp = sx + pl * PSZ;
+    if (dx) {
+      float* dp = dx + (size_t)(plane0 + pl) * gm.H * gm.W;
+      for (int e = t; e < gm.H * gm.W; e += tpp) {
+        int i = e / gm.W, j = e - i * gm.W;
+        float v = 0.f;
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+          int a = i + 1 - u;
+          if (s == 2 && (a & 1)) continue;
+          int io = s == 2 ? (a >> 1) : a;  // in [-1, Ho]: the halo holds zeros
+#pragma unroll
+          for (int v3 = 0; v3 < 3; ++v3) {
+            int bb = j + 1 - v3;
+            if (s == 2 && (bb & 1)) continue;
+            int jo = s == 2 ? (bb >> 1) : bb;
+            v += wc[u * 3 + v3] * gp[(io + 1) * GW + jo + 1];
+          }
+        }
+        dp[e] = v;
+      }
+    }
+    for (int o = t; o < gm.Ho * gm.Wo; o += tpp) {
+      int i = o / gm.Wo, j = o - i * gm.Wo;
+      float gv = gp[(i + 1) * GW + j + 1];
+      const float* b = xp + (i * s) * PW + j * s;
+#pragma unroll
+      for (int u = 0; u < 3; ++u)
+#pragma unroll
+        for (int v3 = 0; v3 < 3; ++v3) acc[u * 3 + v3] += gv * b[u * PW + v3];
+    }
+  }
+  // reduce the nine sums over the tpp threads of each plane (tpp is a power of two >= 16)
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int span = tpp < 64 ? tpp : 64;
+#pragma unroll
+  for (int k = 0; k < 9; ++k)
+    for (int o = span >> 1; o > 0; o >>= 1) acc[k] += __shfl_xor(acc[k], o, 64);
+  if (tpp <= 64) {
+    if (live && t == 0)
+#pragma unroll
+      for (int k = 0; k < 9; ++k) part[(size_t)(plane0 + pl) * 9 + k] = acc[k];
+  } else {
+    if (lane == 0)
+#pragma unroll
+      for (int k = 0; k < 9; ++k) sred[wave * 9 + k] = acc[k];
+    __syncthreads();
+    if (live && t == 0) {
+      const int w0 = threadIdx.x >> 6, nw = tpp >> 6;
+      for (int k = 0; k < 9; ++k) {
+        float v = 0.f;
+        for (int q = 0; q < nw; ++q) v += sred[(w0 + q) * 9 + k];
+        part[(size_t)(plane0 + pl) * 9 + k] = v;
+      }
+    }
+  }
+}
+
+// G[c][t] += sum_n part[n][c][t]: eight sample lanes per output, fixed butterfly order
+__global__ __launch_bounds__(256) void dw3x3_wgrad_final_kernel(const float* __restrict__ part,
+                                                                float* __restrict__ G, int N, int C) {
+  const int i = blockIdx.x * 32 + (threadIdx.x >> 3), nl = threadIdx.x & 7;
+  float s = 0.f;
+  if (i < C * 9)
+    for (int n = nl; n < N; n += 8) s += part[(size_t)n * C * 9 + i];
+  s += __shfl_xor(s, 4, 64);
+  s += __shfl_xor(s, 2, 64);
+  s += __shfl_xor(s, 1, 64);
+  if (nl == 0 && i < C * 9) G[i] += s;
+}
+
+static DwGeom dw_geom(int N, int C, int H, int W, int stride) {
+  DwGeom gm;
+  gm.C = C; gm.H = H; gm.W = W; gm.stride = stride;
+  gm.Ho = conv_out(H, 3, stride, 1); gm.Wo = conv_out(W, 3, stride, 1);
+  gm.ppb = dw_ppb(H, W);
+  gm.NC = N * C;
+  return gm;
+}
+
+void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int N, int C, int H, int W,
+                   int stride) {
+  DwGeom gm = dw_geom(N, C, H, W, stride);
+  size_t lds = ((size_t)gm.ppb * ((H + 2) * (W + 2) + 9)) * sizeof(float);
+  (void)hipFuncSetAttribute((const void*)dw3x3_fwd_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  KLAUNCH(dw3x3_fwd_f32_kernel, dim3(cdiv(gm.NC, gm.ppb)), dim3(256), lds, st, x, w, y, gm);
+}
+size_t dw3x3_bwd_f32_ws(int N, int C) { return (size_t)N * C * 9; }
+void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part,
+                   float* G, int N, int C, int H, int W, int stride) {
+  DwGeom gm = dw_geom(N, C, H, W, stride);
+  size_t lds = ((size_t)gm.ppb * ((H + 2) * (W + 2) + (gm.Ho + 2) * (gm.Wo + 2) + 9) + 36) * sizeof(float);
+  (void)hipFuncSetAttribute((const void*)dw3x3_bwd_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  KLAUNCH(dw3x3_bwd_f32_kernel, dim3(cdiv(gm.NC, gm.ppb)), dim3(256), lds, st, g, x, w, dx, part, gm);
+  KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
+}
+
+}  // namespace ast

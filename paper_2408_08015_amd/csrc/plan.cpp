@@ -268,7 +268,7 @@ ast_status build_plan(Stage& s, std::string& err) {
     size_t need = 0, need2 = 0;
     switch (op.kind) {
       case OP_CONV_PW: need = pw_wgrad_f32_ws(I.n, op.cin, op.cout, I.h * I.w) * sizeof(float); break;
-      case OP_CONV_DW: need = dw3x3_wgrad_f32_ws(I.n, I.c, I.h, I.w, op.stride) * sizeof(float); break;
+      case OP_CONV_DW: need = dw3x3_bwd_f32_ws(I.n, I.c) * sizeof(float); break;
       case OP_BN:
         need = bn_ws_doubles(I.c, (size_t)I.n * I.h * I.w) * sizeof(double);
         need2 = 3 * sizeof(float) * I.c;
