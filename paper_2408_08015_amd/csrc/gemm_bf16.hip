@@ -6,23 +6,27 @@
 //                                              split over K, deterministic fp32 reduction into G
 //
 // Block = 256 threads = 2 x 2 wavefronts; each wavefront owns a WTM x WTN tile made of
-// 32x32 MFMA tiles.  Both operands sit in LDS as [row][k] with k contiguous (row stride 40
-// elements = 80 bytes, which spreads the 16-byte operand reads of 8 consecutive lanes over
-// all banks).  MFMA 32x32x16: lane l supplies A[l%32][8*(l/32) .. +7] and B likewise;
+// 32x32 MFMA tiles; K advances 64 per step.  Both operands sit in LDS as [row][k] with k
+// contiguous (row stride 72 elements = 144 bytes, which spreads the 16-byte operand reads
+// of 8 consecutive lanes over all banks), double-buffered: the global loads of K-tile t+1
+// are issued before the MFMAs of tile t and written to the other buffer after them, one
+// barrier per tile.  MFMA 32x32x16: lane l supplies A[l%32][8*(l/32) .. +7] and B likewise;
 // accumulator register r of lane l is D[8*(r/4) + 4*(l/32) + r%4][l%32].
 // Operands stored with the contraction index strided (weight gradients) are transposed in
-// registers (4 x 8 blocks) on their way into LDS.
-// Global loads of the next K-tile are issued before the MFMAs of the current one.
+// registers (4 x 8 blocks) on their way into LDS.  The bf16 output tile goes through LDS
+// so that every lane stores 16 contiguous bytes.
 #include "device_utils.h"
 #include "kernels_bf16.h"
+#include <cstdlib>
+
 #include "prof.h"
 
 namespace ast {
 
 namespace {
 
-constexpr int BK = 32;
-constexpr int LDS_STRIDE = 40;  // elements per LDS row
+constexpr int BK = 64;
+constexpr int LDS_STRIDE = 72;  // elements per LDS row
 
 enum { A_ROW = 0, A_IM2COL = 1, OP_T = 2, B_ROW = 0, B_T_SHIFT = 3 };
 enum { E_BF16 = 0, E_PART = 1 };
@@ -33,6 +37,8 @@ struct GemmArgs {
   long M, N, K;
   long lda, ldb;
   int H, W, C, ksize;  // image geometry of the gathered / shifted operand
+  int fastc;           // implicit GEMM: C % 64 == 0, so a K-tile lies inside one tap
+  int step_q, step_r;  // 64 / W, 64 % W: pixel advance of one K-tile (shifted operand)
   long k_per_split;    // K range per blockIdx.z (multiple of BK)
   // epilogue
   bf16_t* Cb;          // bf16 output [M][ldc]
@@ -46,18 +52,27 @@ struct GemmArgs {
 
 __device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
 
-template <int WTM, int WTN, int AMODE, int BMODE, int EMODE>
+template <int WTM, int WTN, int AMODE, int BMODE, int EMODE, bool DBUF>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int BM = 2 * WTM, BN = 2 * WTN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t sA[BM * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) bf16_t sB[BN * LDS_STRIDE];
+  constexpr int STAGE = (BM + BN) * LDS_STRIDE;  // elements per buffer
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const long m0 = (long)(blockIdx.x / g.tiles_n) * BM;
-  const long n0 = (long)(blockIdx.x % g.tiles_n) * BN;
-  const int tap = blockIdx.y;  // weight-gradient of a 3x3 conv: one tap per blockIdx.y
+  // Blocks are dealt to the 8 XCDs round-robin; renumber them so that each XCD (own L2) works
+  // on a contiguous range of tiles: the N-tiles of one row tile and neighbouring row tiles
+  // (which share halo pixels in the implicit GEMM) then hit the same L2.
+  int bid = blockIdx.x;
+  {
+    const int nb = gridDim.x, q = nb >> 3, r = nb & 7, xcd = bid & 7;
+    bid = xcd * q + min(xcd, r) + (bid >> 3);
+  }
+  const long m0 = (long)(bid / g.tiles_n) * BM;
+  const long n0 = (long)(bid % g.tiles_n) * BN;
+  const int tap = blockIdx.y;  // weight gradient of a 3x3 conv: one tap per blockIdx.y
   const long kbeg = (long)blockIdx.z * g.k_per_split;
   const long kend = min(kbeg + g.k_per_split, g.K);
   const int nk = (int)((kend - kbeg + BK - 1) / BK);
@@ -70,120 +85,149 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // ---------------- staging registers
+  // ---------------- staging
   constexpr bool ROWMODE = (AMODE != OP_T);
-  // row mode: 16-byte chunks; chunk c -> row c/4, k-chunk c%4
-  constexpr int NCH = ROWMODE ? (BM + BN) * 4 / 256 : 0;
-  // transposed mode: tasks of 4(k) x 8(m); task t -> kq = t / (rows/8), mc = t % (rows/8)
-  constexpr int NTASK = ROWMODE ? 0 : (BM + BN) / 256;
-  uint4 rg[ROWMODE ? NCH : NTASK * 4];
+  // row mode: 16-byte chunks, 8 per row; slot j of a thread: chunk tid + 256*j -> row (tid>>3) + 32*j
+  constexpr int NA = ROWMODE ? BM / 32 : 0;  // slots holding A chunks
+  constexpr int NB = ROWMODE ? BN / 32 : 0;
+  // transposed mode: tasks of 4(k) x 8(cols); 16 k-quads per tile
+  constexpr int TASKS_A = 2 * BM, TASKS_B = 2 * BN;
+  constexpr int NTASK = ROWMODE ? 0 : (TASKS_A + TASKS_B) / 256;
+  uint4 rg[ROWMODE ? (NA + NB) : NTASK * 4];
+  const int kc = tid & 7;  // row mode: which 8-element chunk of the 64-wide K-tile
 
-  // per-chunk pixel coordinates of the implicit-GEMM A operand (fixed over K tiles)
-  int pix_y[AMODE == A_IM2COL ? NCH : 1], pix_x[AMODE == A_IM2COL ? NCH : 1];
-  long pix_n[AMODE == A_IM2COL ? NCH : 1];
+  // implicit GEMM: per A slot the element offset of the row's own pixel and its (y, x)
+  int a_off[AMODE == A_IM2COL ? NA : 1], a_yx[AMODE == A_IM2COL ? NA : 1];
   if (AMODE == A_IM2COL) {
+    const int HWi = g.H * g.W;
 #pragma unroll
-    for (int j = 0; j < NCH; ++j) {
-      int c = tid + 256 * j;
-      if (c < BM * 4) {
-        long row = m0 + (c >> 2);
-        if (row < g.M) {
-          long n = row / ((long)g.H * g.W);
-          int rem = (int)(row - n * g.H * g.W);
-          pix_n[j] = n;
-          pix_y[j] = rem / g.W;
-          pix_x[j] = rem - pix_y[j] * g.W;
-        } else {
-          pix_n[j] = -1; pix_y[j] = 0; pix_x[j] = 0;
-        }
+    for (int j = 0; j < NA; ++j) {
+      long row = m0 + (tid >> 3) + 32 * j;
+      if (row < g.M) {
+        int rem = (int)(row % HWi);
+        int y = rem / g.W;
+        a_off[j] = (int)(row * g.C);
+        a_yx[j] = (y << 16) | (rem - y * g.W);
+      } else {
+        a_off[j] = 0;
+        a_yx[j] = -1;
       }
+    }
+  }
+  // shifted operand of the conv weight gradient: (y, x) of the first pixel row of each B task
+  int t_y[(!ROWMODE && BMODE == B_T_SHIFT) ? NTASK : 1], t_x[(!ROWMODE && BMODE == B_T_SHIFT) ? NTASK : 1];
+  if (!ROWMODE && BMODE == B_T_SHIFT) {
+    const int HWi = g.H * g.W;
+#pragma unroll
+    for (int j = 0; j < NTASK; ++j) {
+      int t = tid + 256 * j;
+      int kq = t >= TASKS_A ? (t - TASKS_A) / (BN / 8) : 0;
+      int rem = (int)((kbeg + kq * 4) % HWi);
+      t_y[j] = rem / g.W;
+      t_x[j] = rem - t_y[j] * g.W;
     }
   }
 
   auto load_tile = [&](int kt) {
     const long k0 = kbeg + (long)kt * BK;
     if (ROWMODE) {
+      const long k = k0 + kc * 8;
+      const bool kv = k < kend;
+      // tap of this K-tile when it is uniform
+      int toff = 0, dy = 0, dx = 0;
+      if (AMODE == A_IM2COL && g.fastc) {
+        int t = (int)(k0 / g.C);
+        if (g.ksize == 3) { dy = t / 3 - 1; dx = t - (t / 3) * 3 - 1; }
+        toff = (dy * g.W + dx) * g.C + (int)(k0 - (long)t * g.C) + kc * 8;
+      }
 #pragma unroll
-      for (int j = 0; j < NCH; ++j) {
-        int c = tid + 256 * j;
+      for (int j = 0; j < NA; ++j) {
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (c < BM * 4) {
-          long k = k0 + (c & 3) * 8;
-          if (AMODE == A_ROW) {
-            long row = m0 + (c >> 2);
-            if (row < g.M && k < kend) v = *reinterpret_cast<const uint4*>(g.A + row * g.lda + k);
-          } else {  // implicit GEMM: k = tap * C + ci over the NHWC image
-            if (pix_n[j] >= 0 && k < kend) {
-              int t = (int)(k / g.C);
-              int ci = (int)(k - (long)t * g.C);
-              int dy = 0, dx = 0;
-              if (g.ksize == 3) { dy = t / 3 - 1; dx = t - (t / 3) * 3 - 1; }
-              int iy = pix_y[j] + dy, ix = pix_x[j] + dx;
-              if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
-                v = *reinterpret_cast<const uint4*>(g.A + ((pix_n[j] * g.H + iy) * g.W + ix) * g.C + ci);
-            }
+        if (AMODE == A_ROW) {
+          long row = m0 + (tid >> 3) + 32 * j;
+          if (row < g.M && kv) v = *reinterpret_cast<const uint4*>(g.A + row * g.lda + k);
+        } else if (kv && a_yx[j] >= 0) {
+          int off = toff;
+          if (!g.fastc) {
+            int t = (int)(k / g.C);
+            int ci = (int)(k - (long)t * g.C);
+            dy = 0; dx = 0;
+            if (g.ksize == 3) { dy = t / 3 - 1; dx = t - (t / 3) * 3 - 1; }
+            off = (dy * g.W + dx) * g.C + ci;
           }
-        } else {
-          int cb = c - BM * 4;
-          long row = n0 + (cb >> 2);
-          long k = k0 + (cb & 3) * 8;
-          if (row < g.N && k < kend) v = *reinterpret_cast<const uint4*>(g.B + row * g.ldb + k);
+          int iy = (a_yx[j] >> 16) + dy, ix = (a_yx[j] & 0xffff) + dx;
+          if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
+            v = *reinterpret_cast<const uint4*>(g.A + a_off[j] + off);
         }
         rg[j] = v;
+      }
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        long row = n0 + (tid >> 3) + 32 * j;
+        if (row < g.N && kv) v = *reinterpret_cast<const uint4*>(g.B + row * g.ldb + k);
+        rg[NA + j] = v;
       }
     } else {
 #pragma unroll
       for (int j = 0; j < NTASK; ++j) {
         int t = tid + 256 * j;
-        const bool isA = t < BM;
-        int tt = isA ? t : t - BM;
+        const bool isA = t < TASKS_A;
+        int tt = isA ? t : t - TASKS_A;
         const int per = (isA ? BM : BN) / 8;
         int kq = tt / per, mc = tt - kq * per;
         long col = (isA ? m0 : n0) + mc * 8;
-        const long ncols = isA ? g.M : g.N;
+        const bool cv = col < (isA ? g.M : g.N);
+        int y = 0, x = 0;
+        if (BMODE == B_T_SHIFT && !isA) { y = t_y[j]; x = t_x[j]; }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           long k = k0 + kq * 4 + r;  // contraction index = matrix row (a pixel or a token)
           uint4 v = make_uint4(0, 0, 0, 0);
-          if (k < kend && col < ncols) {
+          if (k < kend && cv) {
             if (isA) {
               v = *reinterpret_cast<const uint4*>(g.A + k * g.lda + col);
             } else if (BMODE == B_T_SHIFT) {
-              long n = k / ((long)g.H * g.W);
-              int rem = (int)(k - n * g.H * g.W);
-              int y = rem / g.W, x = rem - y * g.W;
-              int iy = y + tap / 3 - 1, ix = x + tap % 3 - 1;
-              if (g.ksize == 1) { iy = y; ix = x; }
+              int dy = g.ksize == 3 ? tap / 3 - 1 : 0, dx = g.ksize == 3 ? tap % 3 - 1 : 0;
+              int iy = y + dy, ix = x + dx;
               if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
-                v = *reinterpret_cast<const uint4*>(g.B + ((n * g.H + iy) * g.W + ix) * g.ldb + col);
+                v = *reinterpret_cast<const uint4*>(g.B + (k + dy * g.W + dx) * g.ldb + col);
             } else {
               v = *reinterpret_cast<const uint4*>(g.B + k * g.ldb + col);
             }
           }
           rg[j * 4 + r] = v;
+          if (BMODE == B_T_SHIFT && !isA) {  // next pixel
+            if (++x >= g.W) { x = 0; if (++y >= g.H) y = 0; }
+          }
+        }
+        if (BMODE == B_T_SHIFT && !isA) {  // advance the task's first pixel by one K-tile (64 pixels)
+          int nx = t_x[j] + g.step_r, ny = t_y[j] + g.step_q;
+          if (nx >= g.W) { nx -= g.W; ++ny; }
+          while (ny >= g.H) ny -= g.H;
+          t_x[j] = nx;
+          t_y[j] = ny;
         }
       }
     }
   };
 
-  auto store_tile = [&]() {
+  auto store_tile = [&](int buf) {
+    bf16_t* sA = smem + buf * STAGE;
+    bf16_t* sB = sA + BM * LDS_STRIDE;
     if (ROWMODE) {
 #pragma unroll
-      for (int j = 0; j < NCH; ++j) {
-        int c = tid + 256 * j;
-        if (c < BM * 4)
-          *reinterpret_cast<uint4*>(&sA[(c >> 2) * LDS_STRIDE + (c & 3) * 8]) = rg[j];
-        else {
-          int cb = c - BM * 4;
-          *reinterpret_cast<uint4*>(&sB[(cb >> 2) * LDS_STRIDE + (cb & 3) * 8]) = rg[j];
-        }
-      }
+      for (int j = 0; j < NA; ++j)
+        *reinterpret_cast<uint4*>(&sA[((tid >> 3) + 32 * j) * LDS_STRIDE + kc * 8]) = rg[j];
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        *reinterpret_cast<uint4*>(&sB[((tid >> 3) + 32 * j) * LDS_STRIDE + kc * 8]) = rg[NA + j];
     } else {
 #pragma unroll
       for (int j = 0; j < NTASK; ++j) {
         int t = tid + 256 * j;
-        const bool isA = t < BM;
-        int tt = isA ? t : t - BM;
+        const bool isA = t < TASKS_A;
+        int tt = isA ? t : t - TASKS_A;
         const int per = (isA ? BM : BN) / 8;
         int kq = tt / per, mc = tt - kq * per;
         bf16_t* dst = (isA ? sA : sB) + (mc * 8) * LDS_STRIDE + kq * 4;
@@ -206,12 +250,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   };
 
   const int lrow = lane & 31, lgrp = lane >> 5;
-  if (nk > 0) load_tile(0);
+  if (nk > 0) {
+    load_tile(0);
+    if (DBUF) store_tile(0);
+  }
+  if (DBUF) __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
-    __syncthreads();
-    store_tile();
-    __syncthreads();
+    const int buf = DBUF ? (kt & 1) : 0;
+    if (!DBUF) {  // one LDS buffer: write the prefetched tile, then prefetch the next into registers
+      __syncthreads();
+      store_tile(0);
+      __syncthreads();
+    }
     if (kt + 1 < nk) load_tile(kt + 1);
+    const bf16_t* sA = smem + buf * STAGE;
+    const bf16_t* sB = sA + BM * LDS_STRIDE;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 af[TM], bfr[TN];
@@ -227,55 +280,87 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
+    if (DBUF) {
+      if (kt + 1 < nk) store_tile(buf ^ 1);
+      __syncthreads();
+    }
   }
+  if (!DBUF) __syncthreads();
 
   // ---------------- epilogue
+  if (EMODE == E_PART) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const long n = n0 + wn * WTN + j * 32 + lrow;
-      if (n >= g.N) continue;
-      const float bv = (EMODE == E_BF16 && g.bias) ? g.bias[n] : 0.f;
+      for (int j = 0; j < TN; ++j) {
+        const long n = n0 + wn * WTN + j * 32 + lrow;
+        if (n >= g.N) continue;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const long m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
-        if (m >= g.M) continue;
-        float v = acc[i][j][r];
-        if (EMODE == E_BF16) {
-          v += bv;
-          if (g.act == ACT_RELU) v = fmaxf(v, 0.f);
-          if (g.act == ACT_GELU) {
-            g.pre[m * g.ldc + n] = f2bf(v);
-            v = gelu_f(v);
-          }
-          g.Cb[m * g.ldc + n] = f2bf(v);
-        } else {
-          g.part[(((long)blockIdx.z * gridDim.y + tap) * g.M + m) * g.N + n] = v;
+        for (int r = 0; r < 16; ++r) {
+          const long m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
+          if (m < g.M) g.part[(((long)blockIdx.z * gridDim.y + tap) * g.M + m) * g.N + n] = acc[i][j][r];
         }
       }
+    return;
+  }
+  // bf16 tile through LDS: [BM][BN + 8]; two passes when the pre-activation is wanted too
+  constexpr int CS = BN + 8;
+  const int npass = (g.act == ACT_GELU) ? 2 : 1;
+  for (int pass = 0; pass < npass; ++pass) {
+    if (pass) __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int nl = wn * WTN + j * 32 + lrow;
+        const long n = n0 + nl;
+        const float bv = (g.bias && n < g.N) ? g.bias[n] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int ml = wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
+          float v = acc[i][j][r] + bv;
+          if (g.act == ACT_RELU) v = fmaxf(v, 0.f);
+          if (g.act == ACT_GELU && pass == 1) v = gelu_f(v);
+          smem[ml * CS + nl] = f2bf(v);
+        }
+      }
+    __syncthreads();
+    bf16_t* out = (g.act == ACT_GELU && pass == 0) ? g.pre : g.Cb;
+    for (int idx = tid; idx < BM * (BN / 8); idx += 256) {
+      int row = idx / (BN / 8), ch = idx - row * (BN / 8);
+      long m = m0 + row, n = n0 + ch * 8;
+      if (m < g.M && n < g.N)
+        *reinterpret_cast<uint4*>(out + m * g.ldc + n) = *reinterpret_cast<const uint4*>(&smem[row * CS + ch * 8]);
     }
   }
 }
 
-// G[co][ci][tap] += sum_s part[s][tap][co][ci]   (taps == 1: plain [M][N] accumulate)
-__global__ void reduce_wgrad_kernel(const float* __restrict__ part, float* __restrict__ G, long M, long N,
-                                    int taps, int splits) {
-  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  long total = (long)taps * M * N;
-  if (i >= total) return;
-  int t = (int)(i / (M * N));
-  long rem = i - (long)t * M * N;  // = co * N + ci
+// G[co][ci][tap] += sum_s part[s][tap][co][ci]   (taps == 1: plain [M][N] accumulate).
+// 64 outputs x 4 interleaved split lanes per block, combined through LDS in a fixed order.
+__global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float* __restrict__ part,
+                                                           float* __restrict__ G, long M, long N, int taps,
+                                                           int splits) {
+  __shared__ float sh[4][64];
+  const int o = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const long i = (long)blockIdx.x * 64 + o;
+  const long total = (long)taps * M * N;
   float s = 0.f;
-  for (int k = 0; k < splits; ++k) s += part[(long)k * total + i];
-  G[rem * taps + t] += s;
+  if (i < total)
+    for (int k = q; k < splits; k += 4) s += part[(long)k * total + i];
+  sh[q][o] = s;
+  __syncthreads();
+  if (q == 0 && i < total) {
+    int t = (int)(i / (M * N));
+    long rem = i - (long)t * M * N;  // = co * N + ci
+    G[rem * taps + t] += (sh[0][o] + sh[1][o]) + (sh[2][o] + sh[3][o]);
+  }
 }
 
 // column sums of a bf16 [R][C] matrix into fp32: stage 1 partials [S][C], stage 2 accumulate
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __restrict__ g,
                                                              float* __restrict__ part, long R, int C,
                                                              long rows_per_block) {
-  // thread -> 8 consecutive columns (one 16-byte load); blockDim.x/ (C/8) row lanes
+  // thread -> 8 consecutive columns (one 16-byte load); blockDim.x / (C/8) row lanes
   const int cg = C / 8;
   const int colg = threadIdx.x % cg, rl = threadIdx.x / cg, nrl = blockDim.x / cg;
   const long r0 = (long)blockIdx.x * rows_per_block, r1 = min(r0 + rows_per_block, R);
@@ -304,12 +389,21 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __res
     part[(long)blockIdx.x * C + c] = s;
   }
 }
-__global__ void colsum_final_kernel(const float* __restrict__ part, float* __restrict__ G, int C, int S) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= C) return;
+// 16 columns x 16 interleaved partial lanes per block, butterfly-added in a fixed order
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part,
+                                                           float* __restrict__ G, int C, int S) {
+  const int c = blockIdx.x * 16 + (threadIdx.x & 15), q = threadIdx.x >> 4;
   float s = 0.f;
-  for (int k = 0; k < S; ++k) s += part[(long)k * C + c];
-  G[c] += s;
+  if (c < C)
+    for (int k = q; k < S; k += 16) s += part[(long)k * C + c];
+  // lanes with equal (threadIdx.x & 15) inside a wavefront differ by multiples of 16
+  s += __shfl_xor(s, 16, 64);
+  s += __shfl_xor(s, 32, 64);
+  __shared__ float sh[4][16];
+  if ((threadIdx.x & 63) < 16) sh[threadIdx.x >> 6][threadIdx.x & 15] = s;
+  __syncthreads();
+  if (threadIdx.x < 16 && c < C)
+    G[c] += (sh[0][threadIdx.x] + sh[1][threadIdx.x]) + (sh[2][threadIdx.x] + sh[3][threadIdx.x]);
 }
 
 inline long cdivl(long a, long b) { return (a + b - 1) / b; }
@@ -348,17 +442,64 @@ void launch_colsum(hipStream_t st, const bf16_t* g, float* G, float* ws, long R,
   blocks = cdivl(R, rpb);
   KLAUNCH(colsum_partial_kernel, dim3((unsigned)blocks), dim3(threads), (size_t)nrl * C * sizeof(float), st, g, ws, R,
           C, rpb);
-  KLAUNCH(colsum_final_kernel, dim3((unsigned)cdivl(C, 256)), dim3(256), 0, st, ws, G, C, (int)blocks);
+  KLAUNCH(colsum_final_kernel, dim3((unsigned)cdivl(C, 16)), dim3(256), 0, st, ws, G, C, (int)blocks);
 }
 
-template <int AMODE>
-void launch_fwd_like(hipStream_t st, GemmArgs& g) {
-  // block tile 128 x 128 (4 wavefronts of 64 x 64)
-  constexpr int WT = 64;
-  long tm = cdivl(g.M, 2 * WT), tn = cdivl(g.N, 2 * WT);
+template <int WTM, int WTN, bool DBUF>
+constexpr size_t lds_bytes() {
+  size_t stage = (size_t)(2 * WTM + 2 * WTN) * LDS_STRIDE * sizeof(bf16_t);
+  size_t ctile = (size_t)2 * WTM * (2 * WTN + 8) * sizeof(bf16_t);  // output tile of the epilogue
+  size_t need = DBUF ? 2 * stage : stage;
+  return need > ctile ? need : ctile;
+}
+
+// experiment switch: ASTEROID_GEMM_VARIANT=<int> overrides the tile choice of forward-like products
+int gemm_variant() {
+  static int v = -2;
+  if (v == -2) {
+    const char* e = getenv("ASTEROID_GEMM_VARIANT");
+    v = e ? atoi(e) : -1;
+  }
+  return v;
+}
+
+template <int WTM, int AMODE>
+constexpr const char* fwd_name() {
+  if (AMODE == A_IM2COL) return WTM == 128 ? "gemm_bf16_kernel<256x128,im2col>" : (WTM == 64 ? "gemm_bf16_kernel<128x128,im2col>" : "gemm_bf16_kernel<64x64,im2col>");
+  return WTM == 128 ? "gemm_bf16_kernel<256x128,rows>" : (WTM == 64 ? "gemm_bf16_kernel<128x128,rows>" : "gemm_bf16_kernel<64x64,rows>");
+}
+
+template <int WTM, int WTN, int AMODE, bool DBUF>
+void launch_tile(hipStream_t st, GemmArgs& g) {
+  long tm = cdivl(g.M, 2 * WTM), tn = cdivl(g.N, 2 * WTN);
   g.tiles_n = (int)tn;
   g.k_per_split = cdivl(g.K, BK) * BK;
-  KLAUNCH((gemm_bf16_kernel<WT, WT, AMODE, B_ROW, E_BF16>), dim3((unsigned)(tm * tn), 1, 1), dim3(256), 0, st, g);
+  auto kern = gemm_bf16_kernel<WTM, WTN, AMODE, B_ROW, E_BF16, DBUF>;
+  constexpr size_t lds = lds_bytes<WTM, WTN, DBUF>();
+  static bool once = false;  // more than 64 KiB of dynamic LDS has to be allowed per kernel
+  if (!once) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    once = true;
+  }
+  KLAUNCH_NAMED((fwd_name<WTM, AMODE>()), kern, dim3((unsigned)(tm * tn), 1, 1), dim3(256), lds, st, g);
+}
+
+// forward-like products: the largest block tile that still yields >= 512 blocks
+template <int AMODE>
+void launch_fwd_like(hipStream_t st, GemmArgs& g) {
+  auto blocks = [&](int bm, int bn) { return cdivl(g.M, bm) * cdivl(g.N, bn); };
+  switch (gemm_variant()) {
+    case 0: launch_tile<128, 64, AMODE, true>(st, g); return;
+    case 1: launch_tile<64, 64, AMODE, true>(st, g); return;
+    case 2: launch_tile<64, 64, AMODE, false>(st, g); return;
+    case 3: launch_tile<32, 32, AMODE, true>(st, g); return;
+    case 4: launch_tile<32, 32, AMODE, false>(st, g); return;
+    case 5: launch_tile<128, 64, AMODE, false>(st, g); return;
+    default: break;
+  }
+  if (blocks(256, 128) >= 512) launch_tile<128, 64, AMODE, true>(st, g);
+  else if (blocks(128, 128) >= 256) launch_tile<64, 64, AMODE, true>(st, g);
+  else launch_tile<32, 32, AMODE, true>(st, g);
 }
 
 template <int BMODE>
@@ -369,10 +510,24 @@ void launch_wgrad(hipStream_t st, GemmArgs& g, float* G, float* ws, int taps) {
   g.k_per_split = cdivl(cdivl(g.K, splits), BK) * BK;
   splits = (int)cdivl(g.K, g.k_per_split);
   g.part = ws;
-  KLAUNCH((gemm_bf16_kernel<WG_T, WG_T, OP_T, BMODE, E_PART>), dim3((unsigned)(tm * tn), taps, splits), dim3(256), 0,
-          st, g);
+  auto kern = gemm_bf16_kernel<WG_T, WG_T, OP_T, BMODE, E_PART, true>;
+  constexpr size_t lds = lds_bytes<WG_T, WG_T, true>();
+  static bool once = false;
+  if (!once) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    once = true;
+  }
+  KLAUNCH_NAMED(BMODE == B_T_SHIFT ? "gemm_bf16_kernel<128x128,wgrad_conv>" : "gemm_bf16_kernel<128x128,wgrad_rows>", kern,
+                dim3((unsigned)(tm * tn), taps, splits), dim3(256), lds, st, g);
   long total = (long)taps * g.M * g.N;
-  KLAUNCH(reduce_wgrad_kernel, dim3((unsigned)cdivl(total, 256)), dim3(256), 0, st, ws, G, g.M, g.N, taps, splits);
+  KLAUNCH(reduce_wgrad_kernel, dim3((unsigned)cdivl(total, 64)), dim3(256), 0, st, ws, G, g.M, g.N, taps, splits);
+}
+
+void set_geometry(GemmArgs& g, int H, int W, int C, int k) {
+  g.H = H; g.W = W; g.C = C; g.ksize = k;
+  g.fastc = (C % BK == 0) ? 1 : 0;
+  g.step_q = BK / W;
+  g.step_r = BK % W;
 }
 
 }  // namespace
@@ -389,7 +544,8 @@ void conv_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh_fwd, const 
   GemmArgs g = {};
   g.A = x; g.B = sh_fwd;
   g.M = (long)N * H * W; g.N = Cout; g.K = (long)k * k * Cin;
-  g.ldb = g.K; g.H = H; g.W = W; g.C = Cin; g.ksize = k;
+  g.ldb = g.K;
+  set_geometry(g, H, W, Cin, k);
   g.Cb = y; g.ldc = Cout; g.bias = bias; g.act = act;
   launch_fwd_like<A_IM2COL>(st, g);
 }
@@ -399,7 +555,8 @@ void conv_bf16_dgrad(hipStream_t st, const bf16_t* gy, const bf16_t* sh_dgrad, b
   GemmArgs g = {};
   g.A = gy; g.B = sh_dgrad;
   g.M = (long)N * H * W; g.N = Cin; g.K = (long)k * k * Cout;
-  g.ldb = g.K; g.H = H; g.W = W; g.C = Cout; g.ksize = k;
+  g.ldb = g.K;
+  set_geometry(g, H, W, Cout, k);
   g.Cb = dx; g.ldc = Cin; g.bias = nullptr; g.act = 0;
   launch_fwd_like<A_IM2COL>(st, g);
 }
@@ -409,7 +566,8 @@ void conv_bf16_wgrad(hipStream_t st, const bf16_t* gy, const bf16_t* x, float* G
   GemmArgs g = {};
   g.A = gy; g.B = x;
   g.M = Cout; g.N = Cin; g.K = (long)N * H * W;
-  g.lda = Cout; g.ldb = Cin; g.H = H; g.W = W; g.C = Cin; g.ksize = k;
+  g.lda = Cout; g.ldb = Cin;
+  set_geometry(g, H, W, Cin, k);
   launch_wgrad<B_T_SHIFT>(st, g, GW, reinterpret_cast<float*>(ws), k * k);
   if (Gb) launch_colsum(st, gy, Gb, reinterpret_cast<float*>(ws), (long)N * H * W, Cout);
 }
@@ -442,7 +600,8 @@ void linear_bf16_wgrad(hipStream_t st, const bf16_t* gy, const bf16_t* x, float*
                        size_t R, int Cin, int Cout) {
   GemmArgs g = {};
   g.A = gy; g.B = x;
-  g.M = Cout; g.N = Cin; g.K = (long)R; g.lda = Cout; g.ldb = Cin; g.ksize = 1; g.H = 1; g.W = 1;
+  g.M = Cout; g.N = Cin; g.K = (long)R; g.lda = Cout; g.ldb = Cin;
+  set_geometry(g, 1, 1, Cin, 1);
   launch_wgrad<OP_T>(st, g, GW, reinterpret_cast<float*>(ws), 1);
   if (Gb) launch_colsum(st, gy, Gb, reinterpret_cast<float*>(ws), (long)R, Cout);
 }

@@ -326,14 +326,24 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
   for (int i = threadIdx.x; i < 2 * D; i += 256)
     part[(size_t)blockIdx.x * 2 * D + i] = (sh[i] + sh[2 * D + i]) + (sh[4 * D + i] + sh[6 * D + i]);
 }
-__global__ void layernorm_bwd_final_kernel(const float* __restrict__ part, float* __restrict__ Ggamma,
-                                           float* __restrict__ Gbeta, int D, int blocks) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= 2 * D) return;
+// 16 outputs x 16 interleaved partial lanes per block, added in a fixed order
+__global__ __launch_bounds__(256) void layernorm_bwd_final_kernel(const float* __restrict__ part,
+                                                                  float* __restrict__ Ggamma,
+                                                                  float* __restrict__ Gbeta, int D, int blocks) {
+  const int i = blockIdx.x * 16 + (threadIdx.x & 15), q = threadIdx.x >> 4;
   float s = 0.f;
-  for (int b = 0; b < blocks; ++b) s += part[(size_t)b * 2 * D + i];
-  if (i < D) Ggamma[i] += s;
-  else Gbeta[i - D] += s;
+  if (i < 2 * D)
+    for (int b = q; b < blocks; b += 16) s += part[(size_t)b * 2 * D + i];
+  s += __shfl_xor(s, 16, 64);
+  s += __shfl_xor(s, 32, 64);
+  __shared__ float sh[4][16];
+  if ((threadIdx.x & 63) < 16) sh[threadIdx.x >> 6][threadIdx.x & 15] = s;
+  __syncthreads();
+  if (threadIdx.x < 16 && i < 2 * D) {
+    float v = (sh[0][threadIdx.x] + sh[1][threadIdx.x]) + (sh[2][threadIdx.x] + sh[3][threadIdx.x]);
+    if (i < D) Ggamma[i] += v;
+    else Gbeta[i - D] += v;
+  }
 }
 
 static inline size_t ln_blocks(size_t R) {
@@ -359,7 +369,7 @@ void layernorm_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, const 
   else
     KLAUNCH(layernorm_bwd_kernel<2>, dim3((unsigned)blocks), dim3(256), (size_t)8 * D * sizeof(float), st, g, x, stat,
             gamma, dx, part, R, D, rpb);
-  KLAUNCH(layernorm_bwd_final_kernel, dim3(cdivu(2 * (size_t)D, 256)), dim3(256), 0, st, part, Ggamma, Gbeta, D,
+  KLAUNCH(layernorm_bwd_final_kernel, dim3(cdivu(2 * (size_t)D, 16)), dim3(256), 0, st, part, Ggamma, Gbeta, D,
           (int)blocks);
 }
 

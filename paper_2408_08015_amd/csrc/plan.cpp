@@ -73,6 +73,9 @@ ast_status build_plan(Stage& s, std::string& err) {
           if (!(g == 1 && (k == 1 || k == 3) && st == 1 && pad == (k - 1) / 2 && Cin % 8 == 0 && Cout % 8 == 0)) {
             err = fmt("layer %d: bf16 conv2d supports dense 1x1/3x3 stride 1 'same' with channels %% 8 == 0", i);
             return AST_EUNSUPPORTED; }
+          if ((size_t)B * A.h * A.w * std::max(Cin, Cout) >= ((size_t)1 << 31)) {
+            err = fmt("layer %d: bf16 conv2d tensors must stay below 2^31 elements", i);
+            return AST_EUNSUPPORTED; }
           op.kind = OP_CONV_IGEMM;
           op.sh_off = shadow; shadow += (size_t)Cout * k * k * Cin;   // [Cout][tap][Cin]
           op.sh2_off = shadow; shadow += (size_t)Cout * k * k * Cin;  // [Cin][tap flipped][Cout]

@@ -45,4 +45,11 @@ struct ProfScope {
     hipLaunchKernelGGL(kern, grid, block, shm, st, __VA_ARGS__);    \
   } while (0)
 
+// same, with an explicit display name (for template kernels launched through a pointer)
+#define KLAUNCH_NAMED(name, kern, grid, block, shm, st, ...)       \
+  do {                                                              \
+    ::ast::ProfScope prof_scope_(name, st);                         \
+    hipLaunchKernelGGL(kern, grid, block, shm, st, __VA_ARGS__);    \
+  } while (0)
+
 }  // namespace ast
