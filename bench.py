@@ -24,24 +24,88 @@ HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
-def dominant_kernel(cfg):
-    """(kernel-name filter, bound, algorithmic units per launch averaged over one round's
-    launches, unit).  The dominant kernel of each workload was read off a rocprofv3
-    kernel trace of this same command (summaries under profiles/)."""
+def _cdiv(a, b):
+    return -(-a // b)
+
+
+def kernel_model(cfg):
+    """Algorithmic work of the kernel classes that can dominate a workload, from the layer list
+    and the launch rules of the library (one entry per launch of one micro-batch):
+    {profile kernel name: [(units, ...), ...]} with units = bytes (HBM-bound) or flops (MFMA)."""
     from asteroid_workloads import gen
-    if cfg.name.startswith("cfg4") or cfg.name.startswith("cfg5"):
-        return None
-    # fp32 MobileNetV2-style stages: BatchNorm backward apply kernel
-    #   per element: read g, read x, write dx  = 12 bytes
-    total, launches = 0, 0
+    B = cfg.B
+    out = {}
     shape = tuple(cfg.in_shape)
-    for L in cfg.layers:
-        if L["kind"] == "batchnorm2d":
+    first = True
+    res_open = False
+    for i, L in enumerate(cfg.layers):
+        k = L["kind"]
+        oshape = gen.out_shape([L], shape)
+        if k == "res_begin":
+            res_open = True
+        if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 1 and L["groups"] == 1:
+            cin, cout = L["cin"], L["cout"]
+            hw = shape[1] * shape[2]
+            nq = B * hw
+
+            def cls(m):
+                px4 = hw % 4 == 0 and _cdiv(nq, 512) * _cdiv(m, 32) >= 512
+                return "pw_conv_f32_px4_kernel" if px4 else "pw_conv_f32_kernel<1>"
+            out.setdefault(cls(cout), []).append(4 * (cin + cout) * nq)            # forward
+            if not first or cfg.needs_input_grad:                                   # input gradient
+                extra = 4 * cin * nq if (res_open and cfg.layers[i - 1]["kind"] == "res_begin") else 0
+                out.setdefault(cls(cin), []).append(4 * (cin + cout) * nq + extra)
+        if k == "batchnorm2d":
             c, h, w = shape
-            total += 12 * cfg.B * c * h * w
-            launches += 1
-        shape = gen.out_shape([L], shape)
-    return "bn_bwd_apply_kernel", "hbm", total / max(launches, 1), "GB/s"
+            out.setdefault("bn_bwd_apply_kernel", []).append(12 * B * c * h * w)
+        if k == "conv2d" and cfg.dtype == "bf16":
+            cin, cout, kk = L["cin"], L["cout"], L["k"] * L["k"]
+            m = B * shape[1] * shape[2]
+
+            def gcls(mm, nn):
+                return "gemm_bf16_kernel<128x128,im2col>" if _cdiv(mm, 128) * _cdiv(nn, 128) >= 256 \
+                    else "gemm_bf16_kernel<64x64,im2col>"
+            out.setdefault(gcls(m, cout), []).append(2 * m * cout * kk * cin)
+            if not first or cfg.needs_input_grad:
+                out.setdefault(gcls(m, cin), []).append(2 * m * cin * kk * cout)
+            out.setdefault("gemm_bf16_kernel<128x128,wgrad_conv>", []).append(2 * m * cout * kk * cin)
+        if cfg.dtype == "bf16" and k in ("linear", "mha"):
+            rows = B * shape[0]
+
+            def lcls(mm, nn):
+                return "gemm_bf16_kernel<128x128,rows>" if _cdiv(mm, 128) * _cdiv(nn, 128) >= 256 \
+                    else "gemm_bf16_kernel<64x64,rows>"
+            mats = [(L["cin"], L["cout"])] if k == "linear" else [(L["d"], 3 * L["d"]), (L["d"], L["d"])]
+            for cin, cout in mats:
+                out.setdefault(lcls(rows, cout), []).append(2 * rows * cin * cout)      # forward
+                out.setdefault(lcls(rows, cin), []).append(2 * rows * cin * cout)       # input gradient
+                out.setdefault("gemm_bf16_kernel<128x128,wgrad_rows>", []).append(2 * rows * cin * cout)
+        if k == "res_add":
+            res_open = False
+        if k not in ("res_begin",):
+            first = False
+        shape = oshape
+    return out
+
+
+# dominant kernel of each workload, read off the rocprofv3 kernel traces under profiles/
+DOMINANT = {
+    "cfg1": ("pw_conv_f32_kernel<1>", "hbm"),
+    "cfg2": ("pw_conv_f32_kernel<1>", "hbm"),
+    "cfg3": ("pw_conv_f32_kernel<1>", "hbm"),
+    "cfg4": ("gemm_bf16_kernel<128x128,im2col>", "mfma"),
+    "cfg5": ("gemm_bf16_kernel<64x64,rows>", "mfma"),
+}
+
+
+def dominant_kernel(cfg, workload):
+    """(kernel-name filter, bound, algorithmic units per launch averaged over one round's
+    launches of that kernel, unit)."""
+    name, bound = DOMINANT[workload]
+    units = kernel_model(cfg).get(name)
+    if not units:
+        return None
+    return name, bound, sum(units) / len(units), "GB/s" if bound == "hbm" else "TFLOP/s"
 
 
 def run(args):
@@ -87,7 +151,7 @@ def run(args):
         one_round()
     torch.cuda.synchronize()
 
-    dom = dominant_kernel(cfg)
+    dom = dominant_kernel(cfg, args.workload)
     filt = "" if args.profile_all else (dom[0] if dom else None)
     if filt is not None:
         st.profile_begin(filt, max_launches=args.steps * (20000 if args.profile_all else 512))
@@ -109,8 +173,8 @@ def run(args):
         ms = sum(v[1] for v in hits.values())
         if n:
             avg_s = ms * 1e-3 / n
-            achieved = units / avg_s / 1e9
-            peak = HBM_PEAK_GBS if bound == "hbm" else MFMA_PEAK_TFLOPS[cfg.dtype] * 1e3
+            achieved = units / avg_s / (1e9 if bound == "hbm" else 1e12)
+            peak = HBM_PEAK_GBS if bound == "hbm" else MFMA_PEAK_TFLOPS[cfg.dtype]
             roofline = {"bound": bound, "kernel": name, "achieved": round(achieved, 1), "peak": peak,
                         "unit": unit, "frac": round(achieved / peak, 4), "traffic": None,
                         "launches": n, "avg_us": round(avg_s * 1e6, 2)}

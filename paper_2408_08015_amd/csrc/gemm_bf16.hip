@@ -50,9 +50,17 @@ struct GemmArgs {
   int tiles_n;         // number of tiles along N (blockIdx.x = tile_m * tiles_n + tile_n)
 };
 
+// Element offset of 16-byte chunk c16 (0..7) of LDS row `row`.  Chunks are XOR-swizzled with
+// bits 3..5 of the row so that the transposed staging of the weight-gradient operands
+// (lanes write rows 8 apart at the same K offset) spreads over the banks instead of piling
+// 16 lanes on one; reads and row-mode writes keep their conflict-free pattern.
+__device__ __forceinline__ int lds_off(int row, int c16) {
+  return row * LDS_STRIDE + ((c16 ^ ((row >> 3) & 7)) << 3);
+}
+
 __device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
 
-template <int WTM, int WTN, int AMODE, int BMODE, int EMODE, bool DBUF>
+template <int WTM, int WTN, int AMODE, int BMODE, int EMODE, bool DBUF, bool FASTC>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int BM = 2 * WTM, BN = 2 * WTN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -96,23 +104,44 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   uint4 rg[ROWMODE ? (NA + NB) : NTASK * 4];
   const int kc = tid & 7;  // row mode: which 8-element chunk of the 64-wide K-tile
 
-  // implicit GEMM: per A slot the element offset of the row's own pixel and its (y, x)
-  int a_off[AMODE == A_IM2COL ? NA : 1], a_yx[AMODE == A_IM2COL ? NA : 1];
-  if (AMODE == A_IM2COL) {
-    const int HWi = g.H * g.W;
+  // Row mode: per slot the element offset of the row (without the K position), so that the
+  // per-tile address is one add.  Implicit GEMM: offset of the row's own pixel and its (y, x).
+  long a_off[ROWMODE ? NA : 1];
+  int a_yx[ROWMODE ? NA : 1];
+  long b_off[ROWMODE ? NB : 1];
+  bool b_ok[ROWMODE ? NB : 1];
+  if (ROWMODE) {
+    const int HWi = AMODE == A_IM2COL ? g.H * g.W : 1;
 #pragma unroll
     for (int j = 0; j < NA; ++j) {
       long row = m0 + (tid >> 3) + 32 * j;
+      a_off[j] = 0;
+      a_yx[j] = -1;
       if (row < g.M) {
-        int rem = (int)(row % HWi);
-        int y = rem / g.W;
-        a_off[j] = (int)(row * g.C);
-        a_yx[j] = (y << 16) | (rem - y * g.W);
-      } else {
-        a_off[j] = 0;
-        a_yx[j] = -1;
+        if (AMODE == A_IM2COL) {
+          int rem = (int)(row % HWi);
+          int y = rem / g.W;
+          a_off[j] = row * g.C;
+          a_yx[j] = (y << 16) | (rem - y * g.W);
+        } else {
+          a_off[j] = row * g.lda + kc * 8;
+          a_yx[j] = 0;
+        }
       }
     }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      long row = n0 + (tid >> 3) + 32 * j;
+      b_ok[j] = row < g.N;
+      b_off[j] = b_ok[j] ? row * g.ldb + kc * 8 : 0;
+    }
+  }
+  // implicit GEMM with C % 64 == 0: the tap and channel offset of the current K-tile, kept as
+  // loop-carried uniform state (no division inside the loop)
+  int cur_tap = 0, cur_ci = 0;
+  if (ROWMODE && AMODE == A_IM2COL && FASTC) {
+    cur_tap = (int)(kbeg / g.C);
+    cur_ci = (int)(kbeg - (long)cur_tap * g.C);
   }
   // shifted operand of the conv weight gradient: (y, x) of the first pixel row of each B task
   int t_y[(!ROWMODE && BMODE == B_T_SHIFT) ? NTASK : 1], t_x[(!ROWMODE && BMODE == B_T_SHIFT) ? NTASK : 1];
@@ -128,45 +157,49 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     }
   }
 
+  // Loads are unconditional from an always-valid address (the operand base when the element
+  // is padding or out of range) and zeroed by a select afterwards: no branches, so the
+  // loads of a tile issue back to back.
   auto load_tile = [&](int kt) {
     const long k0 = kbeg + (long)kt * BK;
     if (ROWMODE) {
       const long k = k0 + kc * 8;
       const bool kv = k < kend;
-      // tap of this K-tile when it is uniform
       int toff = 0, dy = 0, dx = 0;
-      if (AMODE == A_IM2COL && g.fastc) {
-        int t = (int)(k0 / g.C);
+      if (AMODE == A_IM2COL) {
+        int t, ci;
+        if (FASTC) {  // uniform over the tile; advanced incrementally
+          t = cur_tap;
+          ci = cur_ci + kc * 8;
+          cur_ci += BK;
+          if (cur_ci >= g.C) { cur_ci = 0; ++cur_tap; }
+        } else {
+          t = (int)(k / g.C);
+          ci = (int)(k - (long)t * g.C);
+        }
         if (g.ksize == 3) { dy = t / 3 - 1; dx = t - (t / 3) * 3 - 1; }
-        toff = (dy * g.W + dx) * g.C + (int)(k0 - (long)t * g.C) + kc * 8;
+        toff = (dy * g.W + dx) * g.C + ci;
       }
 #pragma unroll
       for (int j = 0; j < NA; ++j) {
-        uint4 v = make_uint4(0, 0, 0, 0);
+        bool ok;
+        long off;
         if (AMODE == A_ROW) {
-          long row = m0 + (tid >> 3) + 32 * j;
-          if (row < g.M && kv) v = *reinterpret_cast<const uint4*>(g.A + row * g.lda + k);
-        } else if (kv && a_yx[j] >= 0) {
-          int off = toff;
-          if (!g.fastc) {
-            int t = (int)(k / g.C);
-            int ci = (int)(k - (long)t * g.C);
-            dy = 0; dx = 0;
-            if (g.ksize == 3) { dy = t / 3 - 1; dx = t - (t / 3) * 3 - 1; }
-            off = (dy * g.W + dx) * g.C + ci;
-          }
+          ok = a_yx[j] >= 0 && kv;
+          off = a_off[j] + k0;
+        } else {
           int iy = (a_yx[j] >> 16) + dy, ix = (a_yx[j] & 0xffff) + dx;
-          if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
-            v = *reinterpret_cast<const uint4*>(g.A + a_off[j] + off);
+          ok = kv && a_yx[j] >= 0 && iy >= 0 && iy < g.H && ix >= 0 && ix < g.W;
+          off = a_off[j] + toff;
         }
-        rg[j] = v;
+        uint4 v = *reinterpret_cast<const uint4*>(g.A + (ok ? off : 0));
+        rg[j] = ok ? v : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        long row = n0 + (tid >> 3) + 32 * j;
-        if (row < g.N && kv) v = *reinterpret_cast<const uint4*>(g.B + row * g.ldb + k);
-        rg[NA + j] = v;
+        const bool ok = b_ok[j] && kv;
+        uint4 v = *reinterpret_cast<const uint4*>(g.B + (ok ? b_off[j] + k0 : 0));
+        rg[NA + j] = ok ? v : make_uint4(0, 0, 0, 0);
       }
     } else {
 #pragma unroll
@@ -180,26 +213,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         const bool cv = col < (isA ? g.M : g.N);
         int y = 0, x = 0;
         if (BMODE == B_T_SHIFT && !isA) { y = t_y[j]; x = t_x[j]; }
+        const int dy = (BMODE == B_T_SHIFT && g.ksize == 3) ? tap / 3 - 1 : 0;
+        const int dx = (BMODE == B_T_SHIFT && g.ksize == 3) ? tap % 3 - 1 : 0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           long k = k0 + kq * 4 + r;  // contraction index = matrix row (a pixel or a token)
-          uint4 v = make_uint4(0, 0, 0, 0);
-          if (k < kend && cv) {
-            if (isA) {
-              v = *reinterpret_cast<const uint4*>(g.A + k * g.lda + col);
-            } else if (BMODE == B_T_SHIFT) {
-              int dy = g.ksize == 3 ? tap / 3 - 1 : 0, dx = g.ksize == 3 ? tap % 3 - 1 : 0;
-              int iy = y + dy, ix = x + dx;
-              if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
-                v = *reinterpret_cast<const uint4*>(g.B + (k + dy * g.W + dx) * g.ldb + col);
-            } else {
-              v = *reinterpret_cast<const uint4*>(g.B + k * g.ldb + col);
-            }
+          bool ok = k < kend && cv;
+          const bf16_t* p;
+          if (isA) {
+            p = g.A + (ok ? k * g.lda + col : 0);
+          } else if (BMODE == B_T_SHIFT) {
+            int iy = y + dy, ix = x + dx;
+            ok = ok && iy >= 0 && iy < g.H && ix >= 0 && ix < g.W;
+            p = g.B + (ok ? (k + dy * g.W + dx) * g.ldb + col : 0);
+            if (++x >= g.W) { x = 0; if (++y >= g.H) y = 0; }  // next pixel
+          } else {
+            p = g.B + (ok ? k * g.ldb + col : 0);
           }
-          rg[j * 4 + r] = v;
-          if (BMODE == B_T_SHIFT && !isA) {  // next pixel
-            if (++x >= g.W) { x = 0; if (++y >= g.H) y = 0; }
-          }
+          uint4 v = *reinterpret_cast<const uint4*>(p);
+          rg[j * 4 + r] = ok ? v : make_uint4(0, 0, 0, 0);
         }
         if (BMODE == B_T_SHIFT && !isA) {  // advance the task's first pixel by one K-tile (64 pixels)
           int nx = t_x[j] + g.step_r, ny = t_y[j] + g.step_q;
@@ -218,10 +250,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     if (ROWMODE) {
 #pragma unroll
       for (int j = 0; j < NA; ++j)
-        *reinterpret_cast<uint4*>(&sA[((tid >> 3) + 32 * j) * LDS_STRIDE + kc * 8]) = rg[j];
+        *reinterpret_cast<uint4*>(&sA[lds_off((tid >> 3) + 32 * j, kc)]) = rg[j];
 #pragma unroll
       for (int j = 0; j < NB; ++j)
-        *reinterpret_cast<uint4*>(&sB[((tid >> 3) + 32 * j) * LDS_STRIDE + kc * 8]) = rg[NA + j];
+        *reinterpret_cast<uint4*>(&sB[lds_off((tid >> 3) + 32 * j, kc)]) = rg[NA + j];
     } else {
 #pragma unroll
       for (int j = 0; j < NTASK; ++j) {
@@ -230,7 +262,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         int tt = isA ? t : t - TASKS_A;
         const int per = (isA ? BM : BN) / 8;
         int kq = tt / per, mc = tt - kq * per;
-        bf16_t* dst = (isA ? sA : sB) + (mc * 8) * LDS_STRIDE + kq * 4;
+        bf16_t* base = isA ? sA : sB;
         const uint32_t* r0 = reinterpret_cast<const uint32_t*>(&rg[j * 4 + 0]);
         const uint32_t* r1 = reinterpret_cast<const uint32_t*>(&rg[j * 4 + 1]);
         const uint32_t* r2 = reinterpret_cast<const uint32_t*>(&rg[j * 4 + 2]);
@@ -242,8 +274,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
           lo.y = (r2[w] & 0xffffu) | (r3[w] << 16);
           hi.x = (r0[w] >> 16) | (r1[w] & 0xffff0000u);
           hi.y = (r2[w] >> 16) | (r3[w] & 0xffff0000u);
-          *reinterpret_cast<uint2*>(dst + (2 * w) * LDS_STRIDE) = lo;
-          *reinterpret_cast<uint2*>(dst + (2 * w + 1) * LDS_STRIDE) = hi;
+          *reinterpret_cast<uint2*>(base + lds_off(mc * 8 + 2 * w, kq >> 1) + (kq & 1) * 4) = lo;
+          *reinterpret_cast<uint2*>(base + lds_off(mc * 8 + 2 * w + 1, kq >> 1) + (kq & 1) * 4) = hi;
         }
       }
     }
@@ -270,10 +302,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
       bf16x8 af[TM], bfr[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(&sA[(wm * WTM + i * 32 + lrow) * LDS_STRIDE + ks * 16 + lgrp * 8]);
+        af[i] = *reinterpret_cast<const bf16x8*>(&sA[lds_off(wm * WTM + i * 32 + lrow, ks * 2 + lgrp)]);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(&sB[(wn * WTN + j * 32 + lrow) * LDS_STRIDE + ks * 16 + lgrp * 8]);
+        bfr[j] = *reinterpret_cast<const bf16x8*>(&sB[lds_off(wn * WTN + j * 32 + lrow, ks * 2 + lgrp)]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -469,12 +501,12 @@ constexpr const char* fwd_name() {
   return WTM == 128 ? "gemm_bf16_kernel<256x128,rows>" : (WTM == 64 ? "gemm_bf16_kernel<128x128,rows>" : "gemm_bf16_kernel<64x64,rows>");
 }
 
-template <int WTM, int WTN, int AMODE, bool DBUF>
-void launch_tile(hipStream_t st, GemmArgs& g) {
+template <int WTM, int WTN, int AMODE, bool DBUF, bool FASTC>
+void launch_tile_c(hipStream_t st, GemmArgs& g) {
   long tm = cdivl(g.M, 2 * WTM), tn = cdivl(g.N, 2 * WTN);
   g.tiles_n = (int)tn;
   g.k_per_split = cdivl(g.K, BK) * BK;
-  auto kern = gemm_bf16_kernel<WTM, WTN, AMODE, B_ROW, E_BF16, DBUF>;
+  auto kern = gemm_bf16_kernel<WTM, WTN, AMODE, B_ROW, E_BF16, DBUF, FASTC>;
   constexpr size_t lds = lds_bytes<WTM, WTN, DBUF>();
   static bool once = false;  // more than 64 KiB of dynamic LDS has to be allowed per kernel
   if (!once) {
@@ -484,22 +516,27 @@ void launch_tile(hipStream_t st, GemmArgs& g) {
   KLAUNCH_NAMED((fwd_name<WTM, AMODE>()), kern, dim3((unsigned)(tm * tn), 1, 1), dim3(256), lds, st, g);
 }
 
+template <int WTM, int WTN, int AMODE, bool DBUF>
+void launch_tile(hipStream_t st, GemmArgs& g) {
+  if (AMODE == A_IM2COL && !g.fastc) launch_tile_c<WTM, WTN, AMODE, DBUF, false>(st, g);
+  else launch_tile_c<WTM, WTN, AMODE, DBUF, true>(st, g);
+}
+
 // forward-like products: the largest block tile that still yields >= 512 blocks
 template <int AMODE>
 void launch_fwd_like(hipStream_t st, GemmArgs& g) {
   auto blocks = [&](int bm, int bn) { return cdivl(g.M, bm) * cdivl(g.N, bn); };
   switch (gemm_variant()) {
-    case 0: launch_tile<128, 64, AMODE, true>(st, g); return;
     case 1: launch_tile<64, 64, AMODE, true>(st, g); return;
     case 2: launch_tile<64, 64, AMODE, false>(st, g); return;
-    case 3: launch_tile<32, 32, AMODE, true>(st, g); return;
     case 4: launch_tile<32, 32, AMODE, false>(st, g); return;
     case 5: launch_tile<128, 64, AMODE, false>(st, g); return;
     default: break;
   }
-  if (blocks(256, 128) >= 512) launch_tile<128, 64, AMODE, true>(st, g);
-  else if (blocks(128, 128) >= 256) launch_tile<64, 64, AMODE, true>(st, g);
-  else launch_tile<32, 32, AMODE, true>(st, g);
+  // measured on MI355X: more resident blocks beat bigger tiles (the loop is latency-bound),
+  // so the 128x128 tile with one LDS buffer (4 blocks per CU) is the default
+  if (blocks(128, 128) >= 256) launch_tile<64, 64, AMODE, false>(st, g);
+  else launch_tile<32, 32, AMODE, false>(st, g);
 }
 
 template <int BMODE>
@@ -510,7 +547,7 @@ void launch_wgrad(hipStream_t st, GemmArgs& g, float* G, float* ws, int taps) {
   g.k_per_split = cdivl(cdivl(g.K, splits), BK) * BK;
   splits = (int)cdivl(g.K, g.k_per_split);
   g.part = ws;
-  auto kern = gemm_bf16_kernel<WG_T, WG_T, OP_T, BMODE, E_PART, true>;
+  auto kern = gemm_bf16_kernel<WG_T, WG_T, OP_T, BMODE, E_PART, true, true>;
   constexpr size_t lds = lds_bytes<WG_T, WG_T, true>();
   static bool once = false;
   if (!once) {
