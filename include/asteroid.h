@@ -142,7 +142,7 @@ ast_status asteroid_stage_set_velocity(asteroid_stage* s, const float* host_flat
 ast_status asteroid_stage_get_velocity(asteroid_stage* s, float* host_flat);
 
 /* Bytes held, in the terms of the memory model Eq. (3): mod = parameters + accumulated
- * gradients (+ reduced-precision weight copies); opt = optimizer state (velocity);
+ * gradients (+ derived weight copies: bf16 layouts, packed pointwise-conv operands); opt = optimizer state (velocity);
  * act_per_mb = activation stash of one micro-batch (the stage holds K of them);
  * workspace = activation-gradient and reduction scratch, independent of K.
  * Any output pointer may be NULL. */

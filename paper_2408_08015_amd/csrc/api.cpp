@@ -2,6 +2,7 @@
 // 1F1B call discipline (Sec. 3.2), allocation in create, and the flat-vector accessors.
 #include <cstring>
 #include <new>
+#include <cstdlib>
 #include <string>
 #include <vector>
 
@@ -58,10 +59,18 @@ void free_stage(ast::Stage& s) {
   if (s.V) (void)hipFree(s.V);
   if (s.shadow) (void)hipFree(s.shadow);
   if (s.running) (void)hipFree(s.running);
+  if (s.wpack) (void)hipFree(s.wpack);
+  s.wpack = nullptr;
   if (s.ws) (void)hipFree(s.ws);
   for (char* p : s.slots)
     if (p) (void)hipFree(p);
   s.slots.clear();
+  for (hipEvent_t ev : s.fork_ev) (void)hipEventDestroy(ev);
+  s.fork_ev.clear();
+  if (s.join_ev) (void)hipEventDestroy(s.join_ev);
+  if (s.side) (void)hipStreamDestroy(s.side);
+  s.join_ev = nullptr;
+  s.side = nullptr;
   s.W = s.G = s.V = nullptr;
   s.shadow = nullptr;
   s.running = nullptr;
@@ -119,12 +128,26 @@ ast_status asteroid_stage_create(const ast_layer* layers, int32_t n_layers, cons
   if ((e = hipMalloc((void**)&s.V, pbytes)) != hipSuccess) return bail(e, "create: hipMalloc(V)");
   if (s.shadow_elems && (e = hipMalloc((void**)&s.shadow, s.shadow_elems * 2 + 16)) != hipSuccess)
     return bail(e, "create: hipMalloc(weight copies)");
+  if (s.wpack_floats && (e = hipMalloc((void**)&s.wpack, s.wpack_floats * sizeof(float))) != hipSuccess)
+    return bail(e, "create: hipMalloc(packed weights)");
   if (s.running_floats && (e = hipMalloc((void**)&s.running, s.running_floats * sizeof(float))) != hipSuccess)
     return bail(e, "create: hipMalloc(running stats)");
   if ((e = hipMalloc((void**)&s.ws, s.ws_bytes)) != hipSuccess) return bail(e, "create: hipMalloc(workspace)");
   s.slots.assign(cfg->K, nullptr);
   for (int k = 0; k < cfg->K; ++k)
     if ((e = hipMalloc((void**)&s.slots[k], s.slot_bytes)) != hipSuccess) return bail(e, "create: hipMalloc(stash)");
+  // Second stream (default priority) for the weight-gradient kernels; ASTEROID_SIDE_STREAM=0
+  // keeps everything on the caller's stream.
+  const char* side_env = getenv("ASTEROID_SIDE_STREAM");
+  if (!(side_env && side_env[0] == '0')) {
+    if ((e = hipStreamCreateWithFlags(&s.side, hipStreamNonBlocking)) != hipSuccess) return bail(e, "create: side stream");
+    if ((e = hipEventCreateWithFlags(&s.join_ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "create: event");
+    for (int i = 0; i < 128; ++i) {
+      hipEvent_t ev;
+      if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "create: event");
+      s.fork_ev.push_back(ev);
+    }
+  }
   if ((e = hipMemset(s.G, 0, pbytes)) != hipSuccess) return bail(e, "create: memset");
   if ((e = hipMemset(s.V, 0, pbytes)) != hipSuccess) return bail(e, "create: memset");
   if ((e = hipMemset(s.ws, 0, s.ws_bytes)) != hipSuccess) return bail(e, "create: memset");
@@ -253,7 +276,7 @@ ast_status asteroid_stage_memory(const asteroid_stage* h, size_t* mod, size_t* o
                                  size_t* workspace) {
   if (!h) return fail(AST_EINVAL, "memory: NULL stage");
   const ast::Stage& s = h->s;
-  if (mod) *mod = 2 * s.nparams * sizeof(float) + s.shadow_elems * 2;
+  if (mod) *mod = 2 * s.nparams * sizeof(float) + s.shadow_elems * 2 + s.wpack_floats * sizeof(float);
   if (opt) *opt = s.nparams * sizeof(float);
   if (act_per_mb) *act_per_mb = s.slot_bytes;
   if (workspace) *workspace = s.ws_bytes;

@@ -12,7 +12,7 @@ struct Ctx {
   Stage& s;
   char* slot;
   int final_act;
-  int launches = 0;
+  bool forked = false;
 };
 
 inline int final_act_of(const Stage& s) { return s.final_act; }
@@ -27,8 +27,23 @@ inline void* grad_ptr(Ctx& c, int id) {
   if (id == c.final_act && !c.s.loss_tail) return const_cast<void*>(c.s.cur_dy);  // id != 0 here
   return c.s.ws + c.s.acts[id].grad_off;
 }
-inline char* scratch(Ctx& c) { return c.s.ws + c.s.scratch_off; }
-inline float* scratch2(Ctx& c) { return reinterpret_cast<float*>(c.s.ws + c.s.scratch2_off); }
+inline char* scratch(Ctx& c, const Op& op) { return c.s.ws + c.s.scratch_off + op.sc_off; }
+// Stream for a weight-gradient kernel.  Nothing later in the same backward pass reads a
+// parameter gradient, so these kernels leave the dependency chain: they run on the stage's
+// second stream, ordered after all work enqueued so far on the main stream, and the pass
+// joins the two streams before it returns.  Kernels that accumulate into the same
+// parameter all run on that one stream, so the accumulation order stays fixed.
+// The hand-over between two hardware queues costs several microseconds, so only the bf16
+// GEMM-sized weight gradients take it; the fp32 ones (tens of microseconds each) stay put.
+inline hipStream_t fork_side(Ctx& c) {
+  Stage& s = c.s;
+  if (!s.side || !s.bf16) return s.stream;
+  hipEvent_t e = s.fork_ev[s.fork_i++ % s.fork_ev.size()];
+  (void)hipEventRecord(e, s.stream);
+  (void)hipStreamWaitEvent(s.side, e, 0);
+  c.forked = true;
+  return s.side;
+}
 inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 typedef const float* cf;
@@ -41,7 +56,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
   const int HW = I.h * I.w;
   switch (op.kind) {
     case OP_CONV_PW:
-      pw_conv_f32(st, s.W + op.w_off, op.cin, 1, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out),
+      pw_conv_f32(st, s.wpack + op.wp_off, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out),
                   op.has_bias ? s.W + op.b_off : nullptr, nullptr, I.n, op.cin, op.cout, HW);
       break;
     case OP_CONV_DW:
@@ -61,7 +76,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       float* aux = reinterpret_cast<float*>(c.slot + op.aux_off);
       bn_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, s.W + op.b_off,
                  op.skip >= 0 ? (cf)act_ptr(c, op.skip) : nullptr, (float*)act_ptr(c, op.out), aux, aux + 2 * I.c,
-                 s.running + op.run_off, reinterpret_cast<double*>(scratch(c)), I.n, I.c, HW, op.eps, op.act);
+                 s.running + op.run_off, reinterpret_cast<double*>(scratch(c, op)), I.n, I.c, HW, op.eps, op.act);
       break;
     }
     case OP_ACT:
@@ -131,50 +146,53 @@ void bwd_op(Ctx& c, const Op& op) {
   switch (op.kind) {
     case OP_CONV_PW: {
       cf g = (cf)grad_ptr(c, op.out);
+      hipStream_t sw = fork_side(c);
       if (gin)
-        pw_conv_f32(st, s.W + op.w_off, 1, op.cin, g, (float*)gin, nullptr,
+        pw_conv_f32(st, s.wpack + op.wp2_off, g, (float*)gin, nullptr,
                     op.dgrad_add >= 0 ? (cf)grad_ptr(c, op.dgrad_add) : nullptr, I.n, op.cout, op.cin, HW);
-      pw_wgrad_f32(st, g, (cf)act_ptr(c, op.in), reinterpret_cast<float*>(scratch(c)), s.G + op.w_off, I.n,
+      pw_wgrad_f32(sw, g, (cf)act_ptr(c, op.in), reinterpret_cast<float*>(scratch(c, op)), s.G + op.w_off, I.n,
                    op.cin, op.cout, HW);
-      if (op.has_bias) channel_sum_acc_f32(st, g, s.G + op.b_off, I.n, op.cout, HW);
+      if (op.has_bias) channel_sum_acc_f32(sw, g, s.G + op.b_off, I.n, op.cout, HW);
       break;
     }
     case OP_CONV_DW: {
       cf g = (cf)grad_ptr(c, op.out);
-      dw3x3_bwd_f32(st, g, (cf)act_ptr(c, op.in), s.W + op.w_off, (float*)gin, reinterpret_cast<float*>(scratch(c)),
+      dw3x3_bwd_f32(st, g, (cf)act_ptr(c, op.in), s.W + op.w_off, (float*)gin, reinterpret_cast<float*>(scratch(c, op)),
                     s.G + op.w_off, I.n, I.c, I.h, I.w, op.stride);
       break;
     }
     case OP_CONV_DIRECT: {
       cf g = (cf)grad_ptr(c, op.out);
       const Act& O = s.acts[op.out];
+      hipStream_t sw = fork_side(c);
       if (gin)
         conv_direct_dgrad_f32(st, g, s.W + op.w_off, (float*)gin, I.n, op.cin, I.h, I.w, op.cout, op.k,
                               op.stride, op.pad, op.groups);
-      conv_direct_wgrad_f32(st, g, (cf)act_ptr(c, op.in), s.G + op.w_off, I.n, op.cin, I.h, I.w, op.cout,
+      conv_direct_wgrad_f32(sw, g, (cf)act_ptr(c, op.in), s.G + op.w_off, I.n, op.cin, I.h, I.w, op.cout,
                             op.k, op.stride, op.pad, op.groups);
-      if (op.has_bias) channel_sum_acc_f32(st, g, s.G + op.b_off, I.n, op.cout, O.h * O.w);
+      if (op.has_bias) channel_sum_acc_f32(sw, g, s.G + op.b_off, I.n, op.cout, O.h * O.w);
       break;
     }
     case OP_CONV_IGEMM: {
       const Act& O = s.acts[op.out];
       cb g = (cb)grad_ptr(c, op.out);
-      char* sc = scratch(c);
+      char* sc = scratch(c, op);
       if (op.act) {  // mask by the ReLU output
         bf16_t* gm = reinterpret_cast<bf16_t*>(sc);
         act_bwd_bf16(st, g, (cb)act_ptr(c, op.out), gm, O.elems, op.act);
         g = gm;
         sc += align256(O.bytes);
       }
+      hipStream_t sw = fork_side(c);
       if (gin) conv_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin, I.n, I.h, I.w, op.cin, op.cout, op.k);
-      conv_bf16_wgrad(st, g, (cb)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr, sc,
+      conv_bf16_wgrad(sw, g, (cb)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr, sc,
                       I.n, I.h, I.w, op.cin, op.cout, op.k);
       break;
     }
     case OP_BN: {
       float* aux = reinterpret_cast<float*>(c.slot + op.aux_off);
       bn_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), aux, aux + 2 * I.c, s.W + op.w_off,
-                 (float*)gin, s.G + op.w_off, s.G + op.b_off, reinterpret_cast<double*>(scratch(c)), I.n, I.c, HW,
+                 (float*)gin, s.G + op.w_off, s.G + op.b_off, reinterpret_cast<double*>(scratch(c, op)), I.n, I.c, HW,
                  op.act);
       break;
     }
@@ -207,20 +225,22 @@ void bwd_op(Ctx& c, const Op& op) {
         const Act& O = s.acts[op.out];
         const size_t R = (size_t)I.n * I.h * I.w;
         cb g = (cb)grad_ptr(c, op.out);
-        char* sc = scratch(c);
+        char* sc = scratch(c, op);
         if (op.act == 3) {
           bf16_t* gp = reinterpret_cast<bf16_t*>(sc);
           act_bwd_bf16(st, g, (cb)act_ptr(c, op.skip), gp, O.elems, 3);
           g = gp;
           sc += align256(O.bytes);
         }
+        hipStream_t sw = fork_side(c);
         if (gin) linear_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin, R, op.cin, op.cout);
-        linear_bf16_wgrad(st, g, (cb)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr,
+        linear_bf16_wgrad(sw, g, (cb)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr,
                           sc, R, op.cin, op.cout);
       } else {
         cf g = (cf)grad_ptr(c, op.out);
+        hipStream_t sw = fork_side(c);
         if (gin) linear_dgrad_f32(st, g, s.W + op.w_off, (float*)gin, I.n, op.cin, op.cout);
-        linear_wgrad_f32(st, g, (cf)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr,
+        linear_wgrad_f32(sw, g, (cf)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr,
                          I.n, op.cin, op.cout);
       }
       break;
@@ -233,7 +253,7 @@ void bwd_op(Ctx& c, const Op& op) {
     case OP_LAYERNORM:
       layernorm_bwd_bf16(st, (cb)grad_ptr(c, op.out), (cb)act_ptr(c, op.in),
                          reinterpret_cast<float*>(c.slot + op.aux_off), s.W + op.w_off, (bf16_t*)gin,
-                         s.G + op.w_off, s.G + op.b_off, scratch(c), (size_t)I.n * I.h, I.c);
+                         s.G + op.w_off, s.G + op.b_off, scratch(c, op), (size_t)I.n * I.h, I.c);
       break;
     case OP_MHA: {
       const int D = op.cin;
@@ -245,17 +265,19 @@ void bwd_op(Ctx& c, const Op& op) {
       float* Gbq = Gq + (size_t)3 * D * D;
       float* Go = Gbq + 3 * D;
       float* Gbo = Go + (size_t)D * D;
-      char* sc = scratch(c);
+      char* sc = scratch(c, op);
       bf16_t* d_o = reinterpret_cast<bf16_t*>(sc);
       bf16_t* dqkv = d_o + R * D;
       float* dsum = reinterpret_cast<float*>(sc + align256(R * 4 * D * sizeof(bf16_t)));
       char* lw = reinterpret_cast<char*>(dsum) + align256(mha_bf16_ws_bytes(I.n, I.h, D, op.heads));
       cb g = (cb)grad_ptr(c, op.out);
+      hipStream_t sw = fork_side(c);
       linear_bf16_dgrad(st, g, s.shadow + op.sh2_off + (size_t)3 * D * D, d_o, R, D, D);
-      linear_bf16_wgrad(st, g, o, Go, Gbo, lw, R, D, D);
+      linear_bf16_wgrad(sw, g, o, Go, Gbo, lw, R, D, D);
       attention_bwd_bf16(st, qkv, o, d_o, lse, dqkv, dsum, I.n, I.h, D, op.heads);
+      sw = fork_side(c);
       if (gin) linear_bf16_dgrad(st, dqkv, s.shadow + op.sh2_off, (bf16_t*)gin, R, D, 3 * D);
-      linear_bf16_wgrad(st, dqkv, (cb)act_ptr(c, op.in), Gq, Gbq, lw, R, D, 3 * D);
+      linear_bf16_wgrad(sw, dqkv, (cb)act_ptr(c, op.in), Gq, Gbq, lw, R, D, 3 * D);
       break;
     }
   }
@@ -291,13 +313,21 @@ ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, std::strin
   s.cur_dy = dy;
   s.cur_dx = dx;
   for (int j = (int)s.ops.size() - 1; j >= 0; --j) bwd_op(c, s.ops[j]);
+  if (c.forked) {  // join: whatever follows on the main stream sees every gradient
+    (void)hipEventRecord(s.join_ev, s.side);
+    (void)hipStreamWaitEvent(s.stream, s.join_ev, 0);
+  }
   return check_launch(err, "backward");
 }
 
 ast_status refresh_shadow(Stage& s, std::string& err) {
-  if (!s.bf16) return AST_OK;
   for (const Op& op : s.ops) {
-    if (op.kind == OP_CONV_IGEMM) {
+    if (op.kind == OP_CONV_PW) {
+      pw_pack_f32(s.stream, s.W + op.w_off, op.cin, 1, s.wpack + op.wp_off, op.cout, op.cin);
+      pw_pack_f32(s.stream, s.W + op.w_off, 1, op.cin, s.wpack + op.wp2_off, op.cin, op.cout);
+    } else if (!s.bf16) {
+      continue;  // the remaining copies are bf16 layouts
+    } else if (op.kind == OP_CONV_IGEMM) {
       conv_weight_shadow_bf16(s.stream, s.W + op.w_off, s.shadow + op.sh_off, s.shadow + op.sh2_off, op.cout,
                               op.cin, op.k);
     } else if (op.kind == OP_LINEAR) {

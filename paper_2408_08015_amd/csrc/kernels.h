@@ -13,10 +13,13 @@ typedef unsigned short bf16_t;
 // ------------------------------------------------------------------ fp32, NCHW
 // Pointwise (1x1) convolution as a per-pixel matrix product on the fp32 matrix cores:
 //   Y[n][m][p] = sum_k A[m][k] * X[n][k][p] (+ bias[m]) (+ add[n][m][p])
-// A[m][k] = W[m*lda_m + k*lda_k], so the same kernel serves the forward pass
-// (A = W[Cout][Cin]) and the input gradient (A = W^T).
-void pw_conv_f32(hipStream_t st, const float* W, int lda_m, int lda_k, const float* X, float* Y,
-                 const float* bias, const float* add, int N, int Kdim, int Mdim, int HW);
+// A is given as a packed copy Wp (pw_pack_floats(Mdim, Kdim) floats, written by
+// pw_pack_f32 from A[m][k] = W[m*lda_m + k*lda_k]), so the same kernel serves the forward
+// pass (A = W[Cout][Cin]) and the input gradient (A = W^T).
+size_t pw_pack_floats(int Mdim, int Kdim);
+void pw_pack_f32(hipStream_t st, const float* W, int lda_m, int lda_k, float* Wp, int Mdim, int Kdim);
+void pw_conv_f32(hipStream_t st, const float* Wp, const float* X, float* Y, const float* bias,
+                 const float* add, int N, int Kdim, int Mdim, int HW);
 // Weight gradient of the pointwise convolution, split over pixel chunks:
 //   part[chunk][co][ci] = sum_{p in chunk} g[n][co][p] * x[n][ci][p];  then G += sum_chunk part.
 // `part` must hold pw_wgrad_f32_ws(N,Cin,Cout,HW) floats.

@@ -3,9 +3,10 @@
 // Pointwise (1x1) convolution = per-pixel matrix product on the fp32 matrix cores
 // (v_mfma_f32_32x32x2f32).  In NCHW a channel plane is contiguous, so pixels go on the MFMA
 // N dimension: lane l supplies B[k = l/32][pixel = l%32] with one coalesced global load,
-// the small weight matrix comes from LDS as A[m = l%32][k = l/32], and accumulator
-// register r of lane l is D[8*(r/4) + 4*(l/32) + r%4][l%32].  At these shapes the kernels
-// are HBM / latency bound, so the launch shapes are chosen for wavefront count first.
+// the small weight matrix is A[m = l%32][k = l/32], read from a copy packed in exactly that
+// lane order, and accumulator register r of lane l is D[8*(r/4) + 4*(l/32) + r%4][l%32].
+// At these shapes the kernels are HBM / latency bound, so the launch shapes are chosen for
+// wavefront count first.
 //
 // Depthwise 3x3: a block stages whole (n, c) planes (they are contiguous) with a zero halo
 // in LDS; the backward kernel produces the input gradient and the nine weight-gradient
@@ -21,20 +22,23 @@ static inline int conv_out(int H, int k, int stride, int pad) { return (H + 2 * 
 
 // ============================================================== pointwise conv (fwd / dgrad)
 // Block = 4 wavefronts; wavefront w owns pixels [128*bx + 32*w, +32) of the flattened
-// (n, p) index and NT 32-row tiles of output channels.  MFMA 32x32x2: lane l supplies
+// (n, p) index and one 32-row tile of output channels.  MFMA 32x32x2: lane l supplies
 // A[m = l%32][k = l/32] and B[k = l/32][q = l%32]; accumulator register r of lane l is
 // D[8*(r/4) + 4*(l/32) + r%4][l%32].
-template <int NT>
-__global__ __launch_bounds__(256) void pw_conv_f32_kernel(
-    const float* __restrict__ W, int lda_m, int lda_k, const float* __restrict__ X,
-    float* __restrict__ Y, const float* __restrict__ bias, const float* __restrict__ add, long NQ,
-    int HW, int Kdim, int Mdim) {
-  constexpr int KC = 32;
-  constexpr int MT = 32 * NT;
-  __shared__ float sW[KC][MT + 1];
+// The A operand comes from a packed copy of the weights (pw_pack_f32): for m-tile t and
+// k-group g (8 consecutive k), lane l = (m%32, h) finds the four values A[m][8g + 2e + h],
+// e = 0..3, as one 16-byte word at Wp[(t*KG + g)*64 + l]; out-of-range m and k are zero
+// there.  A wavefront therefore reads its operands with fully coalesced 16-byte loads
+// and needs neither LDS nor a barrier, and all loads of a pass are issued before its first
+// MFMA.  NCH = 32-channel chunks per pass.
+template <int NCH>
+__global__ __launch_bounds__(256) void pw_conv_f32_pk_kernel(
+    const float4* __restrict__ Wp, const float* __restrict__ X, float* __restrict__ Y,
+    const float* __restrict__ bias, const float* __restrict__ add, long NQ, int HW, int Kdim, int Mdim,
+    int KG) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int m_base = blockIdx.y * MT;
+  const int m_base = blockIdx.y * 32;
   const long q = (long)blockIdx.x * 128 + wave * 32 + col;
   const bool qv = q < NQ;
   long n = 0;
@@ -44,58 +48,43 @@ __global__ __launch_bounds__(256) void pw_conv_f32_kernel(
     p = (int)(q - n * HW);
   }
   const float* xq = X + (size_t)n * Kdim * HW + p;
-  floatx16 acc[NT];
+  const float4* wl = Wp + (size_t)blockIdx.y * KG * 64 + lane;
+  floatx16 acc;
 #pragma unroll
-  for (int t = 0; t < NT; ++t)
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int g0 = 0; g0 < KG; g0 += NCH * 4) {
+    float4 a[NCH * 4];
+    float b[NCH * 16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-
-  for (int k0 = 0; k0 < Kdim; k0 += KC) {
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < KC * MT; idx += 256) {
-      int kk, mm;
-      if (lda_k == 1) {  // k contiguous in memory
-        kk = idx % KC;
-        mm = idx / KC;
-      } else {
-        mm = idx % MT;
-        kk = idx / MT;
+    for (int g = 0; g < NCH * 4; ++g) {
+      const bool ok = g0 + g < KG;
+      a[g] = ok ? wl[(size_t)(g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int k = (g0 + g) * 8 + 2 * e + half;
+        b[4 * g + e] = (qv && k < Kdim) ? xq[(size_t)k * HW] : 0.f;
       }
-      int m = m_base + mm, k = k0 + kk;
-      float v = 0.f;
-      if (m < Mdim && k < Kdim) v = W[(size_t)m * lda_m + (size_t)k * lda_k];
-      sW[kk][mm] = v;
-    }
-    __syncthreads();
-    float b[KC / 2];
-#pragma unroll
-    for (int j = 0; j < KC / 2; ++j) {
-      int k = k0 + 2 * j + half;
-      b[j] = (qv && k < Kdim) ? xq[(size_t)k * HW] : 0.f;
     }
 #pragma unroll
-    for (int j = 0; j < KC / 2; ++j) {
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        float a = sW[2 * j + half][t * 32 + col];
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j], acc[t], 0, 0, 0);
-      }
+    for (int g = 0; g < NCH * 4; ++g) {
+      if (NCH > 1 && g0 + g >= KG) break;  // uniform: skip the empty tail of the last pass
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g].x, b[4 * g + 0], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g].y, b[4 * g + 1], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g].z, b[4 * g + 2], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g].w, b[4 * g + 3], acc, 0, 0, 0);
     }
   }
   if (!qv) return;
   float* yq = Y + (size_t)n * Mdim * HW + p;
   const float* aq = add ? add + (size_t)n * Mdim * HW + p : nullptr;
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      int m = m_base + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-      if (m < Mdim) {
-        float v = acc[t][r];
-        if (bias) v += bias[m];
-        if (aq) v += aq[(size_t)m * HW];
-        yq[(size_t)m * HW] = v;
-      }
+  for (int r = 0; r < 16; ++r) {
+    const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
+    if (m < Mdim) {
+      float v = acc[r];
+      if (bias) v += bias[m];
+      if (aq) v += aq[(size_t)m * HW];
+      yq[(size_t)m * HW] = v;
     }
   }
 }
@@ -103,13 +92,12 @@ __global__ __launch_bounds__(256) void pw_conv_f32_kernel(
 // Large images: a wavefront owns 128 pixels; every lane loads four consecutive pixels
 // (16 bytes) per input channel and feeds four MFMA column tiles (column j of tile t is
 // pixel 4j + t), so each output row is stored as 16 bytes per lane.  Four times the bytes
-// per memory instruction of the kernel above; needs HW % 4 == 0.
-__global__ __launch_bounds__(256) void pw_conv_f32_px4_kernel(
-    const float* __restrict__ W, int lda_m, int lda_k, const float* __restrict__ X,
-    float* __restrict__ Y, const float* __restrict__ bias, const float* __restrict__ add, long NQ,
-    int HW, int Kdim, int Mdim) {
-  constexpr int KC = 32;
-  __shared__ float sW[KC][33];
+// per memory instruction and a quarter of the weight traffic of the kernel above; needs
+// HW % 4 == 0.
+__global__ __launch_bounds__(256) void pw_conv_f32_pk4_kernel(
+    const float4* __restrict__ Wp, const float* __restrict__ X, float* __restrict__ Y,
+    const float* __restrict__ bias, const float* __restrict__ add, long NQ, int HW, int Kdim, int Mdim,
+    int KG) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int m_base = blockIdx.y * 32;
@@ -122,44 +110,36 @@ __global__ __launch_bounds__(256) void pw_conv_f32_px4_kernel(
     p = (int)(q - n * HW);
   }
   const float* xq = X + (size_t)n * Kdim * HW + p;
+  const float4* wl = Wp + (size_t)blockIdx.y * KG * 64 + lane;
   floatx16 acc[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-  for (int k0 = 0; k0 < Kdim; k0 += KC) {
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < KC * 32; idx += 256) {
-      int kk, mm;
-      if (lda_k == 1) {
-        kk = idx % KC;
-        mm = idx / KC;
-      } else {
-        mm = idx % 32;
-        kk = idx / 32;
+  for (int g0 = 0; g0 < KG; g0 += 4) {
+    float4 a[4];
+    float4 b[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const bool ok = g0 + g < KG;
+      a[g] = ok ? wl[(size_t)(g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int k = (g0 + g) * 8 + 2 * e + half;
+        b[4 * g + e] = (qv && k < Kdim) ? *reinterpret_cast<const float4*>(xq + (size_t)k * HW)
+                                        : make_float4(0.f, 0.f, 0.f, 0.f);
       }
-      int m = m_base + mm, k = k0 + kk;
-      float v = 0.f;
-      if (m < Mdim && k < Kdim) v = W[(size_t)m * lda_m + (size_t)k * lda_k];
-      sW[kk][mm] = v;
     }
-    __syncthreads();
 #pragma unroll
-    for (int jj = 0; jj < KC / 2; jj += 8) {
-      float4 b[8];
+    for (int g = 0; g < 4; ++g) {
+      if (g0 + g >= KG) break;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        int k = k0 + 2 * (jj + j) + half;
-        b[j] = (qv && k < Kdim) ? *reinterpret_cast<const float4*>(xq + (size_t)k * HW)
-                                : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float a = sW[2 * (jj + j) + half][col];
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j].x, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j].y, acc[1], 0, 0, 0);
-        acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j].z, acc[2], 0, 0, 0);
-        acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[j].w, acc[3], 0, 0, 0);
+      for (int e = 0; e < 4; ++e) {
+        const float av = e == 0 ? a[g].x : e == 1 ? a[g].y : e == 2 ? a[g].z : a[g].w;
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b[4 * g + e].x, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b[4 * g + e].y, acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b[4 * g + e].z, acc[2], 0, 0, 0);
+        acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b[4 * g + e].w, acc[3], 0, 0, 0);
       }
     }
   }
@@ -184,19 +164,44 @@ __global__ __launch_bounds__(256) void pw_conv_f32_px4_kernel(
   }
 }
 
-void pw_conv_f32(hipStream_t st, const float* W, int lda_m, int lda_k, const float* X, float* Y,
-                 const float* bias, const float* add, int N, int Kdim, int Mdim, int HW) {
-  long NQ = (long)N * HW;
-  int mt = cdiv(Mdim, 32);
-  // 128-pixel wavefronts when they still fill the chip (measured: 26 % faster at 56x56x32,
-  // slower when fewer than ~500 blocks remain)
-  if (HW % 4 == 0 && (long)cdiv(NQ, 512) * mt >= 512) {
-    KLAUNCH(pw_conv_f32_px4_kernel, dim3(cdiv(NQ, 512), mt), dim3(256), 0, st, W, lda_m, lda_k, X, Y, bias, add, NQ,
-            HW, Kdim, Mdim);
-    return;
+// Packed operand copy: Wp[((t*KG + g)*64 + l)*4 + e] = A[32t + l%32][8g + 2e + l/32], zero
+// outside Mdim x Kdim, with A[m][k] = W[m*lda_m + k*lda_k].
+__global__ void pw_pack_kernel(const float* __restrict__ W, int lda_m, int lda_k, float* __restrict__ Wp,
+                               int Mdim, int Kdim, int KG, size_t total) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int e = (int)(i & 3), l = (int)((i >> 2) & 63);
+  const size_t tg = i >> 8;
+  const int g = (int)(tg % KG), t = (int)(tg / KG);
+  const int m = 32 * t + (l & 31), k = 8 * g + 2 * e + (l >> 5);
+  Wp[i] = (m < Mdim && k < Kdim) ? W[(size_t)m * lda_m + (size_t)k * lda_k] : 0.f;
+}
+
+size_t pw_pack_floats(int Mdim, int Kdim) { return (size_t)cdiv(Mdim, 32) * cdiv(Kdim, 8) * 256; }
+
+void pw_pack_f32(hipStream_t st, const float* W, int lda_m, int lda_k, float* Wp, int Mdim, int Kdim) {
+  const size_t total = pw_pack_floats(Mdim, Kdim);
+  KLAUNCH(pw_pack_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, st, W, lda_m, lda_k, Wp, Mdim, Kdim,
+          cdiv(Kdim, 8), total);
+}
+
+void pw_conv_f32(hipStream_t st, const float* Wp, const float* X, float* Y, const float* bias, const float* add,
+                 int N, int Kdim, int Mdim, int HW) {
+  const long NQ = (long)N * HW;
+  const int mt = cdiv(Mdim, 32), KG = cdiv(Kdim, 8);
+  const float4* wp = reinterpret_cast<const float4*>(Wp);
+  // Measured on 32-sample micro-batches: 128-pixel wavefronts win from 56x56 images up,
+  // 32-pixel ones below (more wavefronts in flight matter more than bytes per instruction).
+  if (HW % 4 == 0 && NQ >= 65536) {
+    KLAUNCH(pw_conv_f32_pk4_kernel, dim3((unsigned)cdiv(NQ, 512), mt), dim3(256), 0, st, wp, X, Y, bias, add, NQ, HW,
+            Kdim, Mdim, KG);
+  } else if (Kdim > 32) {
+    KLAUNCH(pw_conv_f32_pk_kernel<2>, dim3((unsigned)cdiv(NQ, 128), mt), dim3(256), 0, st, wp, X, Y, bias, add, NQ, HW,
+            Kdim, Mdim, KG);
+  } else {
+    KLAUNCH(pw_conv_f32_pk_kernel<1>, dim3((unsigned)cdiv(NQ, 128), mt), dim3(256), 0, st, wp, X, Y, bias, add, NQ, HW,
+            Kdim, Mdim, KG);
   }
-  KLAUNCH(pw_conv_f32_kernel<1>, dim3(cdiv(NQ, 128), mt), dim3(256), 0, st, W, lda_m, lda_k, X, Y, bias, add, NQ, HW,
-          Kdim, Mdim);
 }
 
 // ============================================================== pointwise conv wgrad
@@ -520,6 +525,203 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
   }
 }
 
+// Stride-1 backward without LDS (W % 4 == 0, W <= 256): one wavefront per (n, c) plane.
+// Lane (s = l % SW, rg = l / SW) owns the four-pixel column strip s (SW = W/4 strips per row)
+// of the rows of row group rg and slides a three-row register window of g and x down them;
+// the columns left and right of a strip come from the neighbouring lanes, zeros at the
+// image border.  Per row a lane issues one 16-byte load of g and of x (one row ahead of
+// use) and one 16-byte store of dx; the nine weight-gradient sums stay in registers and
+// are reduced over the wavefront at the end.
+struct DwRow { float v[6]; };  // v[0] = column 4s-1, v[1..4] = the strip, v[5] = column 4s+4
+__device__ __forceinline__ DwRow dw_make_row(float4 c, int s, int SW) {
+  DwRow r;
+  const float left = __shfl_up(c.w, 1, 64), right = __shfl_down(c.x, 1, 64);
+  r.v[0] = s == 0 ? 0.f : left;
+  r.v[1] = c.x; r.v[2] = c.y; r.v[3] = c.z; r.v[4] = c.w;
+  r.v[5] = s == SW - 1 ? 0.f : right;
+  return r;
+}
+__global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __restrict__ g,
+                                                               const float* __restrict__ x,
+                                                               const float* __restrict__ w, float* __restrict__ dx,
+                                                               float* __restrict__ part, int NC, int C, int H,
+                                                               int W, int RPG) {
+  const int lane = threadIdx.x & 63;
+  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (plane >= NC) return;  // whole wavefront
+  const int SW = W >> 2;
+  const int rg = lane / SW, s = lane - rg * SW;
+  const int r0 = rg * RPG;
+  const int r1 = min(r0 + RPG, H);  // lanes past the last group: r0 >= H, no rows
+  const float* gp = g + (size_t)plane * H * W + 4 * s;
+  const float* xp = x + (size_t)plane * H * W + 4 * s;
+  float* dp = dx ? dx + (size_t)plane * H * W + 4 * s : nullptr;
+  float wk[9];
+  const float* wc = w + (size_t)(plane % C) * 9;
+#pragma unroll
+  for (int k = 0; k < 9; ++k) wk[k] = wc[k];
+  const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  // a row is readable by this lane if it lies in the image and the lane has rows at all
+  const bool has = r0 < H;
+  auto ld = [&](const float* base, int row) -> float4 {
+    return (has && row >= 0 && row < H) ? *reinterpret_cast<const float4*>(base + (size_t)row * W) : z4;
+  };
+  DwRow gm = dw_make_row(ld(gp, r0 - 1), s, SW), xm = dw_make_row(ld(xp, r0 - 1), s, SW);
+  DwRow gc = dw_make_row(ld(gp, r0), s, SW), xc = dw_make_row(ld(xp, r0), s, SW);
+  float4 gn = ld(gp, r0 + 1), xn = ld(xp, r0 + 1);
+  float acc[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) acc[k] = 0.f;
+  for (int i = 0; i < RPG; ++i) {  // uniform trip count: the lane exchanges need every lane
+    const int a = r0 + i;
+    const DwRow gq = dw_make_row(gn, s, SW), xq = dw_make_row(xn, s, SW);
+    // past its last row a lane must not see the next group's rows as its own window
+    gn = (a + 2 <= r1) ? ld(gp, a + 2) : z4;
+    xn = (a + 2 <= r1) ? ld(xp, a + 2) : z4;
+    if (a < r1) {
+      if (dp) {
+        float o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float v = 0.f;
+#pragma unroll
+          for (int q = 0; q < 3; ++q) {  // dx[a][b] = sum_{u,q} w[u][q] g[a-u+1][b-q+1]
+            v += wk[0 * 3 + q] * gq.v[j + 2 - q];
+            v += wk[1 * 3 + q] * gc.v[j + 2 - q];
+            v += wk[2 * 3 + q] * gm.v[j + 2 - q];
+          }
+          o[j] = v;
+        }
+        *reinterpret_cast<float4*>(dp + (size_t)a * W) = make_float4(o[0], o[1], o[2], o[3]);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {  // dW[u][q] += g[a][b] x[a+u-1][b+q-1]
+        const float gv = gc.v[j + 1];
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+          acc[0 * 3 + q] += gv * xm.v[j + q];
+          acc[1 * 3 + q] += gv * xc.v[j + q];
+          acc[2 * 3 + q] += gv * xq.v[j + q];
+        }
+      }
+    }
+    gm = gc; gc = gq;
+    xm = xc; xc = xq;
+  }
+#pragma unroll
+  for (int k = 0; k < 9; ++k) acc[k] = wave_sum(acc[k]);
+  if (lane == 0)
+#pragma unroll
+    for (int k = 0; k < 9; ++k) part[(size_t)plane * 9 + k] = acc[k];
+}
+
+// Stride-2 counterpart (W % 4 == 0, H even): lane (s, rg) owns input columns 4s..4s+3 =
+// output columns 2s, 2s+1, and per step one output row i = two input rows 2i, 2i+1.
+// y[i][j] = sum_{u,q} w[u][q] x[2i+u-1][2j+q-1], so an even input row/column meets only the
+// centre tap and an odd one the two outer taps of the neighbouring outputs.
+struct DwG2 { float v[3]; };   // output columns 2s, 2s+1, 2s+2
+struct DwX2 { float v[5]; };   // input columns 4s-1 .. 4s+3
+__device__ __forceinline__ DwG2 dw_make_g2(float2 c, int s, int SW) {
+  DwG2 r;
+  const float right = __shfl_down(c.x, 1, 64);
+  r.v[0] = c.x; r.v[1] = c.y;
+  r.v[2] = s == SW - 1 ? 0.f : right;
+  return r;
+}
+__device__ __forceinline__ DwX2 dw_make_x2(float4 c, int s) {
+  DwX2 r;
+  const float left = __shfl_up(c.w, 1, 64);
+  r.v[0] = s == 0 ? 0.f : left;
+  r.v[1] = c.x; r.v[2] = c.y; r.v[3] = c.z; r.v[4] = c.w;
+  return r;
+}
+// one input row of dx from the output-gradient rows that reach it through kernel rows wa / wb
+__device__ __forceinline__ float4 dw_dx_row2(const float* wa, const DwG2& ga, const float* wb, const DwG2& gb,
+                                             bool two) {
+  float4 o;
+  o.x = wa[1] * ga.v[0];
+  o.y = wa[0] * ga.v[1] + wa[2] * ga.v[0];
+  o.z = wa[1] * ga.v[1];
+  o.w = wa[0] * ga.v[2] + wa[2] * ga.v[1];
+  if (two) {
+    o.x += wb[1] * gb.v[0];
+    o.y += wb[0] * gb.v[1] + wb[2] * gb.v[0];
+    o.z += wb[1] * gb.v[1];
+    o.w += wb[0] * gb.v[2] + wb[2] * gb.v[1];
+  }
+  return o;
+}
+__global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __restrict__ g,
+                                                               const float* __restrict__ x,
+                                                               const float* __restrict__ w, float* __restrict__ dx,
+                                                               float* __restrict__ part, int NC, int C, int H,
+                                                               int W, int RPG) {
+  const int lane = threadIdx.x & 63;
+  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (plane >= NC) return;  // whole wavefront
+  const int SW = W >> 2, Ho = H >> 1, Wo = W >> 1;
+  const int rg = lane / SW, s = lane - rg * SW;
+  const int r0 = rg * RPG;            // output rows [r0, r1)
+  const int r1 = min(r0 + RPG, Ho);
+  const bool has = r0 < Ho;
+  const float* gp = g + (size_t)plane * Ho * Wo + 2 * s;
+  const float* xp = x + (size_t)plane * H * W + 4 * s;
+  float* dp = dx ? dx + (size_t)plane * H * W + 4 * s : nullptr;
+  float wk[9];
+  const float* wc = w + (size_t)(plane % C) * 9;
+#pragma unroll
+  for (int k = 0; k < 9; ++k) wk[k] = wc[k];
+  const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float2 z2 = make_float2(0.f, 0.f);
+  auto ldx = [&](int row) -> float4 {
+    return (has && row >= 0 && row < H) ? *reinterpret_cast<const float4*>(xp + (size_t)row * W) : z4;
+  };
+  auto ldg = [&](int row) -> float2 {
+    return (has && row >= 0 && row < Ho) ? *reinterpret_cast<const float2*>(gp + (size_t)row * Wo) : z2;
+  };
+  DwX2 xm = dw_make_x2(ldx(2 * r0 - 1), s);
+  DwG2 gc = dw_make_g2(ldg(r0), s, SW);
+  float4 xn0 = ldx(2 * r0), xn1 = ldx(2 * r0 + 1);
+  float2 gn = ldg(r0 + 1);
+  float acc[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) acc[k] = 0.f;
+  for (int it = 0; it < RPG; ++it) {  // uniform trip count: the lane exchanges need every lane
+    const int i = r0 + it;
+    const DwX2 x0 = dw_make_x2(xn0, s), x1 = dw_make_x2(xn1, s);
+    const DwG2 gq = dw_make_g2(gn, s, SW);
+    const bool more = i + 1 < r1;
+    xn0 = more ? ldx(2 * i + 2) : z4;
+    xn1 = more ? ldx(2 * i + 3) : z4;
+    gn = more ? ldg(i + 2) : z2;
+    if (i < r1) {
+      if (dp) {
+        // input row 2i: centre kernel row of output row i; row 2i+1: kernel row 0 of output
+        // row i+1 and kernel row 2 of output row i
+        *reinterpret_cast<float4*>(dp + (size_t)(2 * i) * W) = dw_dx_row2(wk + 3, gc, wk + 3, gc, false);
+        *reinterpret_cast<float4*>(dp + (size_t)(2 * i + 1) * W) = dw_dx_row2(wk + 0, gq, wk + 6, gc, true);
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {  // dW[u][q] += g[i][2s+j] x[2i+u-1][4s+2j+q-1]
+        const float gv = gc.v[j];
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+          acc[0 * 3 + q] += gv * xm.v[2 * j + q];
+          acc[1 * 3 + q] += gv * x0.v[2 * j + q];
+          acc[2 * 3 + q] += gv * x1.v[2 * j + q];
+        }
+      }
+    }
+    xm = x1;
+    gc = gq;
+  }
+#pragma unroll
+  for (int k = 0; k < 9; ++k) acc[k] = wave_sum(acc[k]);
+  if (lane == 0)
+#pragma unroll
+    for (int k = 0; k < 9; ++k) part[(size_t)plane * 9 + k] = acc[k];
+}
+
 // G[c][t] += sum_n part[n][c][t]: eight sample lanes per output, fixed butterfly order
 __global__ __launch_bounds__(256) void dw3x3_wgrad_final_kernel(const float* __restrict__ part,
                                                                 float* __restrict__ G, int N, int C) {
@@ -552,6 +754,20 @@ void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int
 size_t dw3x3_bwd_f32_ws(int N, int C) { return (size_t)N * C * 9; }
 void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part,
                    float* G, int N, int C, int H, int W, int stride) {
+  if (stride == 1 && W % 4 == 0 && W <= 256) {
+    const int groups = 64 / (W / 4);
+    KLAUNCH(dw3x3_bwd_s1_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
+            cdiv(H, groups));
+    KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
+    return;
+  }
+  if (stride == 2 && W % 4 == 0 && H % 2 == 0 && W <= 256) {
+    const int groups = 64 / (W / 4);
+    KLAUNCH(dw3x3_bwd_s2_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
+            cdiv(H / 2, groups));
+    KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
+    return;
+  }
   DwGeom gm = dw_geom(N, C, H, W, stride);
   size_t lds = ((size_t)gm.ppb * ((H + 2) * (W + 2) + (gm.Ho + 2) * (gm.Wo + 2) + 9) + 36) * sizeof(float);
   (void)hipFuncSetAttribute((const void*)dw3x3_bwd_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

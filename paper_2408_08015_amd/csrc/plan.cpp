@@ -220,6 +220,15 @@ ast_status build_plan(Stage& s, std::string& err) {
   s.nparams = poff;
   s.running_floats = run;
   s.shadow_elems = shadow;
+  // fp32 pointwise convs read their weights from packed copies: A = W for the forward
+  // product, A = W^T for the input gradient.
+  size_t wpk = 0;
+  for (Op& op : s.ops)
+    if (op.kind == OP_CONV_PW) {
+      op.wp_off = wpk; wpk += pw_pack_floats(op.cout, op.cin);
+      op.wp2_off = wpk; wpk += pw_pack_floats(op.cin, op.cout);
+    }
+  s.wpack_floats = wpk;
 
   // Fuse the skip-gradient add of a residual block into the input-gradient kernel of the
   // pointwise conv that opens the block: dx = W^T g + g_skip.
@@ -264,17 +273,17 @@ ast_status build_plan(Stage& s, std::string& err) {
     if (op.kind == OP_RES_ADD) s.acts[op.in].grad_alias = op.out;
   s.grad_bytes = goff;
 
-  // Scratch: reduction partials (max over ops) and small coefficient vectors.
-  size_t sc = 0, sc2 = 0;
-  for (const Op& op : s.ops) {
+  // Scratch: one private region per op (masked upstream gradients, reduction partials), so
+  // that kernels of different ops may overlap on two streams without sharing a buffer.
+  size_t sc = 0;
+  for (Op& op : s.ops) {
     const Act& I = s.acts[op.in];
-    size_t need = 0, need2 = 0;
+    size_t need = 0;
     switch (op.kind) {
       case OP_CONV_PW: need = pw_wgrad_f32_ws(I.n, op.cin, op.cout, I.h * I.w) * sizeof(float); break;
       case OP_CONV_DW: need = dw3x3_bwd_f32_ws(I.n, I.c) * sizeof(float); break;
       case OP_BN:
         need = bn_ws_doubles(I.c, (size_t)I.n * I.h * I.w) * sizeof(double);
-        need2 = 3 * sizeof(float) * I.c;
         break;
       case OP_CONV_IGEMM:  // masked upstream gradient + split-K partials
         need = align_up(s.acts[op.out].bytes, 256) + conv_bf16_ws_bytes(I.n, I.h, I.w, op.cin, op.cout, op.k);
@@ -291,14 +300,12 @@ ast_status build_plan(Stage& s, std::string& err) {
         break;
       default: break;
     }
-    sc = std::max(sc, need);
-    sc2 = std::max(sc2, need2);
+    op.sc_off = sc;
+    sc += align_up(need, 256);
   }
   s.scratch_off = align_up(goff, 256);
   s.scratch_bytes = align_up(sc, 256);
-  s.scratch2_off = s.scratch_off + s.scratch_bytes;
-  s.scratch2_bytes = align_up(sc2, 256);
-  s.ws_bytes = s.scratch2_off + s.scratch2_bytes + 256;
+  s.ws_bytes = s.scratch_off + s.scratch_bytes + 256;
   return AST_OK;
 }
 

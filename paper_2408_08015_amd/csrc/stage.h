@@ -57,6 +57,8 @@ struct Op {
   int dgrad_add = -1;                 // pointwise conv: add this activation's gradient to dx
   bool noop_bwd = false;              // RES_BEGIN whose add was fused into the next dgrad
   size_t sh_off = 0, sh2_off = 0;     // bf16 weight copies (elements) in the shadow arena
+  size_t wp_off = 0, wp2_off = 0;     // fp32 pointwise conv: packed forward / dgrad operands (floats)
+  size_t sc_off = 0;                  // this op's private scratch region (bytes past scratch_off)
 };
 
 struct Stage {
@@ -77,6 +79,8 @@ struct Stage {
   float *W = nullptr, *G = nullptr, *V = nullptr;  // flat arenas (device)
   unsigned short* shadow = nullptr;                // bf16 weight copies
   size_t shadow_elems = 0;
+  float* wpack = nullptr;  // packed pointwise-conv operands (fp32 stages)
+  size_t wpack_floats = 0;
   float* running = nullptr;  // BatchNorm running mean/var
   size_t running_floats = 0;
 
@@ -84,8 +88,14 @@ struct Stage {
   std::vector<char*> slots;  // K stash slots
   char* ws = nullptr;        // workspace: activation gradients + scratch
   size_t ws_bytes = 0, grad_bytes = 0;
-  size_t scratch_off = 0, scratch_bytes = 0;  // reduction partials
-  size_t scratch2_off = 0, scratch2_bytes = 0;  // small coefficient vectors
+  size_t scratch_off = 0, scratch_bytes = 0;  // per-op scratch regions (masked gradients, partials)
+
+  // Second stream for the weight-gradient kernels, which no later kernel of the same
+  // backward pass depends on (NULL: everything runs on `stream`).
+  hipStream_t side = nullptr;
+  std::vector<hipEvent_t> fork_ev;
+  hipEvent_t join_ev = nullptr;
+  unsigned fork_i = 0;
 
   // 1F1B state
   int next_fwd = 0, next_bwd = 0;

@@ -40,7 +40,7 @@ def test_kp_matches_the_papers_example(A):
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
 def test_plan_memory_follows_eq3(A, name):
     """Eq. (3): Mem = MOD + OPT + K * ACT.  MOD = fp32 params + fp32 accumulated gradients
-    (+ bf16 weight copies), OPT = fp32 velocity, ACT independent of K and M."""
+    (+ derived weight copies), OPT = fp32 velocity, ACT independent of K and M."""
     cfg = get_config(name)
     n = gen.num_params(cfg.layers)
     args = (cfg.layers, cfg.B, cfg.M)
@@ -50,7 +50,8 @@ def test_plan_memory_follows_eq3(A, name):
     mod, opt, act, ws = m1
     assert opt == 4 * n
     if cfg.dtype == "f32":
-        assert mod == 8 * n
+        # two packed layouts of each pointwise-conv matrix, padded to 32 x 8 tiles
+        assert 8 * n <= mod <= 8 * n + 2 * 4 * 2 * n + 65536
     else:
         assert mod > 8 * n and mod <= 8 * n + 2 * 2 * n + 64   # two bf16 layouts of each matrix
     # the stash holds at least the stage input and every conv / linear input

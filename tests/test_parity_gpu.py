@@ -80,7 +80,9 @@ def test_pointwise_conv_with_bias(A):
     check(one([conv(24, 40, 1, bias=True)], (24, 12, 12)))
 
 
-@pytest.mark.parametrize("c,hw,stride,B", [(144, 56, 2, 2), (192, 28, 1, 3), (32, 7, 1, 2), (96, 15, 2, 2), (8, 1, 1, 2), (8, 2, 2, 3)])
+@pytest.mark.parametrize("c,hw,stride,B", [(144, 56, 2, 2), (192, 28, 1, 3), (32, 7, 1, 2), (96, 15, 2, 2), (8, 1, 1, 2), (8, 2, 2, 3),
+                                          (40, 56, 1, 2), (18, 12, 1, 3), (5, 4, 1, 2), (6, 112, 1, 1),
+                                          (10, 12, 2, 2), (7, 4, 2, 3), (6, 112, 2, 1)])
 def test_depthwise_conv(A, c, hw, stride, B):
     check(one([conv(c, c, 3, stride, 1, groups=c)], (c, hw, hw), B=B, name="dw%d" % c))
 
