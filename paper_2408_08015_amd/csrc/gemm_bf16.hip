@@ -7,10 +7,10 @@
 //
 // Block = 256 threads = 2 x 2 wavefronts; each wavefront owns a WTM x WTN tile made of
 // 32x32 MFMA tiles; K advances 64 per step.  Both operands sit in LDS as [row][k] with k
-// contiguous (row stride 72 elements = 144 bytes, which spreads the 16-byte operand reads
-// of 8 consecutive lanes over all banks), double-buffered: the global loads of K-tile t+1
-// are issued before the MFMAs of tile t and written to the other buffer after them, one
-// barrier per tile.  MFMA 32x32x16: lane l supplies A[l%32][8*(l/32) .. +7] and B likewise;
+// contiguous, rows and 16-byte chunks permuted so that operand reads and staging writes
+// are free of bank conflicts (see lds_off).  The global loads of K-tile t+1 are issued
+// before the MFMAs of tile t; with two LDS buffers they are written to the other buffer
+// after them (one barrier per tile), with one buffer at the top of the next step.  MFMA 32x32x16: lane l supplies A[l%32][8*(l/32) .. +7] and B likewise;
 // accumulator register r of lane l is D[8*(r/4) + 4*(l/32) + r%4][l%32].
 // Operands stored with the contraction index strided (weight gradients) are transposed in
 // registers (4 x 8 blocks) on their way into LDS.  The bf16 output tile goes through LDS
@@ -26,7 +26,7 @@ namespace ast {
 namespace {
 
 constexpr int BK = 64;
-constexpr int LDS_STRIDE = 72;  // elements per LDS row
+constexpr int LDS_STRIDE = 64;  // elements per LDS row (= BK: rows are not padded)
 
 enum { A_ROW = 0, A_IM2COL = 1, OP_T = 2, B_ROW = 0, B_T_SHIFT = 3 };
 enum { E_BF16 = 0, E_PART = 1 };
@@ -48,14 +48,32 @@ struct GemmArgs {
   const float* bias;
   int act;
   int tiles_n;         // number of tiles along N (blockIdx.x = tile_m * tiles_n + tile_n)
+  unsigned a_bytes, b_bytes;  // extents of the operands (below 2^31): range of the buffer loads
 };
 
-// Element offset of 16-byte chunk c16 (0..7) of LDS row `row`.  Chunks are XOR-swizzled with
-// bits 3..5 of the row so that the transposed staging of the weight-gradient operands
-// (lanes write rows 8 apart at the same K offset) spreads over the banks instead of piling
-// 16 lanes on one; reads and row-mode writes keep their conflict-free pattern.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// 16-byte load through a buffer descriptor: an offset at or beyond the extent returns zeros
+// (the hardware's range check), so padding and ragged edges need neither a branch nor a select.
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+
+// Element offset of 16-byte chunk c16 (0..7) of LDS row `row`.  The LDS has 64 banks of
+// 4 bytes; a 16-byte operand read is served 16 lanes at a time, an 8-byte write 32 lanes at
+// a time, and either runs at full rate only if those lanes cover all 64 banks once.  Rows
+// are 128 bytes (no padding), two rows per bank sweep, with
+//   physical row = row with bits 0 and 3 exchanged,   chunk ^= (row & 7) ^ ((row >> 4) & 7):
+// the MFMA operand reads (16 consecutive rows, one chunk) then split 8 / 8 over the two
+// halves of a sweep with 8 distinct chunks each, and so do the transposed writes of the
+// weight-gradient operands (16 rows 8 apart, one chunk).  Measured on MI355X: 210 B/clk/CU
+// for the reads against 80 for a 144-byte row stride with chunk ^= row >> 3.
 __device__ __forceinline__ int lds_off(int row, int c16) {
-  return row * LDS_STRIDE + ((c16 ^ ((row >> 3) & 7)) << 3);
+  const int prow = (row & ~9) | ((row & 1) << 3) | ((row >> 3) & 1);
+  return prow * LDS_STRIDE + ((c16 ^ (row & 7) ^ ((row >> 4) & 7)) << 3);
 }
 
 __device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
@@ -138,22 +156,66 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   }
   // implicit GEMM with C % 64 == 0: the tap and channel offset of the current K-tile, kept as
   // loop-carried uniform state (no division inside the loop)
-  int cur_tap = 0, cur_ci = 0;
-  if (ROWMODE && AMODE == A_IM2COL && FASTC) {
-    cur_tap = (int)(kbeg / g.C);
-    cur_ci = (int)(kbeg - (long)cur_tap * g.C);
+  // Row mode with a tile-uniform tap (plain rows, or C % 64 == 0): buffer loads.  Per slot the
+  // byte offset of the row's own data (the extent = "out of range" for rows past the edge)
+  // and, for the implicit GEMM, the set of taps whose shifted pixel lies inside the image.
+  constexpr bool BUFPATH = ROWMODE && (AMODE == A_ROW || FASTC);
+  unsigned a_voff[BUFPATH ? NA : 1], a_taps[BUFPATH ? NA : 1], b_voff[BUFPATH ? NB : 1];
+  const __amdgpu_buffer_rsrc_t rsrcA = make_rsrc(g.A, g.a_bytes), rsrcB = make_rsrc(g.B, g.b_bytes);
+  if (BUFPATH) {
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+      a_voff[j] = g.a_bytes;
+      a_taps[j] = 0;
+      if (a_yx[j] >= 0) {
+        a_voff[j] = (unsigned)(a_off[j] + (AMODE == A_IM2COL ? kc * 8 : 0)) * 2u;
+        if (AMODE == A_IM2COL && g.ksize == 3) {
+          const int y = a_yx[j] >> 16, x = a_yx[j] & 0xffff;
+          for (int tp = 0; tp < 9; ++tp) {
+            const int iy = y + tp / 3 - 1, ix = x + tp % 3 - 1;
+            if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W) a_taps[j] |= 1u << tp;
+          }
+        } else {
+          a_taps[j] = 0xffffffffu;
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) b_voff[j] = b_ok[j] ? (unsigned)b_off[j] * 2u : g.b_bytes;
   }
+  // The K-tiles are visited tap-fastest: the nine taps of one 64-channel slice follow each
+  // other, so consecutive tiles re-read the same pixels shifted by one (the 128-byte line
+  // of a pixel's slice loaded for row m under one tap is the line of row m-1 under the next)
+  // and mostly hit the CU's own L1 instead of the L2.  These launches are never split over K.
+  int cur_tap = 0, cur_ci = 0;
   // shifted operand of the conv weight gradient: (y, x) of the first pixel row of each B task
   int t_y[(!ROWMODE && BMODE == B_T_SHIFT) ? NTASK : 1], t_x[(!ROWMODE && BMODE == B_T_SHIFT) ? NTASK : 1];
-  if (!ROWMODE && BMODE == B_T_SHIFT) {
+  // transposed mode, per task: byte offset of its first row in the current K-tile (the tap
+  // shift of the conv operand folded in), column validity, rows left before kend
+  static_assert(ROWMODE || TASKS_A % 256 == 0, "a task slot must hold one operand only");
+  unsigned t_off[ROWMODE ? 1 : NTASK];
+  bool t_cv[ROWMODE ? 1 : NTASK];
+  int t_rem[ROWMODE ? 1 : NTASK];
+  if (!ROWMODE) {
     const int HWi = g.H * g.W;
+    const int sh = (BMODE == B_T_SHIFT && g.ksize == 3) ? (tap / 3 - 1) * g.W + tap % 3 - 1 : 0;
 #pragma unroll
     for (int j = 0; j < NTASK; ++j) {
-      int t = tid + 256 * j;
-      int kq = t >= TASKS_A ? (t - TASKS_A) / (BN / 8) : 0;
-      int rem = (int)((kbeg + kq * 4) % HWi);
-      t_y[j] = rem / g.W;
-      t_x[j] = rem - t_y[j] * g.W;
+      const int t = tid + 256 * j;
+      const bool isA = t < TASKS_A;
+      const int tt = isA ? t : t - TASKS_A;
+      const int per = (isA ? BM : BN) / 8;
+      const int kq = tt / per, mc = tt - kq * per;
+      const long col = (isA ? m0 : n0) + mc * 8;
+      t_cv[j] = col < (isA ? g.M : g.N);
+      t_rem[j] = (int)(kend - kbeg) - kq * 4;
+      const long row = kbeg + kq * 4 + (isA ? 0 : sh);
+      t_off[j] = (unsigned)((row * (isA ? g.lda : g.ldb) + col) * 2);
+      if (BMODE == B_T_SHIFT) {
+        int rem = (int)((kbeg + kq * 4) % HWi);
+        t_y[j] = rem / g.W;
+        t_x[j] = rem - t_y[j] * g.W;
+      }
     }
   }
 
@@ -162,17 +224,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   // loads of a tile issue back to back.
   auto load_tile = [&](int kt) {
     const long k0 = kbeg + (long)kt * BK;
-    if (ROWMODE) {
+    if (BUFPATH) {
+      const bool kv = k0 + kc * 8 < kend;
+      unsigned tapbit = 1u, da, db;
+      if (AMODE == A_IM2COL) {
+        const int dy = g.ksize == 3 ? cur_tap / 3 - 1 : 0, dx = g.ksize == 3 ? cur_tap - (cur_tap / 3) * 3 - 1 : 0;
+        tapbit = 1u << cur_tap;
+        da = (unsigned)(((dy * g.W + dx) * g.C + cur_ci) * 2);  // may be "negative": wraps back in the sum
+        db = (unsigned)((cur_tap * g.C + cur_ci) * 2);
+        if (++cur_tap >= g.ksize * g.ksize) { cur_tap = 0; cur_ci += BK; }
+      } else {
+        da = db = (unsigned)k0 * 2u;
+      }
+#pragma unroll
+      for (int j = 0; j < NA; ++j)
+        rg[j] = buf_load16(rsrcA, (kv && (a_taps[j] & tapbit)) ? a_voff[j] + da : g.a_bytes);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) rg[NA + j] = buf_load16(rsrcB, kv ? b_voff[j] + db : g.b_bytes);
+    } else if (ROWMODE) {
       const long k = k0 + kc * 8;
       const bool kv = k < kend;
+      long kb = k0;  // K offset of the tile in the B rows
       int toff = 0, dy = 0, dx = 0;
       if (AMODE == A_IM2COL) {
         int t, ci;
         if (FASTC) {  // uniform over the tile; advanced incrementally
           t = cur_tap;
           ci = cur_ci + kc * 8;
-          cur_ci += BK;
-          if (cur_ci >= g.C) { cur_ci = 0; ++cur_tap; }
+          kb = (long)cur_tap * g.C + cur_ci;
+          if (++cur_tap >= g.ksize * g.ksize) { cur_tap = 0; cur_ci += BK; }
         } else {
           t = (int)(k / g.C);
           ci = (int)(k - (long)t * g.C);
@@ -198,48 +278,43 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
         const bool ok = b_ok[j] && kv;
-        uint4 v = *reinterpret_cast<const uint4*>(g.B + (ok ? b_off[j] + k0 : 0));
+        uint4 v = *reinterpret_cast<const uint4*>(g.B + (ok ? b_off[j] + kb : 0));
         rg[NA + j] = ok ? v : make_uint4(0, 0, 0, 0);
       }
     } else {
+      (void)k0;
 #pragma unroll
       for (int j = 0; j < NTASK; ++j) {
-        int t = tid + 256 * j;
-        const bool isA = t < TASKS_A;
-        int tt = isA ? t : t - TASKS_A;
-        const int per = (isA ? BM : BN) / 8;
-        int kq = tt / per, mc = tt - kq * per;
-        long col = (isA ? m0 : n0) + mc * 8;
-        const bool cv = col < (isA ? g.M : g.N);
-        int y = 0, x = 0;
-        if (BMODE == B_T_SHIFT && !isA) { y = t_y[j]; x = t_x[j]; }
-        const int dy = (BMODE == B_T_SHIFT && g.ksize == 3) ? tap / 3 - 1 : 0;
-        const int dx = (BMODE == B_T_SHIFT && g.ksize == 3) ? tap % 3 - 1 : 0;
+        const bool isA = tid + 256 * j < TASKS_A;  // uniform: TASKS_A is a multiple of the block size
+        const unsigned ld2 = (unsigned)(isA ? g.lda : g.ldb) * 2u;
+        const unsigned oob = isA ? g.a_bytes : g.b_bytes;
+        bool ok[4];
+        if (BMODE == B_T_SHIFT && !isA) {
+          const int dy = g.ksize == 3 ? tap / 3 - 1 : 0, dx = g.ksize == 3 ? tap % 3 - 1 : 0;
+          int y = t_y[j], x = t_x[j];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          long k = k0 + kq * 4 + r;  // contraction index = matrix row (a pixel or a token)
-          bool ok = k < kend && cv;
-          const bf16_t* p;
-          if (isA) {
-            p = g.A + (ok ? k * g.lda + col : 0);
-          } else if (BMODE == B_T_SHIFT) {
-            int iy = y + dy, ix = x + dx;
-            ok = ok && iy >= 0 && iy < g.H && ix >= 0 && ix < g.W;
-            p = g.B + (ok ? (k + dy * g.W + dx) * g.ldb + col : 0);
+          for (int r = 0; r < 4; ++r) {
+            ok[r] = r < t_rem[j] && (unsigned)(y + dy) < (unsigned)g.H && (unsigned)(x + dx) < (unsigned)g.W;
             if (++x >= g.W) { x = 0; if (++y >= g.H) y = 0; }  // next pixel
-          } else {
-            p = g.B + (ok ? k * g.ldb + col : 0);
           }
-          uint4 v = *reinterpret_cast<const uint4*>(p);
-          rg[j * 4 + r] = ok ? v : make_uint4(0, 0, 0, 0);
-        }
-        if (BMODE == B_T_SHIFT && !isA) {  // advance the task's first pixel by one K-tile (64 pixels)
+          // advance the task's first pixel by one K-tile (64 pixels)
           int nx = t_x[j] + g.step_r, ny = t_y[j] + g.step_q;
           if (nx >= g.W) { nx -= g.W; ++ny; }
           while (ny >= g.H) ny -= g.H;
           t_x[j] = nx;
           t_y[j] = ny;
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ok[r] = r < t_rem[j];
         }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          // the sum is formed here, modulo 2^32: t_off may be "negative" while row r is valid
+          const unsigned off = (t_cv[j] && ok[r]) ? t_off[j] + r * ld2 : oob;
+          rg[j * 4 + r] = isA ? buf_load16(rsrcA, off) : buf_load16(rsrcB, off);
+        }
+        t_off[j] += BK * ld2;
+        t_rem[j] -= BK;
       }
     }
   };
@@ -270,10 +345,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {  // dword w holds columns 2w (low half) and 2w+1 (high half)
           uint2 lo, hi;
-          lo.x = (r0[w] & 0xffffu) | (r1[w] << 16);
-          lo.y = (r2[w] & 0xffffu) | (r3[w] << 16);
-          hi.x = (r0[w] >> 16) | (r1[w] & 0xffff0000u);
-          hi.y = (r2[w] >> 16) | (r3[w] & 0xffff0000u);
+          lo.x = __builtin_amdgcn_perm(r1[w], r0[w], 0x05040100u);  // low halves of rows 0, 1
+          lo.y = __builtin_amdgcn_perm(r3[w], r2[w], 0x05040100u);
+          hi.x = __builtin_amdgcn_perm(r1[w], r0[w], 0x07060302u);  // high halves
+          hi.y = __builtin_amdgcn_perm(r3[w], r2[w], 0x07060302u);
           *reinterpret_cast<uint2*>(base + lds_off(mc * 8 + 2 * w, kq >> 1) + (kq & 1) * 4) = lo;
           *reinterpret_cast<uint2*>(base + lds_off(mc * 8 + 2 * w + 1, kq >> 1) + (kq & 1) * 4) = hi;
         }
@@ -506,6 +581,8 @@ void launch_tile_c(hipStream_t st, GemmArgs& g) {
   long tm = cdivl(g.M, 2 * WTM), tn = cdivl(g.N, 2 * WTN);
   g.tiles_n = (int)tn;
   g.k_per_split = cdivl(g.K, BK) * BK;
+  g.a_bytes = (unsigned)((AMODE == A_IM2COL ? g.M * g.C : g.M * g.lda) * 2);
+  g.b_bytes = (unsigned)(g.N * g.ldb * 2);
   auto kern = gemm_bf16_kernel<WTM, WTN, AMODE, B_ROW, E_BF16, DBUF, FASTC>;
   constexpr size_t lds = lds_bytes<WTM, WTN, DBUF>();
   static bool once = false;  // more than 64 KiB of dynamic LDS has to be allowed per kernel
@@ -547,6 +624,8 @@ void launch_wgrad(hipStream_t st, GemmArgs& g, float* G, float* ws, int taps) {
   g.k_per_split = cdivl(cdivl(g.K, splits), BK) * BK;
   splits = (int)cdivl(g.K, g.k_per_split);
   g.part = ws;
+  g.a_bytes = (unsigned)(g.K * g.lda * 2);
+  g.b_bytes = (unsigned)(g.K * g.ldb * 2);
   auto kern = gemm_bf16_kernel<WG_T, WG_T, OP_T, BMODE, E_PART, true, true>;
   constexpr size_t lds = lds_bytes<WG_T, WG_T, true>();
   static bool once = false;

@@ -73,8 +73,8 @@ ast_status build_plan(Stage& s, std::string& err) {
           if (!(g == 1 && (k == 1 || k == 3) && st == 1 && pad == (k - 1) / 2 && Cin % 8 == 0 && Cout % 8 == 0)) {
             err = fmt("layer %d: bf16 conv2d supports dense 1x1/3x3 stride 1 'same' with channels %% 8 == 0", i);
             return AST_EUNSUPPORTED; }
-          if ((size_t)B * A.h * A.w * std::max(Cin, Cout) >= ((size_t)1 << 31)) {
-            err = fmt("layer %d: bf16 conv2d tensors must stay below 2^31 elements", i);
+          if ((size_t)B * A.h * A.w * std::max(Cin, Cout) >= ((size_t)1 << 30)) {  // 32-bit byte offsets
+            err = fmt("layer %d: bf16 conv2d tensors must stay below 2^30 elements", i);
             return AST_EUNSUPPORTED; }
           op.kind = OP_CONV_IGEMM;
           op.sh_off = shadow; shadow += (size_t)Cout * k * k * Cin;   // [Cout][tap][Cin]
@@ -157,6 +157,9 @@ ast_status build_plan(Stage& s, std::string& err) {
         if (A.rank == 4 || Cin != A.c || Cout <= 0) { err = fmt("layer %d: linear in=%d does not match input %d", i, Cin, A.c); return AST_EINVAL; }
         if (!s.bf16 && A.rank != 2) { err = fmt("layer %d: fp32 linear works on [B][C] vectors", i); return AST_EUNSUPPORTED; }
         if (s.bf16 && (Cin % 8 || Cout % 8)) { err = fmt("layer %d: bf16 linear needs features %% 8 == 0", i); return AST_EUNSUPPORTED; }
+        if (s.bf16 && A.elems / A.c * std::max(Cin, Cout) >= ((size_t)1 << 30)) {  // 32-bit byte offsets
+          err = fmt("layer %d: bf16 linear tensors must stay below 2^30 elements", i); return AST_EUNSUPPORTED;
+        }
         op.kind = OP_LINEAR; op.cin = Cin; op.cout = Cout; op.has_bias = hb ? 1 : 0;
         op.w_off = poff; poff += (size_t)Cout * Cin;
         if (hb) { op.b_off = poff; poff += Cout; }
@@ -199,6 +202,7 @@ ast_status build_plan(Stage& s, std::string& err) {
         if (!s.bf16 || A.rank != 3) { err = fmt("layer %d: MHA needs bf16 token input", i); return AST_EUNSUPPORTED; }
         if (D != A.c || H <= 0 || D % H) { err = fmt("layer %d: MHA D=%d heads=%d do not match input", i, D, H); return AST_EINVAL; }
         if (D / H != 64 || A.h % 32 || A.h > 256) { err = fmt("layer %d: MHA kernels cover head size 64 and S %% 32 == 0, S <= 256", i); return AST_EUNSUPPORTED; }
+        if ((size_t)A.n * A.h * 3 * D >= ((size_t)1 << 30)) { err = fmt("layer %d: MHA tensors must stay below 2^30 elements", i); return AST_EUNSUPPORTED; }
         op.kind = OP_MHA; op.cin = op.cout = D; op.heads = H; op.has_bias = 1;
         op.w_off = poff; poff += (size_t)3 * D * D + 3 * D + (size_t)D * D + D;
         op.sh_off = shadow; shadow += (size_t)4 * D * D;   // W_qkv [3D][D], W_o [D][D]
