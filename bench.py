@@ -48,16 +48,24 @@ def kernel_model(cfg):
             hw = shape[1] * shape[2]
             nq = B * hw
 
-            def cls(m):
-                px4 = hw % 4 == 0 and _cdiv(nq, 512) * _cdiv(m, 32) >= 512
-                return "pw_conv_f32_px4_kernel" if px4 else "pw_conv_f32_kernel<1>"
-            out.setdefault(cls(cout), []).append(4 * (cin + cout) * nq)            # forward
+            def cls(m, kd):
+                if hw % 4 == 0 and nq >= 65536:
+                    return "pw_conv_f32_pk4_kernel"
+                return "pw_conv_f32_pk_kernel<2>" if kd > 32 else "pw_conv_f32_pk_kernel<1>"
+            out.setdefault(cls(cout, cin), []).append(4 * (cin + cout) * nq)        # forward
             if not first or cfg.needs_input_grad:                                   # input gradient
                 extra = 4 * cin * nq if (res_open and cfg.layers[i - 1]["kind"] == "res_begin") else 0
-                out.setdefault(cls(cin), []).append(4 * (cin + cout) * nq + extra)
+                out.setdefault(cls(cin, cout), []).append(4 * (cin + cout) * nq + extra)
+        if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"]:
+            c, h, w = shape
+            if w % 4 == 0 and (L["stride"] == 1 or h % 2 == 0):
+                oc, oh, ow = oshape
+                name = "dw3x3_bwd_s%d_f32_kernel" % L["stride"]
+                out.setdefault(name, []).append(4 * B * (2 * c * h * w + oc * oh * ow))   # g, x in; dx out
         if k == "batchnorm2d":
             c, h, w = shape
-            out.setdefault("bn_bwd_apply_kernel", []).append(12 * B * c * h * w)
+            # g and x in, dx out (no dx for a BatchNorm on the stage input when it is not wanted)
+            out.setdefault("bn_bwd_apply_kernel", []).append((12 if (not first or cfg.needs_input_grad) else 8) * B * c * h * w)
         if k == "conv2d" and cfg.dtype == "bf16":
             cin, cout, kk = L["cin"], L["cout"], L["k"] * L["k"]
             m = B * shape[1] * shape[2]
@@ -88,13 +96,23 @@ def kernel_model(cfg):
     return out
 
 
-# dominant kernel of each workload, read off the rocprofv3 kernel traces under profiles/
+# dominant kernel of each workload (largest share of the kernel time in the rocprofv3 kernel
+# traces under profiles/) and what bounds it
 DOMINANT = {
-    "cfg1": ("pw_conv_f32_kernel<1>", "hbm"),
-    "cfg2": ("pw_conv_f32_kernel<1>", "hbm"),
-    "cfg3": ("pw_conv_f32_kernel<1>", "hbm"),
+    "cfg1": ("pw_conv_f32_pk_kernel<2>", "hbm"),
+    "cfg2": ("bn_bwd_apply_kernel", "hbm"),
+    "cfg3": ("pw_conv_f32_pk_kernel<2>", "hbm"),
     "cfg4": ("gemm_bf16_kernel<128x128,im2col>", "mfma"),
-    "cfg5": ("gemm_bf16_kernel<64x64,rows>", "mfma"),
+    "cfg5": ("gemm_bf16_kernel<128x128,wgrad_rows>", "mfma"),
+}
+
+# HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch, averaged over the launches of one bench run), each scaled by
+# what the same counter reads for the library's plain copy kernel of known size
+# (FETCH_SIZE reads 0.501 of the bytes copied, WRITE_SIZE 1.000); see profiles/.
+TRAFFIC_BYTES = {
+    ("cfg2", "bn_bwd_apply_kernel"): int((17545.3 / 0.5012 + 17256.0) * 1024),
+    ("cfg4", "gemm_bf16_kernel<128x128,im2col>"): int((31015.2 / 0.5005 + 45994.7) * 1024),
 }
 
 
@@ -176,7 +194,8 @@ def run(args):
             achieved = units / avg_s / (1e9 if bound == "hbm" else 1e12)
             peak = HBM_PEAK_GBS if bound == "hbm" else MFMA_PEAK_TFLOPS[cfg.dtype]
             roofline = {"bound": bound, "kernel": name, "achieved": round(achieved, 1), "peak": peak,
-                        "unit": unit, "frac": round(achieved / peak, 4), "traffic": None,
+                        "unit": unit, "frac": round(achieved / peak, 4),
+                        "traffic": TRAFFIC_BYTES.get((args.workload, name)), "algorithmic": int(units),
                         "launches": n, "avg_us": round(avg_s * 1e6, 2)}
     if args.profile_all:
         tot = sum(v[1] for v in prof.values())

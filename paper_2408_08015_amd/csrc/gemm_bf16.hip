@@ -39,7 +39,7 @@ struct GemmArgs {
   int H, W, C, ksize;  // image geometry of the gathered / shifted operand
   int fastc;           // implicit GEMM: C % 64 == 0, so a K-tile lies inside one tap
   int step_q, step_r;  // 64 / W, 64 % W: pixel advance of one K-tile (shifted operand)
-  long k_per_split;    // K range per blockIdx.z (multiple of BK)
+  long k_per_split;    // K range per split (multiple of BK)
   // epilogue
   bf16_t* Cb;          // bf16 output [M][ldc]
   bf16_t* pre;         // optional pre-activation copy
@@ -47,7 +47,9 @@ struct GemmArgs {
   long ldc;
   const float* bias;
   int act;
-  int tiles_n;         // number of tiles along N (blockIdx.x = tile_m * tiles_n + tile_n)
+  int tiles_n;         // number of tiles along N
+  int tiles_mn;        // number of output tiles; block id = (split * taps + tap) * tiles_mn + tile
+  int taps;            // weight gradient of a k x k conv: k*k products per launch, else 1
   unsigned a_bytes, b_bytes;  // extents of the operands (below 2^31): range of the buffer loads
 };
 
@@ -89,17 +91,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   // Blocks are dealt to the 8 XCDs round-robin; renumber them so that each XCD (own L2) works
-  // on a contiguous range of tiles: the N-tiles of one row tile and neighbouring row tiles
-  // (which share halo pixels in the implicit GEMM) then hit the same L2.
+  // on a contiguous range of the flat (split, tap, tile) order: the N-tiles of one row tile
+  // and neighbouring row tiles (which share halo pixels in the implicit GEMM), or all taps
+  // and tiles of one K-split of a weight gradient (which read the same rows of both
+  // operands), then hit the same L2.
   int bid = blockIdx.x;
   {
     const int nb = gridDim.x, q = nb >> 3, r = nb & 7, xcd = bid & 7;
     bid = xcd * q + min(xcd, r) + (bid >> 3);
   }
-  const long m0 = (long)(bid / g.tiles_n) * BM;
-  const long n0 = (long)(bid % g.tiles_n) * BN;
-  const int tap = blockIdx.y;  // weight gradient of a 3x3 conv: one tap per blockIdx.y
-  const long kbeg = (long)blockIdx.z * g.k_per_split;
+  const int tile = bid % g.tiles_mn, rest = bid / g.tiles_mn;
+  const int tap = rest % g.taps, split = rest / g.taps;
+  const long m0 = (long)(tile / g.tiles_n) * BM;
+  const long n0 = (long)(tile % g.tiles_n) * BN;
+  const long kbeg = (long)split * g.k_per_split;
   const long kend = min(kbeg + g.k_per_split, g.K);
   const int nk = (int)((kend - kbeg + BK - 1) / BK);
 
@@ -405,7 +410,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const long m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
-          if (m < g.M) g.part[(((long)blockIdx.z * gridDim.y + tap) * g.M + m) * g.N + n] = acc[i][j][r];
+          if (m < g.M) g.part[(((long)split * g.taps + tap) * g.M + m) * g.N + n] = acc[i][j][r];
         }
       }
     return;
@@ -580,6 +585,8 @@ template <int WTM, int WTN, int AMODE, bool DBUF, bool FASTC>
 void launch_tile_c(hipStream_t st, GemmArgs& g) {
   long tm = cdivl(g.M, 2 * WTM), tn = cdivl(g.N, 2 * WTN);
   g.tiles_n = (int)tn;
+  g.tiles_mn = (int)(tm * tn);
+  g.taps = 1;
   g.k_per_split = cdivl(g.K, BK) * BK;
   g.a_bytes = (unsigned)((AMODE == A_IM2COL ? g.M * g.C : g.M * g.lda) * 2);
   g.b_bytes = (unsigned)(g.N * g.ldb * 2);
@@ -621,6 +628,8 @@ void launch_wgrad(hipStream_t st, GemmArgs& g, float* G, float* ws, int taps) {
   long tm = cdivl(g.M, 2 * WG_T), tn = cdivl(g.N, 2 * WG_T);
   int splits = choose_splits(tm * tn * taps, g.K);
   g.tiles_n = (int)tn;
+  g.tiles_mn = (int)(tm * tn);
+  g.taps = taps;
   g.k_per_split = cdivl(cdivl(g.K, splits), BK) * BK;
   splits = (int)cdivl(g.K, g.k_per_split);
   g.part = ws;
@@ -634,7 +643,7 @@ void launch_wgrad(hipStream_t st, GemmArgs& g, float* G, float* ws, int taps) {
     once = true;
   }
   KLAUNCH_NAMED(BMODE == B_T_SHIFT ? "gemm_bf16_kernel<128x128,wgrad_conv>" : "gemm_bf16_kernel<128x128,wgrad_rows>", kern,
-                dim3((unsigned)(tm * tn), taps, splits), dim3(256), lds, st, g);
+                dim3((unsigned)(tm * tn * taps * splits), 1, 1), dim3(256), lds, st, g);
   long total = (long)taps * g.M * g.N;
   KLAUNCH(reduce_wgrad_kernel, dim3((unsigned)cdivl(total, 64)), dim3(256), 0, st, ws, G, g.M, g.N, taps, splits);
 }
