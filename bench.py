@@ -49,6 +49,8 @@ def kernel_model(cfg):
             nq = B * hw
 
             def cls(m, kd):
+                if _cdiv(nq, 128) * _cdiv(m, 32) < 256 and _cdiv(kd, 8) >= 16:
+                    return "pw_conv_f32_pkks_kernel"
                 if hw % 4 == 0 and nq >= 65536:
                     return "pw_conv_f32_pk4_kernel"
                 return "pw_conv_f32_pk_kernel<2>" if kd > 32 else "pw_conv_f32_pk_kernel<1>"
@@ -101,7 +103,7 @@ def kernel_model(cfg):
 DOMINANT = {
     "cfg1": ("pw_conv_f32_pk_kernel<2>", "hbm"),
     "cfg2": ("bn_bwd_apply_kernel", "hbm"),
-    "cfg3": ("pw_conv_f32_pk_kernel<2>", "hbm"),
+    "cfg3": ("pw_conv_f32_pkks_kernel", "hbm"),
     "cfg4": ("gemm_bf16_kernel<128x128,im2col>", "mfma"),
     "cfg5": ("gemm_bf16_kernel<128x128,wgrad_rows>", "mfma"),
 }

@@ -168,7 +168,8 @@ void bwd_op(Ctx& c, const Op& op) {
       if (gin)
         conv_direct_dgrad_f32(st, g, s.W + op.w_off, (float*)gin, I.n, op.cin, I.h, I.w, op.cout, op.k,
                               op.stride, op.pad, op.groups);
-      conv_direct_wgrad_f32(sw, g, (cf)act_ptr(c, op.in), s.G + op.w_off, I.n, op.cin, I.h, I.w, op.cout,
+      conv_direct_wgrad_f32(sw, g, (cf)act_ptr(c, op.in), s.G + op.w_off, reinterpret_cast<float*>(scratch(c, op)),
+                            I.n, op.cin, I.h, I.w, op.cout,
                             op.k, op.stride, op.pad, op.groups);
       if (op.has_bias) channel_sum_acc_f32(sw, g, s.G + op.b_off, I.n, op.cout, O.h * O.w);
       break;

@@ -80,7 +80,7 @@ __device__ __forceinline__ int lds_off(int row, int c16) {
 
 __device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
 
-template <int WTM, int WTN, int AMODE, int BMODE, int EMODE, bool DBUF, bool FASTC>
+template <int WTM, int WTN, int AMODE, int BMODE, int EMODE, bool DBUF, bool FASTC, int PF = 1>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int BM = 2 * WTM, BN = 2 * WTN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -124,7 +124,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   // transposed mode: tasks of 4(k) x 8(cols); 16 k-quads per tile
   constexpr int TASKS_A = 2 * BM, TASKS_B = 2 * BN;
   constexpr int NTASK = ROWMODE ? 0 : (TASKS_A + TASKS_B) / 256;
-  uint4 rg[ROWMODE ? (NA + NB) : NTASK * 4];
+  // register staging: PF K-tiles in flight (one LDS buffer), one otherwise
+  constexpr int NSLOT = ROWMODE ? (NA + NB) : NTASK * 4;
+  uint4 rgs[DBUF ? 1 : PF][NSLOT];
   const int kc = tid & 7;  // row mode: which 8-element chunk of the 64-wide K-tile
 
   // Row mode: per slot the element offset of the row (without the K position), so that the
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   // Loads are unconditional from an always-valid address (the operand base when the element
   // is padding or out of range) and zeroed by a select afterwards: no branches, so the
   // loads of a tile issue back to back.
-  auto load_tile = [&](int kt) {
+  auto load_tile = [&](int kt, uint4* rg) {
     const long k0 = kbeg + (long)kt * BK;
     if (BUFPATH) {
       const bool kv = k0 + kc * 8 < kend;
@@ -324,7 +326,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     }
   };
 
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](int buf, const uint4* rg) {
     bf16_t* sA = smem + buf * STAGE;
     bf16_t* sB = sA + BM * LDS_STRIDE;
     if (ROWMODE) {
@@ -362,19 +364,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   };
 
   const int lrow = lane & 31, lgrp = lane >> 5;
-  if (nk > 0) {
-    load_tile(0);
-    if (DBUF) store_tile(0);
-  }
-  if (DBUF) __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = DBUF ? (kt & 1) : 0;
-    if (!DBUF) {  // one LDS buffer: write the prefetched tile, then prefetch the next into registers
-      __syncthreads();
-      store_tile(0);
-      __syncthreads();
-    }
-    if (kt + 1 < nk) load_tile(kt + 1);
+  auto mma_tile = [&](int buf) {
     const bf16_t* sA = smem + buf * STAGE;
     const bf16_t* sB = sA + BM * LDS_STRIDE;
 #pragma unroll
@@ -392,12 +382,42 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (DBUF) {
-      if (kt + 1 < nk) store_tile(buf ^ 1);
+  };
+  if (DBUF) {
+    if (nk > 0) {
+      load_tile(0, rgs[0]);
+      store_tile(0, rgs[0]);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      const int buf = kt & 1;
+      if (kt + 1 < nk) load_tile(kt + 1, rgs[0]);
+      mma_tile(buf);
+      if (kt + 1 < nk) store_tile(buf ^ 1, rgs[0]);
       __syncthreads();
     }
+  } else {
+    // One LDS buffer, PF K-tiles in flight in registers: the loads of tile kt + PF are issued
+    // when tile kt has been written to LDS, so a load has PF - 1 whole steps (and the other
+    // resident blocks) to land before its registers are needed.
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+      if (p < nk) load_tile(p, rgs[p]);
+    for (int kt0 = 0; kt0 < nk; kt0 += PF) {
+#pragma unroll
+      for (int p = 0; p < PF; ++p) {
+        const int kt = kt0 + p;
+        if (kt < nk) {  // uniform
+          __syncthreads();
+          store_tile(0, rgs[p]);
+          __syncthreads();
+          if (kt + PF < nk) load_tile(kt + PF, rgs[p]);
+          mma_tile(0);
+        }
+      }
+    }
+    __syncthreads();
   }
-  if (!DBUF) __syncthreads();
 
   // ---------------- epilogue
   if (EMODE == E_PART) {
@@ -581,7 +601,7 @@ constexpr const char* fwd_name() {
   return WTM == 128 ? "gemm_bf16_kernel<256x128,rows>" : (WTM == 64 ? "gemm_bf16_kernel<128x128,rows>" : "gemm_bf16_kernel<64x64,rows>");
 }
 
-template <int WTM, int WTN, int AMODE, bool DBUF, bool FASTC>
+template <int WTM, int WTN, int AMODE, bool DBUF, bool FASTC, int PF>
 void launch_tile_c(hipStream_t st, GemmArgs& g) {
   long tm = cdivl(g.M, 2 * WTM), tn = cdivl(g.N, 2 * WTN);
   g.tiles_n = (int)tn;
@@ -590,7 +610,7 @@ void launch_tile_c(hipStream_t st, GemmArgs& g) {
   g.k_per_split = cdivl(g.K, BK) * BK;
   g.a_bytes = (unsigned)((AMODE == A_IM2COL ? g.M * g.C : g.M * g.lda) * 2);
   g.b_bytes = (unsigned)(g.N * g.ldb * 2);
-  auto kern = gemm_bf16_kernel<WTM, WTN, AMODE, B_ROW, E_BF16, DBUF, FASTC>;
+  auto kern = gemm_bf16_kernel<WTM, WTN, AMODE, B_ROW, E_BF16, DBUF, FASTC, PF>;
   constexpr size_t lds = lds_bytes<WTM, WTN, DBUF>();
   static bool once = false;  // more than 64 KiB of dynamic LDS has to be allowed per kernel
   if (!once) {
@@ -600,27 +620,42 @@ void launch_tile_c(hipStream_t st, GemmArgs& g) {
   KLAUNCH_NAMED((fwd_name<WTM, AMODE>()), kern, dim3((unsigned)(tm * tn), 1, 1), dim3(256), lds, st, g);
 }
 
-template <int WTM, int WTN, int AMODE, bool DBUF>
+template <int WTM, int WTN, int AMODE, bool DBUF, int PF = 1>
 void launch_tile(hipStream_t st, GemmArgs& g) {
-  if (AMODE == A_IM2COL && !g.fastc) launch_tile_c<WTM, WTN, AMODE, DBUF, false>(st, g);
-  else launch_tile_c<WTM, WTN, AMODE, DBUF, true>(st, g);
+  if (AMODE == A_IM2COL && !g.fastc) launch_tile_c<WTM, WTN, AMODE, DBUF, false, 1>(st, g);
+  else launch_tile_c<WTM, WTN, AMODE, DBUF, true, PF>(st, g);
 }
 
-// forward-like products: the largest block tile that still yields >= 512 blocks
+// experiment switch: ASTEROID_GEMM_PF=<int> overrides the prefetch depth
+int gemm_pf() {
+  static int v = -2;
+  if (v == -2) {
+    const char* e = getenv("ASTEROID_GEMM_PF");
+    v = e ? atoi(e) : -1;
+  }
+  return v;
+}
+
+// forward-like products: the largest block tile that still yields >= 256 blocks
 template <int AMODE>
 void launch_fwd_like(hipStream_t st, GemmArgs& g) {
   auto blocks = [&](int bm, int bn) { return cdivl(g.M, bm) * cdivl(g.N, bn); };
   switch (gemm_variant()) {
     case 1: launch_tile<64, 64, AMODE, true>(st, g); return;
-    case 2: launch_tile<64, 64, AMODE, false>(st, g); return;
-    case 4: launch_tile<32, 32, AMODE, false>(st, g); return;
     case 5: launch_tile<128, 64, AMODE, false>(st, g); return;
     default: break;
   }
   // measured on MI355X: more resident blocks beat bigger tiles (the loop is latency-bound),
-  // so the 128x128 tile with one LDS buffer (4 blocks per CU) is the default
-  if (blocks(128, 128) >= 256) launch_tile<64, 64, AMODE, false>(st, g);
-  else launch_tile<32, 32, AMODE, false>(st, g);
+  // so the 128x128 tile with one LDS buffer (3 blocks per CU) is the default
+  const int pf = gemm_pf();
+  if (blocks(128, 128) >= 256) {
+    if (pf == 2) launch_tile<64, 64, AMODE, false, 2>(st, g);
+    else launch_tile<64, 64, AMODE, false, 1>(st, g);
+  } else {
+    if (pf == 1) launch_tile<32, 32, AMODE, false, 1>(st, g);
+    else if (pf == 2) launch_tile<32, 32, AMODE, false, 2>(st, g);
+    else launch_tile<32, 32, AMODE, false, 4>(st, g);
+  }
 }
 
 template <int BMODE>

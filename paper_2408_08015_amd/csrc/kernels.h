@@ -43,8 +43,12 @@ void conv_direct_fwd_f32(hipStream_t st, const float* x, const float* w, const f
                          int groups);
 void conv_direct_dgrad_f32(hipStream_t st, const float* g, const float* w, float* dx, int N, int Cin,
                            int H, int W, int Cout, int k, int stride, int pad, int groups);
-void conv_direct_wgrad_f32(hipStream_t st, const float* g, const float* x, float* G, int N, int Cin,
+// `ws` holds conv_direct_wgrad_ws(...) floats (0: none needed).
+size_t conv_direct_wgrad_ws(int N, int Cin, int H, int W, int Cout, int k, int stride, int pad, int groups);
+void conv_direct_wgrad_f32(hipStream_t st, const float* g, const float* x, float* G, float* ws, int N, int Cin,
                            int H, int W, int Cout, int k, int stride, int pad, int groups);
+// G[i] += sum_c part[c*n + i], c < parts, in a fixed order.
+void reduce_parts_acc_f32(hipStream_t st, const float* part, float* G, size_t n, int parts);
 // G[c] += sum_{n,p} g[n][c][p]
 void channel_sum_acc_f32(hipStream_t st, const float* g, float* G, int N, int C, int HW);
 

@@ -112,6 +112,64 @@ __global__ __launch_bounds__(256) void conv_direct_wgrad_kernel(
   if (threadIdx.x == 0) G[widx] += s;
 }
 
+// Dense 3x3 conv with up to 4 input channels (an RGB stem): block = one output channel x one
+// chunk of the flattened (n, i, j) output positions; every thread keeps all CG*9 sums of its
+// positions, the block adds them and writes one partial per chunk.
+template <int CG>
+__global__ __launch_bounds__(256) void conv3x3_small_cin_wgrad_kernel(
+    const float* __restrict__ g, const float* __restrict__ x, float* __restrict__ part, int N, int H, int W,
+    int Cout, int Ho, int Wo, int stride, int pad, int per_chunk) {
+  __shared__ float sh[16];
+  const int o = blockIdx.x, chunk = blockIdx.y;
+  const long per = (long)N * Ho * Wo;
+  const long e0 = (long)chunk * per_chunk, e1 = min(e0 + per_chunk, per);
+  float acc[CG * 9];
+#pragma unroll
+  for (int k = 0; k < CG * 9; ++k) acc[k] = 0.f;
+  for (long e = e0 + threadIdx.x; e < e1; e += 256) {
+    const int n = (int)(e / ((long)Ho * Wo));
+    const int r = (int)(e - (long)n * Ho * Wo);
+    const int i = r / Wo, j = r - i * Wo;
+    const float gv = g[((size_t)n * Cout + o) * Ho * Wo + r];
+    const int i0 = i * stride - pad, j0 = j * stride - pad;
+#pragma unroll
+    for (int c = 0; c < CG; ++c) {
+      const float* xc = x + ((size_t)n * CG + c) * H * W;
+#pragma unroll
+      for (int u = 0; u < 3; ++u) {
+        const int ii = i0 + u;
+#pragma unroll
+        for (int v = 0; v < 3; ++v) {
+          const int jj = j0 + v;
+          const bool ok = ii >= 0 && ii < H && jj >= 0 && jj < W;
+          acc[(c * 3 + u) * 3 + v] += gv * (ok ? xc[(size_t)ii * W + jj] : 0.f);
+        }
+      }
+    }
+  }
+  float* out = part + ((size_t)chunk * Cout + o) * (CG * 9);
+#pragma unroll
+  for (int k = 0; k < CG * 9; ++k) {
+    const float s = block_sum<float>(acc[k], sh);
+    if (threadIdx.x == 0) out[k] = s;
+  }
+}
+
+static int small_cin_chunks(int N, int Ho, int Wo, int Cout) {
+  long per = (long)N * Ho * Wo;
+  int want = (int)((1024 + Cout - 1) / Cout);      // about 1024 blocks
+  long cap = (per + 1023) / 1024;                  // at least 1024 positions per block
+  if (want > cap) want = (int)cap;
+  return want < 1 ? 1 : want;
+}
+static bool small_cin_case(int Cin, int k, int groups) { return groups == 1 && k == 3 && Cin >= 1 && Cin <= 4; }
+
+size_t conv_direct_wgrad_ws(int N, int Cin, int H, int W, int Cout, int k, int stride, int pad, int groups) {
+  if (!small_cin_case(Cin, k, groups)) return 0;
+  int Ho = conv_out(H, k, stride, pad), Wo = conv_out(W, k, stride, pad);
+  return (size_t)small_cin_chunks(N, Ho, Wo, Cout) * Cout * Cin * 9;
+}
+
 void conv_direct_fwd_f32(hipStream_t st, const float* x, const float* w, const float* bias, float* y,
                          int N, int Cin, int H, int W, int Cout, int k, int stride, int pad,
                          int groups) {
@@ -127,9 +185,22 @@ void conv_direct_dgrad_f32(hipStream_t st, const float* g, const float* w, float
   KLAUNCH(conv_direct_dgrad_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, w, dx, Cin,
                      H, W, Cout, Ho, Wo, k, stride, pad, groups, total);
 }
-void conv_direct_wgrad_f32(hipStream_t st, const float* g, const float* x, float* G, int N, int Cin,
+void conv_direct_wgrad_f32(hipStream_t st, const float* g, const float* x, float* G, float* ws, int N, int Cin,
                            int H, int W, int Cout, int k, int stride, int pad, int groups) {
   int Ho = conv_out(H, k, stride, pad), Wo = conv_out(W, k, stride, pad);
+  if (ws && small_cin_case(Cin, k, groups)) {
+    const int chunks = small_cin_chunks(N, Ho, Wo, Cout);
+    const int per_chunk = cdiv((long)N * Ho * Wo, chunks);
+    dim3 grid(Cout, chunks);
+    switch (Cin) {
+      case 1: KLAUNCH(conv3x3_small_cin_wgrad_kernel<1>, grid, dim3(256), 0, st, g, x, ws, N, H, W, Cout, Ho, Wo, stride, pad, per_chunk); break;
+      case 2: KLAUNCH(conv3x3_small_cin_wgrad_kernel<2>, grid, dim3(256), 0, st, g, x, ws, N, H, W, Cout, Ho, Wo, stride, pad, per_chunk); break;
+      case 3: KLAUNCH(conv3x3_small_cin_wgrad_kernel<3>, grid, dim3(256), 0, st, g, x, ws, N, H, W, Cout, Ho, Wo, stride, pad, per_chunk); break;
+      default: KLAUNCH(conv3x3_small_cin_wgrad_kernel<4>, grid, dim3(256), 0, st, g, x, ws, N, H, W, Cout, Ho, Wo, stride, pad, per_chunk); break;
+    }
+    reduce_parts_acc_f32(st, ws, G, (size_t)Cout * Cin * 9, chunks);
+    return;
+  }
   int nw = Cout * (Cin / groups) * k * k;
   KLAUNCH(conv_direct_wgrad_kernel, dim3(nw), dim3(256), 0, st, g, x, G, N, Cin, H, W, Cout,
                      Ho, Wo, k, stride, pad, groups);
@@ -311,14 +382,36 @@ __global__ __launch_bounds__(256) void linear_fwd_kernel(const float* __restrict
     }
   }
 }
-__global__ void linear_dgrad_kernel(const float* __restrict__ g, const float* __restrict__ W,
-                                    float* __restrict__ dx, int R, int Cin, int Cout) {
-  int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= R * Cin) return;
-  int r = idx / Cin, i = idx - r * Cin;
-  float acc = 0.f;
-  for (int o = 0; o < Cout; ++o) acc += g[(size_t)r * Cout + o] * W[(size_t)o * Cin + i];
-  dx[idx] = acc;
+// dx[r][i] = sum_o g[r][o] W[o][i].  Block = 64 input features x 16 slices of the output
+// features; a wavefront streams its rows of W (coalesced) against up to eight rows of g at a
+// time, the sixteen partial sums are added through LDS in a fixed order.
+__global__ __launch_bounds__(1024) void linear_dgrad_kernel(const float* __restrict__ g, const float* __restrict__ W,
+                                                            float* __restrict__ dx, int R, int Cin, int Cout) {
+  __shared__ float sh[16][8][64];
+  const int il = threadIdx.x & 63, os = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + il;
+  const bool iv = i < Cin;
+  for (int r0 = 0; r0 < R; r0 += 8) {
+    float acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+    for (int o = os; o < Cout; o += 16) {
+      const float w = iv ? W[(size_t)o * Cin + i] : 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (r0 + q < R) acc[q] += g[(size_t)(r0 + q) * Cout + o] * w;
+    }
+    __syncthreads();  // the previous round's sums have been read
+#pragma unroll
+    for (int q = 0; q < 8; ++q) sh[os][q][il] = acc[q];
+    __syncthreads();
+    if (os < 8 && r0 + os < R && iv) {
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) s += sh[k][os][il];
+      dx[(size_t)(r0 + os) * Cin + i] = s;
+    }
+  }
 }
 __global__ void linear_wgrad_kernel(const float* __restrict__ g, const float* __restrict__ x,
                                     float* __restrict__ GW, float* __restrict__ Gb, int R, int Cin,
@@ -342,8 +435,7 @@ void linear_fwd_f32(hipStream_t st, const float* x, const float* W, const float*
 }
 void linear_dgrad_f32(hipStream_t st, const float* g, const float* W, float* dx, int R, int Cin,
                       int Cout) {
-  KLAUNCH(linear_dgrad_kernel, dim3(cdiv((long)R * Cin, 256)), dim3(256), 0, st, g, W, dx, R,
-                     Cin, Cout);
+  KLAUNCH(linear_dgrad_kernel, dim3(cdiv(Cin, 64)), dim3(1024), 0, st, g, W, dx, R, Cin, Cout);
 }
 void linear_wgrad_f32(hipStream_t st, const float* g, const float* x, float* GW, float* Gb, int R,
                       int Cin, int Cout) {

@@ -89,6 +89,75 @@ __global__ __launch_bounds__(256) void pw_conv_f32_pk_kernel(
   }
 }
 
+// Few pixels, long K (the 14x14 / 7x7 layers of a whole network): the four wavefronts of a
+// block share one 32-pixel x 32-channel output tile and split K between them, so there are
+// four times as many wavefronts and a quarter of the dependent passes; the four partial
+// tiles are added through LDS in a fixed order.
+__global__ __launch_bounds__(256) void pw_conv_f32_pkks_kernel(
+    const float4* __restrict__ Wp, const float* __restrict__ X, float* __restrict__ Y,
+    const float* __restrict__ bias, const float* __restrict__ add, long NQ, int HW, int Kdim, int Mdim,
+    int KG) {
+  constexpr int NCH = 2;
+  __shared__ float sR[4][16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int m_base = blockIdx.y * 32;
+  const long q = (long)blockIdx.x * 32 + col;
+  const bool qv = q < NQ;
+  long n = 0;
+  int p = 0;
+  if (qv) {
+    n = q / HW;
+    p = (int)(q - n * HW);
+  }
+  const float* xq = X + (size_t)n * Kdim * HW + p;
+  const float4* wl = Wp + (size_t)blockIdx.y * KG * 64 + lane;
+  const int gper = (KG + 3) >> 2;  // k-groups per wavefront
+  const int gbeg = wave * gper, gend = min(gbeg + gper, KG);
+  floatx16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int g0 = gbeg; g0 < gend; g0 += NCH * 4) {
+    float4 a[NCH * 4];
+    float b[NCH * 16];
+#pragma unroll
+    for (int g = 0; g < NCH * 4; ++g) {
+      const bool ok = g0 + g < gend;
+      a[g] = ok ? wl[(size_t)(g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int k = (g0 + g) * 8 + 2 * e + half;
+        b[4 * g + e] = (ok && qv && k < Kdim) ? xq[(size_t)k * HW] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < NCH * 4; ++g) {
+      if (g0 + g >= gend) break;  // uniform
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g].x, b[4 * g + 0], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g].y, b[4 * g + 1], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g].z, b[4 * g + 2], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g].w, b[4 * g + 3], acc, 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sR[wave][r][lane] = acc[r];
+  __syncthreads();
+  if (!qv) return;
+  float* yq = Y + (size_t)n * Mdim * HW + p;
+  const float* aq = add ? add + (size_t)n * Mdim * HW + p : nullptr;
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {  // wavefront w finishes rows 4w .. 4w+3 of the register layout
+    const int r = 4 * wave + rr;
+    const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
+    if (m < Mdim) {
+      float v = (sR[0][r][lane] + sR[1][r][lane]) + (sR[2][r][lane] + sR[3][r][lane]);
+      if (bias) v += bias[m];
+      if (aq) v += aq[(size_t)m * HW];
+      yq[(size_t)m * HW] = v;
+    }
+  }
+}
+
 // Large images: a wavefront owns 128 pixels; every lane loads four consecutive pixels
 // (16 bytes) per input channel and feeds four MFMA column tiles (column j of tile t is
 // pixel 4j + t), so each output row is stored as 16 bytes per lane.  Four times the bytes
@@ -192,7 +261,10 @@ void pw_conv_f32(hipStream_t st, const float* Wp, const float* X, float* Y, cons
   const float4* wp = reinterpret_cast<const float4*>(Wp);
   // Measured on 32-sample micro-batches: 128-pixel wavefronts win from 56x56 images up,
   // 32-pixel ones below (more wavefronts in flight matter more than bytes per instruction).
-  if (HW % 4 == 0 && NQ >= 65536) {
+  if ((long)cdiv(NQ, 128) * mt < 256 && KG >= 16) {  // under one block per CU and K >= 128
+    KLAUNCH(pw_conv_f32_pkks_kernel, dim3((unsigned)cdiv(NQ, 32), mt), dim3(256), 0, st, wp, X, Y, bias, add, NQ, HW,
+            Kdim, Mdim, KG);
+  } else if (HW % 4 == 0 && NQ >= 65536) {
     KLAUNCH(pw_conv_f32_pk4_kernel, dim3((unsigned)cdiv(NQ, 512), mt), dim3(256), 0, st, wp, X, Y, bias, add, NQ, HW,
             Kdim, Mdim, KG);
   } else if (Kdim > 32) {
@@ -335,6 +407,10 @@ void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, f
     KLAUNCH(pw_wgrad_f32_kernel<false>, grid, dim3(256), 0, st, g, x, part, Cin, Cout, HW, cps, pxw);
   size_t n = (size_t)Cin * Cout;
   KLAUNCH(reduce_parts_acc_kernel, dim3(cdiv(n, 64)), dim3(256), 0, st, part, G, n, chunks);
+}
+
+void reduce_parts_acc_f32(hipStream_t st, const float* part, float* G, size_t n, int parts) {
+  KLAUNCH(reduce_parts_acc_kernel, dim3(cdiv(n, 64)), dim3(256), 0, st, part, G, n, parts);
 }
 
 // ============================================================== depthwise 3x3 (pad 1, stride 1 or 2)

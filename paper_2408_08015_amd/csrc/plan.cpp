@@ -286,6 +286,9 @@ ast_status build_plan(Stage& s, std::string& err) {
     switch (op.kind) {
       case OP_CONV_PW: need = pw_wgrad_f32_ws(I.n, op.cin, op.cout, I.h * I.w) * sizeof(float); break;
       case OP_CONV_DW: need = dw3x3_bwd_f32_ws(I.n, I.c) * sizeof(float); break;
+      case OP_CONV_DIRECT:
+        need = conv_direct_wgrad_ws(I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride, op.pad, op.groups) * sizeof(float);
+        break;
       case OP_BN:
         need = bn_ws_doubles(I.c, (size_t)I.n * I.h * I.w) * sizeof(double);
         break;
