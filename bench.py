@@ -101,7 +101,7 @@ def kernel_model(cfg):
 # dominant kernel of each workload (largest share of the kernel time in the rocprofv3 kernel
 # traces under profiles/) and what bounds it
 DOMINANT = {
-    "cfg1": ("pw_conv_f32_pk_kernel<2>", "hbm"),
+    "cfg1": ("pw_conv_f32_pkks_kernel", "hbm"),
     "cfg2": ("bn_bwd_apply_kernel", "hbm"),
     "cfg3": ("pw_conv_f32_pkks_kernel", "hbm"),
     "cfg4": ("gemm_bf16_kernel<128x128,im2col>", "mfma"),
@@ -179,6 +179,7 @@ def run(args):
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_round()
+    t_enq = time.perf_counter()      # every launch enqueued; the GPU may still be working
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = st.profile_end() if filt is not None else {}
@@ -222,6 +223,7 @@ def run(args):
         "config": {"workload": "%s: %s, B=%d x M=%d, in %s %s" % (args.workload, cfg.name, B, M,
                                                                  "x".join(map(str, cfg.in_shape)), cfg.layout),
                    "K": 1, "lr": cfg.lr, "momentum": cfg.momentum,
+                   "host_enqueue_ms_per_step": round((t_enq - t0) * 1e3 / args.steps, 4),
                    "stage_bytes": {"mod": mem[0], "opt": mem[1], "act_per_mb": mem[2], "workspace": mem[3]}},
         "roofline": roofline, "cpu_baseline": cpu,
     }

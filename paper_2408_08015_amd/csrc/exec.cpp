@@ -100,7 +100,8 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       if (s.bf16) {
         linear_bf16_fwd(st, (cb)act_ptr(c, op.in), s.shadow + op.sh_off, op.has_bias ? s.W + op.b_off : nullptr,
                         (bf16_t*)act_ptr(c, op.out), op.act == 3 ? (bf16_t*)act_ptr(c, op.skip) : nullptr,
-                        (size_t)I.n * I.h * I.w, op.cin, op.cout, op.act);
+                        op.res_in >= 0 ? (cb)act_ptr(c, op.res_in) : nullptr, (size_t)I.n * I.h * I.w, op.cin, op.cout,
+                        op.act);
       } else {
         linear_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, op.has_bias ? s.W + op.b_off : nullptr,
                        (float*)act_ptr(c, op.out), I.n, op.cin, op.cout);
@@ -128,10 +129,10 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       float* lse = reinterpret_cast<float*>(o + R * D);
       const float* bq = s.W + op.w_off + (size_t)3 * D * D;
       const float* bo = bq + 3 * D + (size_t)D * D;
-      linear_bf16_fwd(st, (cb)act_ptr(c, op.in), s.shadow + op.sh_off, bq, qkv, nullptr, R, D, 3 * D, 0);
+      linear_bf16_fwd(st, (cb)act_ptr(c, op.in), s.shadow + op.sh_off, bq, qkv, nullptr, nullptr, R, D, 3 * D, 0);
       attention_fwd_bf16(st, qkv, o, lse, I.n, I.h, D, op.heads);
       linear_bf16_fwd(st, o, s.shadow + op.sh_off + (size_t)3 * D * D, bo, (bf16_t*)act_ptr(c, op.out), nullptr,
-                      R, D, D, 0);
+                      op.res_in >= 0 ? (cb)act_ptr(c, op.res_in) : nullptr, R, D, D, 0);
       break;
     }
   }
@@ -227,14 +228,17 @@ void bwd_op(Ctx& c, const Op& op) {
         const size_t R = (size_t)I.n * I.h * I.w;
         cb g = (cb)grad_ptr(c, op.out);
         char* sc = scratch(c, op);
-        if (op.act == 3) {
+        if (op.act == 3 && !op.gelu_bwd_fused) {
           bf16_t* gp = reinterpret_cast<bf16_t*>(sc);
           act_bwd_bf16(st, g, (cb)act_ptr(c, op.skip), gp, O.elems, 3);
           g = gp;
           sc += align256(O.bytes);
         }
         hipStream_t sw = fork_side(c);
-        if (gin) linear_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin, R, op.cin, op.cout);
+        if (gin)
+          linear_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin,
+                            op.gelu_from >= 0 ? (cb)act_ptr(c, op.gelu_from) : nullptr,
+                            op.dgrad_add >= 0 ? (cb)grad_ptr(c, op.dgrad_add) : nullptr, R, op.cin, op.cout);
         linear_bf16_wgrad(sw, g, (cb)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr,
                           sc, R, op.cin, op.cout);
       } else {
@@ -253,8 +257,11 @@ void bwd_op(Ctx& c, const Op& op) {
     }
     case OP_LAYERNORM:
       layernorm_bwd_bf16(st, (cb)grad_ptr(c, op.out), (cb)act_ptr(c, op.in),
-                         reinterpret_cast<float*>(c.slot + op.aux_off), s.W + op.w_off, (bf16_t*)gin,
-                         s.G + op.w_off, s.G + op.b_off, scratch(c, op), (size_t)I.n * I.h, I.c);
+                         reinterpret_cast<float*>(c.slot + op.aux_off), s.W + op.w_off,
+                         (gin && op.dgrad_add >= 0) ? (cb)grad_ptr(c, op.dgrad_add) : nullptr, (bf16_t*)gin,
+                         scratch(c, op), (size_t)I.n * I.h, I.c);
+      // the parameter gradients only need the partials of the kernel above
+      layernorm_bwd_params_bf16(fork_side(c), scratch(c, op), s.G + op.w_off, s.G + op.b_off, (size_t)I.n * I.h, I.c);
       break;
     case OP_MHA: {
       const int D = op.cin;
@@ -273,11 +280,13 @@ void bwd_op(Ctx& c, const Op& op) {
       char* lw = reinterpret_cast<char*>(dsum) + align256(mha_bf16_ws_bytes(I.n, I.h, D, op.heads));
       cb g = (cb)grad_ptr(c, op.out);
       hipStream_t sw = fork_side(c);
-      linear_bf16_dgrad(st, g, s.shadow + op.sh2_off + (size_t)3 * D * D, d_o, R, D, D);
+      linear_bf16_dgrad(st, g, s.shadow + op.sh2_off + (size_t)3 * D * D, d_o, nullptr, nullptr, R, D, D);
       linear_bf16_wgrad(sw, g, o, Go, Gbo, lw, R, D, D);
       attention_bwd_bf16(st, qkv, o, d_o, lse, dqkv, dsum, I.n, I.h, D, op.heads);
       sw = fork_side(c);
-      if (gin) linear_bf16_dgrad(st, dqkv, s.shadow + op.sh2_off, (bf16_t*)gin, R, D, 3 * D);
+      if (gin)
+        linear_bf16_dgrad(st, dqkv, s.shadow + op.sh2_off, (bf16_t*)gin, nullptr,
+                          op.dgrad_add >= 0 ? (cb)grad_ptr(c, op.dgrad_add) : nullptr, R, D, 3 * D);
       linear_bf16_wgrad(sw, dqkv, (cb)act_ptr(c, op.in), Gq, Gbq, lw, R, D, 3 * D);
       break;
     }

@@ -46,6 +46,8 @@ struct GemmArgs {
   float* part;         // fp32 partials [split][tap][M][N]
   long ldc;
   const float* bias;
+  const bf16_t* add;   // optional residual input [M][ldc], added to the (rounded) output
+  const bf16_t* gmul;  // optional pre-activation [M][ldc]: the output is multiplied by GELU'(pre)
   int act;
   int tiles_n;         // number of tiles along N
   int tiles_mn;        // number of output tiles; block id = (split * taps + tap) * tiles_mn + tile
@@ -79,6 +81,10 @@ __device__ __forceinline__ int lds_off(int row, int c16) {
 }
 
 __device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
+// d/dx of the exact GELU: Phi(x) + x phi(x)
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
+}
 
 template <int WTM, int WTN, int AMODE, int BMODE, int EMODE, bool DBUF, bool FASTC, int PF = 1>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
@@ -461,8 +467,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     for (int idx = tid; idx < BM * (BN / 8); idx += 256) {
       int row = idx / (BN / 8), ch = idx - row * (BN / 8);
       long m = m0 + row, n = n0 + ch * 8;
-      if (m < g.M && n < g.N)
-        *reinterpret_cast<uint4*>(out + m * g.ldc + n) = *reinterpret_cast<const uint4*>(&smem[row * CS + ch * 8]);
+      if (m < g.M && n < g.N) {
+        uint4 v = *reinterpret_cast<const uint4*>(&smem[row * CS + ch * 8]);
+        if (out == g.Cb && (g.add || g.gmul)) {
+          // applied to the bf16-rounded product, exactly as a separate kernel would see it
+          const uint4 o = *reinterpret_cast<const uint4*>((g.add ? g.add : g.gmul) + m * g.ldc + n);
+          uint32_t* vw = reinterpret_cast<uint32_t*>(&v);
+          const uint32_t* ow = reinterpret_cast<const uint32_t*>(&o);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            float a0 = __uint_as_float(vw[w] << 16), a1 = __uint_as_float(vw[w] & 0xffff0000u);
+            const float b0 = __uint_as_float(ow[w] << 16), b1 = __uint_as_float(ow[w] & 0xffff0000u);
+            if (g.add) { a0 += b0; a1 += b1; }
+            else { a0 *= gelu_grad_f(b0); a1 *= gelu_grad_f(b1); }
+            vw[w] = (uint32_t)f2bf(a0) | ((uint32_t)f2bf(a1) << 16);
+          }
+        }
+        *reinterpret_cast<uint4*>(out + m * g.ldc + n) = v;
+      }
     }
   }
 }
@@ -643,6 +665,8 @@ void launch_fwd_like(hipStream_t st, GemmArgs& g) {
   switch (gemm_variant()) {
     case 1: launch_tile<64, 64, AMODE, true>(st, g); return;
     case 5: launch_tile<128, 64, AMODE, false>(st, g); return;
+    case 6: launch_tile<128, 64, AMODE, false, 2>(st, g); return;
+    case 7: launch_tile<128, 64, AMODE, false, 3>(st, g); return;
     default: break;
   }
   // measured on MI355X: more resident blocks beat bigger tiles (the loop is latency-bound),
@@ -739,17 +763,20 @@ size_t linear_bf16_ws_bytes(size_t R, int Cin, int Cout) {
 }
 
 void linear_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh, const float* bias, bf16_t* y, bf16_t* pre,
-                     size_t R, int Cin, int Cout, int act) {
+                     const bf16_t* add, size_t R, int Cin, int Cout, int act) {
   GemmArgs g = {};
+  g.add = add;
   g.A = x; g.B = sh;
   g.M = (long)R; g.N = Cout; g.K = Cin; g.lda = Cin; g.ldb = Cin;
   g.Cb = y; g.pre = pre; g.ldc = Cout; g.bias = bias; g.act = act;
   launch_fwd_like<A_ROW>(st, g);
 }
 
-void linear_bf16_dgrad(hipStream_t st, const bf16_t* gy, const bf16_t* sh_t, bf16_t* dx, size_t R, int Cin,
-                       int Cout) {
+void linear_bf16_dgrad(hipStream_t st, const bf16_t* gy, const bf16_t* sh_t, bf16_t* dx, const bf16_t* gelu_pre,
+                       const bf16_t* add, size_t R, int Cin, int Cout) {
   GemmArgs g = {};
+  g.gmul = gelu_pre;  // at most one of the two is given
+  g.add = add;
   g.A = gy; g.B = sh_t;
   g.M = (long)R; g.N = Cin; g.K = Cout; g.lda = Cout; g.ldb = Cout;
   g.Cb = dx; g.ldc = Cin; g.act = 0;

@@ -35,10 +35,14 @@ void conv_bf16_wgrad(hipStream_t st, const bf16_t* g, const bf16_t* x, float* GW
 // ---- linear on [R][Cin] rows
 size_t linear_bf16_ws_bytes(size_t R, int Cin, int Cout);
 // y = act(x W^T + b) (+ add); with act == GELU the pre-activation goes to `pre` as well
+// `add` (may be NULL): residual input [R][Cout] added to the rounded output.
 void linear_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh, const float* bias, bf16_t* y,
-                     bf16_t* pre, size_t R, int Cin, int Cout, int act);
-void linear_bf16_dgrad(hipStream_t st, const bf16_t* g, const bf16_t* sh_t, bf16_t* dx, size_t R,
-                       int Cin, int Cout);
+                     bf16_t* pre, const bf16_t* add, size_t R, int Cin, int Cout, int act);
+// dx = g W; with `gelu_pre` ([R][Cin], may be NULL) dx is further multiplied by GELU'(gelu_pre):
+// the backward of a GELU in front of this layer, folded into the epilogue; with `add` ([R][Cin],
+// may be NULL) the gradient arriving over a residual connection is added.  At most one of the two.
+void linear_bf16_dgrad(hipStream_t st, const bf16_t* g, const bf16_t* sh_t, bf16_t* dx, const bf16_t* gelu_pre,
+                       const bf16_t* add, size_t R, int Cin, int Cout);
 void linear_bf16_wgrad(hipStream_t st, const bf16_t* g, const bf16_t* x, float* GW, float* Gb, void* ws,
                        size_t R, int Cin, int Cout);
 
@@ -55,9 +59,12 @@ void maxpool_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, bf16_t* 
 size_t layernorm_bf16_ws_bytes(size_t R, int D);
 void layernorm_fwd_bf16(hipStream_t st, const bf16_t* x, const float* gamma, const float* beta,
                         bf16_t* y, float* stat /*[2][R]*/, size_t R, int D, float eps);
+// Backward in two launches: dx (+ add, the gradient arriving over a residual connection around
+// the LayerNorm; may be NULL) and per-block partials of dgamma / dbeta into ws; then
+// Ggamma / Gbeta += the partials (may run on another stream once the first launch is done).
 void layernorm_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, const float* stat,
-                        const float* gamma, bf16_t* dx, float* Ggamma, float* Gbeta, void* ws, size_t R,
-                        int D);
+                        const float* gamma, const bf16_t* add, bf16_t* dx, void* ws, size_t R, int D);
+void layernorm_bwd_params_bf16(hipStream_t st, const void* ws, float* Ggamma, float* Gbeta, size_t R, int D);
 
 // ---- self-attention core on packed qkv [B][S][3D] (head size 64, S % 32 == 0, S <= 256):
 // o [B][S][D], lse [B][H][S]

@@ -276,6 +276,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
                                                             const bf16_t* __restrict__ x,
                                                             const float* __restrict__ stat,
                                                             const float* __restrict__ gamma,
+                                                            const bf16_t* __restrict__ add,
                                                             bf16_t* __restrict__ dx, float* __restrict__ part,
                                                             size_t R, int D, size_t rows_per_block) {
   extern __shared__ float sh[];  // [4 waves][2][D]
@@ -317,6 +318,12 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
           float o[8];
 #pragma unroll
           for (int k = 0; k < 8; ++k) o[k] = istd * (gh[j][k] - s1 - xh[j][k] * s2);
+          if (add) {  // gradient arriving over the residual connection around this LayerNorm
+            float av[8];
+            unpack8(*reinterpret_cast<const uint4*>(add + row * D + vi * 8), av);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) o[k] += av[k];
+          }
           *reinterpret_cast<uint4*>(dx + row * D + vi * 8) = pack8(o);
         }
       }
@@ -358,19 +365,24 @@ void layernorm_fwd_bf16(hipStream_t st, const bf16_t* x, const float* gamma, con
   else KLAUNCH(layernorm_fwd_kernel<2>, dim3(cdivu(R, 4)), dim3(256), 0, st, x, gamma, beta, y, stat, R, D, eps);
 }
 void layernorm_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, const float* stat, const float* gamma,
-                        bf16_t* dx, float* Ggamma, float* Gbeta, void* ws, size_t R, int D) {
+                        const bf16_t* add, bf16_t* dx, void* ws, size_t R, int D) {
+  size_t blocks = ln_blocks(R);
+  size_t rpb = (R + blocks - 1) / blocks;
+  float* part = reinterpret_cast<float*>(ws);
+  if (D <= 512)
+    KLAUNCH(layernorm_bwd_kernel<1>, dim3((unsigned)((R + rpb - 1) / rpb)), dim3(256), (size_t)8 * D * sizeof(float), st,
+            g, x, stat, gamma, add, dx, part, R, D, rpb);
+  else
+    KLAUNCH(layernorm_bwd_kernel<2>, dim3((unsigned)((R + rpb - 1) / rpb)), dim3(256), (size_t)8 * D * sizeof(float), st,
+            g, x, stat, gamma, add, dx, part, R, D, rpb);
+}
+
+void layernorm_bwd_params_bf16(hipStream_t st, const void* ws, float* Ggamma, float* Gbeta, size_t R, int D) {
   size_t blocks = ln_blocks(R);
   size_t rpb = (R + blocks - 1) / blocks;
   blocks = (R + rpb - 1) / rpb;
-  float* part = reinterpret_cast<float*>(ws);
-  if (D <= 512)
-    KLAUNCH(layernorm_bwd_kernel<1>, dim3((unsigned)blocks), dim3(256), (size_t)8 * D * sizeof(float), st, g, x, stat,
-            gamma, dx, part, R, D, rpb);
-  else
-    KLAUNCH(layernorm_bwd_kernel<2>, dim3((unsigned)blocks), dim3(256), (size_t)8 * D * sizeof(float), st, g, x, stat,
-            gamma, dx, part, R, D, rpb);
-  KLAUNCH(layernorm_bwd_final_kernel, dim3(cdivu(2 * (size_t)D, 16)), dim3(256), 0, st, part, Ggamma, Gbeta, D,
-          (int)blocks);
+  KLAUNCH(layernorm_bwd_final_kernel, dim3(cdivu(2 * (size_t)D, 16)), dim3(256), 0, st,
+          reinterpret_cast<const float*>(ws), Ggamma, Gbeta, D, (int)blocks);
 }
 
 }  // namespace ast

@@ -174,7 +174,20 @@ ast_status build_plan(Stage& s, std::string& err) {
             ++i;
           }
         }
+        bool lin_res = false;
+        if (s.bf16 && op.act == 0 && i + 1 < nl && s.layers[i + 1].kind == AST_RES_ADD && !res_stack.empty()) {
+          const Act& K = s.acts[res_stack.back()];  // residual add folded into the output epilogue
+          if (K.elems == A.elems / A.c * Cout && K.c == Cout && K.rank == A.rank) {
+            op.res_in = res_stack.back();
+            lin_res = true;
+            ++i;
+          }
+        }
         op.out = cur = new_act(s, A.n, Cout, A.h, A.w, A.rank, i, es);
+        if (lin_res) {
+          s.ops[res_op_stack.back()].skip = cur;
+          res_stack.pop_back(); res_op_stack.pop_back();
+        }
         break;
       }
       case AST_SOFTMAX_CE: {
@@ -209,7 +222,20 @@ ast_status build_plan(Stage& s, std::string& err) {
         op.sh2_off = shadow; shadow += (size_t)4 * D * D;  // W_qkv^T [D][3D], W_o^T [D][D]
         // per-slot: qkv [rows][3D] bf16, o [rows][D] bf16, lse [B][H][S] fp32
         take_aux(op, (size_t)A.n * A.h * 4 * D * 2 + (size_t)A.n * H * A.h * 4);
+        bool mha_res = false;
+        if (i + 1 < nl && s.layers[i + 1].kind == AST_RES_ADD && !res_stack.empty()) {
+          const Act& K = s.acts[res_stack.back()];  // residual add folded into the output projection
+          if (K.elems == A.elems && K.c == A.c && K.rank == A.rank) {
+            op.res_in = res_stack.back();
+            mha_res = true;
+            ++i;
+          }
+        }
         op.out = cur = new_act(s, A.n, D, A.h, 1, 3, i, es);
+        if (mha_res) {
+          s.ops[res_op_stack.back()].skip = cur;
+          res_stack.pop_back(); res_op_stack.pop_back();
+        }
         break;
       }
       default:
@@ -234,12 +260,26 @@ ast_status build_plan(Stage& s, std::string& err) {
     }
   s.wpack_floats = wpk;
 
-  // Fuse the skip-gradient add of a residual block into the input-gradient kernel of the
-  // pointwise conv that opens the block: dx = W^T g + g_skip.
+  // GELU backward folded into the input-gradient epilogue of the linear layer that consumes
+  // the GELU output: g_pre = (g W) * GELU'(pre).
+  for (size_t j = 1; j < s.ops.size(); ++j) {
+    Op& pr = s.ops[j - 1];
+    Op& nx = s.ops[j];
+    if (s.bf16 && pr.kind == OP_LINEAR && pr.act == 3 && nx.kind == OP_LINEAR && nx.in == pr.out) {
+      nx.gelu_from = pr.skip;
+      pr.gelu_bwd_fused = true;
+    }
+  }
+
+  // Fuse the skip-gradient add of a residual block into the input-gradient kernel of the op
+  // that opens the block: dx = W^T g + g_skip (pointwise conv, bf16 linear, attention input
+  // projection) or dx = LN'(g) + g_skip.
   for (size_t j = 0; j + 1 < s.ops.size(); ++j) {
     Op& rb = s.ops[j];
     Op& nx = s.ops[j + 1];
-    if (rb.kind == OP_RES_BEGIN && nx.kind == OP_CONV_PW && nx.in == rb.in && rb.skip >= 0) {
+    const bool can = nx.kind == OP_CONV_PW || nx.kind == OP_LAYERNORM || nx.kind == OP_MHA ||
+                     (nx.kind == OP_LINEAR && s.bf16 && nx.gelu_from < 0);
+    if (rb.kind == OP_RES_BEGIN && can && nx.in == rb.in && rb.skip >= 0) {
       nx.dgrad_add = rb.skip;
       rb.noop_bwd = true;
     }

@@ -54,7 +54,11 @@ struct Op {
   float eps = 1e-5f;
   size_t aux_off = 0, aux_bytes = 0;  // per-slot extras (statistics, probabilities, ...)
   size_t run_off = 0;                 // BatchNorm running statistics (floats, persistent)
-  int dgrad_add = -1;                 // pointwise conv: add this activation's gradient to dx
+  int dgrad_add = -1;                 // pointwise conv / LayerNorm: add this activation's gradient to dx
+  int res_in = -1;                    // bf16 linear / MHA: residual input added in the output epilogue
+  int gelu_from = -1;                 // bf16 linear behind a fused linear+GELU: that op's pre-activation;
+                                      // the input gradient is multiplied by GELU'(pre) in the epilogue
+  bool gelu_bwd_fused = false;        // linear+GELU whose GELU backward the consumer already applied
   bool noop_bwd = false;              // RES_BEGIN whose add was fused into the next dgrad
   size_t sh_off = 0, sh2_off = 0;     // bf16 weight copies (elements) in the shadow arena
   size_t wp_off = 0, wp2_off = 0;     // fp32 pointwise conv: packed forward / dgrad operands (floats)
