@@ -26,7 +26,6 @@ namespace ast {
 namespace {
 
 constexpr int BK = 64;
-constexpr int LDS_STRIDE = 64;  // elements per LDS row (= BK: rows are not padded)
 
 enum { A_ROW = 0, A_IM2COL = 1, OP_T = 2, B_ROW = 0, B_T_SHIFT = 3 };
 enum { E_BF16 = 0, E_PART = 1 };
@@ -75,9 +74,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
 // halves of a sweep with 8 distinct chunks each, and so do the transposed writes of the
 // weight-gradient operands (16 rows 8 apart, one chunk).  Measured on MI355X: 210 B/clk/CU
 // for the reads against 80 for a 144-byte row stride with chunk ^= row >> 3.
+template <int BKT>
 __device__ __forceinline__ int lds_off(int row, int c16) {
-  const int prow = (row & ~9) | ((row & 1) << 3) | ((row >> 3) & 1);
-  return prow * LDS_STRIDE + ((c16 ^ (row & 7) ^ ((row >> 4) & 7)) << 3);
+  if (BKT == 64) {
+    const int prow = (row & ~9) | ((row & 1) << 3) | ((row >> 3) & 1);
+    return prow * 64 + ((c16 ^ (row & 7) ^ ((row >> 4) & 7)) << 3);
+  }
+  // deeper tiles (rows of 256 bytes or more = whole bank sweeps): 16 consecutive rows reading
+  // the same chunk must land in 16 different 16-byte slots of a sweep
+  return row * BKT + ((c16 ^ (row & 15)) << 3);
 }
 
 __device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
@@ -86,11 +91,14 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
   return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
 }
 
-template <int WTM, int WTN, int AMODE, int BMODE, int EMODE, bool DBUF, bool FASTC, int PF = 1>
+template <int WTM, int WTN, int AMODE, int BMODE, int EMODE, bool DBUF, bool FASTC, int PF = 1, int BKT = 64>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
+  static_assert(BKT == 64 || (AMODE == A_ROW && BMODE == B_ROW), "deep K-tiles: plain row operands only");
+  constexpr int CPR = BKT / 8;    // 16-byte chunks per LDS row
+  constexpr int RPP = 256 / CPR;  // rows staged per pass of the block
   constexpr int BM = 2 * WTM, BN = 2 * WTN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  constexpr int STAGE = (BM + BN) * LDS_STRIDE;  // elements per buffer
+  constexpr int STAGE = (BM + BN) * BKT;  // elements per buffer
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
 
@@ -112,7 +120,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   const long n0 = (long)(tile % g.tiles_n) * BN;
   const long kbeg = (long)split * g.k_per_split;
   const long kend = min(kbeg + g.k_per_split, g.K);
-  const int nk = (int)((kend - kbeg + BK - 1) / BK);
+  const int nk = (int)((kend - kbeg + BKT - 1) / BKT);
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -125,15 +133,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   // ---------------- staging
   constexpr bool ROWMODE = (AMODE != OP_T);
   // row mode: 16-byte chunks, 8 per row; slot j of a thread: chunk tid + 256*j -> row (tid>>3) + 32*j
-  constexpr int NA = ROWMODE ? BM / 32 : 0;  // slots holding A chunks
-  constexpr int NB = ROWMODE ? BN / 32 : 0;
+  constexpr int NA = ROWMODE ? BM / RPP : 0;  // slots holding A chunks
+  constexpr int NB = ROWMODE ? BN / RPP : 0;
   // transposed mode: tasks of 4(k) x 8(cols); 16 k-quads per tile
   constexpr int TASKS_A = 2 * BM, TASKS_B = 2 * BN;
   constexpr int NTASK = ROWMODE ? 0 : (TASKS_A + TASKS_B) / 256;
   // register staging: PF K-tiles in flight (one LDS buffer), one otherwise
   constexpr int NSLOT = ROWMODE ? (NA + NB) : NTASK * 4;
   uint4 rgs[DBUF ? 1 : PF][NSLOT];
-  const int kc = tid & 7;  // row mode: which 8-element chunk of the 64-wide K-tile
+  const int kc = tid % CPR;  // row mode: which 8-element chunk of the K-tile
+  const int kr = tid / CPR;  // and which row of a pass
 
   // Row mode: per slot the element offset of the row (without the K position), so that the
   // per-tile address is one add.  Implicit GEMM: offset of the row's own pixel and its (y, x).
@@ -145,7 +154,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     const int HWi = AMODE == A_IM2COL ? g.H * g.W : 1;
 #pragma unroll
     for (int j = 0; j < NA; ++j) {
-      long row = m0 + (tid >> 3) + 32 * j;
+      long row = m0 + kr + RPP * j;
       a_off[j] = 0;
       a_yx[j] = -1;
       if (row < g.M) {
@@ -162,7 +171,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     }
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-      long row = n0 + (tid >> 3) + 32 * j;
+      long row = n0 + kr + RPP * j;
       b_ok[j] = row < g.N;
       b_off[j] = b_ok[j] ? row * g.ldb + kc * 8 : 0;
     }
@@ -236,7 +245,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   // is padding or out of range) and zeroed by a select afterwards: no branches, so the
   // loads of a tile issue back to back.
   auto load_tile = [&](int kt, uint4* rg) {
-    const long k0 = kbeg + (long)kt * BK;
+    const long k0 = kbeg + (long)kt * BKT;
     if (BUFPATH) {
       const bool kv = k0 + kc * 8 < kend;
       unsigned tapbit = 1u, da, db;
@@ -334,14 +343,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 
   auto store_tile = [&](int buf, const uint4* rg) {
     bf16_t* sA = smem + buf * STAGE;
-    bf16_t* sB = sA + BM * LDS_STRIDE;
+    bf16_t* sB = sA + BM * BKT;
     if (ROWMODE) {
 #pragma unroll
       for (int j = 0; j < NA; ++j)
-        *reinterpret_cast<uint4*>(&sA[lds_off((tid >> 3) + 32 * j, kc)]) = rg[j];
+        *reinterpret_cast<uint4*>(&sA[lds_off<BKT>(kr + RPP * j, kc)]) = rg[j];
 #pragma unroll
       for (int j = 0; j < NB; ++j)
-        *reinterpret_cast<uint4*>(&sB[lds_off((tid >> 3) + 32 * j, kc)]) = rg[NA + j];
+        *reinterpret_cast<uint4*>(&sB[lds_off<BKT>(kr + RPP * j, kc)]) = rg[NA + j];
     } else {
 #pragma unroll
       for (int j = 0; j < NTASK; ++j) {
@@ -362,8 +371,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
           lo.y = __builtin_amdgcn_perm(r3[w], r2[w], 0x05040100u);
           hi.x = __builtin_amdgcn_perm(r1[w], r0[w], 0x07060302u);  // high halves
           hi.y = __builtin_amdgcn_perm(r3[w], r2[w], 0x07060302u);
-          *reinterpret_cast<uint2*>(base + lds_off(mc * 8 + 2 * w, kq >> 1) + (kq & 1) * 4) = lo;
-          *reinterpret_cast<uint2*>(base + lds_off(mc * 8 + 2 * w + 1, kq >> 1) + (kq & 1) * 4) = hi;
+          *reinterpret_cast<uint2*>(base + lds_off<64>(mc * 8 + 2 * w, kq >> 1) + (kq & 1) * 4) = lo;
+          *reinterpret_cast<uint2*>(base + lds_off<64>(mc * 8 + 2 * w + 1, kq >> 1) + (kq & 1) * 4) = hi;
         }
       }
     }
@@ -372,16 +381,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
   const int lrow = lane & 31, lgrp = lane >> 5;
   auto mma_tile = [&](int buf) {
     const bf16_t* sA = smem + buf * STAGE;
-    const bf16_t* sB = sA + BM * LDS_STRIDE;
+    const bf16_t* sB = sA + BM * BKT;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+    for (int ks = 0; ks < BKT / 16; ++ks) {
       bf16x8 af[TM], bfr[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(&sA[lds_off(wm * WTM + i * 32 + lrow, ks * 2 + lgrp)]);
+        af[i] = *reinterpret_cast<const bf16x8*>(&sA[lds_off<BKT>(wm * WTM + i * 32 + lrow, ks * 2 + lgrp)]);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(&sB[lds_off(wn * WTN + j * 32 + lrow, ks * 2 + lgrp)]);
+        bfr[j] = *reinterpret_cast<const bf16x8*>(&sB[lds_off<BKT>(wn * WTN + j * 32 + lrow, ks * 2 + lgrp)]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -599,9 +608,9 @@ void launch_colsum(hipStream_t st, const bf16_t* g, float* G, float* ws, long R,
   KLAUNCH(colsum_final_kernel, dim3((unsigned)cdivl(C, 16)), dim3(256), 0, st, ws, G, C, (int)blocks);
 }
 
-template <int WTM, int WTN, bool DBUF>
+template <int WTM, int WTN, bool DBUF, int BKT = 64>
 constexpr size_t lds_bytes() {
-  size_t stage = (size_t)(2 * WTM + 2 * WTN) * LDS_STRIDE * sizeof(bf16_t);
+  size_t stage = (size_t)(2 * WTM + 2 * WTN) * BKT * sizeof(bf16_t);
   size_t ctile = (size_t)2 * WTM * (2 * WTN + 8) * sizeof(bf16_t);  // output tile of the epilogue
   size_t need = DBUF ? 2 * stage : stage;
   return need > ctile ? need : ctile;
@@ -623,17 +632,17 @@ constexpr const char* fwd_name() {
   return WTM == 128 ? "gemm_bf16_kernel<256x128,rows>" : (WTM == 64 ? "gemm_bf16_kernel<128x128,rows>" : "gemm_bf16_kernel<64x64,rows>");
 }
 
-template <int WTM, int WTN, int AMODE, bool DBUF, bool FASTC, int PF>
+template <int WTM, int WTN, int AMODE, bool DBUF, bool FASTC, int PF, int BKT = 64>
 void launch_tile_c(hipStream_t st, GemmArgs& g) {
   long tm = cdivl(g.M, 2 * WTM), tn = cdivl(g.N, 2 * WTN);
   g.tiles_n = (int)tn;
   g.tiles_mn = (int)(tm * tn);
   g.taps = 1;
-  g.k_per_split = cdivl(g.K, BK) * BK;
+  g.k_per_split = cdivl(g.K, BKT) * BKT;
   g.a_bytes = (unsigned)((AMODE == A_IM2COL ? g.M * g.C : g.M * g.lda) * 2);
   g.b_bytes = (unsigned)(g.N * g.ldb * 2);
-  auto kern = gemm_bf16_kernel<WTM, WTN, AMODE, B_ROW, E_BF16, DBUF, FASTC, PF>;
-  constexpr size_t lds = lds_bytes<WTM, WTN, DBUF>();
+  auto kern = gemm_bf16_kernel<WTM, WTN, AMODE, B_ROW, E_BF16, DBUF, FASTC, PF, BKT>;
+  constexpr size_t lds = lds_bytes<WTM, WTN, DBUF, BKT>();
   static bool once = false;  // more than 64 KiB of dynamic LDS has to be allowed per kernel
   if (!once) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -642,19 +651,24 @@ void launch_tile_c(hipStream_t st, GemmArgs& g) {
   KLAUNCH_NAMED((fwd_name<WTM, AMODE>()), kern, dim3((unsigned)(tm * tn), 1, 1), dim3(256), lds, st, g);
 }
 
-template <int WTM, int WTN, int AMODE, bool DBUF, int PF = 1>
+template <int WTM, int WTN, int AMODE, bool DBUF, int PF = 1, int BKT = 64>
 void launch_tile(hipStream_t st, GemmArgs& g) {
   if (AMODE == A_IM2COL && !g.fastc) launch_tile_c<WTM, WTN, AMODE, DBUF, false, 1>(st, g);
-  else launch_tile_c<WTM, WTN, AMODE, DBUF, true, PF>(st, g);
+  else launch_tile_c<WTM, WTN, AMODE, DBUF, true, PF, BKT>(st, g);
 }
 
-// experiment switch: ASTEROID_GEMM_PF=<int> overrides the prefetch depth
+// experiment switches: ASTEROID_GEMM_PF=<int> overrides the prefetch depth, ASTEROID_GEMM_BK the
+// K-tile depth of the plain-row products
+int env_int(const char* name) {
+  const char* e = getenv(name);
+  return e ? atoi(e) : -1;
+}
 int gemm_pf() {
-  static int v = -2;
-  if (v == -2) {
-    const char* e = getenv("ASTEROID_GEMM_PF");
-    v = e ? atoi(e) : -1;
-  }
+  static int v = env_int("ASTEROID_GEMM_PF");
+  return v;
+}
+int gemm_bk() {
+  static int v = env_int("ASTEROID_GEMM_BK");
   return v;
 }
 
@@ -665,14 +679,30 @@ void launch_fwd_like(hipStream_t st, GemmArgs& g) {
   switch (gemm_variant()) {
     case 1: launch_tile<64, 64, AMODE, true>(st, g); return;
     case 5: launch_tile<128, 64, AMODE, false>(st, g); return;
-    case 6: launch_tile<128, 64, AMODE, false, 2>(st, g); return;
-    case 7: launch_tile<128, 64, AMODE, false, 3>(st, g); return;
     default: break;
+  }
+  const int pf = gemm_pf(), bk = gemm_bk();
+  const bool big = blocks(128, 128) >= 256;
+  if constexpr (AMODE == A_ROW) {
+    // Deeper K-tiles (fewer, longer steps) were measured on the transformer products
+    // (4096 x {512,1536,2048} x {512,2048}): no gain over 64, so they stay an experiment switch.
+    if (bk > 64 && g.K >= 256) {
+      if (big) {
+        if (pf == 2) launch_tile<64, 64, AMODE, false, 2, 128>(st, g);
+        else launch_tile<64, 64, AMODE, false, 1, 128>(st, g);
+      } else if (bk == 128) {
+        if (pf == 1) launch_tile<32, 32, AMODE, false, 1, 128>(st, g);
+        else launch_tile<32, 32, AMODE, false, 2, 128>(st, g);
+      } else {
+        if (pf == 1) launch_tile<32, 32, AMODE, false, 1, 256>(st, g);
+        else launch_tile<32, 32, AMODE, false, 2, 256>(st, g);
+      }
+      return;
+    }
   }
   // measured on MI355X: more resident blocks beat bigger tiles (the loop is latency-bound),
   // so the 128x128 tile with one LDS buffer (3 blocks per CU) is the default
-  const int pf = gemm_pf();
-  if (blocks(128, 128) >= 256) {
+  if (big) {
     if (pf == 2) launch_tile<64, 64, AMODE, false, 2>(st, g);
     else launch_tile<64, 64, AMODE, false, 1>(st, g);
   } else {
