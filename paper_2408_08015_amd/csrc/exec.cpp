@@ -179,14 +179,16 @@ void bwd_op(Ctx& c, const Op& op) {
       const Act& O = s.acts[op.out];
       cb g = (cb)grad_ptr(c, op.out);
       char* sc = scratch(c, op);
-      if (op.act) {  // mask by the ReLU output
+      if (op.act && !op.relu_bwd_fused) {  // mask by the ReLU output
         bf16_t* gm = reinterpret_cast<bf16_t*>(sc);
         act_bwd_bf16(st, g, (cb)act_ptr(c, op.out), gm, O.elems, op.act);
         g = gm;
         sc += align256(O.bytes);
       }
       hipStream_t sw = fork_side(c);
-      if (gin) conv_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin, I.n, I.h, I.w, op.cin, op.cout, op.k);
+      if (gin)
+        conv_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin,
+                        op.relu_from >= 0 ? (cb)act_ptr(c, op.relu_from) : nullptr, I.n, I.h, I.w, op.cin, op.cout, op.k);
       conv_bf16_wgrad(sw, g, (cb)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr, sc,
                       I.n, I.h, I.w, op.cin, op.cout, op.k);
       break;

@@ -46,7 +46,9 @@ struct GemmArgs {
   long ldc;
   const float* bias;
   const bf16_t* add;   // optional residual input [M][ldc], added to the (rounded) output
-  const bf16_t* gmul;  // optional pre-activation [M][ldc]: the output is multiplied by GELU'(pre)
+  const bf16_t* gmul;  // optional [M][ldc] tensor t: the output is multiplied by GELU'(t), or
+                       // (gmul_relu) zeroed where t <= 0 (ReLU mask by the activation's output)
+  int gmul_relu;
   int act;
   int tiles_n;         // number of tiles along N
   int tiles_mn;        // number of output tiles; block id = (split * taps + tap) * tiles_mn + tile
@@ -488,6 +490,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             float a0 = __uint_as_float(vw[w] << 16), a1 = __uint_as_float(vw[w] & 0xffff0000u);
             const float b0 = __uint_as_float(ow[w] << 16), b1 = __uint_as_float(ow[w] & 0xffff0000u);
             if (g.add) { a0 += b0; a1 += b1; }
+            else if (g.gmul_relu) { a0 = b0 > 0.f ? a0 : 0.f; a1 = b1 > 0.f ? a1 : 0.f; }
             else { a0 *= gelu_grad_f(b0); a1 *= gelu_grad_f(b1); }
             vw[w] = (uint32_t)f2bf(a0) | ((uint32_t)f2bf(a1) << 16);
           }
@@ -508,8 +511,15 @@ __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float* __restri
   const long i = (long)blockIdx.x * 64 + o;
   const long total = (long)taps * M * N;
   float s = 0.f;
-  if (i < total)
-    for (int k = q; k < splits; k += 4) s += part[(long)k * total + i];
+  if (i < total) {
+    int k = q;
+    for (; k + 12 < splits; k += 16) {  // four independent loads in flight
+      const float v0 = part[(long)k * total + i], v1 = part[(long)(k + 4) * total + i];
+      const float v2 = part[(long)(k + 8) * total + i], v3 = part[(long)(k + 12) * total + i];
+      s += (v0 + v1) + (v2 + v3);
+    }
+    for (; k < splits; k += 4) s += part[(long)k * total + i];
+  }
   sh[q][o] = s;
   __syncthreads();
   if (q == 0 && i < total) {
@@ -517,6 +527,31 @@ __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float* __restri
     long rem = i - (long)t * M * N;  // = co * N + ci
     G[rem * taps + t] += (sh[0][o] + sh[1][o]) + (sh[2][o] + sh[3][o]);
   }
+}
+
+// taps == 1 and M*N % 4 == 0: 16-byte loads, one thread per four outputs, every split's load
+// issued before the first add; the splits are added in index order.
+__global__ __launch_bounds__(256) void reduce_wgrad4_kernel(const float4* __restrict__ part,
+                                                            float4* __restrict__ G, long total4, int splits) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total4) return;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  int k = 0;
+  for (; k + 4 <= splits; k += 4) {
+    const float4 v0 = part[(long)k * total4 + i], v1 = part[(long)(k + 1) * total4 + i];
+    const float4 v2 = part[(long)(k + 2) * total4 + i], v3 = part[(long)(k + 3) * total4 + i];
+    s.x += (v0.x + v1.x) + (v2.x + v3.x);
+    s.y += (v0.y + v1.y) + (v2.y + v3.y);
+    s.z += (v0.z + v1.z) + (v2.z + v3.z);
+    s.w += (v0.w + v1.w) + (v2.w + v3.w);
+  }
+  for (; k < splits; ++k) {
+    const float4 v = part[(long)k * total4 + i];
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  float4 gv = G[i];
+  gv.x += s.x; gv.y += s.y; gv.z += s.z; gv.w += s.w;
+  G[i] = gv;
 }
 
 // column sums of a bf16 [R][C] matrix into fp32: stage 1 partials [S][C], stage 2 accumulate
@@ -531,13 +566,22 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __res
 #pragma unroll
   for (int k = 0; k < 8; ++k) acc[k] = 0.f;
   if (rl < nrl) {
-    for (long r = r0 + rl; r < r1; r += nrl) {
-      uint4 v = *reinterpret_cast<const uint4*>(g + r * C + colg * 8);
-      const uint32_t* w = reinterpret_cast<const uint32_t*>(&v);
+    const bf16_t* gc = g + colg * 8;
+    for (long r = r0 + rl; r < r1; r += 4 * nrl) {  // four loads in flight
+      uint4 v[4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        acc[2 * k] += __uint_as_float(w[k] << 16);
-        acc[2 * k + 1] += __uint_as_float(w[k] & 0xffff0000u);
+      for (int u = 0; u < 4; ++u) {
+        const long rr = r + (long)u * nrl;
+        v[u] = rr < r1 ? *reinterpret_cast<const uint4*>(gc + rr * C) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t* w = reinterpret_cast<const uint32_t*>(&v[u]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          acc[2 * k] += __uint_as_float(w[k] << 16);
+          acc[2 * k + 1] += __uint_as_float(w[k] & 0xffff0000u);
+        }
       }
     }
   }
@@ -557,8 +601,15 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
                                                            float* __restrict__ G, int C, int S) {
   const int c = blockIdx.x * 16 + (threadIdx.x & 15), q = threadIdx.x >> 4;
   float s = 0.f;
-  if (c < C)
-    for (int k = q; k < S; k += 16) s += part[(long)k * C + c];
+  if (c < C) {
+    int k = q;
+    for (; k + 48 < S; k += 64) {  // four loads in flight
+      const float v0 = part[(long)k * C + c], v1 = part[(long)(k + 16) * C + c];
+      const float v2 = part[(long)(k + 32) * C + c], v3 = part[(long)(k + 48) * C + c];
+      s += (v0 + v1) + (v2 + v3);
+    }
+    for (; k < S; k += 16) s += part[(long)k * C + c];
+  }
   // lanes with equal (threadIdx.x & 15) inside a wavefront differ by multiples of 16
   s += __shfl_xor(s, 16, 64);
   s += __shfl_xor(s, 32, 64);
@@ -734,7 +785,12 @@ void launch_wgrad(hipStream_t st, GemmArgs& g, float* G, float* ws, int taps) {
   KLAUNCH_NAMED(BMODE == B_T_SHIFT ? "gemm_bf16_kernel<128x128,wgrad_conv>" : "gemm_bf16_kernel<128x128,wgrad_rows>", kern,
                 dim3((unsigned)(tm * tn * taps * splits), 1, 1), dim3(256), lds, st, g);
   long total = (long)taps * g.M * g.N;
-  KLAUNCH(reduce_wgrad_kernel, dim3((unsigned)cdivl(total, 64)), dim3(256), 0, st, ws, G, g.M, g.N, taps, splits);
+  // G sits at an arbitrary float offset of the parameter arena: the 16-byte path needs it aligned
+  if (taps == 1 && total % 4 == 0 && (reinterpret_cast<uintptr_t>(G) & 15) == 0)
+    KLAUNCH(reduce_wgrad4_kernel, dim3((unsigned)cdivl(total / 4, 256)), dim3(256), 0, st,
+            reinterpret_cast<const float4*>(ws), reinterpret_cast<float4*>(G), total / 4, splits);
+  else
+    KLAUNCH(reduce_wgrad_kernel, dim3((unsigned)cdivl(total, 64)), dim3(256), 0, st, ws, G, g.M, g.N, taps, splits);
 }
 
 void set_geometry(GemmArgs& g, int H, int W, int C, int k) {
@@ -764,9 +820,11 @@ void conv_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh_fwd, const 
   launch_fwd_like<A_IM2COL>(st, g);
 }
 
-void conv_bf16_dgrad(hipStream_t st, const bf16_t* gy, const bf16_t* sh_dgrad, bf16_t* dx, int N, int H, int W,
-                     int Cin, int Cout, int k) {
+void conv_bf16_dgrad(hipStream_t st, const bf16_t* gy, const bf16_t* sh_dgrad, bf16_t* dx, const bf16_t* relu_out,
+                     int N, int H, int W, int Cin, int Cout, int k) {
   GemmArgs g = {};
+  g.gmul = relu_out;
+  g.gmul_relu = 1;
   g.A = gy; g.B = sh_dgrad;
   g.M = (long)N * H * W; g.N = Cin; g.K = (long)k * k * Cout;
   g.ldb = g.K;

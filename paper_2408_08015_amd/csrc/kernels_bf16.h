@@ -24,9 +24,10 @@ size_t conv_bf16_ws_bytes(int N, int H, int W, int Cin, int Cout, int k);
 // y = act(conv(x) + bias)
 void conv_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh_fwd, const float* bias, bf16_t* y,
                    int N, int H, int W, int Cin, int Cout, int k, int act);
-// dx = conv^T(g)
-void conv_bf16_dgrad(hipStream_t st, const bf16_t* g, const bf16_t* sh_dgrad, bf16_t* dx, int N, int H,
-                     int W, int Cin, int Cout, int k);
+// dx = conv^T(g); with `relu_out` ([N][H][W][Cin], may be NULL: the output of a ReLU that feeds this
+// conv) dx is zeroed where relu_out <= 0: that ReLU's backward, folded into the epilogue.
+void conv_bf16_dgrad(hipStream_t st, const bf16_t* g, const bf16_t* sh_dgrad, bf16_t* dx, const bf16_t* relu_out,
+                     int N, int H, int W, int Cin, int Cout, int k);
 // GW[Cout][Cin][k][k] += sum_pixels g x ; Gb[Cout] += sum_pixels g.  `ws` holds
 // conv_bf16_ws_bytes().
 void conv_bf16_wgrad(hipStream_t st, const bf16_t* g, const bf16_t* x, float* GW, float* Gb, void* ws,

@@ -269,6 +269,11 @@ ast_status build_plan(Stage& s, std::string& err) {
       nx.gelu_from = pr.skip;
       pr.gelu_bwd_fused = true;
     }
+    // likewise the ReLU of a fused conv+ReLU, masked by its output: g_pre = (conv^T g) * [y > 0]
+    if (s.bf16 && pr.kind == OP_CONV_IGEMM && pr.act == 1 && nx.kind == OP_CONV_IGEMM && nx.in == pr.out) {
+      nx.relu_from = pr.out;
+      pr.relu_bwd_fused = true;
+    }
   }
 
   // Fuse the skip-gradient add of a residual block into the input-gradient kernel of the op

@@ -59,6 +59,9 @@ struct Op {
   int gelu_from = -1;                 // bf16 linear behind a fused linear+GELU: that op's pre-activation;
                                       // the input gradient is multiplied by GELU'(pre) in the epilogue
   bool gelu_bwd_fused = false;        // linear+GELU whose GELU backward the consumer already applied
+  int relu_from = -1;                 // bf16 conv behind a fused conv+ReLU: that op's output; the input
+                                      // gradient is masked by it in the epilogue
+  bool relu_bwd_fused = false;        // conv+ReLU whose ReLU backward the consumer already applied
   bool noop_bwd = false;              // RES_BEGIN whose add was fused into the next dgrad
   size_t sh_off = 0, sh2_off = 0;     // bf16 weight copies (elements) in the shadow arena
   size_t wp_off = 0, wp2_off = 0;     // fp32 pointwise conv: packed forward / dgrad operands (floats)
