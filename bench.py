@@ -58,6 +58,13 @@ def kernel_model(cfg):
             if not first or cfg.needs_input_grad:                                   # input gradient
                 extra = 4 * cin * nq if (res_open and cfg.layers[i - 1]["kind"] == "res_begin") else 0
                 out.setdefault(cls(cin, cout), []).append(4 * (cin + cout) * nq + extra)
+        if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 1 and L["groups"] == 1:
+            hw = shape[1] * shape[2]
+            name = "pw_wgrad_f32_kernel<true>" if hw % 4 == 0 else "pw_wgrad_f32_kernel<false>"
+            out.setdefault(name, []).append(4 * (L["cin"] + L["cout"]) * B * hw)          # g and x in
+        if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"]:
+            oc, oh, ow = oshape
+            out.setdefault("dw3x3_fwd_f32_kernel", []).append(4 * B * (shape[0] * shape[1] * shape[2] + oc * oh * ow))
         if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"]:
             c, h, w = shape
             if w % 4 == 0 and (L["stride"] == 1 or h % 2 == 0):
@@ -66,6 +73,11 @@ def kernel_model(cfg):
                 out.setdefault(name, []).append(4 * B * (2 * c * h * w + oc * oh * ow))   # g, x in; dx out
         if k == "batchnorm2d":
             c, h, w = shape
+            vec = "<true>" if (h * w) % 4 == 0 else "<false>"
+            n_el = B * c * h * w
+            out.setdefault("bn_stats_partial_kernel" + vec, []).append(4 * n_el)
+            out.setdefault("bn_apply_kernel" + vec, []).append(8 * n_el)                  # (+4 with a fused skip)
+            out.setdefault("bn_bwd_partial_kernel" + vec, []).append(8 * n_el)
             # g and x in, dx out (no dx for a BatchNorm on the stage input when it is not wanted)
             out.setdefault("bn_bwd_apply_kernel", []).append((12 if (not first or cfg.needs_input_grad) else 8) * B * c * h * w)
         if k == "conv2d" and cfg.dtype == "bf16":
@@ -90,6 +102,16 @@ def kernel_model(cfg):
                 out.setdefault(lcls(rows, cout), []).append(2 * rows * cin * cout)      # forward
                 out.setdefault(lcls(rows, cin), []).append(2 * rows * cin * cout)       # input gradient
                 out.setdefault("gemm_bf16_kernel<128x128,wgrad_rows>", []).append(2 * rows * cin * cout)
+        if cfg.dtype == "bf16" and k == "mha":
+            S, D = shape
+            fl = 4 * S * D * B * S                                            # QK^T and PV
+            out.setdefault("attention_fwd_kernel", []).append(fl)
+            out.setdefault("attention_bwd_dkv_kernel", []).append(2 * fl)     # S, dP, dV, dK
+            out.setdefault("attention_bwd_dq_kernel", []).append(int(1.5 * fl))   # S, dP, dQ
+        if cfg.dtype == "bf16" and k == "layernorm":
+            S, D = shape
+            out.setdefault("layernorm_fwd_kernel", []).append(4 * B * S * D)      # bf16 in, bf16 out
+            out.setdefault("layernorm_bwd_kernel", []).append(6 * B * S * D)      # g, x in; dx out
         if k == "res_add":
             res_open = False
         if k not in ("res_begin",):
@@ -116,6 +138,10 @@ TRAFFIC_BYTES = {
     ("cfg2", "bn_bwd_apply_kernel"): int((17545.3 / 0.5012 + 17256.0) * 1024),
     ("cfg4", "gemm_bf16_kernel<128x128,im2col>"): int((31015.2 / 0.5005 + 45994.7) * 1024),
 }
+
+
+def kernel_bound(name):
+    return "mfma" if name.startswith(("gemm_bf16", "attention")) else "hbm"
 
 
 def dominant_kernel(cfg, workload):
@@ -204,9 +230,21 @@ def run(args):
         tot = sum(v[1] for v in prof.values())
         print("per-kernel HIP-event times over %d steps (sum %.3f ms/step):" % (args.steps, tot / args.steps),
               file=sys.stderr)
+        km = kernel_model(cfg)
         for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1]):
-            print("  %-48s launches/step %6.1f  us/launch %9.2f  ms/step %8.4f  %5.1f%%" %
-                  (k, v[0] / args.steps, v[1] * 1e3 / v[0], v[1] / args.steps, 100 * v[1] / tot), file=sys.stderr)
+            line = "  %-48s launches/step %6.1f  us/launch %9.2f  ms/step %8.4f  %5.1f%%" % (
+                k, v[0] / args.steps, v[1] * 1e3 / v[0], v[1] / args.steps, 100 * v[1] / tot)
+            units = [u for n, u in km.items() if k.startswith(n)]
+            if units:       # algorithmic work per launch / HIP-event time per launch
+                per = sum(units[0]) / len(units[0])
+                avg_s = v[1] * 1e-3 / v[0]
+                if kernel_bound(k) == "hbm":
+                    line += "  %7.1f MB/launch %7.0f GB/s  %4.0f%% of HBM peak" % (
+                        per / 1e6, per / avg_s / 1e9, 100 * per / avg_s / 1e9 / HBM_PEAK_GBS)
+                else:
+                    line += "  %7.2f GF/launch %7.0f TF/s  %4.0f%% of MFMA peak" % (
+                        per / 1e9, per / avg_s / 1e12, 100 * per / avg_s / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype])
+            print(line, file=sys.stderr)
     mem = st.memory()
     st.close()
 

@@ -420,17 +420,29 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
     for (int p = 0; p < PF; ++p)
       if (p < nk) load_tile(p, rgs[p]);
-    for (int kt0 = 0; kt0 < nk; kt0 += PF) {
+    // Steady state without a branch around any load: the compiler's wait counts are exact
+    // only then (a conditional load makes it wait for every outstanding one, which would
+    // undo the prefetch depth).
+    int kt0 = 0;
+    for (; kt0 + 2 * PF <= nk; kt0 += PF) {
 #pragma unroll
       for (int p = 0; p < PF; ++p) {
-        const int kt = kt0 + p;
-        if (kt < nk) {  // uniform
-          __syncthreads();
-          store_tile(0, rgs[p]);
-          __syncthreads();
-          if (kt + PF < nk) load_tile(kt + PF, rgs[p]);
-          mma_tile(0);
-        }
+        __syncthreads();
+        store_tile(0, rgs[p]);
+        __syncthreads();
+        load_tile(kt0 + p + PF, rgs[p]);
+        mma_tile(0);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 2 * PF; ++r) {  // the last tiles: tile kt0 + r sits in slot r % PF
+      const int kt = kt0 + r;
+      if (kt < nk) {  // uniform
+        __syncthreads();
+        store_tile(0, rgs[r % PF]);
+        __syncthreads();
+        if (kt + PF < nk) load_tile(kt + PF, rgs[r % PF]);
+        mma_tile(0);
       }
     }
     __syncthreads();
