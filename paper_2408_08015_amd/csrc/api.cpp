@@ -59,6 +59,11 @@ void free_stage(ast::Stage& s) {
   if (s.V) (void)hipFree(s.V);
   if (s.shadow) (void)hipFree(s.shadow);
   if (s.running) (void)hipFree(s.running);
+  if (s.red_tasks) (void)hipFree(s.red_tasks);
+  if (s.red_block_task) (void)hipFree(s.red_block_task);
+  s.red_tasks = nullptr;
+  s.red_block_task = nullptr;
+  s.red_nblocks = 0;
   if (s.wpack) (void)hipFree(s.wpack);
   s.wpack = nullptr;
   if (s.ws) (void)hipFree(s.ws);
@@ -164,7 +169,8 @@ ast_status asteroid_stage_create(const ast_layer* layers, int32_t n_layers, cons
   if ((e = hipMemcpy(s.W, w0.data(), pbytes, hipMemcpyHostToDevice)) != hipSuccess) return bail(e, "create: memcpy");
   s.mb_slot.assign(cfg->M, -1);
   for (int k = cfg->K - 1; k >= 0; --k) s.free_slots.push_back(k);
-  r = ast::refresh_shadow(s, err);
+  r = ast::build_reduce_tasks(s, err);
+  if (r == AST_OK) r = ast::refresh_shadow(s, err);
   if (r == AST_OK && (e = hipStreamSynchronize(s.stream)) != hipSuccess) return bail(e, "create: sync");
   if (r != AST_OK) {
     free_stage(s);

@@ -1,5 +1,7 @@
 // Plan execution: forward, backward and optimizer step of a stage, as kernel launches
 // on the stage's stream.  No allocation, no host synchronisation.
+#include <vector>
+
 #include "kernels.h"
 #include "kernels_bf16.h"
 #include "stage.h"
@@ -151,15 +153,15 @@ void bwd_op(Ctx& c, const Op& op) {
       if (gin)
         pw_conv_f32(st, s.wpack + op.wp2_off, g, (float*)gin, nullptr,
                     op.dgrad_add >= 0 ? (cf)grad_ptr(c, op.dgrad_add) : nullptr, I.n, op.cout, op.cin, HW);
-      pw_wgrad_f32(sw, g, (cf)act_ptr(c, op.in), reinterpret_cast<float*>(scratch(c, op)), s.G + op.w_off, I.n,
-                   op.cin, op.cout, HW);
+      pw_wgrad_f32(sw, g, (cf)act_ptr(c, op.in), reinterpret_cast<float*>(scratch(c, op)),
+                   s.red_nblocks ? nullptr : s.G + op.w_off, I.n, op.cin, op.cout, HW);
       if (op.has_bias) channel_sum_acc_f32(sw, g, s.G + op.b_off, I.n, op.cout, HW);
       break;
     }
     case OP_CONV_DW: {
       cf g = (cf)grad_ptr(c, op.out);
       dw3x3_bwd_f32(st, g, (cf)act_ptr(c, op.in), s.W + op.w_off, (float*)gin, reinterpret_cast<float*>(scratch(c, op)),
-                    s.G + op.w_off, I.n, I.c, I.h, I.w, op.stride);
+                    s.red_nblocks ? nullptr : s.G + op.w_off, I.n, I.c, I.h, I.w, op.stride);
       break;
     }
     case OP_CONV_DIRECT: {
@@ -325,11 +327,50 @@ ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, std::strin
   s.cur_dy = dy;
   s.cur_dx = dx;
   for (int j = (int)s.ops.size() - 1; j >= 0; --j) bwd_op(c, s.ops[j]);
+  if (s.red_nblocks)  // every layer's partials -> G, one launch
+    reduce_tasks_f32(s.stream, static_cast<const RedTask*>(s.red_tasks), s.red_block_task, s.red_nblocks);
   if (c.forked) {  // join: whatever follows on the main stream sees every gradient
     (void)hipEventRecord(s.join_ev, s.side);
     (void)hipStreamWaitEvent(s.stream, s.join_ev, 0);
   }
   return check_launch(err, "backward");
+}
+
+ast_status build_reduce_tasks(Stage& s, std::string& err) {
+  if (s.bf16) return AST_OK;
+  std::vector<RedTask> tasks;
+  std::vector<unsigned short> block_task;
+  for (const Op& op : s.ops) {
+    const Act& I = s.acts[op.in];
+    RedTask t = {};
+    t.part = reinterpret_cast<const float*>(s.ws + s.scratch_off + op.sc_off);
+    t.G = s.G + op.w_off;
+    if (op.kind == OP_CONV_PW) {
+      t.n = (unsigned)(op.cin * op.cout);
+      t.parts = (unsigned)pw_wgrad_f32_parts(I.n, op.cin, op.cout, I.h * I.w);
+    } else if (op.kind == OP_CONV_DW) {
+      t.n = (unsigned)(I.c * 9);
+      t.parts = (unsigned)I.n;
+    } else {
+      continue;
+    }
+    if (tasks.size() >= 65535) return AST_OK;  // absurdly long stage: keep the per-layer launches
+    t.block0 = (unsigned)block_task.size();
+    for (unsigned b = 0; b < (t.n + 63) / 64; ++b) block_task.push_back((unsigned short)tasks.size());
+    tasks.push_back(t);
+  }
+  if (tasks.empty() || tasks.size() >= 65535) return AST_OK;
+  hipError_t e;
+  if ((e = hipMalloc(&s.red_tasks, tasks.size() * sizeof(RedTask))) != hipSuccess ||
+      (e = hipMalloc((void**)&s.red_block_task, block_task.size() * sizeof(unsigned short))) != hipSuccess ||
+      (e = hipMemcpy(s.red_tasks, tasks.data(), tasks.size() * sizeof(RedTask), hipMemcpyHostToDevice)) != hipSuccess ||
+      (e = hipMemcpy(s.red_block_task, block_task.data(), block_task.size() * sizeof(unsigned short),
+                     hipMemcpyHostToDevice)) != hipSuccess) {
+    err = std::string("reduction task table: ") + hipGetErrorString(e);
+    return e == hipErrorOutOfMemory ? AST_ENOMEM : AST_EHIP;
+  }
+  s.red_nblocks = (int)block_task.size();
+  return AST_OK;
 }
 
 ast_status refresh_shadow(Stage& s, std::string& err) {

@@ -22,7 +22,8 @@ void pw_conv_f32(hipStream_t st, const float* Wp, const float* X, float* Y, cons
                  const float* add, int N, int Kdim, int Mdim, int HW);
 // Weight gradient of the pointwise convolution, split over pixel chunks:
 //   part[chunk][co][ci] = sum_{p in chunk} g[n][co][p] * x[n][ci][p];  then G += sum_chunk part.
-// `part` must hold pw_wgrad_f32_ws(N,Cin,Cout,HW) floats.
+// `part` must hold pw_wgrad_f32_ws(N,Cin,Cout,HW) floats; with G = NULL only the partials are
+// written (pw_wgrad_f32_parts of them, Cout*Cin floats each).
 size_t pw_wgrad_f32_ws(int N, int Cin, int Cout, int HW);
 void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, float* G, int N,
                   int Cin, int Cout, int HW);
@@ -31,7 +32,8 @@ void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, f
 void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int N, int C, int H,
                    int W, int stride);
 // Backward of the depthwise conv from one read of g and x: dx (skipped if NULL) and
-// G[C][3][3] += weight gradient.  `part` holds dw3x3_bwd_f32_ws(N, C) floats.
+// G[C][3][3] += weight gradient.  `part` holds dw3x3_bwd_f32_ws(N, C) floats: N partials of
+// C*9 sums; with G = NULL the reduction is left to the caller (reduce_tasks_f32).
 size_t dw3x3_bwd_f32_ws(int N, int C);
 void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part,
                    float* G, int N, int C, int H, int W, int stride);
@@ -49,6 +51,17 @@ void conv_direct_wgrad_f32(hipStream_t st, const float* g, const float* x, float
                            int H, int W, int Cout, int k, int stride, int pad, int groups);
 // G[i] += sum_c part[c*n + i], c < parts, in a fixed order.
 void reduce_parts_acc_f32(hipStream_t st, const float* part, float* G, size_t n, int parts);
+// The same reduction for a whole list of (part, G, n, parts) in ONE launch: the weight-gradient
+// kernels of a backward pass only write their partials (pass G = NULL to them) and the list is
+// reduced once at the end of the pass, instead of one few-microsecond launch per layer.
+// Block b of the launch works on task block_task[b], outputs [64*(b - block0), +64).
+struct RedTask {
+  const float* part;
+  float* G;
+  unsigned n, parts, block0, pad;
+};
+void reduce_tasks_f32(hipStream_t st, const RedTask* tasks_dev, const unsigned short* block_task_dev, int nblocks);
+int pw_wgrad_f32_parts(int N, int Cin, int Cout, int HW);  // partial count of pw_wgrad_f32
 // G[c] += sum_{n,p} g[n][c][p]
 void channel_sum_acc_f32(hipStream_t st, const float* g, float* G, int N, int C, int HW);
 

@@ -406,8 +406,37 @@ void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, f
   else
     KLAUNCH(pw_wgrad_f32_kernel<false>, grid, dim3(256), 0, st, g, x, part, Cin, Cout, HW, cps, pxw);
   size_t n = (size_t)Cin * Cout;
-  KLAUNCH(reduce_parts_acc_kernel, dim3(cdiv(n, 64)), dim3(256), 0, st, part, G, n, chunks);
+  if (G) KLAUNCH(reduce_parts_acc_kernel, dim3(cdiv(n, 64)), dim3(256), 0, st, part, G, n, chunks);
 }
+
+__global__ __launch_bounds__(256) void reduce_tasks_kernel(const RedTask* __restrict__ tasks,
+                                                           const unsigned short* __restrict__ block_task) {
+  __shared__ float sh[4][64];
+  const RedTask t = tasks[block_task[blockIdx.x]];
+  const int o = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const size_t n = t.n;
+  const size_t i = (size_t)(blockIdx.x - t.block0) * 64 + o;
+  const int parts = (int)t.parts;
+  float s = 0.f;
+  if (i < n) {
+    int c = q;
+    for (; c + 28 < parts; c += 32) {  // eight independent loads in flight
+      float v0 = t.part[(size_t)c * n + i], v1 = t.part[(size_t)(c + 4) * n + i];
+      float v2 = t.part[(size_t)(c + 8) * n + i], v3 = t.part[(size_t)(c + 12) * n + i];
+      float v4 = t.part[(size_t)(c + 16) * n + i], v5 = t.part[(size_t)(c + 20) * n + i];
+      float v6 = t.part[(size_t)(c + 24) * n + i], v7 = t.part[(size_t)(c + 28) * n + i];
+      s += ((v0 + v1) + (v2 + v3)) + ((v4 + v5) + (v6 + v7));
+    }
+    for (; c < parts; c += 4) s += t.part[(size_t)c * n + i];
+  }
+  sh[q][o] = s;
+  __syncthreads();
+  if (q == 0 && i < n) t.G[i] += (sh[0][o] + sh[1][o]) + (sh[2][o] + sh[3][o]);
+}
+void reduce_tasks_f32(hipStream_t st, const RedTask* tasks_dev, const unsigned short* block_task_dev, int nblocks) {
+  KLAUNCH(reduce_tasks_kernel, dim3(nblocks), dim3(256), 0, st, tasks_dev, block_task_dev);
+}
+int pw_wgrad_f32_parts(int N, int Cin, int Cout, int HW) { return N * cdiv(HW, 4 * wg_pxw(N, Cin, Cout, HW)); }
 
 void reduce_parts_acc_f32(hipStream_t st, const float* part, float* G, size_t n, int parts) {
   KLAUNCH(reduce_parts_acc_kernel, dim3(cdiv(n, 64)), dim3(256), 0, st, part, G, n, parts);
@@ -834,21 +863,21 @@ void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* 
     const int groups = 64 / (W / 4);
     KLAUNCH(dw3x3_bwd_s1_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
             cdiv(H, groups));
-    KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
+    if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
     return;
   }
   if (stride == 2 && W % 4 == 0 && H % 2 == 0 && W <= 256) {
     const int groups = 64 / (W / 4);
     KLAUNCH(dw3x3_bwd_s2_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
             cdiv(H / 2, groups));
-    KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
+    if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
     return;
   }
   DwGeom gm = dw_geom(N, C, H, W, stride);
   size_t lds = ((size_t)gm.ppb * ((H + 2) * (W + 2) + (gm.Ho + 2) * (gm.Wo + 2) + 9) + 36) * sizeof(float);
   (void)hipFuncSetAttribute((const void*)dw3x3_bwd_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   KLAUNCH(dw3x3_bwd_f32_kernel, dim3(cdiv(gm.NC, gm.ppb)), dim3(256), lds, st, g, x, w, dx, part, gm);
-  KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
+  if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
 }
 
 }  // namespace ast

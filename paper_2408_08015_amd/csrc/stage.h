@@ -97,6 +97,12 @@ struct Stage {
   size_t ws_bytes = 0, grad_bytes = 0;
   size_t scratch_off = 0, scratch_bytes = 0;  // per-op scratch regions (masked gradients, partials)
 
+  // fp32 stages: the per-layer reductions of weight-gradient partials into G, batched into one
+  // launch at the end of every backward pass (device-side task table, built at create)
+  void* red_tasks = nullptr;             // RedTask[]
+  unsigned short* red_block_task = nullptr;
+  int red_nblocks = 0;
+
   // Second stream for the weight-gradient kernels, which no later kernel of the same
   // backward pass depends on (NULL: everything runs on `stream`).
   hipStream_t side = nullptr;
@@ -124,5 +130,6 @@ ast_status run_forward(Stage& s, int slot, const void* x, const int32_t* labels,
 ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, std::string& err);
 ast_status run_step(Stage& s, float lr, float mu, std::string& err);
 ast_status refresh_shadow(Stage& s, std::string& err);
+ast_status build_reduce_tasks(Stage& s, std::string& err);  // after the workspace is allocated
 
 }  // namespace ast
