@@ -1,5 +1,6 @@
 // Plan execution: forward, backward and optimizer step of a stage, as kernel launches
 // on the stage's stream.  No allocation, no host synchronisation.
+#include <cstdlib>
 #include <vector>
 
 #include "kernels.h"
@@ -47,6 +48,10 @@ inline hipStream_t fork_side(Ctx& c) {
   return s.side;
 }
 inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+// attention scratch: [d_o, dqkv][row sums of dO*O][weight-gradient partials ...]
+inline size_t mha_lw_offset(int B, int S, int D, int heads) {
+  return align256((size_t)B * S * 4 * D * sizeof(bf16_t)) + align256(mha_bf16_ws_bytes(B, S, D, heads));
+}
 
 typedef const float* cf;
 typedef const bf16_t* cb;
@@ -180,19 +185,19 @@ void bwd_op(Ctx& c, const Op& op) {
     case OP_CONV_IGEMM: {
       const Act& O = s.acts[op.out];
       cb g = (cb)grad_ptr(c, op.out);
-      char* sc = scratch(c, op);
+      char* sc = scratch(c, op);  // [masked upstream gradient][weight-gradient partials]
       if (op.act && !op.relu_bwd_fused) {  // mask by the ReLU output
         bf16_t* gm = reinterpret_cast<bf16_t*>(sc);
         act_bwd_bf16(st, g, (cb)act_ptr(c, op.out), gm, O.elems, op.act);
         g = gm;
-        sc += align256(O.bytes);
       }
+      sc += align256(O.bytes);
       hipStream_t sw = fork_side(c);
       if (gin)
         conv_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin,
                         op.relu_from >= 0 ? (cb)act_ptr(c, op.relu_from) : nullptr, I.n, I.h, I.w, op.cin, op.cout, op.k);
-      conv_bf16_wgrad(sw, g, (cb)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr, sc,
-                      I.n, I.h, I.w, op.cin, op.cout, op.k);
+      conv_bf16_wgrad(sw, g, (cb)act_ptr(c, op.in), s.G + op.w_off, s.G + op.b_off, op.has_bias != 0, s.red_nblocks != 0,
+                      sc, I.n, I.h, I.w, op.cin, op.cout, op.k);
       break;
     }
     case OP_BN: {
@@ -231,20 +236,20 @@ void bwd_op(Ctx& c, const Op& op) {
         const Act& O = s.acts[op.out];
         const size_t R = (size_t)I.n * I.h * I.w;
         cb g = (cb)grad_ptr(c, op.out);
-        char* sc = scratch(c, op);
+        char* sc = scratch(c, op);  // [GELU-masked upstream gradient][weight-gradient partials]
         if (op.act == 3 && !op.gelu_bwd_fused) {
           bf16_t* gp = reinterpret_cast<bf16_t*>(sc);
           act_bwd_bf16(st, g, (cb)act_ptr(c, op.skip), gp, O.elems, 3);
           g = gp;
-          sc += align256(O.bytes);
         }
+        sc += align256(O.bytes);
         hipStream_t sw = fork_side(c);
         if (gin)
           linear_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin,
                             op.gelu_from >= 0 ? (cb)act_ptr(c, op.gelu_from) : nullptr,
                             op.dgrad_add >= 0 ? (cb)grad_ptr(c, op.dgrad_add) : nullptr, R, op.cin, op.cout);
-        linear_bf16_wgrad(sw, g, (cb)act_ptr(c, op.in), s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr,
-                          sc, R, op.cin, op.cout);
+        linear_bf16_wgrad(sw, g, (cb)act_ptr(c, op.in), s.G + op.w_off, s.G + op.b_off, op.has_bias != 0,
+                          s.red_nblocks != 0, sc, R, op.cin, op.cout);
       } else {
         cf g = (cf)grad_ptr(c, op.out);
         hipStream_t sw = fork_side(c);
@@ -265,7 +270,8 @@ void bwd_op(Ctx& c, const Op& op) {
                          (gin && op.dgrad_add >= 0) ? (cb)grad_ptr(c, op.dgrad_add) : nullptr, (bf16_t*)gin,
                          scratch(c, op), (size_t)I.n * I.h, I.c);
       // the parameter gradients only need the partials of the kernel above
-      layernorm_bwd_params_bf16(fork_side(c), scratch(c, op), s.G + op.w_off, s.G + op.b_off, (size_t)I.n * I.h, I.c);
+      if (!s.red_nblocks)
+        layernorm_bwd_params_bf16(fork_side(c), scratch(c, op), s.G + op.w_off, s.G + op.b_off, (size_t)I.n * I.h, I.c);
       break;
     case OP_MHA: {
       const int D = op.cin;
@@ -281,17 +287,20 @@ void bwd_op(Ctx& c, const Op& op) {
       bf16_t* d_o = reinterpret_cast<bf16_t*>(sc);
       bf16_t* dqkv = d_o + R * D;
       float* dsum = reinterpret_cast<float*>(sc + align256(R * 4 * D * sizeof(bf16_t)));
-      char* lw = reinterpret_cast<char*>(dsum) + align256(mha_bf16_ws_bytes(I.n, I.h, D, op.heads));
+      // partials of the two projections' weight gradients: output projection, then qkv
+      char* lw_o = sc + mha_lw_offset(I.n, I.h, D, op.heads);
+      char* lw_q = lw_o + align256(linear_bf16_ws_bytes(R, D, D));
+      const bool defer = s.red_nblocks != 0;
       cb g = (cb)grad_ptr(c, op.out);
       hipStream_t sw = fork_side(c);
       linear_bf16_dgrad(st, g, s.shadow + op.sh2_off + (size_t)3 * D * D, d_o, nullptr, nullptr, R, D, D);
-      linear_bf16_wgrad(sw, g, o, Go, Gbo, lw, R, D, D);
+      linear_bf16_wgrad(sw, g, o, Go, Gbo, true, defer, lw_o, R, D, D);
       attention_bwd_bf16(st, qkv, o, d_o, lse, dqkv, dsum, I.n, I.h, D, op.heads);
       sw = fork_side(c);
       if (gin)
         linear_bf16_dgrad(st, dqkv, s.shadow + op.sh2_off, (bf16_t*)gin, nullptr,
                           op.dgrad_add >= 0 ? (cb)grad_ptr(c, op.dgrad_add) : nullptr, R, D, 3 * D);
-      linear_bf16_wgrad(sw, dqkv, (cb)act_ptr(c, op.in), Gq, Gbq, lw, R, D, 3 * D);
+      linear_bf16_wgrad(sw, dqkv, (cb)act_ptr(c, op.in), Gq, Gbq, true, defer, lw_q, R, D, 3 * D);
       break;
     }
   }
@@ -327,8 +336,8 @@ ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, std::strin
   s.cur_dy = dy;
   s.cur_dx = dx;
   for (int j = (int)s.ops.size() - 1; j >= 0; --j) bwd_op(c, s.ops[j]);
-  if (s.red_nblocks)  // every layer's partials -> G, one launch
-    reduce_tasks_f32(s.stream, static_cast<const RedTask*>(s.red_tasks), s.red_block_task, s.red_nblocks);
+  if (s.red_nblocks)  // every layer's partials -> G, one launch (behind all of this pass's kernels)
+    reduce_tasks_f32(fork_side(c), static_cast<const RedTask*>(s.red_tasks), s.red_block_task, s.red_nblocks);
   if (c.forked) {  // join: whatever follows on the main stream sees every gradient
     (void)hipEventRecord(s.join_ev, s.side);
     (void)hipStreamWaitEvent(s.stream, s.join_ev, 0);
@@ -337,29 +346,73 @@ ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, std::strin
 }
 
 ast_status build_reduce_tasks(Stage& s, std::string& err) {
-  if (s.bf16) return AST_OK;
+  if (const char* e = getenv("ASTEROID_BATCHED_REDUCE"))
+    if (e[0] == '0') return AST_OK;  // per-layer reduction launches instead
   std::vector<RedTask> tasks;
   std::vector<unsigned short> block_task;
+  bool overflow = false;
+  auto add = [&](const float* part, float* G, size_t n, int parts, size_t stride, int taps, size_t mn) {
+    if (tasks.size() >= 65535 || n >= 0xffffffffu || stride >= 0xffffffffu) { overflow = true; return; }
+    RedTask t = {};
+    t.part = part; t.G = G;
+    t.n = (unsigned)n; t.parts = (unsigned)parts; t.stride = (unsigned)stride;
+    t.taps = (unsigned)taps; t.mn = (unsigned)mn;
+    t.block0 = (unsigned)block_task.size();
+    for (size_t b = 0; b < (n + 63) / 64; ++b) block_task.push_back((unsigned short)tasks.size());
+    tasks.push_back(t);
+  };
+  auto add_wgrad = [&](float* base, const WgradParts& wp, float* GW, float* Gb, size_t cout, size_t cin, int taps) {
+    const size_t mn = cout * cin;
+    add(base, GW, taps * mn, wp.splits, taps * mn, taps, mn);
+    if (Gb) add(base + wp.bias_off, Gb, cout, wp.bias_parts, cout, 1, cout);
+  };
   for (const Op& op : s.ops) {
     const Act& I = s.acts[op.in];
-    RedTask t = {};
-    t.part = reinterpret_cast<const float*>(s.ws + s.scratch_off + op.sc_off);
-    t.G = s.G + op.w_off;
-    if (op.kind == OP_CONV_PW) {
-      t.n = (unsigned)(op.cin * op.cout);
-      t.parts = (unsigned)pw_wgrad_f32_parts(I.n, op.cin, op.cout, I.h * I.w);
-    } else if (op.kind == OP_CONV_DW) {
-      t.n = (unsigned)(I.c * 9);
-      t.parts = (unsigned)I.n;
-    } else {
-      continue;
+    char* sc = s.ws + s.scratch_off + op.sc_off;
+    float* scf = reinterpret_cast<float*>(sc);
+    switch (op.kind) {
+      case OP_CONV_PW: {
+        const size_t n = (size_t)op.cin * op.cout;
+        add(scf, s.G + op.w_off, n, pw_wgrad_f32_parts(I.n, op.cin, op.cout, I.h * I.w), n, 1, n);
+        break;
+      }
+      case OP_CONV_DW:
+        add(scf, s.G + op.w_off, (size_t)I.c * 9, I.n, (size_t)I.c * 9, 1, (size_t)I.c * 9);
+        break;
+      case OP_CONV_IGEMM:
+        add_wgrad(reinterpret_cast<float*>(sc + align256(s.acts[op.out].bytes)),
+                  conv_bf16_wgrad_parts(I.n, I.h, I.w, op.cin, op.cout, op.k), s.G + op.w_off,
+                  op.has_bias ? s.G + op.b_off : nullptr, op.cout, op.cin, op.k * op.k);
+        break;
+      case OP_LINEAR:
+        if (s.bf16)
+          add_wgrad(reinterpret_cast<float*>(sc + align256(s.acts[op.out].bytes)),
+                    linear_bf16_wgrad_parts((size_t)I.n * I.h * I.w, op.cin, op.cout), s.G + op.w_off,
+                    op.has_bias ? s.G + op.b_off : nullptr, op.cout, op.cin, 1);
+        break;
+      case OP_MHA: {
+        const int D = op.cin;
+        const size_t R = (size_t)I.n * I.h;
+        float* Gq = s.G + op.w_off;
+        float* Gbq = Gq + (size_t)3 * D * D;
+        float* Go = Gbq + 3 * D;
+        float* Gbo = Go + (size_t)D * D;
+        char* lw_o = sc + mha_lw_offset(I.n, I.h, D, op.heads);
+        char* lw_q = lw_o + align256(linear_bf16_ws_bytes(R, D, D));
+        add_wgrad(reinterpret_cast<float*>(lw_o), linear_bf16_wgrad_parts(R, D, D), Go, Gbo, D, D, 1);
+        add_wgrad(reinterpret_cast<float*>(lw_q), linear_bf16_wgrad_parts(R, D, 3 * D), Gq, Gbq, (size_t)3 * D, D, 1);
+        break;
+      }
+      case OP_LAYERNORM: {
+        const int parts = layernorm_bwd_parts((size_t)I.n * I.h);
+        add(scf, s.G + op.w_off, I.c, parts, (size_t)2 * I.c, 1, I.c);          // dgamma
+        add(scf + I.c, s.G + op.b_off, I.c, parts, (size_t)2 * I.c, 1, I.c);    // dbeta
+        break;
+      }
+      default: break;
     }
-    if (tasks.size() >= 65535) return AST_OK;  // absurdly long stage: keep the per-layer launches
-    t.block0 = (unsigned)block_task.size();
-    for (unsigned b = 0; b < (t.n + 63) / 64; ++b) block_task.push_back((unsigned short)tasks.size());
-    tasks.push_back(t);
   }
-  if (tasks.empty() || tasks.size() >= 65535) return AST_OK;
+  if (tasks.empty() || overflow) return AST_OK;  // (absurdly long stage: per-layer launches)
   hipError_t e;
   if ((e = hipMalloc(&s.red_tasks, tasks.size() * sizeof(RedTask))) != hipSuccess ||
       (e = hipMalloc((void**)&s.red_block_task, block_task.size() * sizeof(unsigned short))) != hipSuccess ||

@@ -647,28 +647,42 @@ int choose_splits(long tiles, long K) {
 
 constexpr int WG_T = 64;  // wave tile of the weight-gradient kernels (block tile 128 x 128)
 
-size_t wgrad_ws_floats(long M, long N, long K, int taps) {
+// number of K-splits (= partial copies) launch_wgrad uses
+int wgrad_splits(long M, long N, long K, int taps) {
   long tiles = cdivl(M, 2 * WG_T) * cdivl(N, 2 * WG_T) * taps;
   int s = choose_splits(tiles, K);
-  return (size_t)s * taps * M * N;
+  long kps = cdivl(cdivl(K, s), BK) * BK;
+  return (int)cdivl(K, kps);
 }
+size_t wgrad_ws_floats(long M, long N, long K, int taps) {
+  long tiles = cdivl(M, 2 * WG_T) * cdivl(N, 2 * WG_T) * taps;
+  return (size_t)choose_splits(tiles, K) * taps * M * N;
+}
+// weight partials at ws[0, bias_off), bias partials from ws + bias_off (both 64-float aligned)
+static size_t align64f(size_t f) { return (f + 63) / 64 * 64; }
 constexpr int kColsumBlocks = 256;
 size_t colsum_ws_floats(int C) { return (size_t)kColsumBlocks * C; }
 
-void launch_colsum(hipStream_t st, const bf16_t* g, float* G, float* ws, long R, int C) {
+struct ColsumShape { int threads, nrl; long blocks, rpb; };
+ColsumShape colsum_shape(long R, int C) {
   // threads: C/8 column groups x row lanes; C up to 8192
+  ColsumShape s;
   int cg = C / 8;
-  int threads = 256;
-  if (cg > 256) threads = 1024;
-  int nrl = threads / cg;
-  if (nrl < 1) nrl = 1;
-  long blocks = kColsumBlocks;
-  if (blocks > cdivl(R, nrl)) blocks = cdivl(R, nrl);
-  long rpb = cdivl(R, blocks);
-  blocks = cdivl(R, rpb);
-  KLAUNCH(colsum_partial_kernel, dim3((unsigned)blocks), dim3(threads), (size_t)nrl * C * sizeof(float), st, g, ws, R,
-          C, rpb);
-  KLAUNCH(colsum_final_kernel, dim3((unsigned)cdivl(C, 16)), dim3(256), 0, st, ws, G, C, (int)blocks);
+  s.threads = cg > 256 ? 1024 : 256;
+  s.nrl = s.threads / cg;
+  if (s.nrl < 1) s.nrl = 1;
+  s.blocks = kColsumBlocks;
+  if (s.blocks > cdivl(R, s.nrl)) s.blocks = cdivl(R, s.nrl);
+  s.rpb = cdivl(R, s.blocks);
+  s.blocks = cdivl(R, s.rpb);
+  return s;
+}
+// partials into ws[blocks][C]; with G the final accumulation follows, else it is the caller's
+void launch_colsum(hipStream_t st, const bf16_t* g, float* G, float* ws, long R, int C) {
+  const ColsumShape s = colsum_shape(R, C);
+  KLAUNCH(colsum_partial_kernel, dim3((unsigned)s.blocks), dim3(s.threads), (size_t)s.nrl * C * sizeof(float), st, g,
+          ws, R, C, s.rpb);
+  if (G) KLAUNCH(colsum_final_kernel, dim3((unsigned)cdivl(C, 16)), dim3(256), 0, st, ws, G, C, (int)s.blocks);
 }
 
 template <int WTM, int WTN, bool DBUF, int BKT = 64>
@@ -797,6 +811,7 @@ void launch_wgrad(hipStream_t st, GemmArgs& g, float* G, float* ws, int taps) {
   KLAUNCH_NAMED(BMODE == B_T_SHIFT ? "gemm_bf16_kernel<128x128,wgrad_conv>" : "gemm_bf16_kernel<128x128,wgrad_rows>", kern,
                 dim3((unsigned)(tm * tn * taps * splits), 1, 1), dim3(256), lds, st, g);
   long total = (long)taps * g.M * g.N;
+  if (!G) return;  // the caller reduces the partials
   // G sits at an arbitrary float offset of the parameter arena: the 16-byte path needs it aligned
   if (taps == 1 && total % 4 == 0 && (reinterpret_cast<uintptr_t>(G) & 15) == 0)
     KLAUNCH(reduce_wgrad4_kernel, dim3((unsigned)cdivl(total / 4, 256)), dim3(256), 0, st,
@@ -816,9 +831,14 @@ void set_geometry(GemmArgs& g, int H, int W, int C, int k) {
 
 // ------------------------------------------------------------------ public launchers
 size_t conv_bf16_ws_bytes(int N, int H, int W, int Cin, int Cout, int k) {
-  size_t a = wgrad_ws_floats(Cout, Cin, (long)N * H * W, k * k);
-  size_t b = colsum_ws_floats(Cout);
-  return (a > b ? a : b) * sizeof(float) + 256;
+  return (align64f(wgrad_ws_floats(Cout, Cin, (long)N * H * W, k * k)) + colsum_ws_floats(Cout)) * sizeof(float) + 256;
+}
+WgradParts conv_bf16_wgrad_parts(int N, int H, int W, int Cin, int Cout, int k) {
+  WgradParts p;
+  p.splits = wgrad_splits(Cout, Cin, (long)N * H * W, k * k);
+  p.bias_off = align64f(wgrad_ws_floats(Cout, Cin, (long)N * H * W, k * k));
+  p.bias_parts = (int)colsum_shape((long)N * H * W, Cout).blocks;
+  return p;
 }
 
 void conv_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh_fwd, const float* bias, bf16_t* y, int N,
@@ -845,21 +865,29 @@ void conv_bf16_dgrad(hipStream_t st, const bf16_t* gy, const bf16_t* sh_dgrad, b
   launch_fwd_like<A_IM2COL>(st, g);
 }
 
-void conv_bf16_wgrad(hipStream_t st, const bf16_t* gy, const bf16_t* x, float* GW, float* Gb, void* ws, int N,
-                     int H, int W, int Cin, int Cout, int k) {
+void conv_bf16_wgrad(hipStream_t st, const bf16_t* gy, const bf16_t* x, float* GW, float* Gb, bool has_bias,
+                     bool defer, void* ws, int N, int H, int W, int Cin, int Cout, int k) {
   GemmArgs g = {};
   g.A = gy; g.B = x;
   g.M = Cout; g.N = Cin; g.K = (long)N * H * W;
   g.lda = Cout; g.ldb = Cin;
   set_geometry(g, H, W, Cin, k);
-  launch_wgrad<B_T_SHIFT>(st, g, GW, reinterpret_cast<float*>(ws), k * k);
-  if (Gb) launch_colsum(st, gy, Gb, reinterpret_cast<float*>(ws), (long)N * H * W, Cout);
+  launch_wgrad<B_T_SHIFT>(st, g, defer ? nullptr : GW, reinterpret_cast<float*>(ws), k * k);
+  if (has_bias)
+    launch_colsum(st, gy, defer ? nullptr : Gb,
+                  reinterpret_cast<float*>(ws) + align64f(wgrad_ws_floats(Cout, Cin, (long)N * H * W, k * k)),
+                  (long)N * H * W, Cout);
 }
 
 size_t linear_bf16_ws_bytes(size_t R, int Cin, int Cout) {
-  size_t a = wgrad_ws_floats(Cout, Cin, (long)R, 1);
-  size_t b = colsum_ws_floats(Cout);
-  return (a > b ? a : b) * sizeof(float) + 256;
+  return (align64f(wgrad_ws_floats(Cout, Cin, (long)R, 1)) + colsum_ws_floats(Cout)) * sizeof(float) + 256;
+}
+WgradParts linear_bf16_wgrad_parts(size_t R, int Cin, int Cout) {
+  WgradParts p;
+  p.splits = wgrad_splits(Cout, Cin, (long)R, 1);
+  p.bias_off = align64f(wgrad_ws_floats(Cout, Cin, (long)R, 1));
+  p.bias_parts = (int)colsum_shape((long)R, Cout).blocks;
+  return p;
 }
 
 void linear_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh, const float* bias, bf16_t* y, bf16_t* pre,
@@ -883,14 +911,16 @@ void linear_bf16_dgrad(hipStream_t st, const bf16_t* gy, const bf16_t* sh_t, bf1
   launch_fwd_like<A_ROW>(st, g);
 }
 
-void linear_bf16_wgrad(hipStream_t st, const bf16_t* gy, const bf16_t* x, float* GW, float* Gb, void* ws,
-                       size_t R, int Cin, int Cout) {
+void linear_bf16_wgrad(hipStream_t st, const bf16_t* gy, const bf16_t* x, float* GW, float* Gb, bool has_bias,
+                       bool defer, void* ws, size_t R, int Cin, int Cout) {
   GemmArgs g = {};
   g.A = gy; g.B = x;
   g.M = Cout; g.N = Cin; g.K = (long)R; g.lda = Cout; g.ldb = Cin;
   set_geometry(g, 1, 1, Cin, 1);
-  launch_wgrad<OP_T>(st, g, GW, reinterpret_cast<float*>(ws), 1);
-  if (Gb) launch_colsum(st, gy, Gb, reinterpret_cast<float*>(ws), (long)R, Cout);
+  launch_wgrad<OP_T>(st, g, defer ? nullptr : GW, reinterpret_cast<float*>(ws), 1);
+  if (has_bias)
+    launch_colsum(st, gy, defer ? nullptr : Gb,
+                  reinterpret_cast<float*>(ws) + align64f(wgrad_ws_floats(Cout, Cin, (long)R, 1)), (long)R, Cout);
 }
 
 }  // namespace ast

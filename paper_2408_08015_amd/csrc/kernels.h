@@ -55,10 +55,12 @@ void reduce_parts_acc_f32(hipStream_t st, const float* part, float* G, size_t n,
 // kernels of a backward pass only write their partials (pass G = NULL to them) and the list is
 // reduced once at the end of the pass, instead of one few-microsecond launch per layer.
 // Block b of the launch works on task block_task[b], outputs [64*(b - block0), +64).
+// General form: G[out(i)] += sum_{c < parts} part[c*stride + i], i < n, with out(i) = i, or for
+// the k x k conv layout (taps > 1, n = taps*mn) out(i) = (i % mn)*taps + i / mn.
 struct RedTask {
   const float* part;
   float* G;
-  unsigned n, parts, block0, pad;
+  unsigned n, parts, block0, stride, taps, mn;
 };
 void reduce_tasks_f32(hipStream_t st, const RedTask* tasks_dev, const unsigned short* block_task_dev, int nblocks);
 int pw_wgrad_f32_parts(int N, int Cin, int Cout, int HW);  // partial count of pw_wgrad_f32

@@ -28,10 +28,14 @@ void conv_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh_fwd, const 
 // conv) dx is zeroed where relu_out <= 0: that ReLU's backward, folded into the epilogue.
 void conv_bf16_dgrad(hipStream_t st, const bf16_t* g, const bf16_t* sh_dgrad, bf16_t* dx, const bf16_t* relu_out,
                      int N, int H, int W, int Cin, int Cout, int k);
-// GW[Cout][Cin][k][k] += sum_pixels g x ; Gb[Cout] += sum_pixels g.  `ws` holds
-// conv_bf16_ws_bytes().
-void conv_bf16_wgrad(hipStream_t st, const bf16_t* g, const bf16_t* x, float* GW, float* Gb, void* ws,
-                     int N, int H, int W, int Cin, int Cout, int k);
+// Scratch layout of a weight-gradient call: `splits` partial copies of the weight gradient at
+// ws[0, ...), `bias_parts` partial bias gradients ([bias_parts][Cout]) from float offset bias_off.
+struct WgradParts { int splits; size_t bias_off; int bias_parts; };
+WgradParts conv_bf16_wgrad_parts(int N, int H, int W, int Cin, int Cout, int k);
+// GW[Cout][Cin][k][k] += conv weight gradient, Gb[Cout] += sum of g (if has_bias).  With
+// `defer` only the partials are written and the caller reduces them (reduce_tasks_f32).
+void conv_bf16_wgrad(hipStream_t st, const bf16_t* g, const bf16_t* x, float* GW, float* Gb, bool has_bias,
+                     bool defer, void* ws, int N, int H, int W, int Cin, int Cout, int k);
 
 // ---- linear on [R][Cin] rows
 size_t linear_bf16_ws_bytes(size_t R, int Cin, int Cout);
@@ -44,8 +48,9 @@ void linear_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh, const fl
 // may be NULL) the gradient arriving over a residual connection is added.  At most one of the two.
 void linear_bf16_dgrad(hipStream_t st, const bf16_t* g, const bf16_t* sh_t, bf16_t* dx, const bf16_t* gelu_pre,
                        const bf16_t* add, size_t R, int Cin, int Cout);
-void linear_bf16_wgrad(hipStream_t st, const bf16_t* g, const bf16_t* x, float* GW, float* Gb, void* ws,
-                       size_t R, int Cin, int Cout);
+WgradParts linear_bf16_wgrad_parts(size_t R, int Cin, int Cout);
+void linear_bf16_wgrad(hipStream_t st, const bf16_t* g, const bf16_t* x, float* GW, float* Gb, bool has_bias,
+                       bool defer, void* ws, size_t R, int Cin, int Cout);
 
 // ---- elementwise on bf16
 // g' = g * act'(.) : ReLU masks by the OUTPUT y (> 0), GELU uses the stashed pre-activation.
@@ -66,6 +71,7 @@ void layernorm_fwd_bf16(hipStream_t st, const bf16_t* x, const float* gamma, con
 void layernorm_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, const float* stat,
                         const float* gamma, const bf16_t* add, bf16_t* dx, void* ws, size_t R, int D);
 void layernorm_bwd_params_bf16(hipStream_t st, const void* ws, float* Ggamma, float* Gbeta, size_t R, int D);
+int layernorm_bwd_parts(size_t R);  // number of [2][D] partial rows the backward kernel writes
 
 // ---- self-attention core on packed qkv [B][S][3D] (head size 64, S % 32 == 0, S <= 256):
 // o [B][S][D], lse [B][H][S]

@@ -377,6 +377,12 @@ void layernorm_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, const 
             g, x, stat, gamma, add, dx, part, R, D, rpb);
 }
 
+int layernorm_bwd_parts(size_t R) {
+  size_t blocks = ln_blocks(R);
+  size_t rpb = (R + blocks - 1) / blocks;
+  return (int)((R + rpb - 1) / rpb);
+}
+
 void layernorm_bwd_params_bf16(hipStream_t st, const void* ws, float* Ggamma, float* Gbeta, size_t R, int D) {
   size_t blocks = ln_blocks(R);
   size_t rpb = (R + blocks - 1) / blocks;

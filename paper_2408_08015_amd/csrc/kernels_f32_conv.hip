@@ -414,24 +414,32 @@ __global__ __launch_bounds__(256) void reduce_tasks_kernel(const RedTask* __rest
   __shared__ float sh[4][64];
   const RedTask t = tasks[block_task[blockIdx.x]];
   const int o = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const size_t n = t.n;
+  const size_t n = t.n, st = t.stride;
   const size_t i = (size_t)(blockIdx.x - t.block0) * 64 + o;
   const int parts = (int)t.parts;
+  const float* p = t.part + i;
   float s = 0.f;
   if (i < n) {
     int c = q;
     for (; c + 28 < parts; c += 32) {  // eight independent loads in flight
-      float v0 = t.part[(size_t)c * n + i], v1 = t.part[(size_t)(c + 4) * n + i];
-      float v2 = t.part[(size_t)(c + 8) * n + i], v3 = t.part[(size_t)(c + 12) * n + i];
-      float v4 = t.part[(size_t)(c + 16) * n + i], v5 = t.part[(size_t)(c + 20) * n + i];
-      float v6 = t.part[(size_t)(c + 24) * n + i], v7 = t.part[(size_t)(c + 28) * n + i];
+      float v0 = p[(size_t)c * st], v1 = p[(size_t)(c + 4) * st];
+      float v2 = p[(size_t)(c + 8) * st], v3 = p[(size_t)(c + 12) * st];
+      float v4 = p[(size_t)(c + 16) * st], v5 = p[(size_t)(c + 20) * st];
+      float v6 = p[(size_t)(c + 24) * st], v7 = p[(size_t)(c + 28) * st];
       s += ((v0 + v1) + (v2 + v3)) + ((v4 + v5) + (v6 + v7));
     }
-    for (; c < parts; c += 4) s += t.part[(size_t)c * n + i];
+    for (; c < parts; c += 4) s += p[(size_t)c * st];
   }
   sh[q][o] = s;
   __syncthreads();
-  if (q == 0 && i < n) t.G[i] += (sh[0][o] + sh[1][o]) + (sh[2][o] + sh[3][o]);
+  if (q == 0 && i < n) {
+    size_t out = i;
+    if (t.taps > 1) {
+      const size_t tp = i / t.mn;
+      out = (i - tp * t.mn) * t.taps + tp;
+    }
+    t.G[out] += (sh[0][o] + sh[1][o]) + (sh[2][o] + sh[3][o]);
+  }
 }
 void reduce_tasks_f32(hipStream_t st, const RedTask* tasks_dev, const unsigned short* block_task_dev, int nblocks) {
   KLAUNCH(reduce_tasks_kernel, dim3(nblocks), dim3(256), 0, st, tasks_dev, block_task_dev);

@@ -345,9 +345,10 @@ ast_status build_plan(Stage& s, std::string& err) {
           need = align_up(s.acts[op.out].bytes, 256) + linear_bf16_ws_bytes((size_t)I.n * I.h * I.w, op.cin, op.cout);
         break;
       case OP_LAYERNORM: need = layernorm_bf16_ws_bytes((size_t)I.n * I.h, I.c); break;
-      case OP_MHA:  // d_o and dqkv, then the split-K partials of the two projections
+      case OP_MHA:  // d_o and dqkv, the row sums, then the split-K partials of each projection
         need = align_up((size_t)I.n * I.h * 4 * op.cin * 2, 256) +
                align_up(mha_bf16_ws_bytes(I.n, I.h, op.cin, op.heads), 256) +
+               align_up(linear_bf16_ws_bytes((size_t)I.n * I.h, op.cin, op.cin), 256) +
                linear_bf16_ws_bytes((size_t)I.n * I.h, op.cin, 3 * op.cin);
         break;
       default: break;
