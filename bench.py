@@ -135,8 +135,8 @@ DOMINANT = {
 # what the same counter reads for the library's plain copy kernel of known size
 # (FETCH_SIZE reads 0.501 of the bytes copied, WRITE_SIZE 1.000); see profiles/.
 TRAFFIC_BYTES = {
-    ("cfg2", "bn_bwd_apply_kernel"): int((17545.3 / 0.5012 + 17256.0) * 1024),
-    ("cfg4", "gemm_bf16_kernel<128x128,im2col>"): int((31015.2 / 0.5005 + 45994.7) * 1024),
+    ("cfg2", "bn_bwd_apply_kernel"): int((17545.4 / 0.5012 + 17256.0) * 1024),
+    ("cfg4", "gemm_bf16_kernel<128x128,im2col>"): int((49636.4 / 0.5004 + 45994.7) * 1024),
 }
 
 

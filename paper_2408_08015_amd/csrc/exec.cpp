@@ -1,5 +1,6 @@
 // Plan execution: forward, backward and optimizer step of a stage, as kernel launches
 // on the stage's stream.  No allocation, no host synchronisation.
+#include <cstdint>
 #include <cstdlib>
 #include <vector>
 
@@ -358,7 +359,10 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
     t.n = (unsigned)n; t.parts = (unsigned)parts; t.stride = (unsigned)stride;
     t.taps = (unsigned)taps; t.mn = (unsigned)mn;
     t.block0 = (unsigned)block_task.size();
-    for (size_t b = 0; b < (n + 63) / 64; ++b) block_task.push_back((unsigned short)tasks.size());
+    // many outputs, few partials: 16-byte loads, a thread sums all partials of its outputs
+    t.wide = (n >= 16384 && n % 4 == 0 && stride % 4 == 0 && (reinterpret_cast<uintptr_t>(part) & 15) == 0) ? 1u : 0u;
+    const size_t per_block = t.wide ? 1024 : 64;
+    for (size_t b = 0; b < (n + per_block - 1) / per_block; ++b) block_task.push_back((unsigned short)tasks.size());
     tasks.push_back(t);
   };
   auto add_wgrad = [&](float* base, const WgradParts& wp, float* GW, float* Gb, size_t cout, size_t cin, int taps) {

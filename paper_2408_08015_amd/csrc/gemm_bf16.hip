@@ -207,10 +207,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) b_voff[j] = b_ok[j] ? (unsigned)b_off[j] * 2u : g.b_bytes;
   }
-  // The K-tiles are visited tap-fastest: the nine taps of one 64-channel slice follow each
-  // other, so consecutive tiles re-read the same pixels shifted by one (the 128-byte line
-  // of a pixel's slice loaded for row m under one tap is the line of row m-1 under the next)
-  // and mostly hit the CU's own L1 instead of the L2.  These launches are never split over K.
+  // Implicit GEMM with a tile-uniform tap: K runs tap-major ([tap][ci], the layout of the weight
+  // copy), the tap and channel offset of the current K-tile are loop-carried uniform state.
+  // (Visiting the nine taps of one 64-channel slice back to back, for L1 reuse of the shifted
+  // pixels, was measured: same time, 25 % more HBM traffic.)  These launches are never split over K.
   int cur_tap = 0, cur_ci = 0;
   // shifted operand of the conv weight gradient: (y, x) of the first pixel row of each B task
   int t_y[(!ROWMODE && BMODE == B_T_SHIFT) ? NTASK : 1], t_x[(!ROWMODE && BMODE == B_T_SHIFT) ? NTASK : 1];
@@ -256,7 +256,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         tapbit = 1u << cur_tap;
         da = (unsigned)(((dy * g.W + dx) * g.C + cur_ci) * 2);  // may be "negative": wraps back in the sum
         db = (unsigned)((cur_tap * g.C + cur_ci) * 2);
-        if (++cur_tap >= g.ksize * g.ksize) { cur_tap = 0; cur_ci += BK; }
+        cur_ci += BK;
+        if (cur_ci >= g.C) { cur_ci = 0; ++cur_tap; }
       } else {
         da = db = (unsigned)k0 * 2u;
       }

@@ -57,10 +57,13 @@ void reduce_parts_acc_f32(hipStream_t st, const float* part, float* G, size_t n,
 // Block b of the launch works on task block_task[b], outputs [64*(b - block0), +64).
 // General form: G[out(i)] += sum_{c < parts} part[c*stride + i], i < n, with out(i) = i, or for
 // the k x k conv layout (taps > 1, n = taps*mn) out(i) = (i % mn)*taps + i / mn.
+// wide != 0: the task's blocks cover 1024 outputs each (one thread = four consecutive outputs
+// read with 16-byte loads, all partials of a thread in flight together; needs part 16-byte
+// aligned and n, stride multiples of 4), else 64 outputs x 4 interleaved partial lanes.
 struct RedTask {
   const float* part;
   float* G;
-  unsigned n, parts, block0, stride, taps, mn;
+  unsigned n, parts, block0, stride, taps, mn, wide, pad;
 };
 void reduce_tasks_f32(hipStream_t st, const RedTask* tasks_dev, const unsigned short* block_task_dev, int nblocks);
 int pw_wgrad_f32_parts(int N, int Cin, int Cout, int HW);  // partial count of pw_wgrad_f32

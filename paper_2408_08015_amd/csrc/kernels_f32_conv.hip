@@ -413,6 +413,40 @@ __global__ __launch_bounds__(256) void reduce_tasks_kernel(const RedTask* __rest
                                                            const unsigned short* __restrict__ block_task) {
   __shared__ float sh[4][64];
   const RedTask t = tasks[block_task[blockIdx.x]];
+  if (t.wide) {  // uniform per block
+    const size_t i4 = ((size_t)(blockIdx.x - t.block0) * 256 + threadIdx.x) * 4;
+    if (i4 >= t.n) return;
+    const float* p4 = t.part + i4;
+    const size_t st4 = t.stride;
+    const int parts4 = (int)t.parts;
+    float4 s4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    int c4 = 0;
+    for (; c4 + 4 <= parts4; c4 += 4) {
+      const float4 v0 = *reinterpret_cast<const float4*>(p4 + (size_t)c4 * st4);
+      const float4 v1 = *reinterpret_cast<const float4*>(p4 + (size_t)(c4 + 1) * st4);
+      const float4 v2 = *reinterpret_cast<const float4*>(p4 + (size_t)(c4 + 2) * st4);
+      const float4 v3 = *reinterpret_cast<const float4*>(p4 + (size_t)(c4 + 3) * st4);
+      s4.x += (v0.x + v1.x) + (v2.x + v3.x);
+      s4.y += (v0.y + v1.y) + (v2.y + v3.y);
+      s4.z += (v0.z + v1.z) + (v2.z + v3.z);
+      s4.w += (v0.w + v1.w) + (v2.w + v3.w);
+    }
+    for (; c4 < parts4; ++c4) {
+      const float4 v = *reinterpret_cast<const float4*>(p4 + (size_t)c4 * st4);
+      s4.x += v.x; s4.y += v.y; s4.z += v.z; s4.w += v.w;
+    }
+    const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      size_t out = i4 + e;
+      if (t.taps > 1) {
+        const size_t tp = out / t.mn;
+        out = (out - tp * t.mn) * t.taps + tp;
+      }
+      t.G[out] += sv[e];
+    }
+    return;
+  }
   const int o = threadIdx.x & 63, q = threadIdx.x >> 6;
   const size_t n = t.n, st = t.stride;
   const size_t i = (size_t)(blockIdx.x - t.block0) * 64 + o;
