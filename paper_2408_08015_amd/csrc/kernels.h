@@ -70,8 +70,8 @@ int pw_wgrad_f32_parts(int N, int Cin, int Cout, int HW);  // partial count of p
 // G[c] += sum_{n,p} g[n][c][p]
 void channel_sum_acc_f32(hipStream_t st, const float* g, float* G, int N, int C, int HW);
 
-// BatchNorm2d, training mode.  `ws` holds bn_ws_doubles(C, N*HW) doubles.
-size_t bn_ws_doubles(int C, size_t per_channel);
+// BatchNorm2d, training mode.  `ws` holds bn_ws_doubles(C, N, HW) doubles.
+size_t bn_ws_doubles(int C, int N, int HW);
 // Forward: batch statistics of x, then y = act(x*scale[c] + shift[c]) (+ skip).
 // mean/istd -> stat[0..C) / stat[C..2C); scale/shift -> scale_shift[0..2C);
 // running[0..C) mean, running[C..2C) var updated in place (momentum 0.1, unbiased variance).

@@ -1,8 +1,8 @@
 // BatchNorm2d (training mode, NCHW, fp32) forward and backward, HBM-bound.
 //
 // Each direction is two streaming kernels and nothing else:
-//   partial:  (channel, split) blocks reduce a share of the channel's N*H*W elements
-//             (fp32 per thread, fp64 across threads) into ws[channel][split][2];
+//   partial:  (channel, part) blocks reduce a few whole samples or one plane chunk of the
+//             channel (fp32 per thread, fp64 across threads) into ws[channel][part][2];
 //   apply:    one block per (plane, chunk); its first wavefront adds the channel's partials
 //             in a fixed butterfly order in fp64 (every block of a channel computes bit-identical
 //             coefficients), then the block streams its chunk.  The block of sample 0 /
@@ -18,66 +18,82 @@ namespace ast {
 
 static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
-static inline int bn_split(int C, size_t per) {
-  int S = cdiv(2048, C);
-  int maxS = (int)((per + 4095) / 4096);
-  if (S > maxS) S = maxS;
-  if (S > 64) S = 64;  // one wavefront adds the partials
-  return S < 1 ? 1 : S;
+// A channel's N*HW elements are N contiguous planes.  A partial-sum block takes `spb` whole
+// samples (small planes) or one chunk of one plane (large planes) of one channel, so it
+// streams contiguous memory with no index arithmetic per element; P = groups * chunks
+// partial pairs per channel.
+struct BnSplit { int spb, groups, nchunks, chunk, P; };
+static inline BnSplit bn_split(int N, int HW) {
+  BnSplit b;
+  b.nchunks = cdiv(HW, 4096);
+  b.chunk = (cdiv(HW, b.nchunks) + 3) & ~3;
+  b.nchunks = cdiv(HW, b.chunk);
+  b.spb = b.nchunks > 1 ? 1 : 4096 / HW;
+  if (b.spb < 1) b.spb = 1;
+  if (b.spb > N) b.spb = N;
+  b.groups = cdiv(N, b.spb);
+  b.P = b.groups * b.nchunks;
+  return b;
 }
-size_t bn_ws_doubles(int C, size_t per) { return (size_t)C * bn_split(C, per) * 2; }
+size_t bn_ws_doubles(int C, int N, int HW) { return (size_t)C * bn_split(N, HW).P * 2; }
 
-// element range of split s, aligned to 4 elements
-__device__ __forceinline__ void split_range(long per, int S, int s, long& e0, long& e1) {
-  long len = ((per + S - 1) / S + 3) & ~3L;
-  e0 = (long)s * len;
-  e1 = min(e0 + len, per);
-  if (e0 > per) e0 = per;
-}
-
-// sums of the channel's partial pairs, identical in every lane of the calling wavefront
-__device__ __forceinline__ void add_partials(const double* __restrict__ ws, int c, int S, double& s1, double& s2) {
+// sums of the channel's P partial pairs in a fixed order, identical in every lane of the
+// calling wavefront
+__device__ __forceinline__ void add_partials(const double* __restrict__ ws, int c, int P, double& s1, double& s2) {
   const int lane = threadIdx.x & 63;
   double a = 0.0, b = 0.0;
-  if (lane < S) {
-    a = ws[((size_t)c * S + lane) * 2 + 0];
-    b = ws[((size_t)c * S + lane) * 2 + 1];
+  for (int k = lane; k < P; k += 64) {
+    a += ws[((size_t)c * P + k) * 2 + 0];
+    b += ws[((size_t)c * P + k) * 2 + 1];
   }
   s1 = wave_sum_d(a);
   s2 = wave_sum_d(b);
 }
 
+// both sums of a block in one pass; the result is valid in thread 0
+__device__ __forceinline__ void block_sum2(float f1, float f2, double* sh, double& d1, double& d2) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const double a = wave_sum_d((double)f1), b = wave_sum_d((double)f2);
+  if (lane == 0) {
+    sh[w] = a;
+    sh[4 + w] = b;
+  }
+  __syncthreads();
+  d1 = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+  d2 = (sh[4] + sh[5]) + (sh[6] + sh[7]);
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(256) void bn_stats_partial_kernel(const float* __restrict__ x,
-                                                               double* __restrict__ ws, int N, int C,
-                                                               int HW, int S) {
-  __shared__ double sh[16];
-  const int c = blockIdx.x, s = blockIdx.y;
-  long e0, e1;
-  split_range((long)N * HW, S, s, e0, e1);
+                                                               double* __restrict__ ws, int N, int C, int HW,
+                                                               BnSplit b) {
+  __shared__ double sh[8];
+  const int c = blockIdx.x, grp = blockIdx.y / b.nchunks, ch = blockIdx.y - grp * b.nchunks;
+  const int n0 = grp * b.spb, n1 = min(n0 + b.spb, N);
+  const int e0 = ch * b.chunk, e1 = min(e0 + b.chunk, HW), len = e1 - e0;
   float s1 = 0.f, s2 = 0.f;
   if (VEC) {
-    for (long e = e0 + 4L * threadIdx.x; e < e1; e += 1024) {
-      long n = e / HW;
-      int p = (int)(e - n * HW);
-      float4 v = *reinterpret_cast<const float4*>(x + ((size_t)n * C + c) * HW + p);
+    const int q = len >> 2, total = (n1 - n0) * q;
+    for (int idx = threadIdx.x; idx < total; idx += 256) {
+      const int nl = idx / q, e = e0 + 4 * (idx - nl * q);
+      const float4 v = *reinterpret_cast<const float4*>(x + ((size_t)(n0 + nl) * C + c) * HW + e);
       s1 += (v.x + v.y) + (v.z + v.w);
       s2 += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
     }
   } else {
-    for (long e = e0 + threadIdx.x; e < e1; e += 256) {
-      long n = e / HW;
-      int p = (int)(e - n * HW);
-      float v = x[((size_t)n * C + c) * HW + p];
+    const int total = (n1 - n0) * len;
+    for (int idx = threadIdx.x; idx < total; idx += 256) {
+      const int nl = idx / len, e = e0 + idx - nl * len;
+      const float v = x[((size_t)(n0 + nl) * C + c) * HW + e];
       s1 += v;
       s2 += v * v;
     }
   }
-  double d1 = block_sum<double>((double)s1, sh);
-  double d2 = block_sum<double>((double)s2, sh);
+  double d1, d2;
+  block_sum2(s1, s2, sh, d1, d2);
   if (threadIdx.x == 0) {
-    ws[((size_t)c * S + s) * 2 + 0] = d1;
-    ws[((size_t)c * S + s) * 2 + 1] = d2;
+    ws[((size_t)c * b.P + blockIdx.y) * 2 + 0] = d1;
+    ws[((size_t)c * b.P + blockIdx.y) * 2 + 1] = d2;
   }
 }
 
@@ -154,10 +170,11 @@ void bn_fwd_f32(hipStream_t st, const float* x, const float* gamma, const float*
                 float* y, float* stat, float* scale_shift, float* running, double* ws, int N, int C, int HW,
                 float eps, int act) {
   size_t per = (size_t)N * HW;
-  int S = bn_split(C, per);
+  const BnSplit b = bn_split(N, HW);
+  const int S = b.P;
   const bool vec = HW % 4 == 0;
-  if (vec) KLAUNCH(bn_stats_partial_kernel<true>, dim3(C, S), dim3(256), 0, st, x, ws, N, C, HW, S);
-  else KLAUNCH(bn_stats_partial_kernel<false>, dim3(C, S), dim3(256), 0, st, x, ws, N, C, HW, S);
+  if (vec) KLAUNCH(bn_stats_partial_kernel<true>, dim3(C, b.P), dim3(256), 0, st, x, ws, N, C, HW, b);
+  else KLAUNCH(bn_stats_partial_kernel<false>, dim3(C, b.P), dim3(256), 0, st, x, ws, N, C, HW, b);
   int nchunks, chunk;
   bn_chunking(HW, nchunks, chunk);
   dim3 grid((unsigned)(N * C), nchunks);
@@ -175,18 +192,18 @@ __global__ __launch_bounds__(256) void bn_bwd_partial_kernel(const float* __rest
                                                              const float* __restrict__ stat,
                                                              const float* __restrict__ ss,
                                                              double* __restrict__ ws, int N, int C,
-                                                             int HW, int S, int act) {
-  __shared__ double sh[16];
-  const int c = blockIdx.x, s = blockIdx.y;
-  long e0, e1;
-  split_range((long)N * HW, S, s, e0, e1);
+                                                             int HW, BnSplit b, int act) {
+  __shared__ double sh[8];
+  const int c = blockIdx.x, grp = blockIdx.y / b.nchunks, ch = blockIdx.y - grp * b.nchunks;
+  const int n0 = grp * b.spb, n1 = min(n0 + b.spb, N);
+  const int e0 = ch * b.chunk, e1 = min(e0 + b.chunk, HW), len = e1 - e0;
   const float mean = stat[c], istd = stat[C + c], sc = ss[c], sf = ss[C + c];
   float s1 = 0.f, s2 = 0.f;
   if (VEC) {
-    for (long e = e0 + 4L * threadIdx.x; e < e1; e += 1024) {
-      long n = e / HW;
-      int p = (int)(e - n * HW);
-      size_t off = ((size_t)n * C + c) * HW + p;
+    const int q = len >> 2, total = (n1 - n0) * q;
+    for (int idx = threadIdx.x; idx < total; idx += 256) {
+      const int nl = idx / q, e = e0 + 4 * (idx - nl * q);
+      const size_t off = ((size_t)(n0 + nl) * C + c) * HW + e;
       float4 xv = *reinterpret_cast<const float4*>(x + off);
       float4 gv = *reinterpret_cast<const float4*>(g + off);
       float g0 = gv.x * act_mask(xv.x * sc + sf, act), g1 = gv.y * act_mask(xv.y * sc + sf, act);
@@ -196,21 +213,21 @@ __global__ __launch_bounds__(256) void bn_bwd_partial_kernel(const float* __rest
             (g2 * ((xv.z - mean) * istd) + g3 * ((xv.w - mean) * istd));
     }
   } else {
-    for (long e = e0 + threadIdx.x; e < e1; e += 256) {
-      long n = e / HW;
-      int p = (int)(e - n * HW);
-      size_t off = ((size_t)n * C + c) * HW + p;
+    const int total = (n1 - n0) * len;
+    for (int idx = threadIdx.x; idx < total; idx += 256) {
+      const int nl = idx / len, e = e0 + idx - nl * len;
+      const size_t off = ((size_t)(n0 + nl) * C + c) * HW + e;
       float xv = x[off];
       float gv = g[off] * act_mask(xv * sc + sf, act);
       s1 += gv;
       s2 += gv * ((xv - mean) * istd);
     }
   }
-  double d1 = block_sum<double>((double)s1, sh);
-  double d2 = block_sum<double>((double)s2, sh);
+  double d1, d2;
+  block_sum2(s1, s2, sh, d1, d2);
   if (threadIdx.x == 0) {
-    ws[((size_t)c * S + s) * 2 + 0] = d1;
-    ws[((size_t)c * S + s) * 2 + 1] = d2;
+    ws[((size_t)c * b.P + blockIdx.y) * 2 + 0] = d1;
+    ws[((size_t)c * b.P + blockIdx.y) * 2 + 1] = d2;
   }
 }
 
@@ -269,10 +286,11 @@ void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* sta
                 const float* gamma, float* dx, float* Ggamma, float* Gbeta, double* ws, int N, int C, int HW,
                 int act) {
   size_t per = (size_t)N * HW;
-  int S = bn_split(C, per);
+  const BnSplit b = bn_split(N, HW);
+  const int S = b.P;
   const bool vec = HW % 4 == 0;
-  if (vec) KLAUNCH(bn_bwd_partial_kernel<true>, dim3(C, S), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, S, act);
-  else KLAUNCH(bn_bwd_partial_kernel<false>, dim3(C, S), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, S, act);
+  if (vec) KLAUNCH(bn_bwd_partial_kernel<true>, dim3(C, b.P), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, b, act);
+  else KLAUNCH(bn_bwd_partial_kernel<false>, dim3(C, b.P), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, b, act);
   int nchunks, chunk;
   bn_chunking(HW, nchunks, chunk);
   // without an input gradient only the sample-0 / chunk-0 blocks have work (dgamma, dbeta)

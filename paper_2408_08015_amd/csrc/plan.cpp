@@ -335,7 +335,7 @@ ast_status build_plan(Stage& s, std::string& err) {
         need = conv_direct_wgrad_ws(I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride, op.pad, op.groups) * sizeof(float);
         break;
       case OP_BN:
-        need = bn_ws_doubles(I.c, (size_t)I.n * I.h * I.w) * sizeof(double);
+        need = bn_ws_doubles(I.c, I.n, I.h * I.w) * sizeof(double);
         break;
       case OP_CONV_IGEMM:  // masked upstream gradient + split-K partials
         need = align_up(s.acts[op.out].bytes, 256) + conv_bf16_ws_bytes(I.n, I.h, I.w, op.cin, op.cout, op.k);
