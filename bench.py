@@ -50,18 +50,20 @@ def kernel_model(cfg):
 
             def cls(m, kd):
                 if _cdiv(nq, 128) * _cdiv(m, 32) < 256 and _cdiv(kd, 8) >= 16:
-                    return "pw_conv_f32_pkks_kernel"
+                    return "pkks"
                 if hw % 4 == 0 and nq >= 65536:
-                    return "pw_conv_f32_pk4_kernel"
-                return "pw_conv_f32_pk_kernel<2>" if kd > 32 else "pw_conv_f32_pk_kernel<1>"
-            out.setdefault(cls(cout, cin), []).append(4 * (cin + cout) * nq)        # forward
-            if not first or cfg.needs_input_grad:                                   # input gradient
+                    return "pk4"
+                return "pk2" if kd > 32 else "pk1"
+            fwd_names = {"pkks": "pw_conv_f32_pkks_kernel", "pk4": "pw_conv_f32_pk4_kernel",
+                         "pk2": "pw_conv_f32_pk_kernel<2>", "pk1": "pw_conv_f32_pk_kernel<1>"}
+            out.setdefault(fwd_names[cls(cout, cin)], []).append(4 * (cin + cout) * nq)      # forward
+            if not first or cfg.needs_input_grad:
+                # input gradient and weight-gradient partials in one launch: g and x in, dx out
                 extra = 4 * cin * nq if (res_open and cfg.layers[i - 1]["kind"] == "res_begin") else 0
-                out.setdefault(cls(cin, cout), []).append(4 * (cin + cout) * nq + extra)
-        if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 1 and L["groups"] == 1:
-            hw = shape[1] * shape[2]
-            name = "pw_wgrad_f32_kernel<true>" if hw % 4 == 0 else "pw_wgrad_f32_kernel<false>"
-            out.setdefault(name, []).append(4 * (L["cin"] + L["cout"]) * B * hw)          # g and x in
+                out.setdefault("pw_bwd_dual_kernel<%s>" % cls(cin, cout), []).append(4 * (2 * cin + cout) * nq + extra)
+            else:
+                name = "pw_wgrad_f32_kernel<true>" if hw % 4 == 0 else "pw_wgrad_f32_kernel<false>"
+                out.setdefault(name, []).append(4 * (cin + cout) * nq)                      # g and x in
         if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"]:
             oc, oh, ow = oshape
             out.setdefault("dw3x3_fwd_f32_kernel", []).append(4 * B * (shape[0] * shape[1] * shape[2] + oc * oh * ow))

@@ -155,13 +155,15 @@ void bwd_op(Ctx& c, const Op& op) {
   switch (op.kind) {
     case OP_CONV_PW: {
       cf g = (cf)grad_ptr(c, op.out);
-      hipStream_t sw = fork_side(c);
-      if (gin)
-        pw_conv_f32(st, s.wpack + op.wp2_off, g, (float*)gin, nullptr,
-                    op.dgrad_add >= 0 ? (cf)grad_ptr(c, op.dgrad_add) : nullptr, I.n, op.cout, op.cin, HW);
-      pw_wgrad_f32(sw, g, (cf)act_ptr(c, op.in), reinterpret_cast<float*>(scratch(c, op)),
-                   s.red_nblocks ? nullptr : s.G + op.w_off, I.n, op.cin, op.cout, HW);
-      if (op.has_bias) channel_sum_acc_f32(sw, g, s.G + op.b_off, I.n, op.cout, HW);
+      float* part = reinterpret_cast<float*>(scratch(c, op));
+      float* Gw = s.red_nblocks ? nullptr : s.G + op.w_off;
+      if (gin)  // input gradient and weight-gradient partials share one launch
+        pw_conv_bwd_f32(st, s.wpack + op.wp2_off, g, (float*)gin,
+                        op.dgrad_add >= 0 ? (cf)grad_ptr(c, op.dgrad_add) : nullptr, (cf)act_ptr(c, op.in), part, Gw,
+                        I.n, op.cin, op.cout, HW);
+      else
+        pw_wgrad_f32(st, g, (cf)act_ptr(c, op.in), part, Gw, I.n, op.cin, op.cout, HW);
+      if (op.has_bias) channel_sum_acc_f32(st, g, s.G + op.b_off, I.n, op.cout, HW);
       break;
     }
     case OP_CONV_DW: {

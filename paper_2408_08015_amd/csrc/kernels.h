@@ -67,6 +67,10 @@ struct RedTask {
 };
 void reduce_tasks_f32(hipStream_t st, const RedTask* tasks_dev, const unsigned short* block_task_dev, int nblocks);
 int pw_wgrad_f32_parts(int N, int Cin, int Cout, int HW);  // partial count of pw_wgrad_f32
+// Backward of a pointwise conv in one launch: dx = W^T g (+ add) with Wp_t the packed W^T, and
+// the weight-gradient partials (then G += their sum, unless G is NULL: left to the caller).
+void pw_conv_bwd_f32(hipStream_t st, const float* Wp_t, const float* g, float* dx, const float* add, const float* x,
+                     float* part, float* G, int N, int Cin, int Cout, int HW);
 // G[c] += sum_{n,p} g[n][c][p]
 void channel_sum_acc_f32(hipStream_t st, const float* g, float* G, int N, int C, int HW);
 

@@ -25,6 +25,22 @@ static inline int conv_out(int H, int k, int stride, int pad) { return (H + 2 * 
 // (n, p) index and one 32-row tile of output channels.  MFMA 32x32x2: lane l supplies
 // A[m = l%32][k = l/32] and B[k = l/32][q = l%32]; accumulator register r of lane l is
 // D[8*(r/4) + 4*(l/32) + r%4][l%32].
+struct PwArgs {  // one pointwise-conv product Y = A X (+ bias) (+ add)
+  const float4* Wp;
+  const float* X;
+  float* Y;
+  const float* bias;
+  const float* add;
+  long NQ;
+  int HW, Kdim, Mdim, KG;
+};
+struct WgArgs {  // one pointwise-conv weight-gradient launch (partials only)
+  const float* g;
+  const float* x;
+  float* part;
+  int Cin, Cout, HW, cps, pxw;
+};
+
 // The A operand comes from a packed copy of the weights (pw_pack_f32): for m-tile t and
 // k-group g (8 consecutive k), lane l = (m%32, h) finds the four values A[m][8g + 2e + h],
 // e = 0..3, as one 16-byte word at Wp[(t*KG + g)*64 + l]; out-of-range m and k are zero
@@ -32,14 +48,19 @@ static inline int conv_out(int H, int k, int stride, int pad) { return (H + 2 * 
 // and needs neither LDS nor a barrier, and all loads of a pass are issued before its first
 // MFMA.  NCH = 32-channel chunks per pass.
 template <int NCH>
-__global__ __launch_bounds__(256) void pw_conv_f32_pk_kernel(
-    const float4* __restrict__ Wp, const float* __restrict__ X, float* __restrict__ Y,
-    const float* __restrict__ bias, const float* __restrict__ add, long NQ, int HW, int Kdim, int Mdim,
-    int KG) {
+__device__ __forceinline__ void pw_pk_body(const PwArgs& a, int bx, int by) {
+  const float4* __restrict__ Wp = a.Wp;
+  const float* __restrict__ X = a.X;
+  float* __restrict__ Y = a.Y;
+  const float* __restrict__ bias = a.bias;
+  const float* __restrict__ add = a.add;
+  const long NQ = a.NQ;
+  const int HW = a.HW, Kdim = a.Kdim, Mdim = a.Mdim, KG = a.KG;
+
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int m_base = blockIdx.y * 32;
-  const long q = (long)blockIdx.x * 128 + wave * 32 + col;
+  const int m_base = by * 32;
+  const long q = (long)bx * 128 + wave * 32 + col;
   const bool qv = q < NQ;
   long n = 0;
   int p = 0;
@@ -48,7 +69,7 @@ __global__ __launch_bounds__(256) void pw_conv_f32_pk_kernel(
     p = (int)(q - n * HW);
   }
   const float* xq = X + (size_t)n * Kdim * HW + p;
-  const float4* wl = Wp + (size_t)blockIdx.y * KG * 64 + lane;
+  const float4* wl = Wp + (size_t)by * KG * 64 + lane;
   floatx16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -88,21 +109,29 @@ __global__ __launch_bounds__(256) void pw_conv_f32_pk_kernel(
     }
   }
 }
+template <int NCH>
+__global__ __launch_bounds__(256) void pw_conv_f32_pk_kernel(PwArgs a) {
+  pw_pk_body<NCH>(a, blockIdx.x, blockIdx.y);
+}
 
 // Few pixels, long K (the 14x14 / 7x7 layers of a whole network): the four wavefronts of a
 // block share one 32-pixel x 32-channel output tile and split K between them, so there are
 // four times as many wavefronts and a quarter of the dependent passes; the four partial
 // tiles are added through LDS in a fixed order.
-__global__ __launch_bounds__(256) void pw_conv_f32_pkks_kernel(
-    const float4* __restrict__ Wp, const float* __restrict__ X, float* __restrict__ Y,
-    const float* __restrict__ bias, const float* __restrict__ add, long NQ, int HW, int Kdim, int Mdim,
-    int KG) {
+__device__ __forceinline__ void pw_pkks_body(const PwArgs& a, int bx, int by, float (*sR)[16][64]) {
+  const float4* __restrict__ Wp = a.Wp;
+  const float* __restrict__ X = a.X;
+  float* __restrict__ Y = a.Y;
+  const float* __restrict__ bias = a.bias;
+  const float* __restrict__ add = a.add;
+  const long NQ = a.NQ;
+  const int HW = a.HW, Kdim = a.Kdim, Mdim = a.Mdim, KG = a.KG;
+
   constexpr int NCH = 2;
-  __shared__ float sR[4][16][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int m_base = blockIdx.y * 32;
-  const long q = (long)blockIdx.x * 32 + col;
+  const int m_base = by * 32;
+  const long q = (long)bx * 32 + col;
   const bool qv = q < NQ;
   long n = 0;
   int p = 0;
@@ -111,7 +140,7 @@ __global__ __launch_bounds__(256) void pw_conv_f32_pkks_kernel(
     p = (int)(q - n * HW);
   }
   const float* xq = X + (size_t)n * Kdim * HW + p;
-  const float4* wl = Wp + (size_t)blockIdx.y * KG * 64 + lane;
+  const float4* wl = Wp + (size_t)by * KG * 64 + lane;
   const int gper = (KG + 3) >> 2;  // k-groups per wavefront
   const int gbeg = wave * gper, gend = min(gbeg + gper, KG);
   floatx16 acc;
@@ -157,20 +186,29 @@ __global__ __launch_bounds__(256) void pw_conv_f32_pkks_kernel(
     }
   }
 }
+__global__ __launch_bounds__(256) void pw_conv_f32_pkks_kernel(PwArgs a) {
+  __shared__ float sR[4][16][64];
+  pw_pkks_body(a, blockIdx.x, blockIdx.y, sR);
+}
 
 // Large images: a wavefront owns 128 pixels; every lane loads four consecutive pixels
 // (16 bytes) per input channel and feeds four MFMA column tiles (column j of tile t is
 // pixel 4j + t), so each output row is stored as 16 bytes per lane.  Four times the bytes
 // per memory instruction and a quarter of the weight traffic of the kernel above; needs
 // HW % 4 == 0.
-__global__ __launch_bounds__(256) void pw_conv_f32_pk4_kernel(
-    const float4* __restrict__ Wp, const float* __restrict__ X, float* __restrict__ Y,
-    const float* __restrict__ bias, const float* __restrict__ add, long NQ, int HW, int Kdim, int Mdim,
-    int KG) {
+__device__ __forceinline__ void pw_pk4_body(const PwArgs& a, int bx, int by) {
+  const float4* __restrict__ Wp = a.Wp;
+  const float* __restrict__ X = a.X;
+  float* __restrict__ Y = a.Y;
+  const float* __restrict__ bias = a.bias;
+  const float* __restrict__ add = a.add;
+  const long NQ = a.NQ;
+  const int HW = a.HW, Kdim = a.Kdim, Mdim = a.Mdim, KG = a.KG;
+
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int m_base = blockIdx.y * 32;
-  const long q = (long)blockIdx.x * 512 + wave * 128 + col * 4;
+  const int m_base = by * 32;
+  const long q = (long)bx * 512 + wave * 128 + col * 4;
   const bool qv = q < NQ;  // NQ % 4 == 0: the four pixels are valid together
   long n = 0;
   int p = 0;
@@ -179,7 +217,7 @@ __global__ __launch_bounds__(256) void pw_conv_f32_pk4_kernel(
     p = (int)(q - n * HW);
   }
   const float* xq = X + (size_t)n * Kdim * HW + p;
-  const float4* wl = Wp + (size_t)blockIdx.y * KG * 64 + lane;
+  const float4* wl = Wp + (size_t)by * KG * 64 + lane;
   floatx16 acc[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t)
@@ -232,6 +270,9 @@ __global__ __launch_bounds__(256) void pw_conv_f32_pk4_kernel(
     }
   }
 }
+__global__ __launch_bounds__(256) void pw_conv_f32_pk4_kernel(PwArgs a) {
+  pw_pk4_body(a, blockIdx.x, blockIdx.y);
+}
 
 // Packed operand copy: Wp[((t*KG + g)*64 + l)*4 + e] = A[32t + l%32][8g + 2e + l/32], zero
 // outside Mdim x Kdim, with A[m][k] = W[m*lda_m + k*lda_k].
@@ -254,25 +295,39 @@ void pw_pack_f32(hipStream_t st, const float* W, int lda_m, int lda_k, float* Wp
           cdiv(Kdim, 8), total);
 }
 
+// which product kernel serves a shape, and its grid
+struct PwPick { int var; dim3 grid; };
+static PwPick pw_pick(long NQ, int HW, int Kdim, int Mdim) {
+  const int mt = cdiv(Mdim, 32), KG = cdiv(Kdim, 8);
+  PwPick p;
+  // Measured on 32-sample micro-batches: 128-pixel wavefronts win from 56x56 images up,
+  // 32-pixel ones below (more wavefronts in flight matter more than bytes per instruction);
+  // under one block per CU and K >= 128 the block splits K instead.
+  if ((long)cdiv(NQ, 128) * mt < 256 && KG >= 16) { p.var = 2; p.grid = dim3((unsigned)cdiv(NQ, 32), mt); }
+  else if (HW % 4 == 0 && NQ >= 65536) { p.var = 3; p.grid = dim3((unsigned)cdiv(NQ, 512), mt); }
+  else if (Kdim > 32) { p.var = 1; p.grid = dim3((unsigned)cdiv(NQ, 128), mt); }
+  else { p.var = 0; p.grid = dim3((unsigned)cdiv(NQ, 128), mt); }
+  return p;
+}
+static PwArgs pw_args(const float* Wp, const float* X, float* Y, const float* bias, const float* add, int N, int Kdim,
+                      int Mdim, int HW) {
+  PwArgs a;
+  a.Wp = reinterpret_cast<const float4*>(Wp);
+  a.X = X; a.Y = Y; a.bias = bias; a.add = add;
+  a.NQ = (long)N * HW;
+  a.HW = HW; a.Kdim = Kdim; a.Mdim = Mdim; a.KG = cdiv(Kdim, 8);
+  return a;
+}
+
 void pw_conv_f32(hipStream_t st, const float* Wp, const float* X, float* Y, const float* bias, const float* add,
                  int N, int Kdim, int Mdim, int HW) {
-  const long NQ = (long)N * HW;
-  const int mt = cdiv(Mdim, 32), KG = cdiv(Kdim, 8);
-  const float4* wp = reinterpret_cast<const float4*>(Wp);
-  // Measured on 32-sample micro-batches: 128-pixel wavefronts win from 56x56 images up,
-  // 32-pixel ones below (more wavefronts in flight matter more than bytes per instruction).
-  if ((long)cdiv(NQ, 128) * mt < 256 && KG >= 16) {  // under one block per CU and K >= 128
-    KLAUNCH(pw_conv_f32_pkks_kernel, dim3((unsigned)cdiv(NQ, 32), mt), dim3(256), 0, st, wp, X, Y, bias, add, NQ, HW,
-            Kdim, Mdim, KG);
-  } else if (HW % 4 == 0 && NQ >= 65536) {
-    KLAUNCH(pw_conv_f32_pk4_kernel, dim3((unsigned)cdiv(NQ, 512), mt), dim3(256), 0, st, wp, X, Y, bias, add, NQ, HW,
-            Kdim, Mdim, KG);
-  } else if (Kdim > 32) {
-    KLAUNCH(pw_conv_f32_pk_kernel<2>, dim3((unsigned)cdiv(NQ, 128), mt), dim3(256), 0, st, wp, X, Y, bias, add, NQ, HW,
-            Kdim, Mdim, KG);
-  } else {
-    KLAUNCH(pw_conv_f32_pk_kernel<1>, dim3((unsigned)cdiv(NQ, 128), mt), dim3(256), 0, st, wp, X, Y, bias, add, NQ, HW,
-            Kdim, Mdim, KG);
+  const PwArgs a = pw_args(Wp, X, Y, bias, add, N, Kdim, Mdim, HW);
+  const PwPick p = pw_pick(a.NQ, HW, Kdim, Mdim);
+  switch (p.var) {
+    case 2: KLAUNCH(pw_conv_f32_pkks_kernel, p.grid, dim3(256), 0, st, a); break;
+    case 3: KLAUNCH(pw_conv_f32_pk4_kernel, p.grid, dim3(256), 0, st, a); break;
+    case 1: KLAUNCH(pw_conv_f32_pk_kernel<2>, p.grid, dim3(256), 0, st, a); break;
+    default: KLAUNCH(pw_conv_f32_pk_kernel<1>, p.grid, dim3(256), 0, st, a); break;
   }
 }
 
@@ -283,18 +338,19 @@ void pw_conv_f32(hipStream_t st, const float* Wp, const float* X, float* Y, cons
 // are added through LDS and written as one partial.  A second kernel adds the partials in a
 // fixed order and performs G += (in-place gradient accumulation).
 template <bool VEC>
-__global__ __launch_bounds__(256) void pw_wgrad_f32_kernel(const float* __restrict__ g,
-                                                           const float* __restrict__ x,
-                                                           float* __restrict__ part, int Cin, int Cout,
-                                                           int HW, int cps, int pxw) {
-  __shared__ float sR[4][16][64];
+__device__ __forceinline__ void pw_wgrad_body(const WgArgs& w, int bx, int by, int bz, float (*sR)[16][64]) {
+  const float* __restrict__ g = w.g;
+  const float* __restrict__ x = w.x;
+  float* __restrict__ part = w.part;
+  const int Cin = w.Cin, Cout = w.Cout, HW = w.HW, cps = w.cps, pxw = w.pxw;
+
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 31, half = lane >> 5;
-  const int chunk = blockIdx.x;
+  const int chunk = bx;
   const int n = chunk / cps;
   const int p0 = ((chunk - n * cps) * 4 + wave) * pxw;
   const int p1 = min(p0 + pxw, HW);
-  const int ci_base = blockIdx.y * 32, co_base = blockIdx.z * 32;
+  const int ci_base = by * 32, co_base = bz * 32;
   const bool av = co_base + row < Cout, bv = ci_base + row < Cin;
   const float* ga = g + ((size_t)n * Cout + (av ? co_base + row : 0)) * HW;
   const float* xb = x + ((size_t)n * Cin + (bv ? ci_base + row : 0)) * HW;
@@ -359,6 +415,35 @@ __global__ __launch_bounds__(256) void pw_wgrad_f32_kernel(const float* __restri
     }
   }
 }
+template <bool VEC>
+__global__ __launch_bounds__(256) void pw_wgrad_f32_kernel(WgArgs w) {
+  __shared__ float sR[4][16][64];
+  pw_wgrad_body<VEC>(w, blockIdx.x, blockIdx.y, blockIdx.z, sR);
+}
+
+// Input gradient and weight-gradient partials of one pointwise conv in ONE launch: the two
+// products only share their input g, and each alone is too short to fill the chip (they
+// are bound by the latency of one load-compute-store chain), so their blocks are dealt from
+// one grid: block ids [0, nA) form the (x, y) grid of the input-gradient product, the rest
+// the (x, y, z) grid of the weight-gradient kernel.  VAR selects the product kernel:
+// 0 / 1 = 32-pixel wavefronts with one / two 32-channel chunks per pass, 2 = K split over the
+// block, 3 = 128-pixel wavefronts.
+template <int VAR, bool VEC>
+__global__ __launch_bounds__(256) void pw_bwd_dual_kernel(PwArgs a, WgArgs w, unsigned nA, unsigned gAx,
+                                                          unsigned gWx, unsigned gWy) {
+  __shared__ float sR[4][16][64];
+  if (blockIdx.x < nA) {  // uniform per block
+    const int bx = (int)(blockIdx.x % gAx), by = (int)(blockIdx.x / gAx);
+    if (VAR == 0) pw_pk_body<1>(a, bx, by);
+    else if (VAR == 1) pw_pk_body<2>(a, bx, by);
+    else if (VAR == 2) pw_pkks_body(a, bx, by, sR);
+    else pw_pk4_body(a, bx, by);
+  } else {
+    const unsigned b = blockIdx.x - nA;
+    const unsigned bx = b % gWx, r = b / gWx;
+    pw_wgrad_body<VEC>(w, (int)bx, (int)(r % gWy), (int)(r / gWy), sR);
+  }
+}
 
 // G[i] += sum_c part[c][i]: 64 outputs per block, four interleaved part lanes, fixed order
 __global__ __launch_bounds__(256) void reduce_parts_acc_kernel(const float* __restrict__ part,
@@ -395,18 +480,49 @@ size_t pw_wgrad_f32_ws(int N, int Cin, int Cout, int HW) {
   int pxw = wg_pxw(N, Cin, Cout, HW);
   return (size_t)N * cdiv(HW, 4 * pxw) * Cin * Cout;
 }
+static WgArgs wg_args(const float* g, const float* x, float* part, int N, int Cin, int Cout, int HW, dim3& grid) {
+  WgArgs w;
+  w.g = g; w.x = x; w.part = part;
+  w.Cin = Cin; w.Cout = Cout; w.HW = HW;
+  w.pxw = wg_pxw(N, Cin, Cout, HW);
+  w.cps = cdiv(HW, 4 * w.pxw);
+  grid = dim3(N * w.cps, cdiv(Cin, 32), cdiv(Cout, 32));
+  return w;
+}
 void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, float* G, int N,
                   int Cin, int Cout, int HW) {
-  int pxw = wg_pxw(N, Cin, Cout, HW);
-  int cps = cdiv(HW, 4 * pxw);
-  int chunks = N * cps;
-  dim3 grid(chunks, cdiv(Cin, 32), cdiv(Cout, 32));
-  if (HW % 4 == 0)
-    KLAUNCH(pw_wgrad_f32_kernel<true>, grid, dim3(256), 0, st, g, x, part, Cin, Cout, HW, cps, pxw);
-  else
-    KLAUNCH(pw_wgrad_f32_kernel<false>, grid, dim3(256), 0, st, g, x, part, Cin, Cout, HW, cps, pxw);
+  dim3 grid;
+  const WgArgs w = wg_args(g, x, part, N, Cin, Cout, HW, grid);
+  if (HW % 4 == 0) KLAUNCH(pw_wgrad_f32_kernel<true>, grid, dim3(256), 0, st, w);
+  else KLAUNCH(pw_wgrad_f32_kernel<false>, grid, dim3(256), 0, st, w);
   size_t n = (size_t)Cin * Cout;
-  if (G) KLAUNCH(reduce_parts_acc_kernel, dim3(cdiv(n, 64)), dim3(256), 0, st, part, G, n, chunks);
+  if (G) KLAUNCH(reduce_parts_acc_kernel, dim3(cdiv(n, 64)), dim3(256), 0, st, part, G, n, (int)grid.x);
+}
+
+template <int VAR>
+static void launch_dual(hipStream_t st, const PwArgs& a, const WgArgs& w, dim3 gA, dim3 gW, bool vec) {
+  const unsigned nA = gA.x * gA.y, nW = gW.x * gW.y * gW.z;
+  constexpr const char* name = VAR == 0 ? "pw_bwd_dual_kernel<pk1>" : VAR == 1 ? "pw_bwd_dual_kernel<pk2>"
+                             : VAR == 2 ? "pw_bwd_dual_kernel<pkks>" : "pw_bwd_dual_kernel<pk4>";
+  if (vec) KLAUNCH_NAMED(name, (pw_bwd_dual_kernel<VAR, true>), dim3(nA + nW), dim3(256), 0, st, a, w, nA, gA.x, gW.x, gW.y);
+  else KLAUNCH_NAMED(name, (pw_bwd_dual_kernel<VAR, false>), dim3(nA + nW), dim3(256), 0, st, a, w, nA, gA.x, gW.x, gW.y);
+}
+
+void pw_conv_bwd_f32(hipStream_t st, const float* Wp_t, const float* g, float* dx, const float* add, const float* x,
+                     float* part, float* G, int N, int Cin, int Cout, int HW) {
+  const PwArgs a = pw_args(Wp_t, g, dx, nullptr, add, N, Cout, Cin, HW);  // dx = W^T g (+ add)
+  const PwPick p = pw_pick(a.NQ, HW, Cout, Cin);
+  dim3 gW;
+  const WgArgs w = wg_args(g, x, part, N, Cin, Cout, HW, gW);
+  const bool vec = HW % 4 == 0;
+  switch (p.var) {
+    case 2: launch_dual<2>(st, a, w, p.grid, gW, vec); break;
+    case 3: launch_dual<3>(st, a, w, p.grid, gW, vec); break;
+    case 1: launch_dual<1>(st, a, w, p.grid, gW, vec); break;
+    default: launch_dual<0>(st, a, w, p.grid, gW, vec); break;
+  }
+  size_t n = (size_t)Cin * Cout;
+  if (G) KLAUNCH(reduce_parts_acc_kernel, dim3(cdiv(n, 64)), dim3(256), 0, st, part, G, n, (int)gW.x);
 }
 
 __global__ __launch_bounds__(256) void reduce_tasks_kernel(const RedTask* __restrict__ tasks,
