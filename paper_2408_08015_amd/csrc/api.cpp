@@ -59,6 +59,11 @@ void free_stage(ast::Stage& s) {
   if (s.V) (void)hipFree(s.V);
   if (s.shadow) (void)hipFree(s.shadow);
   if (s.running) (void)hipFree(s.running);
+  if (s.pack_tasks) (void)hipFree(s.pack_tasks);
+  if (s.pack_block_task) (void)hipFree(s.pack_block_task);
+  s.pack_tasks = nullptr;
+  s.pack_block_task = nullptr;
+  s.pack_nblocks = 0;
   if (s.red_tasks) (void)hipFree(s.red_tasks);
   if (s.red_block_task) (void)hipFree(s.red_block_task);
   s.red_tasks = nullptr;

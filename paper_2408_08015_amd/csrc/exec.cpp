@@ -348,7 +348,41 @@ ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, std::strin
   return check_launch(err, "backward");
 }
 
+static ast_status build_pack_tasks(Stage& s, std::string& err) {
+  std::vector<PackTask> tasks;
+  std::vector<unsigned short> block_task;
+  auto add = [&](const float* W, int lda_m, int lda_k, size_t off, int Mdim, int Kdim) {
+    PackTask t = {};
+    t.W = W; t.lda_m = lda_m; t.lda_k = lda_k; t.Mdim = Mdim; t.Kdim = Kdim; t.KG = (Kdim + 7) / 8;
+    t.block0 = (unsigned)block_task.size();
+    if (off != (size_t)t.block0 * 256) return false;  // the arena is laid out in op order: cannot happen
+    for (size_t b = 0; b < pw_pack_floats(Mdim, Kdim) / 256; ++b) block_task.push_back((unsigned short)tasks.size());
+    tasks.push_back(t);
+    return true;
+  };
+  for (const Op& op : s.ops)
+    if (op.kind == OP_CONV_PW) {
+      if (tasks.size() + 2 >= 65535) return AST_OK;  // per-conv launches instead
+      if (!add(s.W + op.w_off, op.cin, 1, op.wp_off, op.cout, op.cin) ||
+          !add(s.W + op.w_off, 1, op.cin, op.wp2_off, op.cin, op.cout))
+        return AST_OK;
+    }
+  if (tasks.empty()) return AST_OK;
+  hipError_t e;
+  if ((e = hipMalloc(&s.pack_tasks, tasks.size() * sizeof(PackTask))) != hipSuccess ||
+      (e = hipMalloc((void**)&s.pack_block_task, block_task.size() * sizeof(unsigned short))) != hipSuccess ||
+      (e = hipMemcpy(s.pack_tasks, tasks.data(), tasks.size() * sizeof(PackTask), hipMemcpyHostToDevice)) != hipSuccess ||
+      (e = hipMemcpy(s.pack_block_task, block_task.data(), block_task.size() * sizeof(unsigned short),
+                     hipMemcpyHostToDevice)) != hipSuccess) {
+    err = std::string("pack task table: ") + hipGetErrorString(e);
+    return e == hipErrorOutOfMemory ? AST_ENOMEM : AST_EHIP;
+  }
+  s.pack_nblocks = (int)block_task.size();
+  return AST_OK;
+}
+
 ast_status build_reduce_tasks(Stage& s, std::string& err) {
+  if (ast_status r = build_pack_tasks(s, err)) return r;
   if (const char* e = getenv("ASTEROID_BATCHED_REDUCE"))
     if (e[0] == '0') return AST_OK;  // per-layer reduction launches instead
   std::vector<RedTask> tasks;
@@ -433,8 +467,11 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
 }
 
 ast_status refresh_shadow(Stage& s, std::string& err) {
+  if (s.pack_nblocks)
+    pw_pack_all_f32(s.stream, static_cast<const PackTask*>(s.pack_tasks), s.pack_block_task, s.wpack, s.pack_nblocks);
   for (const Op& op : s.ops) {
     if (op.kind == OP_CONV_PW) {
+      if (s.pack_nblocks) continue;
       pw_pack_f32(s.stream, s.W + op.w_off, op.cin, 1, s.wpack + op.wp_off, op.cout, op.cin);
       pw_pack_f32(s.stream, s.W + op.w_off, 1, op.cin, s.wpack + op.wp2_off, op.cin, op.cout);
     } else if (!s.bf16) {

@@ -18,6 +18,16 @@ typedef unsigned short bf16_t;
 // pass (A = W[Cout][Cin]) and the input gradient (A = W^T).
 size_t pw_pack_floats(int Mdim, int Kdim);
 void pw_pack_f32(hipStream_t st, const float* W, int lda_m, int lda_k, float* Wp, int Mdim, int Kdim);
+// All packed copies of a stage in one launch.  The copies lie back to back in `arena` in task
+// order (each pw_pack_floats() long = a whole number of 256-float blocks); block b of the
+// launch writes arena[256*b, +256) for task block_task[b], whose first block is block0.
+struct PackTask {
+  const float* W;
+  int lda_m, lda_k, Mdim, Kdim, KG;
+  unsigned block0;
+};
+void pw_pack_all_f32(hipStream_t st, const PackTask* tasks_dev, const unsigned short* block_task_dev, float* arena,
+                     int nblocks);
 void pw_conv_f32(hipStream_t st, const float* Wp, const float* X, float* Y, const float* bias,
                  const float* add, int N, int Kdim, int Mdim, int HW);
 // Weight gradient of the pointwise convolution, split over pixel chunks:

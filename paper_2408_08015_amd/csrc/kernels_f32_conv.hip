@@ -289,6 +289,25 @@ __global__ void pw_pack_kernel(const float* __restrict__ W, int lda_m, int lda_k
 
 size_t pw_pack_floats(int Mdim, int Kdim) { return (size_t)cdiv(Mdim, 32) * cdiv(Kdim, 8) * 256; }
 
+// Every packed copy of a stage in one launch: the copies sit back to back in one arena, each a
+// multiple of 256 floats, so block b (256 floats of the arena) belongs to one task.
+__global__ __launch_bounds__(256) void pw_pack_all_kernel(const PackTask* __restrict__ tasks,
+                                                          const unsigned short* __restrict__ block_task,
+                                                          float* __restrict__ arena) {
+  const PackTask t = tasks[block_task[blockIdx.x]];
+  const size_t i = (size_t)(blockIdx.x - t.block0) * 256 + threadIdx.x;  // index inside the copy
+  const int e = (int)(i & 3), l = (int)((i >> 2) & 63);
+  const size_t tg = i >> 8;
+  const int g = (int)(tg % t.KG), tt = (int)(tg / t.KG);
+  const int m = 32 * tt + (l & 31), k = 8 * g + 2 * e + (l >> 5);
+  arena[(size_t)blockIdx.x * 256 + threadIdx.x] =
+      (m < t.Mdim && k < t.Kdim) ? t.W[(size_t)m * t.lda_m + (size_t)k * t.lda_k] : 0.f;
+}
+void pw_pack_all_f32(hipStream_t st, const PackTask* tasks_dev, const unsigned short* block_task_dev, float* arena,
+                     int nblocks) {
+  KLAUNCH(pw_pack_all_kernel, dim3(nblocks), dim3(256), 0, st, tasks_dev, block_task_dev, arena);
+}
+
 void pw_pack_f32(hipStream_t st, const float* W, int lda_m, int lda_k, float* Wp, int Mdim, int Kdim) {
   const size_t total = pw_pack_floats(Mdim, Kdim);
   KLAUNCH(pw_pack_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, st, W, lda_m, lda_k, Wp, Mdim, Kdim,

@@ -99,6 +99,9 @@ struct Stage {
 
   // fp32 stages: the per-layer reductions of weight-gradient partials into G, batched into one
   // launch at the end of every backward pass (device-side task table, built at create)
+  void* pack_tasks = nullptr;            // PackTask[]: all packed pointwise-conv copies, one launch
+  unsigned short* pack_block_task = nullptr;
+  int pack_nblocks = 0;
   void* red_tasks = nullptr;             // RedTask[]
   unsigned short* red_block_task = nullptr;
   int red_nblocks = 0;
