@@ -68,9 +68,26 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
                   op.has_bias ? s.W + op.b_off : nullptr, nullptr, I.n, op.cin, op.cout, HW);
       break;
     case OP_CONV_DW:
-      dw3x3_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, (float*)act_ptr(c, op.out), I.n, I.c, I.h,
-                    I.w, op.stride);
+    {
+      DwBnIn bi{};
+      cf x = (cf)act_ptr(c, op.in);
+      if (op.bn_in_op >= 0) {  // normalise the BatchNorm's input on load; finish and record its statistics
+        const Op& bn = s.ops[op.bn_in_op];
+        const Act& BI = s.acts[bn.in];
+        float* aux = reinterpret_cast<float*>(c.slot + bn.aux_off);
+        x = (cf)act_ptr(c, bn.in);
+        bi.ws = reinterpret_cast<const double*>(scratch(c, bn));
+        bi.gamma = s.W + bn.w_off; bi.beta = s.W + bn.b_off;
+        bi.stat = aux; bi.ss = aux + 2 * I.c; bi.running = s.running + bn.run_off;
+        bi.count = (double)BI.n * BI.h * BI.w; bi.eps = bn.eps;
+        bi.P = bn.bn_stats_given ? BI.n : bn_parts(BI.n, BI.h * BI.w);
+        bi.act = bn.act; bi.on = 1;
+      }
+      dw3x3_fwd_f32(st, x, s.W + op.w_off, (float*)act_ptr(c, op.out), I.n, I.c, I.h, I.w, op.stride,
+                    op.bn_in_op >= 0 ? &bi : nullptr,
+                    op.bn_out_op >= 0 ? reinterpret_cast<double*>(scratch(c, s.ops[op.bn_out_op])) : nullptr);
       break;
+    }
     case OP_CONV_DIRECT:
       conv_direct_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, op.has_bias ? s.W + op.b_off : nullptr,
                           (float*)act_ptr(c, op.out), I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride,
@@ -82,9 +99,14 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       break;
     case OP_BN: {
       float* aux = reinterpret_cast<float*>(c.slot + op.aux_off);
-      bn_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, s.W + op.b_off,
-                 op.skip >= 0 ? (cf)act_ptr(c, op.skip) : nullptr, (float*)act_ptr(c, op.out), aux, aux + 2 * I.c,
-                 s.running + op.run_off, reinterpret_cast<double*>(scratch(c, op)), I.n, I.c, HW, op.eps, op.act);
+      double* ws = reinterpret_cast<double*>(scratch(c, op));
+      cf x = (cf)act_ptr(c, op.in);
+      // statistics: from the depthwise conv in front (one partial pair per plane) or a pass of its own
+      if (!op.bn_stats_given) bn_stats_f32(st, x, ws, I.n, I.c, HW);
+      if (!op.bn_lazy)  // else the depthwise conv behind normalises on load
+        bn_apply_f32(st, x, s.W + op.w_off, s.W + op.b_off, op.skip >= 0 ? (cf)act_ptr(c, op.skip) : nullptr,
+                     (float*)act_ptr(c, op.out), aux, aux + 2 * I.c, s.running + op.run_off, ws,
+                     op.bn_stats_given ? I.n : bn_parts(I.n, HW), I.n, I.c, HW, op.eps, op.act);
       break;
     }
     case OP_ACT:
@@ -168,8 +190,16 @@ void bwd_op(Ctx& c, const Op& op) {
     }
     case OP_CONV_DW: {
       cf g = (cf)grad_ptr(c, op.out);
-      dw3x3_bwd_f32(st, g, (cf)act_ptr(c, op.in), s.W + op.w_off, (float*)gin, reinterpret_cast<float*>(scratch(c, op)),
-                    s.red_nblocks ? nullptr : s.G + op.w_off, I.n, I.c, I.h, I.w, op.stride);
+      cf x = (cf)act_ptr(c, op.in), xss = nullptr;
+      int xact = 0;
+      if (op.bn_in_op >= 0) {  // recompute the BatchNorm output from its input and recorded coefficients
+        const Op& bn = s.ops[op.bn_in_op];
+        x = (cf)act_ptr(c, bn.in);
+        xss = reinterpret_cast<const float*>(c.slot + bn.aux_off) + 2 * I.c;
+        xact = bn.act;
+      }
+      dw3x3_bwd_f32(st, g, x, s.W + op.w_off, (float*)gin, reinterpret_cast<float*>(scratch(c, op)),
+                    s.red_nblocks ? nullptr : s.G + op.w_off, I.n, I.c, I.h, I.w, op.stride, xss, xact);
       break;
     }
     case OP_CONV_DIRECT: {

@@ -39,14 +39,37 @@ void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, f
                   int Cin, int Cout, int HW);
 
 // Depthwise 3x3 convolution, pad 1, stride 1 or 2, weights [C][3][3].
+// The forward kernel can take over the BatchNorm passes around it:
+// DwBnIn: its input is x' = act(x*scale[c] + shift[c]) of a BatchNorm over the tensor passed as x;
+//   the kernel finishes that BatchNorm's statistics from the P partial pairs ws[c][P][2]
+//   (records them as the BatchNorm's own apply pass would) and normalises while staging;
+// DwBnOut: it leaves per-plane (sum, sum of squares) of its output in ws[c][N][2] for the
+//   BatchNorm that follows.
+struct DwBnIn {
+  const double* ws;
+  const float* gamma;
+  const float* beta;
+  float* stat;
+  float* ss;
+  float* running;
+  double count;
+  float eps;
+  int P, act, on;
+};
+struct DwBnOut {
+  double* ws;
+  int on;
+};
+// bn_in (may be NULL): see DwBnIn, `on` must be 1; stats_out (may be NULL): DwBnOut's ws.
 void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int N, int C, int H,
-                   int W, int stride);
+                   int W, int stride, const DwBnIn* bn_in = nullptr, double* stats_out = nullptr);
 // Backward of the depthwise conv from one read of g and x: dx (skipped if NULL) and
 // G[C][3][3] += weight gradient.  `part` holds dw3x3_bwd_f32_ws(N, C) floats: N partials of
 // C*9 sums; with G = NULL the reduction is left to the caller (reduce_tasks_f32).
 size_t dw3x3_bwd_f32_ws(int N, int C);
+// With xss (scale[C], shift[C]) the convolution's input was act(x*scale + shift), recomputed on load.
 void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part,
-                   float* G, int N, int C, int H, int W, int stride);
+                   float* G, int N, int C, int H, int W, int stride, const float* xss = nullptr, int xact = 0);
 
 // Generic direct convolution (any k, stride, pad, groups); the fallback for shapes the
 // specialised kernels do not cover (e.g. a 3-channel stem).
@@ -94,6 +117,14 @@ void bn_fwd_f32(hipStream_t st, const float* x, const float* gamma, const float*
                 float eps, int act);
 // Backward: g' = g * act'(x*scale+shift); dbeta += sum g'; dgamma += sum g'*xhat;
 // dx = gamma*istd*(g' - mean(g') - xhat*mean(g'*xhat)); dx may be NULL (not wanted).
+// The two halves of bn_fwd_f32, for stages that take one of them over: statistics partials
+// ws[C][bn_parts(N, HW)][2] (sum, sum of squares), and the normalisation from P partial pairs per
+// channel (P = bn_parts() for bn_stats_f32's, or whatever the producer of `ws` wrote).
+int bn_parts(int N, int HW);
+void bn_stats_f32(hipStream_t st, const float* x, double* ws, int N, int C, int HW);
+void bn_apply_f32(hipStream_t st, const float* x, const float* gamma, const float* beta, const float* skip, float* y,
+                  float* stat, float* scale_shift, float* running, const double* ws, int P, int N, int C, int HW,
+                  float eps, int act);
 void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* scale_shift,
                 const float* gamma, float* dx, float* Ggamma, float* Gbeta, double* ws, int N, int C, int HW,
                 int act);

@@ -10,6 +10,7 @@
 //             into G.
 // Doing the tiny "finish the reduction" step inside the consumer removes two
 // latency-bound launches per BatchNorm per micro-batch.
+#include "bn_common.h"
 #include "device_utils.h"
 #include "kernels.h"
 #include "prof.h"
@@ -36,19 +37,6 @@ static inline BnSplit bn_split(int N, int HW) {
   return b;
 }
 size_t bn_ws_doubles(int C, int N, int HW) { return (size_t)C * bn_split(N, HW).P * 2; }
-
-// sums of the channel's P partial pairs in a fixed order, identical in every lane of the
-// calling wavefront
-__device__ __forceinline__ void add_partials(const double* __restrict__ ws, int c, int P, double& s1, double& s2) {
-  const int lane = threadIdx.x & 63;
-  double a = 0.0, b = 0.0;
-  for (int k = lane; k < P; k += 64) {
-    a += ws[((size_t)c * P + k) * 2 + 0];
-    b += ws[((size_t)c * P + k) * 2 + 1];
-  }
-  s1 = wave_sum_d(a);
-  s2 = wave_sum_d(b);
-}
 
 // both sums of a block in one pass; the result is valid in thread 0
 __device__ __forceinline__ void block_sum2(float f1, float f2, double* sh, double& d1, double& d2) {
@@ -111,28 +99,10 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
   const int plane = blockIdx.x, c = plane % C;
   if (threadIdx.x < 64) {
     double s1, s2;
-    add_partials(ws, c, S, s1, s2);
-    if (threadIdx.x == 0) {
-      double mean = s1 / count;
-      double var = s2 / count - mean * mean;
-      if (var < 0) var = 0;
-      double istd = 1.0 / sqrt(var + (double)eps);
-      double sc = (double)gamma[c] * istd;
-      float scf = (float)sc, sff = (float)((double)beta[c] - mean * sc);
-      coef[0] = scf;
-      coef[1] = sff;
-      if (plane < C && blockIdx.y == 0) {  // sample 0, chunk 0: record the channel's statistics
-        stat[c] = (float)mean;
-        stat[C + c] = (float)istd;
-        ss[c] = scf;
-        ss[C + c] = sff;
-        if (running) {
-          double unb = count > 1 ? var * count / (count - 1) : var;
-          running[c] += 0.1f * ((float)mean - running[c]);
-          running[C + c] += 0.1f * ((float)unb - running[C + c]);
-        }
-      }
-    }
+    bn_add_partials(ws, c, S, s1, s2);
+    if (threadIdx.x == 0)  // sample 0, chunk 0 records the channel's statistics
+      bn_coefficients(s1, s2, count, gamma[c], beta[c], eps, c, C, plane < C && blockIdx.y == 0, stat, ss, running,
+                      coef[0], coef[1]);
   }
   __syncthreads();
   const float sc = coef[0], sf = coef[1];
@@ -166,24 +136,34 @@ static inline void bn_chunking(int HW, int& nchunks, int& chunk) {
   nchunks = cdiv(HW, chunk);
 }
 
-void bn_fwd_f32(hipStream_t st, const float* x, const float* gamma, const float* beta, const float* skip,
-                float* y, float* stat, float* scale_shift, float* running, double* ws, int N, int C, int HW,
-                float eps, int act) {
-  size_t per = (size_t)N * HW;
+int bn_parts(int N, int HW) { return bn_split(N, HW).P; }
+
+void bn_stats_f32(hipStream_t st, const float* x, double* ws, int N, int C, int HW) {
   const BnSplit b = bn_split(N, HW);
-  const int S = b.P;
-  const bool vec = HW % 4 == 0;
-  if (vec) KLAUNCH(bn_stats_partial_kernel<true>, dim3(C, b.P), dim3(256), 0, st, x, ws, N, C, HW, b);
+  if (HW % 4 == 0) KLAUNCH(bn_stats_partial_kernel<true>, dim3(C, b.P), dim3(256), 0, st, x, ws, N, C, HW, b);
   else KLAUNCH(bn_stats_partial_kernel<false>, dim3(C, b.P), dim3(256), 0, st, x, ws, N, C, HW, b);
+}
+
+void bn_apply_f32(hipStream_t st, const float* x, const float* gamma, const float* beta, const float* skip, float* y,
+                  float* stat, float* scale_shift, float* running, const double* ws, int P, int N, int C, int HW,
+                  float eps, int act) {
+  size_t per = (size_t)N * HW;
   int nchunks, chunk;
   bn_chunking(HW, nchunks, chunk);
   dim3 grid((unsigned)(N * C), nchunks);
-  if (vec)
+  if (HW % 4 == 0)
     KLAUNCH(bn_apply_kernel<true>, grid, dim3(256), 0, st, x, ws, gamma, beta, skip, y, stat, scale_shift, running, C,
-            HW, S, (double)per, eps, act, chunk);
+            HW, P, (double)per, eps, act, chunk);
   else
     KLAUNCH(bn_apply_kernel<false>, grid, dim3(256), 0, st, x, ws, gamma, beta, skip, y, stat, scale_shift, running,
-            C, HW, S, (double)per, eps, act, chunk);
+            C, HW, P, (double)per, eps, act, chunk);
+}
+
+void bn_fwd_f32(hipStream_t st, const float* x, const float* gamma, const float* beta, const float* skip,
+                float* y, float* stat, float* scale_shift, float* running, double* ws, int N, int C, int HW,
+                float eps, int act) {
+  bn_stats_f32(st, x, ws, N, C, HW);
+  bn_apply_f32(st, x, gamma, beta, skip, y, stat, scale_shift, running, ws, bn_parts(N, HW), N, C, HW, eps, act);
 }
 
 template <bool VEC>
@@ -246,7 +226,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
   const int plane = blockIdx.x, c = plane % C;
   if (threadIdx.x < 64) {
     double s1, s2;
-    add_partials(ws, c, S, s1, s2);
+    bn_add_partials(ws, c, S, s1, s2);
     if (threadIdx.x == 0) {
       coef[0] = gamma[c] * stat[C + c];
       coef[1] = (float)(s1 / count);

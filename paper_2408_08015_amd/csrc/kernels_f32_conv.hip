@@ -11,6 +11,7 @@
 // Depthwise 3x3: a block stages whole (n, c) planes (they are contiguous) with a zero halo
 // in LDS; the backward kernel produces the input gradient and the nine weight-gradient
 // sums of each plane from one read of g and x.
+#include "bn_common.h"
 #include "device_utils.h"
 #include "kernels.h"
 #include "prof.h"
@@ -640,8 +641,10 @@ __device__ __forceinline__ void dw_zero(float* dst, int count) {
 // Copy one h x w plane into an LDS plane of (h+2) x (w+2) (halo already zero) with the tpp
 // threads of the plane's group (t = index in the group).  Four loads are issued before
 // the first LDS write so the memory latency is paid once per four elements, not per element.
+// With act >= 0 every element is first mapped to act(v*sc + sf): the plane is the input of a
+// BatchNorm(+activation) whose output is never written out.
 __device__ __forceinline__ void dw_stage_plane(float* dst, const float* __restrict__ src, int h, int w, int t,
-                                               int tpp) {
+                                               int tpp, float sc = 1.f, float sf = 0.f, int act = -1) {
   const int pw = w + 2;
   if ((w & 3) == 0) {
     const int nq = (h * w) >> 2, qpr = w >> 2;
@@ -659,6 +662,10 @@ __device__ __forceinline__ void dw_stage_plane(float* dst, const float* __restri
         if (q < nq) {
           int i = q / qpr, j = (q - i * qpr) * 4;
           float* d = dst + (i + 1) * pw + j + 1;
+          if (act >= 0) {
+            v[u].x = apply_act(v[u].x * sc + sf, act); v[u].y = apply_act(v[u].y * sc + sf, act);
+            v[u].z = apply_act(v[u].z * sc + sf, act); v[u].w = apply_act(v[u].w * sc + sf, act);
+          }
           d[0] = v[u].x; d[1] = v[u].y; d[2] = v[u].z; d[3] = v[u].w;
         }
       }
@@ -677,7 +684,7 @@ __device__ __forceinline__ void dw_stage_plane(float* dst, const float* __restri
         int e = e0 + u * tpp;
         if (e < ne) {
           int i = e / w, j = e - i * w;
-          dst[(i + 1) * pw + j + 1] = v[u];
+          dst[(i + 1) * pw + j + 1] = act >= 0 ? apply_act(v[u] * sc + sf, act) : v[u];
         }
       }
     }
@@ -686,32 +693,90 @@ __device__ __forceinline__ void dw_stage_plane(float* dst, const float* __restri
 
 __global__ __launch_bounds__(256) void dw3x3_fwd_f32_kernel(const float* __restrict__ x,
                                                             const float* __restrict__ w,
-                                                            float* __restrict__ y, DwGeom gm) {
+                                                            float* __restrict__ y, DwGeom gm, DwBnIn bi, DwBnOut bo) {
   extern __shared__ float sm[];
   const int PW = gm.W + 2, PSZ = (gm.H + 2) * PW;
   float* sx = sm;
-  float* sw = sm + gm.ppb * PSZ;  // [ppb][9]
+  float* sw = sm + gm.ppb * PSZ;   // [ppb][9]
+  float* scoef = sw + gm.ppb * 9;  // [ppb][2] scale, shift of the input BatchNorm
+  double* sred = reinterpret_cast<double*>(sm + ((gm.ppb * (PSZ + 11) + 1) & ~1));  // [4 waves][2]
   const int plane0 = blockIdx.x * gm.ppb;
   const int np = min(gm.ppb, gm.NC - plane0);
   const int tpp = 256 / gm.ppb;
   const int pl = threadIdx.x / tpp, t = threadIdx.x - pl * tpp;
-  dw_zero(sx, gm.ppb * PSZ);
-  if (pl < np) dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
+  const bool live = pl < np;
+  if (bi.on) {  // finish the statistics of each plane's channel: one wavefront per plane
+    for (int q = threadIdx.x >> 6; q < np; q += 4) {
+      const int plane = plane0 + q, c = plane % gm.C;
+      double s1, s2;
+      bn_add_partials(bi.ws, c, bi.P, s1, s2);
+      if ((threadIdx.x & 63) == 0)  // the sample-0 plane of a channel records its statistics
+        bn_coefficients(s1, s2, bi.count, bi.gamma[c], bi.beta[c], bi.eps, c, gm.C, plane < gm.C, bi.stat, bi.ss,
+                        bi.running, scoef[2 * q], scoef[2 * q + 1]);
+    }
+  }
+  dw_zero(sx, gm.ppb * PSZ);  // ends with a barrier: the coefficients are visible
+  if (live) {
+    if (bi.on)
+      dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp, scoef[2 * pl],
+                     scoef[2 * pl + 1], bi.act);
+    else
+      dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
+  }
   for (int i = threadIdx.x; i < np * 9; i += 256) sw[i] = w[((plane0 + i / 9) % gm.C) * 9 + i % 9];
   __syncthreads();
-  if (pl >= np) return;
-  const float* wc = sw + pl * 9;
-  const float w0 = wc[0], w1 = wc[1], w2 = wc[2], w3 = wc[3], w4 = wc[4], w5 = wc[5], w6 = wc[6], w7 = wc[7], w8 = wc[8];
-  const float* sp = sx + pl * PSZ;
-  float* yp = y + (size_t)(plane0 + pl) * gm.Ho * gm.Wo;
-  const int s = gm.stride;
-  for (int o = t; o < gm.Ho * gm.Wo; o += tpp) {
-    int i = o / gm.Wo, j = o - i * gm.Wo;
-    const float* b = sp + (i * s) * PW + j * s;
-    float acc = w0 * b[0] + w1 * b[1] + w2 * b[2];
-    acc += w3 * b[PW] + w4 * b[PW + 1] + w5 * b[PW + 2];
-    acc += w6 * b[2 * PW] + w7 * b[2 * PW + 1] + w8 * b[2 * PW + 2];
-    yp[o] = acc;
+  float s1 = 0.f, s2 = 0.f;
+  if (live) {
+    const float* wc = sw + pl * 9;
+    const float w0 = wc[0], w1 = wc[1], w2 = wc[2], w3 = wc[3], w4 = wc[4], w5 = wc[5], w6 = wc[6], w7 = wc[7], w8 = wc[8];
+    const float* sp = sx + pl * PSZ;
+    float* yp = y + (size_t)(plane0 + pl) * gm.Ho * gm.Wo;
+    const int s = gm.stride;
+    for (int o = t; o < gm.Ho * gm.Wo; o += tpp) {
+      int i = o / gm.Wo, j = o - i * gm.Wo;
+      const float* b = sp + (i * s) * PW + j * s;
+      float acc = w0 * b[0] + w1 * b[1] + w2 * b[2];
+      acc += w3 * b[PW] + w4 * b[PW + 1] + w5 * b[PW + 2];
+      acc += w6 * b[2 * PW] + w7 * b[2 * PW + 1] + w8 * b[2 * PW + 2];
+      yp[o] = acc;
+      s1 += acc;
+      s2 += acc * acc;
+    }
+  }
+  if (!bo.on) return;  // uniform
+  // per-plane (sum, sum of squares) of the output for the BatchNorm that follows: fp32 per
+  // thread, fp64 across the tpp threads of the plane (tpp is a power of two >= 16)
+  double d1 = (double)s1, d2 = (double)s2;
+  const int span = tpp < 64 ? tpp : 64;
+  for (int o = span >> 1; o > 0; o >>= 1) {
+    d1 += __shfl_xor(d1, o, 64);
+    d2 += __shfl_xor(d2, o, 64);
+  }
+  const int plane = plane0 + pl;
+  const int N = gm.NC / gm.C;
+  double* out = bo.ws + ((size_t)(plane % gm.C) * N + plane / gm.C) * 2;
+  if (tpp <= 64) {
+    if (live && t == 0) {
+      out[0] = d1;
+      out[1] = d2;
+    }
+  } else {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) {
+      sred[2 * wave] = d1;
+      sred[2 * wave + 1] = d2;
+    }
+    __syncthreads();
+    if (live && t == 0) {
+      const int w0i = threadIdx.x >> 6, nw = tpp >> 6;
+      double a = 0.0, b = 0.0;
+      for (int q = 0; q < nw; ++q) {
+        a += sred[2 * (w0i + q)];
+        b += sred[2 * (w0i + q) + 1];
+      }
+      out[0] = a;
+      out[1] = b;
+    }
   }
 }
 
@@ -722,7 +787,7 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
                                                             const float* __restrict__ x,
                                                             const float* __restrict__ w,
                                                             float* __restrict__ dx, float* __restrict__ part,
-                                                            DwGeom gm) {
+                                                            DwGeom gm, const float* __restrict__ xss, int xact) {
   extern __shared__ float sm[];
   const int PW = gm.W + 2, PSZ = (gm.H + 2) * PW;
   const int GW = gm.Wo + 2, GSZ = (gm.Ho + 2) * GW;
@@ -737,7 +802,12 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
   const bool live = pl < np;
   dw_zero(sx, gm.ppb * (PSZ + GSZ));  // sx and sg are adjacent
   if (live) {
-    dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
+    const int ch = (plane0 + pl) % gm.C;
+    if (xss)  // x is the input of a BatchNorm(+activation) whose output the convolution saw
+      dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp, xss[ch], xss[gm.C + ch],
+                     xact);
+    else
+      dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
     dw_stage_plane(sg + pl * GSZ, g + (size_t)(plane0 + pl) * gm.Ho * gm.Wo, gm.Ho, gm.Wo, t, tpp);
   }
   for (int i = threadIdx.x; i < np * 9; i += 256) sw[i] = w[((plane0 + i / 9) % gm.C) * 9 + i % 9];
@@ -814,6 +884,11 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
 // image border.  Per row a lane issues one 16-byte load of g and of x (one row ahead of
 // use) and one 16-byte store of dx; the nine weight-gradient sums stay in registers and
 // are reduced over the wavefront at the end.
+__device__ __forceinline__ float4 dw_norm4(float4 v, float sc, float sf, int act) {
+  v.x = apply_act(v.x * sc + sf, act); v.y = apply_act(v.y * sc + sf, act);
+  v.z = apply_act(v.z * sc + sf, act); v.w = apply_act(v.w * sc + sf, act);
+  return v;
+}
 struct DwRow { float v[6]; };  // v[0] = column 4s-1, v[1..4] = the strip, v[5] = column 4s+4
 __device__ __forceinline__ DwRow dw_make_row(float4 c, int s, int SW) {
   DwRow r;
@@ -827,7 +902,8 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
                                                                const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ dx,
                                                                float* __restrict__ part, int NC, int C, int H,
-                                                               int W, int RPG) {
+                                                               int W, int RPG, const float* __restrict__ xss,
+                                                               int xact) {
   const int lane = threadIdx.x & 63;
   const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (plane >= NC) return;  // whole wavefront
@@ -848,9 +924,17 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
   auto ld = [&](const float* base, int row) -> float4 {
     return (has && row >= 0 && row < H) ? *reinterpret_cast<const float4*>(base + (size_t)row * W) : z4;
   };
-  DwRow gm = dw_make_row(ld(gp, r0 - 1), s, SW), xm = dw_make_row(ld(xp, r0 - 1), s, SW);
-  DwRow gc = dw_make_row(ld(gp, r0), s, SW), xc = dw_make_row(ld(xp, r0), s, SW);
-  float4 gn = ld(gp, r0 + 1), xn = ld(xp, r0 + 1);
+  // with xss the convolution's input was act(x*scale + shift) (a BatchNorm whose output is not
+  // kept); the padding around it stays zero
+  const float xsc = xss ? xss[plane % C] : 1.f, xsf = xss ? xss[C + plane % C] : 0.f;
+  auto ldx = [&](int row) -> float4 {
+    if (!(has && row >= 0 && row < H)) return z4;
+    const float4 v = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
+    return xss ? dw_norm4(v, xsc, xsf, xact) : v;
+  };
+  DwRow gm = dw_make_row(ld(gp, r0 - 1), s, SW), xm = dw_make_row(ldx(r0 - 1), s, SW);
+  DwRow gc = dw_make_row(ld(gp, r0), s, SW), xc = dw_make_row(ldx(r0), s, SW);
+  float4 gn = ld(gp, r0 + 1), xn = ldx(r0 + 1);
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
@@ -859,7 +943,7 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
     const DwRow gq = dw_make_row(gn, s, SW), xq = dw_make_row(xn, s, SW);
     // past its last row a lane must not see the next group's rows as its own window
     gn = (a + 2 <= r1) ? ld(gp, a + 2) : z4;
-    xn = (a + 2 <= r1) ? ld(xp, a + 2) : z4;
+    xn = (a + 2 <= r1) ? ldx(a + 2) : z4;
     if (a < r1) {
       if (dp) {
         float o[4];
@@ -937,7 +1021,8 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
                                                                const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ dx,
                                                                float* __restrict__ part, int NC, int C, int H,
-                                                               int W, int RPG) {
+                                                               int W, int RPG, const float* __restrict__ xss,
+                                                               int xact) {
   const int lane = threadIdx.x & 63;
   const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (plane >= NC) return;  // whole wavefront
@@ -955,8 +1040,11 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
   for (int k = 0; k < 9; ++k) wk[k] = wc[k];
   const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   const float2 z2 = make_float2(0.f, 0.f);
-  auto ldx = [&](int row) -> float4 {
-    return (has && row >= 0 && row < H) ? *reinterpret_cast<const float4*>(xp + (size_t)row * W) : z4;
+  const float xsc = xss ? xss[plane % C] : 1.f, xsf = xss ? xss[C + plane % C] : 0.f;
+  auto ldx = [&](int row) -> float4 {  // with xss: the BatchNorm(+activation) output the convolution saw
+    if (!(has && row >= 0 && row < H)) return z4;
+    const float4 v = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
+    return xss ? dw_norm4(v, xsc, xsf, xact) : v;
   };
   auto ldg = [&](int row) -> float2 {
     return (has && row >= 0 && row < Ho) ? *reinterpret_cast<const float2*>(gp + (size_t)row * Wo) : z2;
@@ -1027,33 +1115,37 @@ static DwGeom dw_geom(int N, int C, int H, int W, int stride) {
 }
 
 void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int N, int C, int H, int W,
-                   int stride) {
+                   int stride, const DwBnIn* bn_in, double* stats_out) {
   DwGeom gm = dw_geom(N, C, H, W, stride);
-  size_t lds = ((size_t)gm.ppb * ((H + 2) * (W + 2) + 9)) * sizeof(float);
+  DwBnIn bi{};
+  if (bn_in) bi = *bn_in;
+  DwBnOut bo{stats_out, stats_out != nullptr};
+  // planes, weights, coefficients; then (8-byte aligned) four pairs of doubles
+  size_t lds = ((((size_t)gm.ppb * ((H + 2) * (W + 2) + 11)) + 1) & ~(size_t)1) * sizeof(float) + 8 * sizeof(double);
   (void)hipFuncSetAttribute((const void*)dw3x3_fwd_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  KLAUNCH(dw3x3_fwd_f32_kernel, dim3(cdiv(gm.NC, gm.ppb)), dim3(256), lds, st, x, w, y, gm);
+  KLAUNCH(dw3x3_fwd_f32_kernel, dim3(cdiv(gm.NC, gm.ppb)), dim3(256), lds, st, x, w, y, gm, bi, bo);
 }
 size_t dw3x3_bwd_f32_ws(int N, int C) { return (size_t)N * C * 9; }
 void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part,
-                   float* G, int N, int C, int H, int W, int stride) {
+                   float* G, int N, int C, int H, int W, int stride, const float* xss, int xact) {
   if (stride == 1 && W % 4 == 0 && W <= 256) {
     const int groups = 64 / (W / 4);
     KLAUNCH(dw3x3_bwd_s1_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
-            cdiv(H, groups));
+            cdiv(H, groups), xss, xact);
     if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
     return;
   }
   if (stride == 2 && W % 4 == 0 && H % 2 == 0 && W <= 256) {
     const int groups = 64 / (W / 4);
     KLAUNCH(dw3x3_bwd_s2_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
-            cdiv(H / 2, groups));
+            cdiv(H / 2, groups), xss, xact);
     if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
     return;
   }
   DwGeom gm = dw_geom(N, C, H, W, stride);
   size_t lds = ((size_t)gm.ppb * ((H + 2) * (W + 2) + (gm.Ho + 2) * (gm.Wo + 2) + 9) + 36) * sizeof(float);
   (void)hipFuncSetAttribute((const void*)dw3x3_bwd_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  KLAUNCH(dw3x3_bwd_f32_kernel, dim3(cdiv(gm.NC, gm.ppb)), dim3(256), lds, st, g, x, w, dx, part, gm);
+  KLAUNCH(dw3x3_bwd_f32_kernel, dim3(cdiv(gm.NC, gm.ppb)), dim3(256), lds, st, g, x, w, dx, part, gm, xss, xact);
   if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
 }
 

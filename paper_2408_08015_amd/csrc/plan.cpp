@@ -2,6 +2,7 @@
 // layout of the flat arenas, the stash slot and the workspace.  Host code only.
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 
 #include "kernels.h"
 #include "kernels_bf16.h"
@@ -290,6 +291,35 @@ ast_status build_plan(Stage& s, std::string& err) {
     }
   }
 
+  // fp32 inverted-residual pattern BN(+act) -> depthwise 3x3 -> BN: the first BatchNorm's apply pass
+  // and the second one's statistics pass move into the convolution (ASTEROID_BN_FUSE=0 keeps them).
+  std::vector<char> virtual_act(s.acts.size(), 0);  // activations that are never materialised
+  {
+    const char* e = getenv("ASTEROID_BN_FUSE");
+    const bool fuse = !(e && e[0] == '0');
+    for (size_t j = 0; fuse && j < s.ops.size(); ++j) {
+      Op& dw = s.ops[j];
+      if (dw.kind != OP_CONV_DW) continue;
+      if (j > 0) {
+        Op& bn = s.ops[j - 1];
+        if (bn.kind == OP_BN && bn.out == dw.in && bn.skip < 0) {
+          bn.bn_lazy = true;
+          dw.bn_in_op = (int)j - 1;
+          virtual_act[bn.out] = 1;
+          for (int& la : s.layer_act)
+            if (la == bn.out) la = -1;
+        }
+      }
+      if (j + 1 < s.ops.size()) {
+        Op& bn = s.ops[j + 1];
+        if (bn.kind == OP_BN && bn.in == dw.out) {
+          bn.bn_stats_given = true;
+          dw.bn_out_op = (int)j + 1;
+        }
+      }
+    }
+  }
+
   // Stash slot: every activation (the stage input is copied in; the final output goes to
   // the caller's buffer) followed by the per-op extras.
   size_t off = 0;
@@ -302,6 +332,7 @@ ast_status build_plan(Stage& s, std::string& err) {
       s.final_in_slot = true;
   for (size_t a = 0; a < s.acts.size(); ++a) {
     if ((int)a == final_act && !s.loss_tail && a != 0 && !s.final_in_slot) continue;
+    if (virtual_act[a]) continue;
     s.acts[a].slot_off = off;
     off = align_up(off + s.acts[a].bytes, 256);
   }
@@ -335,7 +366,7 @@ ast_status build_plan(Stage& s, std::string& err) {
         need = conv_direct_wgrad_ws(I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride, op.pad, op.groups) * sizeof(float);
         break;
       case OP_BN:
-        need = bn_ws_doubles(I.c, I.n, I.h * I.w) * sizeof(double);
+        need = std::max(bn_ws_doubles(I.c, I.n, I.h * I.w), (size_t)2 * I.c * I.n) * sizeof(double);
         break;
       case OP_CONV_IGEMM:  // masked upstream gradient + split-K partials
         need = align_up(s.acts[op.out].bytes, 256) + conv_bf16_ws_bytes(I.n, I.h, I.w, op.cin, op.cout, op.k);

@@ -66,6 +66,12 @@ struct Op {
   size_t sh_off = 0, sh2_off = 0;     // bf16 weight copies (elements) in the shadow arena
   size_t wp_off = 0, wp2_off = 0;     // fp32 pointwise conv: packed forward / dgrad operands (floats)
   size_t sc_off = 0;                  // this op's private scratch region (bytes past scratch_off)
+  // fp32 BatchNorm passes taken over by the depthwise conv next to them:
+  bool bn_lazy = false;               // BatchNorm(+act) feeding a depthwise conv: the output is never written; the
+                                      // conv normalises on load (forward and backward) and finishes the statistics
+  bool bn_stats_given = false;        // BatchNorm behind a depthwise conv: the conv's epilogue leaves per-plane sums
+  int bn_in_op = -1;                  // depthwise conv: index of the lazy BatchNorm op in front
+  int bn_out_op = -1;                 // depthwise conv: index of the BatchNorm op it writes statistics for
 };
 
 struct Stage {
