@@ -38,6 +38,19 @@ def kernel_model(cfg):
     shape = tuple(cfg.in_shape)
     first = True
     res_open = False
+    # BatchNorm passes that the depthwise conv next to them takes over (fp32): the apply pass of a
+    # BatchNorm(+ReLU) directly in front, the statistics pass of a BatchNorm directly behind
+    lazy_bn, given_bn = set(), set()
+    kinds = [L["kind"] for L in cfg.layers]
+    for i, L in enumerate(cfg.layers):
+        if L["kind"] == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"] \
+                and L.get("pad", 1) == 1 and not L.get("bias", False):
+            if i >= 1 and kinds[i - 1] == "batchnorm2d":
+                lazy_bn.add(i - 1)
+            elif i >= 2 and kinds[i - 1] in ("relu", "relu6") and kinds[i - 2] == "batchnorm2d":
+                lazy_bn.add(i - 2)
+            if i + 1 < len(kinds) and kinds[i + 1] == "batchnorm2d":
+                given_bn.add(i + 1)
     for i, L in enumerate(cfg.layers):
         k = L["kind"]
         oshape = gen.out_shape([L], shape)
@@ -72,16 +85,22 @@ def kernel_model(cfg):
             if w % 4 == 0 and (L["stride"] == 1 or h % 2 == 0):
                 oc, oh, ow = oshape
                 name = "dw3x3_bwd_s%d_f32_kernel" % L["stride"]
-                out.setdefault(name, []).append(4 * B * (2 * c * h * w + oc * oh * ow))   # g, x in; dx out
+                # g, x in; dx out; with a BatchNorm behind also the conv output (that BatchNorm's input)
+                ny = 2 if (i + 1) in given_bn else 1
+                out.setdefault(name, []).append(4 * B * (2 * c * h * w + ny * oc * oh * ow))
         if k == "batchnorm2d":
             c, h, w = shape
             vec = "<true>" if (h * w) % 4 == 0 else "<false>"
             n_el = B * c * h * w
-            out.setdefault("bn_stats_partial_kernel" + vec, []).append(4 * n_el)
-            out.setdefault("bn_apply_kernel" + vec, []).append(8 * n_el)                  # (+4 with a fused skip)
-            out.setdefault("bn_bwd_partial_kernel" + vec, []).append(8 * n_el)
-            # g and x in, dx out (no dx for a BatchNorm on the stage input when it is not wanted)
-            out.setdefault("bn_bwd_apply_kernel", []).append((12 if (not first or cfg.needs_input_grad) else 8) * B * c * h * w)
+            if i not in given_bn:
+                out.setdefault("bn_stats_partial_kernel" + vec, []).append(4 * n_el)
+            if i not in lazy_bn:
+                out.setdefault("bn_apply_kernel" + vec, []).append(8 * n_el)              # (+4 with a fused skip)
+            if i not in lazy_bn:     # else the depthwise conv behind leaves the sums
+                out.setdefault("bn_bwd_partial_kernel" + vec, []).append(8 * n_el)
+            if i not in given_bn:    # else the depthwise conv in front forms the input gradient on load
+                # g and x in, dx out (no dx for a BatchNorm on the stage input when it is not wanted)
+                out.setdefault("bn_bwd_apply_kernel", []).append((12 if (not first or cfg.needs_input_grad) else 8) * B * c * h * w)
         if k == "conv2d" and cfg.dtype == "bf16":
             cin, cout, kk = L["cin"], L["cout"], L["k"] * L["k"]
             m = B * shape[1] * shape[2]

@@ -190,16 +190,34 @@ void bwd_op(Ctx& c, const Op& op) {
     }
     case OP_CONV_DW: {
       cf g = (cf)grad_ptr(c, op.out);
-      cf x = (cf)act_ptr(c, op.in), xss = nullptr;
-      int xact = 0;
+      cf x = (cf)act_ptr(c, op.in);
+      DwBwdFuse f;
       if (op.bn_in_op >= 0) {  // recompute the BatchNorm output from its input and recorded coefficients
         const Op& bn = s.ops[op.bn_in_op];
+        const float* aux = reinterpret_cast<const float*>(c.slot + bn.aux_off);
         x = (cf)act_ptr(c, bn.in);
-        xss = reinterpret_cast<const float*>(c.slot + bn.aux_off) + 2 * I.c;
-        xact = bn.act;
+        f.xss = aux + 2 * I.c;
+        f.xact = bn.act;
+        if (bn.bn_bwd_sums_given) {  // and leave that BatchNorm's backward sums, one pair per plane
+          f.xstat = aux;
+          f.ws_in = reinterpret_cast<double*>(scratch(c, bn));
+        }
+      }
+      if (op.bn_bwd_out_op >= 0) {  // the upstream gradient is still the BatchNorm's: finish its backward on load
+        const Op& bn = s.ops[op.bn_bwd_out_op];
+        const Act& O = s.acts[op.out];
+        const float* aux = reinterpret_cast<const float*>(c.slot + bn.aux_off);
+        g = (cf)grad_ptr(c, bn.out);
+        f.y = (cf)act_ptr(c, op.out);
+        f.ystat = aux; f.yss = aux + 2 * O.c; f.ygamma = s.W + bn.w_off;
+        f.ws_out = reinterpret_cast<const double*>(scratch(c, bn));
+        f.Ggamma = s.G + bn.w_off; f.Gbeta = s.G + bn.b_off;
+        f.ycount = (double)O.n * O.h * O.w;
+        f.P_out = bn.bn_bwd_sums_given ? O.n : bn_parts(O.n, O.h * O.w);
+        f.yact = bn.act;
       }
       dw3x3_bwd_f32(st, g, x, s.W + op.w_off, (float*)gin, reinterpret_cast<float*>(scratch(c, op)),
-                    s.red_nblocks ? nullptr : s.G + op.w_off, I.n, I.c, I.h, I.w, op.stride, xss, xact);
+                    s.red_nblocks ? nullptr : s.G + op.w_off, I.n, I.c, I.h, I.w, op.stride, &f);
       break;
     }
     case OP_CONV_DIRECT: {
@@ -235,9 +253,15 @@ void bwd_op(Ctx& c, const Op& op) {
     }
     case OP_BN: {
       float* aux = reinterpret_cast<float*>(c.slot + op.aux_off);
-      bn_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), aux, aux + 2 * I.c, s.W + op.w_off,
-                 (float*)gin, s.G + op.w_off, s.G + op.b_off, reinterpret_cast<double*>(scratch(c, op)), I.n, I.c, HW,
-                 op.act);
+      double* ws = reinterpret_cast<double*>(scratch(c, op));
+      cf g = (cf)grad_ptr(c, op.out), x = (cf)act_ptr(c, op.in);
+      // partial sums: left per plane by the backward of the depthwise conv behind (it ran just before), or
+      // a pass of its own; input gradient: formed by the depthwise conv in front on load, or a pass of its own
+      const bool given = op.bn_bwd_sums_given;
+      if (!given) bn_bwd_partial_f32(st, g, x, aux, aux + 2 * I.c, ws, I.n, I.c, HW, op.act);
+      if (!op.bn_bwd_apply_fused)
+        bn_bwd_apply_f32(st, g, x, aux, aux + 2 * I.c, s.W + op.w_off, ws, given ? I.n : bn_parts(I.n, HW), (float*)gin,
+                         s.G + op.w_off, s.G + op.b_off, I.n, I.c, HW, op.act);
       break;
     }
     case OP_ACT:

@@ -67,9 +67,31 @@ void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int
 // G[C][3][3] += weight gradient.  `part` holds dw3x3_bwd_f32_ws(N, C) floats: N partials of
 // C*9 sums; with G = NULL the reduction is left to the caller (reduce_tasks_f32).
 size_t dw3x3_bwd_f32_ws(int N, int C);
-// With xss (scale[C], shift[C]) the convolution's input was act(x*scale + shift), recomputed on load.
+// Optional BatchNorm work of the depthwise backward kernel (a NULL pointer switches a part off).
+struct DwBwdFuse {
+  // BatchNorm(+act) in front of the conv whose output was never written: the conv's input is
+  // act(x*xss[c] + xss[C + c]), recomputed on load
+  const float* xss = nullptr;
+  int xact = 0;
+  // ... and that BatchNorm's backward sums, one pair per plane: ws_in[c][N][2] =
+  // (sum g', sum g'*xhat), g' = dx*act'(.), xhat = (x - xstat[c])*xstat[C + c]; needs xss and dx
+  const float* xstat = nullptr;
+  double* ws_in = nullptr;
+  // BatchNorm(+act) behind the conv: `g` is THAT BatchNorm's upstream gradient, y its input (the
+  // conv's output); the conv's own upstream gradient is the BatchNorm's input gradient, formed on
+  // load from g, y and the backward sums ws_out[c][P_out][2]; the kernel adds dgamma and dbeta
+  const float* y = nullptr;
+  const float* ystat = nullptr;   // mean[C], 1/std[C]
+  const float* yss = nullptr;     // scale[C], shift[C]
+  const float* ygamma = nullptr;
+  const double* ws_out = nullptr;
+  float* Ggamma = nullptr;
+  float* Gbeta = nullptr;
+  double ycount = 0;              // elements per channel of y
+  int P_out = 0, yact = 0;
+};
 void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part,
-                   float* G, int N, int C, int H, int W, int stride, const float* xss = nullptr, int xact = 0);
+                   float* G, int N, int C, int H, int W, int stride, const DwBwdFuse* fuse = nullptr);
 
 // Generic direct convolution (any k, stride, pad, groups); the fallback for shapes the
 // specialised kernels do not cover (e.g. a 3-channel stem).
@@ -128,6 +150,13 @@ void bn_apply_f32(hipStream_t st, const float* x, const float* gamma, const floa
 void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* scale_shift,
                 const float* gamma, float* dx, float* Ggamma, float* Gbeta, double* ws, int N, int C, int HW,
                 int act);
+// Its two halves: the partial sums ws[C][bn_parts(N, HW)][2] = (sum g', sum g'*xhat), and the input
+// gradient (+ dgamma, dbeta) from P partial pairs per channel, whoever wrote them.
+void bn_bwd_partial_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* scale_shift,
+                        double* ws, int N, int C, int HW, int act);
+void bn_bwd_apply_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* scale_shift,
+                      const float* gamma, const double* ws, int P, float* dx, float* Ggamma, float* Gbeta, int N,
+                      int C, int HW, int act);
 
 // Elementwise
 void act_fwd_f32(hipStream_t st, const float* x, float* y, size_t n, int act);

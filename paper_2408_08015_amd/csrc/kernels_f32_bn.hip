@@ -262,25 +262,36 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
   }
 }
 
-void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* ss,
-                const float* gamma, float* dx, float* Ggamma, float* Gbeta, double* ws, int N, int C, int HW,
-                int act) {
-  size_t per = (size_t)N * HW;
+void bn_bwd_partial_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* ss,
+                        double* ws, int N, int C, int HW, int act) {
   const BnSplit b = bn_split(N, HW);
-  const int S = b.P;
-  const bool vec = HW % 4 == 0;
-  if (vec) KLAUNCH(bn_bwd_partial_kernel<true>, dim3(C, b.P), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, b, act);
-  else KLAUNCH(bn_bwd_partial_kernel<false>, dim3(C, b.P), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, b, act);
+  if (HW % 4 == 0)
+    KLAUNCH(bn_bwd_partial_kernel<true>, dim3(C, b.P), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, b, act);
+  else
+    KLAUNCH(bn_bwd_partial_kernel<false>, dim3(C, b.P), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, b, act);
+}
+
+void bn_bwd_apply_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* ss,
+                      const float* gamma, const double* ws, int P, float* dx, float* Ggamma, float* Gbeta, int N,
+                      int C, int HW, int act) {
+  size_t per = (size_t)N * HW;
   int nchunks, chunk;
   bn_chunking(HW, nchunks, chunk);
   // without an input gradient only the sample-0 / chunk-0 blocks have work (dgamma, dbeta)
   dim3 grid(dx ? (unsigned)(N * C) : (unsigned)C, dx ? nchunks : 1);
-  if (vec)
-    KLAUNCH(bn_bwd_apply_kernel<true>, grid, dim3(256), 0, st, g, x, stat, ss, gamma, ws, dx, Ggamma, Gbeta, C, HW, S,
+  if (HW % 4 == 0)
+    KLAUNCH(bn_bwd_apply_kernel<true>, grid, dim3(256), 0, st, g, x, stat, ss, gamma, ws, dx, Ggamma, Gbeta, C, HW, P,
             (double)per, act, chunk);
   else
     KLAUNCH(bn_bwd_apply_kernel<false>, grid, dim3(256), 0, st, g, x, stat, ss, gamma, ws, dx, Ggamma, Gbeta, C, HW,
-            S, (double)per, act, chunk);
+            P, (double)per, act, chunk);
+}
+
+void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* ss,
+                const float* gamma, float* dx, float* Ggamma, float* Gbeta, double* ws, int N, int C, int HW,
+                int act) {
+  bn_bwd_partial_f32(st, g, x, stat, ss, ws, N, C, HW, act);
+  bn_bwd_apply_f32(st, g, x, stat, ss, gamma, ws, bn_parts(N, HW), dx, Ggamma, Gbeta, N, C, HW, act);
 }
 
 }  // namespace ast

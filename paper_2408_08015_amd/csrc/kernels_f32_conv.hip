@@ -780,6 +780,31 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_f32_kernel(const float* __restr
   }
 }
 
+// BatchNorm backward folded into the load of the conv's upstream gradient (see DwBwdFuse)
+struct DwBnBwd {
+  float k, m1, m2, mean, istd, sc, sf;
+  int act;
+};
+__device__ __forceinline__ float dw_bn_dx(float g, float y, const DwBnBwd& b) {
+  return b.k * (g * act_mask(y * b.sc + b.sf, b.act) - b.m1 - (y - b.mean) * b.istd * b.m2);
+}
+// whole wavefront: finish the backward sums of channel c; with `record` lane 0 adds dbeta, dgamma
+__device__ __forceinline__ DwBnBwd dw_bn_bwd_coef(const DwBwdFuse& f, int c, int C, bool record) {
+  double s1, s2;
+  bn_add_partials(f.ws_out, c, f.P_out, s1, s2);
+  DwBnBwd b;
+  b.mean = f.ystat[c]; b.istd = f.ystat[C + c]; b.sc = f.yss[c]; b.sf = f.yss[C + c];
+  b.k = f.ygamma[c] * b.istd;
+  b.m1 = (float)(s1 / f.ycount);
+  b.m2 = (float)(s2 / f.ycount);
+  b.act = f.yact;
+  if (record && (threadIdx.x & 63) == 0) {
+    f.Gbeta[c] += (float)s1;
+    f.Ggamma[c] += (float)s2;
+  }
+  return b;
+}
+
 // Input gradient (if dx) and the nine weight-gradient sums of every plane:
 //   dx[i][j] = sum_{u,v} w[u][v] g[(i+1-u)/s][(j+1-v)/s]   (terms with a non-integer index drop)
 //   part[plane][u*3+v] = sum_{i,j} g[i][j] x[i*s-1+u][j*s-1+v]
@@ -787,41 +812,67 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
                                                             const float* __restrict__ x,
                                                             const float* __restrict__ w,
                                                             float* __restrict__ dx, float* __restrict__ part,
-                                                            DwGeom gm, const float* __restrict__ xss, int xact) {
+                                                            DwGeom gm, DwBwdFuse f) {
   extern __shared__ float sm[];
   const int PW = gm.W + 2, PSZ = (gm.H + 2) * PW;
   const int GW = gm.Wo + 2, GSZ = (gm.Ho + 2) * GW;
   float* sx = sm;
   float* sg = sx + gm.ppb * PSZ;
-  float* sw = sg + gm.ppb * GSZ;  // [ppb][9]
-  float* sred = sw + gm.ppb * 9;  // [4 waves][9]
+  float* sw = sg + gm.ppb * GSZ;   // [ppb][9]
+  float* sred = sw + gm.ppb * 9;   // [4 waves][11]
+  float* scoef = sred + 44;        // [ppb][3]: k, m1, m2 of the BatchNorm behind the conv
   const int plane0 = blockIdx.x * gm.ppb;
   const int np = min(gm.ppb, gm.NC - plane0);
   const int tpp = 256 / gm.ppb;
   const int pl = threadIdx.x / tpp, t = threadIdx.x - pl * tpp;
   const bool live = pl < np;
-  dw_zero(sx, gm.ppb * (PSZ + GSZ));  // sx and sg are adjacent
+  if (f.y) {  // one wavefront per plane finishes the sums of the BatchNorm behind the conv
+    for (int q = threadIdx.x >> 6; q < np; q += 4) {
+      const DwBnBwd b = dw_bn_bwd_coef(f, (plane0 + q) % gm.C, gm.C, plane0 + q < gm.C);
+      if ((threadIdx.x & 63) == 0) {
+        scoef[3 * q] = b.k;
+        scoef[3 * q + 1] = b.m1;
+        scoef[3 * q + 2] = b.m2;
+      }
+    }
+  }
+  dw_zero(sx, gm.ppb * (PSZ + GSZ));  // sx and sg are adjacent; ends with a barrier
+  const int ch = (plane0 + (live ? pl : 0)) % gm.C;
   if (live) {
-    const int ch = (plane0 + pl) % gm.C;
-    if (xss)  // x is the input of a BatchNorm(+activation) whose output the convolution saw
-      dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp, xss[ch], xss[gm.C + ch],
-                     xact);
+    if (f.xss)  // x is the input of a BatchNorm(+activation) whose output the convolution saw
+      dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp, f.xss[ch],
+                     f.xss[gm.C + ch], f.xact);
     else
       dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
-    dw_stage_plane(sg + pl * GSZ, g + (size_t)(plane0 + pl) * gm.Ho * gm.Wo, gm.Ho, gm.Wo, t, tpp);
+    if (f.y) {  // the conv's upstream gradient = input gradient of the BatchNorm behind it
+      DwBnBwd b;
+      b.k = scoef[3 * pl]; b.m1 = scoef[3 * pl + 1]; b.m2 = scoef[3 * pl + 2];
+      b.mean = f.ystat[ch]; b.istd = f.ystat[gm.C + ch]; b.sc = f.yss[ch]; b.sf = f.yss[gm.C + ch]; b.act = f.yact;
+      const float* gsrc = g + (size_t)(plane0 + pl) * gm.Ho * gm.Wo;
+      const float* ysrc = f.y + (size_t)(plane0 + pl) * gm.Ho * gm.Wo;
+      float* dst = sg + pl * GSZ;
+      for (int e = t; e < gm.Ho * gm.Wo; e += tpp) {
+        const int i = e / gm.Wo, jj = e - i * gm.Wo;
+        dst[(i + 1) * GW + jj + 1] = dw_bn_dx(gsrc[e], ysrc[e], b);
+      }
+    } else {
+      dw_stage_plane(sg + pl * GSZ, g + (size_t)(plane0 + pl) * gm.Ho * gm.Wo, gm.Ho, gm.Wo, t, tpp);
+    }
   }
   for (int i = threadIdx.x; i < np * 9; i += 256) sw[i] = w[((plane0 + i / 9) % gm.C) * 9 + i % 9];
   __syncthreads();
   const int s = gm.stride;
-  float acc[9];
+  float acc[11];  // nine weight-gradient sums, then the two sums of the BatchNorm in front
 #pragma unroll
-  for (int k = 0; k < 9; ++k) acc[k] = 0.f;
+  for (int k = 0; k < 11; ++k) acc[k] = 0.f;
   if (live) {
     const float* wc = sw + pl * 9;
     const float* gp = sg + pl * GSZ;
     const float* xp = sx + pl * PSZ;
     if (dx) {
       float* dp = dx + (size_t)(plane0 + pl) * gm.H * gm.W;
+      const float* xraw = x + (size_t)(plane0 + pl) * gm.H * gm.W;
+      const float mean1 = f.ws_in ? f.xstat[ch] : 0.f, istd1 = f.ws_in ? f.xstat[gm.C + ch] : 0.f;
       for (int e = t; e < gm.H * gm.W; e += tpp) {
         int i = e / gm.W, j = e - i * gm.W;
         float v = 0.f;
@@ -839,6 +890,11 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
           }
         }
         dp[e] = v;
+        if (f.ws_in) {  // backward sums of the BatchNorm in front: g' = dx*act'(.), g'*xhat
+          const float gmk = v * act_mask(xp[(i + 1) * PW + j + 1], f.xact);
+          acc[9] += gmk;
+          acc[10] += gmk * ((xraw[e] - mean1) * istd1);
+        }
       }
     }
     for (int o = t; o < gm.Ho * gm.Wo; o += tpp) {
@@ -851,27 +907,39 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
         for (int v3 = 0; v3 < 3; ++v3) acc[u * 3 + v3] += gv * b[u * PW + v3];
     }
   }
-  // reduce the nine sums over the tpp threads of each plane (tpp is a power of two >= 16)
+  // reduce the sums over the tpp threads of each plane (tpp is a power of two >= 16)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int span = tpp < 64 ? tpp : 64;
 #pragma unroll
-  for (int k = 0; k < 9; ++k)
+  for (int k = 0; k < 11; ++k)
     for (int o = span >> 1; o > 0; o >>= 1) acc[k] += __shfl_xor(acc[k], o, 64);
+  const int N = gm.NC / gm.C;
+  double* bws = f.ws_in ? f.ws_in + ((size_t)ch * N + (plane0 + pl) / gm.C) * 2 : nullptr;
   if (tpp <= 64) {
-    if (live && t == 0)
+    if (live && t == 0) {
 #pragma unroll
       for (int k = 0; k < 9; ++k) part[(size_t)(plane0 + pl) * 9 + k] = acc[k];
+      if (bws) {
+        bws[0] = (double)acc[9];
+        bws[1] = (double)acc[10];
+      }
+    }
   } else {
     if (lane == 0)
 #pragma unroll
-      for (int k = 0; k < 9; ++k) sred[wave * 9 + k] = acc[k];
+      for (int k = 0; k < 11; ++k) sred[wave * 11 + k] = acc[k];
     __syncthreads();
     if (live && t == 0) {
       const int w0 = threadIdx.x >> 6, nw = tpp >> 6;
-      for (int k = 0; k < 9; ++k) {
-        float v = 0.f;
-        for (int q = 0; q < nw; ++q) v += sred[(w0 + q) * 9 + k];
-        part[(size_t)(plane0 + pl) * 9 + k] = v;
+      float v[11];
+      for (int k = 0; k < 11; ++k) {
+        v[k] = 0.f;
+        for (int q = 0; q < nw; ++q) v[k] += sred[(w0 + q) * 11 + k];
+      }
+      for (int k = 0; k < 9; ++k) part[(size_t)(plane0 + pl) * 9 + k] = v[k];
+      if (bws) {
+        bws[0] = (double)v[9];
+        bws[1] = (double)v[10];
       }
     }
   }
@@ -902,48 +970,63 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
                                                                const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ dx,
                                                                float* __restrict__ part, int NC, int C, int H,
-                                                               int W, int RPG, const float* __restrict__ xss,
-                                                               int xact) {
+                                                               int W, int RPG, DwBwdFuse f) {
   const int lane = threadIdx.x & 63;
   const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (plane >= NC) return;  // whole wavefront
+  const int ch = plane % C;
   const int SW = W >> 2;
   const int rg = lane / SW, s = lane - rg * SW;
   const int r0 = rg * RPG;
   const int r1 = min(r0 + RPG, H);  // lanes past the last group: r0 >= H, no rows
   const float* gp = g + (size_t)plane * H * W + 4 * s;
   const float* xp = x + (size_t)plane * H * W + 4 * s;
+  const float* yp = f.y ? f.y + (size_t)plane * H * W + 4 * s : nullptr;
   float* dp = dx ? dx + (size_t)plane * H * W + 4 * s : nullptr;
   float wk[9];
-  const float* wc = w + (size_t)(plane % C) * 9;
+  const float* wc = w + (size_t)ch * 9;
 #pragma unroll
   for (int k = 0; k < 9; ++k) wk[k] = wc[k];
+  DwBnBwd yb{};
+  if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
   const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   // a row is readable by this lane if it lies in the image and the lane has rows at all
   const bool has = r0 < H;
-  auto ld = [&](const float* base, int row) -> float4 {
-    return (has && row >= 0 && row < H) ? *reinterpret_cast<const float4*>(base + (size_t)row * W) : z4;
+  auto ldg = [&](int row, bool ok) -> float4 {
+    if (!(ok && has && row >= 0 && row < H)) return z4;
+    float4 gv = *reinterpret_cast<const float4*>(gp + (size_t)row * W);
+    if (f.y) {  // input gradient of the BatchNorm behind the conv
+      const float4 yv = *reinterpret_cast<const float4*>(yp + (size_t)row * W);
+      gv.x = dw_bn_dx(gv.x, yv.x, yb); gv.y = dw_bn_dx(gv.y, yv.y, yb);
+      gv.z = dw_bn_dx(gv.z, yv.z, yb); gv.w = dw_bn_dx(gv.w, yv.w, yb);
+    }
+    return gv;
   };
   // with xss the convolution's input was act(x*scale + shift) (a BatchNorm whose output is not
-  // kept); the padding around it stays zero
-  const float xsc = xss ? xss[plane % C] : 1.f, xsf = xss ? xss[C + plane % C] : 0.f;
-  auto ldx = [&](int row) -> float4 {
-    if (!(has && row >= 0 && row < H)) return z4;
-    const float4 v = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
-    return xss ? dw_norm4(v, xsc, xsf, xact) : v;
+  // kept); the padding around it stays zero.  `raw` gets x itself.
+  const float xsc = f.xss ? f.xss[ch] : 1.f, xsf = f.xss ? f.xss[C + ch] : 0.f;
+  const float mean1 = f.ws_in ? f.xstat[ch] : 0.f, istd1 = f.ws_in ? f.xstat[C + ch] : 0.f;
+  auto ldx = [&](int row, bool ok, float4& raw) -> float4 {
+    raw = z4;
+    if (!(ok && has && row >= 0 && row < H)) return z4;
+    raw = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
+    return f.xss ? dw_norm4(raw, xsc, xsf, f.xact) : raw;
   };
-  DwRow gm = dw_make_row(ld(gp, r0 - 1), s, SW), xm = dw_make_row(ldx(r0 - 1), s, SW);
-  DwRow gc = dw_make_row(ld(gp, r0), s, SW), xc = dw_make_row(ldx(r0), s, SW);
-  float4 gn = ld(gp, r0 + 1), xn = ldx(r0 + 1);
+  float4 xcr, xnr, tmp;
+  DwRow gm = dw_make_row(ldg(r0 - 1, true), s, SW), xm = dw_make_row(ldx(r0 - 1, true, tmp), s, SW);
+  DwRow gc = dw_make_row(ldg(r0, true), s, SW), xc = dw_make_row(ldx(r0, true, xcr), s, SW);
+  float4 gn = ldg(r0 + 1, true), xn = ldx(r0 + 1, true, xnr);
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
+  float b1 = 0.f, b2 = 0.f;
   for (int i = 0; i < RPG; ++i) {  // uniform trip count: the lane exchanges need every lane
     const int a = r0 + i;
     const DwRow gq = dw_make_row(gn, s, SW), xq = dw_make_row(xn, s, SW);
+    const float4 xqr = xnr;
     // past its last row a lane must not see the next group's rows as its own window
-    gn = (a + 2 <= r1) ? ld(gp, a + 2) : z4;
-    xn = (a + 2 <= r1) ? ldx(a + 2) : z4;
+    gn = ldg(a + 2, a + 2 <= r1);
+    xn = ldx(a + 2, a + 2 <= r1, xnr);
     if (a < r1) {
       if (dp) {
         float o[4];
@@ -959,6 +1042,15 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
           o[j] = v;
         }
         *reinterpret_cast<float4*>(dp + (size_t)a * W) = make_float4(o[0], o[1], o[2], o[3]);
+        if (f.ws_in) {  // backward sums of the BatchNorm in front: g' = dx*act'(.), g'*xhat
+          const float raw[4] = {xcr.x, xcr.y, xcr.z, xcr.w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float gmk = o[j] * act_mask(xc.v[j + 1], f.xact);
+            b1 += gmk;
+            b2 += gmk * ((raw[j] - mean1) * istd1);
+          }
+        }
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {  // dW[u][q] += g[a][b] x[a+u-1][b+q-1]
@@ -973,12 +1065,21 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
     }
     gm = gc; gc = gq;
     xm = xc; xc = xq;
+    xcr = xqr;
   }
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = wave_sum(acc[k]);
   if (lane == 0)
 #pragma unroll
     for (int k = 0; k < 9; ++k) part[(size_t)plane * 9 + k] = acc[k];
+  if (f.ws_in) {
+    const double d1 = wave_sum_d((double)b1), d2 = wave_sum_d((double)b2);
+    if (lane == 0) {
+      double* o = f.ws_in + ((size_t)ch * (NC / C) + plane / C) * 2;
+      o[0] = d1;
+      o[1] = d2;
+    }
+  }
 }
 
 // Stride-2 counterpart (W % 4 == 0, H even): lane (s, rg) owns input columns 4s..4s+3 =
@@ -1021,55 +1122,83 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
                                                                const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ dx,
                                                                float* __restrict__ part, int NC, int C, int H,
-                                                               int W, int RPG, const float* __restrict__ xss,
-                                                               int xact) {
+                                                               int W, int RPG, DwBwdFuse f) {
   const int lane = threadIdx.x & 63;
   const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (plane >= NC) return;  // whole wavefront
+  const int ch = plane % C;
   const int SW = W >> 2, Ho = H >> 1, Wo = W >> 1;
   const int rg = lane / SW, s = lane - rg * SW;
   const int r0 = rg * RPG;            // output rows [r0, r1)
   const int r1 = min(r0 + RPG, Ho);
   const bool has = r0 < Ho;
   const float* gp = g + (size_t)plane * Ho * Wo + 2 * s;
+  const float* yp = f.y ? f.y + (size_t)plane * Ho * Wo + 2 * s : nullptr;
   const float* xp = x + (size_t)plane * H * W + 4 * s;
   float* dp = dx ? dx + (size_t)plane * H * W + 4 * s : nullptr;
   float wk[9];
-  const float* wc = w + (size_t)(plane % C) * 9;
+  const float* wc = w + (size_t)ch * 9;
 #pragma unroll
   for (int k = 0; k < 9; ++k) wk[k] = wc[k];
+  DwBnBwd yb{};
+  if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
   const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   const float2 z2 = make_float2(0.f, 0.f);
-  const float xsc = xss ? xss[plane % C] : 1.f, xsf = xss ? xss[C + plane % C] : 0.f;
-  auto ldx = [&](int row) -> float4 {  // with xss: the BatchNorm(+activation) output the convolution saw
-    if (!(has && row >= 0 && row < H)) return z4;
-    const float4 v = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
-    return xss ? dw_norm4(v, xsc, xsf, xact) : v;
+  const float xsc = f.xss ? f.xss[ch] : 1.f, xsf = f.xss ? f.xss[C + ch] : 0.f;
+  const float mean1 = f.ws_in ? f.xstat[ch] : 0.f, istd1 = f.ws_in ? f.xstat[C + ch] : 0.f;
+  // with xss: the BatchNorm(+activation) output the convolution saw; `raw` gets x itself
+  auto ldx = [&](int row, bool ok, float4& raw) -> float4 {
+    raw = z4;
+    if (!(ok && has && row >= 0 && row < H)) return z4;
+    raw = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
+    return f.xss ? dw_norm4(raw, xsc, xsf, f.xact) : raw;
   };
-  auto ldg = [&](int row) -> float2 {
-    return (has && row >= 0 && row < Ho) ? *reinterpret_cast<const float2*>(gp + (size_t)row * Wo) : z2;
+  auto ldg = [&](int row, bool ok) -> float2 {
+    if (!(ok && has && row >= 0 && row < Ho)) return z2;
+    float2 gv = *reinterpret_cast<const float2*>(gp + (size_t)row * Wo);
+    if (f.y) {  // input gradient of the BatchNorm behind the conv
+      const float2 yv = *reinterpret_cast<const float2*>(yp + (size_t)row * Wo);
+      gv.x = dw_bn_dx(gv.x, yv.x, yb);
+      gv.y = dw_bn_dx(gv.y, yv.y, yb);
+    }
+    return gv;
   };
-  DwX2 xm = dw_make_x2(ldx(2 * r0 - 1), s);
-  DwG2 gc = dw_make_g2(ldg(r0), s, SW);
-  float4 xn0 = ldx(2 * r0), xn1 = ldx(2 * r0 + 1);
-  float2 gn = ldg(r0 + 1);
+  float4 xn0r, xn1r, tmp;
+  DwX2 xm = dw_make_x2(ldx(2 * r0 - 1, true, tmp), s);
+  DwG2 gc = dw_make_g2(ldg(r0, true), s, SW);
+  float4 xn0 = ldx(2 * r0, true, xn0r), xn1 = ldx(2 * r0 + 1, true, xn1r);
+  float2 gn = ldg(r0 + 1, true);
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
+  float b1 = 0.f, b2 = 0.f;
   for (int it = 0; it < RPG; ++it) {  // uniform trip count: the lane exchanges need every lane
     const int i = r0 + it;
     const DwX2 x0 = dw_make_x2(xn0, s), x1 = dw_make_x2(xn1, s);
+    const float4 x0r = xn0r, x1r = xn1r;
     const DwG2 gq = dw_make_g2(gn, s, SW);
     const bool more = i + 1 < r1;
-    xn0 = more ? ldx(2 * i + 2) : z4;
-    xn1 = more ? ldx(2 * i + 3) : z4;
-    gn = more ? ldg(i + 2) : z2;
+    xn0 = ldx(2 * i + 2, more, xn0r);
+    xn1 = ldx(2 * i + 3, more, xn1r);
+    gn = ldg(i + 2, more);
     if (i < r1) {
       if (dp) {
         // input row 2i: centre kernel row of output row i; row 2i+1: kernel row 0 of output
         // row i+1 and kernel row 2 of output row i
-        *reinterpret_cast<float4*>(dp + (size_t)(2 * i) * W) = dw_dx_row2(wk + 3, gc, wk + 3, gc, false);
-        *reinterpret_cast<float4*>(dp + (size_t)(2 * i + 1) * W) = dw_dx_row2(wk + 0, gq, wk + 6, gc, true);
+        const float4 d0 = dw_dx_row2(wk + 3, gc, wk + 3, gc, false);
+        const float4 d1 = dw_dx_row2(wk + 0, gq, wk + 6, gc, true);
+        *reinterpret_cast<float4*>(dp + (size_t)(2 * i) * W) = d0;
+        *reinterpret_cast<float4*>(dp + (size_t)(2 * i + 1) * W) = d1;
+        if (f.ws_in) {  // backward sums of the BatchNorm in front: g' = dx*act'(.), g'*xhat
+          const float dd[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+          const float rr[8] = {x0r.x, x0r.y, x0r.z, x0r.w, x1r.x, x1r.y, x1r.z, x1r.w};
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float gmk = dd[j] * act_mask(j < 4 ? x0.v[j + 1] : x1.v[j - 3], f.xact);
+            b1 += gmk;
+            b2 += gmk * ((rr[j] - mean1) * istd1);
+          }
+        }
       }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {  // dW[u][q] += g[i][2s+j] x[2i+u-1][4s+2j+q-1]
@@ -1090,6 +1219,14 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
   if (lane == 0)
 #pragma unroll
     for (int k = 0; k < 9; ++k) part[(size_t)plane * 9 + k] = acc[k];
+  if (f.ws_in) {
+    const double d1 = wave_sum_d((double)b1), d2 = wave_sum_d((double)b2);
+    if (lane == 0) {
+      double* o = f.ws_in + ((size_t)ch * (NC / C) + plane / C) * 2;
+      o[0] = d1;
+      o[1] = d2;
+    }
+  }
 }
 
 // G[c][t] += sum_n part[n][c][t]: eight sample lanes per output, fixed butterfly order
@@ -1127,25 +1264,29 @@ void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int
 }
 size_t dw3x3_bwd_f32_ws(int N, int C) { return (size_t)N * C * 9; }
 void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part,
-                   float* G, int N, int C, int H, int W, int stride, const float* xss, int xact) {
+                   float* G, int N, int C, int H, int W, int stride, const DwBwdFuse* fuse) {
+  DwBwdFuse f;
+  if (fuse) f = *fuse;
+  if (!dx || !f.xss) f.ws_in = nullptr;  // those sums need dx and the normalised input
   if (stride == 1 && W % 4 == 0 && W <= 256) {
     const int groups = 64 / (W / 4);
     KLAUNCH(dw3x3_bwd_s1_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
-            cdiv(H, groups), xss, xact);
+            cdiv(H, groups), f);
     if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
     return;
   }
   if (stride == 2 && W % 4 == 0 && H % 2 == 0 && W <= 256) {
     const int groups = 64 / (W / 4);
     KLAUNCH(dw3x3_bwd_s2_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
-            cdiv(H / 2, groups), xss, xact);
+            cdiv(H / 2, groups), f);
     if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
     return;
   }
   DwGeom gm = dw_geom(N, C, H, W, stride);
-  size_t lds = ((size_t)gm.ppb * ((H + 2) * (W + 2) + (gm.Ho + 2) * (gm.Wo + 2) + 9) + 36) * sizeof(float);
+  size_t lds =
+      ((size_t)gm.ppb * ((H + 2) * (W + 2) + (gm.Ho + 2) * (gm.Wo + 2) + 9 + 3) + 44) * sizeof(float);
   (void)hipFuncSetAttribute((const void*)dw3x3_bwd_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  KLAUNCH(dw3x3_bwd_f32_kernel, dim3(cdiv(gm.NC, gm.ppb)), dim3(256), lds, st, g, x, w, dx, part, gm, xss, xact);
+  KLAUNCH(dw3x3_bwd_f32_kernel, dim3(cdiv(gm.NC, gm.ppb)), dim3(256), lds, st, g, x, w, dx, part, gm, f);
   if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
 }
 

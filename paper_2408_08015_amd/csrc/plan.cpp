@@ -291,19 +291,24 @@ ast_status build_plan(Stage& s, std::string& err) {
     }
   }
 
-  // fp32 inverted-residual pattern BN(+act) -> depthwise 3x3 -> BN: the first BatchNorm's apply pass
-  // and the second one's statistics pass move into the convolution (ASTEROID_BN_FUSE=0 keeps them).
+  // fp32 inverted-residual pattern BN(+act) -> depthwise 3x3 -> BN: BatchNorm passes move into the
+  // convolution.  ASTEROID_BN_FUSE is a bit mask of the moves to make (default: all):
+  //   1  forward: the first BatchNorm's apply pass (normalise on load, also in the conv's backward)
+  //      and the second one's statistics pass (conv epilogue)
+  //   2  backward: the first BatchNorm's partial sums (conv backward epilogue); needs 1
+  //   4  backward: the second BatchNorm's apply pass (on load of the conv's upstream gradient)
   std::vector<char> virtual_act(s.acts.size(), 0);  // activations that are never materialised
   {
     const char* e = getenv("ASTEROID_BN_FUSE");
-    const bool fuse = !(e && e[0] == '0');
+    const int fuse = e ? atoi(e) : 7;
     for (size_t j = 0; fuse && j < s.ops.size(); ++j) {
       Op& dw = s.ops[j];
       if (dw.kind != OP_CONV_DW) continue;
-      if (j > 0) {
+      if (j > 0 && (fuse & 1)) {
         Op& bn = s.ops[j - 1];
         if (bn.kind == OP_BN && bn.out == dw.in && bn.skip < 0) {
           bn.bn_lazy = true;
+          bn.bn_bwd_sums_given = (fuse & 2) != 0;
           dw.bn_in_op = (int)j - 1;
           virtual_act[bn.out] = 1;
           for (int& la : s.layer_act)
@@ -313,8 +318,14 @@ ast_status build_plan(Stage& s, std::string& err) {
       if (j + 1 < s.ops.size()) {
         Op& bn = s.ops[j + 1];
         if (bn.kind == OP_BN && bn.in == dw.out) {
-          bn.bn_stats_given = true;
-          dw.bn_out_op = (int)j + 1;
+          if (fuse & 1) {
+            bn.bn_stats_given = true;
+            dw.bn_out_op = (int)j + 1;
+          }
+          if (fuse & 4) {
+            bn.bn_bwd_apply_fused = true;
+            dw.bn_bwd_out_op = (int)j + 1;
+          }
         }
       }
     }

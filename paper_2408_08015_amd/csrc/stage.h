@@ -70,8 +70,12 @@ struct Op {
   bool bn_lazy = false;               // BatchNorm(+act) feeding a depthwise conv: the output is never written; the
                                       // conv normalises on load (forward and backward) and finishes the statistics
   bool bn_stats_given = false;        // BatchNorm behind a depthwise conv: the conv's epilogue leaves per-plane sums
+  bool bn_bwd_sums_given = false;     // lazy BatchNorm: the conv's backward leaves its backward sums per plane
+  bool bn_bwd_apply_fused = false;    // BatchNorm behind a depthwise conv: the conv's backward forms the
+                                      // BatchNorm's input gradient on load and adds dgamma, dbeta
   int bn_in_op = -1;                  // depthwise conv: index of the lazy BatchNorm op in front
   int bn_out_op = -1;                 // depthwise conv: index of the BatchNorm op it writes statistics for
+  int bn_bwd_out_op = -1;             // depthwise conv: index of the BatchNorm op whose backward apply it does
 };
 
 struct Stage {

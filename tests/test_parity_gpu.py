@@ -101,6 +101,28 @@ def test_batchnorm(A, c, hw, B, act):
     check(one(L, (c, hw, hw), B=B, name="bn%d" % c))
 
 
+@pytest.mark.parametrize("c,hw,stride,B,act", [
+    (24, 56, 1, 2, "relu6"),   # one plane per block, four-pixel strips, stride 1
+    (16, 28, 2, 3, "relu6"),   # stride 2 register-window path
+    (10, 15, 1, 2, "relu"),    # odd width: planes staged through LDS
+    (6, 9, 2, 3, None),        # odd width, stride 2, no activation
+    (8, 112, 2, 1, "relu6"),   # largest plane of MobileNetV2
+    (12, 7, 1, 4, "relu6"),    # 49-pixel planes, many planes per block
+])
+@pytest.mark.parametrize("need_dx", [True, False])
+def test_batchnorm_depthwise_batchnorm(A, c, hw, stride, B, act, need_dx):
+    # the BatchNorm passes next to a depthwise conv run inside the conv kernels
+    L = [bn(c)] + ([simple(act)] if act else []) + [conv(c, c, 3, stride, 1, groups=c), bn(c), simple("relu6")]
+    check(one(L, (c, hw, hw), B=B, name="bn_dw_bn%d" % c, needs_input_grad=need_dx))
+
+
+def test_depthwise_chain_between_batchnorms(A):
+    # a BatchNorm that is both behind one depthwise conv and in front of the next
+    L = [conv(8, 8, 3, 1, 1, groups=8), bn(8), simple("relu6"), conv(8, 8, 3, 2, 1, groups=8), bn(8),
+         conv(8, 8, 3, 1, 1, groups=8)]
+    check(one(L, (8, 12, 12), B=3, name="dw_chain"))
+
+
 def test_residual_block_and_unfused_residual(A):
     check(one(irb(16, 16, 1, 6), (16, 12, 12), B=3, name="irb"))
     # RES_ADD not preceded by a BatchNorm: standalone add + skip-gradient add
