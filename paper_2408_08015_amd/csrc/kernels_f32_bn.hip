@@ -97,6 +97,21 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
                                                        double count, float eps, int act, int chunk) {
   __shared__ float coef[2];
   const int plane = blockIdx.x, c = plane % C;
+  const int e0 = blockIdx.y * chunk, e1 = min(e0 + chunk, HW);
+  const size_t base = (size_t)plane * HW;
+  // The chunk's data (at most 4096 elements: four 16-byte words per thread) is requested before
+  // the statistics are finished, so the two memory latencies overlap instead of adding up.
+  float4 xv[4], kv[4];
+  if (VEC) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = e0 + 4 * threadIdx.x + 1024 * u;
+      if (e < e1) {
+        xv[u] = *reinterpret_cast<const float4*>(x + base + e);
+        if (skip) kv[u] = *reinterpret_cast<const float4*>(skip + base + e);
+      }
+    }
+  }
   if (threadIdx.x < 64) {
     double s1, s2;
     bn_add_partials(ws, c, S, s1, s2);
@@ -106,10 +121,23 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
   }
   __syncthreads();
   const float sc = coef[0], sf = coef[1];
-  const int e0 = blockIdx.y * chunk, e1 = min(e0 + chunk, HW);
-  const size_t base = (size_t)plane * HW;
   if (VEC) {
-    for (int e = e0 + 4 * threadIdx.x; e < e1; e += 1024) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = e0 + 4 * threadIdx.x + 1024 * u;
+      if (e < e1) {
+        float4 v = xv[u];
+        v.x = apply_act(v.x * sc + sf, act);
+        v.y = apply_act(v.y * sc + sf, act);
+        v.z = apply_act(v.z * sc + sf, act);
+        v.w = apply_act(v.w * sc + sf, act);
+        if (skip) {
+          v.x += kv[u].x; v.y += kv[u].y; v.z += kv[u].z; v.w += kv[u].w;
+        }
+        *reinterpret_cast<float4*>(y + base + e) = v;
+      }
+    }
+    for (int e = e0 + 4 * threadIdx.x + 4096; e < e1; e += 1024) {  // longer chunks (not produced by the launcher)
       float4 v = *reinterpret_cast<const float4*>(x + base + e);
       v.x = apply_act(v.x * sc + sf, act);
       v.y = apply_act(v.y * sc + sf, act);
@@ -224,6 +252,21 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
                                                            int chunk) {
   __shared__ float coef[3];
   const int plane = blockIdx.x, c = plane % C;
+  const float mean = stat[c], istd = stat[C + c], sc = ss[c], sf = ss[C + c];
+  const int e0 = blockIdx.y * chunk, e1 = min(e0 + chunk, HW);
+  const size_t base = (size_t)plane * HW;
+  // the chunk's data (at most 4096 elements) is requested before the sums are finished
+  float4 xpre[4], gpre[4];
+  if (VEC && dx) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = e0 + 4 * threadIdx.x + 1024 * u;
+      if (e < e1) {
+        xpre[u] = *reinterpret_cast<const float4*>(x + base + e);
+        gpre[u] = *reinterpret_cast<const float4*>(g + base + e);
+      }
+    }
+  }
   if (threadIdx.x < 64) {
     double s1, s2;
     bn_add_partials(ws, c, S, s1, s2);
@@ -240,11 +283,21 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
   __syncthreads();
   if (!dx) return;  // the input gradient is not wanted
   const float k = coef[0], m1 = coef[1], m2 = coef[2];
-  const float mean = stat[c], istd = stat[C + c], sc = ss[c], sf = ss[C + c];
-  const int e0 = blockIdx.y * chunk, e1 = min(e0 + chunk, HW);
-  const size_t base = (size_t)plane * HW;
   if (VEC) {
-    for (int e = e0 + 4 * threadIdx.x; e < e1; e += 1024) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = e0 + 4 * threadIdx.x + 1024 * u;
+      if (e < e1) {
+        const float4 xv = xpre[u], gv = gpre[u];
+        float4 o;
+        o.x = k * (gv.x * act_mask(xv.x * sc + sf, act) - m1 - (xv.x - mean) * istd * m2);
+        o.y = k * (gv.y * act_mask(xv.y * sc + sf, act) - m1 - (xv.y - mean) * istd * m2);
+        o.z = k * (gv.z * act_mask(xv.z * sc + sf, act) - m1 - (xv.z - mean) * istd * m2);
+        o.w = k * (gv.w * act_mask(xv.w * sc + sf, act) - m1 - (xv.w - mean) * istd * m2);
+        *reinterpret_cast<float4*>(dx + base + e) = o;
+      }
+    }
+    for (int e = e0 + 4 * threadIdx.x + 4096; e < e1; e += 1024) {  // longer chunks (not produced by the launcher)
       float4 xv = *reinterpret_cast<const float4*>(x + base + e);
       float4 gv = *reinterpret_cast<const float4*>(g + base + e);
       float4 o;

@@ -643,18 +643,37 @@ __device__ __forceinline__ void dw_zero(float* dst, int count) {
 // the first LDS write so the memory latency is paid once per four elements, not per element.
 // With act >= 0 every element is first mapped to act(v*sc + sf): the plane is the input of a
 // BatchNorm(+activation) whose output is never written out.
+// `pre` (w % 4 == 0 only): the first four words of this thread, requested earlier with
+// dw_stage_preload so that their latency overlaps the kernel's prologue.
+struct DwPre { float4 v[4]; };
+__device__ __forceinline__ void dw_stage_preload(DwPre& pre, const float* __restrict__ src, int h, int w, int t,
+                                                 int tpp) {
+  const int nq = (h * w) >> 2;
+  const float4* s4 = reinterpret_cast<const float4*>(src);
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int q = t + u * tpp;
+    pre.v[u] = q < nq ? s4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+}
 __device__ __forceinline__ void dw_stage_plane(float* dst, const float* __restrict__ src, int h, int w, int t,
-                                               int tpp, float sc = 1.f, float sf = 0.f, int act = -1) {
+                                               int tpp, float sc = 1.f, float sf = 0.f, int act = -1,
+                                               const DwPre* pre = nullptr) {
   const int pw = w + 2;
   if ((w & 3) == 0) {
     const int nq = (h * w) >> 2, qpr = w >> 2;
     const float4* s4 = reinterpret_cast<const float4*>(src);
     for (int q0 = t; q0 < nq; q0 += 4 * tpp) {
       float4 v[4];
+      if (pre && q0 == t) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        int q = q0 + u * tpp;
-        v[u] = q < nq ? s4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int u = 0; u < 4; ++u) v[u] = pre->v[u];
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          int q = q0 + u * tpp;
+          v[u] = q < nq ? s4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -705,6 +724,10 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_f32_kernel(const float* __restr
   const int tpp = 256 / gm.ppb;
   const int pl = threadIdx.x / tpp, t = threadIdx.x - pl * tpp;
   const bool live = pl < np;
+  // the first words of the plane are requested before the prologue and the LDS clear
+  const bool vecw = (gm.W & 3) == 0;
+  DwPre pre;
+  if (live && vecw) dw_stage_preload(pre, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
   if (bi.on) {  // finish the statistics of each plane's channel: one wavefront per plane
     for (int q = threadIdx.x >> 6; q < np; q += 4) {
       const int plane = plane0 + q, c = plane % gm.C;
@@ -719,9 +742,10 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_f32_kernel(const float* __restr
   if (live) {
     if (bi.on)
       dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp, scoef[2 * pl],
-                     scoef[2 * pl + 1], bi.act);
+                     scoef[2 * pl + 1], bi.act, vecw ? &pre : nullptr);
     else
-      dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
+      dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp, 1.f, 0.f, -1,
+                     vecw ? &pre : nullptr);
   }
   for (int i = threadIdx.x; i < np * 9; i += 256) sw[i] = w[((plane0 + i / 9) % gm.C) * 9 + i % 9];
   __syncthreads();
@@ -988,19 +1012,27 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
 #pragma unroll
   for (int k = 0; k < 9; ++k) wk[k] = wc[k];
   DwBnBwd yb{};
-  if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
   const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   // a row is readable by this lane if it lies in the image and the lane has rows at all
   const bool has = r0 < H;
-  auto ldg = [&](int row, bool ok) -> float4 {
-    if (!(ok && has && row >= 0 && row < H)) return z4;
-    float4 gv = *reinterpret_cast<const float4*>(gp + (size_t)row * W);
-    if (f.y) {  // input gradient of the BatchNorm behind the conv
-      const float4 yv = *reinterpret_cast<const float4*>(yp + (size_t)row * W);
+  auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
+  auto ldg_raw = [&](int row, bool ok, float4& yv) -> float4 {
+    yv = z4;
+    if (!rowok(row, ok)) return z4;
+    if (f.y) yv = *reinterpret_cast<const float4*>(yp + (size_t)row * W);
+    return *reinterpret_cast<const float4*>(gp + (size_t)row * W);
+  };
+  auto bn_g = [&](float4 gv, const float4& yv, bool valid) -> float4 {
+    if (f.y && valid) {  // input gradient of the BatchNorm behind the conv
       gv.x = dw_bn_dx(gv.x, yv.x, yb); gv.y = dw_bn_dx(gv.y, yv.y, yb);
       gv.z = dw_bn_dx(gv.z, yv.z, yb); gv.w = dw_bn_dx(gv.w, yv.w, yb);
     }
     return gv;
+  };
+  auto ldg = [&](int row, bool ok) -> float4 {
+    float4 yv;
+    const float4 gv = ldg_raw(row, ok, yv);
+    return bn_g(gv, yv, rowok(row, ok));
   };
   // with xss the convolution's input was act(x*scale + shift) (a BatchNorm whose output is not
   // kept); the padding around it stays zero.  `raw` gets x itself.
@@ -1012,10 +1044,16 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
     raw = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
     return f.xss ? dw_norm4(raw, xsc, xsf, f.xact) : raw;
   };
-  float4 xcr, xnr, tmp;
-  DwRow gm = dw_make_row(ldg(r0 - 1, true), s, SW), xm = dw_make_row(ldx(r0 - 1, true, tmp), s, SW);
-  DwRow gc = dw_make_row(ldg(r0, true), s, SW), xc = dw_make_row(ldx(r0, true, xcr), s, SW);
-  float4 gn = ldg(r0 + 1, true), xn = ldx(r0 + 1, true, xnr);
+  // the first three rows are requested before the BatchNorm sums are finished
+  float4 xcr, xnr, tmp, y0, y1, y2;
+  float4 g0 = ldg_raw(r0 - 1, true, y0), g1 = ldg_raw(r0, true, y1), g2 = ldg_raw(r0 + 1, true, y2);
+  DwRow xm = dw_make_row(ldx(r0 - 1, true, tmp), s, SW);
+  DwRow xc = dw_make_row(ldx(r0, true, xcr), s, SW);
+  float4 xn = ldx(r0 + 1, true, xnr);
+  if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
+  DwRow gm = dw_make_row(bn_g(g0, y0, rowok(r0 - 1, true)), s, SW);
+  DwRow gc = dw_make_row(bn_g(g1, y1, rowok(r0, true)), s, SW);
+  float4 gn = bn_g(g2, y2, rowok(r0 + 1, true));
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
@@ -1141,7 +1179,6 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
 #pragma unroll
   for (int k = 0; k < 9; ++k) wk[k] = wc[k];
   DwBnBwd yb{};
-  if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
   const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   const float2 z2 = make_float2(0.f, 0.f);
   const float xsc = f.xss ? f.xss[ch] : 1.f, xsf = f.xss ? f.xss[C + ch] : 0.f;
@@ -1153,21 +1190,34 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
     raw = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
     return f.xss ? dw_norm4(raw, xsc, xsf, f.xact) : raw;
   };
-  auto ldg = [&](int row, bool ok) -> float2 {
-    if (!(ok && has && row >= 0 && row < Ho)) return z2;
-    float2 gv = *reinterpret_cast<const float2*>(gp + (size_t)row * Wo);
-    if (f.y) {  // input gradient of the BatchNorm behind the conv
-      const float2 yv = *reinterpret_cast<const float2*>(yp + (size_t)row * Wo);
+  auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < Ho; };
+  auto ldg_raw = [&](int row, bool ok, float2& yv) -> float2 {
+    yv = z2;
+    if (!rowok(row, ok)) return z2;
+    if (f.y) yv = *reinterpret_cast<const float2*>(yp + (size_t)row * Wo);
+    return *reinterpret_cast<const float2*>(gp + (size_t)row * Wo);
+  };
+  auto bn_g = [&](float2 gv, const float2& yv, bool valid) -> float2 {
+    if (f.y && valid) {  // input gradient of the BatchNorm behind the conv
       gv.x = dw_bn_dx(gv.x, yv.x, yb);
       gv.y = dw_bn_dx(gv.y, yv.y, yb);
     }
     return gv;
   };
+  auto ldg = [&](int row, bool ok) -> float2 {
+    float2 yv;
+    const float2 gv = ldg_raw(row, ok, yv);
+    return bn_g(gv, yv, rowok(row, ok));
+  };
+  // the first rows are requested before the BatchNorm sums are finished
   float4 xn0r, xn1r, tmp;
+  float2 y0, y1;
+  float2 g0 = ldg_raw(r0, true, y0), g1 = ldg_raw(r0 + 1, true, y1);
   DwX2 xm = dw_make_x2(ldx(2 * r0 - 1, true, tmp), s);
-  DwG2 gc = dw_make_g2(ldg(r0, true), s, SW);
   float4 xn0 = ldx(2 * r0, true, xn0r), xn1 = ldx(2 * r0 + 1, true, xn1r);
-  float2 gn = ldg(r0 + 1, true);
+  if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
+  DwG2 gc = dw_make_g2(bn_g(g0, y0, rowok(r0, true)), s, SW);
+  float2 gn = bn_g(g1, y1, rowok(r0 + 1, true));
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
