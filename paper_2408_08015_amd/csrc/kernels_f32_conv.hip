@@ -1016,55 +1016,55 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
   // a row is readable by this lane if it lies in the image and the lane has rows at all
   const bool has = r0 < H;
   auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
-  auto ldg_raw = [&](int row, bool ok, float4& yv) -> float4 {
-    yv = z4;
-    if (!rowok(row, ok)) return z4;
-    if (f.y) yv = *reinterpret_cast<const float4*>(yp + (size_t)row * W);
-    return *reinterpret_cast<const float4*>(gp + (size_t)row * W);
+  // Rows travel as raw words (zeros where not readable) and are only transformed when they
+  // enter the window, so a load is not waited for before the rows ahead of it are used up.
+  struct Pend { float4 g, y, x; };
+  auto load_row = [&](int row, bool ok) -> Pend {
+    Pend q;
+    q.g = q.y = q.x = z4;
+    if (rowok(row, ok)) {
+      q.g = *reinterpret_cast<const float4*>(gp + (size_t)row * W);
+      if (f.y) q.y = *reinterpret_cast<const float4*>(yp + (size_t)row * W);
+      q.x = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
+    }
+    return q;
   };
-  auto bn_g = [&](float4 gv, const float4& yv, bool valid) -> float4 {
+  auto use_g = [&](const Pend& q, bool valid) -> float4 {
+    float4 gv = q.g;
     if (f.y && valid) {  // input gradient of the BatchNorm behind the conv
-      gv.x = dw_bn_dx(gv.x, yv.x, yb); gv.y = dw_bn_dx(gv.y, yv.y, yb);
-      gv.z = dw_bn_dx(gv.z, yv.z, yb); gv.w = dw_bn_dx(gv.w, yv.w, yb);
+      gv.x = dw_bn_dx(gv.x, q.y.x, yb); gv.y = dw_bn_dx(gv.y, q.y.y, yb);
+      gv.z = dw_bn_dx(gv.z, q.y.z, yb); gv.w = dw_bn_dx(gv.w, q.y.w, yb);
     }
     return gv;
   };
-  auto ldg = [&](int row, bool ok) -> float4 {
-    float4 yv;
-    const float4 gv = ldg_raw(row, ok, yv);
-    return bn_g(gv, yv, rowok(row, ok));
-  };
   // with xss the convolution's input was act(x*scale + shift) (a BatchNorm whose output is not
-  // kept); the padding around it stays zero.  `raw` gets x itself.
+  // kept); the padding around it stays zero
   const float xsc = f.xss ? f.xss[ch] : 1.f, xsf = f.xss ? f.xss[C + ch] : 0.f;
   const float mean1 = f.ws_in ? f.xstat[ch] : 0.f, istd1 = f.ws_in ? f.xstat[C + ch] : 0.f;
-  auto ldx = [&](int row, bool ok, float4& raw) -> float4 {
-    raw = z4;
-    if (!(ok && has && row >= 0 && row < H)) return z4;
-    raw = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
-    return f.xss ? dw_norm4(raw, xsc, xsf, f.xact) : raw;
+  auto use_x = [&](const Pend& q, bool valid) -> float4 {
+    return (f.xss && valid) ? dw_norm4(q.x, xsc, xsf, f.xact) : q.x;
   };
-  // the first three rows are requested before the BatchNorm sums are finished
-  float4 xcr, xnr, tmp, y0, y1, y2;
-  float4 g0 = ldg_raw(r0 - 1, true, y0), g1 = ldg_raw(r0, true, y1), g2 = ldg_raw(r0 + 1, true, y2);
-  DwRow xm = dw_make_row(ldx(r0 - 1, true, tmp), s, SW);
-  DwRow xc = dw_make_row(ldx(r0, true, xcr), s, SW);
-  float4 xn = ldx(r0 + 1, true, xnr);
+  // the first rows are requested before the BatchNorm sums are finished
+  const Pend pm = load_row(r0 - 1, true), pc = load_row(r0, true);
+  Pend p1 = load_row(r0 + 1, true), p2 = load_row(r0 + 2, r0 + 2 <= r1);
   if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
-  DwRow gm = dw_make_row(bn_g(g0, y0, rowok(r0 - 1, true)), s, SW);
-  DwRow gc = dw_make_row(bn_g(g1, y1, rowok(r0, true)), s, SW);
-  float4 gn = bn_g(g2, y2, rowok(r0 + 1, true));
+  DwRow gm = dw_make_row(use_g(pm, rowok(r0 - 1, true)), s, SW);
+  DwRow gc = dw_make_row(use_g(pc, rowok(r0, true)), s, SW);
+  DwRow xm = dw_make_row(use_x(pm, rowok(r0 - 1, true)), s, SW);
+  DwRow xc = dw_make_row(use_x(pc, rowok(r0, true)), s, SW);
+  float4 xcr = pc.x;
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
   float b1 = 0.f, b2 = 0.f;
   for (int i = 0; i < RPG; ++i) {  // uniform trip count: the lane exchanges need every lane
     const int a = r0 + i;
-    const DwRow gq = dw_make_row(gn, s, SW), xq = dw_make_row(xn, s, SW);
-    const float4 xqr = xnr;
     // past its last row a lane must not see the next group's rows as its own window
-    gn = ldg(a + 2, a + 2 <= r1);
-    xn = ldx(a + 2, a + 2 <= r1, xnr);
+    const bool v1 = rowok(a + 1, a + 1 <= r1);
+    const DwRow gq = dw_make_row(use_g(p1, v1), s, SW), xq = dw_make_row(use_x(p1, v1), s, SW);
+    const float4 xqr = p1.x;
+    p1 = p2;
+    p2 = load_row(a + 3, a + 3 <= r1);
     if (a < r1) {
       if (dp) {
         float o[4];
@@ -1183,54 +1183,59 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
   const float2 z2 = make_float2(0.f, 0.f);
   const float xsc = f.xss ? f.xss[ch] : 1.f, xsf = f.xss ? f.xss[C + ch] : 0.f;
   const float mean1 = f.ws_in ? f.xstat[ch] : 0.f, istd1 = f.ws_in ? f.xstat[C + ch] : 0.f;
-  // with xss: the BatchNorm(+activation) output the convolution saw; `raw` gets x itself
-  auto ldx = [&](int row, bool ok, float4& raw) -> float4 {
-    raw = z4;
-    if (!(ok && has && row >= 0 && row < H)) return z4;
-    raw = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
-    return f.xss ? dw_norm4(raw, xsc, xsf, f.xact) : raw;
+  auto xok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
+  auto gok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < Ho; };
+  // The words of a step (input rows 2i, 2i+1, gradient row i+1) travel raw (zeros where not
+  // readable) and are only transformed when the step uses them, so a load is not waited for
+  // before the step ahead of it is done.
+  struct Pend { float4 x0, x1; float2 g, y; };
+  auto load_step = [&](int i, bool ok) -> Pend {
+    Pend q;
+    q.x0 = q.x1 = z4;
+    q.g = q.y = z2;
+    if (xok(2 * i, ok)) q.x0 = *reinterpret_cast<const float4*>(xp + (size_t)(2 * i) * W);
+    if (xok(2 * i + 1, ok)) q.x1 = *reinterpret_cast<const float4*>(xp + (size_t)(2 * i + 1) * W);
+    if (gok(i + 1, ok)) {
+      q.g = *reinterpret_cast<const float2*>(gp + (size_t)(i + 1) * Wo);
+      if (f.y) q.y = *reinterpret_cast<const float2*>(yp + (size_t)(i + 1) * Wo);
+    }
+    return q;
   };
-  auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < Ho; };
-  auto ldg_raw = [&](int row, bool ok, float2& yv) -> float2 {
-    yv = z2;
-    if (!rowok(row, ok)) return z2;
-    if (f.y) yv = *reinterpret_cast<const float2*>(yp + (size_t)row * Wo);
-    return *reinterpret_cast<const float2*>(gp + (size_t)row * Wo);
-  };
-  auto bn_g = [&](float2 gv, const float2& yv, bool valid) -> float2 {
+  auto use_g = [&](float2 gv, const float2& yv, bool valid) -> float2 {
     if (f.y && valid) {  // input gradient of the BatchNorm behind the conv
       gv.x = dw_bn_dx(gv.x, yv.x, yb);
       gv.y = dw_bn_dx(gv.y, yv.y, yb);
     }
     return gv;
   };
-  auto ldg = [&](int row, bool ok) -> float2 {
-    float2 yv;
-    const float2 gv = ldg_raw(row, ok, yv);
-    return bn_g(gv, yv, rowok(row, ok));
+  // with xss: the BatchNorm(+activation) output the convolution saw; the padding stays zero
+  auto use_x = [&](const float4& raw, bool valid) -> float4 {
+    return (f.xss && valid) ? dw_norm4(raw, xsc, xsf, f.xact) : raw;
   };
   // the first rows are requested before the BatchNorm sums are finished
-  float4 xn0r, xn1r, tmp;
-  float2 y0, y1;
-  float2 g0 = ldg_raw(r0, true, y0), g1 = ldg_raw(r0 + 1, true, y1);
-  DwX2 xm = dw_make_x2(ldx(2 * r0 - 1, true, tmp), s);
-  float4 xn0 = ldx(2 * r0, true, xn0r), xn1 = ldx(2 * r0 + 1, true, xn1r);
+  float4 xm_raw = z4;
+  float2 gc_raw = z2, yc_raw = z2;
+  if (xok(2 * r0 - 1, true)) xm_raw = *reinterpret_cast<const float4*>(xp + (size_t)(2 * r0 - 1) * W);
+  if (gok(r0, true)) {
+    gc_raw = *reinterpret_cast<const float2*>(gp + (size_t)r0 * Wo);
+    if (f.y) yc_raw = *reinterpret_cast<const float2*>(yp + (size_t)r0 * Wo);
+  }
+  Pend p1 = load_step(r0, true), p2 = load_step(r0 + 1, r0 + 1 < r1);
   if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
-  DwG2 gc = dw_make_g2(bn_g(g0, y0, rowok(r0, true)), s, SW);
-  float2 gn = bn_g(g1, y1, rowok(r0 + 1, true));
+  DwX2 xm = dw_make_x2(use_x(xm_raw, xok(2 * r0 - 1, true)), s);
+  DwG2 gc = dw_make_g2(use_g(gc_raw, yc_raw, gok(r0, true)), s, SW);
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
   float b1 = 0.f, b2 = 0.f;
   for (int it = 0; it < RPG; ++it) {  // uniform trip count: the lane exchanges need every lane
     const int i = r0 + it;
-    const DwX2 x0 = dw_make_x2(xn0, s), x1 = dw_make_x2(xn1, s);
-    const float4 x0r = xn0r, x1r = xn1r;
-    const DwG2 gq = dw_make_g2(gn, s, SW);
-    const bool more = i + 1 < r1;
-    xn0 = ldx(2 * i + 2, more, xn0r);
-    xn1 = ldx(2 * i + 3, more, xn1r);
-    gn = ldg(i + 2, more);
+    const bool ok = it == 0 || i < r1;  // a lane must not see the next group's rows as its own
+    const DwX2 x0 = dw_make_x2(use_x(p1.x0, xok(2 * i, ok)), s), x1 = dw_make_x2(use_x(p1.x1, xok(2 * i + 1, ok)), s);
+    const float4 x0r = p1.x0, x1r = p1.x1;
+    const DwG2 gq = dw_make_g2(use_g(p1.g, p1.y, gok(i + 1, ok)), s, SW);
+    p1 = p2;
+    p2 = load_step(i + 2, i + 2 < r1);
     if (i < r1) {
       if (dp) {
         // input row 2i: centre kernel row of output row i; row 2i+1: kernel row 0 of output
