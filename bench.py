@@ -79,7 +79,11 @@ def kernel_model(cfg):
                 out.setdefault(name, []).append(4 * (cin + cout) * nq)                      # g and x in
         if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"]:
             oc, oh, ow = oshape
-            out.setdefault("dw3x3_fwd_f32_kernel", []).append(4 * B * (shape[0] * shape[1] * shape[2] + oc * oh * ow))
+            if shape[2] % 4 == 0 and (L["stride"] == 1 or shape[1] % 2 == 0):
+                name = "dw3x3_fwd_s%d_f32_kernel" % L["stride"]
+            else:
+                name = "dw3x3_fwd_f32_kernel"
+            out.setdefault(name, []).append(4 * B * (shape[0] * shape[1] * shape[2] + oc * oh * ow))
         if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"]:
             c, h, w = shape
             if w % 4 == 0 and (L["stride"] == 1 or h % 2 == 0):

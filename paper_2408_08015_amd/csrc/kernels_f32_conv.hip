@@ -1284,6 +1284,166 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
   }
 }
 
+// Forward without LDS (W % 4 == 0, W <= 256), the same lane layout as the backward kernels above:
+// one wavefront per (n, c) plane, lane (s, rg) owns a four-pixel column strip of the rows of row
+// group rg and slides a three-row register window down them.  Rows travel raw and two steps
+// ahead; with a BatchNorm in front they are normalised when they enter the window (padding
+// stays zero).  One 16-byte load and one 16-byte store (stride 2: two loads, one 8-byte store)
+// per lane and step.
+__global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __restrict__ x,
+                                                               const float* __restrict__ w, float* __restrict__ y,
+                                                               int NC, int C, int H, int W, int RPG, DwBnIn bi,
+                                                               DwBnOut bo) {
+  const int lane = threadIdx.x & 63;
+  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (plane >= NC) return;  // whole wavefront
+  const int ch = plane % C;
+  const int SW = W >> 2;
+  const int rg = lane / SW, s = lane - rg * SW;
+  const int r0 = rg * RPG;
+  const int r1 = min(r0 + RPG, H);  // lanes past the last group: r0 >= H, no rows
+  const bool has = r0 < H;
+  const float* xp = x + (size_t)plane * H * W + 4 * s;
+  float* yp = y + (size_t)plane * H * W + 4 * s;
+  float wk[9];
+  const float* wc = w + (size_t)ch * 9;
+#pragma unroll
+  for (int k = 0; k < 9; ++k) wk[k] = wc[k];
+  const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
+  auto load_row = [&](int row, bool ok) -> float4 {
+    return rowok(row, ok) ? *reinterpret_cast<const float4*>(xp + (size_t)row * W) : z4;
+  };
+  // the first rows are requested before the statistics of the BatchNorm in front are finished
+  const float4 pm = load_row(r0 - 1, true), pc = load_row(r0, true);
+  float4 p1 = load_row(r0 + 1, true), p2 = load_row(r0 + 2, r0 + 2 <= r1);
+  float sc = 1.f, sf = 0.f;
+  if (bi.on) {  // every lane computes the same coefficients; lane 0 of a sample-0 plane records them
+    double s1, s2;
+    bn_add_partials(bi.ws, ch, bi.P, s1, s2);
+    bn_coefficients(s1, s2, bi.count, bi.gamma[ch], bi.beta[ch], bi.eps, ch, C, plane < C && lane == 0, bi.stat, bi.ss,
+                    bi.running, sc, sf);
+  }
+  auto use_x = [&](const float4& raw, bool valid) -> float4 {
+    return (bi.on && valid) ? dw_norm4(raw, sc, sf, bi.act) : raw;
+  };
+  DwRow xm = dw_make_row(use_x(pm, rowok(r0 - 1, true)), s, SW);
+  DwRow xc = dw_make_row(use_x(pc, rowok(r0, true)), s, SW);
+  float t1 = 0.f, t2 = 0.f;
+  for (int i = 0; i < RPG; ++i) {  // uniform trip count: the lane exchanges need every lane
+    const int a = r0 + i;
+    // past its last row a lane must not see the next group's rows as its own window
+    const DwRow xq = dw_make_row(use_x(p1, rowok(a + 1, a + 1 <= r1)), s, SW);
+    p1 = p2;
+    p2 = load_row(a + 3, a + 3 <= r1);
+    if (a < r1) {
+      float o[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {  // y[a][b] = sum_{u,q} w[u][q] x[a+u-1][b+q-1]
+        float v = 0.f;
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+          v += wk[0 * 3 + q] * xm.v[j + q];
+          v += wk[1 * 3 + q] * xc.v[j + q];
+          v += wk[2 * 3 + q] * xq.v[j + q];
+        }
+        o[j] = v;
+        t1 += v;
+        t2 += v * v;
+      }
+      *reinterpret_cast<float4*>(yp + (size_t)a * W) = make_float4(o[0], o[1], o[2], o[3]);
+    }
+    xm = xc;
+    xc = xq;
+  }
+  if (bo.on) {  // (sum, sum of squares) of the plane for the BatchNorm behind
+    const double d1 = wave_sum_d((double)t1), d2 = wave_sum_d((double)t2);
+    if (lane == 0) {
+      double* o = bo.ws + ((size_t)ch * (NC / C) + plane / C) * 2;
+      o[0] = d1;
+      o[1] = d2;
+    }
+  }
+}
+
+// stride 2 (H even): per step one output row i = input rows 2i, 2i+1 (row 2i-1 is carried over);
+// lane (s, rg) owns input columns 4s..4s+3 = output columns 2s, 2s+1
+__global__ __launch_bounds__(256) void dw3x3_fwd_s2_f32_kernel(const float* __restrict__ x,
+                                                               const float* __restrict__ w, float* __restrict__ y,
+                                                               int NC, int C, int H, int W, int RPG, DwBnIn bi,
+                                                               DwBnOut bo) {
+  const int lane = threadIdx.x & 63;
+  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (plane >= NC) return;  // whole wavefront
+  const int ch = plane % C;
+  const int SW = W >> 2, Ho = H >> 1, Wo = W >> 1;
+  const int rg = lane / SW, s = lane - rg * SW;
+  const int r0 = rg * RPG;  // output rows [r0, r1)
+  const int r1 = min(r0 + RPG, Ho);
+  const bool has = r0 < Ho;
+  const float* xp = x + (size_t)plane * H * W + 4 * s;
+  float* yp = y + (size_t)plane * Ho * Wo + 2 * s;
+  float wk[9];
+  const float* wc = w + (size_t)ch * 9;
+#pragma unroll
+  for (int k = 0; k < 9; ++k) wk[k] = wc[k];
+  const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
+  auto load_row = [&](int row, bool ok) -> float4 {
+    return rowok(row, ok) ? *reinterpret_cast<const float4*>(xp + (size_t)row * W) : z4;
+  };
+  const float4 pm = load_row(2 * r0 - 1, true);
+  float4 p1a = load_row(2 * r0, true), p1b = load_row(2 * r0 + 1, true);
+  float4 p2a = load_row(2 * r0 + 2, r0 + 1 < r1), p2b = load_row(2 * r0 + 3, r0 + 1 < r1);
+  float sc = 1.f, sf = 0.f;
+  if (bi.on) {
+    double s1, s2;
+    bn_add_partials(bi.ws, ch, bi.P, s1, s2);
+    bn_coefficients(s1, s2, bi.count, bi.gamma[ch], bi.beta[ch], bi.eps, ch, C, plane < C && lane == 0, bi.stat, bi.ss,
+                    bi.running, sc, sf);
+  }
+  auto use_x = [&](const float4& raw, bool valid) -> float4 {
+    return (bi.on && valid) ? dw_norm4(raw, sc, sf, bi.act) : raw;
+  };
+  DwX2 xm = dw_make_x2(use_x(pm, rowok(2 * r0 - 1, true)), s);
+  float t1 = 0.f, t2 = 0.f;
+  for (int it = 0; it < RPG; ++it) {  // uniform trip count: the lane exchanges need every lane
+    const int i = r0 + it;
+    const bool ok = it == 0 || i < r1;  // a lane must not see the next group's rows as its own
+    const DwX2 x0 = dw_make_x2(use_x(p1a, rowok(2 * i, ok)), s), x1 = dw_make_x2(use_x(p1b, rowok(2 * i + 1, ok)), s);
+    p1a = p2a;
+    p1b = p2b;
+    p2a = load_row(2 * i + 4, i + 2 < r1);
+    p2b = load_row(2 * i + 5, i + 2 < r1);
+    if (i < r1) {
+      float o[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {  // y[i][2s+j] = sum_{u,q} w[u][q] x[2i+u-1][4s+2j+q-1]
+        float v = 0.f;
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+          v += wk[0 * 3 + q] * xm.v[2 * j + q];
+          v += wk[1 * 3 + q] * x0.v[2 * j + q];
+          v += wk[2 * 3 + q] * x1.v[2 * j + q];
+        }
+        o[j] = v;
+        t1 += v;
+        t2 += v * v;
+      }
+      *reinterpret_cast<float2*>(yp + (size_t)i * Wo) = make_float2(o[0], o[1]);
+    }
+    xm = x1;
+  }
+  if (bo.on) {
+    const double d1 = wave_sum_d((double)t1), d2 = wave_sum_d((double)t2);
+    if (lane == 0) {
+      double* o = bo.ws + ((size_t)ch * (NC / C) + plane / C) * 2;
+      o[0] = d1;
+      o[1] = d2;
+    }
+  }
+}
+
 // G[c][t] += sum_n part[n][c][t]: eight sample lanes per output, fixed butterfly order
 __global__ __launch_bounds__(256) void dw3x3_wgrad_final_kernel(const float* __restrict__ part,
                                                                 float* __restrict__ G, int N, int C) {
@@ -1308,10 +1468,22 @@ static DwGeom dw_geom(int N, int C, int H, int W, int stride) {
 
 void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int N, int C, int H, int W,
                    int stride, const DwBnIn* bn_in, double* stats_out) {
-  DwGeom gm = dw_geom(N, C, H, W, stride);
   DwBnIn bi{};
   if (bn_in) bi = *bn_in;
   DwBnOut bo{stats_out, stats_out != nullptr};
+  if (stride == 1 && W % 4 == 0 && W <= 256) {
+    const int groups = 64 / (W / 4);
+    KLAUNCH(dw3x3_fwd_s1_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, x, w, y, N * C, C, H, W,
+            cdiv(H, groups), bi, bo);
+    return;
+  }
+  if (stride == 2 && W % 4 == 0 && H % 2 == 0 && W <= 256) {
+    const int groups = 64 / (W / 4);
+    KLAUNCH(dw3x3_fwd_s2_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, x, w, y, N * C, C, H, W,
+            cdiv(H / 2, groups), bi, bo);
+    return;
+  }
+  DwGeom gm = dw_geom(N, C, H, W, stride);
   // planes, weights, coefficients; then (8-byte aligned) four pairs of doubles
   size_t lds = ((((size_t)gm.ppb * ((H + 2) * (W + 2) + 11)) + 1) & ~(size_t)1) * sizeof(float) + 8 * sizeof(double);
   (void)hipFuncSetAttribute((const void*)dw3x3_fwd_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
