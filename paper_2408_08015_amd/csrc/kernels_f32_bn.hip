@@ -61,12 +61,24 @@ __global__ __launch_bounds__(256) void bn_stats_partial_kernel(const float* __re
   const int e0 = ch * b.chunk, e1 = min(e0 + b.chunk, HW), len = e1 - e0;
   float s1 = 0.f, s2 = 0.f;
   if (VEC) {
+    // a block's share is at most 4096 elements: all of a thread's words are requested at once
     const int q = len >> 2, total = (n1 - n0) * q;
-    for (int idx = threadIdx.x; idx < total; idx += 256) {
-      const int nl = idx / q, e = e0 + 4 * (idx - nl * q);
-      const float4 v = *reinterpret_cast<const float4*>(x + ((size_t)(n0 + nl) * C + c) * HW + e);
-      s1 += (v.x + v.y) + (v.z + v.w);
-      s2 += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+    for (int i0 = threadIdx.x; i0 < total; i0 += 1024) {
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int idx = i0 + 256 * u;
+        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (idx < total) {
+          const int nl = idx / q, e = e0 + 4 * (idx - nl * q);
+          v[u] = *reinterpret_cast<const float4*>(x + ((size_t)(n0 + nl) * C + c) * HW + e);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        s1 += (v[u].x + v[u].y) + (v[u].z + v[u].w);
+        s2 += (v[u].x * v[u].x + v[u].y * v[u].y) + (v[u].z * v[u].z + v[u].w * v[u].w);
+      }
     }
   } else {
     const int total = (n1 - n0) * len;
@@ -208,17 +220,30 @@ __global__ __launch_bounds__(256) void bn_bwd_partial_kernel(const float* __rest
   const float mean = stat[c], istd = stat[C + c], sc = ss[c], sf = ss[C + c];
   float s1 = 0.f, s2 = 0.f;
   if (VEC) {
+    // a block's share is at most 4096 elements: all of a thread's words are requested at once
     const int q = len >> 2, total = (n1 - n0) * q;
-    for (int idx = threadIdx.x; idx < total; idx += 256) {
-      const int nl = idx / q, e = e0 + 4 * (idx - nl * q);
-      const size_t off = ((size_t)(n0 + nl) * C + c) * HW + e;
-      float4 xv = *reinterpret_cast<const float4*>(x + off);
-      float4 gv = *reinterpret_cast<const float4*>(g + off);
-      float g0 = gv.x * act_mask(xv.x * sc + sf, act), g1 = gv.y * act_mask(xv.y * sc + sf, act);
-      float g2 = gv.z * act_mask(xv.z * sc + sf, act), g3 = gv.w * act_mask(xv.w * sc + sf, act);
-      s1 += (g0 + g1) + (g2 + g3);
-      s2 += (g0 * ((xv.x - mean) * istd) + g1 * ((xv.y - mean) * istd)) +
-            (g2 * ((xv.z - mean) * istd) + g3 * ((xv.w - mean) * istd));
+    for (int i0 = threadIdx.x; i0 < total; i0 += 1024) {
+      float4 xq[4], gq[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int idx = i0 + 256 * u;
+        xq[u] = gq[u] = make_float4(0.f, 0.f, 0.f, 0.f);  // g = 0 adds nothing to either sum
+        if (idx < total) {
+          const int nl = idx / q, e = e0 + 4 * (idx - nl * q);
+          const size_t off = ((size_t)(n0 + nl) * C + c) * HW + e;
+          xq[u] = *reinterpret_cast<const float4*>(x + off);
+          gq[u] = *reinterpret_cast<const float4*>(g + off);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float4 xv = xq[u], gv = gq[u];
+        float g0 = gv.x * act_mask(xv.x * sc + sf, act), g1 = gv.y * act_mask(xv.y * sc + sf, act);
+        float g2 = gv.z * act_mask(xv.z * sc + sf, act), g3 = gv.w * act_mask(xv.w * sc + sf, act);
+        s1 += (g0 + g1) + (g2 + g3);
+        s2 += (g0 * ((xv.x - mean) * istd) + g1 * ((xv.y - mean) * istd)) +
+              (g2 * ((xv.z - mean) * istd) + g3 * ((xv.w - mean) * istd));
+      }
     }
   } else {
     const int total = (n1 - n0) * len;
