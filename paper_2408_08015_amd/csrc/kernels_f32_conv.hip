@@ -990,6 +990,7 @@ __device__ __forceinline__ DwRow dw_make_row(float4 c, int s, int SW) {
   r.v[5] = s == SW - 1 ? 0.f : right;
   return r;
 }
+template <int D>  // rows requested ahead of the window (2, or 4 for short row groups)
 __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __restrict__ g,
                                                                const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ dx,
@@ -1046,7 +1047,10 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
   };
   // the first rows are requested before the BatchNorm sums are finished
   const Pend pm = load_row(r0 - 1, true), pc = load_row(r0, true);
-  Pend p1 = load_row(r0 + 1, true), p2 = load_row(r0 + 2, r0 + 2 <= r1);
+  Pend pn[D];
+  pn[0] = load_row(r0 + 1, true);
+#pragma unroll
+  for (int d = 1; d < D; ++d) pn[d] = load_row(r0 + 1 + d, r0 + 1 + d <= r1);
   if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
   DwRow gm = dw_make_row(use_g(pm, rowok(r0 - 1, true)), s, SW);
   DwRow gc = dw_make_row(use_g(pc, rowok(r0, true)), s, SW);
@@ -1061,10 +1065,11 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
     const int a = r0 + i;
     // past its last row a lane must not see the next group's rows as its own window
     const bool v1 = rowok(a + 1, a + 1 <= r1);
-    const DwRow gq = dw_make_row(use_g(p1, v1), s, SW), xq = dw_make_row(use_x(p1, v1), s, SW);
-    const float4 xqr = p1.x;
-    p1 = p2;
-    p2 = load_row(a + 3, a + 3 <= r1);
+    const DwRow gq = dw_make_row(use_g(pn[0], v1), s, SW), xq = dw_make_row(use_x(pn[0], v1), s, SW);
+    const float4 xqr = pn[0].x;
+#pragma unroll
+    for (int d = 0; d + 1 < D; ++d) pn[d] = pn[d + 1];
+    pn[D - 1] = load_row(a + 1 + D, a + 1 + D <= r1);
     if (a < r1) {
       if (dp) {
         float o[4];
@@ -1290,6 +1295,7 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
 // ahead; with a BatchNorm in front they are normalised when they enter the window (padding
 // stays zero).  One 16-byte load and one 16-byte store (stride 2: two loads, one 8-byte store)
 // per lane and step.
+template <int D>  // rows requested ahead of the window (2, or 4 for short row groups)
 __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ y,
                                                                int NC, int C, int H, int W, int RPG, DwBnIn bi,
@@ -1312,11 +1318,16 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __re
   const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
   auto load_row = [&](int row, bool ok) -> float4 {
-    return rowok(row, ok) ? *reinterpret_cast<const float4*>(xp + (size_t)row * W) : z4;
+    float4 v = z4;
+    if (rowok(row, ok)) v = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
+    return v;
   };
   // the first rows are requested before the statistics of the BatchNorm in front are finished
   const float4 pm = load_row(r0 - 1, true), pc = load_row(r0, true);
-  float4 p1 = load_row(r0 + 1, true), p2 = load_row(r0 + 2, r0 + 2 <= r1);
+  float4 pn[D];
+  pn[0] = load_row(r0 + 1, true);
+#pragma unroll
+  for (int d = 1; d < D; ++d) pn[d] = load_row(r0 + 1 + d, r0 + 1 + d <= r1);
   float sc = 1.f, sf = 0.f;
   if (bi.on) {  // every lane computes the same coefficients; lane 0 of a sample-0 plane records them
     double s1, s2;
@@ -1333,9 +1344,10 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __re
   for (int i = 0; i < RPG; ++i) {  // uniform trip count: the lane exchanges need every lane
     const int a = r0 + i;
     // past its last row a lane must not see the next group's rows as its own window
-    const DwRow xq = dw_make_row(use_x(p1, rowok(a + 1, a + 1 <= r1)), s, SW);
-    p1 = p2;
-    p2 = load_row(a + 3, a + 3 <= r1);
+    const DwRow xq = dw_make_row(use_x(pn[0], rowok(a + 1, a + 1 <= r1)), s, SW);
+#pragma unroll
+    for (int d = 0; d + 1 < D; ++d) pn[d] = pn[d + 1];
+    pn[D - 1] = load_row(a + 1 + D, a + 1 + D <= r1);
     if (a < r1) {
       float o[4];
 #pragma unroll
@@ -1390,7 +1402,9 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s2_f32_kernel(const float* __re
   const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
   auto load_row = [&](int row, bool ok) -> float4 {
-    return rowok(row, ok) ? *reinterpret_cast<const float4*>(xp + (size_t)row * W) : z4;
+    float4 v = z4;
+    if (rowok(row, ok)) v = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
+    return v;
   };
   const float4 pm = load_row(2 * r0 - 1, true);
   float4 p1a = load_row(2 * r0, true), p1b = load_row(2 * r0 + 1, true);
@@ -1473,8 +1487,13 @@ void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int
   DwBnOut bo{stats_out, stats_out != nullptr};
   if (stride == 1 && W % 4 == 0 && W <= 256) {
     const int groups = 64 / (W / 4);
-    KLAUNCH(dw3x3_fwd_s1_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, x, w, y, N * C, C, H, W,
-            cdiv(H, groups), bi, bo);
+    const int rpg = cdiv(H, groups);
+    if (rpg <= 4)  // short row groups: every row of a lane is requested up front
+      KLAUNCH(dw3x3_fwd_s1_f32_kernel<4>, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg,
+              bi, bo);
+    else
+      KLAUNCH(dw3x3_fwd_s1_f32_kernel<2>, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg,
+              bi, bo);
     return;
   }
   if (stride == 2 && W % 4 == 0 && H % 2 == 0 && W <= 256) {
@@ -1497,7 +1516,8 @@ void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* 
   if (!dx || !f.xss) f.ws_in = nullptr;  // those sums need dx and the normalised input
   if (stride == 1 && W % 4 == 0 && W <= 256) {
     const int groups = 64 / (W / 4);
-    KLAUNCH(dw3x3_bwd_s1_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
+    // two rows ahead: four cost a wavefront of occupancy (three tensors per row) and measured slower
+    KLAUNCH(dw3x3_bwd_s1_f32_kernel<2>, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
             cdiv(H, groups), f);
     if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
     return;
