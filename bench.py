@@ -62,21 +62,28 @@ def kernel_model(cfg):
             nq = B * hw
 
             def cls(m, kd):
-                if _cdiv(nq, 128) * _cdiv(m, 32) < 256 and _cdiv(kd, 8) >= 16:
-                    return "pkks"
+                kg = _cdiv(kd, 8)
+                if _cdiv(nq, 128) * _cdiv(m, 32) < 256 and kg >= 16:    # K split over 4 / 8 / 16 wavefronts
+                    return "pkks" if kg <= 32 else ("pkks8" if kg <= 64 else "pkks16")
                 if hw % 4 == 0 and nq >= 65536:
                     return "pk4"
                 return "pk2" if kd > 32 else "pk1"
-            fwd_names = {"pkks": "pw_conv_f32_pkks_kernel", "pk4": "pw_conv_f32_pk4_kernel",
+            fwd_names = {"pkks": "pw_conv_f32_pkks_kernel", "pkks8": "pw_conv_f32_pkks_kernel<8>",
+                         "pkks16": "pw_conv_f32_pkks_kernel<16>", "pk4": "pw_conv_f32_pk4_kernel",
                          "pk2": "pw_conv_f32_pk_kernel<2>", "pk1": "pw_conv_f32_pk_kernel<1>"}
+            wg_name = "pw_wgrad_f32_kernel<true>" if hw % 4 == 0 else "pw_wgrad_f32_kernel<false>"
             out.setdefault(fwd_names[cls(cout, cin)], []).append(4 * (cin + cout) * nq)      # forward
             if not first or cfg.needs_input_grad:
-                # input gradient and weight-gradient partials in one launch: g and x in, dx out
                 extra = 4 * cin * nq if (res_open and cfg.layers[i - 1]["kind"] == "res_begin") else 0
-                out.setdefault("pw_bwd_dual_kernel<%s>" % cls(cin, cout), []).append(4 * (2 * cin + cout) * nq + extra)
+                bc = cls(cin, cout)
+                if bc in ("pkks8", "pkks16"):   # long K: input gradient and weight gradient as two launches
+                    out.setdefault(fwd_names[bc], []).append(4 * (cin + cout) * nq + extra)
+                    out.setdefault(wg_name, []).append(4 * (cin + cout) * nq)
+                else:
+                    # input gradient and weight-gradient partials in one launch: g and x in, dx out
+                    out.setdefault("pw_bwd_dual_kernel<%s>" % bc, []).append(4 * (2 * cin + cout) * nq + extra)
             else:
-                name = "pw_wgrad_f32_kernel<true>" if hw % 4 == 0 else "pw_wgrad_f32_kernel<false>"
-                out.setdefault(name, []).append(4 * (cin + cout) * nq)                      # g and x in
+                out.setdefault(wg_name, []).append(4 * (cin + cout) * nq)                   # g and x in
         if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"]:
             oc, oh, ow = oshape
             if shape[2] % 4 == 0 and (L["stride"] == 1 or shape[1] % 2 == 0):

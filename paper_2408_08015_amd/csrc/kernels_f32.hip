@@ -369,11 +369,19 @@ __global__ __launch_bounds__(256) void linear_fwd_kernel(const float* __restrict
     float acc[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) acc[k] = 0.f;
-    for (int i = lane; i < Cin; i += 64) {
-      float wv = wr[i];
+    for (int i0 = lane; i0 < Cin; i0 += 256) {  // four weights and their inputs requested at once
+      float wv[4], xv[4][8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k)
-        if (r0 + k < R) acc[k] += wv * x[(size_t)(r0 + k) * Cin + i];
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + 64 * u;
+        wv[u] = i < Cin ? wr[i] : 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) xv[u][k] = (i < Cin && r0 + k < R) ? x[(size_t)(r0 + k) * Cin + i] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k] += wv[u] * xv[u][k];
     }
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
@@ -395,11 +403,19 @@ __global__ __launch_bounds__(1024) void linear_dgrad_kernel(const float* __restr
     float acc[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) acc[q] = 0.f;
-    for (int o = os; o < Cout; o += 16) {
-      const float w = iv ? W[(size_t)o * Cin + i] : 0.f;
+    for (int o0 = os; o0 < Cout; o0 += 64) {  // four weights and their gradients requested at once
+      float wv[4], gv[4][8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q)
-        if (r0 + q < R) acc[q] += g[(size_t)(r0 + q) * Cout + o] * w;
+      for (int u = 0; u < 4; ++u) {
+        const int o = o0 + 16 * u;
+        wv[u] = (iv && o < Cout) ? W[(size_t)o * Cin + i] : 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) gv[u][q] = (o < Cout && r0 + q < R) ? g[(size_t)(r0 + q) * Cout + o] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] += gv[u][q] * wv[u];
     }
     __syncthreads();  // the previous round's sums have been read
 #pragma unroll

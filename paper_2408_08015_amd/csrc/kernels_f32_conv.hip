@@ -119,6 +119,7 @@ __global__ __launch_bounds__(256) void pw_conv_f32_pk_kernel(PwArgs a) {
 // block share one 32-pixel x 32-channel output tile and split K between them, so there are
 // four times as many wavefronts and a quarter of the dependent passes; the four partial
 // tiles are added through LDS in a fixed order.
+template <int WV>  // wavefronts per block = ways K is split (4, 8 or 16)
 __device__ __forceinline__ void pw_pkks_body(const PwArgs& a, int bx, int by, float (*sR)[16][64]) {
   const float4* __restrict__ Wp = a.Wp;
   const float* __restrict__ X = a.X;
@@ -142,7 +143,7 @@ __device__ __forceinline__ void pw_pkks_body(const PwArgs& a, int bx, int by, fl
   }
   const float* xq = X + (size_t)n * Kdim * HW + p;
   const float4* wl = Wp + (size_t)by * KG * 64 + lane;
-  const int gper = (KG + 3) >> 2;  // k-groups per wavefront
+  const int gper = (KG + WV - 1) / WV;  // k-groups per wavefront
   const int gbeg = wave * gper, gend = min(gbeg + gper, KG);
   floatx16 acc;
 #pragma unroll
@@ -175,21 +176,26 @@ __device__ __forceinline__ void pw_pkks_body(const PwArgs& a, int bx, int by, fl
   if (!qv) return;
   float* yq = Y + (size_t)n * Mdim * HW + p;
   const float* aq = add ? add + (size_t)n * Mdim * HW + p : nullptr;
+  constexpr int RW = 16 / WV;  // rows of the register layout each wavefront finishes
 #pragma unroll
-  for (int rr = 0; rr < 4; ++rr) {  // wavefront w finishes rows 4w .. 4w+3 of the register layout
-    const int r = 4 * wave + rr;
+  for (int rr = 0; rr < RW; ++rr) {
+    const int r = RW * wave + rr;
     const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
     if (m < Mdim) {
-      float v = (sR[0][r][lane] + sR[1][r][lane]) + (sR[2][r][lane] + sR[3][r][lane]);
+      float v = 0.f;
+#pragma unroll
+      for (int k = 0; k < WV; k += 4)  // fixed order
+        v += (sR[k][r][lane] + sR[k + 1][r][lane]) + (sR[k + 2][r][lane] + sR[k + 3][r][lane]);
       if (bias) v += bias[m];
       if (aq) v += aq[(size_t)m * HW];
       yq[(size_t)m * HW] = v;
     }
   }
 }
-__global__ __launch_bounds__(256) void pw_conv_f32_pkks_kernel(PwArgs a) {
-  __shared__ float sR[4][16][64];
-  pw_pkks_body(a, blockIdx.x, blockIdx.y, sR);
+template <int WV>
+__global__ __launch_bounds__(64 * WV) void pw_conv_f32_pkks_kernel(PwArgs a) {
+  __shared__ float sR[WV][16][64];
+  pw_pkks_body<WV>(a, blockIdx.x, blockIdx.y, sR);
 }
 
 // Large images: a wavefront owns 128 pixels; every lane loads four consecutive pixels
@@ -316,14 +322,21 @@ void pw_pack_f32(hipStream_t st, const float* W, int lda_m, int lda_k, float* Wp
 }
 
 // which product kernel serves a shape, and its grid
-struct PwPick { int var; dim3 grid; };
+struct PwPick { int var; dim3 grid; int wv; };  // wv: wavefronts per block of the K-split kernel
 static PwPick pw_pick(long NQ, int HW, int Kdim, int Mdim) {
   const int mt = cdiv(Mdim, 32), KG = cdiv(Kdim, 8);
   PwPick p;
   // Measured on 32-sample micro-batches: 128-pixel wavefronts win from 56x56 images up,
   // 32-pixel ones below (more wavefronts in flight matter more than bytes per instruction);
   // under one block per CU and K >= 128 the block splits K instead.
-  if ((long)cdiv(NQ, 128) * mt < 256 && KG >= 16) { p.var = 2; p.grid = dim3((unsigned)cdiv(NQ, 32), mt); }
+  p.wv = 4;
+  if ((long)cdiv(NQ, 128) * mt < 256 && KG >= 16) {
+    p.var = 2;
+    p.grid = dim3((unsigned)cdiv(NQ, 32), mt);
+    // one pass of 64 channels per wavefront where K allows: a longer K is a chain of dependent
+    // load-then-multiply passes, the whole cost of these small products
+    p.wv = KG <= 32 ? 4 : (KG <= 64 ? 8 : 16);
+  }
   else if (HW % 4 == 0 && NQ >= 65536) { p.var = 3; p.grid = dim3((unsigned)cdiv(NQ, 512), mt); }
   else if (Kdim > 32) { p.var = 1; p.grid = dim3((unsigned)cdiv(NQ, 128), mt); }
   else { p.var = 0; p.grid = dim3((unsigned)cdiv(NQ, 128), mt); }
@@ -339,12 +352,18 @@ static PwArgs pw_args(const float* Wp, const float* X, float* Y, const float* bi
   return a;
 }
 
+static void launch_pkks(hipStream_t st, const PwArgs& a, const PwPick& p) {
+  if (p.wv == 16) KLAUNCH_NAMED("pw_conv_f32_pkks_kernel<16>", (pw_conv_f32_pkks_kernel<16>), p.grid, dim3(1024), 0, st, a);
+  else if (p.wv == 8) KLAUNCH_NAMED("pw_conv_f32_pkks_kernel<8>", (pw_conv_f32_pkks_kernel<8>), p.grid, dim3(512), 0, st, a);
+  else KLAUNCH_NAMED("pw_conv_f32_pkks_kernel", (pw_conv_f32_pkks_kernel<4>), p.grid, dim3(256), 0, st, a);
+}
+
 void pw_conv_f32(hipStream_t st, const float* Wp, const float* X, float* Y, const float* bias, const float* add,
                  int N, int Kdim, int Mdim, int HW) {
   const PwArgs a = pw_args(Wp, X, Y, bias, add, N, Kdim, Mdim, HW);
   const PwPick p = pw_pick(a.NQ, HW, Kdim, Mdim);
   switch (p.var) {
-    case 2: KLAUNCH(pw_conv_f32_pkks_kernel, p.grid, dim3(256), 0, st, a); break;
+    case 2: launch_pkks(st, a, p); break;
     case 3: KLAUNCH(pw_conv_f32_pk4_kernel, p.grid, dim3(256), 0, st, a); break;
     case 1: KLAUNCH(pw_conv_f32_pk_kernel<2>, p.grid, dim3(256), 0, st, a); break;
     default: KLAUNCH(pw_conv_f32_pk_kernel<1>, p.grid, dim3(256), 0, st, a); break;
@@ -456,7 +475,7 @@ __global__ __launch_bounds__(256) void pw_bwd_dual_kernel(PwArgs a, WgArgs w, un
     const int bx = (int)(blockIdx.x % gAx), by = (int)(blockIdx.x / gAx);
     if (VAR == 0) pw_pk_body<1>(a, bx, by);
     else if (VAR == 1) pw_pk_body<2>(a, bx, by);
-    else if (VAR == 2) pw_pkks_body(a, bx, by, sR);
+    else if (VAR == 2) pw_pkks_body<4>(a, bx, by, sR);
     else pw_pk4_body(a, bx, by);
   } else {
     const unsigned b = blockIdx.x - nA;
@@ -535,7 +554,13 @@ void pw_conv_bwd_f32(hipStream_t st, const float* Wp_t, const float* g, float* d
   dim3 gW;
   const WgArgs w = wg_args(g, x, part, N, Cin, Cout, HW, gW);
   const bool vec = HW % 4 == 0;
-  switch (p.var) {
+  if (p.var == 2 && p.wv > 4) {
+    // long K: the input gradient runs as wider blocks (K split 8 or 16 ways) than the weight-gradient
+    // kernel's, so the two go as separate launches
+    launch_pkks(st, a, p);
+    if (vec) KLAUNCH(pw_wgrad_f32_kernel<true>, gW, dim3(256), 0, st, w);
+    else KLAUNCH(pw_wgrad_f32_kernel<false>, gW, dim3(256), 0, st, w);
+  } else switch (p.var) {
     case 2: launch_dual<2>(st, a, w, p.grid, gW, vec); break;
     case 3: launch_dual<3>(st, a, w, p.grid, gW, vec); break;
     case 1: launch_dual<1>(st, a, w, p.grid, gW, vec); break;
@@ -626,10 +651,13 @@ struct DwGeom {
 };
 
 // planes per block: about 4096 input elements per block, a power of two in [1, 16]
-static int dw_ppb(int H, int W) {
+// planes per block of the LDS kernels: a power of two up to 16 with about 4096 elements per
+// block, but fewer while that leaves under 1024 blocks (small tensors are latency-bound: more,
+// shorter blocks, and one wavefront per plane in the BatchNorm prologues)
+static int dw_ppb(int H, int W, long NC) {
   int p = 4096 / (H * W);
   int r = 1;
-  while (r * 2 <= p && r < 16) r *= 2;
+  while (r * 2 <= p && r < 16 && NC / (r * 2) >= 1024) r *= 2;
   return r;
 }
 
@@ -1475,8 +1503,8 @@ static DwGeom dw_geom(int N, int C, int H, int W, int stride) {
   DwGeom gm;
   gm.C = C; gm.H = H; gm.W = W; gm.stride = stride;
   gm.Ho = conv_out(H, 3, stride, 1); gm.Wo = conv_out(W, 3, stride, 1);
-  gm.ppb = dw_ppb(H, W);
   gm.NC = N * C;
+  gm.ppb = dw_ppb(H, W, gm.NC);
   return gm;
 }
 

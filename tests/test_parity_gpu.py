@@ -71,6 +71,9 @@ def one(layers, in_shape, B=4, M=2, name="op", seed=7, needs_input_grad=True):
     (160, 960, 7, 2),     # many output tiles
     (6, 10, 5, 3),        # everything smaller than one tile
     (33, 65, 9, 2),       # odd channel counts
+    (384, 64, 14, 2),     # few pixels, K = 384: the block splits K over 8 wavefronts
+    (64, 384, 14, 2),     # ... and in the input gradient
+    (960, 168, 7, 3),     # K = 960: 16 wavefronts; ragged output tile
 ])
 def test_pointwise_conv(A, cin, cout, hw, B):
     check(one([conv(cin, cout, 1)], (cin, hw, hw), B=B, name="pw%dx%d" % (cin, cout)))
