@@ -80,7 +80,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
         bi.gamma = s.W + bn.w_off; bi.beta = s.W + bn.b_off;
         bi.stat = aux; bi.ss = aux + 2 * I.c; bi.running = s.running + bn.run_off;
         bi.count = (double)BI.n * BI.h * BI.w; bi.eps = bn.eps;
-        bi.P = bn.bn_stats_given ? BI.n : bn_parts(BI.n, BI.h * BI.w);
+        bi.P = bn.bn_stats_given ? bn.given_parts : bn_parts(BI.n, BI.h * BI.w);
         bi.act = bn.act; bi.on = 1;
       }
       dw3x3_fwd_f32(st, x, s.W + op.w_off, (float*)act_ptr(c, op.out), I.n, I.c, I.h, I.w, op.stride,
@@ -106,7 +106,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       if (!op.bn_lazy)  // else the depthwise conv behind normalises on load
         bn_apply_f32(st, x, s.W + op.w_off, s.W + op.b_off, op.skip >= 0 ? (cf)act_ptr(c, op.skip) : nullptr,
                      (float*)act_ptr(c, op.out), aux, aux + 2 * I.c, s.running + op.run_off, ws,
-                     op.bn_stats_given ? I.n : bn_parts(I.n, HW), I.n, I.c, HW, op.eps, op.act);
+                     op.bn_stats_given ? op.given_parts : bn_parts(I.n, HW), I.n, I.c, HW, op.eps, op.act);
       break;
     }
     case OP_ACT:
@@ -213,7 +213,7 @@ void bwd_op(Ctx& c, const Op& op) {
         f.ws_out = reinterpret_cast<const double*>(scratch(c, bn));
         f.Ggamma = s.G + bn.w_off; f.Gbeta = s.G + bn.b_off;
         f.ycount = (double)O.n * O.h * O.w;
-        f.P_out = bn.bn_bwd_sums_given ? O.n : bn_parts(O.n, O.h * O.w);
+        f.P_out = bn.bn_bwd_sums_given ? bn.given_bwd_parts : bn_parts(O.n, O.h * O.w);
         f.yact = bn.act;
       }
       dw3x3_bwd_f32(st, g, x, s.W + op.w_off, (float*)gin, reinterpret_cast<float*>(scratch(c, op)),
@@ -260,7 +260,7 @@ void bwd_op(Ctx& c, const Op& op) {
       const bool given = op.bn_bwd_sums_given;
       if (!given) bn_bwd_partial_f32(st, g, x, aux, aux + 2 * I.c, ws, I.n, I.c, HW, op.act);
       if (!op.bn_bwd_apply_fused)
-        bn_bwd_apply_f32(st, g, x, aux, aux + 2 * I.c, s.W + op.w_off, ws, given ? I.n : bn_parts(I.n, HW), (float*)gin,
+        bn_bwd_apply_f32(st, g, x, aux, aux + 2 * I.c, s.W + op.w_off, ws, given ? op.given_bwd_parts : bn_parts(I.n, HW), (float*)gin,
                          s.G + op.w_off, s.G + op.b_off, I.n, I.c, HW, op.act);
       break;
     }
@@ -471,7 +471,7 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
         break;
       }
       case OP_CONV_DW:
-        add(scf, s.G + op.w_off, (size_t)I.c * 9, I.n, (size_t)I.c * 9, 1, (size_t)I.c * 9);
+        add(scf, s.G + op.w_off, (size_t)I.c * 9, dw3x3_parts(I.n, I.c, I.h, I.w, op.stride), (size_t)I.c * 9, 1, (size_t)I.c * 9);
         break;
       case OP_CONV_IGEMM:
         add_wgrad(reinterpret_cast<float*>(sc + align256(s.acts[op.out].bytes)),

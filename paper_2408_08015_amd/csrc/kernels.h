@@ -43,7 +43,7 @@ void pw_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, f
 // DwBnIn: its input is x' = act(x*scale[c] + shift[c]) of a BatchNorm over the tensor passed as x;
 //   the kernel finishes that BatchNorm's statistics from the P partial pairs ws[c][P][2]
 //   (records them as the BatchNorm's own apply pass would) and normalises while staging;
-// DwBnOut: it leaves per-plane (sum, sum of squares) of its output in ws[c][N][2] for the
+// DwBnOut: it leaves (sum, sum of squares) of its output in ws[c][dw3x3_parts()][2] for the
 //   BatchNorm that follows.
 struct DwBnIn {
   const double* ws;
@@ -64,16 +64,22 @@ struct DwBnOut {
 void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int N, int C, int H,
                    int W, int stride, const DwBnIn* bn_in = nullptr, double* stats_out = nullptr);
 // Backward of the depthwise conv from one read of g and x: dx (skipped if NULL) and
-// G[C][3][3] += weight gradient.  `part` holds dw3x3_bwd_f32_ws(N, C) floats: N partials of
+// G[C][3][3] += weight gradient.  `part` holds dw3x3_bwd_f32_ws(...) floats: dw3x3_parts() partials of
 // C*9 sums; with G = NULL the reduction is left to the caller (reduce_tasks_f32).
-size_t dw3x3_bwd_f32_ws(int N, int C);
+size_t dw3x3_bwd_f32_ws(int N, int C, int H, int W, int stride);
+// Partial sums per channel that the depthwise kernels leave (weight-gradient partials, BatchNorm
+// sums): one per sample, or several where a plane is split into bands of rows over wavefronts.
+int dw3x3_parts(int N, int C, int H, int W, int stride);
+struct DwBands {
+  int bands, rpb;  // bands per plane, rows per band
+};
 // Optional BatchNorm work of the depthwise backward kernel (a NULL pointer switches a part off).
 struct DwBwdFuse {
   // BatchNorm(+act) in front of the conv whose output was never written: the conv's input is
   // act(x*xss[c] + xss[C + c]), recomputed on load
   const float* xss = nullptr;
   int xact = 0;
-  // ... and that BatchNorm's backward sums, one pair per plane: ws_in[c][N][2] =
+  // ... and that BatchNorm's backward sums: ws_in[c][dw3x3_parts()][2] =
   // (sum g', sum g'*xhat), g' = dx*act'(.), xhat = (x - xstat[c])*xstat[C + c]; needs xss and dx
   const float* xstat = nullptr;
   double* ws_in = nullptr;

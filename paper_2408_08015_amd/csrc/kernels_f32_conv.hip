@@ -1023,15 +1023,18 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
                                                                const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ dx,
                                                                float* __restrict__ part, int NC, int C, int H,
-                                                               int W, int RPG, DwBwdFuse f) {
+                                                               int W, int RPG, DwBands bd, DwBwdFuse f) {
   const int lane = threadIdx.x & 63;
-  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (plane >= NC) return;  // whole wavefront
+  const int pb = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (pb >= NC * bd.bands) return;  // whole wavefront
+  const int plane = pb / bd.bands, band = pb - plane * bd.bands;
+  const int b0 = band * bd.rpb, b1 = min(b0 + bd.rpb, H);  // this wavefront's rows of the plane
   const int ch = plane % C;
+  const int pidx = (plane / C) * bd.bands + band, nparts = (NC / C) * bd.bands;  // partial index, partials per channel
   const int SW = W >> 2;
   const int rg = lane / SW, s = lane - rg * SW;
-  const int r0 = rg * RPG;
-  const int r1 = min(r0 + RPG, H);  // lanes past the last group: r0 >= H, no rows
+  const int r0 = b0 + rg * RPG;
+  const int r1 = min(r0 + RPG, b1);  // lanes past the last group: r0 >= b1, no rows
   const float* gp = g + (size_t)plane * H * W + 4 * s;
   const float* xp = x + (size_t)plane * H * W + 4 * s;
   const float* yp = f.y ? f.y + (size_t)plane * H * W + 4 * s : nullptr;
@@ -1043,7 +1046,7 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
   DwBnBwd yb{};
   const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   // a row is readable by this lane if it lies in the image and the lane has rows at all
-  const bool has = r0 < H;
+  const bool has = r0 < b1;
   auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
   // Rows travel as raw words (zeros where not readable) and are only transformed when they
   // enter the window, so a load is not waited for before the rows ahead of it are used up.
@@ -1079,7 +1082,7 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
   pn[0] = load_row(r0 + 1, true);
 #pragma unroll
   for (int d = 1; d < D; ++d) pn[d] = load_row(r0 + 1 + d, r0 + 1 + d <= r1);
-  if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
+  if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C && band == 0);
   DwRow gm = dw_make_row(use_g(pm, rowok(r0 - 1, true)), s, SW);
   DwRow gc = dw_make_row(use_g(pc, rowok(r0, true)), s, SW);
   DwRow xm = dw_make_row(use_x(pm, rowok(r0 - 1, true)), s, SW);
@@ -1088,7 +1091,7 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
-  float b1 = 0.f, b2 = 0.f;
+  float bs1 = 0.f, bs2 = 0.f;
   for (int i = 0; i < RPG; ++i) {  // uniform trip count: the lane exchanges need every lane
     const int a = r0 + i;
     // past its last row a lane must not see the next group's rows as its own window
@@ -1118,8 +1121,8 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             const float gmk = o[j] * act_mask(xc.v[j + 1], f.xact);
-            b1 += gmk;
-            b2 += gmk * ((raw[j] - mean1) * istd1);
+            bs1 += gmk;
+            bs2 += gmk * ((raw[j] - mean1) * istd1);
           }
         }
       }
@@ -1142,11 +1145,11 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
   for (int k = 0; k < 9; ++k) acc[k] = wave_sum(acc[k]);
   if (lane == 0)
 #pragma unroll
-    for (int k = 0; k < 9; ++k) part[(size_t)plane * 9 + k] = acc[k];
+    for (int k = 0; k < 9; ++k) part[((size_t)pidx * C + ch) * 9 + k] = acc[k];
   if (f.ws_in) {
-    const double d1 = wave_sum_d((double)b1), d2 = wave_sum_d((double)b2);
+    const double d1 = wave_sum_d((double)bs1), d2 = wave_sum_d((double)bs2);
     if (lane == 0) {
-      double* o = f.ws_in + ((size_t)ch * (NC / C) + plane / C) * 2;
+      double* o = f.ws_in + ((size_t)ch * nparts + pidx) * 2;
       o[0] = d1;
       o[1] = d2;
     }
@@ -1193,16 +1196,19 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
                                                                const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ dx,
                                                                float* __restrict__ part, int NC, int C, int H,
-                                                               int W, int RPG, DwBwdFuse f) {
+                                                               int W, int RPG, DwBands bd, DwBwdFuse f) {
   const int lane = threadIdx.x & 63;
-  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (plane >= NC) return;  // whole wavefront
+  const int pb = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (pb >= NC * bd.bands) return;  // whole wavefront
+  const int plane = pb / bd.bands, band = pb - plane * bd.bands;
   const int ch = plane % C;
+  const int pidx = (plane / C) * bd.bands + band, nparts = (NC / C) * bd.bands;  // partial index, partials per channel
   const int SW = W >> 2, Ho = H >> 1, Wo = W >> 1;
+  const int b0 = band * bd.rpb, b1 = min(b0 + bd.rpb, Ho);  // this wavefront's output rows
   const int rg = lane / SW, s = lane - rg * SW;
-  const int r0 = rg * RPG;            // output rows [r0, r1)
-  const int r1 = min(r0 + RPG, Ho);
-  const bool has = r0 < Ho;
+  const int r0 = b0 + rg * RPG;       // output rows [r0, r1)
+  const int r1 = min(r0 + RPG, b1);
+  const bool has = r0 < b1;
   const float* gp = g + (size_t)plane * Ho * Wo + 2 * s;
   const float* yp = f.y ? f.y + (size_t)plane * Ho * Wo + 2 * s : nullptr;
   const float* xp = x + (size_t)plane * H * W + 4 * s;
@@ -1254,13 +1260,13 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
     if (f.y) yc_raw = *reinterpret_cast<const float2*>(yp + (size_t)r0 * Wo);
   }
   Pend p1 = load_step(r0, true), p2 = load_step(r0 + 1, r0 + 1 < r1);
-  if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C);
+  if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C && band == 0);
   DwX2 xm = dw_make_x2(use_x(xm_raw, xok(2 * r0 - 1, true)), s);
   DwG2 gc = dw_make_g2(use_g(gc_raw, yc_raw, gok(r0, true)), s, SW);
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
-  float b1 = 0.f, b2 = 0.f;
+  float bs1 = 0.f, bs2 = 0.f;
   for (int it = 0; it < RPG; ++it) {  // uniform trip count: the lane exchanges need every lane
     const int i = r0 + it;
     const bool ok = it == 0 || i < r1;  // a lane must not see the next group's rows as its own
@@ -1283,8 +1289,8 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const float gmk = dd[j] * act_mask(j < 4 ? x0.v[j + 1] : x1.v[j - 3], f.xact);
-            b1 += gmk;
-            b2 += gmk * ((rr[j] - mean1) * istd1);
+            bs1 += gmk;
+            bs2 += gmk * ((rr[j] - mean1) * istd1);
           }
         }
       }
@@ -1306,11 +1312,11 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
   for (int k = 0; k < 9; ++k) acc[k] = wave_sum(acc[k]);
   if (lane == 0)
 #pragma unroll
-    for (int k = 0; k < 9; ++k) part[(size_t)plane * 9 + k] = acc[k];
+    for (int k = 0; k < 9; ++k) part[((size_t)pidx * C + ch) * 9 + k] = acc[k];
   if (f.ws_in) {
-    const double d1 = wave_sum_d((double)b1), d2 = wave_sum_d((double)b2);
+    const double d1 = wave_sum_d((double)bs1), d2 = wave_sum_d((double)bs2);
     if (lane == 0) {
-      double* o = f.ws_in + ((size_t)ch * (NC / C) + plane / C) * 2;
+      double* o = f.ws_in + ((size_t)ch * nparts + pidx) * 2;
       o[0] = d1;
       o[1] = d2;
     }
@@ -1326,17 +1332,20 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
 template <int D>  // rows requested ahead of the window (2, or 4 for short row groups)
 __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ y,
-                                                               int NC, int C, int H, int W, int RPG, DwBnIn bi,
-                                                               DwBnOut bo) {
+                                                               int NC, int C, int H, int W, int RPG, DwBands bd,
+                                                               DwBnIn bi, DwBnOut bo) {
   const int lane = threadIdx.x & 63;
-  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (plane >= NC) return;  // whole wavefront
+  const int pb = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (pb >= NC * bd.bands) return;  // whole wavefront
+  const int plane = pb / bd.bands, band = pb - plane * bd.bands;
+  const int b0 = band * bd.rpb, b1 = min(b0 + bd.rpb, H);  // this wavefront's rows of the plane
   const int ch = plane % C;
+  const int pidx = (plane / C) * bd.bands + band, nparts = (NC / C) * bd.bands;  // partial index, partials per channel
   const int SW = W >> 2;
   const int rg = lane / SW, s = lane - rg * SW;
-  const int r0 = rg * RPG;
-  const int r1 = min(r0 + RPG, H);  // lanes past the last group: r0 >= H, no rows
-  const bool has = r0 < H;
+  const int r0 = b0 + rg * RPG;
+  const int r1 = min(r0 + RPG, b1);  // lanes past the last group: r0 >= b1, no rows
+  const bool has = r0 < b1;
   const float* xp = x + (size_t)plane * H * W + 4 * s;
   float* yp = y + (size_t)plane * H * W + 4 * s;
   float wk[9];
@@ -1360,8 +1369,8 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __re
   if (bi.on) {  // every lane computes the same coefficients; lane 0 of a sample-0 plane records them
     double s1, s2;
     bn_add_partials(bi.ws, ch, bi.P, s1, s2);
-    bn_coefficients(s1, s2, bi.count, bi.gamma[ch], bi.beta[ch], bi.eps, ch, C, plane < C && lane == 0, bi.stat, bi.ss,
-                    bi.running, sc, sf);
+    bn_coefficients(s1, s2, bi.count, bi.gamma[ch], bi.beta[ch], bi.eps, ch, C, plane < C && band == 0 && lane == 0,
+                    bi.stat, bi.ss, bi.running, sc, sf);
   }
   auto use_x = [&](const float4& raw, bool valid) -> float4 {
     return (bi.on && valid) ? dw_norm4(raw, sc, sf, bi.act) : raw;
@@ -1399,7 +1408,7 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __re
   if (bo.on) {  // (sum, sum of squares) of the plane for the BatchNorm behind
     const double d1 = wave_sum_d((double)t1), d2 = wave_sum_d((double)t2);
     if (lane == 0) {
-      double* o = bo.ws + ((size_t)ch * (NC / C) + plane / C) * 2;
+      double* o = bo.ws + ((size_t)ch * nparts + pidx) * 2;
       o[0] = d1;
       o[1] = d2;
     }
@@ -1410,17 +1419,20 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __re
 // lane (s, rg) owns input columns 4s..4s+3 = output columns 2s, 2s+1
 __global__ __launch_bounds__(256) void dw3x3_fwd_s2_f32_kernel(const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ y,
-                                                               int NC, int C, int H, int W, int RPG, DwBnIn bi,
-                                                               DwBnOut bo) {
+                                                               int NC, int C, int H, int W, int RPG, DwBands bd,
+                                                               DwBnIn bi, DwBnOut bo) {
   const int lane = threadIdx.x & 63;
-  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (plane >= NC) return;  // whole wavefront
+  const int pb = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (pb >= NC * bd.bands) return;  // whole wavefront
+  const int plane = pb / bd.bands, band = pb - plane * bd.bands;
   const int ch = plane % C;
+  const int pidx = (plane / C) * bd.bands + band, nparts = (NC / C) * bd.bands;  // partial index, partials per channel
   const int SW = W >> 2, Ho = H >> 1, Wo = W >> 1;
+  const int b0 = band * bd.rpb, b1 = min(b0 + bd.rpb, Ho);  // this wavefront's output rows
   const int rg = lane / SW, s = lane - rg * SW;
-  const int r0 = rg * RPG;  // output rows [r0, r1)
-  const int r1 = min(r0 + RPG, Ho);
-  const bool has = r0 < Ho;
+  const int r0 = b0 + rg * RPG;  // output rows [r0, r1)
+  const int r1 = min(r0 + RPG, b1);
+  const bool has = r0 < b1;
   const float* xp = x + (size_t)plane * H * W + 4 * s;
   float* yp = y + (size_t)plane * Ho * Wo + 2 * s;
   float wk[9];
@@ -1441,8 +1453,8 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s2_f32_kernel(const float* __re
   if (bi.on) {
     double s1, s2;
     bn_add_partials(bi.ws, ch, bi.P, s1, s2);
-    bn_coefficients(s1, s2, bi.count, bi.gamma[ch], bi.beta[ch], bi.eps, ch, C, plane < C && lane == 0, bi.stat, bi.ss,
-                    bi.running, sc, sf);
+    bn_coefficients(s1, s2, bi.count, bi.gamma[ch], bi.beta[ch], bi.eps, ch, C, plane < C && band == 0 && lane == 0,
+                    bi.stat, bi.ss, bi.running, sc, sf);
   }
   auto use_x = [&](const float4& raw, bool valid) -> float4 {
     return (bi.on && valid) ? dw_norm4(raw, sc, sf, bi.act) : raw;
@@ -1479,7 +1491,7 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s2_f32_kernel(const float* __re
   if (bo.on) {
     const double d1 = wave_sum_d((double)t1), d2 = wave_sum_d((double)t2);
     if (lane == 0) {
-      double* o = bo.ws + ((size_t)ch * (NC / C) + plane / C) * 2;
+      double* o = bo.ws + ((size_t)ch * nparts + pidx) * 2;
       o[0] = d1;
       o[1] = d2;
     }
@@ -1499,6 +1511,26 @@ __global__ __launch_bounds__(256) void dw3x3_wgrad_final_kernel(const float* __r
   if (nl == 0 && i < C * 9) G[i] += s;
 }
 
+// The register-window kernels give a plane to one wavefront, or to several (each a band of
+// rows) while there are too few planes to fill the chip; every wavefront leaves its own partial
+// sums, so a channel has dw3x3_parts() partials instead of N.
+static bool dw_regwin(int H, int W, int stride) {
+  return W % 4 == 0 && W <= 256 && (stride == 1 || (stride == 2 && H % 2 == 0));
+}
+static DwBands dw_bands(int N, int C, int H, int W, int stride) {
+  DwBands b{1, stride == 1 ? H : H / 2};
+  if (!dw_regwin(H, W, stride)) return b;
+  const int rows = b.rpb, groups = 64 / (W / 4);
+  const long want = (4096 + (long)N * C - 1) / ((long)N * C);  // wavefronts wanted per plane
+  const int cap = rows / (2 * groups) > 1 ? rows / (2 * groups) : 1;  // at least two rows per lane group
+  int bands = (int)(want < cap ? want : cap);
+  if (bands < 1) bands = 1;
+  b.rpb = cdiv(rows, bands);
+  b.bands = cdiv(rows, b.rpb);
+  return b;
+}
+int dw3x3_parts(int N, int C, int H, int W, int stride) { return N * dw_bands(N, C, H, W, stride).bands; }
+
 static DwGeom dw_geom(int N, int C, int H, int W, int stride) {
   DwGeom gm;
   gm.C = C; gm.H = H; gm.W = W; gm.stride = stride;
@@ -1513,21 +1545,17 @@ void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int
   DwBnIn bi{};
   if (bn_in) bi = *bn_in;
   DwBnOut bo{stats_out, stats_out != nullptr};
-  if (stride == 1 && W % 4 == 0 && W <= 256) {
+  if (dw_regwin(H, W, stride)) {
+    const DwBands bd = dw_bands(N, C, H, W, stride);
     const int groups = 64 / (W / 4);
-    const int rpg = cdiv(H, groups);
-    if (rpg <= 4)  // short row groups: every row of a lane is requested up front
-      KLAUNCH(dw3x3_fwd_s1_f32_kernel<4>, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg,
-              bi, bo);
+    const int rpg = cdiv(bd.rpb, groups);
+    const dim3 grid(cdiv((long)N * C * bd.bands, 4));
+    if (stride == 2)
+      KLAUNCH(dw3x3_fwd_s2_f32_kernel, grid, dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg, bd, bi, bo);
+    else if (rpg <= 4)  // short row groups: every row of a lane is requested up front
+      KLAUNCH(dw3x3_fwd_s1_f32_kernel<4>, grid, dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg, bd, bi, bo);
     else
-      KLAUNCH(dw3x3_fwd_s1_f32_kernel<2>, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg,
-              bi, bo);
-    return;
-  }
-  if (stride == 2 && W % 4 == 0 && H % 2 == 0 && W <= 256) {
-    const int groups = 64 / (W / 4);
-    KLAUNCH(dw3x3_fwd_s2_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, x, w, y, N * C, C, H, W,
-            cdiv(H / 2, groups), bi, bo);
+      KLAUNCH(dw3x3_fwd_s1_f32_kernel<2>, grid, dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg, bd, bi, bo);
     return;
   }
   DwGeom gm = dw_geom(N, C, H, W, stride);
@@ -1536,25 +1564,25 @@ void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int
   (void)hipFuncSetAttribute((const void*)dw3x3_fwd_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   KLAUNCH(dw3x3_fwd_f32_kernel, dim3(cdiv(gm.NC, gm.ppb)), dim3(256), lds, st, x, w, y, gm, bi, bo);
 }
-size_t dw3x3_bwd_f32_ws(int N, int C) { return (size_t)N * C * 9; }
+size_t dw3x3_bwd_f32_ws(int N, int C, int H, int W, int stride) {
+  return (size_t)dw3x3_parts(N, C, H, W, stride) * C * 9;
+}
 void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part,
                    float* G, int N, int C, int H, int W, int stride, const DwBwdFuse* fuse) {
   DwBwdFuse f;
   if (fuse) f = *fuse;
   if (!dx || !f.xss) f.ws_in = nullptr;  // those sums need dx and the normalised input
-  if (stride == 1 && W % 4 == 0 && W <= 256) {
+  if (dw_regwin(H, W, stride)) {
+    const DwBands bd = dw_bands(N, C, H, W, stride);
     const int groups = 64 / (W / 4);
-    // two rows ahead: four cost a wavefront of occupancy (three tensors per row) and measured slower
-    KLAUNCH(dw3x3_bwd_s1_f32_kernel<2>, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
-            cdiv(H, groups), f);
-    if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
-    return;
-  }
-  if (stride == 2 && W % 4 == 0 && H % 2 == 0 && W <= 256) {
-    const int groups = 64 / (W / 4);
-    KLAUNCH(dw3x3_bwd_s2_f32_kernel, dim3(cdiv((long)N * C, 4)), dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W,
-            cdiv(H / 2, groups), f);
-    if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N, C);
+    const int rpg = cdiv(bd.rpb, groups);
+    const dim3 grid(cdiv((long)N * C * bd.bands, 4));
+    // stride 1: two rows ahead; four cost a wavefront of occupancy (three tensors per row) and measured slower
+    if (stride == 1)
+      KLAUNCH(dw3x3_bwd_s1_f32_kernel<2>, grid, dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W, rpg, bd, f);
+    else
+      KLAUNCH(dw3x3_bwd_s2_f32_kernel, grid, dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W, rpg, bd, f);
+    if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N * bd.bands, C);
     return;
   }
   DwGeom gm = dw_geom(N, C, H, W, stride);

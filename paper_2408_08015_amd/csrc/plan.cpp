@@ -304,11 +304,14 @@ ast_status build_plan(Stage& s, std::string& err) {
     for (size_t j = 0; fuse && j < s.ops.size(); ++j) {
       Op& dw = s.ops[j];
       if (dw.kind != OP_CONV_DW) continue;
+      const Act& DI = s.acts[dw.in];
+      const int dparts = dw3x3_parts(DI.n, DI.c, DI.h, DI.w, dw.stride);  // partial sums per channel it leaves
       if (j > 0 && (fuse & 1)) {
         Op& bn = s.ops[j - 1];
         if (bn.kind == OP_BN && bn.out == dw.in && bn.skip < 0) {
           bn.bn_lazy = true;
           bn.bn_bwd_sums_given = (fuse & 2) != 0;
+          bn.given_bwd_parts = dparts;
           dw.bn_in_op = (int)j - 1;
           virtual_act[bn.out] = 1;
           for (int& la : s.layer_act)
@@ -320,6 +323,7 @@ ast_status build_plan(Stage& s, std::string& err) {
         if (bn.kind == OP_BN && bn.in == dw.out) {
           if (fuse & 1) {
             bn.bn_stats_given = true;
+            bn.given_parts = dparts;
             dw.bn_out_op = (int)j + 1;
           }
           if (fuse & 4) {
@@ -372,12 +376,13 @@ ast_status build_plan(Stage& s, std::string& err) {
     size_t need = 0;
     switch (op.kind) {
       case OP_CONV_PW: need = pw_wgrad_f32_ws(I.n, op.cin, op.cout, I.h * I.w) * sizeof(float); break;
-      case OP_CONV_DW: need = dw3x3_bwd_f32_ws(I.n, I.c) * sizeof(float); break;
+      case OP_CONV_DW: need = dw3x3_bwd_f32_ws(I.n, I.c, I.h, I.w, op.stride) * sizeof(float); break;
       case OP_CONV_DIRECT:
         need = conv_direct_wgrad_ws(I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride, op.pad, op.groups) * sizeof(float);
         break;
       case OP_BN:
-        need = std::max(bn_ws_doubles(I.c, I.n, I.h * I.w), (size_t)2 * I.c * I.n) * sizeof(double);
+        need = std::max(bn_ws_doubles(I.c, I.n, I.h * I.w),
+                        (size_t)2 * I.c * std::max(op.given_parts, op.given_bwd_parts)) * sizeof(double);
         break;
       case OP_CONV_IGEMM:  // masked upstream gradient + split-K partials
         need = align_up(s.acts[op.out].bytes, 256) + conv_bf16_ws_bytes(I.n, I.h, I.w, op.cin, op.cout, op.k);

@@ -73,6 +73,8 @@ struct Op {
   bool bn_bwd_sums_given = false;     // lazy BatchNorm: the conv's backward leaves its backward sums per plane
   bool bn_bwd_apply_fused = false;    // BatchNorm behind a depthwise conv: the conv's backward forms the
                                       // BatchNorm's input gradient on load and adds dgamma, dbeta
+  int given_parts = 0;                // BatchNorm: partial pairs per channel the depthwise conv in front leaves (forward)
+  int given_bwd_parts = 0;            // BatchNorm: ... the depthwise conv behind leaves (backward)
   int bn_in_op = -1;                  // depthwise conv: index of the lazy BatchNorm op in front
   int bn_out_op = -1;                 // depthwise conv: index of the BatchNorm op it writes statistics for
   int bn_bwd_out_op = -1;             // depthwise conv: index of the BatchNorm op whose backward apply it does
