@@ -432,11 +432,16 @@ __device__ __forceinline__ void pw_wgrad_body(const WgArgs& w, int bx, int by, i
       mma(f3);
     }
   } else {
-    for (int p = p0; p < p1; p += 2) {
-      const int pp = p + half;
-      float a = (av && pp < p1) ? ga[pp] : 0.f;
-      float b = (bv && pp < p1) ? xb[pp] : 0.f;
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    for (int p = p0; p < p1; p += 32) {  // sixteen pixel pairs requested before the first MFMA
+      float a[16], b[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int pp = p + 2 * u + half;
+        a[u] = (av && pp < p1) ? ga[pp] : 0.f;
+        b[u] = (bv && pp < p1) ? xb[pp] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc, 0, 0, 0);
     }
   }
 #pragma unroll
@@ -674,6 +679,14 @@ __device__ __forceinline__ void dw_zero(float* dst, int count) {
 // `pre` (w % 4 == 0 only): the first four words of this thread, requested earlier with
 // dw_stage_preload so that their latency overlaps the kernel's prologue.
 struct DwPre { float4 v[4]; };
+struct DwPreS { float v[4]; };  // the same for widths that are not multiples of four (4-byte words)
+__device__ __forceinline__ void dw_stage_preload_s(DwPreS& pre, const float* __restrict__ src, int ne, int t, int tpp) {
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int e = t + u * tpp;
+    pre.v[u] = e < ne ? src[e] : 0.f;
+  }
+}
 __device__ __forceinline__ void dw_stage_preload(DwPre& pre, const float* __restrict__ src, int h, int w, int t,
                                                  int tpp) {
   const int nq = (h * w) >> 2;
@@ -686,7 +699,7 @@ __device__ __forceinline__ void dw_stage_preload(DwPre& pre, const float* __rest
 }
 __device__ __forceinline__ void dw_stage_plane(float* dst, const float* __restrict__ src, int h, int w, int t,
                                                int tpp, float sc = 1.f, float sf = 0.f, int act = -1,
-                                               const DwPre* pre = nullptr) {
+                                               const DwPre* pre = nullptr, const DwPreS* pres = nullptr) {
   const int pw = w + 2;
   if ((w & 3) == 0) {
     const int nq = (h * w) >> 2, qpr = w >> 2;
@@ -721,10 +734,15 @@ __device__ __forceinline__ void dw_stage_plane(float* dst, const float* __restri
     const int ne = h * w;
     for (int e0 = t; e0 < ne; e0 += 4 * tpp) {
       float v[4];
+      if (pres && e0 == t) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        int e = e0 + u * tpp;
-        v[u] = e < ne ? src[e] : 0.f;
+        for (int u = 0; u < 4; ++u) v[u] = pres->v[u];
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          int e = e0 + u * tpp;
+          v[u] = e < ne ? src[e] : 0.f;
+        }
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -755,7 +773,9 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_f32_kernel(const float* __restr
   // the first words of the plane are requested before the prologue and the LDS clear
   const bool vecw = (gm.W & 3) == 0;
   DwPre pre;
+  DwPreS pres;
   if (live && vecw) dw_stage_preload(pre, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
+  if (live && !vecw) dw_stage_preload_s(pres, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H * gm.W, t, tpp);
   if (bi.on) {  // finish the statistics of each plane's channel: one wavefront per plane
     for (int q = threadIdx.x >> 6; q < np; q += 4) {
       const int plane = plane0 + q, c = plane % gm.C;
@@ -770,10 +790,10 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_f32_kernel(const float* __restr
   if (live) {
     if (bi.on)
       dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp, scoef[2 * pl],
-                     scoef[2 * pl + 1], bi.act, vecw ? &pre : nullptr);
+                     scoef[2 * pl + 1], bi.act, vecw ? &pre : nullptr, vecw ? nullptr : &pres);
     else
       dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp, 1.f, 0.f, -1,
-                     vecw ? &pre : nullptr);
+                     vecw ? &pre : nullptr, vecw ? nullptr : &pres);
   }
   for (int i = threadIdx.x; i < np * 9; i += 256) sw[i] = w[((plane0 + i / 9) % gm.C) * 9 + i % 9];
   __syncthreads();
@@ -878,6 +898,16 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
   const int tpp = 256 / gm.ppb;
   const int pl = threadIdx.x / tpp, t = threadIdx.x - pl * tpp;
   const bool live = pl < np;
+  // Widths that are not multiples of four (the usual case here): a thread's first four words of
+  // x, g (and y) are requested before the prologue and the LDS clear; the thread that stages
+  // element e also computes dx[e], so x is not read again for the sums of the BatchNorm in front.
+  const bool vecw = (gm.W & 3) == 0, vecg = (gm.Wo & 3) == 0;
+  DwPreS xpre{}, gpre{}, ypre{};
+  if (live && !vecw) dw_stage_preload_s(xpre, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H * gm.W, t, tpp);
+  if (live && (f.y || !vecg)) {
+    dw_stage_preload_s(gpre, g + (size_t)(plane0 + pl) * gm.Ho * gm.Wo, gm.Ho * gm.Wo, t, tpp);
+    if (f.y) dw_stage_preload_s(ypre, f.y + (size_t)(plane0 + pl) * gm.Ho * gm.Wo, gm.Ho * gm.Wo, t, tpp);
+  }
   if (f.y) {  // one wavefront per plane finishes the sums of the BatchNorm behind the conv
     for (int q = threadIdx.x >> 6; q < np; q += 4) {
       const DwBnBwd b = dw_bn_bwd_coef(f, (plane0 + q) % gm.C, gm.C, plane0 + q < gm.C);
@@ -893,9 +923,10 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
   if (live) {
     if (f.xss)  // x is the input of a BatchNorm(+activation) whose output the convolution saw
       dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp, f.xss[ch],
-                     f.xss[gm.C + ch], f.xact);
+                     f.xss[gm.C + ch], f.xact, nullptr, vecw ? nullptr : &xpre);
     else
-      dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp);
+      dw_stage_plane(sx + pl * PSZ, x + (size_t)(plane0 + pl) * gm.H * gm.W, gm.H, gm.W, t, tpp, 1.f, 0.f, -1, nullptr,
+                     vecw ? nullptr : &xpre);
     if (f.y) {  // the conv's upstream gradient = input gradient of the BatchNorm behind it
       DwBnBwd b;
       b.k = scoef[3 * pl]; b.m1 = scoef[3 * pl + 1]; b.m2 = scoef[3 * pl + 2];
@@ -903,12 +934,32 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
       const float* gsrc = g + (size_t)(plane0 + pl) * gm.Ho * gm.Wo;
       const float* ysrc = f.y + (size_t)(plane0 + pl) * gm.Ho * gm.Wo;
       float* dst = sg + pl * GSZ;
-      for (int e = t; e < gm.Ho * gm.Wo; e += tpp) {
-        const int i = e / gm.Wo, jj = e - i * gm.Wo;
-        dst[(i + 1) * GW + jj + 1] = dw_bn_dx(gsrc[e], ysrc[e], b);
+      const int ne = gm.Ho * gm.Wo;
+      for (int e0 = t; e0 < ne; e0 += 4 * tpp) {
+        float gv[4], yv[4];
+        if (e0 == t) {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) { gv[u] = gpre.v[u]; yv[u] = ypre.v[u]; }
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * tpp;
+            gv[u] = e < ne ? gsrc[e] : 0.f;
+            yv[u] = e < ne ? ysrc[e] : 0.f;
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int e = e0 + u * tpp;
+          if (e < ne) {
+            const int i = e / gm.Wo, jj = e - i * gm.Wo;
+            dst[(i + 1) * GW + jj + 1] = dw_bn_dx(gv[u], yv[u], b);
+          }
+        }
       }
     } else {
-      dw_stage_plane(sg + pl * GSZ, g + (size_t)(plane0 + pl) * gm.Ho * gm.Wo, gm.Ho, gm.Wo, t, tpp);
+      dw_stage_plane(sg + pl * GSZ, g + (size_t)(plane0 + pl) * gm.Ho * gm.Wo, gm.Ho, gm.Wo, t, tpp, 1.f, 0.f, -1, nullptr,
+                     vecg ? nullptr : &gpre);
     }
   }
   for (int i = threadIdx.x; i < np * 9; i += 256) sw[i] = w[((plane0 + i / 9) % gm.C) * 9 + i % 9];
@@ -925,7 +976,7 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
       float* dp = dx + (size_t)(plane0 + pl) * gm.H * gm.W;
       const float* xraw = x + (size_t)(plane0 + pl) * gm.H * gm.W;
       const float mean1 = f.ws_in ? f.xstat[ch] : 0.f, istd1 = f.ws_in ? f.xstat[gm.C + ch] : 0.f;
-      for (int e = t; e < gm.H * gm.W; e += tpp) {
+      auto dx_at = [&](int e, float raw) {
         int i = e / gm.W, j = e - i * gm.W;
         float v = 0.f;
 #pragma unroll
@@ -945,9 +996,19 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
         if (f.ws_in) {  // backward sums of the BatchNorm in front: g' = dx*act'(.), g'*xhat
           const float gmk = v * act_mask(xp[(i + 1) * PW + j + 1], f.xact);
           acc[9] += gmk;
-          acc[10] += gmk * ((xraw[e] - mean1) * istd1);
+          acc[10] += gmk * ((raw - mean1) * istd1);
         }
+      };
+      const int ne = gm.H * gm.W;
+      int e = t;
+      if (!vecw) {  // the first four elements of this thread: x is still in registers
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (t + u * tpp < ne) dx_at(t + u * tpp, xpre.v[u]);
+        }
+        e = t + 4 * tpp;
       }
+      for (; e < ne; e += tpp) dx_at(e, f.ws_in ? xraw[e] : 0.f);
     }
     for (int o = t; o < gm.Ho * gm.Wo; o += tpp) {
       int i = o / gm.Wo, j = o - i * gm.Wo;
