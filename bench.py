@@ -28,6 +28,17 @@ def _cdiv(a, b):
     return -(-a // b)
 
 
+def _dw_vw(h, w, stride):
+    """Strip width (pixels per lane) of the depthwise register-window kernels; 0 = LDS kernels."""
+    if stride == 2 and (h % 2 or w % 2):
+        return 0
+    if w % 4 == 0 and w // 4 <= 64:
+        return 4
+    if w % 2 == 0 and w // 2 <= 64:
+        return 2
+    return 1 if (stride == 1 and w <= 64) else 0
+
+
 def kernel_model(cfg):
     """Algorithmic work of the kernel classes that can dominate a workload, from the layer list
     and the launch rules of the library (one entry per launch of one micro-batch):
@@ -86,14 +97,14 @@ def kernel_model(cfg):
                 out.setdefault(wg_name, []).append(4 * (cin + cout) * nq)                   # g and x in
         if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"]:
             oc, oh, ow = oshape
-            if shape[2] % 4 == 0 and (L["stride"] == 1 or shape[1] % 2 == 0):
+            if _dw_vw(shape[1], shape[2], L["stride"]):
                 name = "dw3x3_fwd_s%d_f32_kernel" % L["stride"]
             else:
                 name = "dw3x3_fwd_f32_kernel"
             out.setdefault(name, []).append(4 * B * (shape[0] * shape[1] * shape[2] + oc * oh * ow))
         if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"]:
             c, h, w = shape
-            if w % 4 == 0 and (L["stride"] == 1 or h % 2 == 0):
+            if _dw_vw(h, w, L["stride"]):
                 oc, oh, ow = oshape
                 name = "dw3x3_bwd_s%d_f32_kernel" % L["stride"]
                 # g, x in; dx out; with a BatchNorm behind also the conv output (that BatchNorm's input)

@@ -1058,33 +1058,74 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
   }
 }
 
-// Stride-1 backward without LDS (W % 4 == 0, W <= 256): one wavefront per (n, c) plane.
-// Lane (s = l % SW, rg = l / SW) owns the four-pixel column strip s (SW = W/4 strips per row)
-// of the rows of row group rg and slides a three-row register window of g and x down them;
-// the columns left and right of a strip come from the neighbouring lanes, zeros at the
-// image border.  Per row a lane issues one 16-byte load of g and of x (one row ahead of
-// use) and one 16-byte store of dx; the nine weight-gradient sums stay in registers and
-// are reduced over the wavefront at the end.
-__device__ __forceinline__ float4 dw_norm4(float4 v, float sc, float sf, int act) {
-  v.x = apply_act(v.x * sc + sf, act); v.y = apply_act(v.y * sc + sf, act);
-  v.z = apply_act(v.z * sc + sf, act); v.w = apply_act(v.w * sc + sf, act);
-  return v;
-}
-struct DwRow { float v[6]; };  // v[0] = column 4s-1, v[1..4] = the strip, v[5] = column 4s+4
-__device__ __forceinline__ DwRow dw_make_row(float4 c, int s, int SW) {
-  DwRow r;
-  const float left = __shfl_up(c.w, 1, 64), right = __shfl_down(c.x, 1, 64);
-  r.v[0] = s == 0 ? 0.f : left;
-  r.v[1] = c.x; r.v[2] = c.y; r.v[3] = c.z; r.v[4] = c.w;
-  r.v[5] = s == SW - 1 ? 0.f : right;
+// ============================================================== depthwise, register windows
+// Kernels without LDS for widths that are a multiple of the strip width VW (4, 2 or 1 pixels:
+// 16-, 8- or 4-byte accesses) with at most 64 strips per row: one wavefront per (n, c) plane
+// (or per band of rows of a plane).  Lane (s = l % SW, rg = l / SW) owns the VW-pixel column
+// strip s (SW = W/VW strips per row) of the rows of row group rg and slides a three-row
+// register window down them; the columns left and right of a strip come from the neighbouring
+// lanes, zeros at the image border.  Rows travel as raw words (zeros where not readable), some
+// steps ahead, and are only transformed when they enter the window, so a load is not waited
+// for before the rows ahead of it are used up.  Sums stay in registers and are reduced over
+// the wavefront at the end.
+template <int VW> struct DwVec { float e[VW]; };
+template <int VW>
+__device__ __forceinline__ DwVec<VW> dw_zero_vec() {
+  DwVec<VW> r;
+#pragma unroll
+  for (int j = 0; j < VW; ++j) r.e[j] = 0.f;
   return r;
 }
-template <int D>  // rows requested ahead of the window (2, or 4 for short row groups)
+template <int VW>
+__device__ __forceinline__ DwVec<VW> dw_ldv(const float* __restrict__ p) {
+  DwVec<VW> r;
+  if constexpr (VW == 4) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    r.e[0] = t.x; r.e[1] = t.y; r.e[2] = t.z; r.e[3] = t.w;
+  } else if constexpr (VW == 2) {
+    const float2 t = *reinterpret_cast<const float2*>(p);
+    r.e[0] = t.x; r.e[1] = t.y;
+  } else {
+    r.e[0] = *p;
+  }
+  return r;
+}
+template <int VW>
+__device__ __forceinline__ void dw_stv(float* __restrict__ p, const DwVec<VW>& v) {
+  if constexpr (VW == 4) *reinterpret_cast<float4*>(p) = make_float4(v.e[0], v.e[1], v.e[2], v.e[3]);
+  else if constexpr (VW == 2) *reinterpret_cast<float2*>(p) = make_float2(v.e[0], v.e[1]);
+  else *p = v.e[0];
+}
+template <int VW>
+__device__ __forceinline__ DwVec<VW> dw_norm(DwVec<VW> v, float sc, float sf, int act) {
+#pragma unroll
+  for (int j = 0; j < VW; ++j) v.e[j] = apply_act(v.e[j] * sc + sf, act);
+  return v;
+}
+// a row of the window: v[0] = the column left of the strip, v[1..VW] = the strip, v[VW+1] = the
+// column right of it
+template <int VW> struct DwRow { float v[VW + 2]; };
+template <int VW>
+__device__ __forceinline__ DwRow<VW> dw_make_row(const DwVec<VW>& c, int s, int SW) {
+  DwRow<VW> r;
+  const float left = __shfl_up(c.e[VW - 1], 1, 64), right = __shfl_down(c.e[0], 1, 64);
+  r.v[0] = s == 0 ? 0.f : left;
+#pragma unroll
+  for (int j = 0; j < VW; ++j) r.v[j + 1] = c.e[j];
+  r.v[VW + 1] = s == SW - 1 ? 0.f : right;
+  return r;
+}
+
+// Stride-1 backward: per row a lane issues one load of g, of x (and of y with a BatchNorm behind)
+// and one store of dx.  D = rows requested ahead of the window.
+template <int VW, int D>
 __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __restrict__ g,
                                                                const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ dx,
                                                                float* __restrict__ part, int NC, int C, int H,
                                                                int W, int RPG, DwBands bd, DwBwdFuse f) {
+  typedef DwVec<VW> Vec;
+  typedef DwRow<VW> Row;
   const int lane = threadIdx.x & 63;
   const int pb = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (pb >= NC * bd.bands) return;  // whole wavefront
@@ -1092,41 +1133,38 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
   const int b0 = band * bd.rpb, b1 = min(b0 + bd.rpb, H);  // this wavefront's rows of the plane
   const int ch = plane % C;
   const int pidx = (plane / C) * bd.bands + band, nparts = (NC / C) * bd.bands;  // partial index, partials per channel
-  const int SW = W >> 2;
+  const int SW = W / VW;
   const int rg = lane / SW, s = lane - rg * SW;
   const int r0 = b0 + rg * RPG;
   const int r1 = min(r0 + RPG, b1);  // lanes past the last group: r0 >= b1, no rows
-  const float* gp = g + (size_t)plane * H * W + 4 * s;
-  const float* xp = x + (size_t)plane * H * W + 4 * s;
-  const float* yp = f.y ? f.y + (size_t)plane * H * W + 4 * s : nullptr;
-  float* dp = dx ? dx + (size_t)plane * H * W + 4 * s : nullptr;
+  const float* gp = g + (size_t)plane * H * W + VW * s;
+  const float* xp = x + (size_t)plane * H * W + VW * s;
+  const float* yp = f.y ? f.y + (size_t)plane * H * W + VW * s : nullptr;
+  float* dp = dx ? dx + (size_t)plane * H * W + VW * s : nullptr;
   float wk[9];
   const float* wc = w + (size_t)ch * 9;
 #pragma unroll
   for (int k = 0; k < 9; ++k) wk[k] = wc[k];
   DwBnBwd yb{};
-  const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   // a row is readable by this lane if it lies in the image and the lane has rows at all
   const bool has = r0 < b1;
   auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
-  // Rows travel as raw words (zeros where not readable) and are only transformed when they
-  // enter the window, so a load is not waited for before the rows ahead of it are used up.
-  struct Pend { float4 g, y, x; };
+  struct Pend { Vec g, y, x; };
   auto load_row = [&](int row, bool ok) -> Pend {
     Pend q;
-    q.g = q.y = q.x = z4;
+    q.g = q.y = q.x = dw_zero_vec<VW>();
     if (rowok(row, ok)) {
-      q.g = *reinterpret_cast<const float4*>(gp + (size_t)row * W);
-      if (f.y) q.y = *reinterpret_cast<const float4*>(yp + (size_t)row * W);
-      q.x = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
+      q.g = dw_ldv<VW>(gp + (size_t)row * W);
+      if (f.y) q.y = dw_ldv<VW>(yp + (size_t)row * W);
+      q.x = dw_ldv<VW>(xp + (size_t)row * W);
     }
     return q;
   };
-  auto use_g = [&](const Pend& q, bool valid) -> float4 {
-    float4 gv = q.g;
+  auto use_g = [&](const Pend& q, bool valid) -> Vec {
+    Vec gv = q.g;
     if (f.y && valid) {  // input gradient of the BatchNorm behind the conv
-      gv.x = dw_bn_dx(gv.x, q.y.x, yb); gv.y = dw_bn_dx(gv.y, q.y.y, yb);
-      gv.z = dw_bn_dx(gv.z, q.y.z, yb); gv.w = dw_bn_dx(gv.w, q.y.w, yb);
+#pragma unroll
+      for (int j = 0; j < VW; ++j) gv.e[j] = dw_bn_dx(gv.e[j], q.y.e[j], yb);
     }
     return gv;
   };
@@ -1134,8 +1172,8 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
   // kept); the padding around it stays zero
   const float xsc = f.xss ? f.xss[ch] : 1.f, xsf = f.xss ? f.xss[C + ch] : 0.f;
   const float mean1 = f.ws_in ? f.xstat[ch] : 0.f, istd1 = f.ws_in ? f.xstat[C + ch] : 0.f;
-  auto use_x = [&](const Pend& q, bool valid) -> float4 {
-    return (f.xss && valid) ? dw_norm4(q.x, xsc, xsf, f.xact) : q.x;
+  auto use_x = [&](const Pend& q, bool valid) -> Vec {
+    return (f.xss && valid) ? dw_norm<VW>(q.x, xsc, xsf, f.xact) : q.x;
   };
   // the first rows are requested before the BatchNorm sums are finished
   const Pend pm = load_row(r0 - 1, true), pc = load_row(r0, true);
@@ -1144,11 +1182,11 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
 #pragma unroll
   for (int d = 1; d < D; ++d) pn[d] = load_row(r0 + 1 + d, r0 + 1 + d <= r1);
   if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C && band == 0);
-  DwRow gm = dw_make_row(use_g(pm, rowok(r0 - 1, true)), s, SW);
-  DwRow gc = dw_make_row(use_g(pc, rowok(r0, true)), s, SW);
-  DwRow xm = dw_make_row(use_x(pm, rowok(r0 - 1, true)), s, SW);
-  DwRow xc = dw_make_row(use_x(pc, rowok(r0, true)), s, SW);
-  float4 xcr = pc.x;
+  Row gm = dw_make_row<VW>(use_g(pm, rowok(r0 - 1, true)), s, SW);
+  Row gc = dw_make_row<VW>(use_g(pc, rowok(r0, true)), s, SW);
+  Row xm = dw_make_row<VW>(use_x(pm, rowok(r0 - 1, true)), s, SW);
+  Row xc = dw_make_row<VW>(use_x(pc, rowok(r0, true)), s, SW);
+  Vec xcr = pc.x;
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
@@ -1157,16 +1195,16 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
     const int a = r0 + i;
     // past its last row a lane must not see the next group's rows as its own window
     const bool v1 = rowok(a + 1, a + 1 <= r1);
-    const DwRow gq = dw_make_row(use_g(pn[0], v1), s, SW), xq = dw_make_row(use_x(pn[0], v1), s, SW);
-    const float4 xqr = pn[0].x;
+    const Row gq = dw_make_row<VW>(use_g(pn[0], v1), s, SW), xq = dw_make_row<VW>(use_x(pn[0], v1), s, SW);
+    const Vec xqr = pn[0].x;
 #pragma unroll
     for (int d = 0; d + 1 < D; ++d) pn[d] = pn[d + 1];
     pn[D - 1] = load_row(a + 1 + D, a + 1 + D <= r1);
     if (a < r1) {
       if (dp) {
-        float o[4];
+        Vec o;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < VW; ++j) {
           float v = 0.f;
 #pragma unroll
           for (int q = 0; q < 3; ++q) {  // dx[a][b] = sum_{u,q} w[u][q] g[a-u+1][b-q+1]
@@ -1174,21 +1212,20 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
             v += wk[1 * 3 + q] * gc.v[j + 2 - q];
             v += wk[2 * 3 + q] * gm.v[j + 2 - q];
           }
-          o[j] = v;
+          o.e[j] = v;
         }
-        *reinterpret_cast<float4*>(dp + (size_t)a * W) = make_float4(o[0], o[1], o[2], o[3]);
+        dw_stv<VW>(dp + (size_t)a * W, o);
         if (f.ws_in) {  // backward sums of the BatchNorm in front: g' = dx*act'(.), g'*xhat
-          const float raw[4] = {xcr.x, xcr.y, xcr.z, xcr.w};
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float gmk = o[j] * act_mask(xc.v[j + 1], f.xact);
+          for (int j = 0; j < VW; ++j) {
+            const float gmk = o.e[j] * act_mask(xc.v[j + 1], f.xact);
             bs1 += gmk;
-            bs2 += gmk * ((raw[j] - mean1) * istd1);
+            bs2 += gmk * ((xcr.e[j] - mean1) * istd1);
           }
         }
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {  // dW[u][q] += g[a][b] x[a+u-1][b+q-1]
+      for (int j = 0; j < VW; ++j) {  // dW[u][q] += g[a][b] x[a+u-1][b+q-1]
         const float gv = gc.v[j + 1];
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
@@ -1217,113 +1254,122 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s1_f32_kernel(const float* __re
   }
 }
 
-// Stride-2 counterpart (W % 4 == 0, H even): lane (s, rg) owns input columns 4s..4s+3 =
-// output columns 2s, 2s+1, and per step one output row i = two input rows 2i, 2i+1.
+// Stride-2 counterpart (VW = 4 or 2, H even): lane (s, rg) owns input columns VW*s .. VW*s+VW-1
+// = output columns (VW/2)*s .., and per step one output row i = two input rows 2i, 2i+1.
 // y[i][j] = sum_{u,q} w[u][q] x[2i+u-1][2j+q-1], so an even input row/column meets only the
 // centre tap and an odd one the two outer taps of the neighbouring outputs.
-struct DwG2 { float v[3]; };   // output columns 2s, 2s+1, 2s+2
-struct DwX2 { float v[5]; };   // input columns 4s-1 .. 4s+3
-__device__ __forceinline__ DwG2 dw_make_g2(float2 c, int s, int SW) {
-  DwG2 r;
-  const float right = __shfl_down(c.x, 1, 64);
-  r.v[0] = c.x; r.v[1] = c.y;
-  r.v[2] = s == SW - 1 ? 0.f : right;
+template <int VW> struct DwG2 { float v[VW / 2 + 1]; };  // the strip's output columns and the one right of them
+template <int VW> struct DwX2 { float v[VW + 1]; };      // the input column left of the strip, then the strip
+template <int VW>
+__device__ __forceinline__ DwG2<VW> dw_make_g2(const DwVec<VW / 2>& c, int s, int SW) {
+  DwG2<VW> r;
+  const float right = __shfl_down(c.e[0], 1, 64);
+#pragma unroll
+  for (int j = 0; j < VW / 2; ++j) r.v[j] = c.e[j];
+  r.v[VW / 2] = s == SW - 1 ? 0.f : right;
   return r;
 }
-__device__ __forceinline__ DwX2 dw_make_x2(float4 c, int s) {
-  DwX2 r;
-  const float left = __shfl_up(c.w, 1, 64);
+template <int VW>
+__device__ __forceinline__ DwX2<VW> dw_make_x2(const DwVec<VW>& c, int s) {
+  DwX2<VW> r;
+  const float left = __shfl_up(c.e[VW - 1], 1, 64);
   r.v[0] = s == 0 ? 0.f : left;
-  r.v[1] = c.x; r.v[2] = c.y; r.v[3] = c.z; r.v[4] = c.w;
+#pragma unroll
+  for (int j = 0; j < VW; ++j) r.v[j + 1] = c.e[j];
   return r;
 }
-// one input row of dx from the output-gradient rows that reach it through kernel rows wa / wb
-__device__ __forceinline__ float4 dw_dx_row2(const float* wa, const DwG2& ga, const float* wb, const DwG2& gb,
-                                             bool two) {
-  float4 o;
-  o.x = wa[1] * ga.v[0];
-  o.y = wa[0] * ga.v[1] + wa[2] * ga.v[0];
-  o.z = wa[1] * ga.v[1];
-  o.w = wa[0] * ga.v[2] + wa[2] * ga.v[1];
+// one input row of dx from the output-gradient rows that reach it through kernel rows wa / wb:
+// an even input column c meets the centre tap of output column c/2, an odd one the outer taps
+// of output columns (c-1)/2 and (c+1)/2
+template <int VW>
+__device__ __forceinline__ DwVec<VW> dw_dx_row2(const float* wa, const DwG2<VW>& ga, const float* wb,
+                                                const DwG2<VW>& gb, bool two) {
+  DwVec<VW> o;
+#pragma unroll
+  for (int c = 0; c < VW; ++c) {
+    if (c % 2 == 0) o.e[c] = wa[1] * ga.v[c / 2];
+    else o.e[c] = wa[0] * ga.v[(c + 1) / 2] + wa[2] * ga.v[(c - 1) / 2];
+  }
   if (two) {
-    o.x += wb[1] * gb.v[0];
-    o.y += wb[0] * gb.v[1] + wb[2] * gb.v[0];
-    o.z += wb[1] * gb.v[1];
-    o.w += wb[0] * gb.v[2] + wb[2] * gb.v[1];
+#pragma unroll
+    for (int c = 0; c < VW; ++c) {
+      if (c % 2 == 0) o.e[c] += wb[1] * gb.v[c / 2];
+      else o.e[c] += wb[0] * gb.v[(c + 1) / 2] + wb[2] * gb.v[(c - 1) / 2];
+    }
   }
   return o;
 }
+template <int VW>
 __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __restrict__ g,
                                                                const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ dx,
                                                                float* __restrict__ part, int NC, int C, int H,
                                                                int W, int RPG, DwBands bd, DwBwdFuse f) {
+  constexpr int VG = VW / 2;  // output columns per lane
+  typedef DwVec<VW> Vec;
+  typedef DwVec<VG> VecG;
   const int lane = threadIdx.x & 63;
   const int pb = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (pb >= NC * bd.bands) return;  // whole wavefront
   const int plane = pb / bd.bands, band = pb - plane * bd.bands;
   const int ch = plane % C;
   const int pidx = (plane / C) * bd.bands + band, nparts = (NC / C) * bd.bands;  // partial index, partials per channel
-  const int SW = W >> 2, Ho = H >> 1, Wo = W >> 1;
+  const int SW = W / VW, Ho = H >> 1, Wo = W >> 1;
   const int b0 = band * bd.rpb, b1 = min(b0 + bd.rpb, Ho);  // this wavefront's output rows
   const int rg = lane / SW, s = lane - rg * SW;
   const int r0 = b0 + rg * RPG;       // output rows [r0, r1)
   const int r1 = min(r0 + RPG, b1);
   const bool has = r0 < b1;
-  const float* gp = g + (size_t)plane * Ho * Wo + 2 * s;
-  const float* yp = f.y ? f.y + (size_t)plane * Ho * Wo + 2 * s : nullptr;
-  const float* xp = x + (size_t)plane * H * W + 4 * s;
-  float* dp = dx ? dx + (size_t)plane * H * W + 4 * s : nullptr;
+  const float* gp = g + (size_t)plane * Ho * Wo + VG * s;
+  const float* yp = f.y ? f.y + (size_t)plane * Ho * Wo + VG * s : nullptr;
+  const float* xp = x + (size_t)plane * H * W + VW * s;
+  float* dp = dx ? dx + (size_t)plane * H * W + VW * s : nullptr;
   float wk[9];
   const float* wc = w + (size_t)ch * 9;
 #pragma unroll
   for (int k = 0; k < 9; ++k) wk[k] = wc[k];
   DwBnBwd yb{};
-  const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
-  const float2 z2 = make_float2(0.f, 0.f);
   const float xsc = f.xss ? f.xss[ch] : 1.f, xsf = f.xss ? f.xss[C + ch] : 0.f;
   const float mean1 = f.ws_in ? f.xstat[ch] : 0.f, istd1 = f.ws_in ? f.xstat[C + ch] : 0.f;
   auto xok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
   auto gok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < Ho; };
-  // The words of a step (input rows 2i, 2i+1, gradient row i+1) travel raw (zeros where not
-  // readable) and are only transformed when the step uses them, so a load is not waited for
-  // before the step ahead of it is done.
-  struct Pend { float4 x0, x1; float2 g, y; };
+  // the words of a step: input rows 2i, 2i+1, gradient row i+1
+  struct Pend { Vec x0, x1; VecG g, y; };
   auto load_step = [&](int i, bool ok) -> Pend {
     Pend q;
-    q.x0 = q.x1 = z4;
-    q.g = q.y = z2;
-    if (xok(2 * i, ok)) q.x0 = *reinterpret_cast<const float4*>(xp + (size_t)(2 * i) * W);
-    if (xok(2 * i + 1, ok)) q.x1 = *reinterpret_cast<const float4*>(xp + (size_t)(2 * i + 1) * W);
+    q.x0 = q.x1 = dw_zero_vec<VW>();
+    q.g = q.y = dw_zero_vec<VG>();
+    if (xok(2 * i, ok)) q.x0 = dw_ldv<VW>(xp + (size_t)(2 * i) * W);
+    if (xok(2 * i + 1, ok)) q.x1 = dw_ldv<VW>(xp + (size_t)(2 * i + 1) * W);
     if (gok(i + 1, ok)) {
-      q.g = *reinterpret_cast<const float2*>(gp + (size_t)(i + 1) * Wo);
-      if (f.y) q.y = *reinterpret_cast<const float2*>(yp + (size_t)(i + 1) * Wo);
+      q.g = dw_ldv<VG>(gp + (size_t)(i + 1) * Wo);
+      if (f.y) q.y = dw_ldv<VG>(yp + (size_t)(i + 1) * Wo);
     }
     return q;
   };
-  auto use_g = [&](float2 gv, const float2& yv, bool valid) -> float2 {
+  auto use_g = [&](VecG gv, const VecG& yv, bool valid) -> VecG {
     if (f.y && valid) {  // input gradient of the BatchNorm behind the conv
-      gv.x = dw_bn_dx(gv.x, yv.x, yb);
-      gv.y = dw_bn_dx(gv.y, yv.y, yb);
+#pragma unroll
+      for (int j = 0; j < VG; ++j) gv.e[j] = dw_bn_dx(gv.e[j], yv.e[j], yb);
     }
     return gv;
   };
   // with xss: the BatchNorm(+activation) output the convolution saw; the padding stays zero
-  auto use_x = [&](const float4& raw, bool valid) -> float4 {
-    return (f.xss && valid) ? dw_norm4(raw, xsc, xsf, f.xact) : raw;
+  auto use_x = [&](const Vec& raw, bool valid) -> Vec {
+    return (f.xss && valid) ? dw_norm<VW>(raw, xsc, xsf, f.xact) : raw;
   };
   // the first rows are requested before the BatchNorm sums are finished
-  float4 xm_raw = z4;
-  float2 gc_raw = z2, yc_raw = z2;
-  if (xok(2 * r0 - 1, true)) xm_raw = *reinterpret_cast<const float4*>(xp + (size_t)(2 * r0 - 1) * W);
+  Vec xm_raw = dw_zero_vec<VW>();
+  VecG gc_raw = dw_zero_vec<VG>(), yc_raw = dw_zero_vec<VG>();
+  if (xok(2 * r0 - 1, true)) xm_raw = dw_ldv<VW>(xp + (size_t)(2 * r0 - 1) * W);
   if (gok(r0, true)) {
-    gc_raw = *reinterpret_cast<const float2*>(gp + (size_t)r0 * Wo);
-    if (f.y) yc_raw = *reinterpret_cast<const float2*>(yp + (size_t)r0 * Wo);
+    gc_raw = dw_ldv<VG>(gp + (size_t)r0 * Wo);
+    if (f.y) yc_raw = dw_ldv<VG>(yp + (size_t)r0 * Wo);
   }
   Pend p1 = load_step(r0, true), p2 = load_step(r0 + 1, r0 + 1 < r1);
   if (f.y) yb = dw_bn_bwd_coef(f, ch, C, plane < C && band == 0);
-  DwX2 xm = dw_make_x2(use_x(xm_raw, xok(2 * r0 - 1, true)), s);
-  DwG2 gc = dw_make_g2(use_g(gc_raw, yc_raw, gok(r0, true)), s, SW);
+  DwX2<VW> xm = dw_make_x2<VW>(use_x(xm_raw, xok(2 * r0 - 1, true)), s);
+  DwG2<VW> gc = dw_make_g2<VW>(use_g(gc_raw, yc_raw, gok(r0, true)), s, SW);
   float acc[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) acc[k] = 0.f;
@@ -1331,32 +1377,31 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
   for (int it = 0; it < RPG; ++it) {  // uniform trip count: the lane exchanges need every lane
     const int i = r0 + it;
     const bool ok = it == 0 || i < r1;  // a lane must not see the next group's rows as its own
-    const DwX2 x0 = dw_make_x2(use_x(p1.x0, xok(2 * i, ok)), s), x1 = dw_make_x2(use_x(p1.x1, xok(2 * i + 1, ok)), s);
-    const float4 x0r = p1.x0, x1r = p1.x1;
-    const DwG2 gq = dw_make_g2(use_g(p1.g, p1.y, gok(i + 1, ok)), s, SW);
+    const DwX2<VW> x0 = dw_make_x2<VW>(use_x(p1.x0, xok(2 * i, ok)), s);
+    const DwX2<VW> x1 = dw_make_x2<VW>(use_x(p1.x1, xok(2 * i + 1, ok)), s);
+    const Vec x0r = p1.x0, x1r = p1.x1;
+    const DwG2<VW> gq = dw_make_g2<VW>(use_g(p1.g, p1.y, gok(i + 1, ok)), s, SW);
     p1 = p2;
     p2 = load_step(i + 2, i + 2 < r1);
     if (i < r1) {
       if (dp) {
         // input row 2i: centre kernel row of output row i; row 2i+1: kernel row 0 of output
         // row i+1 and kernel row 2 of output row i
-        const float4 d0 = dw_dx_row2(wk + 3, gc, wk + 3, gc, false);
-        const float4 d1 = dw_dx_row2(wk + 0, gq, wk + 6, gc, true);
-        *reinterpret_cast<float4*>(dp + (size_t)(2 * i) * W) = d0;
-        *reinterpret_cast<float4*>(dp + (size_t)(2 * i + 1) * W) = d1;
+        const Vec d0 = dw_dx_row2<VW>(wk + 3, gc, wk + 3, gc, false);
+        const Vec d1 = dw_dx_row2<VW>(wk + 0, gq, wk + 6, gc, true);
+        dw_stv<VW>(dp + (size_t)(2 * i) * W, d0);
+        dw_stv<VW>(dp + (size_t)(2 * i + 1) * W, d1);
         if (f.ws_in) {  // backward sums of the BatchNorm in front: g' = dx*act'(.), g'*xhat
-          const float dd[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
-          const float rr[8] = {x0r.x, x0r.y, x0r.z, x0r.w, x1r.x, x1r.y, x1r.z, x1r.w};
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const float gmk = dd[j] * act_mask(j < 4 ? x0.v[j + 1] : x1.v[j - 3], f.xact);
-            bs1 += gmk;
-            bs2 += gmk * ((rr[j] - mean1) * istd1);
+          for (int j = 0; j < VW; ++j) {
+            const float g0 = d0.e[j] * act_mask(x0.v[j + 1], f.xact), g1 = d1.e[j] * act_mask(x1.v[j + 1], f.xact);
+            bs1 += g0 + g1;
+            bs2 += g0 * ((x0r.e[j] - mean1) * istd1) + g1 * ((x1r.e[j] - mean1) * istd1);
           }
         }
       }
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {  // dW[u][q] += g[i][2s+j] x[2i+u-1][4s+2j+q-1]
+      for (int j = 0; j < VG; ++j) {  // dW[u][q] += g[i][j'] x[2i+u-1][2j'+q-1]
         const float gv = gc.v[j];
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
@@ -1384,17 +1429,16 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_s2_f32_kernel(const float* __re
   }
 }
 
-// Forward without LDS (W % 4 == 0, W <= 256), the same lane layout as the backward kernels above:
-// one wavefront per (n, c) plane, lane (s, rg) owns a four-pixel column strip of the rows of row
-// group rg and slides a three-row register window down them.  Rows travel raw and two steps
-// ahead; with a BatchNorm in front they are normalised when they enter the window (padding
-// stays zero).  One 16-byte load and one 16-byte store (stride 2: two loads, one 8-byte store)
-// per lane and step.
-template <int D>  // rows requested ahead of the window (2, or 4 for short row groups)
+// Forward, the same lane layout: one load and one store per lane and row (stride 2: two loads,
+// one half-width store); with a BatchNorm in front rows are normalised when they enter the
+// window (padding stays zero).
+template <int VW, int D>  // D = rows requested ahead of the window
 __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ y,
                                                                int NC, int C, int H, int W, int RPG, DwBands bd,
                                                                DwBnIn bi, DwBnOut bo) {
+  typedef DwVec<VW> Vec;
+  typedef DwRow<VW> Row;
   const int lane = threadIdx.x & 63;
   const int pb = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (pb >= NC * bd.bands) return;  // whole wavefront
@@ -1402,27 +1446,26 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __re
   const int b0 = band * bd.rpb, b1 = min(b0 + bd.rpb, H);  // this wavefront's rows of the plane
   const int ch = plane % C;
   const int pidx = (plane / C) * bd.bands + band, nparts = (NC / C) * bd.bands;  // partial index, partials per channel
-  const int SW = W >> 2;
+  const int SW = W / VW;
   const int rg = lane / SW, s = lane - rg * SW;
   const int r0 = b0 + rg * RPG;
   const int r1 = min(r0 + RPG, b1);  // lanes past the last group: r0 >= b1, no rows
   const bool has = r0 < b1;
-  const float* xp = x + (size_t)plane * H * W + 4 * s;
-  float* yp = y + (size_t)plane * H * W + 4 * s;
+  const float* xp = x + (size_t)plane * H * W + VW * s;
+  float* yp = y + (size_t)plane * H * W + VW * s;
   float wk[9];
   const float* wc = w + (size_t)ch * 9;
 #pragma unroll
   for (int k = 0; k < 9; ++k) wk[k] = wc[k];
-  const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
-  auto load_row = [&](int row, bool ok) -> float4 {
-    float4 v = z4;
-    if (rowok(row, ok)) v = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
+  auto load_row = [&](int row, bool ok) -> Vec {
+    Vec v = dw_zero_vec<VW>();
+    if (rowok(row, ok)) v = dw_ldv<VW>(xp + (size_t)row * W);
     return v;
   };
   // the first rows are requested before the statistics of the BatchNorm in front are finished
-  const float4 pm = load_row(r0 - 1, true), pc = load_row(r0, true);
-  float4 pn[D];
+  const Vec pm = load_row(r0 - 1, true), pc = load_row(r0, true);
+  Vec pn[D];
   pn[0] = load_row(r0 + 1, true);
 #pragma unroll
   for (int d = 1; d < D; ++d) pn[d] = load_row(r0 + 1 + d, r0 + 1 + d <= r1);
@@ -1433,23 +1476,23 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __re
     bn_coefficients(s1, s2, bi.count, bi.gamma[ch], bi.beta[ch], bi.eps, ch, C, plane < C && band == 0 && lane == 0,
                     bi.stat, bi.ss, bi.running, sc, sf);
   }
-  auto use_x = [&](const float4& raw, bool valid) -> float4 {
-    return (bi.on && valid) ? dw_norm4(raw, sc, sf, bi.act) : raw;
+  auto use_x = [&](const Vec& raw, bool valid) -> Vec {
+    return (bi.on && valid) ? dw_norm<VW>(raw, sc, sf, bi.act) : raw;
   };
-  DwRow xm = dw_make_row(use_x(pm, rowok(r0 - 1, true)), s, SW);
-  DwRow xc = dw_make_row(use_x(pc, rowok(r0, true)), s, SW);
+  Row xm = dw_make_row<VW>(use_x(pm, rowok(r0 - 1, true)), s, SW);
+  Row xc = dw_make_row<VW>(use_x(pc, rowok(r0, true)), s, SW);
   float t1 = 0.f, t2 = 0.f;
   for (int i = 0; i < RPG; ++i) {  // uniform trip count: the lane exchanges need every lane
     const int a = r0 + i;
     // past its last row a lane must not see the next group's rows as its own window
-    const DwRow xq = dw_make_row(use_x(pn[0], rowok(a + 1, a + 1 <= r1)), s, SW);
+    const Row xq = dw_make_row<VW>(use_x(pn[0], rowok(a + 1, a + 1 <= r1)), s, SW);
 #pragma unroll
     for (int d = 0; d + 1 < D; ++d) pn[d] = pn[d + 1];
     pn[D - 1] = load_row(a + 1 + D, a + 1 + D <= r1);
     if (a < r1) {
-      float o[4];
+      Vec o;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {  // y[a][b] = sum_{u,q} w[u][q] x[a+u-1][b+q-1]
+      for (int j = 0; j < VW; ++j) {  // y[a][b] = sum_{u,q} w[u][q] x[a+u-1][b+q-1]
         float v = 0.f;
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
@@ -1457,16 +1500,16 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __re
           v += wk[1 * 3 + q] * xc.v[j + q];
           v += wk[2 * 3 + q] * xq.v[j + q];
         }
-        o[j] = v;
+        o.e[j] = v;
         t1 += v;
         t2 += v * v;
       }
-      *reinterpret_cast<float4*>(yp + (size_t)a * W) = make_float4(o[0], o[1], o[2], o[3]);
+      dw_stv<VW>(yp + (size_t)a * W, o);
     }
     xm = xc;
     xc = xq;
   }
-  if (bo.on) {  // (sum, sum of squares) of the plane for the BatchNorm behind
+  if (bo.on) {  // (sum, sum of squares) of this wavefront's rows for the BatchNorm behind
     const double d1 = wave_sum_d((double)t1), d2 = wave_sum_d((double)t2);
     if (lane == 0) {
       double* o = bo.ws + ((size_t)ch * nparts + pidx) * 2;
@@ -1476,40 +1519,42 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s1_f32_kernel(const float* __re
   }
 }
 
-// stride 2 (H even): per step one output row i = input rows 2i, 2i+1 (row 2i-1 is carried over);
-// lane (s, rg) owns input columns 4s..4s+3 = output columns 2s, 2s+1
+// stride 2 (VW = 4 or 2, H even): per step one output row i = input rows 2i, 2i+1 (row 2i-1 is
+// carried over)
+template <int VW>
 __global__ __launch_bounds__(256) void dw3x3_fwd_s2_f32_kernel(const float* __restrict__ x,
                                                                const float* __restrict__ w, float* __restrict__ y,
                                                                int NC, int C, int H, int W, int RPG, DwBands bd,
                                                                DwBnIn bi, DwBnOut bo) {
+  constexpr int VG = VW / 2;  // output columns per lane
+  typedef DwVec<VW> Vec;
   const int lane = threadIdx.x & 63;
   const int pb = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (pb >= NC * bd.bands) return;  // whole wavefront
   const int plane = pb / bd.bands, band = pb - plane * bd.bands;
   const int ch = plane % C;
   const int pidx = (plane / C) * bd.bands + band, nparts = (NC / C) * bd.bands;  // partial index, partials per channel
-  const int SW = W >> 2, Ho = H >> 1, Wo = W >> 1;
+  const int SW = W / VW, Ho = H >> 1, Wo = W >> 1;
   const int b0 = band * bd.rpb, b1 = min(b0 + bd.rpb, Ho);  // this wavefront's output rows
   const int rg = lane / SW, s = lane - rg * SW;
   const int r0 = b0 + rg * RPG;  // output rows [r0, r1)
   const int r1 = min(r0 + RPG, b1);
   const bool has = r0 < b1;
-  const float* xp = x + (size_t)plane * H * W + 4 * s;
-  float* yp = y + (size_t)plane * Ho * Wo + 2 * s;
+  const float* xp = x + (size_t)plane * H * W + VW * s;
+  float* yp = y + (size_t)plane * Ho * Wo + VG * s;
   float wk[9];
   const float* wc = w + (size_t)ch * 9;
 #pragma unroll
   for (int k = 0; k < 9; ++k) wk[k] = wc[k];
-  const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
   auto rowok = [&](int row, bool ok) -> bool { return ok && has && row >= 0 && row < H; };
-  auto load_row = [&](int row, bool ok) -> float4 {
-    float4 v = z4;
-    if (rowok(row, ok)) v = *reinterpret_cast<const float4*>(xp + (size_t)row * W);
+  auto load_row = [&](int row, bool ok) -> Vec {
+    Vec v = dw_zero_vec<VW>();
+    if (rowok(row, ok)) v = dw_ldv<VW>(xp + (size_t)row * W);
     return v;
   };
-  const float4 pm = load_row(2 * r0 - 1, true);
-  float4 p1a = load_row(2 * r0, true), p1b = load_row(2 * r0 + 1, true);
-  float4 p2a = load_row(2 * r0 + 2, r0 + 1 < r1), p2b = load_row(2 * r0 + 3, r0 + 1 < r1);
+  const Vec pm = load_row(2 * r0 - 1, true);
+  Vec p1a = load_row(2 * r0, true), p1b = load_row(2 * r0 + 1, true);
+  Vec p2a = load_row(2 * r0 + 2, r0 + 1 < r1), p2b = load_row(2 * r0 + 3, r0 + 1 < r1);
   float sc = 1.f, sf = 0.f;
   if (bi.on) {
     double s1, s2;
@@ -1517,23 +1562,24 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s2_f32_kernel(const float* __re
     bn_coefficients(s1, s2, bi.count, bi.gamma[ch], bi.beta[ch], bi.eps, ch, C, plane < C && band == 0 && lane == 0,
                     bi.stat, bi.ss, bi.running, sc, sf);
   }
-  auto use_x = [&](const float4& raw, bool valid) -> float4 {
-    return (bi.on && valid) ? dw_norm4(raw, sc, sf, bi.act) : raw;
+  auto use_x = [&](const Vec& raw, bool valid) -> Vec {
+    return (bi.on && valid) ? dw_norm<VW>(raw, sc, sf, bi.act) : raw;
   };
-  DwX2 xm = dw_make_x2(use_x(pm, rowok(2 * r0 - 1, true)), s);
+  DwX2<VW> xm = dw_make_x2<VW>(use_x(pm, rowok(2 * r0 - 1, true)), s);
   float t1 = 0.f, t2 = 0.f;
   for (int it = 0; it < RPG; ++it) {  // uniform trip count: the lane exchanges need every lane
     const int i = r0 + it;
     const bool ok = it == 0 || i < r1;  // a lane must not see the next group's rows as its own
-    const DwX2 x0 = dw_make_x2(use_x(p1a, rowok(2 * i, ok)), s), x1 = dw_make_x2(use_x(p1b, rowok(2 * i + 1, ok)), s);
+    const DwX2<VW> x0 = dw_make_x2<VW>(use_x(p1a, rowok(2 * i, ok)), s);
+    const DwX2<VW> x1 = dw_make_x2<VW>(use_x(p1b, rowok(2 * i + 1, ok)), s);
     p1a = p2a;
     p1b = p2b;
     p2a = load_row(2 * i + 4, i + 2 < r1);
     p2b = load_row(2 * i + 5, i + 2 < r1);
     if (i < r1) {
-      float o[2];
+      DwVec<VG> o;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {  // y[i][2s+j] = sum_{u,q} w[u][q] x[2i+u-1][4s+2j+q-1]
+      for (int j = 0; j < VG; ++j) {  // y[i][j'] = sum_{u,q} w[u][q] x[2i+u-1][2j'+q-1]
         float v = 0.f;
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
@@ -1541,11 +1587,11 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_s2_f32_kernel(const float* __re
           v += wk[1 * 3 + q] * x0.v[2 * j + q];
           v += wk[2 * 3 + q] * x1.v[2 * j + q];
         }
-        o[j] = v;
+        o.e[j] = v;
         t1 += v;
         t2 += v * v;
       }
-      *reinterpret_cast<float2*>(yp + (size_t)i * Wo) = make_float2(o[0], o[1]);
+      dw_stv<VG>(yp + (size_t)i * Wo, o);
     }
     xm = x1;
   }
@@ -1575,13 +1621,21 @@ __global__ __launch_bounds__(256) void dw3x3_wgrad_final_kernel(const float* __r
 // The register-window kernels give a plane to one wavefront, or to several (each a band of
 // rows) while there are too few planes to fill the chip; every wavefront leaves its own partial
 // sums, so a channel has dw3x3_parts() partials instead of N.
-static bool dw_regwin(int H, int W, int stride) {
-  return W % 4 == 0 && W <= 256 && (stride == 1 || (stride == 2 && H % 2 == 0));
+// strip width of the register-window kernels for a shape: the widest of 4, 2, 1 pixels that
+// divides W with at most 64 strips per row (stride 2: even H and W); 0 = LDS kernels
+static int dw_vw(int H, int W, int stride) {
+  if (stride == 2 && (H % 2 || W % 2)) return 0;
+  if (stride != 1 && stride != 2) return 0;
+  if (W % 4 == 0 && W / 4 <= 64) return 4;
+  if (W % 2 == 0 && W / 2 <= 64) return 2;
+  if (stride == 1 && W <= 64) return 1;
+  return 0;
 }
 static DwBands dw_bands(int N, int C, int H, int W, int stride) {
   DwBands b{1, stride == 1 ? H : H / 2};
-  if (!dw_regwin(H, W, stride)) return b;
-  const int rows = b.rpb, groups = 64 / (W / 4);
+  const int vw = dw_vw(H, W, stride);
+  if (!vw) return b;
+  const int rows = b.rpb, groups = 64 / (W / vw);
   const long want = (4096 + (long)N * C - 1) / ((long)N * C);  // wavefronts wanted per plane
   const int cap = rows / (2 * groups) > 1 ? rows / (2 * groups) : 1;  // at least two rows per lane group
   int bands = (int)(want < cap ? want : cap);
@@ -1606,17 +1660,25 @@ void dw3x3_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int
   DwBnIn bi{};
   if (bn_in) bi = *bn_in;
   DwBnOut bo{stats_out, stats_out != nullptr};
-  if (dw_regwin(H, W, stride)) {
+  if (const int vw = dw_vw(H, W, stride)) {
     const DwBands bd = dw_bands(N, C, H, W, stride);
-    const int groups = 64 / (W / 4);
+    const int groups = 64 / (W / vw);
     const int rpg = cdiv(bd.rpb, groups);
     const dim3 grid(cdiv((long)N * C * bd.bands, 4));
-    if (stride == 2)
-      KLAUNCH(dw3x3_fwd_s2_f32_kernel, grid, dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg, bd, bi, bo);
-    else if (rpg <= 4)  // short row groups: every row of a lane is requested up front
-      KLAUNCH(dw3x3_fwd_s1_f32_kernel<4>, grid, dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg, bd, bi, bo);
-    else
-      KLAUNCH(dw3x3_fwd_s1_f32_kernel<2>, grid, dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg, bd, bi, bo);
+#define DW_FWD(name, kern) KLAUNCH_NAMED(name, kern, grid, dim3(256), 0, st, x, w, y, N * C, C, H, W, rpg, bd, bi, bo)
+    if (stride == 2) {
+      if (vw == 4) DW_FWD("dw3x3_fwd_s2_f32_kernel<w4>", (dw3x3_fwd_s2_f32_kernel<4>));
+      else DW_FWD("dw3x3_fwd_s2_f32_kernel<w2>", (dw3x3_fwd_s2_f32_kernel<2>));
+    } else if (rpg <= 4) {  // short row groups: every row of a lane is requested up front
+      if (vw == 4) DW_FWD("dw3x3_fwd_s1_f32_kernel<w4,4>", (dw3x3_fwd_s1_f32_kernel<4, 4>));
+      else if (vw == 2) DW_FWD("dw3x3_fwd_s1_f32_kernel<w2,4>", (dw3x3_fwd_s1_f32_kernel<2, 4>));
+      else DW_FWD("dw3x3_fwd_s1_f32_kernel<w1,4>", (dw3x3_fwd_s1_f32_kernel<1, 4>));
+    } else {
+      if (vw == 4) DW_FWD("dw3x3_fwd_s1_f32_kernel<w4,2>", (dw3x3_fwd_s1_f32_kernel<4, 2>));
+      else if (vw == 2) DW_FWD("dw3x3_fwd_s1_f32_kernel<w2,2>", (dw3x3_fwd_s1_f32_kernel<2, 2>));
+      else DW_FWD("dw3x3_fwd_s1_f32_kernel<w1,2>", (dw3x3_fwd_s1_f32_kernel<1, 2>));
+    }
+#undef DW_FWD
     return;
   }
   DwGeom gm = dw_geom(N, C, H, W, stride);
@@ -1633,16 +1695,23 @@ void dw3x3_bwd_f32(hipStream_t st, const float* g, const float* x, const float* 
   DwBwdFuse f;
   if (fuse) f = *fuse;
   if (!dx || !f.xss) f.ws_in = nullptr;  // those sums need dx and the normalised input
-  if (dw_regwin(H, W, stride)) {
+  if (const int vw = dw_vw(H, W, stride)) {
     const DwBands bd = dw_bands(N, C, H, W, stride);
-    const int groups = 64 / (W / 4);
+    const int groups = 64 / (W / vw);
     const int rpg = cdiv(bd.rpb, groups);
     const dim3 grid(cdiv((long)N * C * bd.bands, 4));
-    // stride 1: two rows ahead; four cost a wavefront of occupancy (three tensors per row) and measured slower
-    if (stride == 1)
-      KLAUNCH(dw3x3_bwd_s1_f32_kernel<2>, grid, dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W, rpg, bd, f);
-    else
-      KLAUNCH(dw3x3_bwd_s2_f32_kernel, grid, dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W, rpg, bd, f);
+#define DW_BWD(name, kern) KLAUNCH_NAMED(name, kern, grid, dim3(256), 0, st, g, x, w, dx, part, N * C, C, H, W, rpg, bd, f)
+    // stride 1: two rows ahead; four cost a wavefront of occupancy at 16-byte strips (three tensors
+    // per row) and measured slower there; narrow strips have the registers for it
+    if (stride == 1) {
+      if (vw == 4) DW_BWD("dw3x3_bwd_s1_f32_kernel<w4>", (dw3x3_bwd_s1_f32_kernel<4, 2>));
+      else if (vw == 2) DW_BWD("dw3x3_bwd_s1_f32_kernel<w2>", (dw3x3_bwd_s1_f32_kernel<2, 4>));
+      else DW_BWD("dw3x3_bwd_s1_f32_kernel<w1>", (dw3x3_bwd_s1_f32_kernel<1, 4>));
+    } else {
+      if (vw == 4) DW_BWD("dw3x3_bwd_s2_f32_kernel<w4>", (dw3x3_bwd_s2_f32_kernel<4>));
+      else DW_BWD("dw3x3_bwd_s2_f32_kernel<w2>", (dw3x3_bwd_s2_f32_kernel<2>));
+    }
+#undef DW_BWD
     if (G) KLAUNCH(dw3x3_wgrad_final_kernel, dim3(cdiv(C * 9, 32)), dim3(256), 0, st, part, G, N * bd.bands, C);
     return;
   }

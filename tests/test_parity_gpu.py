@@ -85,7 +85,9 @@ def test_pointwise_conv_with_bias(A):
 
 @pytest.mark.parametrize("c,hw,stride,B", [(144, 56, 2, 2), (192, 28, 1, 3), (32, 7, 1, 2), (96, 15, 2, 2), (8, 1, 1, 2), (8, 2, 2, 3),
                                           (40, 56, 1, 2), (18, 12, 1, 3), (5, 4, 1, 2), (6, 112, 1, 1),
-                                          (10, 12, 2, 2), (7, 4, 2, 3), (6, 112, 2, 1)])
+                                          (10, 12, 2, 2), (7, 4, 2, 3), (6, 112, 2, 1),
+                                          # widths 14, 6, 10: two-pixel strips; 7, 5: one-pixel strips; 9 stride 2: LDS kernels
+                                          (12, 14, 1, 3), (12, 14, 2, 2), (9, 6, 1, 2), (6, 10, 2, 2), (20, 5, 1, 3), (5, 9, 2, 2)])
 def test_depthwise_conv(A, c, hw, stride, B):
     check(one([conv(c, c, 3, stride, 1, groups=c)], (c, hw, hw), B=B, name="dw%d" % c))
 
@@ -110,7 +112,10 @@ def test_batchnorm(A, c, hw, B, act):
     (10, 15, 1, 2, "relu"),    # odd width: planes staged through LDS
     (6, 9, 2, 3, None),        # odd width, stride 2, no activation
     (8, 112, 2, 1, "relu6"),   # largest plane of MobileNetV2
-    (12, 7, 1, 4, "relu6"),    # 49-pixel planes, many planes per block
+    (12, 7, 1, 4, "relu6"),    # 49-pixel planes: one-pixel strips
+    (16, 14, 1, 4, "relu6"),   # width 14: two-pixel strips
+    (16, 14, 2, 3, "relu"),    # ... stride 2
+    (6, 66, 1, 1, None),       # 33 two-pixel strips per row: one row group per wavefront, bands
 ])
 @pytest.mark.parametrize("need_dx", [True, False])
 def test_batchnorm_depthwise_batchnorm(A, c, hw, stride, B, act, need_dx):
