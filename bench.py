@@ -114,15 +114,24 @@ def kernel_model(cfg):
             c, h, w = shape
             vec = "<true>" if (h * w) % 4 == 0 else "<false>"
             n_el = B * c * h * w
-            if i not in given_bn:
-                out.setdefault("bn_stats_partial_kernel" + vec, []).append(4 * n_el)
-            if i not in lazy_bn:
-                out.setdefault("bn_apply_kernel" + vec, []).append(8 * n_el)              # (+4 with a fused skip)
-            if i not in lazy_bn:     # else the depthwise conv behind leaves the sums
-                out.setdefault("bn_bwd_partial_kernel" + vec, []).append(8 * n_el)
-            if i not in given_bn:    # else the depthwise conv in front forms the input gradient on load
-                # g and x in, dx out (no dx for a BatchNorm on the stage input when it is not wanted)
-                out.setdefault("bn_bwd_apply_kernel", []).append((12 if (not first or cfg.needs_input_grad) else 8) * B * c * h * w)
+            small = B * h * w <= 8192    # one block per channel, one launch per direction
+            plain = i not in given_bn and i not in lazy_bn
+            bwd_bytes = (12 if (not first or cfg.needs_input_grad) else 8) * n_el
+            if small and plain:
+                out.setdefault("bn_fwd_onepass_kernel", []).append(8 * n_el)               # (+4 with a fused skip)
+            else:
+                if i not in given_bn:
+                    out.setdefault("bn_stats_partial_kernel" + vec, []).append(4 * n_el)
+                if i not in lazy_bn:
+                    out.setdefault("bn_apply_kernel" + vec, []).append(8 * n_el)          # (+4 with a fused skip)
+            if small and plain:
+                out.setdefault("bn_bwd_onepass_kernel", []).append(bwd_bytes)
+            else:
+                if i not in lazy_bn:     # else the depthwise conv behind leaves the sums
+                    out.setdefault("bn_bwd_partial_kernel" + vec, []).append(8 * n_el)
+                if i not in given_bn:    # else the depthwise conv in front forms the input gradient on load
+                    # g and x in, dx out (no dx for a BatchNorm on the stage input when it is not wanted)
+                    out.setdefault("bn_bwd_apply_kernel", []).append(bwd_bytes)
         if k == "conv2d" and cfg.dtype == "bf16":
             cin, cout, kk = L["cin"], L["cout"], L["k"] * L["k"]
             m = B * shape[1] * shape[2]

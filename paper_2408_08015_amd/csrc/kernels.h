@@ -156,6 +156,14 @@ void bn_apply_f32(hipStream_t st, const float* x, const float* gamma, const floa
 void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* scale_shift,
                 const float* gamma, float* dx, float* Ggamma, float* Gbeta, double* ws, int N, int C, int HW,
                 int act);
+// Small tensors (bn_onepass_fits: at most 8192 elements per channel): forward and backward as ONE
+// launch each, one block per channel, no workspace.
+bool bn_onepass_fits(int N, int HW);
+void bn_fwd_onepass_f32(hipStream_t st, const float* x, const float* gamma, const float* beta, const float* skip,
+                        float* y, float* stat, float* scale_shift, float* running, int N, int C, int HW, float eps,
+                        int act);
+void bn_bwd_onepass_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* scale_shift,
+                        const float* gamma, float* dx, float* Ggamma, float* Gbeta, int N, int C, int HW, int act);
 // Its two halves: the partial sums ws[C][bn_parts(N, HW)][2] = (sum g', sum g'*xhat), and the input
 // gradient (+ dgamma, dbeta) from P partial pairs per channel, whoever wrote them.
 void bn_bwd_partial_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* scale_shift,

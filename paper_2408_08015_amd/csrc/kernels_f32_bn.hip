@@ -340,6 +340,139 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
   }
 }
 
+// ---------------------------------------------------------------- small tensors: one pass
+// A channel with at most 8192 elements (N*HW) is handled by ONE block that keeps the channel in
+// registers (eight values per thread): statistics and normalisation, or backward sums and input
+// gradient, in a single launch instead of two, each reading its inputs once.  Element k of thread
+// t is flat index t + k*T of the channel's N planes.
+template <int T>
+__device__ __forceinline__ void block_sum2_t(float f1, float f2, double* sh, double& d1, double& d2) {
+  constexpr int NW = T / 64;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const double a = wave_sum_d((double)f1), b = wave_sum_d((double)f2);
+  if (lane == 0) {
+    sh[w] = a;
+    sh[NW + w] = b;
+  }
+  __syncthreads();
+  d1 = 0.0;
+  d2 = 0.0;
+#pragma unroll
+  for (int k = 0; k < NW; ++k) {  // fixed order, the same in every thread
+    d1 += sh[k];
+    d2 += sh[NW + k];
+  }
+}
+
+template <int T>
+__global__ __launch_bounds__(T) void bn_fwd_onepass_kernel(const float* __restrict__ x,
+                                                           const float* __restrict__ gamma,
+                                                           const float* __restrict__ beta,
+                                                           const float* __restrict__ skip, float* __restrict__ y,
+                                                           float* __restrict__ stat, float* __restrict__ ss,
+                                                           float* __restrict__ running, int N, int C, int HW,
+                                                           float eps, int act) {
+  __shared__ double sh[2 * (T / 64)];
+  const int c = blockIdx.x, E = N * HW;
+  float v[8], kv[8];
+  size_t off[8];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int idx = threadIdx.x + k * T;
+    v[k] = 0.f;
+    kv[k] = 0.f;
+    off[k] = 0;
+    if (idx < E) {
+      const int n = idx / HW, e = idx - n * HW;
+      off[k] = ((size_t)n * C + c) * HW + e;
+      v[k] = x[off[k]];
+      if (skip) kv[k] = skip[off[k]];
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    s1 += v[k];
+    s2 += v[k] * v[k];
+  }
+  double d1, d2;
+  block_sum2_t<T>(s1, s2, sh, d1, d2);
+  float sc, sf;  // every thread computes the same coefficients; thread 0 records them
+  bn_coefficients(d1, d2, (double)E, gamma[c], beta[c], eps, c, C, threadIdx.x == 0, stat, ss, running, sc, sf);
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (threadIdx.x + k * T < E) y[off[k]] = apply_act(v[k] * sc + sf, act) + kv[k];
+}
+
+template <int T>
+__global__ __launch_bounds__(T) void bn_bwd_onepass_kernel(const float* __restrict__ g,
+                                                           const float* __restrict__ x,
+                                                           const float* __restrict__ stat,
+                                                           const float* __restrict__ ss,
+                                                           const float* __restrict__ gamma, float* __restrict__ dx,
+                                                           float* __restrict__ Ggamma, float* __restrict__ Gbeta,
+                                                           int N, int C, int HW, int act) {
+  __shared__ double sh[2 * (T / 64)];
+  const int c = blockIdx.x, E = N * HW;
+  const float mean = stat[c], istd = stat[C + c], sc = ss[c], sf = ss[C + c];
+  float gm[8], xh[8];  // masked upstream gradient, normalised input
+  size_t off[8];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int idx = threadIdx.x + k * T;
+    gm[k] = 0.f;
+    xh[k] = 0.f;
+    off[k] = 0;
+    if (idx < E) {
+      const int n = idx / HW, e = idx - n * HW;
+      off[k] = ((size_t)n * C + c) * HW + e;
+      const float xv = x[off[k]];
+      gm[k] = g[off[k]] * act_mask(xv * sc + sf, act);
+      xh[k] = (xv - mean) * istd;
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    s1 += gm[k];
+    s2 += gm[k] * xh[k];
+  }
+  double d1, d2;
+  block_sum2_t<T>(s1, s2, sh, d1, d2);
+  if (threadIdx.x == 0) {
+    Gbeta[c] += (float)d1;
+    Ggamma[c] += (float)d2;
+  }
+  if (!dx) return;  // the input gradient is not wanted
+  const float kk = gamma[c] * istd, m1 = (float)(d1 / (double)E), m2 = (float)(d2 / (double)E);
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (threadIdx.x + k * T < E) dx[off[k]] = kk * (gm[k] - m1 - xh[k] * m2);
+}
+
+bool bn_onepass_fits(int N, int HW) { return (long)N * HW <= 8192; }
+
+void bn_fwd_onepass_f32(hipStream_t st, const float* x, const float* gamma, const float* beta, const float* skip,
+                        float* y, float* stat, float* scale_shift, float* running, int N, int C, int HW, float eps,
+                        int act) {
+  if ((long)N * HW <= 2048)
+    KLAUNCH_NAMED("bn_fwd_onepass_kernel", (bn_fwd_onepass_kernel<256>), dim3(C), dim3(256), 0, st, x, gamma, beta,
+                  skip, y, stat, scale_shift, running, N, C, HW, eps, act);
+  else
+    KLAUNCH_NAMED("bn_fwd_onepass_kernel", (bn_fwd_onepass_kernel<1024>), dim3(C), dim3(1024), 0, st, x, gamma, beta,
+                  skip, y, stat, scale_shift, running, N, C, HW, eps, act);
+}
+
+void bn_bwd_onepass_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* ss,
+                        const float* gamma, float* dx, float* Ggamma, float* Gbeta, int N, int C, int HW, int act) {
+  if ((long)N * HW <= 2048)
+    KLAUNCH_NAMED("bn_bwd_onepass_kernel", (bn_bwd_onepass_kernel<256>), dim3(C), dim3(256), 0, st, g, x, stat, ss,
+                  gamma, dx, Ggamma, Gbeta, N, C, HW, act);
+  else
+    KLAUNCH_NAMED("bn_bwd_onepass_kernel", (bn_bwd_onepass_kernel<1024>), dim3(C), dim3(1024), 0, st, g, x, stat, ss,
+                  gamma, dx, Ggamma, Gbeta, N, C, HW, act);
+}
+
 void bn_bwd_partial_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* ss,
                         double* ws, int N, int C, int HW, int act) {
   const BnSplit b = bn_split(N, HW);
