@@ -283,10 +283,40 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nv = D / 8;
   float* my = sh + (size_t)wave * 2 * D;
-  for (int i = lane; i < 2 * D; i += 64) my[i] = 0.f;
   const size_t r0 = (size_t)blockIdx.x * rows_per_block;
   const size_t r1 = r0 + rows_per_block < R ? r0 + rows_per_block : R;
+  // A lane owns the same features in every row of its wavefront: dgamma / dbeta stay in
+  // registers until the rows are done.  The words of the next row are requested before this
+  // row is worked on.
+  float dg[LN_MAXV][8], db[LN_MAXV][8], gam[LN_MAXV][8];
+#pragma unroll
+  for (int j = 0; j < LN_MAXV; ++j) {
+    const int vi = lane + 64 * j;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      dg[j][k] = 0.f;
+      db[j][k] = 0.f;
+      gam[j][k] = vi < nv ? gamma[vi * 8 + k] : 0.f;
+    }
+  }
+  struct RowWords { uint4 x[LN_MAXV], g[LN_MAXV], a[LN_MAXV]; };
+  auto load_row = [&](size_t row, RowWords& w) {
+#pragma unroll
+    for (int j = 0; j < LN_MAXV; ++j) {
+      const int vi = lane + 64 * j;
+      w.x[j] = w.g[j] = w.a[j] = make_uint4(0u, 0u, 0u, 0u);
+      if (row < r1 && vi < nv) {
+        w.x[j] = *reinterpret_cast<const uint4*>(x + row * D + vi * 8);
+        w.g[j] = *reinterpret_cast<const uint4*>(g + row * D + vi * 8);
+        if (add && dx) w.a[j] = *reinterpret_cast<const uint4*>(add + row * D + vi * 8);
+      }
+    }
+  };
+  RowWords nxt;
+  load_row(r0 + wave, nxt);
   for (size_t row = r0 + wave; row < r1; row += 4) {
+    const RowWords cur = nxt;
+    load_row(row + 4, nxt);
     const float mean = stat[row], istd = stat[R + row];
     float xh[LN_MAXV][8], gh[LN_MAXV][8];
     float s1 = 0.f, s2 = 0.f;
@@ -295,14 +325,14 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
       int vi = lane + 64 * j;
       if (vi < nv) {
         float gv[8];
-        unpack8(*reinterpret_cast<const uint4*>(x + row * D + vi * 8), xh[j]);
-        unpack8(*reinterpret_cast<const uint4*>(g + row * D + vi * 8), gv);
+        unpack8(cur.x[j], xh[j]);
+        unpack8(cur.g[j], gv);
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           xh[j][k] = (xh[j][k] - mean) * istd;
-          my[vi * 8 + k] += gv[k] * xh[j][k];  // dgamma (this lane owns these features)
-          my[D + vi * 8 + k] += gv[k];         // dbeta
-          gh[j][k] = gv[k] * gamma[vi * 8 + k];
+          dg[j][k] += gv[k] * xh[j][k];  // dgamma (this lane owns these features)
+          db[j][k] += gv[k];             // dbeta
+          gh[j][k] = gv[k] * gam[j][k];
           s1 += gh[j][k];
           s2 += gh[j][k] * xh[j][k];
         }
@@ -320,12 +350,23 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
           for (int k = 0; k < 8; ++k) o[k] = istd * (gh[j][k] - s1 - xh[j][k] * s2);
           if (add) {  // gradient arriving over the residual connection around this LayerNorm
             float av[8];
-            unpack8(*reinterpret_cast<const uint4*>(add + row * D + vi * 8), av);
+            unpack8(cur.a[j], av);
 #pragma unroll
             for (int k = 0; k < 8; ++k) o[k] += av[k];
           }
           *reinterpret_cast<uint4*>(dx + row * D + vi * 8) = pack8(o);
         }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < LN_MAXV; ++j) {
+    const int vi = lane + 64 * j;
+    if (vi < nv) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        my[vi * 8 + k] = dg[j][k];
+        my[D + vi * 8 + k] = db[j][k];
       }
     }
   }
