@@ -175,9 +175,9 @@ def kernel_model(cfg):
 # dominant kernel of each workload (largest share of the kernel time in the rocprofv3 kernel
 # traces under profiles/) and what bounds it
 DOMINANT = {
-    "cfg1": ("pw_conv_f32_pkks_kernel", "hbm"),
+    "cfg1": ("dw3x3_bwd_s1_f32_kernel", "hbm"),
     "cfg2": ("bn_bwd_apply_kernel", "hbm"),
-    "cfg3": ("pw_conv_f32_pkks_kernel", "hbm"),
+    "cfg3": ("pw_conv_f32_pkks_kernel<16>", "hbm"),
     "cfg4": ("gemm_bf16_kernel<128x128,im2col>", "mfma"),
     "cfg5": ("gemm_bf16_kernel<128x128,wgrad_rows>", "mfma"),
 }
@@ -187,8 +187,8 @@ DOMINANT = {
 # what the same counter reads for the library's plain copy kernel of known size
 # (FETCH_SIZE reads 0.501 of the bytes copied, WRITE_SIZE 1.000); see profiles/.
 TRAFFIC_BYTES = {
-    ("cfg2", "bn_bwd_apply_kernel"): int((17545.4 / 0.5012 + 17256.0) * 1024),
-    ("cfg4", "gemm_bf16_kernel<128x128,im2col>"): int((49636.4 / 0.5004 + 45994.7) * 1024),
+    ("cfg2", "bn_bwd_apply_kernel"): int((17501.7 / 0.5012 + 17254.5) * 1024),
+    ("cfg4", "gemm_bf16_kernel<128x128,im2col>"): int((49588.9 / 0.5005 + 45994.7) * 1024),
 }
 
 
