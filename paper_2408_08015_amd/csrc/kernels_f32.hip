@@ -112,25 +112,78 @@ __global__ __launch_bounds__(256) void conv_direct_wgrad_kernel(
   if (threadIdx.x == 0) G[widx] += s;
 }
 
-// Dense 3x3 conv with up to 4 input channels (an RGB stem): block = one output channel x one
-// chunk of the flattened (n, i, j) output positions; every thread keeps all CG*9 sums of its
-// positions, the block adds them and writes one partial per chunk.
+// Dense 3x3 conv (pad 1, any stride) with up to 4 input channels (an RGB stem), forward: a thread
+// owns one output position and eight output channels: its CG*9 inputs are read once into
+// registers, the block's 8 x CG*9 weights sit in LDS (read as broadcasts), the eight results go
+// out as eight coalesced stores.  The generic kernel spends ~400 instructions per output on
+// index arithmetic and bounds checks; this one about 45.
+template <int CG>
+__global__ __launch_bounds__(256) void conv3x3_small_cin_fwd_kernel(const float* __restrict__ x,
+                                                                    const float* __restrict__ w,
+                                                                    const float* __restrict__ bias,
+                                                                    float* __restrict__ y, int H, int W, int Cout,
+                                                                    int Ho, int Wo, int stride) {
+  constexpr int T = CG * 9, OC = 8;
+  __shared__ float sw[OC * T];
+  const int o0 = blockIdx.y * OC, n = blockIdx.z;
+  for (int i = threadIdx.x; i < OC * T; i += 256) {
+    const int oo = i / T;
+    sw[i] = o0 + oo < Cout ? w[(size_t)(o0 + oo) * T + (i - oo * T)] : 0.f;
+  }
+  __syncthreads();
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= Ho * Wo) return;
+  const int i = r / Wo, j = r - i * Wo;
+  const int i0 = i * stride - 1, j0 = j * stride - 1;
+  float xin[T];
+#pragma unroll
+  for (int c = 0; c < CG; ++c) {
+    const float* xc = x + ((size_t)n * CG + c) * H * W;
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+#pragma unroll
+      for (int v = 0; v < 3; ++v) {
+        const int ii = i0 + u, jj = j0 + v;
+        const bool ok = ii >= 0 && ii < H && jj >= 0 && jj < W;
+        xin[(c * 3 + u) * 3 + v] = ok ? xc[(size_t)ii * W + jj] : 0.f;
+      }
+  }
+#pragma unroll
+  for (int oo = 0; oo < OC; ++oo) {
+    if (o0 + oo >= Cout) break;  // uniform
+    float acc = bias ? bias[o0 + oo] : 0.f;
+#pragma unroll
+    for (int k = 0; k < T; ++k) acc += sw[oo * T + k] * xin[k];
+    y[((size_t)n * Cout + o0 + oo) * Ho * Wo + r] = acc;
+  }
+}
+
+// Dense 3x3 conv with up to 4 input channels (an RGB stem), weight gradient: block = four output
+// channels x one chunk of the flattened (n, i, j) output positions; a thread reads the CG*9
+// inputs of a position once and keeps the 4 x CG*9 sums of its positions in registers; the block
+// adds them (wavefront butterflies, then one pass through LDS) and writes one partial per chunk.
 template <int CG>
 __global__ __launch_bounds__(256) void conv3x3_small_cin_wgrad_kernel(
     const float* __restrict__ g, const float* __restrict__ x, float* __restrict__ part, int N, int H, int W,
     int Cout, int Ho, int Wo, int stride, int pad, int per_chunk) {
-  __shared__ float sh[16];
-  const int o = blockIdx.x, chunk = blockIdx.y;
+  constexpr int T = CG * 9, OC = 4;
+  __shared__ float sh[4][OC * T];
+  const int o0 = blockIdx.x * OC, chunk = blockIdx.y;
   const long per = (long)N * Ho * Wo;
   const long e0 = (long)chunk * per_chunk, e1 = min(e0 + per_chunk, per);
-  float acc[CG * 9];
+  float acc[OC][T];
 #pragma unroll
-  for (int k = 0; k < CG * 9; ++k) acc[k] = 0.f;
+  for (int oo = 0; oo < OC; ++oo)
+#pragma unroll
+    for (int k = 0; k < T; ++k) acc[oo][k] = 0.f;
   for (long e = e0 + threadIdx.x; e < e1; e += 256) {
     const int n = (int)(e / ((long)Ho * Wo));
     const int r = (int)(e - (long)n * Ho * Wo);
     const int i = r / Wo, j = r - i * Wo;
-    const float gv = g[((size_t)n * Cout + o) * Ho * Wo + r];
+    float gv[OC];
+#pragma unroll
+    for (int oo = 0; oo < OC; ++oo)
+      gv[oo] = o0 + oo < Cout ? g[((size_t)n * Cout + o0 + oo) * Ho * Wo + r] : 0.f;
     const int i0 = i * stride - pad, j0 = j * stride - pad;
 #pragma unroll
     for (int c = 0; c < CG; ++c) {
@@ -142,22 +195,33 @@ __global__ __launch_bounds__(256) void conv3x3_small_cin_wgrad_kernel(
         for (int v = 0; v < 3; ++v) {
           const int jj = j0 + v;
           const bool ok = ii >= 0 && ii < H && jj >= 0 && jj < W;
-          acc[(c * 3 + u) * 3 + v] += gv * (ok ? xc[(size_t)ii * W + jj] : 0.f);
+          const float xv = ok ? xc[(size_t)ii * W + jj] : 0.f;
+#pragma unroll
+          for (int oo = 0; oo < OC; ++oo) acc[oo][(c * 3 + u) * 3 + v] += gv[oo] * xv;
         }
       }
     }
   }
-  float* out = part + ((size_t)chunk * Cout + o) * (CG * 9);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-  for (int k = 0; k < CG * 9; ++k) {
-    const float s = block_sum<float>(acc[k], sh);
-    if (threadIdx.x == 0) out[k] = s;
+  for (int oo = 0; oo < OC; ++oo)
+#pragma unroll
+    for (int k = 0; k < T; ++k) {
+      const float s = wave_sum(acc[oo][k]);
+      if (lane == 0) sh[wave][oo * T + k] = s;
+    }
+  __syncthreads();
+  for (int q = threadIdx.x; q < OC * T; q += 256) {
+    const int oo = q / T;
+    if (o0 + oo < Cout)
+      part[((size_t)chunk * Cout + o0 + oo) * T + (q - oo * T)] = (sh[0][q] + sh[1][q]) + (sh[2][q] + sh[3][q]);
   }
 }
 
 static int small_cin_chunks(int N, int Ho, int Wo, int Cout) {
   long per = (long)N * Ho * Wo;
-  int want = (int)((1024 + Cout - 1) / Cout);      // about 1024 blocks
+  const int og = (Cout + 3) / 4;                   // blocks per chunk: four output channels each
+  int want = (int)((1024 + og - 1) / og);          // about 1024 blocks
   long cap = (per + 1023) / 1024;                  // at least 1024 positions per block
   if (want > cap) want = (int)cap;
   return want < 1 ? 1 : want;
@@ -174,6 +238,16 @@ void conv_direct_fwd_f32(hipStream_t st, const float* x, const float* w, const f
                          int N, int Cin, int H, int W, int Cout, int k, int stride, int pad,
                          int groups) {
   int Ho = conv_out(H, k, stride, pad), Wo = conv_out(W, k, stride, pad);
+  if (small_cin_case(Cin, k, groups) && pad == 1 && N <= 65535) {
+    dim3 grid(cdiv((long)Ho * Wo, 256), cdiv(Cout, 8), N);
+    switch (Cin) {
+      case 1: KLAUNCH(conv3x3_small_cin_fwd_kernel<1>, grid, dim3(256), 0, st, x, w, bias, y, H, W, Cout, Ho, Wo, stride); break;
+      case 2: KLAUNCH(conv3x3_small_cin_fwd_kernel<2>, grid, dim3(256), 0, st, x, w, bias, y, H, W, Cout, Ho, Wo, stride); break;
+      case 3: KLAUNCH(conv3x3_small_cin_fwd_kernel<3>, grid, dim3(256), 0, st, x, w, bias, y, H, W, Cout, Ho, Wo, stride); break;
+      default: KLAUNCH(conv3x3_small_cin_fwd_kernel<4>, grid, dim3(256), 0, st, x, w, bias, y, H, W, Cout, Ho, Wo, stride); break;
+    }
+    return;
+  }
   size_t total = (size_t)N * Cout * Ho * Wo;
   KLAUNCH(conv_direct_fwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, x, w, bias, y,
                      Cin, H, W, Cout, Ho, Wo, k, stride, pad, groups, total);
@@ -191,7 +265,7 @@ void conv_direct_wgrad_f32(hipStream_t st, const float* g, const float* x, float
   if (ws && small_cin_case(Cin, k, groups)) {
     const int chunks = small_cin_chunks(N, Ho, Wo, Cout);
     const int per_chunk = cdiv((long)N * Ho * Wo, chunks);
-    dim3 grid(Cout, chunks);
+    dim3 grid(cdiv(Cout, 4), chunks);
     switch (Cin) {
       case 1: KLAUNCH(conv3x3_small_cin_wgrad_kernel<1>, grid, dim3(256), 0, st, g, x, ws, N, H, W, Cout, Ho, Wo, stride, pad, per_chunk); break;
       case 2: KLAUNCH(conv3x3_small_cin_wgrad_kernel<2>, grid, dim3(256), 0, st, g, x, ws, N, H, W, Cout, Ho, Wo, stride, pad, per_chunk); break;

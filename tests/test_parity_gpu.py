@@ -95,6 +95,8 @@ def test_depthwise_conv(A, c, hw, stride, B):
 @pytest.mark.parametrize("cin,cout,k,stride,pad,groups,hw", [
     (3, 32, 3, 2, 1, 1, 32),     # MobileNetV2 stem shape
     (8, 12, 3, 1, 1, 2, 9), (4, 4, 5, 1, 2, 4, 8), (6, 6, 3, 2, 0, 1, 9),
+    # the small-Cin 3x3 kernels: 1, 2, 4 input channels, output channels not a multiple of 8 / 4
+    (1, 5, 3, 1, 1, 1, 9), (2, 13, 3, 2, 1, 1, 11), (4, 10, 3, 1, 1, 1, 8), (3, 16, 3, 1, 1, 1, 20),
 ])
 def test_direct_conv(A, cin, cout, k, stride, pad, groups, hw):
     check(one([conv(cin, cout, k, stride, pad, groups, bias=True)], (cin, hw, hw), B=2, name="direct"))
