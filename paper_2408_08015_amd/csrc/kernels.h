@@ -70,6 +70,7 @@ size_t dw3x3_bwd_f32_ws(int N, int C, int H, int W, int stride);
 // Partial sums per channel that the depthwise kernels leave (weight-gradient partials, BatchNorm
 // sums): one per sample, or several where a plane is split into bands of rows over wavefronts.
 int dw3x3_parts(int N, int C, int H, int W, int stride);
+bool dw3x3_supported(int H, int W, int stride);  // else the generic grouped-conv kernels apply
 struct DwBands {
   int bands, rpb;  // bands per plane, rows per band
 };

@@ -1645,6 +1645,14 @@ static DwBands dw_bands(int N, int C, int H, int W, int stride) {
   return b;
 }
 int dw3x3_parts(int N, int C, int H, int W, int stride) { return N * dw_bands(N, C, H, W, stride).bands; }
+// Shapes the depthwise kernels cover: every shape with register windows; otherwise one padded
+// plane of x and of g must fit the LDS kernels' 160 KB
+bool dw3x3_supported(int H, int W, int stride) {
+  if (stride != 1 && stride != 2) return false;
+  if (dw_vw(H, W, stride)) return true;
+  const long Ho = conv_out(H, 3, stride, 1), Wo = conv_out(W, 3, stride, 1);
+  return ((long)(H + 2) * (W + 2) + (Ho + 2) * (Wo + 2) + 64) * 4 <= 150 * 1024;
+}
 
 static DwGeom dw_geom(int N, int C, int H, int W, int stride) {
   DwGeom gm;

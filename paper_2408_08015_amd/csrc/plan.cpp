@@ -83,7 +83,8 @@ ast_status build_plan(Stage& s, std::string& err) {
           if (i + 1 < nl && s.layers[i + 1].kind == AST_RELU) { op.act = 1; ++i; }
         } else if (k == 1 && st == 1 && pad == 0 && g == 1) {
           op.kind = OP_CONV_PW;
-        } else if (k == 3 && pad == 1 && g == Cin && Cin == Cout && (st == 1 || st == 2) && !hb) {
+        } else if (k == 3 && pad == 1 && g == Cin && Cin == Cout && (st == 1 || st == 2) && !hb &&
+                   dw3x3_supported(A.h, A.w, st)) {
           op.kind = OP_CONV_DW;
         } else {
           op.kind = OP_CONV_DIRECT;

@@ -87,7 +87,9 @@ def test_pointwise_conv_with_bias(A):
                                           (40, 56, 1, 2), (18, 12, 1, 3), (5, 4, 1, 2), (6, 112, 1, 1),
                                           (10, 12, 2, 2), (7, 4, 2, 3), (6, 112, 2, 1),
                                           # widths 14, 6, 10: two-pixel strips; 7, 5: one-pixel strips; 9 stride 2: LDS kernels
-                                          (12, 14, 1, 3), (12, 14, 2, 2), (9, 6, 1, 2), (6, 10, 2, 2), (20, 5, 1, 3), (5, 9, 2, 2)])
+                                          (12, 14, 1, 3), (12, 14, 2, 2), (9, 6, 1, 2), (6, 10, 2, 2), (20, 5, 1, 3), (5, 9, 2, 2),
+                                          # planes no depthwise kernel covers (too wide for 64 strips, too big for LDS): generic kernels
+                                          (2, 270, 1, 1), (2, 258, 2, 1)])
 def test_depthwise_conv(A, c, hw, stride, B):
     check(one([conv(c, c, 3, stride, 1, groups=c)], (c, hw, hw), B=B, name="dw%d" % c))
 
