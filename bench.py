@@ -62,6 +62,19 @@ def kernel_model(cfg):
                 lazy_bn.add(i - 2)
             if i + 1 < len(kinds) and kinds[i + 1] == "batchnorm2d":
                 given_bn.add(i + 1)
+    # statistics partials that a pointwise conv (no bias) leaves for the BatchNorm behind it: offered by the
+    # 32- and 128-pixel-wavefront kernels while there are at most 256 pixel blocks
+    stat_bn = set()
+    shp = tuple(cfg.in_shape)
+    for i, L in enumerate(cfg.layers):
+        if L["kind"] == "conv2d" and cfg.dtype == "f32" and L["k"] == 1 and L["groups"] == 1 and not L.get("bias", False) \
+                and i + 1 < len(kinds) and kinds[i + 1] == "batchnorm2d" and (i + 1) not in given_bn:
+            hw_, nq_ = shp[1] * shp[2], B * shp[1] * shp[2]
+            ks = not (_cdiv(nq_, 128) * _cdiv(L["cout"], 32) < 256 and _cdiv(L["cin"], 8) >= 16)
+            parts = _cdiv(nq_, 512) if (hw_ % 4 == 0 and nq_ >= 65536) else _cdiv(nq_, 128)
+            if ks and parts <= 256:
+                stat_bn.add(i + 1)
+        shp = gen.out_shape([L], shp)
     for i, L in enumerate(cfg.layers):
         k = L["kind"]
         oshape = gen.out_shape([L], shape)
@@ -117,10 +130,10 @@ def kernel_model(cfg):
             small = B * h * w <= 8192    # one block per channel, one launch per direction
             plain = i not in given_bn and i not in lazy_bn
             bwd_bytes = (12 if (not first or cfg.needs_input_grad) else 8) * n_el
-            if small and plain:
+            if small and plain and i not in stat_bn:
                 out.setdefault("bn_fwd_onepass_kernel", []).append(8 * n_el)               # (+4 with a fused skip)
             else:
-                if i not in given_bn:
+                if i not in given_bn and i not in stat_bn:
                     out.setdefault("bn_stats_partial_kernel" + vec, []).append(4 * n_el)
                 if i not in lazy_bn:
                     out.setdefault("bn_apply_kernel" + vec, []).append(8 * n_el)          # (+4 with a fused skip)

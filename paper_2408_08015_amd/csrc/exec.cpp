@@ -65,7 +65,8 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
   switch (op.kind) {
     case OP_CONV_PW:
       pw_conv_f32(st, s.wpack + op.wp_off, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out),
-                  op.has_bias ? s.W + op.b_off : nullptr, nullptr, I.n, op.cin, op.cout, HW);
+                  op.has_bias ? s.W + op.b_off : nullptr, nullptr, I.n, op.cin, op.cout, HW,
+                  op.stats_op >= 0 ? reinterpret_cast<double*>(scratch(c, s.ops[op.stats_op])) : nullptr);
       break;
     case OP_CONV_DW:
     {

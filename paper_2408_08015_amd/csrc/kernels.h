@@ -28,8 +28,12 @@ struct PackTask {
 };
 void pw_pack_all_f32(hipStream_t st, const PackTask* tasks_dev, const unsigned short* block_task_dev, float* arena,
                      int nblocks);
+// stats (may be NULL; needs bias == add == NULL and pw_conv_stats_parts() > 0): the kernel also
+// leaves (sum, sum of squares) of Y per channel and pixel block, stats[Mdim][pw_conv_stats_parts()][2],
+// for a BatchNorm behind the convolution.
+int pw_conv_stats_parts(int N, int Kdim, int Mdim, int HW);
 void pw_conv_f32(hipStream_t st, const float* Wp, const float* X, float* Y, const float* bias,
-                 const float* add, int N, int Kdim, int Mdim, int HW);
+                 const float* add, int N, int Kdim, int Mdim, int HW, double* stats = nullptr);
 // Weight gradient of the pointwise convolution, split over pixel chunks:
 //   part[chunk][co][ci] = sum_{p in chunk} g[n][co][p] * x[n][ci][p];  then G += sum_chunk part.
 // `part` must hold pw_wgrad_f32_ws(N,Cin,Cout,HW) floats; with G = NULL only the partials are

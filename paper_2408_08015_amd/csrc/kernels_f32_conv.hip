@@ -32,6 +32,7 @@ struct PwArgs {  // one pointwise-conv product Y = A X (+ bias) (+ add)
   float* Y;
   const float* bias;
   const float* add;
+  double* stats;  // or NULL: per block (sum, sum of squares) of the output per channel, stats[m][gridDim.x][2]
   long NQ;
   int HW, Kdim, Mdim, KG;
 };
@@ -48,8 +49,41 @@ struct WgArgs {  // one pointwise-conv weight-gradient launch (partials only)
 // there.  A wavefront therefore reads its operands with fully coalesced 16-byte loads
 // and needs neither LDS nor a barrier, and all loads of a pass are issued before its first
 // MFMA.  NCH = 32-channel chunks per pass.
+// Statistics epilogue of the forward product (for a BatchNorm behind the convolution): lane l
+// holds, for each of its 16 accumulator rows, the sum s and sum of squares q of its pixels; the
+// block adds them per channel over its pixels (through LDS, two rounds of 16 KB) and writes one
+// (sum, sum of squares) pair per channel and block.  All 256 threads take part.
+__device__ __forceinline__ void pw_stats_epilogue(const float (&s)[16], const float (&q)[16], float (*sR)[16][64],
+                                                  double* __restrict__ stats, int m_base, int Mdim, int bx, int P) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ci = threadIdx.x >> 3, part = threadIdx.x & 7;  // channel of the 32-row tile, slice of its 128 values
+  const int r = 4 * (ci >> 3) + (ci & 3), half = (ci >> 2) & 1;
+  const int w = part >> 1, c0 = half * 32 + (part & 1) * 16;
+  const int rot = (ci & 3) * 4 + w;  // start of the 16-value walk: the 64 lanes of a wavefront hit 64 banks
+  float tot[2];
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    if (pass) __syncthreads();  // the first round has been read
+#pragma unroll
+    for (int k = 0; k < 16; ++k) sR[wave][k][lane] = pass ? q[k] : s[k];
+    __syncthreads();
+    float v = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v += sR[w][r][c0 + ((k + rot) & 15)];
+    v += __shfl_xor(v, 1, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 4, 64);
+    tot[pass] = v;
+  }
+  if (part == 0 && m_base + ci < Mdim) {
+    double* o = stats + ((size_t)(m_base + ci) * P + bx) * 2;
+    o[0] = (double)tot[0];
+    o[1] = (double)tot[1];
+  }
+}
+
 template <int NCH>
-__device__ __forceinline__ void pw_pk_body(const PwArgs& a, int bx, int by) {
+__device__ __forceinline__ void pw_pk_body(const PwArgs& a, int bx, int by, float (*sR)[16][64], int P) {
   const float4* __restrict__ Wp = a.Wp;
   const float* __restrict__ X = a.X;
   float* __restrict__ Y = a.Y;
@@ -96,23 +130,34 @@ __device__ __forceinline__ void pw_pk_body(const PwArgs& a, int bx, int by) {
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g].w, b[4 * g + 3], acc, 0, 0, 0);
     }
   }
-  if (!qv) return;
-  float* yq = Y + (size_t)n * Mdim * HW + p;
-  const float* aq = add ? add + (size_t)n * Mdim * HW + p : nullptr;
+  if (qv) {
+    float* yq = Y + (size_t)n * Mdim * HW + p;
+    const float* aq = add ? add + (size_t)n * Mdim * HW + p : nullptr;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
-    if (m < Mdim) {
-      float v = acc[r];
-      if (bias) v += bias[m];
-      if (aq) v += aq[(size_t)m * HW];
-      yq[(size_t)m * HW] = v;
+    for (int r = 0; r < 16; ++r) {
+      const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (m < Mdim) {
+        float v = acc[r];
+        if (bias) v += bias[m];
+        if (aq) v += aq[(size_t)m * HW];
+        yq[(size_t)m * HW] = v;
+      }
     }
+  }
+  if (a.stats) {  // uniform; only without bias / add (the accumulators are the outputs; invalid pixels hold zeros)
+    float s[16], q2[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s[r] = acc[r];
+      q2[r] = acc[r] * acc[r];
+    }
+    pw_stats_epilogue(s, q2, sR, a.stats, m_base, Mdim, bx, P);
   }
 }
 template <int NCH>
 __global__ __launch_bounds__(256) void pw_conv_f32_pk_kernel(PwArgs a) {
-  pw_pk_body<NCH>(a, blockIdx.x, blockIdx.y);
+  __shared__ float sR[4][16][64];
+  pw_pk_body<NCH>(a, blockIdx.x, blockIdx.y, sR, gridDim.x);
 }
 
 // Few pixels, long K (the 14x14 / 7x7 layers of a whole network): the four wavefronts of a
@@ -203,7 +248,7 @@ __global__ __launch_bounds__(64 * WV) void pw_conv_f32_pkks_kernel(PwArgs a) {
 // pixel 4j + t), so each output row is stored as 16 bytes per lane.  Four times the bytes
 // per memory instruction and a quarter of the weight traffic of the kernel above; needs
 // HW % 4 == 0.
-__device__ __forceinline__ void pw_pk4_body(const PwArgs& a, int bx, int by) {
+__device__ __forceinline__ void pw_pk4_body(const PwArgs& a, int bx, int by, float (*sR)[16][64], int P) {
   const float4* __restrict__ Wp = a.Wp;
   const float* __restrict__ X = a.X;
   float* __restrict__ Y = a.Y;
@@ -257,28 +302,39 @@ __device__ __forceinline__ void pw_pk4_body(const PwArgs& a, int bx, int by) {
       }
     }
   }
-  if (!qv) return;
-  float* yq = Y + (size_t)n * Mdim * HW + p;
-  const float* aq = add ? add + (size_t)n * Mdim * HW + p : nullptr;
+  if (qv) {
+    float* yq = Y + (size_t)n * Mdim * HW + p;
+    const float* aq = add ? add + (size_t)n * Mdim * HW + p : nullptr;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
-    if (m < Mdim) {
-      float4 v = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
-      if (bias) {
-        const float bv = bias[m];
-        v.x += bv; v.y += bv; v.z += bv; v.w += bv;
+    for (int r = 0; r < 16; ++r) {
+      const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (m < Mdim) {
+        float4 v = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+        if (bias) {
+          const float bv = bias[m];
+          v.x += bv; v.y += bv; v.z += bv; v.w += bv;
+        }
+        if (aq) {
+          const float4 k = *reinterpret_cast<const float4*>(aq + (size_t)m * HW);
+          v.x += k.x; v.y += k.y; v.z += k.z; v.w += k.w;
+        }
+        *reinterpret_cast<float4*>(yq + (size_t)m * HW) = v;
       }
-      if (aq) {
-        const float4 k = *reinterpret_cast<const float4*>(aq + (size_t)m * HW);
-        v.x += k.x; v.y += k.y; v.z += k.z; v.w += k.w;
-      }
-      *reinterpret_cast<float4*>(yq + (size_t)m * HW) = v;
     }
+  }
+  if (a.stats) {  // uniform; only without bias / add (invalid pixels hold zeros)
+    float s[16], q2[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s[r] = (acc[0][r] + acc[1][r]) + (acc[2][r] + acc[3][r]);
+      q2[r] = (acc[0][r] * acc[0][r] + acc[1][r] * acc[1][r]) + (acc[2][r] * acc[2][r] + acc[3][r] * acc[3][r]);
+    }
+    pw_stats_epilogue(s, q2, sR, a.stats, m_base, Mdim, bx, P);
   }
 }
 __global__ __launch_bounds__(256) void pw_conv_f32_pk4_kernel(PwArgs a) {
-  pw_pk4_body(a, blockIdx.x, blockIdx.y);
+  __shared__ float sR[4][16][64];
+  pw_pk4_body(a, blockIdx.x, blockIdx.y, sR, gridDim.x);
 }
 
 // Packed operand copy: Wp[((t*KG + g)*64 + l)*4 + e] = A[32t + l%32][8g + 2e + l/32], zero
@@ -347,6 +403,7 @@ static PwArgs pw_args(const float* Wp, const float* X, float* Y, const float* bi
   PwArgs a;
   a.Wp = reinterpret_cast<const float4*>(Wp);
   a.X = X; a.Y = Y; a.bias = bias; a.add = add;
+  a.stats = nullptr;
   a.NQ = (long)N * HW;
   a.HW = HW; a.Kdim = Kdim; a.Mdim = Mdim; a.KG = cdiv(Kdim, 8);
   return a;
@@ -358,10 +415,20 @@ static void launch_pkks(hipStream_t st, const PwArgs& a, const PwPick& p) {
   else KLAUNCH_NAMED("pw_conv_f32_pkks_kernel", (pw_conv_f32_pkks_kernel<4>), p.grid, dim3(256), 0, st, a);
 }
 
+// Partial pairs per channel that the forward product can leave for a BatchNorm behind it: the
+// number of pixel blocks of the 32- and 128-pixel-wavefront kernels while that is at most 256
+// (more would cost the consumer more than a statistics pass of its own); 0 = not offered.
+int pw_conv_stats_parts(int N, int Kdim, int Mdim, int HW) {
+  const PwPick p = pw_pick((long)N * HW, HW, Kdim, Mdim);
+  if (p.var == 2 || p.grid.x > 256) return 0;
+  return (int)p.grid.x;
+}
+
 void pw_conv_f32(hipStream_t st, const float* Wp, const float* X, float* Y, const float* bias, const float* add,
-                 int N, int Kdim, int Mdim, int HW) {
-  const PwArgs a = pw_args(Wp, X, Y, bias, add, N, Kdim, Mdim, HW);
+                 int N, int Kdim, int Mdim, int HW, double* stats) {
+  PwArgs a = pw_args(Wp, X, Y, bias, add, N, Kdim, Mdim, HW);
   const PwPick p = pw_pick(a.NQ, HW, Kdim, Mdim);
+  if (stats && !bias && !add && p.var != 2) a.stats = stats;
   switch (p.var) {
     case 2: launch_pkks(st, a, p); break;
     case 3: KLAUNCH(pw_conv_f32_pk4_kernel, p.grid, dim3(256), 0, st, a); break;
@@ -478,10 +545,10 @@ __global__ __launch_bounds__(256) void pw_bwd_dual_kernel(PwArgs a, WgArgs w, un
   __shared__ float sR[4][16][64];
   if (blockIdx.x < nA) {  // uniform per block
     const int bx = (int)(blockIdx.x % gAx), by = (int)(blockIdx.x / gAx);
-    if (VAR == 0) pw_pk_body<1>(a, bx, by);
-    else if (VAR == 1) pw_pk_body<2>(a, bx, by);
+    if (VAR == 0) pw_pk_body<1>(a, bx, by, sR, 0);
+    else if (VAR == 1) pw_pk_body<2>(a, bx, by, sR, 0);
     else if (VAR == 2) pw_pkks_body<4>(a, bx, by, sR);
-    else pw_pk4_body(a, bx, by);
+    else pw_pk4_body(a, bx, by, sR, 0);
   } else {
     const unsigned b = blockIdx.x - nA;
     const unsigned bx = b % gWx, r = b / gWx;

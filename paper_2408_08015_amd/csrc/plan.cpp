@@ -298,10 +298,11 @@ ast_status build_plan(Stage& s, std::string& err) {
   //      and the second one's statistics pass (conv epilogue)
   //   2  backward: the first BatchNorm's partial sums (conv backward epilogue); needs 1
   //   4  backward: the second BatchNorm's apply pass (on load of the conv's upstream gradient)
+  //   8  see below (pointwise conv -> BatchNorm)
   std::vector<char> virtual_act(s.acts.size(), 0);  // activations that are never materialised
   {
     const char* e = getenv("ASTEROID_BN_FUSE");
-    const int fuse = e ? atoi(e) : 7;
+    const int fuse = e ? atoi(e) : 15;
     for (size_t j = 0; fuse && j < s.ops.size(); ++j) {
       Op& dw = s.ops[j];
       if (dw.kind != OP_CONV_DW) continue;
@@ -333,6 +334,24 @@ ast_status build_plan(Stage& s, std::string& err) {
           }
         }
       }
+    }
+  }
+
+  // ... and bit 8: a pointwise conv (no bias) directly in front of a BatchNorm leaves that
+  // BatchNorm's statistics partials in its epilogue, where its launch shape offers them.
+  {
+    const char* e = getenv("ASTEROID_BN_FUSE");
+    const int fuse = e ? atoi(e) : 15;
+    for (size_t j = 0; (fuse & 8) && j + 1 < s.ops.size(); ++j) {
+      Op& pw = s.ops[j];
+      Op& bn = s.ops[j + 1];
+      if (pw.kind != OP_CONV_PW || pw.has_bias || bn.kind != OP_BN || bn.in != pw.out || bn.bn_stats_given) continue;
+      const Act& I = s.acts[pw.in];
+      const int parts = pw_conv_stats_parts(I.n, pw.cin, pw.cout, I.h * I.w);
+      if (parts <= 0) continue;
+      bn.bn_stats_given = true;
+      bn.given_parts = parts;
+      pw.stats_op = (int)j + 1;
     }
   }
 

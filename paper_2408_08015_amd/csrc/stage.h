@@ -78,6 +78,7 @@ struct Op {
   int bn_in_op = -1;                  // depthwise conv: index of the lazy BatchNorm op in front
   int bn_out_op = -1;                 // depthwise conv: index of the BatchNorm op it writes statistics for
   int bn_bwd_out_op = -1;             // depthwise conv: index of the BatchNorm op whose backward apply it does
+  int stats_op = -1;                  // pointwise conv: index of the BatchNorm op it writes statistics for
 };
 
 struct Stage {
