@@ -79,6 +79,17 @@ def test_pointwise_conv(A, cin, cout, hw, B):
     check(one([conv(cin, cout, 1)], (cin, hw, hw), B=B, name="pw%dx%d" % (cin, cout)))
 
 
+@pytest.mark.parametrize("cin,cout,hw,B", [
+    (24, 40, 12, 3),      # 32-pixel wavefronts, one channel chunk; ragged output tile, ragged pixel block
+    (40, 72, 12, 3),      # two channel chunks per pass
+    (16, 48, 64, 16),     # 128-pixel wavefronts (65536 pixels), 128 pixel blocks
+    (160, 24, 7, 2),      # K-split kernel: no statistics epilogue, the BatchNorm makes its own pass
+])
+def test_pointwise_conv_then_batchnorm(A, cin, cout, hw, B):
+    # the convolution's epilogue leaves the BatchNorm's statistics partials where its launch shape offers them
+    check(one([conv(cin, cout, 1), bn(cout), simple("relu6")], (cin, hw, hw), B=B, name="pw_bn%dx%d" % (cin, cout)))
+
+
 def test_pointwise_conv_with_bias(A):
     check(one([conv(24, 40, 1, bias=True)], (24, 12, 12)))
 
