@@ -171,8 +171,7 @@ def kernel_model(cfg):
             S, D = shape
             fl = 4 * S * D * B * S                                            # QK^T and PV
             out.setdefault("attention_fwd_kernel", []).append(fl)
-            out.setdefault("attention_bwd_dkv_kernel", []).append(2 * fl)     # S, dP, dV, dK
-            out.setdefault("attention_bwd_dq_kernel", []).append(int(1.5 * fl))   # S, dP, dQ
+            out.setdefault("attention_bwd_kernel", []).append(int(3.5 * fl))  # dK/dV role: S, dP, dV, dK; dQ role: S, dP, dQ
         if cfg.dtype == "bf16" and k == "layernorm":
             S, D = shape
             out.setdefault("layernorm_fwd_kernel", []).append(4 * B * S * D)      # bf16 in, bf16 out

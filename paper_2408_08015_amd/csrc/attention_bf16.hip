@@ -190,12 +190,12 @@ __global__ void attn_dsum_kernel(const bf16_t* __restrict__ o, const bf16_t* __r
 }
 
 // dK, dV: a wavefront owns 32 keys (lane = key), loops over query tiles.
-__global__ __launch_bounds__(256) void attention_bwd_dkv_kernel(const bf16_t* __restrict__ qkv,
-                                                                const bf16_t* __restrict__ d_o,
-                                                                const float* __restrict__ lse,
-                                                                const float* __restrict__ dsum,
-                                                                bf16_t* __restrict__ dqkv, int S, int D, int H) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+__device__ __forceinline__ void attention_bwd_dkv_body(const bf16_t* __restrict__ qkv,
+                                                       const bf16_t* __restrict__ d_o,
+                                                       const float* __restrict__ lse,
+                                                       const float* __restrict__ dsum,
+                                                       bf16_t* __restrict__ dqkv, int S, int D, int H, int bx,
+                                                       unsigned char* smem) {
   const int TS = S + 8;
   bf16_t* sQ = reinterpret_cast<bf16_t*>(smem);  // [S][RS]
   bf16_t* sdO = sQ + S * RS;                     // [S][RS]
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(256) void attention_bwd_dkv_kernel(const bf16_t* __
     sD[i] = dsum[((long)b * H + h) * S + i];
   }
   __syncthreads();
-  const int k0 = blockIdx.x * 128 + wave * 32;
+  const int k0 = bx * 128 + wave * 32;
   if (k0 >= S) return;
   const int key = k0 + col;
   bf16x8 kf[4], vf[4];
@@ -278,12 +278,12 @@ __global__ __launch_bounds__(256) void attention_bwd_dkv_kernel(const bf16_t* __
 }
 
 // dQ: a wavefront owns 32 queries (lane = query), loops over key tiles.
-__global__ __launch_bounds__(256) void attention_bwd_dq_kernel(const bf16_t* __restrict__ qkv,
-                                                               const bf16_t* __restrict__ d_o,
-                                                               const float* __restrict__ lse,
-                                                               const float* __restrict__ dsum,
-                                                               bf16_t* __restrict__ dqkv, int S, int D, int H) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+__device__ __forceinline__ void attention_bwd_dq_body(const bf16_t* __restrict__ qkv,
+                                                      const bf16_t* __restrict__ d_o,
+                                                      const float* __restrict__ lse,
+                                                      const float* __restrict__ dsum,
+                                                      bf16_t* __restrict__ dqkv, int S, int D, int H, int bx,
+                                                      unsigned char* smem) {
   const int TS = S + 8;
   bf16_t* sK = reinterpret_cast<bf16_t*>(smem);  // [S][RS]
   bf16_t* sV = sK + S * RS;                      // [S][RS]
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(256) void attention_bwd_dq_kernel(const bf16_t* __r
   stage_rows(sV, base + 2 * D, ld, S);
   stage_rows_T(sKt, base + D, ld, S);
   __syncthreads();
-  const int q0 = blockIdx.x * 128 + wave * 32;
+  const int q0 = bx * 128 + wave * 32;
   if (q0 >= S) return;
   const int q = q0 + col;
   bf16x8 qf[4], dof[4];
@@ -353,6 +353,19 @@ size_t lds_dkv(int S) { return ((size_t)2 * S * RS + (size_t)2 * HD * (S + 8)) *
 size_t lds_dq(int S) { return ((size_t)2 * S * RS + (size_t)HD * (S + 8)) * 2; }
 
 // kernels may need more than the default 64 KiB of dynamic LDS (S = 256)
+// dK/dV and dQ in ONE launch: the two are independent and each alone is a short latency-bound
+// chain, so their blocks are dealt from one grid: block ids [0, nx) of the x dimension are the
+// key tiles of the dK/dV role, [nx, 2 nx) the query tiles of the dQ role.
+__global__ __launch_bounds__(256) void attention_bwd_kernel(const bf16_t* __restrict__ qkv,
+                                                            const bf16_t* __restrict__ d_o,
+                                                            const float* __restrict__ lse,
+                                                            const float* __restrict__ dsum,
+                                                            bf16_t* __restrict__ dqkv, int S, int D, int H, int nx) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  if ((int)blockIdx.x < nx) attention_bwd_dkv_body(qkv, d_o, lse, dsum, dqkv, S, D, H, (int)blockIdx.x, smem);  // uniform
+  else attention_bwd_dq_body(qkv, d_o, lse, dsum, dqkv, S, D, H, (int)blockIdx.x - nx, smem);
+}
+
 void allow_lds(const void* fn, size_t bytes) {
   (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
@@ -374,12 +387,11 @@ void attention_bwd_bf16(hipStream_t st, const bf16_t* qkv, const bf16_t* o, cons
                         bf16_t* dqkv, float* dsum, int B, int S, int D, int heads) {
   long total = (long)B * S * heads;
   KLAUNCH(attn_dsum_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, o, d_o, dsum, S, D, heads, total);
-  size_t l1 = lds_dkv(S), l2 = lds_dq(S);
-  allow_lds((const void*)attention_bwd_dkv_kernel, l1);
-  allow_lds((const void*)attention_bwd_dq_kernel, l2);
-  dim3 grid((S + 127) / 128, heads, B);
-  KLAUNCH(attention_bwd_dkv_kernel, grid, dim3(256), l1, st, qkv, d_o, lse, dsum, dqkv, S, D, heads);
-  KLAUNCH(attention_bwd_dq_kernel, grid, dim3(256), l2, st, qkv, d_o, lse, dsum, dqkv, S, D, heads);
+  const size_t l1 = lds_dkv(S), l2 = lds_dq(S), lds = l1 > l2 ? l1 : l2;
+  allow_lds((const void*)attention_bwd_kernel, lds);
+  const int nx = (S + 127) / 128;
+  dim3 grid(2 * nx, heads, B);
+  KLAUNCH(attention_bwd_kernel, grid, dim3(256), lds, st, qkv, d_o, lse, dsum, dqkv, S, D, heads, nx);
 }
 
 }  // namespace ast

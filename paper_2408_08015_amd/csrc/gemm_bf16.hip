@@ -639,8 +639,10 @@ inline long cdivl(long a, long b) { return (a + b - 1) / b; }
 // at least 16 tiles, multiple of BK.  Every split writes, and the reduction reads, a full copy
 // of the gradient: on the transformer stage (K = 4096 rows) 8 splits made 1.2 GB of partial
 // traffic per backward pass; 4 measured 6 % faster for the whole step, 2, 3, 5 and 6 slower.
+int env_int(const char* name);
 int choose_splits(long tiles, long K) {
-  long want = cdivl(768, tiles);
+  static const int target = env_int("ASTEROID_WG_TARGET") > 0 ? env_int("ASTEROID_WG_TARGET") : 768;  // experiment switch
+  long want = cdivl(target, tiles);
   long maxs = K / (BK * 16);
   if (maxs < 1) maxs = 1;
   if (want > maxs) want = maxs;
@@ -762,7 +764,8 @@ void launch_fwd_like(hipStream_t st, GemmArgs& g) {
     default: break;
   }
   const int pf = gemm_pf(), bk = gemm_bk();
-  const bool big = blocks(128, 128) >= 256;
+  static const int big_min = env_int("ASTEROID_GEMM_BIG") > 0 ? env_int("ASTEROID_GEMM_BIG") : 256;  // experiment switch
+  const bool big = blocks(128, 128) >= big_min;
   if constexpr (AMODE == A_ROW) {
     // Deeper K-tiles (fewer, longer steps) were measured on the transformer products
     // (4096 x {512,1536,2048} x {512,2048}): no gain over 64, so they stay an experiment switch.
