@@ -99,6 +99,11 @@ std::vector<float> initial_params(const ast::Stage& s) {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 }  // namespace
 
+namespace ast {
+// message for asteroid_last_error() from the other translation units of the library
+void set_last_error(const std::string& msg) { g_err = msg; }
+}  // namespace ast
+
 extern "C" {
 
 const char* asteroid_last_error(void) { return g_err.c_str(); }

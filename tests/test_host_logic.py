@@ -22,9 +22,11 @@ def A():
 
 
 def test_library_exports_every_declared_symbol(A):
-    hdr = open(os.path.join(ROOT, "include", "asteroid.h")).read()
+    import glob
+    hdr = "".join(open(h).read() for h in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
     names = sorted(set(re.findall(r"\b(asteroid_[a-z_0-9]+)\s*\(", hdr)))
-    assert "asteroid_stage_create" in names and "asteroid_stage_step" in names and len(names) >= 15
+    assert "asteroid_stage_create" in names and "asteroid_stage_step" in names and len(names) >= 19
+    assert "asteroid_plan_hpp" in names and "asteroid_plan_allocate" in names
     lib = ctypes.CDLL(A.lib_path())
     for n in names:
         assert hasattr(lib, n), n
