@@ -117,3 +117,31 @@ def test_bf16_rounding_helper():
     c4 = get_config("cfg4", B=1, M=1, hw=4, cin=8, c=8)
     inp = gen.make_inputs(c4)
     assert np.array_equal(gen.round_to_bf16(inp["x"]), inp["x"]) and inp["x"].shape == (1, 4, 4, 8)
+
+
+def test_profiler_units_cut_only_where_a_stage_may_end():
+    """Sec. 3.3: the model is a layer sequence split between layers; the profiler's units are
+    the shortest runs a stage can consist of (never inside a residual block, a BatchNorm or
+    activation stays with its convolution, the loss with the classifier)."""
+    from paper_2408_08015_amd.profiler import split_units
+    L = C.mobilenetv2_layers(10)
+    units = split_units(L)
+    assert units[0] == (0, 3) and units[-1] == (len(L) - 3, len(L))
+    assert [u[0] for u in units[1:]] == [u[1] for u in units[:-1]]
+    for lo, hi in units:
+        kinds = [l["kind"] for l in L[lo:hi]]
+        assert kinds.count("res_begin") == kinds.count("res_add")
+        assert kinds[0] in ("conv2d", "res_begin", "global_avgpool")
+    enc = C.encoder_layer(64, 2, 128) * 2
+    assert split_units(enc) == [(0, 4), (4, 10), (10, 14), (14, 20)]
+    assert split_units(C.vgg_layers(8, 16)) == [(0, 2), (2, 4), (4, 7)]
+
+
+def test_profiler_table_interpolation():
+    from paper_2408_08015_amd.profiler import tables_for_planner
+    units = [dict(tf={1: 10.0, 4: 16.0}, tb={1: 20.0, 4: 32.0}, a=8, act=24.0, w=100)]
+    tf, tb, a, act, w = tables_for_planner(units, 6, n_devices=3)
+    assert tf.shape == (3, 1, 7)
+    assert list(tf[2, 0]) == [0.0, 10.0, 12.0, 14.0, 16.0, 18.0, 20.0]      # last slope continues
+    assert list(tb[0, 0]) == [0.0, 20.0, 24.0, 28.0, 32.0, 36.0, 40.0]
+    assert (a[0], act[0], w[0]) == (8.0, 24.0, 100.0)

@@ -181,6 +181,41 @@ def test_cfg3_small(A):
     check(C.cfg3(B=8, M=2, hw=96, num_classes=24), tol_y=1e-4, tol_g=5e-2, rounds=1)
 
 
+@pytest.mark.parametrize("beta", [1, 3])
+@pytest.mark.parametrize("unit", [0, 1, 2, 4, 6, 13, 19, 26, 31, 32])
+def test_profiling_units_of_mobilenetv2(A, unit, beta):
+    """The stages the profiler times (Sec. 3.3): single units of the full-size model at the
+    small batch sizes of its tables, each against the oracle."""
+    from paper_2408_08015_amd.profiler import _out_shape, split_units
+    full = C.cfg3()
+    shape = full.in_shape
+    for i, (lo, hi) in enumerate(split_units(full.layers)):
+        sub = full.layers[lo:hi]
+        if i == unit:
+            break
+        shape = _out_shape(sub, shape)
+    cfg = StageConfig("mbv2_unit%d" % unit, sub, beta, 1, shape, "f32", "nchw", unit > 0, 900 + unit)
+    # one sample at 7x7 leaves 49 values per BatchNorm channel: fp32 statistics are worth ~1e-3
+    check(cfg, tol_g=5e-3 if beta * shape[-1] * shape[-1] < 200 else TOL_GRAD, rounds=1)
+
+
+def test_profiler_tables(A):
+    """profile_model returns one row per unit with positive times for every batch size, sizes
+    that match the shapes, and tables_for_planner passes through the measured points."""
+    from paper_2408_08015_amd import profiler
+    cfg = C.cfg1()
+    units = profiler.profile_model(cfg.layers, cfg.in_shape, cfg.dtype, cfg.layout, [1, 2, 4], True, reps=3)
+    assert [(u["lo"], u["hi"]) for u in units] == profiler.split_units(cfg.layers)
+    assert units[0]["a"] == 32 * 16 * 16 * 4 and units[-1]["a"] == 10 * 4
+    assert units[0]["w"] == 4 * gen.num_params(cfg.layers[:units[0]["hi"]])
+    for u in units:
+        assert all(u["tf"][b] > 0 and u["tb"][b] > 0 for b in (1, 2, 4))
+    tf, tb, a, act, w = profiler.tables_for_planner(units, 6, n_devices=2)
+    assert tf.shape == (2, len(units), 7) and np.all(tf[:, :, 0] == 0)
+    assert tf[1, 0, 4] == units[0]["tf"][4] and tb[0, 1, 2] == units[1]["tb"][2]
+    assert abs(tf[0, 0, 3] - 0.5 * (units[0]["tf"][2] + units[0]["tf"][4])) < 1e-12
+
+
 # ------------------------------------------------------------------ 1F1B discipline, K, determinism
 def test_state_machine_and_K_independence(A):
     import torch
