@@ -43,6 +43,13 @@ def load_library():
     path = lib_path()
     if not os.path.exists(path):
         raise ImportError("HIP library not built: %s is missing (run __graft_entry__.build())" % path)
+    try:
+        # The caller's tensors and streams come from PyTorch, whose wheel carries its own HIP
+        # runtime: load it first so that this library binds to the same runtime instance (a
+        # second instance loaded beforehand sees no device once PyTorch initialises its own).
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(path)
     vp, i32, f32p, szp = C.c_void_p, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_size_t)
     lib.asteroid_stage_create.argtypes = [C.POINTER(ast_layer), i32, C.POINTER(ast_stage_cfg), vp, C.POINTER(vp)]
