@@ -6,7 +6,10 @@ into M micro-batches of size B.  Micro-batch m holds samples [m*B, (m+1)*B).
 Layer dictionaries (keys are plain ints/floats/bools):
   conv2d       cin cout k stride pad groups bias
   batchnorm2d  c eps
-  relu / relu6 / gelu / res_begin / res_add / global_avgpool / maxpool2x2 / softmax_ce
+  relu / relu6 / gelu / swish / sigmoid / res_begin / res_add / global_avgpool / maxpool2x2 / softmax_ce
+  se_begin ... se_scale   squeeze-and-excitation: the layers in between (global_avgpool, linear,
+               swish, linear, sigmoid) turn the tensor at se_begin into one gate per sample and
+               channel; se_scale multiplies that tensor by its gate
   linear       cin cout bias
   layernorm    d eps
   mha          d heads
@@ -44,6 +47,30 @@ def irb(cin, cout, stride, expand):
     if expand != 1:
         L += [conv(cin, hid, 1), bn(hid), simple("relu6")]
     L += [conv(hid, hid, 3, stride, 1, groups=hid), bn(hid), simple("relu6")]
+    L += [conv(hid, cout, 1), bn(cout)]
+    if res:
+        L.append(simple("res_add"))
+    return L
+
+
+def squeeze_excite(c, cr):
+    return [simple("se_begin"), simple("global_avgpool"), linear(c, cr), simple("swish"),
+            linear(cr, c), simple("sigmoid"), simple("se_scale")]
+
+
+def mbconv(cin, cout, k, stride, expand, se_ratio=0.25):
+    """EfficientNet block: 1x1 expand, BN, swish, kxk depthwise, BN, swish, squeeze-and-excitation
+    (reduced to se_ratio * cin channels), 1x1 project, BN, residual add iff stride 1 and
+    cin == cout.  The expansion conv is absent when expand == 1."""
+    hid = cin * expand
+    res = stride == 1 and cin == cout
+    L = []
+    if res:
+        L.append(simple("res_begin"))
+    if expand != 1:
+        L += [conv(cin, hid, 1), bn(hid), simple("swish")]
+    L += [conv(hid, hid, k, stride, k // 2, groups=hid), bn(hid), simple("swish")]
+    L += squeeze_excite(hid, max(1, int(cin * se_ratio)))
     L += [conv(hid, cout, 1), bn(cout)]
     if res:
         L.append(simple("res_add"))
@@ -131,11 +158,18 @@ def cfg5(B=32, M=4, S=128, d=512, heads=8, ffn=2048, nlayers=6, seed=1005):
                        init="normal0.02")
 
 
+def cfg6(B=32, M=4, hw=60, seed=1006):
+    """EfficientNet-B1 (Table 4) third block group at its 240x240 input resolution: three
+    MBConv6 blocks with 5x5 depthwise convolutions, 24 -> 40 channels, 60x60 -> 30x30."""
+    L = mbconv(24, 40, 5, 2, 6) + mbconv(40, 40, 5, 1, 6) + mbconv(40, 40, 5, 1, 6)
+    return StageConfig("cfg6_effnetb1_stage", L, B, M, (24, hw, hw), "f32", "nchw", True, seed)
+
+
 CONFIGS = {
-    "cfg1": cfg1, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4, "cfg5": cfg5,
+    "cfg1": cfg1, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4, "cfg5": cfg5, "cfg6": cfg6,
 }
 
 
 def get_config(name, **kw):
-    """Full-size config by name ("cfg1".."cfg5"); keyword overrides shrink it for tests."""
+    """Full-size config by name ("cfg1".."cfg6"); keyword overrides shrink it for tests."""
     return CONFIGS[name](**kw)

@@ -81,9 +81,14 @@ def boundary_shape(layout, per_sample, n):
 def out_shape(layers, in_shape):
     """Per-sample logical output shape of the stage ((C,H,W), (S,D) or (classes,))."""
     s = tuple(in_shape)
+    se = []
     for L in layers:
         k = L["kind"]
-        if k == "conv2d":
+        if k == "se_begin":
+            se.append(s)
+        elif k == "se_scale":
+            s = se.pop()
+        elif k == "conv2d":
             c, h, w = s
             ho = (h + 2 * L["pad"] - L["k"]) // L["stride"] + 1
             wo = (w + 2 * L["pad"] - L["k"]) // L["stride"] + 1

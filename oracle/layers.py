@@ -141,6 +141,27 @@ def gelu_bwd(g, x):
     return g * (cdf + x * pdf)
 
 
+def sigmoid_fwd(x):
+    """1 / (1 + exp(-x))."""
+    return 1.0 / (1.0 + np.exp(-x))
+
+
+def sigmoid_bwd(g, x):
+    s = sigmoid_fwd(x)
+    return g * s * (1.0 - s)
+
+
+def swish_fwd(x):
+    """x * sigmoid(x): the activation of the EfficientNet workload (Sec. 5.1, Table 4)."""
+    return x * sigmoid_fwd(x)
+
+
+def swish_bwd(g, x):
+    """d/dx [x s(x)] = s + x s (1 - s)."""
+    s = sigmoid_fwd(x)
+    return g * (s + x * s * (1.0 - s))
+
+
 # --------------------------------------------------------------------------- pooling
 def global_avgpool_fwd(x):
     return x.mean(axis=(2, 3))

@@ -134,6 +134,7 @@ class OracleStage:
         a = self._to_logical(x)
         saved = []
         res = []
+        se = []
         loss = None
         logits = None
         trace = []
@@ -164,6 +165,21 @@ class OracleStage:
             elif k == "gelu":
                 saved.append(a)
                 a = L.gelu_fwd(a)
+            elif k == "swish":
+                saved.append(a)
+                a = L.swish_fwd(a)
+            elif k == "sigmoid":
+                saved.append(a)
+                a = L.sigmoid_fwd(a)
+            elif k == "se_begin":
+                # squeeze-and-excitation: the layers up to se_scale turn this tensor into one
+                # gate per sample and channel, which then scales it
+                se.append(a)
+                saved.append(None)
+            elif k == "se_scale":
+                xs = se.pop()
+                saved.append((xs, a))
+                a = xs * a[:, :, None, None]
             elif k == "res_begin":
                 res.append(a)
                 saved.append(None)
@@ -190,7 +206,7 @@ class OracleStage:
                 saved.append((p, np.asarray(labels)))
             else:
                 raise ValueError(k)
-            if self.storage == "bf16" and k not in ("softmax_ce", "res_begin"):
+            if self.storage == "bf16" and k not in ("softmax_ce", "res_begin", "se_begin"):
                 a = round_bf16(a)
         self.stash[mb] = saved
         if self.keep_acts:
@@ -227,6 +243,16 @@ class OracleStage:
                 g = L.relu6_bwd(g, sv)
             elif k == "gelu":
                 g = L.gelu_bwd(g, sv)
+            elif k == "swish":
+                g = L.swish_bwd(g, sv)
+            elif k == "sigmoid":
+                g = L.sigmoid_bwd(g, sv)
+            elif k == "se_scale":
+                xs, gate = sv
+                skip.append(g * gate[:, :, None, None])      # through the scaled tensor
+                g = (g * xs).sum(axis=(2, 3))                # through the gate
+            elif k == "se_begin":
+                g = g + skip.pop()
             elif k == "res_add":
                 skip.append(g)
             elif k == "res_begin":

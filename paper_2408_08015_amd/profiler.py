@@ -4,7 +4,7 @@ and the FP / BP time t_f(beta), t_b(beta) over a set of batch sizes -- on the GP
 
 A "layer" of the table is a profiling unit: the shortest run of consecutive layers that a
 pipeline stage may start or end at (a convolution with its BatchNorm and activation, a whole
-residual block, an attention or feed-forward block with its LayerNorm).  Sec. 5.6 "Planning
+residual block, an attention or feed-forward block with its LayerNorm).  Sec. 5.7 "Planning
 Overhead" suggests this granularity to keep the planner's search small.
 
 Every time is measured by running the unit as a one-micro-batch stage through the C ABI
@@ -21,21 +21,22 @@ import numpy as np
 
 from . import binding as A
 
-_STARTS = ("conv2d", "res_begin", "mha", "global_avgpool")
+_STARTS = ("conv2d", "res_begin", "se_begin", "mha", "global_avgpool")
 
 
 def split_units(layers):
     """[(lo, hi)) runs of layer indices: cut in front of a convolution, a residual block, an
-    attention layer or the pooling of the classifier, never inside a residual block."""
+    attention layer, a squeeze-and-excitation block or the pooling of the classifier, never inside
+    a residual or squeeze-and-excitation block."""
     cuts, depth = [0], 0
     for i, L in enumerate(layers):
         k = L["kind"]
         start = k in _STARTS or (k == "linear" and i > 0 and layers[i - 1]["kind"] != "global_avgpool")
         if i > 0 and depth == 0 and start:
             cuts.append(i)
-        if k == "res_begin":
+        if k in ("res_begin", "se_begin"):
             depth += 1
-        elif k == "res_add":
+        elif k in ("res_add", "se_scale"):
             depth -= 1
     cuts.append(len(layers))
     return [(cuts[i], cuts[i + 1]) for i in range(len(cuts) - 1)]
@@ -43,9 +44,14 @@ def split_units(layers):
 
 def _out_shape(layers, s):
     s = tuple(s)
+    se = []
     for L in layers:
         k = L["kind"]
-        if k == "conv2d":
+        if k == "se_begin":
+            se.append(s)
+        elif k == "se_scale":
+            s = se.pop()
+        elif k == "conv2d":
             c, h, w = s
             s = (L["cout"], (h + 2 * L["pad"] - L["k"]) // L["stride"] + 1,
                  (w + 2 * L["pad"] - L["k"]) // L["stride"] + 1)

@@ -135,6 +135,9 @@ def test_profiler_units_cut_only_where_a_stage_may_end():
     enc = C.encoder_layer(64, 2, 128) * 2
     assert split_units(enc) == [(0, 4), (4, 10), (10, 14), (14, 20)]
     assert split_units(C.vgg_layers(8, 16)) == [(0, 2), (2, 4), (4, 7)]
+    mb = C.mbconv(24, 40, 5, 2, 6)       # expand, depthwise, squeeze-and-excitation, project
+    assert split_units(mb) == [(0, 3), (3, 6), (6, 13), (13, 15)]
+    assert len(split_units(C.mbconv(40, 40, 5, 1, 6))) == 1
 
 
 def test_profiler_table_interpolation():

@@ -153,6 +153,8 @@ def test_fd_pointwise_and_pool():
     fd_check(L.relu_fwd, [x], 0, gy, L.relu_bwd(gy, x))
     fd_check(L.relu6_fwd, [x], 0, gy, L.relu6_bwd(gy, x))
     fd_check(L.gelu_fwd, [x], 0, gy, L.gelu_bwd(gy, x))
+    fd_check(L.swish_fwd, [x], 0, gy, L.swish_bwd(gy, x))
+    fd_check(L.sigmoid_fwd, [x], 0, gy, L.sigmoid_bwd(gy, x))
     y, idx = L.maxpool2x2_fwd(x)
     gp = r.standard_normal(y.shape)
     fd_check(lambda x: L.maxpool2x2_fwd(x)[0], [x], 0, gp, L.maxpool2x2_bwd(gp, idx, 6, 6))
@@ -193,6 +195,38 @@ def test_gelu_matches_math_erf():
     ref = np.array([x * 0.5 * (1 + math.erf(x / math.sqrt(2))) for x in xs])
     np.testing.assert_allclose(L.gelu_fwd(xs), ref, atol=1e-14)
     assert abs(L.gelu_fwd(np.array([1.0]))[0] - 0.8413447460685429) < 1e-14      # Phi(1)
+
+
+def test_sigmoid_swish_closed_forms():
+    xs = np.linspace(-6, 6, 25)
+    ref = np.array([1.0 / (1.0 + math.exp(-x)) for x in xs])
+    np.testing.assert_allclose(L.sigmoid_fwd(xs), ref, atol=1e-15)
+    np.testing.assert_allclose(L.sigmoid_fwd(xs) + L.sigmoid_fwd(-xs), 1.0, atol=1e-15)   # s(-x) = 1 - s(x)
+    np.testing.assert_allclose(L.sigmoid_fwd(xs), 0.5 * (1.0 + np.tanh(xs / 2.0)), atol=1e-15)
+    np.testing.assert_allclose(L.swish_fwd(xs) - L.swish_fwd(-xs), xs, atol=1e-14)        # odd part is x/2 * 2
+    assert L.swish_fwd(np.array([0.0]))[0] == 0.0
+    assert abs(L.swish_fwd(np.array([1.0]))[0] - 0.7310585786300049) < 1e-15              # 1/(1+1/e)
+
+
+def test_squeeze_excite_with_zero_fc_halves_the_tensor():
+    """Both SE linear layers at zero: the gate is sigmoid(0) = 1/2 for every channel, the block
+    scales its input by 1/2, passes half the gradient through and gives the FC weights none
+    except through the last bias."""
+    Ls = C.squeeze_excite(6, 2)
+    cfg = C.StageConfig("se", Ls, 2, 1, (6, 5, 5), "f32", "nchw", True, 3)
+    st = OracleStage(cfg.layers, cfg.B, cfg.M, cfg.in_shape)
+    st.set_params(np.zeros(st.nparams))
+    r = RNG(5)
+    x = r.standard_normal((2, 6, 5, 5))
+    dy = r.standard_normal((2, 6, 5, 5))
+    y, _ = st.forward(0, x)
+    np.testing.assert_allclose(y, 0.5 * x, atol=1e-15)
+    dx = st.backward(0, dy)
+    np.testing.assert_allclose(dx, 0.5 * dy, atol=1e-15)
+    gW1, gb1, gW2, gb2 = st._p(st.G, 2) + st._p(st.G, 4)
+    assert not gW1.any() and not gb1.any() and not gW2.any()
+    # d gate = sum_hw dy*x per (sample, channel); sigmoid'(0) = 1/4; the bias sums over samples
+    np.testing.assert_allclose(gb2, 0.25 * (dy * x).sum(axis=(0, 2, 3)), atol=1e-13)
 
 
 def test_bn_ln_invariants():
@@ -371,6 +405,7 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False)
         if cfg.layout == "nhwc":
             a = a.permute(0, 3, 1, 2)
         res = []
+        se = []
         for l in cfg.layers:
             k = l["kind"]
             if k == "conv2d":
@@ -389,6 +424,14 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False)
                 a = TF.relu6(a)
             elif k == "gelu":
                 a = TF.gelu(a)
+            elif k == "swish":
+                a = TF.silu(a)
+            elif k == "sigmoid":
+                a = torch.sigmoid(a)
+            elif k == "se_begin":
+                se.append(a)
+            elif k == "se_scale":
+                a = se.pop() * a[:, :, None, None]
             elif k == "res_begin":
                 res.append(a)
             elif k == "res_add":
@@ -412,7 +455,7 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False)
             elif k == "softmax_ce":
                 lab = torch.tensor(target[m * B:(m + 1) * B].astype(np.int64))
                 total = total + TF.cross_entropy(a, lab, reduction="sum") / (M * B)
-            if k not in ("softmax_ce", "res_begin"):
+            if k not in ("softmax_ce", "res_begin", "se_begin"):
                 a = rb(a)
         if not cfg.loss_tail:
             if cfg.layout == "nhwc":
@@ -429,6 +472,7 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False)
     C.cfg3(B=3, M=2, hw=64, num_classes=7),
     C.cfg4(B=2, M=2, hw=6, cin=4, c=6),
     C.cfg5(B=2, M=2, S=7, d=16, heads=2, ffn=24, nlayers=2),
+    C.cfg6(B=3, M=2, hw=10),
 ], ids=lambda c: c.name)
 def test_stage_matches_torch_float64_autograd(cfg):
     st, inp = tiny_stage(cfg)
