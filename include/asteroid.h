@@ -69,7 +69,15 @@ typedef enum {
   AST_MAXPOOL2X2 = 9,  /* 2x2 window, stride 2; gradient to the first maximum in row-major order */
   AST_LAYERNORM = 10,  /* p = {D}; eps; over the last dimension                               */
   AST_MHA = 11,        /* p = {D, heads}; self-attention, no mask, no dropout                 */
-  AST_GELU = 12        /* x * Phi(x) with the exact erf form                                  */
+  AST_GELU = 12,       /* x * Phi(x) with the exact erf form                                  */
+  AST_SWISH = 13,      /* x * sigmoid(x)  (fp32 stages; the EfficientNet workload of Table 4)  */
+  AST_SIGMOID = 14,    /* 1 / (1 + exp(-x))  (fp32 stages)                                     */
+  AST_SE_BEGIN = 15,   /* squeeze-and-excitation: remembers the current image tensor x; must be
+                          followed by AST_GLOBAL_AVGPOOL; the layers up to AST_SE_SCALE compute
+                          a gate [B][C] from the pooled vector                                 */
+  AST_SE_SCALE = 16    /* y[b][c][h][w] = x[b][c][h][w] * gate[b][c], x from the matching
+                          AST_SE_BEGIN; the gradient reaches x through the product and through
+                          the gate                                                             */
 } ast_layer_kind;
 
 typedef struct {

@@ -121,7 +121,13 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       else act_fwd_f32(st, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out), I.elems, op.act);
       break;
     case OP_RES_BEGIN:
+    case OP_SE_BEGIN:
       break;
+    case OP_SE_SCALE: {
+      const Act& X = s.acts[op.skip];
+      se_scale_fwd_f32(st, (cf)act_ptr(c, op.skip), (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out), X.n * X.c, X.h * X.w);
+      break;
+    }
     case OP_RES_ADD:
       if (s.bf16) add_bf16(st, (cb)act_ptr(c, op.in), (cb)act_ptr(c, op.skip), (bf16_t*)act_ptr(c, op.out), I.elems);
       else add_f32(st, (cf)act_ptr(c, op.in), (cf)act_ptr(c, op.skip), (float*)act_ptr(c, op.out), I.elems);
@@ -284,6 +290,14 @@ void bwd_op(Ctx& c, const Op& op) {
       else
         act_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), (float*)gin, I.elems, op.act);
       break;
+    case OP_SE_BEGIN:  // both gradients of the tensor are already in its buffer (OP_SE_SCALE, then the pool)
+      break;
+    case OP_SE_SCALE: {
+      const Act& X = s.acts[op.skip];
+      se_scale_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.skip), (cf)act_ptr(c, op.in), (float*)gin,
+                       (float*)grad_ptr(c, op.skip), X.n * X.c, X.h * X.w);
+      break;
+    }
     case OP_RES_BEGIN:
       if (op.noop_bwd || !gin || op.skip < 0) break;
       if (s.bf16) add_bf16(st, (cb)gin, (cb)grad_ptr(c, op.skip), (bf16_t*)gin, I.elems);
@@ -293,7 +307,7 @@ void bwd_op(Ctx& c, const Op& op) {
       if (gin && gin != grad_ptr(c, op.out)) copy_bytes(st, grad_ptr(c, op.out), gin, I.bytes);
       break;
     case OP_GAP:
-      if (gin) gap_bwd_f32(st, (cf)grad_ptr(c, op.out), (float*)gin, I.n * I.c, HW);
+      if (gin) gap_bwd_f32(st, (cf)grad_ptr(c, op.out), (float*)gin, I.n * I.c, HW, op.grad_accum);
       break;
     case OP_MAXPOOL:
       if (!gin) break;

@@ -186,7 +186,11 @@ void fill_zero(hipStream_t st, void* dst, size_t bytes);
 
 // Pooling
 void gap_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int HW);
-void gap_bwd_f32(hipStream_t st, const float* g, float* dx, int NC, int HW);
+void gap_bwd_f32(hipStream_t st, const float* g, float* dx, int NC, int HW, bool accumulate = false);
+// squeeze-and-excitation scale: y = x * gate[plane]; backward: dgate[plane] = sum dy*x, dx = dy * gate (dx may be NULL)
+void se_scale_fwd_f32(hipStream_t st, const float* x, const float* gate, float* y, int NC, int HW);
+void se_scale_bwd_f32(hipStream_t st, const float* dy, const float* x, const float* gate, float* dgate, float* dx,
+                      int NC, int HW);
 void maxpool_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int H, int W);
 void maxpool_bwd_f32(hipStream_t st, const float* g, const float* x, float* dx, int NC, int H, int W);
 

@@ -300,14 +300,45 @@ void channel_sum_acc_f32(hipStream_t st, const float* g, float* G, int N, int C,
 }
 
 // ============================================================== elementwise
+// swish and sigmoid exist only as standalone layers: the three-way apply_act / act_mask of the
+// fused kernels stay as they are
+__device__ __forceinline__ float sigmoid_f(float v) { return 1.f / (1.f + expf(-v)); }
+__device__ __forceinline__ float act_value(float v, int act) {
+  if (act == ACT_SWISH) return v * sigmoid_f(v);
+  if (act == ACT_SIGMOID) return sigmoid_f(v);
+  return apply_act(v, act);
+}
+// derivative of the activation at pre-activation v
+__device__ __forceinline__ float act_slope(float v, int act) {
+  if (act == ACT_SWISH) { const float s = sigmoid_f(v); return s + v * s * (1.f - s); }
+  if (act == ACT_SIGMOID) { const float s = sigmoid_f(v); return s * (1.f - s); }
+  return act_mask(v, act);
+}
 __global__ void act_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, size_t n, int act) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) y[i] = apply_act(x[i], act);
+  if (i < n) y[i] = act_value(x[i], act);
 }
 __global__ void act_bwd_kernel(const float* __restrict__ g, const float* __restrict__ x,
                                float* __restrict__ dx, size_t n, int act) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) dx[i] = g[i] * act_mask(x[i], act);
+  if (i < n) dx[i] = g[i] * act_slope(x[i], act);
+}
+// four elements per thread (n4 = n / 4 whole float4; buffers are 256-byte aligned arena slices)
+__global__ void act_fwd4_kernel(const float4* __restrict__ x, float4* __restrict__ y, size_t n4, int act) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  float4 v = x[i];
+  v.x = act_value(v.x, act); v.y = act_value(v.y, act); v.z = act_value(v.z, act); v.w = act_value(v.w, act);
+  y[i] = v;
+}
+__global__ void act_bwd4_kernel(const float4* __restrict__ g, const float4* __restrict__ x, float4* __restrict__ dx,
+                                size_t n4, int act) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  const float4 v = x[i];
+  float4 d = g[i];
+  d.x *= act_slope(v.x, act); d.y *= act_slope(v.y, act); d.z *= act_slope(v.z, act); d.w *= act_slope(v.w, act);
+  dx[i] = d;
 }
 // y may alias a (in-place accumulation of a skip gradient): no __restrict__ here
 __global__ void add_kernel(const float* a, const float* b, float* y, size_t n) {
@@ -330,11 +361,19 @@ __global__ void zero16_kernel(uint4* __restrict__ d, size_t n16, unsigned char* 
   size_t t = tail0 + i;
   if (i < 16 && t < bytes) db[t] = 0;
 }
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 void act_fwd_f32(hipStream_t st, const float* x, float* y, size_t n, int act) {
-  KLAUNCH(act_fwd_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, x, y, n, act);
+  if (n % 4 == 0 && n >= 4096 && aligned16(x) && aligned16(y))
+    KLAUNCH(act_fwd4_kernel, dim3(cdiv(n / 4, 256)), dim3(256), 0, st, (const float4*)x, (float4*)y, n / 4, act);
+  else
+    KLAUNCH(act_fwd_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, x, y, n, act);
 }
 void act_bwd_f32(hipStream_t st, const float* g, const float* x, float* dx, size_t n, int act) {
-  KLAUNCH(act_bwd_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, g, x, dx, n, act);
+  if (n % 4 == 0 && n >= 4096 && aligned16(g) && aligned16(x) && aligned16(dx))
+    KLAUNCH(act_bwd4_kernel, dim3(cdiv(n / 4, 256)), dim3(256), 0, st, (const float4*)g, (const float4*)x, (float4*)dx,
+            n / 4, act);
+  else
+    KLAUNCH(act_bwd_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, g, x, dx, n, act);
 }
 void add_f32(hipStream_t st, const float* a, const float* b, float* y, size_t n) {
   KLAUNCH(add_kernel, dim3(cdiv(n, 256)), dim3(256), 0, st, a, b, y, n);
@@ -374,9 +413,79 @@ __global__ void gap_bwd_kernel(const float* __restrict__ g, float* __restrict__ 
 void gap_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int HW) {
   KLAUNCH(gap_fwd_kernel, dim3(cdiv(NC, 4)), dim3(256), 0, st, x, y, NC, HW);
 }
-void gap_bwd_f32(hipStream_t st, const float* g, float* dx, int NC, int HW) {
+__global__ void gap_bwd_acc_kernel(const float* __restrict__ g, float* __restrict__ dx, size_t total, int HW) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total) dx[i] += g[i / HW] / (float)HW;
+}
+void gap_bwd_f32(hipStream_t st, const float* g, float* dx, int NC, int HW, bool accumulate) {
   size_t total = (size_t)NC * HW;
-  KLAUNCH(gap_bwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, dx, total, HW);
+  if (accumulate) KLAUNCH(gap_bwd_acc_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, dx, total, HW);
+  else KLAUNCH(gap_bwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, dx, total, HW);
+}
+
+// ============================================================== squeeze-and-excitation scale
+// y[plane][p] = x[plane][p] * gate[plane]; one wavefront per plane (sample, channel), four per block
+__global__ __launch_bounds__(256) void se_scale_fwd_kernel(const float* __restrict__ x, const float* __restrict__ gate,
+                                                           float* __restrict__ y, int NC, int HW) {
+  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (plane >= NC) return;
+  const float gt = gate[plane];
+  const float* xp = x + (size_t)plane * HW;
+  float* yp = y + (size_t)plane * HW;
+  if ((HW & 3) == 0) {
+    const float4* x4 = reinterpret_cast<const float4*>(xp);
+    float4* y4 = reinterpret_cast<float4*>(yp);
+    for (int p = lane; p < HW / 4; p += 64) {
+      float4 v = x4[p];
+      v.x *= gt; v.y *= gt; v.z *= gt; v.w *= gt;
+      y4[p] = v;
+    }
+  } else {
+    for (int p = lane; p < HW; p += 64) yp[p] = xp[p] * gt;
+  }
+}
+// dgate[plane] = sum_p dy*x;  dx[plane][p] = dy[plane][p] * gate[plane]  (dx may be NULL)
+__global__ __launch_bounds__(256) void se_scale_bwd_kernel(const float* __restrict__ dy, const float* __restrict__ x,
+                                                           const float* __restrict__ gate, float* __restrict__ dgate,
+                                                           float* __restrict__ dx, int NC, int HW) {
+  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (plane >= NC) return;
+  const float gt = gate[plane];
+  const float* gp = dy + (size_t)plane * HW;
+  const float* xp = x + (size_t)plane * HW;
+  float* dp = dx ? dx + (size_t)plane * HW : nullptr;
+  float acc = 0.f;
+  if ((HW & 3) == 0) {
+    const float4* g4 = reinterpret_cast<const float4*>(gp);
+    const float4* x4 = reinterpret_cast<const float4*>(xp);
+    float4* d4 = reinterpret_cast<float4*>(dp);
+    for (int p = lane; p < HW / 4; p += 64) {
+      float4 g = g4[p];
+      const float4 v = x4[p];
+      acc += g.x * v.x + g.y * v.y + g.z * v.z + g.w * v.w;
+      if (dp) {
+        g.x *= gt; g.y *= gt; g.z *= gt; g.w *= gt;
+        d4[p] = g;
+      }
+    }
+  } else {
+    for (int p = lane; p < HW; p += 64) {
+      const float g = gp[p];
+      acc += g * xp[p];
+      if (dp) dp[p] = g * gt;
+    }
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) dgate[plane] = acc;
+}
+void se_scale_fwd_f32(hipStream_t st, const float* x, const float* gate, float* y, int NC, int HW) {
+  KLAUNCH(se_scale_fwd_kernel, dim3(cdiv(NC, 4)), dim3(256), 0, st, x, gate, y, NC, HW);
+}
+void se_scale_bwd_f32(hipStream_t st, const float* dy, const float* x, const float* gate, float* dgate, float* dx,
+                      int NC, int HW) {
+  KLAUNCH(se_scale_bwd_kernel, dim3(cdiv(NC, 4)), dim3(256), 0, st, dy, x, gate, dgate, dx, NC, HW);
 }
 
 __device__ __forceinline__ int first_argmax4(float a, float b, float c, float d) {

@@ -50,6 +50,8 @@ ast_status build_plan(Stage& s, std::string& err) {
   s.layer_act.assign(nl, -1);
   std::vector<int> res_stack;      // activation ids of open RES_BEGINs
   std::vector<int> res_op_stack;   // op indices of those RES_BEGINs
+  std::vector<int> se_stack;       // activation ids of open SE_BEGINs
+  bool se_opens = false;           // the previous layer was an SE_BEGIN
   size_t poff = 0, aux = 0, run = 0, shadow = 0;
   auto take_aux = [&](Op& op, size_t bytes) { op.aux_off = aux; op.aux_bytes = bytes; aux = align_up(aux + bytes, 256); };
 
@@ -116,11 +118,33 @@ ast_status build_plan(Stage& s, std::string& err) {
         }
         break;
       }
-      case AST_RELU: case AST_RELU6: case AST_GELU: {
+      case AST_RELU: case AST_RELU6: case AST_GELU: case AST_SWISH: case AST_SIGMOID: {
         op.kind = OP_ACT;
-        op.act = L.kind == AST_RELU ? 1 : (L.kind == AST_RELU6 ? 2 : 3);
+        op.act = L.kind == AST_RELU ? 1 : L.kind == AST_RELU6 ? 2 : L.kind == AST_GELU ? 3 : L.kind == AST_SWISH ? 4 : 5;
         if (!s.bf16 && op.act == 3) { err = fmt("layer %d: GELU is bf16-only", i); return AST_EUNSUPPORTED; }
+        if (s.bf16 && op.act > 3) { err = fmt("layer %d: swish / sigmoid are fp32-only", i); return AST_EUNSUPPORTED; }
         op.out = cur = new_act(s, A.n, A.c, A.h, A.w, A.rank, i, es);
+        break;
+      }
+      case AST_SE_BEGIN: {
+        if (s.bf16 || A.rank != 4) { err = fmt("layer %d: SE_BEGIN needs an fp32 image tensor", i); return AST_EUNSUPPORTED; }
+        if (i + 1 >= nl || s.layers[i + 1].kind != AST_GLOBAL_AVGPOOL) {
+          err = fmt("layer %d: SE_BEGIN must be followed by GLOBAL_AVGPOOL", i); return AST_EINVAL; }
+        op.kind = OP_SE_BEGIN; op.out = cur;
+        se_stack.push_back(cur);
+        se_opens = true;
+        s.layer_act[i] = -1;
+        s.ops.push_back(op);
+        continue;
+      }
+      case AST_SE_SCALE: {
+        if (se_stack.empty()) { err = fmt("layer %d: SE_SCALE without SE_BEGIN", i); return AST_EINVAL; }
+        const Act& X = s.acts[se_stack.back()];
+        if (A.rank != 2 || A.n != X.n || A.c != X.c) {
+          err = fmt("layer %d: SE_SCALE needs a gate [B][%d]", i, X.c); return AST_EINVAL; }
+        op.kind = OP_SE_SCALE; op.skip = se_stack.back();
+        se_stack.pop_back();
+        op.out = cur = new_act(s, X.n, X.c, X.h, X.w, 4, i, es);
         break;
       }
       case AST_RES_BEGIN: {
@@ -144,6 +168,8 @@ ast_status build_plan(Stage& s, std::string& err) {
       case AST_GLOBAL_AVGPOOL: {
         if (s.bf16 || A.rank != 4) { err = fmt("layer %d: global avg-pool needs an fp32 image tensor", i); return AST_EUNSUPPORTED; }
         op.kind = OP_GAP;
+        op.grad_accum = se_opens;  // the pooled tensor is also scaled by the gate: two gradients meet
+        se_opens = false;
         op.out = cur = new_act(s, B, A.c, 1, 1, 2, i, es);
         break;
       }
@@ -248,6 +274,7 @@ ast_status build_plan(Stage& s, std::string& err) {
     s.ops.push_back(op);
   }
   if (!res_stack.empty()) { err = "RES_BEGIN without RES_ADD"; return AST_EINVAL; }
+  if (!se_stack.empty()) { err = "SE_BEGIN without SE_SCALE"; return AST_EINVAL; }
   if (s.ops.empty()) { err = "empty stage"; return AST_EINVAL; }
   s.nparams = poff;
   s.running_floats = run;

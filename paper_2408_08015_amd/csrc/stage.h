@@ -18,7 +18,9 @@ enum OpKind {
   OP_CONV_DIRECT,  // fp32 generic conv
   OP_CONV_IGEMM,   // bf16 NHWC implicit-GEMM conv (+bias, +ReLU)
   OP_BN,           // BatchNorm (+ReLU/ReLU6) (+residual add)
-  OP_ACT,          // standalone ReLU / ReLU6 / GELU
+  OP_ACT,          // standalone ReLU / ReLU6 / GELU / swish / sigmoid
+  OP_SE_BEGIN,     // squeeze-and-excitation: marks the tensor that OP_SE_SCALE multiplies by its gate
+  OP_SE_SCALE,     // in = gate [B][C], skip = the image tensor of the matching OP_SE_BEGIN
   OP_RES_BEGIN,
   OP_RES_ADD,
   OP_GAP,
@@ -63,6 +65,8 @@ struct Op {
                                       // gradient is masked by it in the epilogue
   bool relu_bwd_fused = false;        // conv+ReLU whose ReLU backward the consumer already applied
   bool noop_bwd = false;              // RES_BEGIN whose add was fused into the next dgrad
+  bool grad_accum = false;            // global average pool that opens a squeeze-and-excitation branch: its input
+                                      // gradient is added to the one OP_SE_SCALE has already written
   size_t sh_off = 0, sh2_off = 0;     // bf16 weight copies (elements) in the shadow arena
   size_t wp_off = 0, wp2_off = 0;     // fp32 pointwise conv: packed forward / dgrad operands (floats)
   size_t sc_off = 0;                  // this op's private scratch region (bytes past scratch_off)

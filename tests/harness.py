@@ -110,8 +110,8 @@ def score(cfg, hip, ora):
             out["r%d.loss" % r] = abs(h["loss"] - o["loss"]) / abs(o["loss"])
         gw = [(n, rel_l2(a, b)) for (n, a), (_, b) in zip(split_params(cfg.layers, h["G"]), split_params(cfg.layers, o["G"]))]
         ww = [(n, rel_l2(a, b)) for (n, a), (_, b) in zip(split_params(cfg.layers, h["W"]), split_params(cfg.layers, o["W"]))]
-        out["r%d.G" % r] = max(gw, key=lambda t: t[1])
-        out["r%d.W" % r] = max(ww, key=lambda t: t[1])
+        out["r%d.G" % r] = max(gw, key=lambda t: t[1], default=("-", 0.0))   # no parameters: nothing to score
+        out["r%d.W" % r] = max(ww, key=lambda t: t[1], default=("-", 0.0))
         out["r%d.G_all" % r] = gw
     return out
 

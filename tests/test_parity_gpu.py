@@ -41,7 +41,7 @@ def check(cfg, tol_y=TOL_ACT, tol_g=TOL_GRAD, K=1, rounds=2):
     # gradients that are exactly zero in exact arithmetic (a BatchNorm beta feeding another
     # BatchNorm through a linear map) are scored against the overall gradient scale
     for r in range(rounds):
-        g_rms = float(np.sqrt(np.mean(ora[r]["G"] ** 2)))
+        g_rms = float(np.sqrt(np.mean(ora[r]["G"] ** 2))) if ora[r]["G"].size else 0.0
         worst = 0.0
         for (name, hv), (_, ov) in zip(harness.split_params(cfg.layers, hip[r]["G"]),
                                        harness.split_params(cfg.layers, ora[r]["G"])):
@@ -179,6 +179,56 @@ def test_cfg3_small(A):
     # gradients whatever the implementation (PyTorch CPU fp32 shows 4e-3 median / 1.2e-2 max
     # on this very input); the forward is well conditioned.
     check(C.cfg3(B=8, M=2, hw=96, num_classes=24), tol_y=1e-4, tol_g=5e-2, rounds=1)
+
+
+# ------------------------------------------------------------------ EfficientNet blocks (Table 4 workload)
+@pytest.mark.parametrize("kind", ["swish", "sigmoid"])
+@pytest.mark.parametrize("shape,B", [((8, 6, 6), 3), ((16, 32, 32), 4), ((5, 7, 3), 1)])
+def test_swish_sigmoid(A, kind, shape, B):
+    check(one([simple(kind)], shape, B=B), rounds=1)
+
+
+@pytest.mark.parametrize("c,cr,hw,B", [(24, 6, 10, 3), (144, 6, 30, 2), (16, 4, 7, 2), (8, 1, 1, 4), (40, 10, 8, 1)])
+@pytest.mark.parametrize("need_dx", [True, False])
+def test_squeeze_excite(A, c, cr, hw, B, need_dx):
+    """The block alone: the tensor at se_begin gets its gradient from the product and from the gate."""
+    check(one(C.squeeze_excite(c, cr), (c, hw, hw), B=B, needs_input_grad=need_dx), rounds=1)
+
+
+def test_squeeze_excite_behind_a_layer_and_in_a_residual_block(A):
+    L = [conv(8, 16, 1), bn(16), simple("swish")] + C.squeeze_excite(16, 4) + [conv(16, 8, 1), bn(8)]
+    check(one(L, (8, 9, 9), B=3), rounds=1)
+    check(one([simple("res_begin")] + L + [simple("res_add")], (8, 9, 9), B=3), rounds=1)
+
+
+@pytest.mark.parametrize("cin,cout,k,stride,expand,hw,B", [
+    (16, 16, 3, 1, 6, 12, 3),      # residual, 3x3 depthwise (register-window kernels, BatchNorm statistics fused)
+    (16, 24, 5, 2, 6, 12, 2),      # the 5x5 stride-2 block that opens cfg6's group
+    (40, 40, 5, 1, 6, 15, 2),      # residual 5x5
+    (32, 16, 3, 1, 1, 8, 3),       # no expansion conv
+])
+def test_mbconv(A, cin, cout, k, stride, expand, hw, B):
+    check(one(C.mbconv(cin, cout, k, stride, expand), (cin, hw, hw), B=B), rounds=1)
+
+
+def test_cfg6_small(A):
+    check(C.cfg6(B=3, M=2, hw=12), rounds=1)
+    check(C.cfg6(B=2, M=3, hw=20), rounds=1, K=2)
+
+
+def test_se_rejects_malformed_blocks(A):
+    with pytest.raises(A.AsteroidError) as e:
+        A.Stage([simple("se_begin"), simple("swish"), simple("se_scale")], 2, 1, 1, (8, 4, 4))
+    assert e.value.status == -1
+    with pytest.raises(A.AsteroidError) as e:
+        A.Stage([simple("se_begin"), simple("global_avgpool"), linear(8, 4), simple("se_scale")], 2, 1, 1, (8, 4, 4))
+    assert e.value.status == -1                          # gate has 4 channels, the tensor 8
+    with pytest.raises(A.AsteroidError) as e:
+        A.Stage([simple("se_begin"), simple("global_avgpool")], 2, 1, 1, (8, 4, 4))
+    assert e.value.status == -1
+    with pytest.raises(A.AsteroidError) as e:
+        A.Stage([simple("global_avgpool"), simple("se_scale")], 2, 1, 1, (8, 4, 4))
+    assert e.value.status == -1
 
 
 @pytest.mark.parametrize("beta", [1, 3])
@@ -331,6 +381,10 @@ def test_cfg2_full_golden(A):
     # gradient, 5e-3 bounds every parameter tensor.
     sc = golden_check("cfg2", 1e-4, 1e-3, 5e-3, 5e-3)
     assert sc["G_median"] <= 1e-3
+
+
+def test_cfg6_full_golden(A):
+    golden_check("cfg6", 1e-4, 1e-3, 1e-3, 1e-3)
 
 
 def test_cfg3_full_golden(A):
