@@ -78,10 +78,11 @@ def boundary_shape(layout, per_sample, n):
     raise ValueError(layout)
 
 
-def out_shape(layers, in_shape):
-    """Per-sample logical output shape of the stage ((C,H,W), (S,D) or (classes,))."""
+def layer_shapes(layers, in_shape):
+    """Per-sample logical output shape of every layer ((C,H,W), (S,D) or (classes,))."""
     s = tuple(in_shape)
     se = []
+    shapes = []
     for L in layers:
         k = L["kind"]
         if k == "se_begin":
@@ -99,7 +100,14 @@ def out_shape(layers, in_shape):
             s = (s[0],)
         elif k == "linear":
             s = s[:-1] + (L["cout"],)
-    return s
+        shapes.append(s)
+    return shapes
+
+
+def out_shape(layers, in_shape):
+    """Per-sample logical output shape of the stage."""
+    shapes = layer_shapes(layers, in_shape)
+    return shapes[-1] if shapes else tuple(in_shape)
 
 
 def make_inputs(cfg, randomize_affine=False):

@@ -66,6 +66,7 @@ def kernel_model(cfg):
     # 32- and 128-pixel-wavefront kernels while there are at most 256 pixel blocks
     stat_bn = set()
     shp = tuple(cfg.in_shape)
+    outs = gen.layer_shapes(cfg.layers, cfg.in_shape)
     for i, L in enumerate(cfg.layers):
         if L["kind"] == "conv2d" and cfg.dtype == "f32" and L["k"] == 1 and L["groups"] == 1 and not L.get("bias", False) \
                 and i + 1 < len(kinds) and kinds[i + 1] == "batchnorm2d" and (i + 1) not in given_bn:
@@ -74,10 +75,10 @@ def kernel_model(cfg):
             parts = _cdiv(nq_, 512) if (hw_ % 4 == 0 and nq_ >= 65536) else _cdiv(nq_, 128)
             if ks and parts <= 256:
                 stat_bn.add(i + 1)
-        shp = gen.out_shape([L], shp)
+        shp = outs[i]
     for i, L in enumerate(cfg.layers):
         k = L["kind"]
-        oshape = gen.out_shape([L], shape)
+        oshape = outs[i]
         if k == "res_begin":
             res_open = True
         if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 1 and L["groups"] == 1:
@@ -108,6 +109,12 @@ def kernel_model(cfg):
                     out.setdefault("pw_bwd_dual_kernel<%s>" % bc, []).append(4 * (2 * cin + cout) * nq + extra)
             else:
                 out.setdefault(wg_name, []).append(4 * (cin + cout) * nq)                   # g and x in
+        if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 5 and L["groups"] == L["cin"] == L["cout"]:
+            c, h, w = shape
+            oc, oh, ow = oshape
+            out.setdefault("dwk_fwd_f32_kernel<s%d>" % L["stride"], []).append(4 * B * (c * h * w + oc * oh * ow))
+            # upstream gradient and input in, input gradient out
+            out.setdefault("dwk_bwd_f32_kernel<s%d>" % L["stride"], []).append(4 * B * (2 * c * h * w + oc * oh * ow))
         if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == L["cin"] == L["cout"]:
             oc, oh, ow = oshape
             if _dw_vw(shape[1], shape[2], L["stride"]):
@@ -211,6 +218,8 @@ def kernel_bound(name):
 def dominant_kernel(cfg, workload):
     """(kernel-name filter, bound, algorithmic units per launch averaged over one round's
     launches of that kernel, unit)."""
+    if workload not in DOMINANT:
+        return None
     name, bound = DOMINANT[workload]
     units = kernel_model(cfg).get(name)
     if not units:

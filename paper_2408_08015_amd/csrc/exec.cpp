@@ -89,6 +89,10 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
                     op.bn_out_op >= 0 ? reinterpret_cast<double*>(scratch(c, s.ops[op.bn_out_op])) : nullptr);
       break;
     }
+    case OP_CONV_DWK:
+      dwk_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, (float*)act_ptr(c, op.out), I.n, I.c, I.h, I.w, op.k,
+                  op.stride);
+      break;
     case OP_CONV_DIRECT:
       conv_direct_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, op.has_bias ? s.W + op.b_off : nullptr,
                           (float*)act_ptr(c, op.out), I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride,
@@ -233,6 +237,10 @@ void bwd_op(Ctx& c, const Op& op) {
                     s.red_nblocks ? nullptr : s.G + op.w_off, I.n, I.c, I.h, I.w, op.stride, &f);
       break;
     }
+    case OP_CONV_DWK:
+      dwk_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), s.W + op.w_off, (float*)gin,
+                  reinterpret_cast<float*>(scratch(c, op)), s.G + op.w_off, I.n, I.c, I.h, I.w, op.k, op.stride);
+      break;
     case OP_CONV_DIRECT: {
       cf g = (cf)grad_ptr(c, op.out);
       const Act& O = s.acts[op.out];

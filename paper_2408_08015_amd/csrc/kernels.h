@@ -75,6 +75,15 @@ size_t dw3x3_bwd_f32_ws(int N, int C, int H, int W, int stride);
 // sums): one per sample, or several where a plane is split into bands of rows over wavefronts.
 int dw3x3_parts(int N, int C, int H, int W, int stride);
 bool dw3x3_supported(int H, int W, int stride);  // else the generic grouped-conv kernels apply
+// Depthwise K x K (K = 5), pad K/2, stride 1 or 2, no bias: one block per plane, taps from LDS.
+// Backward: dx (may be NULL), and G[C][K][K] += weight gradient through `part`
+// (dwk_bwd_f32_ws floats of scratch: one K*K partial per plane, added over the samples in order).
+bool dwk_supported(int K, int H, int W, int stride);
+size_t dwk_bwd_f32_ws(int N, int C, int K);
+void dwk_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int N, int C, int H, int W, int K,
+                 int stride);
+void dwk_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part, float* G,
+                 int N, int C, int H, int W, int K, int stride);
 struct DwBands {
   int bands, rpb;  // bands per plane, rows per band
 };

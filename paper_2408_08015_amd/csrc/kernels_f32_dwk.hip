@@ -1,0 +1,276 @@
+// fp32 depthwise 5x5 convolution ('same' padding 2, stride 1 or 2) for the 5x5 blocks of the
+// EfficientNet workload (Table 4): one block per plane (sample, channel), the zero-padded plane
+// staged once in LDS so that the taps of an output are LDS reads.  A thread owns a strip of four
+// consecutive outputs of a row: its 5 x 8 (stride 2: 5 x 11) window is read as 16-byte LDS words
+// and feeds 100 multiply-adds.  The backward pass stages the plane of x and of the upstream
+// gradient, forms the plane's 25 weight-gradient sums (same strips) and the input gradient in gather
+// form (stride 1: the same strips with the flipped kernel over the zero-padded gradient; stride 2:
+// a thread owns a 2 x 2 quad of dx, whose four parity classes together use each weight once on a
+// 3 x 3 window of g) -- no atomics; a second small launch adds the per-plane sums over the samples
+// into G in a fixed order.
+//
+// HBM-bound by design: every tensor is read or written once per pass (x and y forward; g, x and dx
+// backward).
+#include <algorithm>
+
+#include "device_utils.h"
+#include "kernels.h"
+#include "prof.h"
+
+namespace ast {
+
+namespace {
+
+constexpr int K = 5, P = 2, KK = 25;
+constexpr int DWK_LDS_LIMIT = 60 * 1024;
+
+inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+inline int up4(int v) { return (v + 3) & ~3; }
+
+// Geometry of one plane in LDS.  x: H+4 rows of WX floats, image at (2, 2); every strip window
+// (columns j0*stride .. j0*stride + 3*stride + 4, read as whole 16-byte words) stays inside a row.
+// g: halo PG (stride 1: 2, for the flipped-kernel strips; stride 2: 1, for the quads), rows of WG.
+struct DwkGeom {
+  int C, H, W, Ho, Wo, stride;
+  int SWo;  // strips per output row
+  int SWx;  // stride 1: strips per dx row
+  int WX, WG, PG, HG;
+};
+
+inline DwkGeom dwk_geom(int C, int H, int W, int stride) {
+  DwkGeom g;
+  g.C = C; g.H = H; g.W = W; g.stride = stride;
+  g.Ho = (H - 1) / stride + 1;
+  g.Wo = (W - 1) / stride + 1;
+  g.SWo = cdiv(g.Wo, 4);
+  g.SWx = cdiv(W, 4);
+  g.WX = up4(std::max(W + K - 1, (g.SWo * 4 - 1) * stride + K + (stride == 2 ? 1 : 0)));
+  g.PG = stride == 1 ? P : 1;
+  g.HG = g.Ho + 2 * g.PG;
+  // stride 1: dx strips read columns j0 .. j0 + 7 of the padded gradient; weight-gradient strips read g[i][j0 .. j0+3]
+  g.WG = up4(std::max(g.Wo + 2 * g.PG, stride == 1 ? g.SWx * 4 + 4 : g.SWo * 4 + g.PG));
+  return g;
+}
+inline size_t x_floats(const DwkGeom& g) { return (size_t)(g.H + K - 1) * g.WX; }
+inline size_t g_floats(const DwkGeom& g) { return (size_t)g.HG * g.WG; }
+
+// rows x width floats at `sh`, image h x w placed at (pad, pad), zero elsewhere
+__device__ __forceinline__ void stage_plane(const float* __restrict__ src, float* __restrict__ sh, int h, int w, int rows,
+                                            int width, int pad) {
+  for (int i = threadIdx.x; i < rows * width; i += 256) {
+    const int r = i / width, q = i - r * width;
+    const int hr = r - pad, wq = q - pad;
+    float v = 0.f;
+    if (hr >= 0 && hr < h && wq >= 0 && wq < w) v = src[(size_t)hr * w + wq];
+    sh[i] = v;
+  }
+}
+
+// NW 16-byte words of a row
+template <int NW>
+__device__ __forceinline__ void read_row(const float* __restrict__ p, float (&r)[NW * 4]) {
+#pragma unroll
+  for (int k = 0; k < NW; ++k) {
+    const float4 v = *reinterpret_cast<const float4*>(p + 4 * k);
+    r[4 * k] = v.x; r[4 * k + 1] = v.y; r[4 * k + 2] = v.z; r[4 * k + 3] = v.w;
+  }
+}
+
+__device__ __forceinline__ void store_strip(float* __restrict__ row, int j0, int n, const float (&o)[4]) {
+  if (((n & 3) == 0)) {  // rows are multiples of four floats: the strip is one aligned 16-byte word
+    *reinterpret_cast<float4*>(row + j0) = make_float4(o[0], o[1], o[2], o[3]);
+  } else {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (j0 + q < n) row[j0 + q] = o[q];
+  }
+}
+
+template <int S>
+__global__ __launch_bounds__(256) void dwk_fwd_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                          float* __restrict__ y, DwkGeom gm) {
+  extern __shared__ __align__(16) float sh[];
+  constexpr int NW = S == 1 ? 2 : 3;
+  const int plane = blockIdx.x, c = plane % gm.C;
+  stage_plane(x + (size_t)plane * gm.H * gm.W, sh, gm.H, gm.W, gm.H + K - 1, gm.WX, P);
+  float wk[KK];
+#pragma unroll
+  for (int t = 0; t < KK; ++t) wk[t] = w[(size_t)c * KK + t];
+  __syncthreads();
+  float* yp = y + (size_t)plane * gm.Ho * gm.Wo;
+  for (int sidx = threadIdx.x; sidx < gm.Ho * gm.SWo; sidx += 256) {
+    const int i = sidx / gm.SWo, j0 = (sidx - i * gm.SWo) * 4;
+    float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+      float r[NW * 4];
+      read_row<NW>(sh + (i * S + u) * gm.WX + j0 * S, r);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int v = 0; v < K; ++v) o[q] += wk[u * K + v] * r[q * S + v];
+    }
+    store_strip(yp + (size_t)i * gm.Wo, j0, gm.Wo, o);
+  }
+}
+
+// LDS: [x plane][g plane][4 wavefronts x 25 partial sums].  Block (c, group): the planes of channel c of
+// the samples group*NB .. group*NB + NB - 1, one after the other; the 25 weight-gradient sums stay in
+// registers across them, so their reduction over the block is paid once per NB planes.
+template <int S>
+__global__ __launch_bounds__(256) void dwk_bwd_f32_kernel(const float* __restrict__ g, const float* __restrict__ x,
+                                                          const float* __restrict__ w, float* __restrict__ dx,
+                                                          float* __restrict__ part, DwkGeom gm, int N, int NB) {
+  extern __shared__ __align__(16) float sh[];
+  constexpr int NW = S == 1 ? 2 : 3;
+  const int c = blockIdx.x, group = blockIdx.y;
+  float* shx = sh;
+  float* shg = sh + (gm.H + K - 1) * gm.WX;
+  float* shr = shg + gm.HG * gm.WG;
+  float wk[KK];
+#pragma unroll
+  for (int t = 0; t < KK; ++t) wk[t] = w[(size_t)c * KK + t];
+  float acc[KK];
+#pragma unroll
+  for (int t = 0; t < KK; ++t) acc[t] = 0.f;
+  const int n_end = min(N, (group + 1) * NB);
+  for (int n = group * NB; n < n_end; ++n) {
+    const size_t plane = (size_t)n * gm.C + c;
+    if (n != group * NB) __syncthreads();  // the previous plane has been consumed
+    stage_plane(x + plane * gm.H * gm.W, shx, gm.H, gm.W, gm.H + K - 1, gm.WX, P);
+    stage_plane(g + plane * gm.Ho * gm.Wo, shg, gm.Ho, gm.Wo, gm.HG, gm.WG, gm.PG);
+    __syncthreads();
+
+    // weight gradient: dW[u][v] += sum_{i,j} g[i][j] * x[i*S - 2 + u][j*S - 2 + v]
+    for (int sidx = threadIdx.x; sidx < gm.Ho * gm.SWo; sidx += 256) {
+      const int i = sidx / gm.SWo, j0 = (sidx - i * gm.SWo) * 4;
+      float gv[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) gv[q] = shg[(i + gm.PG) * gm.WG + gm.PG + j0 + q];  // zero beyond Wo
+#pragma unroll
+      for (int u = 0; u < K; ++u) {
+        float r[NW * 4];
+        read_row<NW>(shx + (i * S + u) * gm.WX + j0 * S, r);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int v = 0; v < K; ++v) acc[u * K + v] += gv[q] * r[q * S + v];
+      }
+    }
+
+    if (!dx) continue;
+    float* dp = dx + plane * gm.H * gm.W;
+    if (S == 1) {
+      // dx[i][j] = sum_{u,v} w[4-u][4-v] * gpad[i + u][j + v], gpad = g with a zero halo of two
+      for (int sidx = threadIdx.x; sidx < gm.H * gm.SWx; sidx += 256) {
+        const int i = sidx / gm.SWx, j0 = (sidx - i * gm.SWx) * 4;
+        float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < K; ++u) {
+          float r[8];
+          read_row<2>(shg + (i + u) * gm.WG + j0, r);
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int v = 0; v < K; ++v) o[q] += wk[(K - 1 - u) * K + (K - 1 - v)] * r[q + v];
+        }
+        store_strip(dp + (size_t)i * gm.W, j0, gm.W, o);
+      }
+    } else {
+      // quad (2a, 2b) .. (2a+1, 2b+1): dx[i][j] = sum over the taps u = i (mod 2), v = j (mod 2) of
+      // w[u][v] * g[(i + 2 - u) / 2][(j + 2 - v) / 2]; with gw[d][e] = g[a - 1 + d][b - 1 + e] (zero halo):
+      // even rows use u = 0, 2, 4 on d = 2, 1, 0; odd rows u = 1, 3 on d = 2, 1; columns alike
+      const int QH = (gm.H + 1) / 2, QW = (gm.W + 1) / 2;
+      for (int qidx = threadIdx.x; qidx < QH * QW; qidx += 256) {
+        const int a = qidx / QW, b = qidx - a * QW;
+        float gw[3][3];
+#pragma unroll
+        for (int d = 0; d < 3; ++d)
+#pragma unroll
+          for (int e = 0; e < 3; ++e) gw[d][e] = shg[(a + d) * gm.WG + b + e];
+        float oee = 0.f, oeo = 0.f, ooe = 0.f, ooo = 0.f;
+#pragma unroll
+        for (int u = 0; u < K; ++u)
+#pragma unroll
+          for (int v = 0; v < K; ++v) {
+            const int d = (u & 1) ? 2 - (u - 1) / 2 : 2 - u / 2;
+            const int e = (v & 1) ? 2 - (v - 1) / 2 : 2 - v / 2;
+            const float t = wk[u * K + v] * gw[d][e];
+            if (!(u & 1) && !(v & 1)) oee += t;
+            else if (!(u & 1)) oeo += t;
+            else if (!(v & 1)) ooe += t;
+            else ooo += t;
+          }
+        const int i = 2 * a, j = 2 * b;
+        dp[(size_t)i * gm.W + j] = oee;
+        if (j + 1 < gm.W) dp[(size_t)i * gm.W + j + 1] = oeo;
+        if (i + 1 < gm.H) {
+          dp[(size_t)(i + 1) * gm.W + j] = ooe;
+          if (j + 1 < gm.W) dp[(size_t)(i + 1) * gm.W + j + 1] = ooo;
+        }
+      }
+    }
+  }
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+  for (int t = 0; t < KK; ++t) {
+    const float s = wave_sum(acc[t]);
+    if (lane == 0) shr[wv * KK + t] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x < KK)
+    part[((size_t)group * gm.C + c) * KK + threadIdx.x] =
+        shr[threadIdx.x] + shr[KK + threadIdx.x] + shr[2 * KK + threadIdx.x] + shr[3 * KK + threadIdx.x];
+}
+
+// G[c][t] += sum over the N sample groups of part[group][c][t], in order
+__global__ void dwk_wgrad_final_kernel(const float* __restrict__ part, float* __restrict__ G, int N, int C) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= C * KK) return;
+  float s = 0.f;
+  for (int n = 0; n < N; ++n) s += part[(size_t)n * C * KK + idx];
+  G[idx] += s;
+}
+
+size_t fwd_lds(const DwkGeom& g) { return x_floats(g) * sizeof(float); }
+size_t bwd_lds(const DwkGeom& g) { return (x_floats(g) + g_floats(g) + 4 * KK) * sizeof(float); }
+
+}  // namespace
+
+bool dwk_supported(int k, int H, int W, int stride) {
+  if (k != K || (stride != 1 && stride != 2) || H < 1 || W < 1) return false;
+  return bwd_lds(dwk_geom(1, H, W, stride)) <= (size_t)DWK_LDS_LIMIT;
+}
+
+size_t dwk_bwd_f32_ws(int N, int C, int k) { return (size_t)N * C * k * k; }
+
+void dwk_fwd_f32(hipStream_t st, const float* x, const float* w, float* y, int N, int C, int H, int W, int k,
+                 int stride) {
+  (void)k;
+  const DwkGeom gm = dwk_geom(C, H, W, stride);
+  if (stride == 1)
+    KLAUNCH_NAMED("dwk_fwd_f32_kernel<s1>", (dwk_fwd_f32_kernel<1>), dim3(N * C), dim3(256), fwd_lds(gm), st, x, w, y, gm);
+  else
+    KLAUNCH_NAMED("dwk_fwd_f32_kernel<s2>", (dwk_fwd_f32_kernel<2>), dim3(N * C), dim3(256), fwd_lds(gm), st, x, w, y, gm);
+}
+
+// Samples per block of the backward kernel.  One: with several (the reduction of the 25 sums paid once
+// per block) the planes of a block queue behind one another and the launch measured 20 % slower.
+static int dwk_group(int N, int C) { (void)N; (void)C; return 1; }
+
+void dwk_bwd_f32(hipStream_t st, const float* g, const float* x, const float* w, float* dx, float* part, float* G,
+                 int N, int C, int H, int W, int k, int stride) {
+  (void)k;
+  const DwkGeom gm = dwk_geom(C, H, W, stride);
+  const int NB = dwk_group(N, C), groups = cdiv(N, NB);
+  const dim3 grid(C, groups);
+  if (stride == 1)
+    KLAUNCH_NAMED("dwk_bwd_f32_kernel<s1>", (dwk_bwd_f32_kernel<1>), grid, dim3(256), bwd_lds(gm), st, g, x, w, dx, part, gm,
+                  N, NB);
+  else
+    KLAUNCH_NAMED("dwk_bwd_f32_kernel<s2>", (dwk_bwd_f32_kernel<2>), grid, dim3(256), bwd_lds(gm), st, g, x, w, dx, part, gm,
+                  N, NB);
+  KLAUNCH(dwk_wgrad_final_kernel, dim3(cdiv(C * KK, 256)), dim3(256), 0, st, part, G, groups, C);
+}
+
+}  // namespace ast

@@ -88,6 +88,8 @@ ast_status build_plan(Stage& s, std::string& err) {
         } else if (k == 3 && pad == 1 && g == Cin && Cin == Cout && (st == 1 || st == 2) && !hb &&
                    dw3x3_supported(A.h, A.w, st)) {
           op.kind = OP_CONV_DW;
+        } else if (g == Cin && Cin == Cout && pad == k / 2 && !hb && dwk_supported(k, A.h, A.w, st)) {
+          op.kind = OP_CONV_DWK;
         } else {
           op.kind = OP_CONV_DIRECT;
         }
@@ -424,6 +426,7 @@ ast_status build_plan(Stage& s, std::string& err) {
     switch (op.kind) {
       case OP_CONV_PW: need = pw_wgrad_f32_ws(I.n, op.cin, op.cout, I.h * I.w) * sizeof(float); break;
       case OP_CONV_DW: need = dw3x3_bwd_f32_ws(I.n, I.c, I.h, I.w, op.stride) * sizeof(float); break;
+      case OP_CONV_DWK: need = dwk_bwd_f32_ws(I.n, I.c, op.k) * sizeof(float); break;
       case OP_CONV_DIRECT:
         need = conv_direct_wgrad_ws(I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride, op.pad, op.groups) * sizeof(float);
         break;

@@ -201,6 +201,22 @@ def test_squeeze_excite_behind_a_layer_and_in_a_residual_block(A):
     check(one([simple("res_begin")] + L + [simple("res_add")], (8, 9, 9), B=3), rounds=1)
 
 
+@pytest.mark.parametrize("c,h,w,stride,B", [
+    (144, 60, 60, 2, 2),     # cfg6's stride-2 plane
+    (240, 30, 30, 1, 2),     # cfg6's stride-1 plane
+    (16, 15, 15, 2, 3),      # odd size at stride 2
+    (8, 9, 7, 1, 2),         # not square
+    (8, 7, 9, 2, 2),
+    (24, 1, 1, 1, 4),        # a single pixel: only the centre tap
+    (4, 2, 3, 2, 3),
+    (2, 112, 112, 1, 1),     # plane too large for the LDS kernels: the generic grouped kernels take it
+])
+@pytest.mark.parametrize("need_dx", [True, False])
+def test_depthwise_5x5(A, c, h, w, stride, B, need_dx):
+    L = [conv(c, c, 5, stride, 2, groups=c)]
+    check(one(L, (c, h, w), B=B, needs_input_grad=need_dx), rounds=1)
+
+
 @pytest.mark.parametrize("cin,cout,k,stride,expand,hw,B", [
     (16, 16, 3, 1, 6, 12, 3),      # residual, 3x3 depthwise (register-window kernels, BatchNorm statistics fused)
     (16, 24, 5, 2, 6, 12, 2),      # the 5x5 stride-2 block that opens cfg6's group
