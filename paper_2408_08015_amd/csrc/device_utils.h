@@ -58,16 +58,34 @@ __device__ __forceinline__ float relu6f(float v) { return fminf(fmaxf(v, 0.f), 6
 // activation codes used by fused kernels
 enum : int { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3, ACT_SWISH = 4, ACT_SIGMOID = 5 };
 
+__device__ __forceinline__ float sigmoid_f(float v) { return 1.f / (1.f + expf(-v)); }
+// ReLU / ReLU6, the activations every fused kernel knows (`act` is uniform over a launch)
 __device__ __forceinline__ float apply_act(float v, int act) {
   if (act == ACT_RELU) return fmaxf(v, 0.f);
   if (act == ACT_RELU6) return relu6f(v);
   return v;
 }
-// derivative mask of the activation evaluated at pre-activation v (0 at the kinks)
+// derivative mask of the activation evaluated at pre-activation v (0 at the kinks); the activated
+// value gives the same answer
 __device__ __forceinline__ float act_mask(float v, int act) {
   if (act == ACT_RELU) return v > 0.f ? 1.f : 0.f;
   if (act == ACT_RELU6) return (v > 0.f && v < 6.f) ? 1.f : 0.f;
   return 1.f;
+}
+// ... and the variants of the kernels that also fuse swish (instantiated apart, so that the ReLU
+// kernels carry no exponential): value and derivative at pre-activation v
+template <bool SW>
+__device__ __forceinline__ float apply_act_sw(float v, int act) {
+  if (SW) return v * sigmoid_f(v);
+  return apply_act(v, act);
+}
+template <bool SW>
+__device__ __forceinline__ float act_slope_sw(float v, int act) {
+  if (SW) {
+    const float s = sigmoid_f(v);
+    return s + v * s * (1.f - s);
+  }
+  return act_mask(v, act);
 }
 
 }  // namespace ast

@@ -106,7 +106,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       float* aux = reinterpret_cast<float*>(c.slot + op.aux_off);
       double* ws = reinterpret_cast<double*>(scratch(c, op));
       cf x = (cf)act_ptr(c, op.in);
-      if (!op.bn_stats_given && !op.bn_lazy && bn_onepass_fits(I.n, HW)) {  // small tensor: one launch
+      if (!op.bn_stats_given && !op.bn_lazy && op.act != 4 && bn_onepass_fits(I.n, HW)) {  // small tensor: one launch
         bn_fwd_onepass_f32(st, x, s.W + op.w_off, s.W + op.b_off, op.skip >= 0 ? (cf)act_ptr(c, op.skip) : nullptr,
                            (float*)act_ptr(c, op.out), aux, aux + 2 * I.c, s.running + op.run_off, I.n, I.c, HW, op.eps,
                            op.act);
@@ -279,7 +279,7 @@ void bwd_op(Ctx& c, const Op& op) {
       // partial sums: left per plane by the backward of the depthwise conv behind (it ran just before), or
       // a pass of its own; input gradient: formed by the depthwise conv in front on load, or a pass of its own
       const bool given = op.bn_bwd_sums_given;
-      if (!given && !op.bn_bwd_apply_fused && bn_onepass_fits(I.n, HW)) {  // small tensor: one launch
+      if (!given && !op.bn_bwd_apply_fused && op.act != 4 && bn_onepass_fits(I.n, HW)) {  // small tensor: one launch
         bn_bwd_onepass_f32(st, g, x, aux, aux + 2 * I.c, s.W + op.w_off, (float*)gin, s.G + op.w_off, s.G + op.b_off, I.n,
                            I.c, HW, op.act);
         break;

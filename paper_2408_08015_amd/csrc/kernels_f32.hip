@@ -300,9 +300,7 @@ void channel_sum_acc_f32(hipStream_t st, const float* g, float* G, int N, int C,
 }
 
 // ============================================================== elementwise
-// swish and sigmoid exist only as standalone layers: the three-way apply_act / act_mask of the
-// fused kernels stay as they are
-__device__ __forceinline__ float sigmoid_f(float v) { return 1.f / (1.f + expf(-v)); }
+// the standalone activation layers also know swish and sigmoid
 __device__ __forceinline__ float act_value(float v, int act) {
   if (act == ACT_SWISH) return v * sigmoid_f(v);
   if (act == ACT_SIGMOID) return sigmoid_f(v);
@@ -310,7 +308,7 @@ __device__ __forceinline__ float act_value(float v, int act) {
 }
 // derivative of the activation at pre-activation v
 __device__ __forceinline__ float act_slope(float v, int act) {
-  if (act == ACT_SWISH) { const float s = sigmoid_f(v); return s + v * s * (1.f - s); }
+  if (act == ACT_SWISH) return act_slope_sw<true>(v, act);
   if (act == ACT_SIGMOID) { const float s = sigmoid_f(v); return s * (1.f - s); }
   return act_mask(v, act);
 }

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void bn_stats_partial_kernel(const float* __re
 }
 
 // y = act(x*scale + shift) (+ skip); grid (planes, chunks)
-template <bool VEC>
+template <bool VEC, bool SW = false>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__ x,
                                                        const double* __restrict__ ws,
                                                        const float* __restrict__ gamma,
@@ -139,10 +139,10 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
       const int e = e0 + 4 * threadIdx.x + 1024 * u;
       if (e < e1) {
         float4 v = xv[u];
-        v.x = apply_act(v.x * sc + sf, act);
-        v.y = apply_act(v.y * sc + sf, act);
-        v.z = apply_act(v.z * sc + sf, act);
-        v.w = apply_act(v.w * sc + sf, act);
+        v.x = apply_act_sw<SW>(v.x * sc + sf, act);
+        v.y = apply_act_sw<SW>(v.y * sc + sf, act);
+        v.z = apply_act_sw<SW>(v.z * sc + sf, act);
+        v.w = apply_act_sw<SW>(v.w * sc + sf, act);
         if (skip) {
           v.x += kv[u].x; v.y += kv[u].y; v.z += kv[u].z; v.w += kv[u].w;
         }
@@ -151,10 +151,10 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
     }
     for (int e = e0 + 4 * threadIdx.x + 4096; e < e1; e += 1024) {  // longer chunks (not produced by the launcher)
       float4 v = *reinterpret_cast<const float4*>(x + base + e);
-      v.x = apply_act(v.x * sc + sf, act);
-      v.y = apply_act(v.y * sc + sf, act);
-      v.z = apply_act(v.z * sc + sf, act);
-      v.w = apply_act(v.w * sc + sf, act);
+      v.x = apply_act_sw<SW>(v.x * sc + sf, act);
+      v.y = apply_act_sw<SW>(v.y * sc + sf, act);
+      v.z = apply_act_sw<SW>(v.z * sc + sf, act);
+      v.w = apply_act_sw<SW>(v.w * sc + sf, act);
       if (skip) {
         float4 k = *reinterpret_cast<const float4*>(skip + base + e);
         v.x += k.x; v.y += k.y; v.z += k.z; v.w += k.w;
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
     }
   } else {
     for (int e = e0 + threadIdx.x; e < e1; e += 256) {
-      float v = apply_act(x[base + e] * sc + sf, act);
+      float v = apply_act_sw<SW>(x[base + e] * sc + sf, act);
       if (skip) v += skip[base + e];
       y[base + e] = v;
     }
@@ -191,12 +191,18 @@ void bn_apply_f32(hipStream_t st, const float* x, const float* gamma, const floa
   int nchunks, chunk;
   bn_chunking(HW, nchunks, chunk);
   dim3 grid((unsigned)(N * C), nchunks);
-  if (HW % 4 == 0)
-    KLAUNCH(bn_apply_kernel<true>, grid, dim3(256), 0, st, x, ws, gamma, beta, skip, y, stat, scale_shift, running, C,
-            HW, P, (double)per, eps, act, chunk);
-  else
-    KLAUNCH(bn_apply_kernel<false>, grid, dim3(256), 0, st, x, ws, gamma, beta, skip, y, stat, scale_shift, running,
-            C, HW, P, (double)per, eps, act, chunk);
+#define BN_APPLY(name, kern)                                                                                          \
+  KLAUNCH_NAMED(name, kern, grid, dim3(256), 0, st, x, ws, gamma, beta, skip, y, stat, scale_shift, running, C, HW, P, \
+                (double)per, eps, act, chunk)
+  const bool sw = act == ACT_SWISH;  // the swish instantiations share the profile names of the others
+  if (HW % 4 == 0) {
+    if (sw) BN_APPLY("bn_apply_kernel<true>", (bn_apply_kernel<true, true>));
+    else BN_APPLY("bn_apply_kernel<true>", (bn_apply_kernel<true, false>));
+  } else {
+    if (sw) BN_APPLY("bn_apply_kernel<false>", (bn_apply_kernel<false, true>));
+    else BN_APPLY("bn_apply_kernel<false>", (bn_apply_kernel<false, false>));
+  }
+#undef BN_APPLY
 }
 
 void bn_fwd_f32(hipStream_t st, const float* x, const float* gamma, const float* beta, const float* skip,
@@ -206,7 +212,7 @@ void bn_fwd_f32(hipStream_t st, const float* x, const float* gamma, const float*
   bn_apply_f32(st, x, gamma, beta, skip, y, stat, scale_shift, running, ws, bn_parts(N, HW), N, C, HW, eps, act);
 }
 
-template <bool VEC>
+template <bool VEC, bool SW = false>
 __global__ __launch_bounds__(256) void bn_bwd_partial_kernel(const float* __restrict__ g,
                                                              const float* __restrict__ x,
                                                              const float* __restrict__ stat,
@@ -238,8 +244,8 @@ __global__ __launch_bounds__(256) void bn_bwd_partial_kernel(const float* __rest
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const float4 xv = xq[u], gv = gq[u];
-        float g0 = gv.x * act_mask(xv.x * sc + sf, act), g1 = gv.y * act_mask(xv.y * sc + sf, act);
-        float g2 = gv.z * act_mask(xv.z * sc + sf, act), g3 = gv.w * act_mask(xv.w * sc + sf, act);
+        float g0 = gv.x * act_slope_sw<SW>(xv.x * sc + sf, act), g1 = gv.y * act_slope_sw<SW>(xv.y * sc + sf, act);
+        float g2 = gv.z * act_slope_sw<SW>(xv.z * sc + sf, act), g3 = gv.w * act_slope_sw<SW>(xv.w * sc + sf, act);
         s1 += (g0 + g1) + (g2 + g3);
         s2 += (g0 * ((xv.x - mean) * istd) + g1 * ((xv.y - mean) * istd)) +
               (g2 * ((xv.z - mean) * istd) + g3 * ((xv.w - mean) * istd));
@@ -251,7 +257,7 @@ __global__ __launch_bounds__(256) void bn_bwd_partial_kernel(const float* __rest
       const int nl = idx / len, e = e0 + idx - nl * len;
       const size_t off = ((size_t)(n0 + nl) * C + c) * HW + e;
       float xv = x[off];
-      float gv = g[off] * act_mask(xv * sc + sf, act);
+      float gv = g[off] * act_slope_sw<SW>(xv * sc + sf, act);
       s1 += gv;
       s2 += gv * ((xv - mean) * istd);
     }
@@ -265,7 +271,7 @@ __global__ __launch_bounds__(256) void bn_bwd_partial_kernel(const float* __rest
 }
 
 // dx = gamma*istd*(g' - mean(g') - xhat*mean(g'*xhat)); sample 0 / chunk 0 blocks add dgamma, dbeta to G
-template <bool VEC>
+template <bool VEC, bool SW = false>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restrict__ g,
                                                            const float* __restrict__ x,
                                                            const float* __restrict__ stat,
@@ -315,10 +321,10 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
       if (e < e1) {
         const float4 xv = xpre[u], gv = gpre[u];
         float4 o;
-        o.x = k * (gv.x * act_mask(xv.x * sc + sf, act) - m1 - (xv.x - mean) * istd * m2);
-        o.y = k * (gv.y * act_mask(xv.y * sc + sf, act) - m1 - (xv.y - mean) * istd * m2);
-        o.z = k * (gv.z * act_mask(xv.z * sc + sf, act) - m1 - (xv.z - mean) * istd * m2);
-        o.w = k * (gv.w * act_mask(xv.w * sc + sf, act) - m1 - (xv.w - mean) * istd * m2);
+        o.x = k * (gv.x * act_slope_sw<SW>(xv.x * sc + sf, act) - m1 - (xv.x - mean) * istd * m2);
+        o.y = k * (gv.y * act_slope_sw<SW>(xv.y * sc + sf, act) - m1 - (xv.y - mean) * istd * m2);
+        o.z = k * (gv.z * act_slope_sw<SW>(xv.z * sc + sf, act) - m1 - (xv.z - mean) * istd * m2);
+        o.w = k * (gv.w * act_slope_sw<SW>(xv.w * sc + sf, act) - m1 - (xv.w - mean) * istd * m2);
         *reinterpret_cast<float4*>(dx + base + e) = o;
       }
     }
@@ -326,16 +332,16 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
       float4 xv = *reinterpret_cast<const float4*>(x + base + e);
       float4 gv = *reinterpret_cast<const float4*>(g + base + e);
       float4 o;
-      o.x = k * (gv.x * act_mask(xv.x * sc + sf, act) - m1 - (xv.x - mean) * istd * m2);
-      o.y = k * (gv.y * act_mask(xv.y * sc + sf, act) - m1 - (xv.y - mean) * istd * m2);
-      o.z = k * (gv.z * act_mask(xv.z * sc + sf, act) - m1 - (xv.z - mean) * istd * m2);
-      o.w = k * (gv.w * act_mask(xv.w * sc + sf, act) - m1 - (xv.w - mean) * istd * m2);
+      o.x = k * (gv.x * act_slope_sw<SW>(xv.x * sc + sf, act) - m1 - (xv.x - mean) * istd * m2);
+      o.y = k * (gv.y * act_slope_sw<SW>(xv.y * sc + sf, act) - m1 - (xv.y - mean) * istd * m2);
+      o.z = k * (gv.z * act_slope_sw<SW>(xv.z * sc + sf, act) - m1 - (xv.z - mean) * istd * m2);
+      o.w = k * (gv.w * act_slope_sw<SW>(xv.w * sc + sf, act) - m1 - (xv.w - mean) * istd * m2);
       *reinterpret_cast<float4*>(dx + base + e) = o;
     }
   } else {
     for (int e = e0 + threadIdx.x; e < e1; e += 256) {
       float xv = x[base + e];
-      dx[base + e] = k * (g[base + e] * act_mask(xv * sc + sf, act) - m1 - (xv - mean) * istd * m2);
+      dx[base + e] = k * (g[base + e] * act_slope_sw<SW>(xv * sc + sf, act) - m1 - (xv - mean) * istd * m2);
     }
   }
 }
@@ -476,10 +482,16 @@ void bn_bwd_onepass_f32(hipStream_t st, const float* g, const float* x, const fl
 void bn_bwd_partial_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* ss,
                         double* ws, int N, int C, int HW, int act) {
   const BnSplit b = bn_split(N, HW);
-  if (HW % 4 == 0)
-    KLAUNCH(bn_bwd_partial_kernel<true>, dim3(C, b.P), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, b, act);
-  else
-    KLAUNCH(bn_bwd_partial_kernel<false>, dim3(C, b.P), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, b, act);
+#define BN_BWDP(name, kern) KLAUNCH_NAMED(name, kern, dim3(C, b.P), dim3(256), 0, st, g, x, stat, ss, ws, N, C, HW, b, act)
+  const bool sw = act == ACT_SWISH;
+  if (HW % 4 == 0) {
+    if (sw) BN_BWDP("bn_bwd_partial_kernel<true>", (bn_bwd_partial_kernel<true, true>));
+    else BN_BWDP("bn_bwd_partial_kernel<true>", (bn_bwd_partial_kernel<true, false>));
+  } else {
+    if (sw) BN_BWDP("bn_bwd_partial_kernel<false>", (bn_bwd_partial_kernel<false, true>));
+    else BN_BWDP("bn_bwd_partial_kernel<false>", (bn_bwd_partial_kernel<false, false>));
+  }
+#undef BN_BWDP
 }
 
 void bn_bwd_apply_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* ss,
@@ -490,12 +502,18 @@ void bn_bwd_apply_f32(hipStream_t st, const float* g, const float* x, const floa
   bn_chunking(HW, nchunks, chunk);
   // without an input gradient only the sample-0 / chunk-0 blocks have work (dgamma, dbeta)
   dim3 grid(dx ? (unsigned)(N * C) : (unsigned)C, dx ? nchunks : 1);
-  if (HW % 4 == 0)
-    KLAUNCH(bn_bwd_apply_kernel<true>, grid, dim3(256), 0, st, g, x, stat, ss, gamma, ws, dx, Ggamma, Gbeta, C, HW, P,
-            (double)per, act, chunk);
-  else
-    KLAUNCH(bn_bwd_apply_kernel<false>, grid, dim3(256), 0, st, g, x, stat, ss, gamma, ws, dx, Ggamma, Gbeta, C, HW,
-            P, (double)per, act, chunk);
+#define BN_BWDA(name, kern)                                                                                        \
+  KLAUNCH_NAMED(name, kern, grid, dim3(256), 0, st, g, x, stat, ss, gamma, ws, dx, Ggamma, Gbeta, C, HW, P, (double)per, \
+                act, chunk)
+  const bool sw = act == ACT_SWISH;
+  if (HW % 4 == 0) {
+    if (sw) BN_BWDA("bn_bwd_apply_kernel<true>", (bn_bwd_apply_kernel<true, true>));
+    else BN_BWDA("bn_bwd_apply_kernel<true>", (bn_bwd_apply_kernel<true, false>));
+  } else {
+    if (sw) BN_BWDA("bn_bwd_apply_kernel<false>", (bn_bwd_apply_kernel<false, true>));
+    else BN_BWDA("bn_bwd_apply_kernel<false>", (bn_bwd_apply_kernel<false, false>));
+  }
+#undef BN_BWDA
 }
 
 void bn_bwd_f32(hipStream_t st, const float* g, const float* x, const float* stat, const float* ss,

@@ -103,8 +103,9 @@ ast_status build_plan(Stage& s, std::string& err) {
         op.w_off = poff; poff += A.c; op.b_off = poff; poff += A.c; op.has_bias = 1;
         op.run_off = run; run += 2 * (size_t)A.c;
         take_aux(op, 4 * sizeof(float) * A.c);  // mean, istd, scale, shift
-        if (i + 1 < nl && (s.layers[i + 1].kind == AST_RELU || s.layers[i + 1].kind == AST_RELU6)) {
-          op.act = s.layers[i + 1].kind == AST_RELU ? 1 : 2; ++i;
+        if (i + 1 < nl && (s.layers[i + 1].kind == AST_RELU || s.layers[i + 1].kind == AST_RELU6 ||
+                           s.layers[i + 1].kind == AST_SWISH)) {
+          op.act = s.layers[i + 1].kind == AST_RELU ? 1 : s.layers[i + 1].kind == AST_RELU6 ? 2 : 4; ++i;
         }
         if (i + 1 < nl && s.layers[i + 1].kind == AST_RES_ADD && !res_stack.empty()) {
           const Act& K = s.acts[res_stack.back()];
@@ -339,7 +340,8 @@ ast_status build_plan(Stage& s, std::string& err) {
       const int dparts = dw3x3_parts(DI.n, DI.c, DI.h, DI.w, dw.stride);  // partial sums per channel it leaves
       if (j > 0 && (fuse & 1)) {
         Op& bn = s.ops[j - 1];
-        if (bn.kind == OP_BN && bn.out == dw.in && bn.skip < 0) {
+        // (the conv's kernels apply ReLU / ReLU6 only, and mask by the recomputed activated value)
+        if (bn.kind == OP_BN && bn.out == dw.in && bn.skip < 0 && bn.act <= 2) {
           bn.bn_lazy = true;
           bn.bn_bwd_sums_given = (fuse & 2) != 0;
           bn.given_bwd_parts = dparts;
@@ -357,7 +359,7 @@ ast_status build_plan(Stage& s, std::string& err) {
             bn.given_parts = dparts;
             dw.bn_out_op = (int)j + 1;
           }
-          if (fuse & 4) {
+          if ((fuse & 4) && bn.act <= 2) {  // the conv's kernels know ReLU / ReLU6 only
             bn.bn_bwd_apply_fused = true;
             dw.bn_bwd_out_op = (int)j + 1;
           }
