@@ -62,7 +62,16 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
   hipStream_t st = s.stream;
   const Act& I = s.acts[op.in];
   const int HW = I.h * I.w;
+  if (op.absorbed) return;
   switch (op.kind) {
+    case OP_SE_GATE: {  // this op is the first linear layer; swish, the second linear layer and sigmoid follow it
+      const Op* q = &op;
+      const Op &a1 = q[1], &l2 = q[2], &a2 = q[3];
+      se_gate_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, op.has_bias ? s.W + op.b_off : nullptr, s.W + l2.w_off,
+                      l2.has_bias ? s.W + l2.b_off : nullptr, (float*)act_ptr(c, op.out), (float*)act_ptr(c, a1.out),
+                      (float*)act_ptr(c, l2.out), (float*)act_ptr(c, a2.out), I.n, op.cin, op.cout);
+      break;
+    }
     case OP_CONV_PW:
       pw_conv_f32(st, s.wpack + op.wp_off, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out),
                   op.has_bias ? s.W + op.b_off : nullptr, nullptr, I.n, op.cin, op.cout, HW,
@@ -191,7 +200,17 @@ void bwd_op(Ctx& c, const Op& op) {
   const Act& I = s.acts[op.in];
   const int HW = I.h * I.w;
   void* gin = grad_ptr(c, op.in);  // NULL: not wanted
+  if (op.absorbed) return;
   switch (op.kind) {
+    case OP_SE_GATE: {
+      const Op* q = &op;
+      const Op &a1 = q[1], &l2 = q[2], &a2 = q[3];
+      se_gate_bwd_f32(st, (cf)grad_ptr(c, a2.out), (cf)act_ptr(c, l2.out), (cf)act_ptr(c, op.out), (cf)act_ptr(c, op.in),
+                      (cf)act_ptr(c, a1.out), s.W + op.w_off, s.W + l2.w_off, (float*)grad_ptr(c, l2.out),
+                      (float*)grad_ptr(c, op.out), (float*)gin, s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr,
+                      s.G + l2.w_off, l2.has_bias ? s.G + l2.b_off : nullptr, I.n, op.cin, op.cout);
+      break;
+    }
     case OP_CONV_PW: {
       cf g = (cf)grad_ptr(c, op.out);
       float* part = reinterpret_cast<float*>(scratch(c, op));

@@ -196,6 +196,16 @@ void fill_zero(hipStream_t st, void* dst, size_t bytes);
 // Pooling
 void gap_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int HW);
 void gap_bwd_f32(hipStream_t st, const float* g, float* dx, int NC, int HW, bool accumulate = false);
+// Squeeze-and-excitation gate in one launch per direction: p [N][C] -> hpre = W1 p + b1 [N][Cr] ->
+// h = swish(hpre) -> z = W2 h + b2 [N][C] -> gate = sigmoid(z).  Backward: dz and dhp (the gradients
+// of z and hpre) are written as by-products, dp may be NULL; G* += the parameter gradients (a bias
+// gradient pointer is NULL when the layer has no bias).
+bool se_gate_supported(int C, int Cr);
+void se_gate_fwd_f32(hipStream_t st, const float* p, const float* W1, const float* b1, const float* W2, const float* b2,
+                     float* hpre, float* h, float* z, float* gate, int N, int C, int Cr);
+void se_gate_bwd_f32(hipStream_t st, const float* dgate, const float* z, const float* hpre, const float* p, const float* h,
+                     const float* W1, const float* W2, float* dz, float* dhp, float* dp, float* GW1, float* Gb1, float* GW2,
+                     float* Gb2, int N, int C, int Cr);
 // squeeze-and-excitation scale: y = x * gate[plane]; backward: dgate[plane] = sum dy*x, dx = dy * gate (dx may be NULL)
 void se_scale_fwd_f32(hipStream_t st, const float* x, const float* gate, float* y, int NC, int HW);
 void se_scale_bwd_f32(hipStream_t st, const float* dy, const float* x, const float* gate, float* dgate, float* dx,

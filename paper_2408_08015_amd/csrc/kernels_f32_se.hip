@@ -1,0 +1,142 @@
+// Squeeze-and-excitation gate of the EfficientNet blocks (Table 4 workload) in one launch per
+// direction: pooled vector p[B][C] -> h_pre = W1 p + b1 -> h = swish(h_pre) -> z = W2 h + b2 ->
+// gate = sigmoid(z), with C a few hundred and Cr = C/24 or so.  The layer-by-layer path spends six
+// launches of 4-13 us on these few kFLOP per sample; here a block owns a sample.  Every
+// intermediate is still written to its place in the stash (the backward reads them).
+//
+// Backward, launch A (block per sample): dz = dgate * sigmoid'(z); dh = W2^T dz;
+// dh_pre = dh * swish'(h_pre); dp = W1^T dh_pre.  dz and dh_pre stay in the gradient buffers of z and
+// h_pre.  Launch B (thread per parameter): the sums over the samples, in order, into G.
+#include "device_utils.h"
+#include "kernels.h"
+#include "prof.h"
+
+namespace ast {
+
+namespace {
+
+inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+
+// LDS: p[C] then h[Cr]
+__global__ __launch_bounds__(256) void se_gate_fwd_kernel(const float* __restrict__ p, const float* __restrict__ W1,
+                                                          const float* __restrict__ b1, const float* __restrict__ W2,
+                                                          const float* __restrict__ b2, float* __restrict__ hpre,
+                                                          float* __restrict__ h, float* __restrict__ z,
+                                                          float* __restrict__ gate, int C, int Cr) {
+  extern __shared__ float sh[];
+  float* sp = sh;
+  float* shh = sh + C;
+  const int n = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  for (int c = threadIdx.x; c < C; c += 256) sp[c] = p[(size_t)n * C + c];
+  __syncthreads();
+  for (int r = wv; r < Cr; r += 4) {  // a wavefront per hidden unit
+    float a = 0.f;
+    for (int c = lane; c < C; c += 64) a += W1[(size_t)r * C + c] * sp[c];
+    a = wave_sum(a) + (b1 ? b1[r] : 0.f);
+    if (lane == 0) {
+      hpre[(size_t)n * Cr + r] = a;
+      const float hv = a * sigmoid_f(a);
+      h[(size_t)n * Cr + r] = hv;
+      shh[r] = hv;
+    }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < C; c += 256) {
+    float a = b2 ? b2[c] : 0.f;
+    for (int r = 0; r < Cr; ++r) a += W2[(size_t)c * Cr + r] * shh[r];
+    z[(size_t)n * C + c] = a;
+    gate[(size_t)n * C + c] = sigmoid_f(a);
+  }
+}
+
+// LDS: dz[C] then dhp[Cr]
+__global__ __launch_bounds__(256) void se_gate_bwd_kernel(const float* __restrict__ dgate, const float* __restrict__ z,
+                                                          const float* __restrict__ hpre, const float* __restrict__ W1,
+                                                          const float* __restrict__ W2, float* __restrict__ dz,
+                                                          float* __restrict__ dhp, float* __restrict__ dp, int C, int Cr) {
+  extern __shared__ float sh[];
+  float* sdz = sh;
+  float* sdh = sh + C;
+  const int n = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  for (int c = threadIdx.x; c < C; c += 256) {
+    const float s = sigmoid_f(z[(size_t)n * C + c]);
+    const float v = dgate[(size_t)n * C + c] * s * (1.f - s);
+    sdz[c] = v;
+    dz[(size_t)n * C + c] = v;
+  }
+  __syncthreads();
+  for (int r = wv; r < Cr; r += 4) {
+    float a = 0.f;
+    for (int c = lane; c < C; c += 64) a += W2[(size_t)c * Cr + r] * sdz[c];
+    a = wave_sum(a);
+    if (lane == 0) {
+      const float v = a * act_slope_sw<true>(hpre[(size_t)n * Cr + r], ACT_SWISH);
+      sdh[r] = v;
+      dhp[(size_t)n * Cr + r] = v;
+    }
+  }
+  __syncthreads();
+  if (dp)
+    for (int c = threadIdx.x; c < C; c += 256) {
+      float a = 0.f;
+      for (int r = 0; r < Cr; ++r) a += W1[(size_t)r * C + c] * sdh[r];
+      dp[(size_t)n * C + c] = a;
+    }
+}
+
+// parameters in the order [W1: Cr*C][b1: Cr][W2: C*Cr][b2: C]; G* may be NULL for an absent bias
+__global__ void se_gate_wgrad_kernel(const float* __restrict__ dz, const float* __restrict__ dhp,
+                                     const float* __restrict__ p, const float* __restrict__ h, float* __restrict__ GW1,
+                                     float* __restrict__ Gb1, float* __restrict__ GW2, float* __restrict__ Gb2, int N, int C,
+                                     int Cr) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const int nW = C * Cr;
+  float a = 0.f;
+  if (idx < nW) {  // W1[r][c]
+    const int r = idx / C, c = idx - r * C;
+    for (int n = 0; n < N; ++n) a += dhp[(size_t)n * Cr + r] * p[(size_t)n * C + c];
+    GW1[idx] += a;
+    return;
+  }
+  idx -= nW;
+  if (idx < Cr) {
+    if (Gb1) {
+      for (int n = 0; n < N; ++n) a += dhp[(size_t)n * Cr + idx];
+      Gb1[idx] += a;
+    }
+    return;
+  }
+  idx -= Cr;
+  if (idx < nW) {  // W2[c][r]
+    const int c = idx / Cr, r = idx - c * Cr;
+    for (int n = 0; n < N; ++n) a += dz[(size_t)n * C + c] * h[(size_t)n * Cr + r];
+    GW2[idx] += a;
+    return;
+  }
+  idx -= nW;
+  if (idx < C && Gb2) {
+    for (int n = 0; n < N; ++n) a += dz[(size_t)n * C + idx];
+    Gb2[idx] += a;
+  }
+}
+
+}  // namespace
+
+bool se_gate_supported(int C, int Cr) { return C >= 1 && Cr >= 1 && (size_t)(C + Cr) * sizeof(float) <= 48 * 1024; }
+
+void se_gate_fwd_f32(hipStream_t st, const float* p, const float* W1, const float* b1, const float* W2, const float* b2,
+                     float* hpre, float* h, float* z, float* gate, int N, int C, int Cr) {
+  KLAUNCH(se_gate_fwd_kernel, dim3(N), dim3(256), (size_t)(C + Cr) * sizeof(float), st, p, W1, b1, W2, b2, hpre, h, z, gate,
+          C, Cr);
+}
+
+void se_gate_bwd_f32(hipStream_t st, const float* dgate, const float* z, const float* hpre, const float* p, const float* h,
+                     const float* W1, const float* W2, float* dz, float* dhp, float* dp, float* GW1, float* Gb1, float* GW2,
+                     float* Gb2, int N, int C, int Cr) {
+  KLAUNCH(se_gate_bwd_kernel, dim3(N), dim3(256), (size_t)(C + Cr) * sizeof(float), st, dgate, z, hpre, W1, W2, dz, dhp, dp, C,
+          Cr);
+  KLAUNCH(se_gate_wgrad_kernel, dim3(cdiv(2L * C * Cr + C + Cr, 256)), dim3(256), 0, st, dz, dhp, p, h, GW1, Gb1, GW2, Gb2, N,
+          C, Cr);
+}
+
+}  // namespace ast

@@ -292,6 +292,28 @@ ast_status build_plan(Stage& s, std::string& err) {
     }
   s.wpack_floats = wpk;
 
+  // Squeeze-and-excitation gate: linear -> swish -> linear -> sigmoid between the pooling and the
+  // scale becomes one launch per direction (ASTEROID_SE_FUSE=0 keeps the layer-by-layer path).
+  {
+    const char* e = getenv("ASTEROID_SE_FUSE");
+    const bool on = !e || atoi(e) != 0;
+    for (size_t j = 1; on && !s.bf16 && j + 4 < s.ops.size(); ++j) {
+      Op& l1 = s.ops[j];
+      Op& a1 = s.ops[j + 1];
+      Op& l2 = s.ops[j + 2];
+      Op& a2 = s.ops[j + 3];
+      const Op& gp = s.ops[j - 1];
+      const Op& sc = s.ops[j + 4];
+      if (gp.kind != OP_GAP || !gp.grad_accum || l1.kind != OP_LINEAR || l1.in != gp.out || a1.kind != OP_ACT ||
+          a1.act != 4 || a1.in != l1.out || l2.kind != OP_LINEAR || l2.in != a1.out || a2.kind != OP_ACT || a2.act != 5 ||
+          a2.in != l2.out || sc.kind != OP_SE_SCALE || sc.in != a2.out)
+        continue;
+      if (l2.cin != l1.cout || l2.cout != l1.cin || !se_gate_supported(l1.cin, l1.cout)) continue;
+      l1.kind = OP_SE_GATE;
+      a1.absorbed = l2.absorbed = a2.absorbed = true;
+    }
+  }
+
   // GELU backward folded into the input-gradient epilogue of the linear layer that consumes
   // the GELU output: g_pre = (g W) * GELU'(pre).
   for (size_t j = 1; j < s.ops.size(); ++j) {

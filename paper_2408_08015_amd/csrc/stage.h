@@ -22,6 +22,8 @@ enum OpKind {
   OP_ACT,          // standalone ReLU / ReLU6 / GELU / swish / sigmoid
   OP_SE_BEGIN,     // squeeze-and-excitation: marks the tensor that OP_SE_SCALE multiplies by its gate
   OP_SE_SCALE,     // in = gate [B][C], skip = the image tensor of the matching OP_SE_BEGIN
+  OP_SE_GATE,      // linear -> swish -> linear -> sigmoid on the pooled vector, as one launch (takes the place of
+                   // the first linear op; the three ops behind it are marked `absorbed`)
   OP_RES_BEGIN,
   OP_RES_ADD,
   OP_GAP,
@@ -66,6 +68,7 @@ struct Op {
                                       // gradient is masked by it in the epilogue
   bool relu_bwd_fused = false;        // conv+ReLU whose ReLU backward the consumer already applied
   bool noop_bwd = false;              // RES_BEGIN whose add was fused into the next dgrad
+  bool absorbed = false;              // executed by the OP_SE_GATE in front of it: skipped in both passes
   bool grad_accum = false;            // global average pool that opens a squeeze-and-excitation branch: its input
                                       // gradient is added to the one OP_SE_SCALE has already written
   size_t sh_off = 0, sh2_off = 0;     // bf16 weight copies (elements) in the shadow arena

@@ -195,6 +195,23 @@ def test_squeeze_excite(A, c, cr, hw, B, need_dx):
     check(one(C.squeeze_excite(c, cr), (c, hw, hw), B=B, needs_input_grad=need_dx), rounds=1)
 
 
+def test_squeeze_excite_layer_by_layer_path(A, monkeypatch):
+    """With the one-launch gate switched off every layer of the block runs as its own operator."""
+    monkeypatch.setenv("ASTEROID_SE_FUSE", "0")
+    check(one(C.squeeze_excite(24, 6), (24, 10, 10), B=3), rounds=1)
+    check(one(C.mbconv(16, 24, 5, 2, 6), (16, 12, 12), B=2), rounds=1)
+
+
+def test_squeeze_excite_gate_without_biases_and_other_activations(A):
+    nb = [simple("se_begin"), simple("global_avgpool"), linear(12, 3, bias=False), simple("swish"),
+          linear(3, 12, bias=False), simple("sigmoid"), simple("se_scale")]
+    check(one(nb, (12, 6, 6), B=3), rounds=1)
+    # a gate built from other layers is not the one-launch pattern and still works
+    other = [simple("se_begin"), simple("global_avgpool"), linear(12, 5), simple("relu"), linear(5, 12),
+             simple("sigmoid"), simple("se_scale")]
+    check(one(other, (12, 6, 6), B=3), rounds=1)
+
+
 def test_squeeze_excite_behind_a_layer_and_in_a_residual_block(A):
     L = [conv(8, 16, 1), bn(16), simple("swish")] + C.squeeze_excite(16, 4) + [conv(16, 8, 1), bn(8)]
     check(one(L, (8, 9, 9), B=3), rounds=1)
