@@ -54,15 +54,25 @@ inline DwkGeom dwk_geom(int C, int H, int W, int stride) {
 inline size_t x_floats(const DwkGeom& g) { return (size_t)(g.H + K - 1) * g.WX; }
 inline size_t g_floats(const DwkGeom& g) { return (size_t)g.HG * g.WG; }
 
-// rows x width floats at `sh`, image h x w placed at (pad, pad), zero elsewhere
+// rows x width floats at `sh`, image h x w placed at (pad, pad), zero elsewhere.  Eight loads per
+// thread are requested before the first is stored, so that a plane costs one or two memory latencies
+// instead of one per 256 elements.
 __device__ __forceinline__ void stage_plane(const float* __restrict__ src, float* __restrict__ sh, int h, int w, int rows,
                                             int width, int pad) {
-  for (int i = threadIdx.x; i < rows * width; i += 256) {
-    const int r = i / width, q = i - r * width;
-    const int hr = r - pad, wq = q - pad;
-    float v = 0.f;
-    if (hr >= 0 && hr < h && wq >= 0 && wq < w) v = src[(size_t)hr * w + wq];
-    sh[i] = v;
+  const int total = rows * width;
+  for (int i0 = threadIdx.x; i0 < total; i0 += 8 * 256) {
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int i = i0 + 256 * k;
+      const int r = i / width, q = i - r * width;
+      const int hr = r - pad, wq = q - pad;
+      v[k] = 0.f;
+      if (i < total && hr >= 0 && hr < h && wq >= 0 && wq < w) v[k] = src[(size_t)hr * w + wq];
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (i0 + 256 * k < total) sh[i0 + 256 * k] = v[k];
   }
 }
 
@@ -211,11 +221,20 @@ __global__ __launch_bounds__(256) void dwk_bwd_f32_kernel(const float* __restric
       }
     }
   }
+  // the 25 sums over the wavefront step by step together: 25 independent lane exchanges in flight per
+  // step instead of 150 dependent ones
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
-  for (int t = 0; t < KK; ++t) {
-    const float s = wave_sum(acc[t]);
-    if (lane == 0) shr[wv * KK + t] = s;
+  for (int o = 32; o > 0; o >>= 1) {
+    float other[KK];
+#pragma unroll
+    for (int t = 0; t < KK; ++t) other[t] = __shfl_xor(acc[t], o, 64);
+#pragma unroll
+    for (int t = 0; t < KK; ++t) acc[t] += other[t];
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int t = 0; t < KK; ++t) shr[wv * KK + t] = acc[t];
   }
   __syncthreads();
   if (threadIdx.x < KK)

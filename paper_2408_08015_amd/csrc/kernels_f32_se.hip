@@ -84,6 +84,24 @@ __global__ __launch_bounds__(256) void se_gate_bwd_kernel(const float* __restric
     }
 }
 
+// sum over the samples of a[n*sa + ia] * b[n*sb + ib] (b == NULL: of a alone), eight loads in flight
+__device__ __forceinline__ float sample_dot(const float* __restrict__ a, size_t sa, size_t ia, const float* __restrict__ b,
+                                            size_t sb, size_t ib, int N) {
+  float acc = 0.f;
+  for (int n0 = 0; n0 < N; n0 += 8) {
+    float av[8], bv[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const bool ok = n0 + k < N;
+      av[k] = ok ? a[(size_t)(n0 + k) * sa + ia] : 0.f;
+      bv[k] = (ok && b) ? b[(size_t)(n0 + k) * sb + ib] : 1.f;
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc += av[k] * bv[k];
+  }
+  return acc;
+}
+
 // parameters in the order [W1: Cr*C][b1: Cr][W2: C*Cr][b2: C]; G* may be NULL for an absent bias
 __global__ void se_gate_wgrad_kernel(const float* __restrict__ dz, const float* __restrict__ dhp,
                                      const float* __restrict__ p, const float* __restrict__ h, float* __restrict__ GW1,
@@ -91,33 +109,24 @@ __global__ void se_gate_wgrad_kernel(const float* __restrict__ dz, const float* 
                                      int Cr) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   const int nW = C * Cr;
-  float a = 0.f;
   if (idx < nW) {  // W1[r][c]
     const int r = idx / C, c = idx - r * C;
-    for (int n = 0; n < N; ++n) a += dhp[(size_t)n * Cr + r] * p[(size_t)n * C + c];
-    GW1[idx] += a;
+    GW1[idx] += sample_dot(dhp, Cr, r, p, C, c, N);
     return;
   }
   idx -= nW;
   if (idx < Cr) {
-    if (Gb1) {
-      for (int n = 0; n < N; ++n) a += dhp[(size_t)n * Cr + idx];
-      Gb1[idx] += a;
-    }
+    if (Gb1) Gb1[idx] += sample_dot(dhp, Cr, idx, nullptr, 0, 0, N);
     return;
   }
   idx -= Cr;
   if (idx < nW) {  // W2[c][r]
     const int c = idx / Cr, r = idx - c * Cr;
-    for (int n = 0; n < N; ++n) a += dz[(size_t)n * C + c] * h[(size_t)n * Cr + r];
-    GW2[idx] += a;
+    GW2[idx] += sample_dot(dz, C, c, h, Cr, r, N);
     return;
   }
   idx -= nW;
-  if (idx < C && Gb2) {
-    for (int n = 0; n < N; ++n) a += dz[(size_t)n * C + idx];
-    Gb2[idx] += a;
-  }
+  if (idx < C && Gb2) Gb2[idx] += sample_dot(dz, C, idx, nullptr, 0, 0, N);
 }
 
 }  // namespace
