@@ -94,6 +94,26 @@ def mobilenetv2_layers(num_classes=1000, schedule=MBV2_SCHEDULE, stem=32, last=1
     return L
 
 
+# (t, c, n, s, k): expansion, output channels, repeats, stride of the first repeat, depthwise kernel;
+# EfficientNet-B0's groups with the repeats scaled by B1's depth factor 1.1 (rounded up)
+EFFNET_B1_SCHEDULE = [(1, 16, 2, 1, 3), (6, 24, 3, 2, 3), (6, 40, 3, 2, 5), (6, 80, 4, 2, 3),
+                      (6, 112, 4, 1, 5), (6, 192, 5, 2, 5), (6, 320, 2, 1, 3)]
+
+
+def efficientnet_b1_layers(num_classes=1000, schedule=EFFNET_B1_SCHEDULE, stem=32, last=1280):
+    """EfficientNet-B1 (Table 4 workload; width 1.0, depth 1.1, 240x240 input): 3x3 stride-2 stem,
+    23 MBConv blocks with squeeze-and-excitation, 1x1 head, pooled classifier."""
+    L = [conv(3, stem, 3, 2, 1), bn(stem), simple("swish")]
+    cin = stem
+    for t, c, n, s, k in schedule:
+        for i in range(n):
+            L += mbconv(cin, c, k, s if i == 0 else 1, t)
+            cin = c
+    L += [conv(cin, last, 1), bn(last), simple("swish"), simple("global_avgpool"),
+          linear(last, num_classes), simple("softmax_ce")]
+    return L
+
+
 def encoder_layer(d, heads, ffn, eps=1e-5):
     """Post-LN encoder layer: h = LN(x + MHA(x)); y = LN(h + W2 GELU(W1 h + b1) + b2)."""
     return [simple("res_begin"), dict(kind="mha", d=d, heads=heads), simple("res_add"),
@@ -165,8 +185,15 @@ def cfg6(B=32, M=4, hw=60, seed=1006):
     return StageConfig("cfg6_effnetb1_stage", L, B, M, (24, hw, hw), "f32", "nchw", True, seed)
 
 
+def effnetb1(B=8, M=8, hw=240, seed=1007, num_classes=1000):
+    """The whole EfficientNet-B1 as one stage (profiler tables; no stored full-size oracle samples)."""
+    return StageConfig("effnetb1_full", efficientnet_b1_layers(num_classes), B, M, (3, hw, hw),
+                       "f32", "nchw", False, seed)
+
+
 CONFIGS = {
     "cfg1": cfg1, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4, "cfg5": cfg5, "cfg6": cfg6,
+    "effnetb1": effnetb1,
 }
 
 

@@ -199,6 +199,7 @@ DOMINANT = {
     "cfg3": ("pw_conv_f32_pkks_kernel<16>", "hbm"),
     "cfg4": ("gemm_bf16_kernel<128x128,im2col>", "mfma"),
     "cfg5": ("gemm_bf16_kernel<128x128,wgrad_rows>", "mfma"),
+    "cfg6": ("pw_bwd_dual_kernel<pk2>", "hbm"),
 }
 
 # HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then

@@ -392,16 +392,47 @@ void fill_zero(hipStream_t st, void* dst, size_t bytes) {
 }
 
 // ============================================================== pooling
-__global__ __launch_bounds__(256) void gap_fwd_kernel(const float* __restrict__ x,
-                                                      float* __restrict__ y, int NC, int HW) {
-  int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
-  int lane = threadIdx.x & 63;
-  if (plane >= NC) return;
-  const float* xp = x + (size_t)plane * HW;
-  float s = 0.f;
-  for (int p = lane; p < HW; p += 64) s += xp[p];
-  s = wave_sum(s);
-  if (lane == 0) y[plane] = s / (float)HW;
+// mean over each plane; TPP threads per plane (a wavefront for small planes, the block for large ones:
+// a squeeze-and-excitation block pools 120 x 120 planes), four loads in flight per thread
+template <int TPP>
+__global__ __launch_bounds__(256) void gap_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int NC, int HW) {
+  __shared__ float sh[4];
+  const int plane = blockIdx.x * (256 / TPP) + threadIdx.x / TPP;
+  const int t = threadIdx.x % TPP, lane = threadIdx.x & 63;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (plane < NC) {
+    const float* xp = x + (size_t)plane * HW;
+    if ((HW & 3) == 0) {
+      const float4* x4 = reinterpret_cast<const float4*>(xp);
+      const int n4 = HW / 4;
+      int p = t;
+      for (; p + 3 * TPP < n4; p += 4 * TPP) {
+        const float4 a = x4[p], b = x4[p + TPP], c = x4[p + 2 * TPP], d = x4[p + 3 * TPP];
+        s0 += (a.x + a.y) + (a.z + a.w);
+        s1 += (b.x + b.y) + (b.z + b.w);
+        s2 += (c.x + c.y) + (c.z + c.w);
+        s3 += (d.x + d.y) + (d.z + d.w);
+      }
+      for (; p < n4; p += TPP) {
+        const float4 a = x4[p];
+        s0 += (a.x + a.y) + (a.z + a.w);
+      }
+    } else {
+      int p = t;
+      for (; p + 3 * TPP < HW; p += 4 * TPP) {
+        s0 += xp[p]; s1 += xp[p + TPP]; s2 += xp[p + 2 * TPP]; s3 += xp[p + 3 * TPP];
+      }
+      for (; p < HW; p += TPP) s0 += xp[p];
+    }
+  }
+  float s = wave_sum((s0 + s1) + (s2 + s3));
+  if (TPP == 64) {
+    if (lane == 0 && plane < NC) y[plane] = s / (float)HW;
+  } else {
+    if (lane == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0 && plane < NC) y[plane] = ((sh[0] + sh[1]) + (sh[2] + sh[3])) / (float)HW;
+  }
 }
 __global__ void gap_bwd_kernel(const float* __restrict__ g, float* __restrict__ dx, size_t total,
                                int HW) {
@@ -409,7 +440,8 @@ __global__ void gap_bwd_kernel(const float* __restrict__ g, float* __restrict__ 
   if (i < total) dx[i] = g[i / HW] / (float)HW;
 }
 void gap_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int HW) {
-  KLAUNCH(gap_fwd_kernel, dim3(cdiv(NC, 4)), dim3(256), 0, st, x, y, NC, HW);
+  if (HW >= 2048) KLAUNCH_NAMED("gap_fwd_kernel", (gap_fwd_kernel<256>), dim3(NC), dim3(256), 0, st, x, y, NC, HW);
+  else KLAUNCH_NAMED("gap_fwd_kernel", (gap_fwd_kernel<64>), dim3(cdiv(NC, 4)), dim3(256), 0, st, x, y, NC, HW);
 }
 __global__ void gap_bwd_acc_kernel(const float* __restrict__ g, float* __restrict__ dx, size_t total, int HW) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

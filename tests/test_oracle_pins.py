@@ -371,6 +371,18 @@ def test_result_independent_of_K_and_sgd_closed_form():
     np.testing.assert_allclose(st.W, W0 - 0.01 * G - 0.01 * 1.9 * G, atol=1e-15)
 
 
+def test_efficientnet_b1_schedule():
+    """23 MBConv blocks, 7.8 M parameters with the 1000-way classifier (the published count of
+    EfficientNet-B1), 240 -> 8 spatial, every block with its squeeze-and-excitation."""
+    L = C.efficientnet_b1_layers()
+    assert sum(1 for l in L if l["kind"] == "se_scale") == 23
+    assert gen.out_shape(L[:-3], (3, 240, 240)) == (1280, 8, 8)
+    n = gen.num_params(L)
+    assert abs(n - 7.79e6) < 0.05e6, n
+    dws = [l for l in L if l["kind"] == "conv2d" and l["groups"] > 1]
+    assert len(dws) == 23 and sum(1 for l in dws if l["k"] == 5) == 12
+
+
 def test_mobilenetv2_schedule():
     Ls = C.mobilenetv2_layers()
     assert gen.num_params(Ls) == 3504872

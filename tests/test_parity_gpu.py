@@ -188,7 +188,8 @@ def test_swish_sigmoid(A, kind, shape, B):
     check(one([simple(kind)], shape, B=B), rounds=1)
 
 
-@pytest.mark.parametrize("c,cr,hw,B", [(24, 6, 10, 3), (144, 6, 30, 2), (16, 4, 7, 2), (8, 1, 1, 4), (40, 10, 8, 1)])
+@pytest.mark.parametrize("c,cr,hw,B", [(24, 6, 10, 3), (144, 6, 30, 2), (16, 4, 7, 2), (8, 1, 1, 4), (40, 10, 8, 1),
+                                       (8, 2, 48, 2), (4, 2, 47, 1)])   # the last two: planes pooled by a whole block
 @pytest.mark.parametrize("need_dx", [True, False])
 def test_squeeze_excite(A, c, cr, hw, B, need_dx):
     """The block alone: the tensor at se_begin gets its gradient from the product and from the gate."""
@@ -247,6 +248,12 @@ def test_mbconv(A, cin, cout, k, stride, expand, hw, B):
 def test_cfg6_small(A):
     check(C.cfg6(B=3, M=2, hw=12), rounds=1)
     check(C.cfg6(B=2, M=3, hw=20), rounds=1, K=2)
+
+
+def test_efficientnet_b1_small(A):
+    # the whole model at a small resolution and batch: 69 stacked BatchNorms over few elements, bar as for
+    # the whole MobileNetV2 (fp32 statistics against fp64, see test_cfg3_small)
+    check(C.effnetb1(B=8, M=2, hw=96, num_classes=24), tol_y=1e-4, tol_g=5e-2, rounds=1)
 
 
 def test_se_rejects_malformed_blocks(A):
