@@ -207,8 +207,8 @@ DOMINANT = {
 # what the same counter reads for the library's plain copy kernel of known size
 # (FETCH_SIZE reads 0.501 of the bytes copied, WRITE_SIZE 1.000); see profiles/.
 TRAFFIC_BYTES = {
-    ("cfg2", "bn_bwd_apply_kernel"): int((17501.7 / 0.5012 + 17254.5) * 1024),
-    ("cfg4", "gemm_bf16_kernel<128x128,im2col>"): int((49570.5 / 0.5005 + 45994.7) * 1024),
+    ("cfg2", "bn_bwd_apply_kernel"): int((17501.9 / 0.5012 + 17254.5) * 1024),
+    ("cfg4", "gemm_bf16_kernel<128x128,im2col>"): int((49588.4 / 0.5005 + 45994.7) * 1024),
 }
 
 
