@@ -94,6 +94,26 @@ def test_plan_hpp(PL, seed, kind, memory):
     assert y_h == merged
 
 
+@pytest.mark.parametrize("L,N,B,M", [(1, 1, 1, 1), (1, 4, 8, 2), (6, 1, 4, 4), (3, 3, 1, 8), (2, 5, 3, 1), (8, 2, 16, 64)])
+def test_plan_hpp_degenerate_sizes(PL, L, N, B, M):
+    """One layer, one device, one sample, one micro-batch, more devices than layers or samples."""
+    for seed, memory in ((0, "loose"), (1, "tight")):
+        o, h = both(PL, 700 + seed, L, N, B, M, kind="stair", memory=memory)
+        lat_o, stages_o, ys_o = O.plan_hpp(o)
+        lat_h, stages_h, y_h = PL.plan_hpp(h)
+        if stages_o is None:
+            assert stages_h is None and math.isinf(lat_h)
+            continue
+        assert (lat_h, stages_h) == (lat_o, stages_o)
+        assert len(stages_h) <= min(L, N) and sum(y_h.values()) == B * len(stages_h)
+        for G in ([0], list(range(N))):
+            want = O.allocate(o, 0, L, G, 1)
+            got = PL.allocate(h, 0, L, G, 1)
+            assert (got is None) == (want is None)
+            if want is not None:
+                assert got[0] == want
+
+
 def test_plan_hpp_real_valued_tables_agree_to_rounding(PL):
     """Measured tables are not whole numbers: sums taken in a different order then differ in
     the last bits, so the latency agrees to rounding (and the plan unless two candidates tie)."""
