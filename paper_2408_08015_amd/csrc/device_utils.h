@@ -58,7 +58,9 @@ __device__ __forceinline__ float relu6f(float v) { return fminf(fmaxf(v, 0.f), 6
 // activation codes used by fused kernels
 enum : int { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3, ACT_SWISH = 4, ACT_SIGMOID = 5 };
 
-__device__ __forceinline__ float sigmoid_f(float v) { return 1.f / (1.f + expf(-v)); }
+// hardware exponential and reciprocal (a few ulp; the fp32 parity bars are 1e-4): the swish
+// kernels are bound by this arithmetic, not by memory
+__device__ __forceinline__ float sigmoid_f(float v) { return __frcp_rn(1.f + __expf(-v)); }
 // ReLU / ReLU6, the activations every fused kernel knows (`act` is uniform over a launch)
 __device__ __forceinline__ float apply_act(float v, int act) {
   if (act == ACT_RELU) return fmaxf(v, 0.f);
