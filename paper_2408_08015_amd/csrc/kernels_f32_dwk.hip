@@ -247,7 +247,13 @@ __global__ void dwk_wgrad_final_kernel(const float* __restrict__ part, float* __
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= C * KK) return;
   float s = 0.f;
-  for (int n = 0; n < N; ++n) s += part[(size_t)n * C * KK + idx];
+  for (int n0 = 0; n0 < N; n0 += 8) {  // eight loads in flight
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = n0 + k < N ? part[(size_t)(n0 + k) * C * KK + idx] : 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s += v[k];
+  }
   G[idx] += s;
 }
 
