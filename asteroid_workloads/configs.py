@@ -7,6 +7,8 @@ Layer dictionaries (keys are plain ints/floats/bools):
   conv2d       cin cout k stride pad groups bias
   batchnorm2d  c eps
   relu / relu6 / gelu / swish / sigmoid / res_begin / res_add / global_avgpool / maxpool2x2 / softmax_ce
+  res_swap     inside res_begin ... res_add: ends the main branch; the layers from here to res_add
+               form the shortcut branch and run on the tensor res_begin remembered
   se_begin ... se_scale   squeeze-and-excitation: the layers in between (global_avgpool, linear,
                swish, linear, sigmoid) turn the tensor at se_begin into one gate per sample and
                channel; se_scale multiplies that tensor by its gate
@@ -114,6 +116,20 @@ def efficientnet_b1_layers(num_classes=1000, schedule=EFFNET_B1_SCHEDULE, stem=3
     return L
 
 
+def bottleneck(cin, mid, stride=1):
+    """ResNet50 bottleneck block (Table 4 workload): 1x1 reduce, BN, ReLU, 3x3 (carries the stride),
+    BN, ReLU, 1x1 expand to 4*mid, BN; shortcut = identity, or 1x1 conv (stride) + BN when the
+    shape changes; ReLU after the sum."""
+    cout = 4 * mid
+    L = [simple("res_begin"),
+         conv(cin, mid, 1), bn(mid), simple("relu"),
+         conv(mid, mid, 3, stride, 1), bn(mid), simple("relu"),
+         conv(mid, cout, 1), bn(cout)]
+    if stride != 1 or cin != cout:
+        L += [simple("res_swap"), conv(cin, cout, 1, stride), bn(cout)]
+    return L + [simple("res_add"), simple("relu")]
+
+
 def encoder_layer(d, heads, ffn, eps=1e-5):
     """Post-LN encoder layer: h = LN(x + MHA(x)); y = LN(h + W2 GELU(W1 h + b1) + b2)."""
     return [simple("res_begin"), dict(kind="mha", d=d, heads=heads), simple("res_add"),
@@ -185,6 +201,17 @@ def cfg6(B=32, M=4, hw=60, seed=1006):
     return StageConfig("cfg6_effnetb1_stage", L, B, M, (24, hw, hw), "f32", "nchw", True, seed)
 
 
+def cfg7(B=32, M=4, hw=56, seed=1008, cin=64, mid=64, blocks=3):
+    """ResNet50's first block group (conv2_x): three bottlenecks, 64 -> 256 channels at 56x56; the
+    first one has a projection shortcut."""
+    L = []
+    c = cin
+    for _ in range(blocks):
+        L += bottleneck(c, mid)
+        c = 4 * mid
+    return StageConfig("cfg7_resnet50_stage", L, B, M, (cin, hw, hw), "f32", "nchw", True, seed)
+
+
 def effnetb1(B=8, M=8, hw=240, seed=1007, num_classes=1000):
     """The whole EfficientNet-B1 as one stage (profiler tables; no stored full-size oracle samples)."""
     return StageConfig("effnetb1_full", efficientnet_b1_layers(num_classes), B, M, (3, hw, hw),
@@ -193,7 +220,7 @@ def effnetb1(B=8, M=8, hw=240, seed=1007, num_classes=1000):
 
 CONFIGS = {
     "cfg1": cfg1, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4, "cfg5": cfg5, "cfg6": cfg6,
-    "effnetb1": effnetb1,
+    "cfg7": cfg7, "effnetb1": effnetb1,
 }
 
 

@@ -82,6 +82,7 @@ def layer_shapes(layers, in_shape):
     """Per-sample logical output shape of every layer ((C,H,W), (S,D) or (classes,))."""
     s = tuple(in_shape)
     se = []
+    res = []
     shapes = []
     for L in layers:
         k = L["kind"]
@@ -89,6 +90,12 @@ def layer_shapes(layers, in_shape):
             se.append(s)
         elif k == "se_scale":
             s = se.pop()
+        elif k == "res_begin":
+            res.append(s)
+        elif k == "res_swap":
+            s, res[-1] = res[-1], s
+        elif k == "res_add":
+            res.pop()
         elif k == "conv2d":
             c, h, w = s
             ho = (h + 2 * L["pad"] - L["k"]) // L["stride"] + 1

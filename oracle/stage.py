@@ -183,6 +183,11 @@ class OracleStage:
             elif k == "res_begin":
                 res.append(a)
                 saved.append(None)
+            elif k == "res_swap":
+                # two-branch residual block (a ResNet block whose shortcut has layers of its own):
+                # the main branch ends here; the layers up to res_add run on the block's input
+                a, res[-1] = res[-1], a
+                saved.append(None)
             elif k == "res_add":
                 a = a + res.pop()
                 saved.append(None)
@@ -206,7 +211,7 @@ class OracleStage:
                 saved.append((p, np.asarray(labels)))
             else:
                 raise ValueError(k)
-            if self.storage == "bf16" and k not in ("softmax_ce", "res_begin", "se_begin"):
+            if self.storage == "bf16" and k not in ("softmax_ce", "res_begin", "res_swap", "se_begin"):
                 a = round_bf16(a)
         self.stash[mb] = saved
         if self.keep_acts:
@@ -255,6 +260,10 @@ class OracleStage:
                 g = g + skip.pop()
             elif k == "res_add":
                 skip.append(g)
+            elif k == "res_swap":
+                # g is the gradient of the block's input through the shortcut branch; the main
+                # branch's output gets the gradient res_add set aside
+                g, skip[-1] = skip[-1], g
             elif k == "res_begin":
                 g = g + skip.pop()
             elif k == "global_avgpool":

@@ -44,13 +44,19 @@ def split_units(layers):
 
 def _out_shape(layers, s):
     s = tuple(s)
-    se = []
+    se, res = [], []
     for L in layers:
         k = L["kind"]
         if k == "se_begin":
             se.append(s)
         elif k == "se_scale":
             s = se.pop()
+        elif k == "res_begin":
+            res.append(s)
+        elif k == "res_swap":
+            s, res[-1] = res[-1], s
+        elif k == "res_add":
+            res.pop()
         elif k == "conv2d":
             c, h, w = s
             s = (L["cout"], (h + 2 * L["pad"] - L["k"]) // L["stride"] + 1,

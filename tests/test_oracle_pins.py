@@ -371,6 +371,31 @@ def test_result_independent_of_K_and_sgd_closed_form():
     np.testing.assert_allclose(st.W, W0 - 0.01 * G - 0.01 * 1.9 * G, atol=1e-15)
 
 
+def test_two_branch_residual_is_the_sum_of_its_branches():
+    """res_begin, main, res_swap, shortcut, res_add against the two branches run as stages of
+    their own on the same input: outputs add, input gradients add, parameter gradients are those
+    of the branches."""
+    main = [C.conv(6, 10, 3, 2, 1), C.bn(10), C.simple("relu")]
+    short = [C.conv(6, 10, 1, 2), C.bn(10)]
+    block = [C.simple("res_begin")] + main + [C.simple("res_swap")] + short + [C.simple("res_add")]
+    r = RNG(12)
+    x = r.standard_normal((2, 6, 7, 7))
+    dy = r.standard_normal((2, 10, 4, 4))
+    stages = {name: OracleStage(L, 2, 1, (6, 7, 7)) for name, L in (("block", block), ("main", main), ("short", short))}
+    wm = RNG(3).standard_normal(stages["main"].nparams)
+    ws = RNG(4).standard_normal(stages["short"].nparams)
+    res = {}
+    for name, w in (("main", wm), ("short", ws), ("block", np.concatenate([wm, ws]))):
+        st = stages[name]
+        st.set_params(w)
+        y, _ = st.forward(0, x)
+        dx = st.backward(0, dy)
+        res[name] = (y, dx, st.G.copy())
+    np.testing.assert_allclose(res["block"][0], res["main"][0] + res["short"][0], atol=1e-12)
+    np.testing.assert_allclose(res["block"][1], res["main"][1] + res["short"][1], atol=1e-12)
+    np.testing.assert_allclose(res["block"][2], np.concatenate([res["main"][2], res["short"][2]]), atol=1e-12)
+
+
 def test_efficientnet_b1_schedule():
     """23 MBConv blocks, 7.8 M parameters with the 1000-way classifier (the published count of
     EfficientNet-B1), 240 -> 8 spatial, every block with its squeeze-and-excitation."""
@@ -446,6 +471,8 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False)
                 a = se.pop() * a[:, :, None, None]
             elif k == "res_begin":
                 res.append(a)
+            elif k == "res_swap":
+                a, res[-1] = res[-1], a
             elif k == "res_add":
                 a = a + res.pop()
             elif k == "global_avgpool":
@@ -467,7 +494,7 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False)
             elif k == "softmax_ce":
                 lab = torch.tensor(target[m * B:(m + 1) * B].astype(np.int64))
                 total = total + TF.cross_entropy(a, lab, reduction="sum") / (M * B)
-            if k not in ("softmax_ce", "res_begin", "se_begin"):
+            if k not in ("softmax_ce", "res_begin", "res_swap", "se_begin"):
                 a = rb(a)
         if not cfg.loss_tail:
             if cfg.layout == "nhwc":
@@ -485,6 +512,8 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False)
     C.cfg4(B=2, M=2, hw=6, cin=4, c=6),
     C.cfg5(B=2, M=2, S=7, d=16, heads=2, ffn=24, nlayers=2),
     C.cfg6(B=3, M=2, hw=10),
+    C.cfg7(B=3, M=2, hw=7, cin=8, mid=4, blocks=2),
+    C.StageConfig("strided_bottlenecks", C.bottleneck(8, 4, 2) + C.bottleneck(16, 4), 3, 2, (8, 9, 9), "f32", "nchw", True, 31),
 ], ids=lambda c: c.name)
 def test_stage_matches_torch_float64_autograd(cfg):
     st, inp = tiny_stage(cfg)
