@@ -75,9 +75,14 @@ typedef enum {
   AST_SE_BEGIN = 15,   /* squeeze-and-excitation: remembers the current image tensor x; must be
                           followed by AST_GLOBAL_AVGPOOL; the layers up to AST_SE_SCALE compute
                           a gate [B][C] from the pooled vector                                 */
-  AST_SE_SCALE = 16    /* y[b][c][h][w] = x[b][c][h][w] * gate[b][c], x from the matching
+  AST_SE_SCALE = 16,   /* y[b][c][h][w] = x[b][c][h][w] * gate[b][c], x from the matching
                           AST_SE_BEGIN; the gradient reaches x through the product and through
                           the gate                                                             */
+  AST_RES_SWAP = 17    /* inside AST_RES_BEGIN ... AST_RES_ADD: ends the main branch of a two-branch
+                          residual block (a ResNet block with a projection shortcut; Table 4
+                          workload).  The layers from here to AST_RES_ADD are the shortcut branch:
+                          they run on the tensor AST_RES_BEGIN remembered, and AST_RES_ADD adds
+                          the main branch's result to theirs                                    */
 } ast_layer_kind;
 
 typedef struct {

@@ -134,6 +134,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       else act_fwd_f32(st, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out), I.elems, op.act);
       break;
     case OP_RES_BEGIN:
+    case OP_RES_SWAP:
     case OP_SE_BEGIN:
       break;
     case OP_SE_SCALE: {
@@ -318,6 +319,7 @@ void bwd_op(Ctx& c, const Op& op) {
         act_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), (float*)gin, I.elems, op.act);
       break;
     case OP_SE_BEGIN:  // both gradients of the tensor are already in its buffer (OP_SE_SCALE, then the pool)
+    case OP_RES_SWAP:
       break;
     case OP_SE_SCALE: {
       const Act& X = s.acts[op.skip];

@@ -50,6 +50,7 @@ ast_status build_plan(Stage& s, std::string& err) {
   s.layer_act.assign(nl, -1);
   std::vector<int> res_stack;      // activation ids of open RES_BEGINs
   std::vector<int> res_op_stack;   // op indices of those RES_BEGINs
+  std::vector<char> res_swapped;   // per open RES_BEGIN: its shortcut branch has begun (RES_SWAP seen)
   std::vector<int> se_stack;       // activation ids of open SE_BEGINs
   bool se_opens = false;           // the previous layer was an SE_BEGIN
   size_t poff = 0, aux = 0, run = 0, shadow = 0;
@@ -107,7 +108,7 @@ ast_status build_plan(Stage& s, std::string& err) {
                            s.layers[i + 1].kind == AST_SWISH)) {
           op.act = s.layers[i + 1].kind == AST_RELU ? 1 : s.layers[i + 1].kind == AST_RELU6 ? 2 : 4; ++i;
         }
-        if (i + 1 < nl && s.layers[i + 1].kind == AST_RES_ADD && !res_stack.empty()) {
+        if (i + 1 < nl && s.layers[i + 1].kind == AST_RES_ADD && !res_stack.empty() && !res_swapped.back()) {
           const Act& K = s.acts[res_stack.back()];
           if (K.elems != A.elems || K.c != A.c) { err = fmt("layer %d: residual shapes differ", i + 1); return AST_EINVAL; }
           op.skip = res_stack.back();
@@ -117,7 +118,7 @@ ast_status build_plan(Stage& s, std::string& err) {
         op.out = cur = new_act(s, B, A.c, A.h, A.w, 4, i, es);
         if (op.skip >= 0) {
           s.ops[res_op_stack.back()].skip = cur;
-          res_stack.pop_back(); res_op_stack.pop_back();
+          res_stack.pop_back(); res_op_stack.pop_back(); res_swapped.pop_back();
         }
         break;
       }
@@ -153,7 +154,25 @@ ast_status build_plan(Stage& s, std::string& err) {
       case AST_RES_BEGIN: {
         op.kind = OP_RES_BEGIN; op.out = cur; op.skip = -1;
         res_stack.push_back(cur);
+        res_swapped.push_back(0);
         res_op_stack.push_back((int)s.ops.size());
+        s.layer_act[i] = -1;
+        s.ops.push_back(op);
+        continue;
+      }
+      case AST_RES_SWAP: {
+        if (res_stack.empty() || res_swapped.back()) { err = fmt("layer %d: RES_SWAP needs an open RES_BEGIN without a RES_SWAP", i); return AST_EINVAL; }
+        // The shortcut branch reads the block's input through a second activation entry: same
+        // tensor, own gradient buffer.  RES_BEGIN's backward adds that gradient (the shortcut's
+        // share) to the one the main branch leaves.
+        const Act X = s.acts[res_stack.back()];
+        const int alias = new_act(s, X.n, X.c, X.h, X.w, X.rank, i, es);
+        s.acts[alias].data_alias = res_stack.back();
+        s.ops[res_op_stack.back()].skip = alias;
+        op.kind = OP_RES_SWAP; op.out = alias;
+        res_stack.back() = cur;   // the main branch's result waits for RES_ADD
+        res_swapped.back() = 1;
+        cur = alias;
         s.layer_act[i] = -1;
         s.ops.push_back(op);
         continue;
@@ -164,8 +183,9 @@ ast_status build_plan(Stage& s, std::string& err) {
         if (K.elems != A.elems || K.c != A.c || K.rank != A.rank) { err = fmt("layer %d: residual shapes differ", i); return AST_EINVAL; }
         op.kind = OP_RES_ADD; op.skip = res_stack.back();
         op.out = cur = new_act(s, A.n, A.c, A.h, A.w, A.rank, i, es);
-        s.ops[res_op_stack.back()].skip = cur;
-        res_stack.pop_back(); res_op_stack.pop_back();
+        if (res_swapped.back()) s.acts[op.skip].grad_alias = cur;  // the main branch's result shares dy with the shortcut's
+        else s.ops[res_op_stack.back()].skip = cur;
+        res_stack.pop_back(); res_op_stack.pop_back(); res_swapped.pop_back();
         break;
       }
       case AST_GLOBAL_AVGPOOL: {
@@ -206,7 +226,8 @@ ast_status build_plan(Stage& s, std::string& err) {
           }
         }
         bool lin_res = false;
-        if (s.bf16 && op.act == 0 && i + 1 < nl && s.layers[i + 1].kind == AST_RES_ADD && !res_stack.empty()) {
+        if (s.bf16 && op.act == 0 && i + 1 < nl && s.layers[i + 1].kind == AST_RES_ADD && !res_stack.empty() &&
+            !res_swapped.back()) {
           const Act& K = s.acts[res_stack.back()];  // residual add folded into the output epilogue
           if (K.elems == A.elems / A.c * Cout && K.c == Cout && K.rank == A.rank) {
             op.res_in = res_stack.back();
@@ -217,7 +238,7 @@ ast_status build_plan(Stage& s, std::string& err) {
         op.out = cur = new_act(s, A.n, Cout, A.h, A.w, A.rank, i, es);
         if (lin_res) {
           s.ops[res_op_stack.back()].skip = cur;
-          res_stack.pop_back(); res_op_stack.pop_back();
+          res_stack.pop_back(); res_op_stack.pop_back(); res_swapped.pop_back();
         }
         break;
       }
@@ -254,7 +275,7 @@ ast_status build_plan(Stage& s, std::string& err) {
         // per-slot: qkv [rows][3D] bf16, o [rows][D] bf16, lse [B][H][S] fp32
         take_aux(op, (size_t)A.n * A.h * 4 * D * 2 + (size_t)A.n * H * A.h * 4);
         bool mha_res = false;
-        if (i + 1 < nl && s.layers[i + 1].kind == AST_RES_ADD && !res_stack.empty()) {
+        if (i + 1 < nl && s.layers[i + 1].kind == AST_RES_ADD && !res_stack.empty() && !res_swapped.back()) {
           const Act& K = s.acts[res_stack.back()];  // residual add folded into the output projection
           if (K.elems == A.elems && K.c == A.c && K.rank == A.rank) {
             op.res_in = res_stack.back();
@@ -265,7 +286,7 @@ ast_status build_plan(Stage& s, std::string& err) {
         op.out = cur = new_act(s, A.n, D, A.h, 1, 3, i, es);
         if (mha_res) {
           s.ops[res_op_stack.back()].skip = cur;
-          res_stack.pop_back(); res_op_stack.pop_back();
+          res_stack.pop_back(); res_op_stack.pop_back(); res_swapped.pop_back();
         }
         break;
       }
@@ -420,10 +441,12 @@ ast_status build_plan(Stage& s, std::string& err) {
       s.final_in_slot = true;
   for (size_t a = 0; a < s.acts.size(); ++a) {
     if ((int)a == final_act && !s.loss_tail && a != 0 && !s.final_in_slot) continue;
-    if (virtual_act[a]) continue;
+    if (virtual_act[a] || s.acts[a].data_alias >= 0) continue;
     s.acts[a].slot_off = off;
     off = align_up(off + s.acts[a].bytes, 256);
   }
+  for (Act& a : s.acts)  // a shortcut branch's input is the tensor RES_BEGIN remembered
+    if (a.data_alias >= 0) a.slot_off = s.acts[a.data_alias].slot_off;
   for (Op& op : s.ops) op.aux_off += off;
   s.slot_bytes = align_up(off + aux, 256);
 

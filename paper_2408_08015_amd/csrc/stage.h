@@ -25,6 +25,7 @@ enum OpKind {
   OP_SE_GATE,      // linear -> swish -> linear -> sigmoid on the pooled vector, as one launch (takes the place of
                    // the first linear op; the three ops behind it are marked `absorbed`)
   OP_RES_BEGIN,
+  OP_RES_SWAP,     // two-branch residual block: the shortcut branch starts (no work of its own)
   OP_RES_ADD,
   OP_GAP,
   OP_MAXPOOL,
@@ -42,6 +43,7 @@ struct Act {
   size_t slot_off = 0;             // byte offset inside a stash slot
   size_t grad_off = 0;             // byte offset inside the gradient workspace
   int grad_alias = -1;             // gradient buffer shared with this activation's
+  int data_alias = -1;             // same tensor as this activation (own gradient buffer): the input of a shortcut branch
   int layer = -1;                  // layer index whose output this is (-1: stage input)
 };
 

@@ -256,6 +256,47 @@ def test_efficientnet_b1_small(A):
     check(C.effnetb1(B=8, M=2, hw=96, num_classes=24), tol_y=1e-4, tol_g=5e-2, rounds=1)
 
 
+# ------------------------------------------------------------------ ResNet blocks (Table 4 workload)
+@pytest.mark.parametrize("need_dx", [True, False])
+@pytest.mark.parametrize("stride", [1, 2])
+def test_two_branch_residual_block(A, stride, need_dx):
+    """res_begin, main branch, res_swap, shortcut branch, res_add with the block's input as the stage input:
+    both branches read it, both gradients reach it."""
+    L = [simple("res_begin"), conv(6, 10, 3, stride, 1), bn(10), simple("relu"), simple("res_swap"),
+         conv(6, 10, 1, stride), bn(10), simple("res_add"), simple("relu")]
+    check(one(L, (6, 9, 9), B=3, needs_input_grad=need_dx), rounds=1)
+
+
+@pytest.mark.parametrize("cin,mid,stride,hw,B", [(8, 4, 1, 8, 3), (16, 4, 1, 8, 2), (16, 8, 2, 10, 2), (64, 16, 1, 14, 2)])
+def test_resnet_bottleneck(A, cin, mid, stride, hw, B):
+    """Projection shortcut when the shape changes, identity otherwise; behind a layer, so that the block's input
+    has a gradient buffer of its own."""
+    L = [conv(cin, cin, 1), bn(cin), simple("relu")] + C.bottleneck(cin, mid, stride)
+    check(one(L, (cin, hw, hw), B=B), rounds=1)
+
+
+def test_cfg7_small(A):
+    check(C.cfg7(B=3, M=2, hw=8, cin=16, mid=8, blocks=2), rounds=1)
+    check(C.cfg7(B=2, M=3, hw=12, cin=64, mid=64, blocks=3), rounds=1, K=2)
+
+
+def test_res_swap_rejects_malformed_blocks(A):
+    with pytest.raises(A.AsteroidError) as e:
+        A.Stage([simple("res_swap"), simple("relu")], 2, 1, 1, (8, 4, 4))
+    assert e.value.status == -1
+    with pytest.raises(A.AsteroidError) as e:
+        A.Stage([simple("res_begin"), simple("relu"), simple("res_swap"), simple("relu"), simple("res_swap"),
+                 simple("res_add")], 2, 1, 1, (8, 4, 4))
+    assert e.value.status == -1
+    with pytest.raises(A.AsteroidError) as e:      # branches of different shapes
+        A.Stage([simple("res_begin"), conv(8, 8, 3, 2, 1), simple("res_swap"), conv(8, 8, 1), simple("res_add")],
+                2, 1, 1, (8, 6, 6))
+    assert e.value.status == -1
+    with pytest.raises(A.AsteroidError) as e:
+        A.Stage([simple("res_begin"), simple("relu"), simple("res_swap"), simple("relu")], 2, 1, 1, (8, 4, 4))
+    assert e.value.status == -1
+
+
 def test_se_rejects_malformed_blocks(A):
     with pytest.raises(A.AsteroidError) as e:
         A.Stage([simple("se_begin"), simple("swish"), simple("se_scale")], 2, 1, 1, (8, 4, 4))
