@@ -1,0 +1,236 @@
+// fp32 dense 3x3 convolution (stride 1, padding 1) on the matrix cores, for the ResNet workload
+// (Table 4): the nine taps are nine pointwise products accumulated in the same registers.
+//
+// Forward / input gradient: as the pointwise kernel -- a wavefront owns 32 pixels and a 32-row tile
+// of output channels, MFMA 32x32x2 with the pixels on the N dimension, the B operand straight from
+// global memory -- but the pixel of tap (du, dv) is the lane's pixel shifted by du rows and dv
+// columns, zero outside the image, and the A operand of tap t comes from the t-th packed weight
+// copy.  The input gradient is the same kernel on the upstream gradient with the taps mirrored and
+// the channel roles exchanged (a second set of nine packed copies).
+// Weight gradient: as the pointwise weight-gradient kernel (pixels are the contraction index), one
+// block per (pixel chunk, 32x32 tile of (cout, cin), tap), the x operand shifted and masked.
+// Partials per pixel chunk, layout [chunk][cout][cin][tap] = the layout of the weights.
+#include "device_utils.h"
+#include "kernels.h"
+#include "prof.h"
+
+namespace ast {
+
+namespace {
+
+inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+
+struct C3Args {
+  const float4* Wp;   // nine packed copies, tap_stride float4 words apart
+  const float* X;
+  float* Y;
+  const float* bias;
+  long NQ;
+  int H, W, Kdim, Mdim, KG;
+  size_t tap_stride;
+};
+
+template <int NCH>
+__global__ __launch_bounds__(256) void conv3x3_mfma_f32_kernel(C3Args a) {
+  const float4* __restrict__ Wp = a.Wp;
+  const float* __restrict__ X = a.X;
+  float* __restrict__ Y = a.Y;
+  const int H = a.H, W = a.W, HW = a.H * a.W, Kdim = a.Kdim, Mdim = a.Mdim, KG = a.KG;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int m_base = blockIdx.y * 32;
+  const long q = (long)blockIdx.x * 128 + wave * 32 + col;
+  const bool qv = q < a.NQ;
+  long n = 0;
+  int p = 0;
+  if (qv) {
+    n = q / HW;
+    p = (int)(q - n * HW);
+  }
+  const int pi = p / W, pj = p - pi * W;
+  const float* xq = X + (size_t)n * Kdim * HW + p;
+  const float4* wl = Wp + (size_t)blockIdx.y * KG * 64 + lane;
+  floatx16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int tap = 0; tap < 9; ++tap) {
+    const int du = tap / 3 - 1, dv = tap - (tap / 3) * 3 - 1;
+    const bool ok = qv && (unsigned)(pi + du) < (unsigned)H && (unsigned)(pj + dv) < (unsigned)W;
+    const float* xt = xq + du * W + dv;  // dereferenced only where ok
+    const float4* wt = wl + (size_t)tap * a.tap_stride;
+    for (int g0 = 0; g0 < KG; g0 += NCH * 4) {
+      float4 av[NCH * 4];
+      float b[NCH * 16];
+#pragma unroll
+      for (int g = 0; g < NCH * 4; ++g) {
+        av[g] = g0 + g < KG ? wt[(size_t)(g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int k = (g0 + g) * 8 + 2 * e + half;
+          float v = 0.f;
+          if (ok && k < Kdim) v = xt[(size_t)k * HW];
+          b[4 * g + e] = v;
+        }
+      }
+#pragma unroll
+      for (int g = 0; g < NCH * 4; ++g) {
+        if (g0 + g >= KG) break;  // uniform
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].x, b[4 * g + 0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].y, b[4 * g + 1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].z, b[4 * g + 2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].w, b[4 * g + 3], acc, 0, 0, 0);
+      }
+    }
+  }
+  if (qv) {
+    float* yq = Y + (size_t)n * Mdim * HW + p;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (m < Mdim) yq[(size_t)m * HW] = acc[r] + (a.bias ? a.bias[m] : 0.f);
+    }
+  }
+}
+
+struct C3WgArgs {
+  const float* g;
+  const float* x;
+  float* part;
+  int Cin, Cout, H, W, cps, pxw, cot;  // cot = 32-row tiles of cout
+};
+
+// block (chunk, ci tile, co tile * 9 + tap); wavefront w of the block takes the w-th quarter of the chunk
+__global__ __launch_bounds__(256) void conv3x3_wgrad_mfma_f32_kernel(C3WgArgs w) {
+  __shared__ float sR[4][16][64];
+  const float* __restrict__ g = w.g;
+  const float* __restrict__ x = w.x;
+  const int Cin = w.Cin, Cout = w.Cout, H = w.H, W = w.W, HW = w.H * w.W;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = lane & 31, half = lane >> 5;
+  const int chunk = blockIdx.x;
+  const int n = chunk / w.cps;
+  const int p0 = ((chunk - n * w.cps) * 4 + wave) * w.pxw;
+  const int p1 = min(p0 + w.pxw, HW);
+  const int tap = blockIdx.z / w.cot, cob = blockIdx.z - tap * w.cot;
+  const int du = tap / 3 - 1, dv = tap - (tap / 3) * 3 - 1;
+  const int ci_base = blockIdx.y * 32, co_base = cob * 32;
+  const bool av = co_base + row < Cout, bv = ci_base + row < Cin;
+  const float* ga = g + ((size_t)n * Cout + (av ? co_base + row : 0)) * HW;
+  const float* xb = x + ((size_t)n * Cin + (bv ? ci_base + row : 0)) * HW + du * W + dv;  // read only where valid
+  floatx16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int p = p0; p < p1; p += 32) {  // sixteen pixel pairs requested before the first MFMA
+    float a[16], b[16];
+    int pp = p + half;
+    int i = pp / W, j = pp - i * W;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const bool in = pp < p1;
+      a[u] = 0.f;
+      b[u] = 0.f;
+      if (av && in) a[u] = ga[pp];
+      if (bv && in && (unsigned)(i + du) < (unsigned)H && (unsigned)(j + dv) < (unsigned)W) b[u] = xb[pp];
+      pp += 2;
+      j += 2;
+      if (j >= W) {  // at most one row further per step unless the image is narrower than two pixels
+        j -= W;
+        ++i;
+        if (j >= W) { i += j / W; j %= W; }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc, 0, 0, 0);
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sR[wave][r][lane] = acc[r];
+  __syncthreads();
+  float* out = w.part + (size_t)chunk * Cout * Cin * 9;
+  const int ci = ci_base + row;
+  if (ci < Cin) {
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int r = 4 * wave + rr;
+      const int co = co_base + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (co < Cout)
+        out[((size_t)co * Cin + ci) * 9 + tap] = (sR[0][r][lane] + sR[1][r][lane]) + (sR[2][r][lane] + sR[3][r][lane]);
+    }
+  }
+}
+
+// G[i] += sum over the chunks of part[chunk][i]
+__global__ __launch_bounds__(256) void conv3x3_reduce_kernel(const float* __restrict__ part, float* __restrict__ G, size_t n,
+                                                             int parts) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int c0 = 0; c0 < parts; c0 += 8) {
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = c0 + k < parts ? part[(size_t)(c0 + k) * n + i] : 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s += v[k];
+  }
+  G[i] += s;
+}
+
+// pixels per wavefront of the weight-gradient kernel: the largest of {256, 128, 64, 32} that still
+// gives about a thousand blocks
+int c3_pxw(int N, int Cin, int Cout, int HW) {
+  const long tiles = (long)cdiv(Cin, 32) * cdiv(Cout, 32) * 9;
+  const int cand[4] = {256, 128, 64, 32};
+  for (int c : cand)
+    if ((long)N * cdiv(HW, 4 * c) * tiles >= 1024) return c;
+  return 32;
+}
+
+void launch_product(hipStream_t st, const float* Wp, const float* X, float* Y, const float* bias, int N, int Kdim, int Mdim,
+                    int H, int W) {
+  C3Args a;
+  a.Wp = reinterpret_cast<const float4*>(Wp);
+  a.X = X; a.Y = Y; a.bias = bias;
+  a.NQ = (long)N * H * W;
+  a.H = H; a.W = W; a.Kdim = Kdim; a.Mdim = Mdim; a.KG = cdiv(Kdim, 8);
+  a.tap_stride = pw_pack_floats(Mdim, Kdim) / 4;
+  const dim3 grid((unsigned)cdiv(a.NQ, 128), (unsigned)cdiv(Mdim, 32));
+  if (Kdim > 32) KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<2>), grid, dim3(256), 0, st, a);
+  else KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<1>), grid, dim3(256), 0, st, a);
+}
+
+}  // namespace
+
+bool conv3x3_mfma_supported(int Cin, int Cout, int k, int stride, int pad, int groups, int H, int W) {
+  return k == 3 && stride == 1 && pad == 1 && groups == 1 && Cin >= 8 && Cout >= 8 && H >= 1 && W >= 1 &&
+         (long)H * W < (1L << 30);
+}
+
+size_t conv3x3_pack_floats(int Mdim, int Kdim) { return 9 * pw_pack_floats(Mdim, Kdim); }
+
+int conv3x3_wgrad_parts(int N, int Cin, int Cout, int H, int W) { return N * cdiv(H * W, 4 * c3_pxw(N, Cin, Cout, H * W)); }
+
+size_t conv3x3_wgrad_ws(int N, int Cin, int Cout, int H, int W) {
+  return (size_t)conv3x3_wgrad_parts(N, Cin, Cout, H, W) * Cin * Cout * 9;
+}
+
+void conv3x3_mfma_fwd_f32(hipStream_t st, const float* Wp, const float* x, float* y, const float* bias, int N, int Cin,
+                          int Cout, int H, int W) {
+  launch_product(st, Wp, x, y, bias, N, Cin, Cout, H, W);
+}
+
+void conv3x3_mfma_bwd_f32(hipStream_t st, const float* Wp_t, const float* g, float* dx, const float* x, float* part,
+                          float* G, int N, int Cin, int Cout, int H, int W) {
+  if (dx) launch_product(st, Wp_t, g, dx, nullptr, N, Cout, Cin, H, W);
+  C3WgArgs w;
+  w.g = g; w.x = x; w.part = part;
+  w.Cin = Cin; w.Cout = Cout; w.H = H; w.W = W;
+  w.pxw = c3_pxw(N, Cin, Cout, H * W);
+  w.cps = cdiv(H * W, 4 * w.pxw);
+  w.cot = cdiv(Cout, 32);
+  const dim3 grid((unsigned)(N * w.cps), (unsigned)cdiv(Cin, 32), (unsigned)(w.cot * 9));
+  KLAUNCH(conv3x3_wgrad_mfma_f32_kernel, grid, dim3(256), 0, st, w);
+  const size_t n = (size_t)Cin * Cout * 9;
+  if (G) KLAUNCH(conv3x3_reduce_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, part, G, n, (int)grid.x);
+}
+
+}  // namespace ast

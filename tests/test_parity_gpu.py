@@ -257,6 +257,31 @@ def test_efficientnet_b1_small(A):
 
 
 # ------------------------------------------------------------------ ResNet blocks (Table 4 workload)
+@pytest.mark.parametrize("cin,cout,h,w,B,bias", [
+    (16, 24, 12, 12, 3, False),
+    (64, 64, 14, 14, 2, False),    # the conv2_x shape, two channel chunks per pass
+    (8, 8, 5, 5, 2, True),
+    (40, 72, 9, 7, 2, False),      # ragged k-group and m-tile, not square
+    (72, 40, 7, 9, 3, True),
+    (32, 16, 1, 1, 4, False),      # one pixel: only the centre tap
+    (8, 8, 1, 6, 2, False),        # one row
+    (8, 8, 6, 1, 2, False),        # one column
+    (128, 128, 8, 8, 1, False),    # four channel passes
+    (16, 8, 33, 33, 2, False),     # several pixel chunks per plane in the weight gradient
+])
+@pytest.mark.parametrize("need_dx", [True, False])
+def test_dense_conv3x3(A, cin, cout, h, w, B, bias, need_dx):
+    L = [conv(cin, cout, 3, 1, 1, bias=bias)]
+    check(one(L, (cin, h, w), B=B, needs_input_grad=need_dx), rounds=1)
+
+
+def test_dense_conv3x3_generic_path(A, monkeypatch):
+    """With the matrix-core kernels switched off the generic grouped-conv kernels take the layer."""
+    monkeypatch.setenv("ASTEROID_CONV3_MFMA", "0")
+    check(one([conv(16, 24, 3, 1, 1)], (16, 12, 12), B=3), rounds=1)
+
+
+
 @pytest.mark.parametrize("need_dx", [True, False])
 @pytest.mark.parametrize("stride", [1, 2])
 def test_two_branch_residual_block(A, stride, need_dx):
