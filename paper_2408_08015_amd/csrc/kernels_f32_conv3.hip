@@ -8,7 +8,8 @@
 // copy.  The input gradient is the same kernel on the upstream gradient with the taps mirrored and
 // the channel roles exchanged (a second set of nine packed copies).
 // Weight gradient: as the pointwise weight-gradient kernel (pixels are the contraction index), one
-// block per (pixel chunk, 32x32 tile of (cout, cin), tap), the x operand shifted and masked.
+// block per (pixel chunk, 32x32 tile of (cout, cin)) with nine accumulator tiles, one per tap: g is
+// loaded once per pass, x nine times shifted and masked.
 // Partials per pixel chunk, layout [chunk][cout][cin][tap] = the layout of the weights.
 #include "device_utils.h"
 #include "kernels.h"
@@ -97,10 +98,13 @@ struct C3WgArgs {
   const float* g;
   const float* x;
   float* part;
-  int Cin, Cout, H, W, cps, pxw, cot;  // cot = 32-row tiles of cout
+  int Cin, Cout, H, W, cps, pxw;
 };
 
-// block (chunk, ci tile, co tile * 9 + tap); wavefront w of the block takes the w-th quarter of the chunk
+// Block (chunk, ci tile, co tile), all nine taps: a pass loads 16 pixel pairs of g once and the nine
+// shifted, masked versions of x (cache hits after the first), 144 MFMAs per pass into nine
+// accumulator tiles.  Wavefront w of the block takes the w-th quarter of the chunk; the four
+// wavefronts' tiles are added through LDS, tap after tap.
 __global__ __launch_bounds__(256) void conv3x3_wgrad_mfma_f32_kernel(C3WgArgs w) {
   __shared__ float sR[4][16][64];
   const float* __restrict__ g = w.g;
@@ -112,49 +116,153 @@ __global__ __launch_bounds__(256) void conv3x3_wgrad_mfma_f32_kernel(C3WgArgs w)
   const int n = chunk / w.cps;
   const int p0 = ((chunk - n * w.cps) * 4 + wave) * w.pxw;
   const int p1 = min(p0 + w.pxw, HW);
-  const int tap = blockIdx.z / w.cot, cob = blockIdx.z - tap * w.cot;
-  const int du = tap / 3 - 1, dv = tap - (tap / 3) * 3 - 1;
-  const int ci_base = blockIdx.y * 32, co_base = cob * 32;
+  const int ci_base = blockIdx.y * 32, co_base = blockIdx.z * 32;
   const bool av = co_base + row < Cout, bv = ci_base + row < Cin;
   const float* ga = g + ((size_t)n * Cout + (av ? co_base + row : 0)) * HW;
-  const float* xb = x + ((size_t)n * Cin + (bv ? ci_base + row : 0)) * HW + du * W + dv;  // read only where valid
-  floatx16 acc;
+  const float* xb = x + ((size_t)n * Cin + (bv ? ci_base + row : 0)) * HW;
+  floatx16 acc[9];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-  for (int p = p0; p < p1; p += 32) {  // sixteen pixel pairs requested before the first MFMA
-    float a[16], b[16];
-    int pp = p + half;
-    int i = pp / W, j = pp - i * W;
+  for (int t = 0; t < 9; ++t)
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const bool in = pp < p1;
-      a[u] = 0.f;
-      b[u] = 0.f;
-      if (av && in) a[u] = ga[pp];
-      if (bv && in && (unsigned)(i + du) < (unsigned)H && (unsigned)(j + dv) < (unsigned)W) b[u] = xb[pp];
-      pp += 2;
-      j += 2;
-      if (j >= W) {  // at most one row further per step unless the image is narrower than two pixels
-        j -= W;
-        ++i;
-        if (j >= W) { i += j / W; j %= W; }
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+  for (int p = p0; p < p1; p += 32) {
+    float a[16];
+    int iu[16], ju[16];  // image coordinates of this lane's 16 pixels (pixel p + 2u + half)
+    {
+      int pp = p + half;
+      int i = pp / W, j = pp - i * W;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        a[u] = 0.f;
+        if (av && pp < p1) a[u] = ga[pp];
+        iu[u] = pp < p1 ? i : -4;  // beyond the chunk: no tap is valid
+        ju[u] = j;
+        pp += 2;
+        j += 2;
+        if (j >= W) {  // at most one row further per step unless the image is narrower than two pixels
+          j -= W;
+          ++i;
+          if (j >= W) { i += j / W; j %= W; }
+        }
       }
     }
 #pragma unroll
-    for (int u = 0; u < 16; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc, 0, 0, 0);
-  }
+    for (int t = 0; t < 9; ++t) {
+      const int du = t / 3 - 1, dv = t % 3 - 1;
+      const float* xt = xb + p + half + du * W + dv;  // read only where the shifted pixel is inside the image
+      float b[16];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) sR[wave][r][lane] = acc[r];
-  __syncthreads();
+      for (int u = 0; u < 16; ++u) {
+        b[u] = 0.f;
+        if (bv && (unsigned)(iu[u] + du) < (unsigned)H && (unsigned)(ju[u] + dv) < (unsigned)W) b[u] = xt[2 * u];
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc[t], 0, 0, 0);
+    }
+  }
   float* out = w.part + (size_t)chunk * Cout * Cin * 9;
   const int ci = ci_base + row;
-  if (ci < Cin) {
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const int r = 4 * wave + rr;
-      const int co = co_base + 8 * (r >> 2) + 4 * half + (r & 3);
-      if (co < Cout)
-        out[((size_t)co * Cin + ci) * 9 + tap] = (sR[0][r][lane] + sR[1][r][lane]) + (sR[2][r][lane] + sR[3][r][lane]);
+  for (int t = 0; t < 9; ++t) {
+    if (t) __syncthreads();  // the previous tap's tiles have been read
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sR[wave][r][lane] = acc[t][r];
+    __syncthreads();
+    if (ci < Cin) {
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int r = 4 * wave + rr;
+        const int co = co_base + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (co < Cout)
+          out[((size_t)co * Cin + ci) * 9 + t] = (sR[0][r][lane] + sR[1][r][lane]) + (sR[2][r][lane] + sR[3][r][lane]);
+      }
+    }
+  }
+}
+
+// The same for W % 4 == 0 (so H*W % 4 == 0 and every aligned group of four pixels lies in one image
+// row): 16-byte loads.  A lane's fragment is eight pixels b .. b+7 (b = p + 16f + 8*half): g as two
+// float4, and per row shift du the two float4 of x at b + du*W plus the pixel to the left of the
+// first and to the right of the second; the three column shifts are re-combinations of these ten
+// values (left / right neighbours are zero at the image border).  28 load instructions feed the
+// 144 MFMAs of a pass (two fragments), against 160 in the scalar kernel.
+__global__ __launch_bounds__(256) void conv3x3_wgrad_vec_mfma_f32_kernel(C3WgArgs w) {
+  __shared__ float sR[4][16][64];
+  const float* __restrict__ g = w.g;
+  const float* __restrict__ x = w.x;
+  const int Cin = w.Cin, Cout = w.Cout, H = w.H, W = w.W, HW = w.H * w.W;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = lane & 31, half = lane >> 5;
+  const int chunk = blockIdx.x;
+  const int n = chunk / w.cps;
+  const int p0 = ((chunk - n * w.cps) * 4 + wave) * w.pxw;
+  const int p1 = min(p0 + w.pxw, HW);
+  const int ci_base = blockIdx.y * 32, co_base = blockIdx.z * 32;
+  const bool av = co_base + row < Cout, bv = ci_base + row < Cin;
+  const float* ga = g + ((size_t)n * Cout + (av ? co_base + row : 0)) * HW;
+  const float* xb = x + ((size_t)n * Cin + (bv ? ci_base + row : 0)) * HW;
+  const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  floatx16 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+  for (int p = p0; p < p1; p += 32) {
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+      const int b0 = p + 16 * f + 8 * half, b1 = b0 + 4;   // the fragment's two groups of four pixels
+      const bool in0 = b0 < p1, in1 = b1 < p1;              // (p1 is a multiple of four)
+      float4 a0 = z4, a1 = z4;
+      if (av && in0) a0 = *reinterpret_cast<const float4*>(ga + b0);
+      if (av && in1) a1 = *reinterpret_cast<const float4*>(ga + b1);
+      const int i0 = b0 / W, j0 = b0 - i0 * W;
+      int i1 = i0, j1 = j0 + 4;
+      if (j1 >= W) { j1 -= W; ++i1; }
+#pragma unroll
+      for (int du = -1; du <= 1; ++du) {
+        const bool v0 = bv && in0 && (unsigned)(i0 + du) < (unsigned)H;
+        const bool v1 = bv && in1 && (unsigned)(i1 + du) < (unsigned)H;
+        const float* x0 = xb + b0 + du * W;  // read only where valid
+        const float* x1 = xb + b1 + du * W;
+        float4 f0 = z4, f1 = z4;
+        float l0 = 0.f, r1 = 0.f;
+        if (v0) f0 = *reinterpret_cast<const float4*>(x0);
+        if (v1) f1 = *reinterpret_cast<const float4*>(x1);
+        if (v0 && j0 > 0) l0 = x0[-1];
+        if (v1 && j1 + 4 < W) r1 = x1[4];
+        // neighbours across the two groups: only inside one image row
+        const float r0 = (j0 + 4 < W) ? f1.x : 0.f;
+        const float l1 = (j1 > 0) ? f0.w : 0.f;
+        const float xm[8] = {l0, f0.x, f0.y, f0.z, l1, f1.x, f1.y, f1.z};    // column shift -1
+        const float xc[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};  // 0
+        const float xp[8] = {f0.y, f0.z, f0.w, r0, f1.y, f1.z, f1.w, r1};      // +1
+        const float av8[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        const int t0 = (du + 1) * 3;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[t0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av8[e], xm[e], acc[t0], 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[t0 + 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av8[e], xc[e], acc[t0 + 1], 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[t0 + 2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av8[e], xp[e], acc[t0 + 2], 0, 0, 0);
+      }
+    }
+  }
+  float* out = w.part + (size_t)chunk * Cout * Cin * 9;
+  const int ci = ci_base + row;
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    if (t) __syncthreads();  // the previous tap's tiles have been read
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sR[wave][r][lane] = acc[t][r];
+    __syncthreads();
+    if (ci < Cin) {
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int r = 4 * wave + rr;
+        const int co = co_base + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (co < Cout)
+          out[((size_t)co * Cin + ci) * 9 + t] = (sR[0][r][lane] + sR[1][r][lane]) + (sR[2][r][lane] + sR[3][r][lane]);
+      }
     }
   }
 }
@@ -178,10 +286,10 @@ __global__ __launch_bounds__(256) void conv3x3_reduce_kernel(const float* __rest
 // pixels per wavefront of the weight-gradient kernel: the largest of {256, 128, 64, 32} that still
 // gives about a thousand blocks
 int c3_pxw(int N, int Cin, int Cout, int HW) {
-  const long tiles = (long)cdiv(Cin, 32) * cdiv(Cout, 32) * 9;
+  const long tiles = (long)cdiv(Cin, 32) * cdiv(Cout, 32);
   const int cand[4] = {256, 128, 64, 32};
   for (int c : cand)
-    if ((long)N * cdiv(HW, 4 * c) * tiles >= 1024) return c;
+    if ((long)N * cdiv(HW, 4 * c) * tiles >= 768) return c;
   return 32;
 }
 
@@ -226,9 +334,9 @@ void conv3x3_mfma_bwd_f32(hipStream_t st, const float* Wp_t, const float* g, flo
   w.Cin = Cin; w.Cout = Cout; w.H = H; w.W = W;
   w.pxw = c3_pxw(N, Cin, Cout, H * W);
   w.cps = cdiv(H * W, 4 * w.pxw);
-  w.cot = cdiv(Cout, 32);
-  const dim3 grid((unsigned)(N * w.cps), (unsigned)cdiv(Cin, 32), (unsigned)(w.cot * 9));
-  KLAUNCH(conv3x3_wgrad_mfma_f32_kernel, grid, dim3(256), 0, st, w);
+  const dim3 grid((unsigned)(N * w.cps), (unsigned)cdiv(Cin, 32), (unsigned)cdiv(Cout, 32));
+  if (W % 4 == 0) KLAUNCH(conv3x3_wgrad_vec_mfma_f32_kernel, grid, dim3(256), 0, st, w);
+  else KLAUNCH(conv3x3_wgrad_mfma_f32_kernel, grid, dim3(256), 0, st, w);
   const size_t n = (size_t)Cin * Cout * 9;
   if (G) KLAUNCH(conv3x3_reduce_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, part, G, n, (int)grid.x);
 }

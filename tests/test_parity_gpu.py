@@ -268,6 +268,10 @@ def test_efficientnet_b1_small(A):
     (8, 8, 6, 1, 2, False),        # one column
     (128, 128, 8, 8, 1, False),    # four channel passes
     (16, 8, 33, 33, 2, False),     # several pixel chunks per plane in the weight gradient
+    (8, 8, 3, 4, 2, False),        # W % 4 == 0 (16-byte weight-gradient loads), H*W not a multiple of 8
+    (16, 16, 28, 28, 2, False),    # rows of 28: the two groups of a fragment lie in different rows
+    (8, 16, 5, 8, 3, True),
+    (24, 8, 2, 40, 1, False),      # wide and flat
 ])
 @pytest.mark.parametrize("need_dx", [True, False])
 def test_dense_conv3x3(A, cin, cout, h, w, B, bias, need_dx):
