@@ -109,6 +109,17 @@ def kernel_model(cfg):
                     out.setdefault("pw_bwd_dual_kernel<%s>" % bc, []).append(4 * (2 * cin + cout) * nq + extra)
             else:
                 out.setdefault(wg_name, []).append(4 * (cin + cout) * nq)                   # g and x in
+        if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 3 and L["groups"] == 1 and L["stride"] == 1 \
+                and L["pad"] == 1 and L["cin"] >= 8 and L["cout"] >= 8:
+            # dense 3x3 on the matrix cores: flops of one product (forward; the input gradient is the same
+            # kernel with the channel roles exchanged) and of the weight gradient
+            c, h, w = shape
+            flops = 2.0 * 9 * L["cin"] * L["cout"] * B * h * w
+            out.setdefault("conv3x3_mfma_f32_kernel", []).append(flops)
+            if not first or cfg.needs_input_grad:
+                out.setdefault("conv3x3_mfma_f32_kernel", []).append(flops)
+            wg = "conv3x3_wgrad_vec_mfma_f32_kernel" if w % 4 == 0 else "conv3x3_wgrad_mfma_f32_kernel"
+            out.setdefault(wg, []).append(flops)
         if k == "conv2d" and cfg.dtype == "f32" and L["k"] == 5 and L["groups"] == L["cin"] == L["cout"]:
             c, h, w = shape
             oc, oh, ow = oshape
@@ -200,6 +211,7 @@ DOMINANT = {
     "cfg4": ("gemm_bf16_kernel<128x128,im2col>", "mfma"),
     "cfg5": ("gemm_bf16_kernel<128x128,wgrad_rows>", "mfma"),
     "cfg6": ("pw_bwd_dual_kernel<pk2>", "hbm"),
+    "cfg7": ("conv3x3_mfma_f32_kernel", "mfma"),
 }
 
 # HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
@@ -213,7 +225,7 @@ TRAFFIC_BYTES = {
 
 
 def kernel_bound(name):
-    return "mfma" if name.startswith(("gemm_bf16", "attention")) else "hbm"
+    return "mfma" if name.startswith(("gemm_bf16", "attention", "conv3x3_")) else "hbm"
 
 
 def dominant_kernel(cfg, workload):

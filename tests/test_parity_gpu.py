@@ -493,6 +493,14 @@ def test_cfg2_full_golden(A):
     assert sc["G_median"] <= 1e-3
 
 
+def test_cfg7_full_golden(A):
+    # Derived bar: PyTorch CPU fp32 on this input deviates from the fp64 oracle by 1.6e-3 (dx), 1.5e-3 (median
+    # over the parameter tensors) and 2.1e-3 (worst tensor): nine BatchNorms over 100 352 values per channel
+    # under an unnormalised upstream gradient.  The forward holds 1e-4; 5e-3 bounds every gradient.
+    sc = golden_check("cfg7", 1e-4, 5e-3, 5e-3, 5e-3)
+    assert sc["G_median"] <= 3e-3
+
+
 def test_cfg6_full_golden(A):
     golden_check("cfg6", 1e-4, 1e-3, 1e-3, 1e-3)
 
