@@ -31,7 +31,9 @@ struct C3Args {
   size_t tap_stride;
 };
 
-template <int NCH>
+// MT = 32-row tiles of output channels per wavefront (1 or 2): with two, a pixel operand loaded once
+// feeds both tiles.
+template <int NCH, int MT>
 __global__ __launch_bounds__(256) void conv3x3_mfma_f32_kernel(C3Args a) {
   const float4* __restrict__ Wp = a.Wp;
   const float* __restrict__ X = a.X;
@@ -40,7 +42,7 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_f32_kernel(C3Args a) {
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int m_base = blockIdx.y * 32;
+  const int tile0 = blockIdx.y * MT;  // first 32-row tile of this block
   const long q = (long)blockIdx.x * 128 + wave * 32 + col;
   const bool qv = q < a.NQ;
   long n = 0;
@@ -51,21 +53,26 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_f32_kernel(C3Args a) {
   }
   const int pi = p / W, pj = p - pi * W;
   const float* xq = X + (size_t)n * Kdim * HW + p;
-  const float4* wl = Wp + (size_t)blockIdx.y * KG * 64 + lane;
-  floatx16 acc;
+  const float4* wl = Wp + (size_t)tile0 * KG * 64 + lane;
+  const bool t1 = MT > 1 && (tile0 + 1) * 32 < Mdim;  // the second tile exists (uniform)
+  floatx16 acc[MT];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
   for (int tap = 0; tap < 9; ++tap) {
     const int du = tap / 3 - 1, dv = tap - (tap / 3) * 3 - 1;
     const bool ok = qv && (unsigned)(pi + du) < (unsigned)H && (unsigned)(pj + dv) < (unsigned)W;
     const float* xt = xq + du * W + dv;  // dereferenced only where ok
     const float4* wt = wl + (size_t)tap * a.tap_stride;
     for (int g0 = 0; g0 < KG; g0 += NCH * 4) {
-      float4 av[NCH * 4];
+      float4 av[MT][NCH * 4];
       float b[NCH * 16];
 #pragma unroll
       for (int g = 0; g < NCH * 4; ++g) {
-        av[g] = g0 + g < KG ? wt[(size_t)(g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
+        const bool gv = g0 + g < KG;
+        av[0][g] = gv ? wt[(size_t)(g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (MT > 1) av[MT - 1][g] = (gv && t1) ? wt[(size_t)(KG + g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int k = (g0 + g) * 8 + 2 * e + half;
@@ -77,20 +84,25 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_f32_kernel(C3Args a) {
 #pragma unroll
       for (int g = 0; g < NCH * 4; ++g) {
         if (g0 + g >= KG) break;  // uniform
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].x, b[4 * g + 0], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].y, b[4 * g + 1], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].z, b[4 * g + 2], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].w, b[4 * g + 3], acc, 0, 0, 0);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+          acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m][g].x, b[4 * g + 0], acc[m], 0, 0, 0);
+          acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m][g].y, b[4 * g + 1], acc[m], 0, 0, 0);
+          acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m][g].z, b[4 * g + 2], acc[m], 0, 0, 0);
+          acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m][g].w, b[4 * g + 3], acc[m], 0, 0, 0);
+        }
       }
     }
   }
   if (qv) {
     float* yq = Y + (size_t)n * Mdim * HW + p;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
-      if (m < Mdim) yq[(size_t)m * HW] = acc[r] + (a.bias ? a.bias[m] : 0.f);
-    }
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = (tile0 + mt) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (m < Mdim) yq[(size_t)m * HW] = acc[mt][r] + (a.bias ? a.bias[m] : 0.f);
+      }
   }
 }
 
@@ -301,9 +313,16 @@ void launch_product(hipStream_t st, const float* Wp, const float* X, float* Y, c
   a.NQ = (long)N * H * W;
   a.H = H; a.W = W; a.Kdim = Kdim; a.Mdim = Mdim; a.KG = cdiv(Kdim, 8);
   a.tap_stride = pw_pack_floats(Mdim, Kdim) / 4;
-  const dim3 grid((unsigned)cdiv(a.NQ, 128), (unsigned)cdiv(Mdim, 32));
-  if (Kdim > 32) KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<2>), grid, dim3(256), 0, st, a);
-  else KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<1>), grid, dim3(256), 0, st, a);
+  // two tiles of output channels per wavefront while that leaves two blocks per compute unit
+  const int mt = (Mdim > 32 && (long)cdiv(a.NQ, 128) * cdiv(Mdim, 64) >= 512) ? 2 : 1;
+  const dim3 grid((unsigned)cdiv(a.NQ, 128), (unsigned)cdiv(Mdim, 32 * mt));
+  if (mt == 2) {
+    if (Kdim > 32) KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<2, 2>), grid, dim3(256), 0, st, a);
+    else KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<1, 2>), grid, dim3(256), 0, st, a);
+  } else {
+    if (Kdim > 32) KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<2, 1>), grid, dim3(256), 0, st, a);
+    else KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<1, 1>), grid, dim3(256), 0, st, a);
+  }
 }
 
 }  // namespace

@@ -272,6 +272,7 @@ def test_efficientnet_b1_small(A):
     (16, 16, 28, 28, 2, False),    # rows of 28: the two groups of a fragment lie in different rows
     (8, 16, 5, 8, 3, True),
     (24, 8, 2, 40, 1, False),      # wide and flat
+    (8, 72, 128, 128, 2, False),   # enough pixels for two output-channel tiles per wavefront; the last block has one
 ])
 @pytest.mark.parametrize("need_dx", [True, False])
 def test_dense_conv3x3(A, cin, cout, h, w, B, bias, need_dx):
