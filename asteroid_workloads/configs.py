@@ -225,5 +225,5 @@ CONFIGS = {
 
 
 def get_config(name, **kw):
-    """Full-size config by name ("cfg1".."cfg6"); keyword overrides shrink it for tests."""
+    """Full-size config by name ("cfg1".."cfg7"); keyword overrides shrink it for tests."""
     return CONFIGS[name](**kw)
