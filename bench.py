@@ -211,7 +211,7 @@ DOMINANT = {
     "cfg4": ("gemm_bf16_kernel<128x128,im2col>", "mfma"),
     "cfg5": ("gemm_bf16_kernel<128x128,wgrad_rows>", "mfma"),
     "cfg6": ("pw_bwd_dual_kernel<pk2>", "hbm"),
-    "cfg7": ("conv3x3_mfma_f32_kernel", "mfma"),
+    "cfg7": ("pw_bwd_dual_kernel<pk4>", "hbm"),
 }
 
 # HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
