@@ -6,7 +6,8 @@ into M micro-batches of size B.  Micro-batch m holds samples [m*B, (m+1)*B).
 Layer dictionaries (keys are plain ints/floats/bools):
   conv2d       cin cout k stride pad groups bias
   batchnorm2d  c eps
-  relu / relu6 / gelu / swish / sigmoid / res_begin / res_add / global_avgpool / maxpool2x2 / softmax_ce
+  relu / relu6 / gelu / swish / sigmoid / res_begin / res_add / global_avgpool / maxpool2x2 /
+  maxpool3x3s2 (3x3 window, stride 2, padding 1) / softmax_ce
   res_swap     inside res_begin ... res_add: ends the main branch; the layers from here to res_add
                form the shortcut branch and run on the tensor res_begin remembered
   se_begin ... se_scale   squeeze-and-excitation: the layers in between (global_avgpool, linear,
@@ -130,6 +131,23 @@ def bottleneck(cin, mid, stride=1):
     return L + [simple("res_add"), simple("relu")]
 
 
+# (mid channels, blocks, stride of the first block) of ResNet50's four block groups
+RESNET50_SCHEDULE = [(64, 3, 1), (128, 4, 2), (256, 6, 2), (512, 3, 2)]
+
+
+def resnet50_layers(num_classes=1000, schedule=RESNET50_SCHEDULE, stem=64):
+    """ResNet50 (Table 4 workload): 7x7 stride-2 stem, BN, ReLU, 3x3 stride-2 max-pool, 16 bottleneck
+    blocks (the stride sits on the 3x3 convolution), pooled classifier."""
+    L = [conv(3, stem, 7, 2, 3), bn(stem), simple("relu"), simple("maxpool3x3s2")]
+    cin = stem
+    for mid, n, s in schedule:
+        for i in range(n):
+            L += bottleneck(cin, mid, s if i == 0 else 1)
+            cin = 4 * mid
+    L += [simple("global_avgpool"), linear(cin, num_classes), simple("softmax_ce")]
+    return L
+
+
 def encoder_layer(d, heads, ffn, eps=1e-5):
     """Post-LN encoder layer: h = LN(x + MHA(x)); y = LN(h + W2 GELU(W1 h + b1) + b2)."""
     return [simple("res_begin"), dict(kind="mha", d=d, heads=heads), simple("res_add"),
@@ -218,9 +236,15 @@ def effnetb1(B=8, M=8, hw=240, seed=1007, num_classes=1000):
                        "f32", "nchw", False, seed)
 
 
+def resnet50(B=8, M=8, hw=224, seed=1009, num_classes=1000):
+    """The whole ResNet50 as one stage (profiler tables; no stored full-size oracle samples)."""
+    return StageConfig("resnet50_full", resnet50_layers(num_classes), B, M, (3, hw, hw), "f32", "nchw",
+                       False, seed)
+
+
 CONFIGS = {
     "cfg1": cfg1, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4, "cfg5": cfg5, "cfg6": cfg6,
-    "cfg7": cfg7, "effnetb1": effnetb1,
+    "cfg7": cfg7, "effnetb1": effnetb1, "resnet50": resnet50,
 }
 
 

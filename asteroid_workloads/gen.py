@@ -103,6 +103,8 @@ def layer_shapes(layers, in_shape):
             s = (L["cout"], ho, wo)
         elif k == "maxpool2x2":
             s = (s[0], s[1] // 2, s[2] // 2)
+        elif k == "maxpool3x3s2":
+            s = (s[0], (s[1] - 1) // 2 + 1, (s[2] - 1) // 2 + 1)
         elif k == "global_avgpool":
             s = (s[0],)
         elif k == "linear":

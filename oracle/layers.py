@@ -190,6 +190,28 @@ def maxpool2x2_bwd(g, idx, h, w):
     return dx
 
 
+def maxpool3x3s2_fwd(x):
+    """3x3 window, stride 2, padding 1 (the pooling behind ResNet's stem; padding never wins: it
+    counts as minus infinity); ties resolved to the first maximum in row-major (u,v) order."""
+    n, c, h, w = x.shape
+    ho, wo = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+    xp = np.full((n, c, 2 * ho + 1, 2 * wo + 1), -np.inf, F)
+    xp[:, :, 1:h + 1, 1:w + 1] = x
+    win = np.stack([xp[:, :, u:u + 2 * ho:2, v:v + 2 * wo:2] for u in range(3) for v in range(3)], axis=-1)
+    idx = win.argmax(axis=-1)
+    y = np.take_along_axis(win, idx[..., None], axis=-1)[..., 0]
+    return y, idx
+
+
+def maxpool3x3s2_bwd(g, idx, h, w):
+    n, c, ho, wo = g.shape
+    dp = np.zeros((n, c, 2 * ho + 1, 2 * wo + 1), F)
+    for t in range(9):
+        u, v = divmod(t, 3)
+        dp[:, :, u:u + 2 * ho:2, v:v + 2 * wo:2] += g * (idx == t)
+    return dp[:, :, 1:h + 1, 1:w + 1]
+
+
 # --------------------------------------------------------------------------- linear / loss
 def linear_fwd(x, w, b):
     y = np.matmul(x, w.T)

@@ -198,6 +198,10 @@ class OracleStage:
                 y, idx = L.maxpool2x2_fwd(a)
                 saved.append((idx, a.shape))
                 a = y
+            elif k == "maxpool3x3s2":
+                y, idx = L.maxpool3x3s2_fwd(a)
+                saved.append((idx, a.shape))
+                a = y
             elif k == "linear":
                 saved.append(a)
                 a = L.linear_fwd(a, P[0], P[1] if l["bias"] else None)
@@ -270,6 +274,8 @@ class OracleStage:
                 g = L.global_avgpool_bwd(g, sv[2], sv[3])
             elif k == "maxpool2x2":
                 g = L.maxpool2x2_bwd(g, sv[0], sv[1][2], sv[1][3])
+            elif k == "maxpool3x3s2":
+                g = L.maxpool3x3s2_bwd(g, sv[0], sv[1][2], sv[1][3])
             elif k == "linear":
                 g, grads = L.linear_bwd(sv, P[0], g, l["bias"])
                 self._acc(i, grads)

@@ -63,6 +63,8 @@ def _out_shape(layers, s):
                  (w + 2 * L["pad"] - L["k"]) // L["stride"] + 1)
         elif k == "maxpool2x2":
             s = (s[0], s[1] // 2, s[2] // 2)
+        elif k == "maxpool3x3s2":
+            s = (s[0], (s[1] - 1) // 2 + 1, (s[2] - 1) // 2 + 1)
         elif k == "global_avgpool":
             s = (s[0],)
         elif k == "linear":

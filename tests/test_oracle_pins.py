@@ -396,6 +396,51 @@ def test_two_branch_residual_is_the_sum_of_its_branches():
     np.testing.assert_allclose(res["block"][2], np.concatenate([res["main"][2], res["short"][2]]), atol=1e-12)
 
 
+def test_maxpool3x3s2_brute_force_and_ties():
+    r = RNG(21)
+    for h, w in ((7, 7), (8, 6), (1, 1), (2, 5)):
+        x = r.standard_normal((2, 3, h, w))
+        y, idx = L.maxpool3x3s2_fwd(x)
+        ho, wo = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+        assert y.shape == (2, 3, ho, wo)
+        g = r.standard_normal(y.shape)
+        dx = L.maxpool3x3s2_bwd(g, idx, h, w)
+        ref_y = np.zeros_like(y)
+        ref_dx = np.zeros_like(x)
+        for n in range(2):
+            for c in range(3):
+                for i in range(ho):
+                    for j in range(wo):
+                        best, arg = -np.inf, None
+                        for u in range(3):
+                            for v in range(3):
+                                ii, jj = 2 * i - 1 + u, 2 * j - 1 + v
+                                if 0 <= ii < h and 0 <= jj < w and x[n, c, ii, jj] > best:
+                                    best, arg = x[n, c, ii, jj], (ii, jj)
+                        ref_y[n, c, i, j] = best
+                        ref_dx[n, c, arg[0], arg[1]] += g[n, c, i, j]
+        np.testing.assert_array_equal(y, ref_y)
+        np.testing.assert_allclose(dx, ref_dx, atol=1e-15)
+    # all equal (a ReLU output of zeros): the gradient goes to the first in-image position of each window
+    z = np.zeros((1, 1, 4, 4))
+    y, idx = L.maxpool3x3s2_fwd(z)
+    dx = L.maxpool3x3s2_bwd(np.ones((1, 1, 2, 2)), idx, 4, 4)
+    expect = np.zeros((4, 4))
+    expect[0, 0] = expect[0, 1] = expect[1, 0] = expect[1, 1] = 1.0
+    np.testing.assert_array_equal(dx[0, 0], expect)
+
+
+def test_resnet50_schedule():
+    """16 bottleneck blocks, 25.56 M parameters with the 1000-way classifier (the published count),
+    224 -> 7 spatial, four projection shortcuts."""
+    Ls = C.resnet50_layers()
+    assert sum(1 for l in Ls if l["kind"] == "res_add") == 16
+    assert sum(1 for l in Ls if l["kind"] == "res_swap") == 4
+    assert gen.out_shape(Ls[:-3], (3, 224, 224)) == (2048, 7, 7)
+    n = gen.num_params(Ls)
+    assert abs(n - 25.557e6) < 0.01e6, n
+
+
 def test_efficientnet_b1_schedule():
     """23 MBConv blocks, 7.8 M parameters with the 1000-way classifier (the published count of
     EfficientNet-B1), 240 -> 8 spatial, every block with its squeeze-and-excitation."""
@@ -479,6 +524,8 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False)
                 a = a.mean(dim=(2, 3))
             elif k == "maxpool2x2":
                 a = TF.max_pool2d(a, 2, 2)
+            elif k == "maxpool3x3s2":
+                a = TF.max_pool2d(a, 3, 2, 1)
             elif k == "linear":
                 w = rb(take((l["cout"], l["cin"])))
                 b = take((l["cout"],)) if l["bias"] else None
@@ -513,6 +560,7 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False)
     C.cfg5(B=2, M=2, S=7, d=16, heads=2, ffn=24, nlayers=2),
     C.cfg6(B=3, M=2, hw=10),
     C.cfg7(B=3, M=2, hw=7, cin=8, mid=4, blocks=2),
+    C.StageConfig("stem_pool", [C.conv(3, 8, 7, 2, 3), C.bn(8), C.simple("relu"), C.simple("maxpool3x3s2")], 2, 2, (3, 17, 15), "f32", "nchw", True, 33),
     C.StageConfig("strided_bottlenecks", C.bottleneck(8, 4, 2) + C.bottleneck(16, 4), 3, 2, (8, 9, 9), "f32", "nchw", True, 31),
 ], ids=lambda c: c.name)
 def test_stage_matches_torch_float64_autograd(cfg):
