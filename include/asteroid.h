@@ -78,11 +78,13 @@ typedef enum {
   AST_SE_SCALE = 16,   /* y[b][c][h][w] = x[b][c][h][w] * gate[b][c], x from the matching
                           AST_SE_BEGIN; the gradient reaches x through the product and through
                           the gate                                                             */
-  AST_RES_SWAP = 17    /* inside AST_RES_BEGIN ... AST_RES_ADD: ends the main branch of a two-branch
+  AST_RES_SWAP = 17,   /* inside AST_RES_BEGIN ... AST_RES_ADD: ends the main branch of a two-branch
                           residual block (a ResNet block with a projection shortcut; Table 4
                           workload).  The layers from here to AST_RES_ADD are the shortcut branch:
                           they run on the tensor AST_RES_BEGIN remembered, and AST_RES_ADD adds
                           the main branch's result to theirs                                    */
+  AST_MAXPOOL3X3S2 = 18 /* 3x3 window, stride 2, padding 1 (padding never wins); fp32 stages; gradient
+                          to the first maximum in row-major order                               */
 } ast_layer_kind;
 
 typedef struct {

@@ -11,7 +11,7 @@ STATUS = {0: "AST_OK", -1: "AST_EINVAL", -2: "AST_ESTATE", -3: "AST_ENOMEM", -4:
           -5: "AST_EUNSUPPORTED"}
 KINDS = {"conv2d": 0, "batchnorm2d": 1, "relu": 2, "relu6": 3, "res_begin": 4, "res_add": 5,
          "global_avgpool": 6, "linear": 7, "softmax_ce": 8, "maxpool2x2": 9, "layernorm": 10,
-         "mha": 11, "gelu": 12, "swish": 13, "sigmoid": 14, "se_begin": 15, "se_scale": 16, "res_swap": 17}
+         "mha": 11, "gelu": 12, "swish": 13, "sigmoid": 14, "se_begin": 15, "se_scale": 16, "res_swap": 17, "maxpool3x3s2": 18}
 DTYPES = {"f32": 0, "bf16": 1}
 LAYOUTS = {"nchw": 0, "nhwc": 1, "bsd": 2}
 

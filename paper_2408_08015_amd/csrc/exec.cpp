@@ -155,6 +155,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       break;
     case OP_MAXPOOL:
       if (s.bf16) maxpool_fwd_bf16(st, (cb)act_ptr(c, op.in), (bf16_t*)act_ptr(c, op.out), I.n, I.h, I.w, I.c);
+      else if (op.k == 3) maxpool3x3s2_fwd_f32(st, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out), I.n * I.c, I.h, I.w);
       else maxpool_fwd_f32(st, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out), I.n * I.c, I.h, I.w);
       break;
     case OP_LINEAR:
@@ -353,6 +354,8 @@ void bwd_op(Ctx& c, const Op& op) {
     case OP_MAXPOOL:
       if (!gin) break;
       if (s.bf16) maxpool_bwd_bf16(st, (cb)grad_ptr(c, op.out), (cb)act_ptr(c, op.in), (bf16_t*)gin, I.n, I.h, I.w, I.c);
+      else if (op.k == 3)
+        maxpool3x3s2_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), (float*)gin, I.n * I.c, I.h, I.w);
       else maxpool_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), (float*)gin, I.n * I.c, I.h, I.w);
       break;
     case OP_LINEAR:

@@ -223,6 +223,10 @@ void se_gate_bwd_f32(hipStream_t st, const float* dgate, const float* z, const f
 void se_scale_fwd_f32(hipStream_t st, const float* x, const float* gate, float* y, int NC, int HW);
 void se_scale_bwd_f32(hipStream_t st, const float* dy, const float* x, const float* gate, float* dgate, float* dx,
                       int NC, int HW);
+// 3x3 window, stride 2, padding 1 (padding never wins); backward in gather form: an input position collects
+// the gradient of every window whose first maximum (row-major) it is
+void maxpool3x3s2_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int H, int W);
+void maxpool3x3s2_bwd_f32(hipStream_t st, const float* g, const float* x, float* dx, int NC, int H, int W);
 void maxpool_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int H, int W);
 void maxpool_bwd_f32(hipStream_t st, const float* g, const float* x, float* dx, int NC, int H, int W);
 

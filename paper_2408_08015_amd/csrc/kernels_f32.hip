@@ -518,6 +518,70 @@ void se_scale_bwd_f32(hipStream_t st, const float* dy, const float* x, const flo
   KLAUNCH(se_scale_bwd_kernel, dim3(cdiv(NC, 4)), dim3(256), 0, st, dy, x, gate, dgate, dx, NC, HW);
 }
 
+// first maximum (row-major) of the 3x3 window of output (i, j): window rows 2i-1 .. 2i+1, columns 2j-1 .. 2j+1,
+// positions outside the image skipped.  Returns the flat input index; the window always holds (2i, 2j).
+__device__ __forceinline__ int maxpool3_argmax(const float* __restrict__ xp, int H, int W, int i, int j, float& best) {
+  int arg = -1;
+  best = 0.f;
+#pragma unroll
+  for (int u = 0; u < 3; ++u) {
+    const int ii = 2 * i - 1 + u;
+    if (ii < 0 || ii >= H) continue;
+#pragma unroll
+    for (int v = 0; v < 3; ++v) {
+      const int jj = 2 * j - 1 + v;
+      if (jj < 0 || jj >= W) continue;
+      const float val = xp[(size_t)ii * W + jj];
+      if (arg < 0 || val > best) { best = val; arg = ii * W + jj; }
+    }
+  }
+  return arg;
+}
+__global__ void maxpool3x3s2_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int H, int W, int Ho, int Wo,
+                                        size_t total) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int j = (int)(idx % Wo);
+  const size_t t = idx / Wo;
+  const int i = (int)(t % Ho);
+  const size_t plane = t / Ho;
+  float best;
+  maxpool3_argmax(x + plane * H * W, H, W, i, j, best);
+  y[idx] = best;
+}
+// thread per input position: the windows that hold it are those of outputs (ceil((r-1)/2) .. floor((r+1)/2)) per axis
+__global__ void maxpool3x3s2_bwd_kernel(const float* __restrict__ g, const float* __restrict__ x, float* __restrict__ dx,
+                                        int H, int W, int Ho, int Wo, size_t total) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int c = (int)(idx % W);
+  const size_t t = idx / W;
+  const int r = (int)(t % H);
+  const size_t plane = t / H;
+  const float* xp = x + plane * H * W;
+  const float* gp = g + plane * Ho * Wo;
+  const int self = r * W + c;
+  float acc = 0.f;
+  const int i0 = r / 2, i1 = min((r + 1) / 2, Ho - 1);   // ceil((r-1)/2) = r/2 for r >= 0
+  const int j0 = c / 2, j1 = min((c + 1) / 2, Wo - 1);
+  for (int i = i0; i <= i1; ++i)
+    for (int j = j0; j <= j1; ++j) {
+      float best;
+      if (maxpool3_argmax(xp, H, W, i, j, best) == self) acc += gp[(size_t)i * Wo + j];
+    }
+  dx[idx] = acc;
+}
+void maxpool3x3s2_fwd_f32(hipStream_t st, const float* x, float* y, int NC, int H, int W) {
+  const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
+  const size_t total = (size_t)NC * Ho * Wo;
+  KLAUNCH(maxpool3x3s2_fwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, x, y, H, W, Ho, Wo, total);
+}
+void maxpool3x3s2_bwd_f32(hipStream_t st, const float* g, const float* x, float* dx, int NC, int H, int W) {
+  const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
+  const size_t total = (size_t)NC * H * W;
+  KLAUNCH(maxpool3x3s2_bwd_kernel, dim3(cdiv(total, 256)), dim3(256), 0, st, g, x, dx, H, W, Ho, Wo, total);
+}
+
 __device__ __forceinline__ int first_argmax4(float a, float b, float c, float d) {
   int k = 0;
   float m = a;

@@ -203,8 +203,14 @@ ast_status build_plan(Stage& s, std::string& err) {
       case AST_MAXPOOL2X2: {
         if (A.rank != 4 || A.h < 2 || A.w < 2) { err = fmt("layer %d: maxpool needs an image of at least 2x2", i); return AST_EINVAL; }
         if (s.bf16 && A.c % 8) { err = fmt("layer %d: bf16 maxpool needs channels %% 8 == 0", i); return AST_EUNSUPPORTED; }
-        op.kind = OP_MAXPOOL;
+        op.kind = OP_MAXPOOL; op.k = 2; op.stride = 2; op.pad = 0;
         op.out = cur = new_act(s, B, A.c, A.h / 2, A.w / 2, 4, i, es);
+        break;
+      }
+      case AST_MAXPOOL3X3S2: {
+        if (s.bf16 || A.rank != 4) { err = fmt("layer %d: the 3x3 stride-2 max-pool needs an fp32 image tensor", i); return AST_EUNSUPPORTED; }
+        op.kind = OP_MAXPOOL; op.k = 3; op.stride = 2; op.pad = 1;
+        op.out = cur = new_act(s, B, A.c, (A.h - 1) / 2 + 1, (A.w - 1) / 2 + 1, 4, i, es);
         break;
       }
       case AST_LINEAR: {

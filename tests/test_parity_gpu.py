@@ -305,6 +305,18 @@ def test_resnet_bottleneck(A, cin, mid, stride, hw, B):
     check(one(L, (cin, hw, hw), B=B), rounds=1)
 
 
+@pytest.mark.parametrize("c,h,w,B", [(8, 7, 7, 2), (16, 8, 6, 3), (4, 1, 1, 2), (3, 2, 5, 2), (64, 112, 112, 1), (5, 9, 16, 2)])
+def test_maxpool3x3s2(A, c, h, w, B):
+    """Behind a ReLU half of the values are equal zeros: the gradient must go to the first maximum of each window."""
+    check(one([simple("relu"), simple("maxpool3x3s2")], (c, h, w), B=B), rounds=1)
+    check(one([simple("maxpool3x3s2")], (c, h, w), B=B, needs_input_grad=True), rounds=1)
+
+
+def test_resnet50_small(A):
+    # the whole model at a small resolution: 53 stacked BatchNorms over few elements (bar as for the other whole models)
+    check(C.resnet50(B=8, M=2, hw=64, num_classes=24), tol_y=1e-4, tol_g=5e-2, rounds=1)
+
+
 def test_cfg7_small(A):
     check(C.cfg7(B=3, M=2, hw=8, cin=16, mid=8, blocks=2), rounds=1)
     check(C.cfg7(B=2, M=3, hw=12, cin=64, mid=64, blocks=3), rounds=1, K=2)
