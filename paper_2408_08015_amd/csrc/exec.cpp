@@ -99,8 +99,8 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       break;
     }
     case OP_CONV_3X3:
-      conv3x3_mfma_fwd_f32(st, s.wpack + op.wp_off, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out),
-                           op.has_bias ? s.W + op.b_off : nullptr, I.n, op.cin, op.cout, I.h, I.w);
+      conv_mfma_fwd_f32(st, s.wpack + op.wp_off, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out),
+                        op.has_bias ? s.W + op.b_off : nullptr, I.n, op.cin, op.cout, I.h, I.w, op.k, op.stride);
       break;
     case OP_CONV_DWK:
       dwk_fwd_f32(st, (cf)act_ptr(c, op.in), s.W + op.w_off, (float*)act_ptr(c, op.out), I.n, I.c, I.h, I.w, op.k,
@@ -264,10 +264,11 @@ void bwd_op(Ctx& c, const Op& op) {
     }
     case OP_CONV_3X3: {
       cf g = (cf)grad_ptr(c, op.out);
-      conv3x3_mfma_bwd_f32(st, s.wpack + op.wp2_off, g, (float*)gin, (cf)act_ptr(c, op.in),
-                           reinterpret_cast<float*>(scratch(c, op)), s.red_nblocks ? nullptr : s.G + op.w_off, I.n, op.cin,
-                           op.cout, I.h, I.w);
-      if (op.has_bias) channel_sum_acc_f32(st, g, s.G + op.b_off, I.n, op.cout, HW);
+      const Act& O = s.acts[op.out];
+      conv_mfma_bwd_f32(st, s.wpack + op.wp2_off, g, (float*)gin, (cf)act_ptr(c, op.in),
+                        reinterpret_cast<float*>(scratch(c, op)), s.red_nblocks ? nullptr : s.G + op.w_off, I.n, op.cin,
+                        op.cout, I.h, I.w, op.k, op.stride);
+      if (op.has_bias) channel_sum_acc_f32(st, g, s.G + op.b_off, I.n, op.cout, O.h * O.w);
       break;
     }
     case OP_CONV_DWK:
@@ -491,14 +492,14 @@ static ast_status build_pack_tasks(Stage& s, std::string& err) {
           !add(s.W + op.w_off, 1, op.cin, op.wp2_off, op.cin, op.cout))
         return AST_OK;
     } else if (op.kind == OP_CONV_3X3) {
-      // W[co][ci][tap]: forward copy t is A[co][ci] = W[..][t]; input-gradient copy t is A[ci][co] = W[..][8 - t]
-      if (tasks.size() + 18 >= 65535) return AST_OK;
+      // W[co][ci][tap]: forward copy t is A[co][ci] = W[..][t]; input-gradient copy t is A[ci][co] = W[..][t]
+      const int kk = op.k * op.k;
+      if (tasks.size() + 2 * kk >= 65535) return AST_OK;
       const float* W = s.W + op.w_off;
-      for (int t = 0; t < 9; ++t)
-        if (!add(W + t, op.cin * 9, 9, op.wp_off + t * pw_pack_floats(op.cout, op.cin), op.cout, op.cin)) return AST_OK;
-      for (int t = 0; t < 9; ++t)
-        if (!add(W + (8 - t), 9, op.cin * 9, op.wp2_off + t * pw_pack_floats(op.cin, op.cout), op.cin, op.cout))
-          return AST_OK;
+      for (int t = 0; t < kk; ++t)
+        if (!add(W + t, op.cin * kk, kk, op.wp_off + t * pw_pack_floats(op.cout, op.cin), op.cout, op.cin)) return AST_OK;
+      for (int t = 0; t < kk; ++t)
+        if (!add(W + t, kk, op.cin * kk, op.wp2_off + t * pw_pack_floats(op.cin, op.cout), op.cin, op.cout)) return AST_OK;
     }
   if (tasks.empty()) return AST_OK;
   hipError_t e;
@@ -550,8 +551,8 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
         break;
       }
       case OP_CONV_3X3: {
-        const size_t n = (size_t)op.cin * op.cout * 9;
-        add(scf, s.G + op.w_off, n, conv3x3_wgrad_parts(I.n, op.cin, op.cout, I.h, I.w), n, 1, n);
+        const size_t n = (size_t)op.cin * op.cout * op.k * op.k;
+        add(scf, s.G + op.w_off, n, conv_mfma_wgrad_parts(I.n, op.cin, op.cout, I.h, I.w, op.k, op.stride), n, 1, n);
         break;
       }
       case OP_CONV_DW:
@@ -615,9 +616,11 @@ ast_status refresh_shadow(Stage& s, std::string& err) {
     } else if (op.kind == OP_CONV_3X3) {
       if (s.pack_nblocks) continue;
       const float* W = s.W + op.w_off;
-      for (int t = 0; t < 9; ++t) {
-        pw_pack_f32(s.stream, W + t, op.cin * 9, 9, s.wpack + op.wp_off + t * pw_pack_floats(op.cout, op.cin), op.cout, op.cin);
-        pw_pack_f32(s.stream, W + (8 - t), 9, op.cin * 9, s.wpack + op.wp2_off + t * pw_pack_floats(op.cin, op.cout), op.cin,
+      const int kk = op.k * op.k;
+      for (int t = 0; t < kk; ++t) {
+        pw_pack_f32(s.stream, W + t, op.cin * kk, kk, s.wpack + op.wp_off + t * pw_pack_floats(op.cout, op.cin), op.cout,
+                    op.cin);
+        pw_pack_f32(s.stream, W + t, kk, op.cin * kk, s.wpack + op.wp2_off + t * pw_pack_floats(op.cin, op.cout), op.cin,
                     op.cout);
       }
     } else if (!s.bf16) {

@@ -75,19 +75,19 @@ size_t dw3x3_bwd_f32_ws(int N, int C, int H, int W, int stride);
 // sums): one per sample, or several where a plane is split into bands of rows over wavefronts.
 int dw3x3_parts(int N, int C, int H, int W, int stride);
 bool dw3x3_supported(int H, int W, int stride);  // else the generic grouped-conv kernels apply
-// Dense 3x3 conv, stride 1, pad 1, on the matrix cores.  Wp: nine packed copies (pw_pack layout, one per
-// tap, conv3x3_pack_floats(Mdim, Kdim) floats in all): forward copy t holds A[co][ci] = W[co][ci][t],
-// input-gradient copy t holds A[ci][co] = W[co][ci][8 - t].  Backward: dx (may be NULL) and the
-// weight-gradient partials in `part` (conv3x3_wgrad_ws floats, conv3x3_wgrad_parts chunks of
-// [Cout][Cin][9]); G (may be NULL: the caller reduces the partials) += their sum.
-bool conv3x3_mfma_supported(int Cin, int Cout, int k, int stride, int pad, int groups, int H, int W);
-size_t conv3x3_pack_floats(int Mdim, int Kdim);
-int conv3x3_wgrad_parts(int N, int Cin, int Cout, int H, int W);
-size_t conv3x3_wgrad_ws(int N, int Cin, int Cout, int H, int W);
-void conv3x3_mfma_fwd_f32(hipStream_t st, const float* Wp, const float* x, float* y, const float* bias, int N, int Cin,
-                          int Cout, int H, int W);
-void conv3x3_mfma_bwd_f32(hipStream_t st, const float* Wp_t, const float* g, float* dx, const float* x, float* part,
-                          float* G, int N, int Cin, int Cout, int H, int W);
+// Dense conv on the matrix cores: 3x3 pad 1 with stride 1 or 2, and 1x1 stride 2.  Wp: k*k packed copies
+// (pw_pack layout, one per tap, conv_mfma_pack_floats(Mdim, Kdim, k) floats in all): forward copy t holds
+// A[co][ci] = W[co][ci][t], input-gradient copy t holds A[ci][co] = W[co][ci][t].  Backward: dx (may be NULL)
+// and the weight-gradient partials in `part` (conv_mfma_wgrad_ws floats, conv_mfma_wgrad_parts chunks of
+// [Cout][Cin][k*k]); G (may be NULL: the caller reduces the partials) += their sum.
+bool conv_mfma_supported(int Cin, int Cout, int k, int stride, int pad, int groups, int H, int W);
+size_t conv_mfma_pack_floats(int Mdim, int Kdim, int k);
+int conv_mfma_wgrad_parts(int N, int Cin, int Cout, int H, int W, int k, int stride);
+size_t conv_mfma_wgrad_ws(int N, int Cin, int Cout, int H, int W, int k, int stride);
+void conv_mfma_fwd_f32(hipStream_t st, const float* Wp, const float* x, float* y, const float* bias, int N, int Cin,
+                       int Cout, int H, int W, int k, int stride);
+void conv_mfma_bwd_f32(hipStream_t st, const float* Wp_t, const float* g, float* dx, const float* x, float* part,
+                       float* G, int N, int Cin, int Cout, int H, int W, int k, int stride);
 // Depthwise K x K (K = 5), pad K/2, stride 1 or 2, no bias: one block per plane, taps from LDS.
 // Backward: dx (may be NULL), and G[C][K][K] += weight gradient through `part`
 // (dwk_bwd_f32_ws floats of scratch: one K*K partial per plane, added over the samples in order).

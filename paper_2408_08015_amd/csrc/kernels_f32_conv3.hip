@@ -1,15 +1,17 @@
-// fp32 dense 3x3 convolution (stride 1, padding 1) on the matrix cores, for the ResNet workload
-// (Table 4): the nine taps are nine pointwise products accumulated in the same registers.
+// fp32 dense convolutions on the matrix cores for the ResNet workload (Table 4): 3x3 with padding 1
+// and stride 1 or 2, and the 1x1 stride-2 projection of a shortcut.  The KS*KS taps are KS*KS
+// pointwise products accumulated in the same registers.
 //
-// Forward / input gradient: as the pointwise kernel -- a wavefront owns 32 pixels and a 32-row tile
-// of output channels, MFMA 32x32x2 with the pixels on the N dimension, the B operand straight from
-// global memory -- but the pixel of tap (du, dv) is the lane's pixel shifted by du rows and dv
-// columns, zero outside the image, and the A operand of tap t comes from the t-th packed weight
-// copy.  The input gradient is the same kernel on the upstream gradient with the taps mirrored and
-// the channel roles exchanged (a second set of nine packed copies).
-// Weight gradient: as the pointwise weight-gradient kernel (pixels are the contraction index), one
-// block per (pixel chunk, 32x32 tile of (cout, cin)) with nine accumulator tiles, one per tap: g is
-// loaded once per pass, x nine times shifted and masked.
+// Forward / input gradient: as the pointwise kernel -- a wavefront owns 32 pixels of the result and
+// one or two 32-row tiles of its channels, MFMA 32x32x2 with the pixels on the N dimension, the B
+// operand straight from global memory -- but the operand pixel of tap (u, v) is, forward, the
+// result pixel times the stride shifted by (u, v) minus the padding, and, for the input gradient,
+// the output pixel ((r + pad - u) / stride, (c + pad - v) / stride) where that division is exact;
+// zero outside the tensor.  The A operand of tap t comes from the t-th packed weight copy (one set
+// of KS*KS copies per direction).
+// Weight gradient: as the pointwise weight-gradient kernel (output pixels are the contraction
+// index), one block per (pixel chunk, 32x32 tile of (cout, cin)) with KS*KS accumulator tiles, one
+// per tap: g is loaded once per pass, x once per tap, shifted, strided and masked.
 // Partials per pixel chunk, layout [chunk][cout][cin][tap] = the layout of the weights.
 #include "device_utils.h"
 #include "kernels.h"
@@ -22,23 +24,25 @@ namespace {
 inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
 struct C3Args {
-  const float4* Wp;   // nine packed copies, tap_stride float4 words apart
-  const float* X;
-  float* Y;
+  const float4* Wp;   // KS*KS packed copies, tap_stride float4 words apart
+  const float* X;     // operand tensor [N][Kdim][XH][XW]
+  float* Y;           // result tensor  [N][Mdim][PH][PW]
   const float* bias;
-  long NQ;
-  int H, W, Kdim, Mdim, KG;
+  long NQ;            // N * PH * PW
+  int PH, PW, XH, XW, S, Kdim, Mdim, KG;
   size_t tap_stride;
 };
 
-// MT = 32-row tiles of output channels per wavefront (1 or 2): with two, a pixel operand loaded once
-// feeds both tiles.
-template <int NCH, int MT>
-__global__ __launch_bounds__(256) void conv3x3_mfma_f32_kernel(C3Args a) {
+// MT = 32-row tiles of result channels per wavefront (1 or 2): with two, a pixel operand loaded once
+// feeds both tiles.  DGRAD: the operand is the upstream gradient (see the file comment).
+template <int NCH, int MT, int KS, bool DGRAD>
+__global__ __launch_bounds__(256) void conv_mfma_f32_kernel(C3Args a) {
+  constexpr int PAD = KS / 2;
   const float4* __restrict__ Wp = a.Wp;
   const float* __restrict__ X = a.X;
   float* __restrict__ Y = a.Y;
-  const int H = a.H, W = a.W, HW = a.H * a.W, Kdim = a.Kdim, Mdim = a.Mdim, KG = a.KG;
+  const int PW = a.PW, PHW = a.PH * a.PW, XH = a.XH, XW = a.XW, XHW = a.XH * a.XW, S = a.S;
+  const int Kdim = a.Kdim, Mdim = a.Mdim, KG = a.KG;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
@@ -48,11 +52,11 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_f32_kernel(C3Args a) {
   long n = 0;
   int p = 0;
   if (qv) {
-    n = q / HW;
-    p = (int)(q - n * HW);
+    n = q / PHW;
+    p = (int)(q - n * PHW);
   }
-  const int pi = p / W, pj = p - pi * W;
-  const float* xq = X + (size_t)n * Kdim * HW + p;
+  const int pi = p / PW, pj = p - pi * PW;
+  const float* xn = X + (size_t)n * Kdim * XHW;
   const float4* wl = Wp + (size_t)tile0 * KG * 64 + lane;
   const bool t1 = MT > 1 && (tile0 + 1) * 32 < Mdim;  // the second tile exists (uniform)
   floatx16 acc[MT];
@@ -60,10 +64,23 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_f32_kernel(C3Args a) {
   for (int m = 0; m < MT; ++m)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
-  for (int tap = 0; tap < 9; ++tap) {
-    const int du = tap / 3 - 1, dv = tap - (tap / 3) * 3 - 1;
-    const bool ok = qv && (unsigned)(pi + du) < (unsigned)H && (unsigned)(pj + dv) < (unsigned)W;
-    const float* xt = xq + du * W + dv;  // dereferenced only where ok
+  for (int tap = 0; tap < KS * KS; ++tap) {
+    const int u = tap / KS, v = tap - u * KS;
+    int xr, xc;
+    bool ok = qv;
+    if (DGRAD) {
+      const int ar = pi + PAD - u, ac = pj + PAD - v;
+      ok = ok && ar >= 0 && ac >= 0;
+      xr = S == 1 ? ar : ar >> 1;
+      xc = S == 1 ? ac : ac >> 1;
+      if (S == 2) ok = ok && !((ar | ac) & 1);
+    } else {
+      xr = pi * S - PAD + u;
+      xc = pj * S - PAD + v;
+      ok = ok && xr >= 0 && xc >= 0;
+    }
+    ok = ok && xr < XH && xc < XW;
+    const float* xt = xn + xr * XW + xc;  // dereferenced only where ok
     const float4* wt = wl + (size_t)tap * a.tap_stride;
     for (int g0 = 0; g0 < KG; g0 += NCH * 4) {
       float4 av[MT][NCH * 4];
@@ -76,9 +93,9 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_f32_kernel(C3Args a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int k = (g0 + g) * 8 + 2 * e + half;
-          float v = 0.f;
-          if (ok && k < Kdim) v = xt[(size_t)k * HW];
-          b[4 * g + e] = v;
+          float val = 0.f;
+          if (ok && k < Kdim) val = xt[(size_t)k * XHW];
+          b[4 * g + e] = val;
         }
       }
 #pragma unroll
@@ -95,87 +112,89 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_f32_kernel(C3Args a) {
     }
   }
   if (qv) {
-    float* yq = Y + (size_t)n * Mdim * HW + p;
+    float* yq = Y + (size_t)n * Mdim * PHW + p;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = (tile0 + mt) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        if (m < Mdim) yq[(size_t)m * HW] = acc[mt][r] + (a.bias ? a.bias[m] : 0.f);
+        if (m < Mdim) yq[(size_t)m * PHW] = acc[mt][r] + (a.bias ? a.bias[m] : 0.f);
       }
   }
 }
 
 struct C3WgArgs {
-  const float* g;
-  const float* x;
+  const float* g;   // [N][Cout][Ho][Wo]
+  const float* x;   // [N][Cin][H][W]
   float* part;
-  int Cin, Cout, H, W, cps, pxw;
+  int Cin, Cout, H, W, Ho, Wo, S, cps, pxw;
 };
 
-// Block (chunk, ci tile, co tile), all nine taps: a pass loads 16 pixel pairs of g once and the nine
-// shifted, masked versions of x (cache hits after the first), 144 MFMAs per pass into nine
-// accumulator tiles.  Wavefront w of the block takes the w-th quarter of the chunk; the four
-// wavefronts' tiles are added through LDS, tap after tap.
-__global__ __launch_bounds__(256) void conv3x3_wgrad_mfma_f32_kernel(C3WgArgs w) {
+// Block (chunk of output pixels, ci tile, co tile), all KS*KS taps: a pass loads 16 pixel pairs of g
+// once and, per tap, the shifted, strided, masked pixels of x (cache hits after the first tap),
+// 16 MFMAs per tap into that tap's accumulator tile.  Wavefront w of the block takes the w-th
+// quarter of the chunk; the four wavefronts' tiles are added through LDS, tap after tap.
+template <int KS>
+__global__ __launch_bounds__(256) void conv_wgrad_mfma_f32_kernel(C3WgArgs w) {
+  constexpr int PAD = KS / 2, KK = KS * KS;
   __shared__ float sR[4][16][64];
   const float* __restrict__ g = w.g;
   const float* __restrict__ x = w.x;
-  const int Cin = w.Cin, Cout = w.Cout, H = w.H, W = w.W, HW = w.H * w.W;
+  const int Cin = w.Cin, Cout = w.Cout, H = w.H, W = w.W, Wo = w.Wo, HWo = w.Ho * w.Wo, S = w.S;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 31, half = lane >> 5;
   const int chunk = blockIdx.x;
   const int n = chunk / w.cps;
   const int p0 = ((chunk - n * w.cps) * 4 + wave) * w.pxw;
-  const int p1 = min(p0 + w.pxw, HW);
+  const int p1 = min(p0 + w.pxw, HWo);
   const int ci_base = blockIdx.y * 32, co_base = blockIdx.z * 32;
   const bool av = co_base + row < Cout, bv = ci_base + row < Cin;
-  const float* ga = g + ((size_t)n * Cout + (av ? co_base + row : 0)) * HW;
-  const float* xb = x + ((size_t)n * Cin + (bv ? ci_base + row : 0)) * HW;
-  floatx16 acc[9];
+  const float* ga = g + ((size_t)n * Cout + (av ? co_base + row : 0)) * HWo;
+  const float* xb = x + ((size_t)n * Cin + (bv ? ci_base + row : 0)) * H * W;
+  floatx16 acc[KK];
 #pragma unroll
-  for (int t = 0; t < 9; ++t)
+  for (int t = 0; t < KK; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
   for (int p = p0; p < p1; p += 32) {
     float a[16];
-    int iu[16], ju[16];  // image coordinates of this lane's 16 pixels (pixel p + 2u + half)
+    int iu[16], ju[16];  // x coordinates of tap (0, 0) for this lane's 16 output pixels (pixel p + 2u + half)
     {
       int pp = p + half;
-      int i = pp / W, j = pp - i * W;
+      int i = pp / Wo, j = pp - i * Wo;
 #pragma unroll
       for (int u = 0; u < 16; ++u) {
         a[u] = 0.f;
         if (av && pp < p1) a[u] = ga[pp];
-        iu[u] = pp < p1 ? i : -4;  // beyond the chunk: no tap is valid
-        ju[u] = j;
+        iu[u] = pp < p1 ? i * S - PAD : -8;  // beyond the chunk: no tap is valid
+        ju[u] = j * S - PAD;
         pp += 2;
         j += 2;
-        if (j >= W) {  // at most one row further per step unless the image is narrower than two pixels
-          j -= W;
+        if (j >= Wo) {  // at most one row further per step unless the plane is narrower than two pixels
+          j -= Wo;
           ++i;
-          if (j >= W) { i += j / W; j %= W; }
+          if (j >= Wo) { i += j / Wo; j %= Wo; }
         }
       }
     }
 #pragma unroll
-    for (int t = 0; t < 9; ++t) {
-      const int du = t / 3 - 1, dv = t % 3 - 1;
-      const float* xt = xb + p + half + du * W + dv;  // read only where the shifted pixel is inside the image
+    for (int t = 0; t < KK; ++t) {
+      const int tu = t / KS, tv = t % KS;
       float b[16];
 #pragma unroll
       for (int u = 0; u < 16; ++u) {
+        const int r = iu[u] + tu, c = ju[u] + tv;
         b[u] = 0.f;
-        if (bv && (unsigned)(iu[u] + du) < (unsigned)H && (unsigned)(ju[u] + dv) < (unsigned)W) b[u] = xt[2 * u];
+        if (bv && (unsigned)r < (unsigned)H && (unsigned)c < (unsigned)W) b[u] = xb[r * W + c];
       }
 #pragma unroll
       for (int u = 0; u < 16; ++u) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc[t], 0, 0, 0);
     }
   }
-  float* out = w.part + (size_t)chunk * Cout * Cin * 9;
+  float* out = w.part + (size_t)chunk * Cout * Cin * KK;
   const int ci = ci_base + row;
 #pragma unroll
-  for (int t = 0; t < 9; ++t) {
+  for (int t = 0; t < KK; ++t) {
     if (t) __syncthreads();  // the previous tap's tiles have been read
 #pragma unroll
     for (int r = 0; r < 16; ++r) sR[wave][r][lane] = acc[t][r];
@@ -186,13 +205,13 @@ __global__ __launch_bounds__(256) void conv3x3_wgrad_mfma_f32_kernel(C3WgArgs w)
         const int r = 4 * wave + rr;
         const int co = co_base + 8 * (r >> 2) + 4 * half + (r & 3);
         if (co < Cout)
-          out[((size_t)co * Cin + ci) * 9 + t] = (sR[0][r][lane] + sR[1][r][lane]) + (sR[2][r][lane] + sR[3][r][lane]);
+          out[((size_t)co * Cin + ci) * KK + t] = (sR[0][r][lane] + sR[1][r][lane]) + (sR[2][r][lane] + sR[3][r][lane]);
       }
     }
   }
 }
 
-// The same for W % 4 == 0 (so H*W % 4 == 0 and every aligned group of four pixels lies in one image
+// The 3x3 stride-1 case for W % 4 == 0 (so H*W % 4 == 0 and every aligned group of four pixels lies in one image
 // row): 16-byte loads.  A lane's fragment is eight pixels b .. b+7 (b = p + 16f + 8*half): g as two
 // float4, and per row shift du the two float4 of x at b + du*W plus the pixel to the left of the
 // first and to the right of the second; the three column shifts are re-combinations of these ten
@@ -296,67 +315,86 @@ __global__ __launch_bounds__(256) void conv3x3_reduce_kernel(const float* __rest
 }
 
 // pixels per wavefront of the weight-gradient kernel: the largest of {256, 128, 64, 32} that still
-// gives about a thousand blocks
-int c3_pxw(int N, int Cin, int Cout, int HW) {
+// gives 768 blocks
+int c3_pxw(int N, int Cin, int Cout, int HWo) {
   const long tiles = (long)cdiv(Cin, 32) * cdiv(Cout, 32);
   const int cand[4] = {256, 128, 64, 32};
   for (int c : cand)
-    if ((long)N * cdiv(HW, 4 * c) * tiles >= 768) return c;
+    if ((long)N * cdiv(HWo, 4 * c) * tiles >= 768) return c;
   return 32;
 }
 
-void launch_product(hipStream_t st, const float* Wp, const float* X, float* Y, const float* bias, int N, int Kdim, int Mdim,
-                    int H, int W) {
+inline int out_dim(int H, int k, int stride) { return (H + 2 * (k / 2) - k) / stride + 1; }
+
+// Y[N][Mdim][PH][PW] = sum over taps of A_tap X(tap)
+template <int KS, bool DGRAD>
+void launch_product(hipStream_t st, const char* name, const float* Wp, const float* X, float* Y, const float* bias, int N,
+                    int Kdim, int Mdim, int PH, int PW, int XH, int XW, int S) {
   C3Args a;
   a.Wp = reinterpret_cast<const float4*>(Wp);
   a.X = X; a.Y = Y; a.bias = bias;
-  a.NQ = (long)N * H * W;
-  a.H = H; a.W = W; a.Kdim = Kdim; a.Mdim = Mdim; a.KG = cdiv(Kdim, 8);
+  a.NQ = (long)N * PH * PW;
+  a.PH = PH; a.PW = PW; a.XH = XH; a.XW = XW; a.S = S;
+  a.Kdim = Kdim; a.Mdim = Mdim; a.KG = cdiv(Kdim, 8);
   a.tap_stride = pw_pack_floats(Mdim, Kdim) / 4;
-  // two tiles of output channels per wavefront while that leaves two blocks per compute unit
+  // two tiles of result channels per wavefront while that leaves two blocks per compute unit
   const int mt = (Mdim > 32 && (long)cdiv(a.NQ, 128) * cdiv(Mdim, 64) >= 512) ? 2 : 1;
   const dim3 grid((unsigned)cdiv(a.NQ, 128), (unsigned)cdiv(Mdim, 32 * mt));
   if (mt == 2) {
-    if (Kdim > 32) KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<2, 2>), grid, dim3(256), 0, st, a);
-    else KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<1, 2>), grid, dim3(256), 0, st, a);
+    if (Kdim > 32) KLAUNCH_NAMED(name, (conv_mfma_f32_kernel<2, 2, KS, DGRAD>), grid, dim3(256), 0, st, a);
+    else KLAUNCH_NAMED(name, (conv_mfma_f32_kernel<1, 2, KS, DGRAD>), grid, dim3(256), 0, st, a);
   } else {
-    if (Kdim > 32) KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<2, 1>), grid, dim3(256), 0, st, a);
-    else KLAUNCH_NAMED("conv3x3_mfma_f32_kernel", (conv3x3_mfma_f32_kernel<1, 1>), grid, dim3(256), 0, st, a);
+    if (Kdim > 32) KLAUNCH_NAMED(name, (conv_mfma_f32_kernel<2, 1, KS, DGRAD>), grid, dim3(256), 0, st, a);
+    else KLAUNCH_NAMED(name, (conv_mfma_f32_kernel<1, 1, KS, DGRAD>), grid, dim3(256), 0, st, a);
   }
+}
+
+const char* product_name(int k, int stride) {
+  return k == 3 && stride == 1 ? "conv3x3_mfma_f32_kernel" : (k == 3 ? "conv3x3s2_mfma_f32_kernel" : "conv1x1s2_mfma_f32_kernel");
 }
 
 }  // namespace
 
-bool conv3x3_mfma_supported(int Cin, int Cout, int k, int stride, int pad, int groups, int H, int W) {
-  return k == 3 && stride == 1 && pad == 1 && groups == 1 && Cin >= 8 && Cout >= 8 && H >= 1 && W >= 1 &&
-         (long)H * W < (1L << 30);
+bool conv_mfma_supported(int Cin, int Cout, int k, int stride, int pad, int groups, int H, int W) {
+  const bool shape = (k == 3 && pad == 1 && (stride == 1 || stride == 2)) || (k == 1 && pad == 0 && stride == 2);
+  return shape && groups == 1 && Cin >= 8 && Cout >= 8 && H >= 1 && W >= 1 && (long)H * W < (1L << 30);
 }
 
-size_t conv3x3_pack_floats(int Mdim, int Kdim) { return 9 * pw_pack_floats(Mdim, Kdim); }
+size_t conv_mfma_pack_floats(int Mdim, int Kdim, int k) { return (size_t)k * k * pw_pack_floats(Mdim, Kdim); }
 
-int conv3x3_wgrad_parts(int N, int Cin, int Cout, int H, int W) { return N * cdiv(H * W, 4 * c3_pxw(N, Cin, Cout, H * W)); }
-
-size_t conv3x3_wgrad_ws(int N, int Cin, int Cout, int H, int W) {
-  return (size_t)conv3x3_wgrad_parts(N, Cin, Cout, H, W) * Cin * Cout * 9;
+int conv_mfma_wgrad_parts(int N, int Cin, int Cout, int H, int W, int k, int stride) {
+  const int HWo = out_dim(H, k, stride) * out_dim(W, k, stride);
+  return N * cdiv(HWo, 4 * c3_pxw(N, Cin, Cout, HWo));
 }
 
-void conv3x3_mfma_fwd_f32(hipStream_t st, const float* Wp, const float* x, float* y, const float* bias, int N, int Cin,
-                          int Cout, int H, int W) {
-  launch_product(st, Wp, x, y, bias, N, Cin, Cout, H, W);
+size_t conv_mfma_wgrad_ws(int N, int Cin, int Cout, int H, int W, int k, int stride) {
+  return (size_t)conv_mfma_wgrad_parts(N, Cin, Cout, H, W, k, stride) * Cin * Cout * k * k;
 }
 
-void conv3x3_mfma_bwd_f32(hipStream_t st, const float* Wp_t, const float* g, float* dx, const float* x, float* part,
-                          float* G, int N, int Cin, int Cout, int H, int W) {
-  if (dx) launch_product(st, Wp_t, g, dx, nullptr, N, Cout, Cin, H, W);
+void conv_mfma_fwd_f32(hipStream_t st, const float* Wp, const float* x, float* y, const float* bias, int N, int Cin,
+                       int Cout, int H, int W, int k, int stride) {
+  const int Ho = out_dim(H, k, stride), Wo = out_dim(W, k, stride);
+  if (k == 3) launch_product<3, false>(st, product_name(k, stride), Wp, x, y, bias, N, Cin, Cout, Ho, Wo, H, W, stride);
+  else launch_product<1, false>(st, product_name(k, stride), Wp, x, y, bias, N, Cin, Cout, Ho, Wo, H, W, stride);
+}
+
+void conv_mfma_bwd_f32(hipStream_t st, const float* Wp_t, const float* g, float* dx, const float* x, float* part,
+                       float* G, int N, int Cin, int Cout, int H, int W, int k, int stride) {
+  const int Ho = out_dim(H, k, stride), Wo = out_dim(W, k, stride);
+  if (dx) {
+    if (k == 3) launch_product<3, true>(st, product_name(k, stride), Wp_t, g, dx, nullptr, N, Cout, Cin, H, W, Ho, Wo, stride);
+    else launch_product<1, true>(st, product_name(k, stride), Wp_t, g, dx, nullptr, N, Cout, Cin, H, W, Ho, Wo, stride);
+  }
   C3WgArgs w;
   w.g = g; w.x = x; w.part = part;
-  w.Cin = Cin; w.Cout = Cout; w.H = H; w.W = W;
-  w.pxw = c3_pxw(N, Cin, Cout, H * W);
-  w.cps = cdiv(H * W, 4 * w.pxw);
+  w.Cin = Cin; w.Cout = Cout; w.H = H; w.W = W; w.Ho = Ho; w.Wo = Wo; w.S = stride;
+  w.pxw = c3_pxw(N, Cin, Cout, Ho * Wo);
+  w.cps = cdiv(Ho * Wo, 4 * w.pxw);
   const dim3 grid((unsigned)(N * w.cps), (unsigned)cdiv(Cin, 32), (unsigned)cdiv(Cout, 32));
-  if (W % 4 == 0) KLAUNCH(conv3x3_wgrad_vec_mfma_f32_kernel, grid, dim3(256), 0, st, w);
-  else KLAUNCH(conv3x3_wgrad_mfma_f32_kernel, grid, dim3(256), 0, st, w);
-  const size_t n = (size_t)Cin * Cout * 9;
+  if (k == 3 && stride == 1 && W % 4 == 0) KLAUNCH(conv3x3_wgrad_vec_mfma_f32_kernel, grid, dim3(256), 0, st, w);
+  else if (k == 3) KLAUNCH_NAMED("conv3x3_wgrad_mfma_f32_kernel", (conv_wgrad_mfma_f32_kernel<3>), grid, dim3(256), 0, st, w);
+  else KLAUNCH_NAMED("conv1x1s2_wgrad_mfma_f32_kernel", (conv_wgrad_mfma_f32_kernel<1>), grid, dim3(256), 0, st, w);
+  const size_t n = (size_t)Cin * Cout * k * k;
   if (G) KLAUNCH(conv3x3_reduce_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, part, G, n, (int)grid.x);
 }
 

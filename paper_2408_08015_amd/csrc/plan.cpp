@@ -51,7 +51,7 @@ ast_status build_plan(Stage& s, std::string& err) {
   std::vector<int> res_stack;      // activation ids of open RES_BEGINs
   std::vector<int> res_op_stack;   // op indices of those RES_BEGINs
   std::vector<char> res_swapped;   // per open RES_BEGIN: its shortcut branch has begun (RES_SWAP seen)
-  const char* c3env = getenv("ASTEROID_CONV3_MFMA");   // 0: dense 3x3 convs on the generic kernels
+  const char* c3env = getenv("ASTEROID_CONV3_MFMA");   // 0: dense 3x3 / strided 1x1 convs on the generic kernels
   const bool conv3_mfma = !c3env || atoi(c3env) != 0;
   std::vector<int> se_stack;       // activation ids of open SE_BEGINs
   bool se_opens = false;           // the previous layer was an SE_BEGIN
@@ -93,7 +93,7 @@ ast_status build_plan(Stage& s, std::string& err) {
           op.kind = OP_CONV_DW;
         } else if (g == Cin && Cin == Cout && pad == k / 2 && !hb && dwk_supported(k, A.h, A.w, st)) {
           op.kind = OP_CONV_DWK;
-        } else if (conv3_mfma && conv3x3_mfma_supported(Cin, Cout, k, st, pad, g, A.h, A.w)) {
+        } else if (conv3_mfma && conv_mfma_supported(Cin, Cout, k, st, pad, g, A.h, A.w)) {
           op.kind = OP_CONV_3X3;
         } else {
           op.kind = OP_CONV_DIRECT;
@@ -320,9 +320,9 @@ ast_status build_plan(Stage& s, std::string& err) {
     if (op.kind == OP_CONV_PW) {
       op.wp_off = wpk; wpk += pw_pack_floats(op.cout, op.cin);
       op.wp2_off = wpk; wpk += pw_pack_floats(op.cin, op.cout);
-    } else if (op.kind == OP_CONV_3X3) {  // nine copies (one per tap) for each direction
-      op.wp_off = wpk; wpk += conv3x3_pack_floats(op.cout, op.cin);
-      op.wp2_off = wpk; wpk += conv3x3_pack_floats(op.cin, op.cout);
+    } else if (op.kind == OP_CONV_3X3) {  // k*k copies (one per tap) for each direction
+      op.wp_off = wpk; wpk += conv_mfma_pack_floats(op.cout, op.cin, op.k);
+      op.wp2_off = wpk; wpk += conv_mfma_pack_floats(op.cin, op.cout, op.k);
     }
   s.wpack_floats = wpk;
 
@@ -487,7 +487,7 @@ ast_status build_plan(Stage& s, std::string& err) {
       case OP_CONV_PW: need = pw_wgrad_f32_ws(I.n, op.cin, op.cout, I.h * I.w) * sizeof(float); break;
       case OP_CONV_DW: need = dw3x3_bwd_f32_ws(I.n, I.c, I.h, I.w, op.stride) * sizeof(float); break;
       case OP_CONV_DWK: need = dwk_bwd_f32_ws(I.n, I.c, op.k) * sizeof(float); break;
-      case OP_CONV_3X3: need = conv3x3_wgrad_ws(I.n, op.cin, op.cout, I.h, I.w) * sizeof(float); break;
+      case OP_CONV_3X3: need = conv_mfma_wgrad_ws(I.n, op.cin, op.cout, I.h, I.w, op.k, op.stride) * sizeof(float); break;
       case OP_CONV_DIRECT:
         need = conv_direct_wgrad_ws(I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride, op.pad, op.groups) * sizeof(float);
         break;

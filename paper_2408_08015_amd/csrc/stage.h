@@ -16,7 +16,8 @@ enum OpKind {
   OP_CONV_PW,      // fp32 1x1 dense conv (matrix cores)
   OP_CONV_DW,      // fp32 depthwise 3x3
   OP_CONV_DWK,     // fp32 depthwise 5x5 (LDS-staged planes)
-  OP_CONV_3X3,     // fp32 dense 3x3, stride 1, pad 1 (matrix cores, nine packed weight copies per direction)
+  OP_CONV_3X3,     // fp32 dense 3x3 (pad 1, stride 1 or 2) or 1x1 stride 2 on the matrix cores (k*k packed weight copies
+                   // per direction)
   OP_CONV_DIRECT,  // fp32 generic conv
   OP_CONV_IGEMM,   // bf16 NHWC implicit-GEMM conv (+bias, +ReLU)
   OP_BN,           // BatchNorm (+ReLU/ReLU6) (+residual add)

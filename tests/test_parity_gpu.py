@@ -280,6 +280,26 @@ def test_dense_conv3x3(A, cin, cout, h, w, B, bias, need_dx):
     check(one(L, (cin, h, w), B=B, needs_input_grad=need_dx), rounds=1)
 
 
+@pytest.mark.parametrize("cin,cout,k,h,w,B,bias", [
+    (16, 24, 3, 12, 12, 3, False),
+    (64, 64, 3, 14, 14, 2, False),
+    (8, 8, 3, 5, 5, 2, True),       # odd size: the last window hangs over the edge
+    (40, 72, 3, 9, 7, 2, False),
+    (8, 8, 3, 1, 1, 3, False),
+    (8, 16, 3, 2, 2, 2, False),
+    (128, 128, 3, 8, 8, 1, False),
+    (16, 32, 1, 12, 12, 3, False),  # the projection of a shortcut
+    (64, 128, 1, 14, 14, 2, False),
+    (8, 8, 1, 7, 5, 2, True),
+    (8, 8, 1, 1, 1, 2, False),
+    (8, 40, 3, 64, 64, 8, False),   # two result tiles per wavefront in the input gradient (8 channels: one tile) and forward
+])
+@pytest.mark.parametrize("need_dx", [True, False])
+def test_dense_conv_stride2(A, cin, cout, k, h, w, B, bias, need_dx):
+    L = [conv(cin, cout, k, 2, k // 2, bias=bias)]
+    check(one(L, (cin, h, w), B=B, needs_input_grad=need_dx), rounds=1)
+
+
 def test_dense_conv3x3_generic_path(A, monkeypatch):
     """With the matrix-core kernels switched off the generic grouped-conv kernels take the layer."""
     monkeypatch.setenv("ASTEROID_CONV3_MFMA", "0")
