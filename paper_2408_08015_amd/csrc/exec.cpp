@@ -98,6 +98,10 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
                     op.bn_out_op >= 0 ? reinterpret_cast<double*>(scratch(c, s.ops[op.bn_out_op])) : nullptr);
       break;
     }
+    case OP_CONV_GK:
+      conv_gatherk_fwd_f32(st, s.wpack + op.wp_off, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out),
+                           op.has_bias ? s.W + op.b_off : nullptr, I.n, op.cin, op.cout, I.h, I.w, op.k, op.stride, op.pad);
+      break;
     case OP_CONV_3X3:
       conv_mfma_fwd_f32(st, s.wpack + op.wp_off, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out),
                         op.has_bias ? s.W + op.b_off : nullptr, I.n, op.cin, op.cout, I.h, I.w, op.k, op.stride);
@@ -260,6 +264,17 @@ void bwd_op(Ctx& c, const Op& op) {
       }
       dw3x3_bwd_f32(st, g, x, s.W + op.w_off, (float*)gin, reinterpret_cast<float*>(scratch(c, op)),
                     s.red_nblocks ? nullptr : s.G + op.w_off, I.n, I.c, I.h, I.w, op.stride, &f);
+      break;
+    }
+    case OP_CONV_GK: {
+      cf g = (cf)grad_ptr(c, op.out);
+      const Act& O = s.acts[op.out];
+      if (gin)  // rarely wanted (the layer is a model's first): the generic kernel
+        conv_direct_dgrad_f32(st, g, s.W + op.w_off, (float*)gin, I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride, op.pad,
+                              op.groups);
+      conv_gatherk_wgrad_f32(st, g, (cf)act_ptr(c, op.in), reinterpret_cast<float*>(scratch(c, op)),
+                             s.red_nblocks ? nullptr : s.G + op.w_off, I.n, op.cin, op.cout, I.h, I.w, op.k, op.stride, op.pad);
+      if (op.has_bias) channel_sum_acc_f32(st, g, s.G + op.b_off, I.n, op.cout, O.h * O.w);
       break;
     }
     case OP_CONV_3X3: {
@@ -491,6 +506,10 @@ static ast_status build_pack_tasks(Stage& s, std::string& err) {
       if (!add(s.W + op.w_off, op.cin, 1, op.wp_off, op.cout, op.cin) ||
           !add(s.W + op.w_off, 1, op.cin, op.wp2_off, op.cin, op.cout))
         return AST_OK;
+    } else if (op.kind == OP_CONV_GK) {
+      if (tasks.size() + 1 >= 65535) return AST_OK;
+      const int kd = op.cin * op.k * op.k;
+      if (!add(s.W + op.w_off, kd, 1, op.wp_off, op.cout, kd)) return AST_OK;
     } else if (op.kind == OP_CONV_3X3) {
       // W[co][ci][tap]: forward copy t is A[co][ci] = W[..][t]; input-gradient copy t is A[ci][co] = W[..][t]
       const int kk = op.k * op.k;
@@ -548,6 +567,11 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
       case OP_CONV_PW: {
         const size_t n = (size_t)op.cin * op.cout;
         add(scf, s.G + op.w_off, n, pw_wgrad_f32_parts(I.n, op.cin, op.cout, I.h * I.w), n, 1, n);
+        break;
+      }
+      case OP_CONV_GK: {
+        const size_t n = (size_t)op.cin * op.cout * op.k * op.k;
+        add(scf, s.G + op.w_off, n, conv_gatherk_wgrad_parts(I.n, op.cin, op.cout, I.h, I.w, op.k, op.stride, op.pad), n, 1, n);
         break;
       }
       case OP_CONV_3X3: {
@@ -613,6 +637,10 @@ ast_status refresh_shadow(Stage& s, std::string& err) {
       if (s.pack_nblocks) continue;
       pw_pack_f32(s.stream, s.W + op.w_off, op.cin, 1, s.wpack + op.wp_off, op.cout, op.cin);
       pw_pack_f32(s.stream, s.W + op.w_off, 1, op.cin, s.wpack + op.wp2_off, op.cin, op.cout);
+    } else if (op.kind == OP_CONV_GK) {
+      if (s.pack_nblocks) continue;
+      const int kd = op.cin * op.k * op.k;
+      pw_pack_f32(s.stream, s.W + op.w_off, kd, 1, s.wpack + op.wp_off, op.cout, kd);
     } else if (op.kind == OP_CONV_3X3) {
       if (s.pack_nblocks) continue;
       const float* W = s.W + op.w_off;

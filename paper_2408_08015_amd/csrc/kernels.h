@@ -88,6 +88,17 @@ void conv_mfma_fwd_f32(hipStream_t st, const float* Wp, const float* x, float* y
                        int Cout, int H, int W, int k, int stride);
 void conv_mfma_bwd_f32(hipStream_t st, const float* Wp_t, const float* g, float* dx, const float* x, float* part,
                        float* G, int N, int Cin, int Cout, int H, int W, int k, int stride);
+// 7x7 dense conv with fewer than 8 input channels (ResNet's stem) on the matrix cores: the contraction index is
+// the flattened (ci, u, v); Wp = pw_pack of W as the [Cout][Cin*49] matrix.  Forward and weight gradient
+// (partials [chunk][Cout][Cin*49] in `part`, G may be NULL: the caller reduces).
+bool conv_gatherk_supported(int Cin, int Cout, int k, int stride, int pad, int groups, int H, int W);
+size_t conv_gatherk_pack_floats(int Cin, int Cout, int k);
+int conv_gatherk_wgrad_parts(int N, int Cin, int Cout, int H, int W, int k, int stride, int pad);
+size_t conv_gatherk_wgrad_ws(int N, int Cin, int Cout, int H, int W, int k, int stride, int pad);
+void conv_gatherk_fwd_f32(hipStream_t st, const float* Wp, const float* x, float* y, const float* bias, int N, int Cin,
+                          int Cout, int H, int W, int k, int stride, int pad);
+void conv_gatherk_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, float* G, int N, int Cin, int Cout,
+                            int H, int W, int k, int stride, int pad);
 // Depthwise K x K (K = 5), pad K/2, stride 1 or 2, no bias: one block per plane, taps from LDS.
 // Backward: dx (may be NULL), and G[C][K][K] += weight gradient through `part`
 // (dwk_bwd_f32_ws floats of scratch: one K*K partial per plane, added over the samples in order).

@@ -298,6 +298,140 @@ __global__ __launch_bounds__(256) void conv3x3_wgrad_vec_mfma_f32_kernel(C3WgArg
   }
 }
 
+// ---- few input channels, large window (ResNet's 7x7 stride-2 stem on 3 channels): the contraction index is
+// the flattened (ci, u, v), K' = Cin*KS*KS, so the weights [Cout][K'] are one pointwise matrix (one packed
+// copy) and the pixel operand of index k is x[ci(k)][pi*S - pad + u(k)][pj*S - pad + v(k)], gathered.
+struct GkArgs {
+  const float4* Wp;
+  const float* X;   // [N][Cin][H][W]
+  float* Y;         // [N][Mdim][Ho][Wo]
+  const float* bias;
+  long NQ;          // N * Ho * Wo
+  int H, W, Ho, Wo, S, PAD, Cin, Kdim, Mdim, KG;
+};
+
+template <int KS>
+__global__ __launch_bounds__(256) void conv_gatherk_mfma_f32_kernel(GkArgs a) {
+  constexpr int KK = KS * KS, NCH = 2;
+  const float4* __restrict__ Wp = a.Wp;
+  const float* __restrict__ X = a.X;
+  float* __restrict__ Y = a.Y;
+  const int H = a.H, W = a.W, HW = a.H * a.W, Wo = a.Wo, HWo = a.Ho * a.Wo, S = a.S, PAD = a.PAD;
+  const int Kdim = a.Kdim, Mdim = a.Mdim, KG = a.KG;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int m_base = blockIdx.y * 32;
+  const long q = (long)blockIdx.x * 128 + wave * 32 + col;
+  const bool qv = q < a.NQ;
+  long n = 0;
+  int p = 0;
+  if (qv) {
+    n = q / HWo;
+    p = (int)(q - n * HWo);
+  }
+  const int pi = p / Wo, pj = p - pi * Wo;
+  const int r0 = pi * S - PAD, c0 = pj * S - PAD;
+  const float* xn = X + (size_t)n * a.Cin * HW;
+  const float4* wl = Wp + (size_t)blockIdx.y * KG * 64 + lane;
+  floatx16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int g0 = 0; g0 < KG; g0 += NCH * 4) {
+    float4 av[NCH * 4];
+    float b[NCH * 16];
+#pragma unroll
+    for (int g = 0; g < NCH * 4; ++g) {
+      av[g] = g0 + g < KG ? wl[(size_t)(g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int k = (g0 + g) * 8 + 2 * e + half;
+        const int ci = k / KK, t = k - ci * KK, u = t / KS, v = t - u * KS;
+        const int xr = r0 + u, xc = c0 + v;
+        float val = 0.f;
+        if (qv && k < Kdim && (unsigned)xr < (unsigned)H && (unsigned)xc < (unsigned)W) val = xn[(size_t)ci * HW + xr * W + xc];
+        b[4 * g + e] = val;
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < NCH * 4; ++g) {
+      if (g0 + g >= KG) break;  // uniform
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].x, b[4 * g + 0], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].y, b[4 * g + 1], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].z, b[4 * g + 2], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g].w, b[4 * g + 3], acc, 0, 0, 0);
+    }
+  }
+  if (qv) {
+    float* yq = Y + (size_t)n * Mdim * HWo + p;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (m < Mdim) yq[(size_t)m * HWo] = acc[r] + (a.bias ? a.bias[m] : 0.f);
+    }
+  }
+}
+
+// weight gradient of the same: rows of the B operand are the flattened (ci, u, v); block (chunk of output
+// pixels, k tile, co tile); partials [chunk][cout][K']
+template <int KS>
+__global__ __launch_bounds__(256) void conv_gatherk_wgrad_mfma_f32_kernel(C3WgArgs w, int PAD) {
+  constexpr int KK = KS * KS;
+  __shared__ float sR[4][16][64];
+  const float* __restrict__ g = w.g;
+  const float* __restrict__ x = w.x;
+  const int Cin = w.Cin, Cout = w.Cout, H = w.H, W = w.W, Wo = w.Wo, HWo = w.Ho * w.Wo, S = w.S;
+  const int Kdim = Cin * KK;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = lane & 31, half = lane >> 5;
+  const int chunk = blockIdx.x;
+  const int n = chunk / w.cps;
+  const int p0 = ((chunk - n * w.cps) * 4 + wave) * w.pxw;
+  const int p1 = min(p0 + w.pxw, HWo);
+  const int k_base = blockIdx.y * 32, co_base = blockIdx.z * 32;
+  const int k = k_base + row;
+  const bool av = co_base + row < Cout, bv = k < Kdim;
+  const int ci = bv ? k / KK : 0, t = k - (k / KK) * KK, tu = t / KS, tv = t - tu * KS;
+  const float* ga = g + ((size_t)n * Cout + (av ? co_base + row : 0)) * HWo;
+  const float* xb = x + ((size_t)n * Cin + ci) * H * W;
+  floatx16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int p = p0; p < p1; p += 32) {
+    float a[16], b[16];
+    int pp = p + half;
+    int i = pp / Wo, j = pp - i * Wo;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      a[u] = 0.f;
+      b[u] = 0.f;
+      const int r = i * S - PAD + tu, c = j * S - PAD + tv;
+      if (av && pp < p1) a[u] = ga[pp];
+      if (bv && pp < p1 && (unsigned)r < (unsigned)H && (unsigned)c < (unsigned)W) b[u] = xb[r * W + c];
+      pp += 2;
+      j += 2;
+      if (j >= Wo) {
+        j -= Wo;
+        ++i;
+        if (j >= Wo) { i += j / Wo; j %= Wo; }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc, 0, 0, 0);
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sR[wave][r][lane] = acc[r];
+  __syncthreads();
+  float* out = w.part + (size_t)chunk * Cout * Kdim;
+  if (bv) {
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int r = 4 * wave + rr;
+      const int co = co_base + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (co < Cout) out[(size_t)co * Kdim + k] = (sR[0][r][lane] + sR[1][r][lane]) + (sR[2][r][lane] + sR[3][r][lane]);
+    }
+  }
+}
+
 // G[i] += sum over the chunks of part[chunk][i]
 __global__ __launch_bounds__(256) void conv3x3_reduce_kernel(const float* __restrict__ part, float* __restrict__ G, size_t n,
                                                              int parts) {
@@ -354,6 +488,47 @@ const char* product_name(int k, int stride) {
 }
 
 }  // namespace
+
+// ---- few input channels, 7x7 window
+bool conv_gatherk_supported(int Cin, int Cout, int k, int stride, int pad, int groups, int H, int W) {
+  return k == 7 && groups == 1 && Cin >= 1 && Cin < 8 && Cout >= 8 && stride >= 1 && stride <= 4 && pad >= 0 && pad <= 3 &&
+         H + 2 * pad >= k && W + 2 * pad >= k && (long)H * W < (1L << 30);
+}
+size_t conv_gatherk_pack_floats(int Cin, int Cout, int k) { return pw_pack_floats(Cout, Cin * k * k); }
+static int gk_out(int H, int k, int stride, int pad) { return (H + 2 * pad - k) / stride + 1; }
+int conv_gatherk_wgrad_parts(int N, int Cin, int Cout, int H, int W, int k, int stride, int pad) {
+  const int HWo = gk_out(H, k, stride, pad) * gk_out(W, k, stride, pad);
+  return N * cdiv(HWo, 4 * c3_pxw(N, Cin * k * k, Cout, HWo));
+}
+size_t conv_gatherk_wgrad_ws(int N, int Cin, int Cout, int H, int W, int k, int stride, int pad) {
+  return (size_t)conv_gatherk_wgrad_parts(N, Cin, Cout, H, W, k, stride, pad) * Cin * Cout * k * k;
+}
+void conv_gatherk_fwd_f32(hipStream_t st, const float* Wp, const float* x, float* y, const float* bias, int N, int Cin,
+                          int Cout, int H, int W, int k, int stride, int pad) {
+  GkArgs a;
+  a.Wp = reinterpret_cast<const float4*>(Wp);
+  a.X = x; a.Y = y; a.bias = bias;
+  a.H = H; a.W = W; a.Ho = gk_out(H, k, stride, pad); a.Wo = gk_out(W, k, stride, pad);
+  a.NQ = (long)N * a.Ho * a.Wo;
+  a.S = stride; a.PAD = pad; a.Cin = Cin; a.Kdim = Cin * k * k; a.Mdim = Cout; a.KG = cdiv(a.Kdim, 8);
+  const dim3 grid((unsigned)cdiv(a.NQ, 128), (unsigned)cdiv(Cout, 32));
+  KLAUNCH_NAMED("conv7x7_gatherk_mfma_f32_kernel", (conv_gatherk_mfma_f32_kernel<7>), grid, dim3(256), 0, st, a);
+}
+// weight gradient only (a layer with so few input channels is a model's first: its input gradient, if asked
+// for, comes from the generic kernel)
+void conv_gatherk_wgrad_f32(hipStream_t st, const float* g, const float* x, float* part, float* G, int N, int Cin, int Cout,
+                            int H, int W, int k, int stride, int pad) {
+  C3WgArgs w;
+  w.g = g; w.x = x; w.part = part;
+  w.Cin = Cin; w.Cout = Cout; w.H = H; w.W = W; w.Ho = gk_out(H, k, stride, pad); w.Wo = gk_out(W, k, stride, pad); w.S = stride;
+  const int Kdim = Cin * k * k;
+  w.pxw = c3_pxw(N, Kdim, Cout, w.Ho * w.Wo);
+  w.cps = cdiv(w.Ho * w.Wo, 4 * w.pxw);
+  const dim3 grid((unsigned)(N * w.cps), (unsigned)cdiv(Kdim, 32), (unsigned)cdiv(Cout, 32));
+  KLAUNCH_NAMED("conv7x7_gatherk_wgrad_mfma_f32_kernel", (conv_gatherk_wgrad_mfma_f32_kernel<7>), grid, dim3(256), 0, st, w, pad);
+  const size_t n = (size_t)Cout * Kdim;
+  if (G) KLAUNCH(conv3x3_reduce_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, part, G, n, (int)grid.x);
+}
 
 bool conv_mfma_supported(int Cin, int Cout, int k, int stride, int pad, int groups, int H, int W) {
   const bool shape = (k == 3 && pad == 1 && (stride == 1 || stride == 2)) || (k == 1 && pad == 0 && stride == 2);

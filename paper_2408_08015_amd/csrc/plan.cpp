@@ -95,6 +95,8 @@ ast_status build_plan(Stage& s, std::string& err) {
           op.kind = OP_CONV_DWK;
         } else if (conv3_mfma && conv_mfma_supported(Cin, Cout, k, st, pad, g, A.h, A.w)) {
           op.kind = OP_CONV_3X3;
+        } else if (conv3_mfma && conv_gatherk_supported(Cin, Cout, k, st, pad, g, A.h, A.w)) {
+          op.kind = OP_CONV_GK;
         } else {
           op.kind = OP_CONV_DIRECT;
         }
@@ -320,6 +322,8 @@ ast_status build_plan(Stage& s, std::string& err) {
     if (op.kind == OP_CONV_PW) {
       op.wp_off = wpk; wpk += pw_pack_floats(op.cout, op.cin);
       op.wp2_off = wpk; wpk += pw_pack_floats(op.cin, op.cout);
+    } else if (op.kind == OP_CONV_GK) {   // the weights as one [cout][cin*k*k] matrix
+      op.wp_off = wpk; wpk += conv_gatherk_pack_floats(op.cin, op.cout, op.k);
     } else if (op.kind == OP_CONV_3X3) {  // k*k copies (one per tap) for each direction
       op.wp_off = wpk; wpk += conv_mfma_pack_floats(op.cout, op.cin, op.k);
       op.wp2_off = wpk; wpk += conv_mfma_pack_floats(op.cin, op.cout, op.k);
@@ -487,6 +491,10 @@ ast_status build_plan(Stage& s, std::string& err) {
       case OP_CONV_PW: need = pw_wgrad_f32_ws(I.n, op.cin, op.cout, I.h * I.w) * sizeof(float); break;
       case OP_CONV_DW: need = dw3x3_bwd_f32_ws(I.n, I.c, I.h, I.w, op.stride) * sizeof(float); break;
       case OP_CONV_DWK: need = dwk_bwd_f32_ws(I.n, I.c, op.k) * sizeof(float); break;
+      case OP_CONV_GK:
+        need = std::max(conv_gatherk_wgrad_ws(I.n, op.cin, op.cout, I.h, I.w, op.k, op.stride, op.pad),
+                        conv_direct_wgrad_ws(I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride, op.pad, op.groups)) * sizeof(float);
+        break;
       case OP_CONV_3X3: need = conv_mfma_wgrad_ws(I.n, op.cin, op.cout, I.h, I.w, op.k, op.stride) * sizeof(float); break;
       case OP_CONV_DIRECT:
         need = conv_direct_wgrad_ws(I.n, op.cin, I.h, I.w, op.cout, op.k, op.stride, op.pad, op.groups) * sizeof(float);

@@ -18,6 +18,7 @@ enum OpKind {
   OP_CONV_DWK,     // fp32 depthwise 5x5 (LDS-staged planes)
   OP_CONV_3X3,     // fp32 dense 3x3 (pad 1, stride 1 or 2) or 1x1 stride 2 on the matrix cores (k*k packed weight copies
                    // per direction)
+  OP_CONV_GK,      // fp32 7x7 conv with few input channels (matrix cores, contraction over (ci, u, v))
   OP_CONV_DIRECT,  // fp32 generic conv
   OP_CONV_IGEMM,   // bf16 NHWC implicit-GEMM conv (+bias, +ReLU)
   OP_BN,           // BatchNorm (+ReLU/ReLU6) (+residual add)

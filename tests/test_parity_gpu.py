@@ -300,6 +300,21 @@ def test_dense_conv_stride2(A, cin, cout, k, h, w, B, bias, need_dx):
     check(one(L, (cin, h, w), B=B, needs_input_grad=need_dx), rounds=1)
 
 
+@pytest.mark.parametrize("cin,cout,stride,pad,h,w,B,bias", [
+    (3, 64, 2, 3, 32, 32, 2, False),    # ResNet's stem
+    (3, 16, 2, 3, 17, 15, 3, True),
+    (1, 8, 1, 3, 9, 9, 2, False),
+    (4, 24, 1, 3, 10, 12, 2, False),
+    (7, 40, 3, 2, 20, 20, 2, False),
+    (3, 8, 2, 0, 7, 7, 4, False),       # one output pixel
+    (3, 64, 2, 3, 112, 112, 1, False),  # several pixel chunks
+])
+@pytest.mark.parametrize("need_dx", [True, False])
+def test_conv7x7_few_input_channels(A, cin, cout, stride, pad, h, w, B, bias, need_dx):
+    L = [conv(cin, cout, 7, stride, pad, bias=bias)]
+    check(one(L, (cin, h, w), B=B, needs_input_grad=need_dx), rounds=1)
+
+
 def test_dense_conv3x3_generic_path(A, monkeypatch):
     """With the matrix-core kernels switched off the generic grouped-conv kernels take the layer."""
     monkeypatch.setenv("ASTEROID_CONV3_MFMA", "0")
