@@ -17,22 +17,45 @@ namespace {
 
 inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
-// LDS: p[C] then h[Cr]
-__global__ __launch_bounds__(256) void se_gate_fwd_kernel(const float* __restrict__ p, const float* __restrict__ W1,
-                                                          const float* __restrict__ b1, const float* __restrict__ W2,
-                                                          const float* __restrict__ b2, float* __restrict__ hpre,
-                                                          float* __restrict__ h, float* __restrict__ z,
-                                                          float* __restrict__ gate, int C, int Cr) {
+// dot product of a row with the LDS vector over the lanes of a wavefront, four loads in flight
+__device__ __forceinline__ float wave_dot(const float* __restrict__ row, const float* __restrict__ sv, int C, int lane) {
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  int c = lane;
+  for (; c + 192 < C; c += 256) {
+    const float w0 = row[c], w1 = row[c + 64], w2 = row[c + 128], w3 = row[c + 192];
+    a0 += w0 * sv[c]; a1 += w1 * sv[c + 64]; a2 += w2 * sv[c + 128]; a3 += w3 * sv[c + 192];
+  }
+  for (; c < C; c += 64) a0 += row[c] * sv[c];
+  return wave_sum((a0 + a1) + (a2 + a3));
+}
+
+// sum_r w[r * stride] * sv[r], r < n, eight loads in flight
+__device__ __forceinline__ float strided_dot(const float* __restrict__ w, size_t stride, const float* __restrict__ sv, int n) {
+  float a = 0.f;
+  for (int r0 = 0; r0 < n; r0 += 8) {
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = r0 + k < n ? w[(size_t)(r0 + k) * stride] : 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) a += v[k] * (r0 + k < n ? sv[r0 + k] : 0.f);
+  }
+  return a;
+}
+
+// Block = one sample, 1024 threads (16 wavefronts: the hidden units are dealt over them).  LDS: p[C] then h[Cr]
+__global__ __launch_bounds__(1024) void se_gate_fwd_kernel(const float* __restrict__ p, const float* __restrict__ W1,
+                                                           const float* __restrict__ b1, const float* __restrict__ W2,
+                                                           const float* __restrict__ b2, float* __restrict__ hpre,
+                                                           float* __restrict__ h, float* __restrict__ z,
+                                                           float* __restrict__ gate, int C, int Cr) {
   extern __shared__ float sh[];
   float* sp = sh;
   float* shh = sh + C;
   const int n = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  for (int c = threadIdx.x; c < C; c += 256) sp[c] = p[(size_t)n * C + c];
+  for (int c = threadIdx.x; c < C; c += 1024) sp[c] = p[(size_t)n * C + c];
   __syncthreads();
-  for (int r = wv; r < Cr; r += 4) {  // a wavefront per hidden unit
-    float a = 0.f;
-    for (int c = lane; c < C; c += 64) a += W1[(size_t)r * C + c] * sp[c];
-    a = wave_sum(a) + (b1 ? b1[r] : 0.f);
+  for (int r = wv; r < Cr; r += 16) {  // a wavefront per hidden unit
+    const float a = wave_dot(W1 + (size_t)r * C, sp, C, lane) + (b1 ? b1[r] : 0.f);
     if (lane == 0) {
       hpre[(size_t)n * Cr + r] = a;
       const float hv = a * sigmoid_f(a);
@@ -41,47 +64,52 @@ __global__ __launch_bounds__(256) void se_gate_fwd_kernel(const float* __restric
     }
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < C; c += 256) {
+  for (int c = threadIdx.x; c < C; c += 1024) {
     float a = b2 ? b2[c] : 0.f;
-    for (int r = 0; r < Cr; ++r) a += W2[(size_t)c * Cr + r] * shh[r];
+    const float* wr = W2 + (size_t)c * Cr;  // (a plain loop: eight explicit loads in flight measured slower here)
+    for (int r = 0; r < Cr; ++r) a += wr[r] * shh[r];
     z[(size_t)n * C + c] = a;
     gate[(size_t)n * C + c] = sigmoid_f(a);
   }
 }
 
-// LDS: dz[C] then dhp[Cr]
-__global__ __launch_bounds__(256) void se_gate_bwd_kernel(const float* __restrict__ dgate, const float* __restrict__ z,
-                                                          const float* __restrict__ hpre, const float* __restrict__ W1,
-                                                          const float* __restrict__ W2, float* __restrict__ dz,
-                                                          float* __restrict__ dhp, float* __restrict__ dp, int C, int Cr) {
+// LDS: dz[C], dhp[Cr], then per-wavefront partial sums [16][Cr]
+__global__ __launch_bounds__(1024) void se_gate_bwd_kernel(const float* __restrict__ dgate, const float* __restrict__ z,
+                                                           const float* __restrict__ hpre, const float* __restrict__ W1,
+                                                           const float* __restrict__ W2, float* __restrict__ dz,
+                                                           float* __restrict__ dhp, float* __restrict__ dp, int C, int Cr) {
   extern __shared__ float sh[];
   float* sdz = sh;
   float* sdh = sh + C;
+  float* spart = sdh + Cr;  // [16][Cr]
   const int n = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  for (int c = threadIdx.x; c < C; c += 256) {
+  for (int c = threadIdx.x; c < C; c += 1024) {
     const float s = sigmoid_f(z[(size_t)n * C + c]);
     const float v = dgate[(size_t)n * C + c] * s * (1.f - s);
     sdz[c] = v;
     dz[(size_t)n * C + c] = v;
   }
   __syncthreads();
-  for (int r = wv; r < Cr; r += 4) {
+  // dh[r] = sum_c W2[c][r] dz[c]: a lane owns channel c and walks its row of W2 (consecutive r: the row stays in
+  // cache), the wavefront adds the 64 products of each r; wavefronts take the channel groups in turn and their
+  // sums meet in LDS in a fixed order
+  for (int r = 0; r < Cr; ++r) {
     float a = 0.f;
-    for (int c = lane; c < C; c += 64) a += W2[(size_t)c * Cr + r] * sdz[c];
+    for (int c = wv * 64 + lane; c < C; c += 1024) a += W2[(size_t)c * Cr + r] * sdz[c];
     a = wave_sum(a);
-    if (lane == 0) {
-      const float v = a * act_slope_sw<true>(hpre[(size_t)n * Cr + r], ACT_SWISH);
-      sdh[r] = v;
-      dhp[(size_t)n * Cr + r] = v;
-    }
+    if (lane == 0) spart[wv * Cr + r] = a;
+  }
+  __syncthreads();
+  for (int r = threadIdx.x; r < Cr; r += 1024) {
+    float a = 0.f;
+    for (int k = 0; k < 16; ++k) a += spart[k * Cr + r];
+    const float v = a * act_slope_sw<true>(hpre[(size_t)n * Cr + r], ACT_SWISH);
+    sdh[r] = v;
+    dhp[(size_t)n * Cr + r] = v;
   }
   __syncthreads();
   if (dp)
-    for (int c = threadIdx.x; c < C; c += 256) {
-      float a = 0.f;
-      for (int r = 0; r < Cr; ++r) a += W1[(size_t)r * C + c] * sdh[r];
-      dp[(size_t)n * C + c] = a;
-    }
+    for (int c = threadIdx.x; c < C; c += 1024) dp[(size_t)n * C + c] = strided_dot(W1 + c, (size_t)C, sdh, Cr);
 }
 
 // sum over the samples of a[n*sa + ia] * b[n*sb + ib] (b == NULL: of a alone), eight loads in flight
@@ -131,19 +159,19 @@ __global__ void se_gate_wgrad_kernel(const float* __restrict__ dz, const float* 
 
 }  // namespace
 
-bool se_gate_supported(int C, int Cr) { return C >= 1 && Cr >= 1 && (size_t)(C + Cr) * sizeof(float) <= 48 * 1024; }
+bool se_gate_supported(int C, int Cr) { return C >= 1 && Cr >= 1 && (size_t)(C + 17 * Cr) * sizeof(float) <= 48 * 1024; }
 
 void se_gate_fwd_f32(hipStream_t st, const float* p, const float* W1, const float* b1, const float* W2, const float* b2,
                      float* hpre, float* h, float* z, float* gate, int N, int C, int Cr) {
-  KLAUNCH(se_gate_fwd_kernel, dim3(N), dim3(256), (size_t)(C + Cr) * sizeof(float), st, p, W1, b1, W2, b2, hpre, h, z, gate,
+  KLAUNCH(se_gate_fwd_kernel, dim3(N), dim3(1024), (size_t)(C + Cr) * sizeof(float), st, p, W1, b1, W2, b2, hpre, h, z, gate,
           C, Cr);
 }
 
 void se_gate_bwd_f32(hipStream_t st, const float* dgate, const float* z, const float* hpre, const float* p, const float* h,
                      const float* W1, const float* W2, float* dz, float* dhp, float* dp, float* GW1, float* Gb1, float* GW2,
                      float* Gb2, int N, int C, int Cr) {
-  KLAUNCH(se_gate_bwd_kernel, dim3(N), dim3(256), (size_t)(C + Cr) * sizeof(float), st, dgate, z, hpre, W1, W2, dz, dhp, dp, C,
-          Cr);
+  KLAUNCH(se_gate_bwd_kernel, dim3(N), dim3(1024), (size_t)(C + 17 * Cr) * sizeof(float), st, dgate, z, hpre, W1, W2, dz, dhp,
+          dp, C, Cr);
   KLAUNCH(se_gate_wgrad_kernel, dim3(cdiv(2L * C * Cr + C + Cr, 256)), dim3(256), 0, st, dz, dhp, p, h, GW1, Gb1, GW2, Gb2, N,
           C, Cr);
 }
