@@ -53,6 +53,15 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
 }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
+// Workgroups are dealt to the 8 XCDs (each with an L2 of its own) round-robin by their flat index.
+// Renumbering: XCD x gets the contiguous range of ids that starts at x*(n/8) + min(x, n%8), so
+// blocks with neighbouring renumbered ids run on the same XCD at about the same time.  A bijection
+// on [0, n).
+__device__ __forceinline__ unsigned xcd_grouped(unsigned id, unsigned n) {
+  const unsigned q = n >> 3, r = n & 7, x = id & 7;
+  return x * q + min(x, r) + (id >> 3);
+}
+
 __device__ __forceinline__ float relu6f(float v) { return fminf(fmaxf(v, 0.f), 6.f); }
 
 // activation codes used by fused kernels

@@ -35,13 +35,29 @@ struct PwArgs {  // one pointwise-conv product Y = A X (+ bias) (+ add)
   double* stats;  // or NULL: per block (sum, sum of squares) of the output per channel, stats[m][gridDim.x][2]
   long NQ;
   int HW, Kdim, Mdim, KG;
+  int tile_order;  // 1: the channel tiles of one pixel block run side by side on one XCD (they share X)
 };
 struct WgArgs {  // one pointwise-conv weight-gradient launch (partials only)
   const float* g;
   const float* x;
   float* part;
   int Cin, Cout, HW, cps, pxw;
+  int tile_order;  // 1: the (ci, co) tiles of one pixel chunk run side by side on one XCD
 };
+
+// Block coordinates of a product grid of gx pixel blocks x gy channel tiles from the flat block id:
+// pixel blocks fastest, or (tile_order) channel tiles fastest within XCD-grouped ids, so that the
+// gy blocks that read the same pixels of X hit one L2.
+__device__ __forceinline__ void pw_block_xy(unsigned id, unsigned gx, unsigned gy, int tile_order, int& bx, int& by) {
+  if (tile_order) {
+    id = xcd_grouped(id, gx * gy);
+    by = (int)(id % gy);
+    bx = (int)(id / gy);
+  } else {
+    bx = (int)(id % gx);
+    by = (int)(id / gx);
+  }
+}
 
 // The A operand comes from a packed copy of the weights (pw_pack_f32): for m-tile t and
 // k-group g (8 consecutive k), lane l = (m%32, h) finds the four values A[m][8g + 2e + h],
@@ -157,7 +173,9 @@ __device__ __forceinline__ void pw_pk_body(const PwArgs& a, int bx, int by, floa
 template <int NCH>
 __global__ __launch_bounds__(256) void pw_conv_f32_pk_kernel(PwArgs a) {
   __shared__ float sR[4][16][64];
-  pw_pk_body<NCH>(a, blockIdx.x, blockIdx.y, sR, gridDim.x);
+  int bx, by;
+  pw_block_xy(blockIdx.y * gridDim.x + blockIdx.x, gridDim.x, gridDim.y, a.tile_order, bx, by);
+  pw_pk_body<NCH>(a, bx, by, sR, gridDim.x);
 }
 
 // Few pixels, long K (the 14x14 / 7x7 layers of a whole network): the four wavefronts of a
@@ -334,7 +352,9 @@ __device__ __forceinline__ void pw_pk4_body(const PwArgs& a, int bx, int by, flo
 }
 __global__ __launch_bounds__(256) void pw_conv_f32_pk4_kernel(PwArgs a) {
   __shared__ float sR[4][16][64];
-  pw_pk4_body(a, blockIdx.x, blockIdx.y, sR, gridDim.x);
+  int bx, by;
+  pw_block_xy(blockIdx.y * gridDim.x + blockIdx.x, gridDim.x, gridDim.y, a.tile_order, bx, by);
+  pw_pk4_body(a, bx, by, sR, gridDim.x);
 }
 
 // Packed operand copy: Wp[((t*KG + g)*64 + l)*4 + e] = A[32t + l%32][8g + 2e + l/32], zero
@@ -398,6 +418,10 @@ static PwPick pw_pick(long NQ, int HW, int Kdim, int Mdim) {
   else { p.var = 0; p.grid = dim3((unsigned)cdiv(NQ, 128), mt); }
   return p;
 }
+static int pw_tile_order() {
+  static const int v = [] { const char* e = getenv("ASTEROID_PW_TILE_ORDER"); return e ? atoi(e) : 3; }();
+  return v;
+}
 static PwArgs pw_args(const float* Wp, const float* X, float* Y, const float* bias, const float* add, int N, int Kdim,
                       int Mdim, int HW) {
   PwArgs a;
@@ -406,6 +430,7 @@ static PwArgs pw_args(const float* Wp, const float* X, float* Y, const float* bi
   a.stats = nullptr;
   a.NQ = (long)N * HW;
   a.HW = HW; a.Kdim = Kdim; a.Mdim = Mdim; a.KG = cdiv(Kdim, 8);
+  a.tile_order = (pw_tile_order() & 1) && Mdim > 32;
   return a;
 }
 
@@ -529,7 +554,10 @@ __device__ __forceinline__ void pw_wgrad_body(const WgArgs& w, int bx, int by, i
 template <bool VEC>
 __global__ __launch_bounds__(256) void pw_wgrad_f32_kernel(WgArgs w) {
   __shared__ float sR[4][16][64];
-  pw_wgrad_body<VEC>(w, blockIdx.x, blockIdx.y, blockIdx.z, sR);
+  int bx, t;
+  pw_block_xy((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x, gridDim.x, gridDim.y * gridDim.z,
+              w.tile_order, bx, t);
+  pw_wgrad_body<VEC>(w, bx, t % (int)gridDim.y, t / (int)gridDim.y, sR);
 }
 
 // Input gradient and weight-gradient partials of one pointwise conv in ONE launch: the two
@@ -544,15 +572,16 @@ __global__ __launch_bounds__(256) void pw_bwd_dual_kernel(PwArgs a, WgArgs w, un
                                                           unsigned gWx, unsigned gWy) {
   __shared__ float sR[4][16][64];
   if (blockIdx.x < nA) {  // uniform per block
-    const int bx = (int)(blockIdx.x % gAx), by = (int)(blockIdx.x / gAx);
+    int bx, by;
+    pw_block_xy(blockIdx.x, gAx, nA / gAx, a.tile_order, bx, by);
     if (VAR == 0) pw_pk_body<1>(a, bx, by, sR, 0);
     else if (VAR == 1) pw_pk_body<2>(a, bx, by, sR, 0);
     else if (VAR == 2) pw_pkks_body<4>(a, bx, by, sR);
     else pw_pk4_body(a, bx, by, sR, 0);
   } else {
-    const unsigned b = blockIdx.x - nA;
-    const unsigned bx = b % gWx, r = b / gWx;
-    pw_wgrad_body<VEC>(w, (int)bx, (int)(r % gWy), (int)(r / gWy), sR);
+    int bx, t;  // the weight-gradient ids start at nA: ids that agree mod 8 still share an XCD
+    pw_block_xy(blockIdx.x - nA, gWx, (gridDim.x - nA) / gWx, w.tile_order, bx, t);
+    pw_wgrad_body<VEC>(w, bx, t % (int)gWy, t / (int)gWy, sR);
   }
 }
 
@@ -597,6 +626,7 @@ static WgArgs wg_args(const float* g, const float* x, float* part, int N, int Ci
   w.Cin = Cin; w.Cout = Cout; w.HW = HW;
   w.pxw = wg_pxw(N, Cin, Cout, HW);
   w.cps = cdiv(HW, 4 * w.pxw);
+  w.tile_order = (pw_tile_order() & 2) && (Cin > 32 || Cout > 32);
   grid = dim3(N * w.cps, cdiv(Cin, 32), cdiv(Cout, 32));
   return w;
 }

@@ -23,6 +23,16 @@ namespace {
 
 inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
+// Block coordinates from the flat block id with the tiles of one pixel block (or pixel chunk)
+// fastest inside XCD-grouped ids: the blocks that read the same pixels run side by side on one XCD
+// and share its L2.  gx = pixel blocks, gt = tiles.
+__device__ __forceinline__ void tile_fastest(unsigned gx, unsigned gt, int& bx, int& t) {
+  const unsigned flat = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+  const unsigned id = xcd_grouped(flat, gx * gt);
+  t = (int)(id % gt);
+  bx = (int)(id / gt);
+}
+
 struct C3Args {
   const float4* Wp;   // KS*KS packed copies, tap_stride float4 words apart
   const float* X;     // operand tensor [N][Kdim][XH][XW]
@@ -46,8 +56,10 @@ __global__ __launch_bounds__(256) void conv_mfma_f32_kernel(C3Args a) {
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int tile0 = blockIdx.y * MT;  // first 32-row tile of this block
-  const long q = (long)blockIdx.x * 128 + wave * 32 + col;
+  int bx, by;
+  tile_fastest(gridDim.x, gridDim.y, bx, by);
+  const int tile0 = by * MT;  // first 32-row tile of this block
+  const long q = (long)bx * 128 + wave * 32 + col;
   const bool qv = q < a.NQ;
   long n = 0;
   int p = 0;
@@ -143,11 +155,12 @@ __global__ __launch_bounds__(256) void conv_wgrad_mfma_f32_kernel(C3WgArgs w) {
   const int Cin = w.Cin, Cout = w.Cout, H = w.H, W = w.W, Wo = w.Wo, HWo = w.Ho * w.Wo, S = w.S;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 31, half = lane >> 5;
-  const int chunk = blockIdx.x;
+  int chunk, tile;
+  tile_fastest(gridDim.x, gridDim.y * gridDim.z, chunk, tile);
   const int n = chunk / w.cps;
   const int p0 = ((chunk - n * w.cps) * 4 + wave) * w.pxw;
   const int p1 = min(p0 + w.pxw, HWo);
-  const int ci_base = blockIdx.y * 32, co_base = blockIdx.z * 32;
+  const int ci_base = (tile % (int)gridDim.y) * 32, co_base = (tile / (int)gridDim.y) * 32;
   const bool av = co_base + row < Cout, bv = ci_base + row < Cin;
   const float* ga = g + ((size_t)n * Cout + (av ? co_base + row : 0)) * HWo;
   const float* xb = x + ((size_t)n * Cin + (bv ? ci_base + row : 0)) * H * W;
@@ -224,11 +237,12 @@ __global__ __launch_bounds__(256) void conv3x3_wgrad_vec_mfma_f32_kernel(C3WgArg
   const int Cin = w.Cin, Cout = w.Cout, H = w.H, W = w.W, HW = w.H * w.W;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 31, half = lane >> 5;
-  const int chunk = blockIdx.x;
+  int chunk, tile;
+  tile_fastest(gridDim.x, gridDim.y * gridDim.z, chunk, tile);
   const int n = chunk / w.cps;
   const int p0 = ((chunk - n * w.cps) * 4 + wave) * w.pxw;
   const int p1 = min(p0 + w.pxw, HW);
-  const int ci_base = blockIdx.y * 32, co_base = blockIdx.z * 32;
+  const int ci_base = (tile % (int)gridDim.y) * 32, co_base = (tile / (int)gridDim.y) * 32;
   const bool av = co_base + row < Cout, bv = ci_base + row < Cin;
   const float* ga = g + ((size_t)n * Cout + (av ? co_base + row : 0)) * HW;
   const float* xb = x + ((size_t)n * Cin + (bv ? ci_base + row : 0)) * HW;
@@ -320,8 +334,10 @@ __global__ __launch_bounds__(256) void conv_gatherk_mfma_f32_kernel(GkArgs a) {
   const int Kdim = a.Kdim, Mdim = a.Mdim, KG = a.KG;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int m_base = blockIdx.y * 32;
-  const long q = (long)blockIdx.x * 128 + wave * 32 + col;
+  int bx, by;
+  tile_fastest(gridDim.x, gridDim.y, bx, by);
+  const int m_base = by * 32;
+  const long q = (long)bx * 128 + wave * 32 + col;
   const bool qv = q < a.NQ;
   long n = 0;
   int p = 0;
@@ -332,7 +348,7 @@ __global__ __launch_bounds__(256) void conv_gatherk_mfma_f32_kernel(GkArgs a) {
   const int pi = p / Wo, pj = p - pi * Wo;
   const int r0 = pi * S - PAD, c0 = pj * S - PAD;
   const float* xn = X + (size_t)n * a.Cin * HW;
-  const float4* wl = Wp + (size_t)blockIdx.y * KG * 64 + lane;
+  const float4* wl = Wp + (size_t)by * KG * 64 + lane;
   floatx16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -383,11 +399,12 @@ __global__ __launch_bounds__(256) void conv_gatherk_wgrad_mfma_f32_kernel(C3WgAr
   const int Kdim = Cin * KK;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 31, half = lane >> 5;
-  const int chunk = blockIdx.x;
+  int chunk, tile;
+  tile_fastest(gridDim.x, gridDim.y * gridDim.z, chunk, tile);
   const int n = chunk / w.cps;
   const int p0 = ((chunk - n * w.cps) * 4 + wave) * w.pxw;
   const int p1 = min(p0 + w.pxw, HWo);
-  const int k_base = blockIdx.y * 32, co_base = blockIdx.z * 32;
+  const int k_base = (tile % (int)gridDim.y) * 32, co_base = (tile / (int)gridDim.y) * 32;
   const int k = k_base + row;
   const bool av = co_base + row < Cout, bv = k < Kdim;
   const int ci = bv ? k / KK : 0, t = k - (k / KK) * KK, tu = t / KS, tv = t - tu * KS;
