@@ -35,7 +35,11 @@ struct DwkGeom {
   int SWo;  // strips per output row
   int SWx;  // stride 1: strips per dx row
   int WX, WG, PG, HG;
+  // floor(2^32 / d) + 1 for the divisors the kernels need (index / d = mul-high for index < 2^32 / d)
+  unsigned mW, mWo, mSWo, mSWx, mQW;
 };
+
+inline unsigned magic(int d) { return d <= 1 ? 0u : (unsigned)((1ull << 32) / (unsigned)d) + 1u; }
 
 inline DwkGeom dwk_geom(int C, int H, int W, int stride) {
   DwkGeom g;
@@ -49,31 +53,83 @@ inline DwkGeom dwk_geom(int C, int H, int W, int stride) {
   g.HG = g.Ho + 2 * g.PG;
   // stride 1: dx strips read columns j0 .. j0 + 7 of the padded gradient; weight-gradient strips read g[i][j0 .. j0+3]
   g.WG = up4(std::max(g.Wo + 2 * g.PG, stride == 1 ? g.SWx * 4 + 4 : g.SWo * 4 + g.PG));
+  g.mW = magic(W); g.mWo = magic(g.Wo); g.mSWo = magic(g.SWo); g.mSWx = magic(g.SWx); g.mQW = magic((W + 1) / 2);
   return g;
 }
 inline size_t x_floats(const DwkGeom& g) { return (size_t)(g.H + K - 1) * g.WX; }
 inline size_t g_floats(const DwkGeom& g) { return (size_t)g.HG * g.WG; }
 
-// rows x width floats at `sh`, image h x w placed at (pad, pad), zero elsewhere.  Eight loads per
-// thread are requested before the first is stored, so that a plane costs one or two memory latencies
-// instead of one per 256 elements.
-__device__ __forceinline__ void stage_plane(const float* __restrict__ src, float* __restrict__ sh, int h, int w, int rows,
-                                            int width, int pad) {
-  const int total = rows * width;
+// index / d with the multiplier of magic(d); exact for index * d < 2^32
+__device__ __forceinline__ int fast_div(int i, int d, unsigned m) { return d <= 1 ? i : (int)__umulhi((unsigned)i, m); }
+
+// n4 16-byte words at sh = 0 (the halo of the staged planes stays zero from then on)
+__device__ __forceinline__ void zero_lds(float* __restrict__ sh, int n4) {
+  for (int i = threadIdx.x; i < n4; i += 256) reinterpret_cast<float4*>(sh)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// The image h x w (contiguous at src) into rows of `width` floats at sh, placed at (pad, pad); the halo
+// is not touched (zero_lds).  The source is walked linearly (coalesced 4-byte loads, the row index by a
+// multiply-high); eight loads per thread are requested before the first is stored, so that a plane
+// costs one or two memory latencies instead of one per 256 elements.
+__device__ __forceinline__ void stage_plane(const float* __restrict__ src, float* __restrict__ sh, int h, int w, int width,
+                                            int pad, unsigned mw) {
+  const int total = h * w;
+  float* dst = sh + pad * width + pad;
   for (int i0 = threadIdx.x; i0 < total; i0 += 8 * 256) {
     float v[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const int i = i0 + 256 * k;
-      const int r = i / width, q = i - r * width;
-      const int hr = r - pad, wq = q - pad;
       v[k] = 0.f;
-      if (i < total && hr >= 0 && hr < h && wq >= 0 && wq < w) v[k] = src[(size_t)hr * w + wq];
+      if (i < total) v[k] = src[i];
     }
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
-      if (i0 + 256 * k < total) sh[i0 + 256 * k] = v[k];
+    for (int k = 0; k < 8; ++k) {
+      const int i = i0 + 256 * k;
+      if (i < total) {
+        const int r = fast_div(i, w, mw);
+        dst[r * width + (i - r * w)] = v[k];
+      }
+    }
   }
+}
+
+// Two images at once (x and the upstream gradient of the backward pass): the loads of both are
+// requested before the first store, so the pair costs one memory latency.
+__device__ __forceinline__ void stage_two(const float* __restrict__ sa, float* __restrict__ sha, int ha, int wa, int widtha,
+                                          int pada, unsigned mwa, const float* __restrict__ sb, float* __restrict__ shb,
+                                          int hb, int wb, int widthb, int padb, unsigned mwb) {
+  const int ta = ha * wa, tb = hb * wb;
+  float* da = sha + pada * widtha + pada;
+  float* db = shb + padb * widthb + padb;
+  for (int i0 = threadIdx.x; i0 < max(ta, tb); i0 += 4 * 256) {
+    float va[4], vb[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + 256 * k;
+      va[k] = vb[k] = 0.f;
+      if (i < ta) va[k] = sa[i];
+      if (i < tb) vb[k] = sb[i];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + 256 * k;
+      if (i < ta) {
+        const int r = fast_div(i, wa, mwa);
+        da[r * widtha + (i - r * wa)] = va[k];
+      }
+      if (i < tb) {
+        const int r = fast_div(i, wb, mwb);
+        db[r * widthb + (i - r * wb)] = vb[k];
+      }
+    }
+  }
+}
+
+// v of the lane that the DPP control CTRL pairs this lane with (all rows and banks enabled)
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
 
 // NW 16-byte words of a row
@@ -102,14 +158,16 @@ __global__ __launch_bounds__(256) void dwk_fwd_f32_kernel(const float* __restric
   extern __shared__ __align__(16) float sh[];
   constexpr int NW = S == 1 ? 2 : 3;
   const int plane = blockIdx.x, c = plane % gm.C;
-  stage_plane(x + (size_t)plane * gm.H * gm.W, sh, gm.H, gm.W, gm.H + K - 1, gm.WX, P);
+  zero_lds(sh, (gm.H + K - 1) * gm.WX / 4);
+  __syncthreads();
+  stage_plane(x + (size_t)plane * gm.H * gm.W, sh, gm.H, gm.W, gm.WX, P, gm.mW);
   float wk[KK];
 #pragma unroll
   for (int t = 0; t < KK; ++t) wk[t] = w[(size_t)c * KK + t];
   __syncthreads();
   float* yp = y + (size_t)plane * gm.Ho * gm.Wo;
   for (int sidx = threadIdx.x; sidx < gm.Ho * gm.SWo; sidx += 256) {
-    const int i = sidx / gm.SWo, j0 = (sidx - i * gm.SWo) * 4;
+    const int i = fast_div(sidx, gm.SWo, gm.mSWo), j0 = (sidx - i * gm.SWo) * 4;
     float o[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int u = 0; u < K; ++u) {
@@ -124,7 +182,7 @@ __global__ __launch_bounds__(256) void dwk_fwd_f32_kernel(const float* __restric
   }
 }
 
-// LDS: [x plane][g plane][4 wavefronts x 25 partial sums].  Block (c, group): the planes of channel c of
+// LDS: [x plane][g plane][16 lane rows x 25 partial sums].  Block (c, group): the planes of channel c of
 // the samples group*NB .. group*NB + NB - 1, one after the other; the 25 weight-gradient sums stay in
 // registers across them, so their reduction over the block is paid once per NB planes.
 template <int S>
@@ -144,16 +202,17 @@ __global__ __launch_bounds__(256) void dwk_bwd_f32_kernel(const float* __restric
 #pragma unroll
   for (int t = 0; t < KK; ++t) acc[t] = 0.f;
   const int n_end = min(N, (group + 1) * NB);
+  zero_lds(sh, ((gm.H + K - 1) * gm.WX + gm.HG * gm.WG) / 4);
   for (int n = group * NB; n < n_end; ++n) {
     const size_t plane = (size_t)n * gm.C + c;
-    if (n != group * NB) __syncthreads();  // the previous plane has been consumed
-    stage_plane(x + plane * gm.H * gm.W, shx, gm.H, gm.W, gm.H + K - 1, gm.WX, P);
-    stage_plane(g + plane * gm.Ho * gm.Wo, shg, gm.Ho, gm.Wo, gm.HG, gm.WG, gm.PG);
+    __syncthreads();  // the halo is zero / the previous plane has been consumed
+    stage_two(x + plane * gm.H * gm.W, shx, gm.H, gm.W, gm.WX, P, gm.mW, g + plane * gm.Ho * gm.Wo, shg, gm.Ho, gm.Wo,
+              gm.WG, gm.PG, gm.mWo);
     __syncthreads();
 
     // weight gradient: dW[u][v] += sum_{i,j} g[i][j] * x[i*S - 2 + u][j*S - 2 + v]
     for (int sidx = threadIdx.x; sidx < gm.Ho * gm.SWo; sidx += 256) {
-      const int i = sidx / gm.SWo, j0 = (sidx - i * gm.SWo) * 4;
+      const int i = fast_div(sidx, gm.SWo, gm.mSWo), j0 = (sidx - i * gm.SWo) * 4;
       float gv[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) gv[q] = shg[(i + gm.PG) * gm.WG + gm.PG + j0 + q];  // zero beyond Wo
@@ -173,7 +232,7 @@ __global__ __launch_bounds__(256) void dwk_bwd_f32_kernel(const float* __restric
     if (S == 1) {
       // dx[i][j] = sum_{u,v} w[4-u][4-v] * gpad[i + u][j + v], gpad = g with a zero halo of two
       for (int sidx = threadIdx.x; sidx < gm.H * gm.SWx; sidx += 256) {
-        const int i = sidx / gm.SWx, j0 = (sidx - i * gm.SWx) * 4;
+        const int i = fast_div(sidx, gm.SWx, gm.mSWx), j0 = (sidx - i * gm.SWx) * 4;
         float o[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = 0; u < K; ++u) {
@@ -192,7 +251,7 @@ __global__ __launch_bounds__(256) void dwk_bwd_f32_kernel(const float* __restric
       // even rows use u = 0, 2, 4 on d = 2, 1, 0; odd rows u = 1, 3 on d = 2, 1; columns alike
       const int QH = (gm.H + 1) / 2, QW = (gm.W + 1) / 2;
       for (int qidx = threadIdx.x; qidx < QH * QW; qidx += 256) {
-        const int a = qidx / QW, b = qidx - a * QW;
+        const int a = fast_div(qidx, QW, gm.mQW), b = qidx - a * QW;
         float gw[3][3];
 #pragma unroll
         for (int d = 0; d < 3; ++d)
@@ -221,25 +280,30 @@ __global__ __launch_bounds__(256) void dwk_bwd_f32_kernel(const float* __restric
       }
     }
   }
-  // the 25 sums over the wavefront step by step together: 25 independent lane exchanges in flight per
-  // step instead of 150 dependent ones
+  // the 25 sums over each row of 16 lanes with data-parallel-primitive adds (lane exchanges inside the
+  // VALU: quad swaps, then the mirrored half row and the mirrored row, whose partner lies in the other
+  // half each time), 25 independent chains per step; the 16 row sums of the block go through LDS and
+  // are added in a fixed order
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    float other[KK];
+  for (int t = 0; t < KK; ++t) acc[t] += dpp_move<0xB1>(acc[t]);   // quad_perm [1,0,3,2]
 #pragma unroll
-    for (int t = 0; t < KK; ++t) other[t] = __shfl_xor(acc[t], o, 64);
+  for (int t = 0; t < KK; ++t) acc[t] += dpp_move<0x4E>(acc[t]);   // quad_perm [2,3,0,1]
 #pragma unroll
-    for (int t = 0; t < KK; ++t) acc[t] += other[t];
-  }
-  if (lane == 0) {
+  for (int t = 0; t < KK; ++t) acc[t] += dpp_move<0x141>(acc[t]);  // row_half_mirror
 #pragma unroll
-    for (int t = 0; t < KK; ++t) shr[wv * KK + t] = acc[t];
+  for (int t = 0; t < KK; ++t) acc[t] += dpp_move<0x140>(acc[t]);  // row_mirror
+  if ((lane & 15) == 0) {
+#pragma unroll
+    for (int t = 0; t < KK; ++t) shr[(wv * 4 + (lane >> 4)) * KK + t] = acc[t];
   }
   __syncthreads();
-  if (threadIdx.x < KK)
-    part[((size_t)group * gm.C + c) * KK + threadIdx.x] =
-        shr[threadIdx.x] + shr[KK + threadIdx.x] + shr[2 * KK + threadIdx.x] + shr[3 * KK + threadIdx.x];
+  if (threadIdx.x < KK) {
+    float s = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += shr[r * KK + threadIdx.x];
+    part[((size_t)group * gm.C + c) * KK + threadIdx.x] = s;
+  }
 }
 
 // G[c][t] += sum over the N sample groups of part[group][c][t], in order
@@ -258,7 +322,7 @@ __global__ void dwk_wgrad_final_kernel(const float* __restrict__ part, float* __
 }
 
 size_t fwd_lds(const DwkGeom& g) { return x_floats(g) * sizeof(float); }
-size_t bwd_lds(const DwkGeom& g) { return (x_floats(g) + g_floats(g) + 4 * KK) * sizeof(float); }
+size_t bwd_lds(const DwkGeom& g) { return (x_floats(g) + g_floats(g) + 16 * KK) * sizeof(float); }
 
 }  // namespace
 
