@@ -13,19 +13,67 @@ typedef unsigned short bf16_t;  // storage type of one bf16 value
 
 constexpr int kWave = 64;
 
+// Lane exchanges inside the VALU (data-parallel primitives) instead of through the LDS crossbar
+// (ds_bpermute, which __shfl_* compile to: an LDS instruction and its latency per exchange).
+// dpp_move<CTRL>(v) = v of the lane that control CTRL pairs this lane with, 0 where there is none.
+constexpr int DPP_QUAD_SWAP1 = 0xB1;    // quad_perm [1,0,3,2]: lane ^ 1
+constexpr int DPP_QUAD_SWAP2 = 0x4E;    // quad_perm [2,3,0,1]: lane ^ 2
+constexpr int DPP_HALF_MIRROR = 0x141;  // lane i of a group of 8 <- lane 7 - i (the other quad)
+constexpr int DPP_ROW_MIRROR = 0x140;   // lane i of a row of 16 <- lane 15 - i (the other half row)
+constexpr int DPP_WAVE_SHR1 = 0x138;    // lane i <- lane i - 1 over the whole wavefront
+constexpr int DPP_WAVE_SHL1 = 0x130;    // lane i <- lane i + 1
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, true);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, true);
+  return __hiloint2double(hi, lo);
+}
+// v of lane - 1 / lane + 1 (0 at the ends of the wavefront)
+__device__ __forceinline__ float lane_up1(float v) { return dpp_move<DPP_WAVE_SHR1>(v); }
+__device__ __forceinline__ float lane_down1(float v) { return dpp_move<DPP_WAVE_SHL1>(v); }
+// sum over the 2, 4, 8, 16 lanes of the aligned group of this lane, valid in each of its lanes (the
+// partner of every step lies in the other half of the group, so all lanes add the same pairs)
+template <typename T> __device__ __forceinline__ T group4_sum(T v) {
+  v += dpp_move<DPP_QUAD_SWAP1>(v);
+  v += dpp_move<DPP_QUAD_SWAP2>(v);
+  return v;
+}
+template <typename T> __device__ __forceinline__ T group8_sum(T v) {
+  v = group4_sum(v);
+  v += dpp_move<DPP_HALF_MIRROR>(v);
+  return v;
+}
+template <typename T> __device__ __forceinline__ T row16_sum(T v) {
+  v = group8_sum(v);
+  v += dpp_move<DPP_ROW_MIRROR>(v);
+  return v;
+}
+// Sums over the wavefront, valid in every lane: four steps inside the rows of 16, the two steps
+// across rows through the LDS crossbar (an inactive lane contributes 0 in both).
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  v = row16_sum(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
   return v;
 }
 __device__ __forceinline__ double wave_sum_d(double v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  v = row16_sum(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
   return v;
 }
+// maximum over the wavefront; all 64 lanes must be active
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  v = fmaxf(v, dpp_move<DPP_QUAD_SWAP1>(v));
+  v = fmaxf(v, dpp_move<DPP_QUAD_SWAP2>(v));
+  v = fmaxf(v, dpp_move<DPP_HALF_MIRROR>(v));
+  v = fmaxf(v, dpp_move<DPP_ROW_MIRROR>(v));
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  v = fmaxf(v, __shfl_xor(v, 32, 64));
   return v;
 }
 
@@ -34,8 +82,9 @@ __device__ __forceinline__ float wave_max(float v) {
 template <typename T>
 __device__ __forceinline__ T block_sum(T v, T* sh) {
   int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  v = row16_sum(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
   __syncthreads();
   if (lane == 0) sh[w] = v;
   __syncthreads();

@@ -86,9 +86,7 @@ __device__ __forceinline__ void pw_stats_epilogue(const float (&s)[16], const fl
     float v = 0.f;
 #pragma unroll
     for (int k = 0; k < 16; ++k) v += sR[w][r][c0 + ((k + rot) & 15)];
-    v += __shfl_xor(v, 1, 64);
-    v += __shfl_xor(v, 2, 64);
-    v += __shfl_xor(v, 4, 64);
+    v = group8_sum(v);
     tot[pass] = v;
   }
   if (part == 0 && m_base + ci < Mdim) {
@@ -917,7 +915,9 @@ __global__ __launch_bounds__(256) void dw3x3_fwd_f32_kernel(const float* __restr
   // thread, fp64 across the tpp threads of the plane (tpp is a power of two >= 16)
   double d1 = (double)s1, d2 = (double)s2;
   const int span = tpp < 64 ? tpp : 64;
-  for (int o = span >> 1; o > 0; o >>= 1) {
+  d1 = row16_sum(d1);
+  d2 = row16_sum(d2);
+  for (int o = 16; o < span; o <<= 1) {  // across the rows of 16 lanes of a wider plane group
     d1 += __shfl_xor(d1, o, 64);
     d2 += __shfl_xor(d2, o, 64);
   }
@@ -1121,8 +1121,10 @@ __global__ __launch_bounds__(256) void dw3x3_bwd_f32_kernel(const float* __restr
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int span = tpp < 64 ? tpp : 64;
 #pragma unroll
-  for (int k = 0; k < 11; ++k)
-    for (int o = span >> 1; o > 0; o >>= 1) acc[k] += __shfl_xor(acc[k], o, 64);
+  for (int k = 0; k < 11; ++k) {
+    acc[k] = row16_sum(acc[k]);
+    for (int o = 16; o < span; o <<= 1) acc[k] += __shfl_xor(acc[k], o, 64);  // across rows of 16 lanes
+  }
   const int N = gm.NC / gm.C;
   double* bws = f.ws_in ? f.ws_in + ((size_t)ch * N + (plane0 + pl) / gm.C) * 2 : nullptr;
   if (tpp <= 64) {
@@ -1205,7 +1207,7 @@ template <int VW> struct DwRow { float v[VW + 2]; };
 template <int VW>
 __device__ __forceinline__ DwRow<VW> dw_make_row(const DwVec<VW>& c, int s, int SW) {
   DwRow<VW> r;
-  const float left = __shfl_up(c.e[VW - 1], 1, 64), right = __shfl_down(c.e[0], 1, 64);
+  const float left = lane_up1(c.e[VW - 1]), right = lane_down1(c.e[0]);
   r.v[0] = s == 0 ? 0.f : left;
 #pragma unroll
   for (int j = 0; j < VW; ++j) r.v[j + 1] = c.e[j];
@@ -1360,7 +1362,7 @@ template <int VW> struct DwX2 { float v[VW + 1]; };      // the input column lef
 template <int VW>
 __device__ __forceinline__ DwG2<VW> dw_make_g2(const DwVec<VW / 2>& c, int s, int SW) {
   DwG2<VW> r;
-  const float right = __shfl_down(c.e[0], 1, 64);
+  const float right = lane_down1(c.e[0]);
 #pragma unroll
   for (int j = 0; j < VW / 2; ++j) r.v[j] = c.e[j];
   r.v[VW / 2] = s == SW - 1 ? 0.f : right;
@@ -1369,7 +1371,7 @@ __device__ __forceinline__ DwG2<VW> dw_make_g2(const DwVec<VW / 2>& c, int s, in
 template <int VW>
 __device__ __forceinline__ DwX2<VW> dw_make_x2(const DwVec<VW>& c, int s) {
   DwX2<VW> r;
-  const float left = __shfl_up(c.e[VW - 1], 1, 64);
+  const float left = lane_up1(c.e[VW - 1]);
   r.v[0] = s == 0 ? 0.f : left;
 #pragma unroll
   for (int j = 0; j < VW; ++j) r.v[j + 1] = c.e[j];
@@ -1709,9 +1711,7 @@ __global__ __launch_bounds__(256) void dw3x3_wgrad_final_kernel(const float* __r
   float s = 0.f;
   if (i < C * 9)
     for (int n = nl; n < N; n += 8) s += part[(size_t)n * C * 9 + i];
-  s += __shfl_xor(s, 4, 64);
-  s += __shfl_xor(s, 2, 64);
-  s += __shfl_xor(s, 1, 64);
+  s = group8_sum(s);
   if (nl == 0 && i < C * 9) G[i] += s;
 }
 
