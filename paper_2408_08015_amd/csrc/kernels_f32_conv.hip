@@ -488,17 +488,18 @@ __device__ __forceinline__ void pw_wgrad_body(const WgArgs& w, int bx, int by, i
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
   if (VEC) {  // HW % 4 == 0: aligned 16-byte loads, 16 pixels per fragment, two fragments in flight
     struct Frag { float4 a0, a1, b0, b1; };
+    // Branch-free: rows beyond Cout / Cin read channel 0 (their products land in rows / columns of the
+    // tile that are never stored); pixels beyond the chunk read pixel 0 and get a zero g operand.
     auto ld = [&](int p, Frag& f) {
       const int pp = p + 8 * half;
-      f.a0 = f.a1 = f.b0 = f.b1 = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (pp < p1) {
-        if (av) f.a0 = *reinterpret_cast<const float4*>(ga + pp);
-        if (bv) f.b0 = *reinterpret_cast<const float4*>(xb + pp);
-      }
-      if (pp + 4 < p1) {
-        if (av) f.a1 = *reinterpret_cast<const float4*>(ga + pp + 4);
-        if (bv) f.b1 = *reinterpret_cast<const float4*>(xb + pp + 4);
-      }
+      const bool v0 = pp < p1, v1 = pp + 4 < p1;
+      const int q0 = v0 ? pp : 0, q1 = v1 ? pp + 4 : 0;
+      f.a0 = *reinterpret_cast<const float4*>(ga + q0);
+      f.b0 = *reinterpret_cast<const float4*>(xb + q0);
+      f.a1 = *reinterpret_cast<const float4*>(ga + q1);
+      f.b1 = *reinterpret_cast<const float4*>(xb + q1);
+      if (!v0) f.a0 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (!v1) f.a1 = make_float4(0.f, 0.f, 0.f, 0.f);
     };
     auto mma = [&](const Frag& f) {
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.x, f.b0.x, acc, 0, 0, 0);
@@ -512,14 +513,19 @@ __device__ __forceinline__ void pw_wgrad_body(const WgArgs& w, int bx, int by, i
     };
     Frag f0, f1, f2, f3;
     for (int p = p0; p < p1; p += 64) {  // four fragments issued before the first MFMA
+      const bool more = p + 32 < p1;     // uniform: a 32-pixel wavefront has two fragments only
       ld(p, f0);
       ld(p + 16, f1);
-      ld(p + 32, f2);
-      ld(p + 48, f3);
+      if (more) {
+        ld(p + 32, f2);
+        ld(p + 48, f3);
+      }
       mma(f0);
       mma(f1);
-      mma(f2);
-      mma(f3);
+      if (more) {
+        mma(f2);
+        mma(f3);
+      }
     }
   } else {
     for (int p = p0; p < p1; p += 32) {  // sixteen pixel pairs requested before the first MFMA
