@@ -109,13 +109,13 @@ __device__ __forceinline__ void pw_pk_body(const PwArgs& a, int bx, int by, floa
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int m_base = by * 32;
-  const long q = (long)bx * 128 + wave * 32 + col;
+  const unsigned q = (unsigned)bx * 128u + wave * 32 + col;  // pixels per micro-batch < 2^31 (checked at create)
   const bool qv = q < NQ;
-  long n = 0;
+  unsigned n = 0;
   int p = 0;
   if (qv) {
-    n = q / HW;
-    p = (int)(q - n * HW);
+    n = q / (unsigned)HW;  // 32-bit: a 64-bit division is ~150 instructions
+    p = (int)(q - n * (unsigned)HW);
   }
   const float* xq = X + (size_t)n * Kdim * HW + p;
   const float4* wl = Wp + (size_t)by * KG * 64 + lane;
@@ -194,13 +194,13 @@ __device__ __forceinline__ void pw_pkks_body(const PwArgs& a, int bx, int by, fl
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int m_base = by * 32;
-  const long q = (long)bx * 32 + col;
+  const unsigned q = (unsigned)bx * 32u + col;  // pixels per micro-batch < 2^31 (checked at create)
   const bool qv = q < NQ;
-  long n = 0;
+  unsigned n = 0;
   int p = 0;
   if (qv) {
-    n = q / HW;
-    p = (int)(q - n * HW);
+    n = q / (unsigned)HW;  // 32-bit: a 64-bit division is ~150 instructions
+    p = (int)(q - n * (unsigned)HW);
   }
   const float* xq = X + (size_t)n * Kdim * HW + p;
   const float4* wl = Wp + (size_t)by * KG * 64 + lane;
@@ -276,13 +276,13 @@ __device__ __forceinline__ void pw_pk4_body(const PwArgs& a, int bx, int by, flo
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int m_base = by * 32;
-  const long q = (long)bx * 512 + wave * 128 + col * 4;
+  const unsigned q = (unsigned)bx * 512u + wave * 128 + col * 4;  // pixels per micro-batch < 2^31 (checked at create)
   const bool qv = q < NQ;  // NQ % 4 == 0: the four pixels are valid together
-  long n = 0;
+  unsigned n = 0;
   int p = 0;
   if (qv) {
-    n = q / HW;
-    p = (int)(q - n * HW);
+    n = q / (unsigned)HW;  // 32-bit: a 64-bit division is ~150 instructions
+    p = (int)(q - n * (unsigned)HW);
   }
   const float* xq = X + (size_t)n * Kdim * HW + p;
   const float4* wl = Wp + (size_t)by * KG * 64 + lane;
@@ -321,20 +321,29 @@ __device__ __forceinline__ void pw_pk4_body(const PwArgs& a, int bx, int by, flo
   if (qv) {
     float* yq = Y + (size_t)n * Mdim * HW + p;
     const float* aq = add ? add + (size_t)n * Mdim * HW + p : nullptr;
+    // bias and addend of eight rows at a time are requested before the first is used (rows past Mdim
+    // read the last row)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
-      if (m < Mdim) {
-        float4 v = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
-        if (bias) {
-          const float bv = bias[m];
-          v.x += bv; v.y += bv; v.z += bv; v.w += bv;
-        }
-        if (aq) {
-          const float4 k = *reinterpret_cast<const float4*>(aq + (size_t)m * HW);
-          v.x += k.x; v.y += k.y; v.z += k.z; v.w += k.w;
-        }
-        *reinterpret_cast<float4*>(yq + (size_t)m * HW) = v;
+    for (int r0 = 0; r0 < 16; r0 += 8) {
+      float bv[8];
+      float4 kv[8];
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr) {
+        const int r = r0 + rr;
+        const int mc = min(m_base + 8 * (r >> 2) + 4 * half + (r & 3), Mdim - 1);
+        bv[rr] = 0.f;
+        kv[rr] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (bias) bv[rr] = bias[mc];
+        if (aq) kv[rr] = *reinterpret_cast<const float4*>(aq + (size_t)mc * HW);
+      }
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr) {
+        const int r = r0 + rr;
+        const int m = m_base + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (m < Mdim)
+          *reinterpret_cast<float4*>(yq + (size_t)m * HW) =
+              make_float4(acc[0][r] + bv[rr] + kv[rr].x, acc[1][r] + bv[rr] + kv[rr].y, acc[2][r] + bv[rr] + kv[rr].z,
+                          acc[3][r] + bv[rr] + kv[rr].w);
       }
     }
   }

@@ -59,13 +59,13 @@ __global__ __launch_bounds__(256) void conv_mfma_f32_kernel(C3Args a) {
   int bx, by;
   tile_fastest(gridDim.x, gridDim.y, bx, by);
   const int tile0 = by * MT;  // first 32-row tile of this block
-  const long q = (long)bx * 128 + wave * 32 + col;
+  const unsigned q = (unsigned)bx * 128u + wave * 32 + col;  // pixels per micro-batch < 2^31 (checked at create)
   const bool qv = q < a.NQ;
-  long n = 0;
+  unsigned n = 0;
   int p = 0;
   if (qv) {
-    n = q / PHW;
-    p = (int)(q - n * PHW);
+    n = q / (unsigned)PHW;  // 32-bit: a 64-bit division is ~150 instructions
+    p = (int)(q - n * (unsigned)PHW);
   }
   const int pi = p / PW, pj = p - pi * PW;
   const float* xn = X + (size_t)n * Kdim * XHW;
@@ -337,13 +337,13 @@ __global__ __launch_bounds__(256) void conv_gatherk_mfma_f32_kernel(GkArgs a) {
   int bx, by;
   tile_fastest(gridDim.x, gridDim.y, bx, by);
   const int m_base = by * 32;
-  const long q = (long)bx * 128 + wave * 32 + col;
+  const unsigned q = (unsigned)bx * 128u + wave * 32 + col;  // pixels per micro-batch < 2^31 (checked at create)
   const bool qv = q < a.NQ;
-  long n = 0;
+  unsigned n = 0;
   int p = 0;
   if (qv) {
-    n = q / HWo;
-    p = (int)(q - n * HWo);
+    n = q / (unsigned)HWo;  // 32-bit: a 64-bit division is ~150 instructions
+    p = (int)(q - n * (unsigned)HWo);
   }
   const int pi = p / Wo, pj = p - pi * Wo;
   const int r0 = pi * S - PAD, c0 = pj * S - PAD;

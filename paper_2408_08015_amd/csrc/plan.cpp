@@ -75,6 +75,9 @@ ast_status build_plan(Stage& s, std::string& err) {
         op.cin = Cin; op.cout = Cout; op.k = k; op.stride = st; op.pad = pad; op.groups = g; op.has_bias = hb ? 1 : 0;
         op.w_off = poff; poff += (size_t)Cout * (Cin / g) * k * k;
         if (hb) { op.b_off = poff; poff += Cout; }
+        if (!s.bf16 && (size_t)B * std::max((size_t)A.h * A.w, (size_t)Ho * Wo) >= ((size_t)1 << 31)) {  // 32-bit pixel indices
+          err = fmt("layer %d: conv2d needs fewer than 2^31 pixels per micro-batch", i);
+          return AST_EUNSUPPORTED; }
         if (s.bf16) {
           if (!(g == 1 && (k == 1 || k == 3) && st == 1 && pad == (k - 1) / 2 && Cin % 8 == 0 && Cout % 8 == 0)) {
             err = fmt("layer %d: bf16 conv2d supports dense 1x1/3x3 stride 1 'same' with channels %% 8 == 0", i);
