@@ -87,6 +87,9 @@ def test_plan_errors(A):
     with pytest.raises(A.AsteroidError) as e:                     # bf16 BatchNorm is not covered
         A.plan_memory(ok.layers, 4, 2, 1, ok.in_shape, "bf16", "nhwc")
     assert e.value.status == -5
+    with pytest.raises(A.AsteroidError) as e:                     # 32-bit pixel indices: B*H*W < 2^31
+        A.plan_memory([dict(kind="conv2d", cin=8, cout=8, k=1, stride=1, pad=0, groups=1, bias=False)], 32, 1, 1, (8, 8192, 8192))
+    assert e.value.status == -5 and "2^31" in str(e.value)
     with pytest.raises(A.AsteroidError):
         A.plan_memory(ok.layers, 0, 2, 1, ok.in_shape)
 
