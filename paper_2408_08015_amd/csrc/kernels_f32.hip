@@ -161,24 +161,26 @@ __global__ __launch_bounds__(256) void conv3x3_small_cin_fwd_kernel(const float*
 // Dense 3x3 conv with up to 4 input channels (an RGB stem), weight gradient: block = four output
 // channels x one chunk of the flattened (n, i, j) output positions; a thread reads the CG*9
 // inputs of a position once and keeps the 4 x CG*9 sums of its positions in registers; the block
-// adds them (wavefront butterflies, then one pass through LDS) and writes one partial per chunk.
+// adds them (DPP adds inside the rows of 16 lanes, then the 16 row sums through LDS in a fixed order)
+// and writes one partial per chunk.  Positions are 32-bit (fewer than 2^31 per micro-batch, checked
+// at create).
 template <int CG>
 __global__ __launch_bounds__(256) void conv3x3_small_cin_wgrad_kernel(
     const float* __restrict__ g, const float* __restrict__ x, float* __restrict__ part, int N, int H, int W,
     int Cout, int Ho, int Wo, int stride, int pad, int per_chunk) {
   constexpr int T = CG * 9, OC = 4;
-  __shared__ float sh[4][OC * T];
+  __shared__ float sh[16][OC * T];
   const int o0 = blockIdx.x * OC, chunk = blockIdx.y;
-  const long per = (long)N * Ho * Wo;
-  const long e0 = (long)chunk * per_chunk, e1 = min(e0 + per_chunk, per);
+  const unsigned HWo = (unsigned)(Ho * Wo), per = (unsigned)N * HWo;
+  const unsigned e0 = (unsigned)chunk * (unsigned)per_chunk, e1 = min(e0 + (unsigned)per_chunk, per);
   float acc[OC][T];
 #pragma unroll
   for (int oo = 0; oo < OC; ++oo)
 #pragma unroll
     for (int k = 0; k < T; ++k) acc[oo][k] = 0.f;
-  for (long e = e0 + threadIdx.x; e < e1; e += 256) {
-    const int n = (int)(e / ((long)Ho * Wo));
-    const int r = (int)(e - (long)n * Ho * Wo);
+  for (unsigned e = e0 + threadIdx.x; e < e1; e += 256) {
+    const int n = (int)(e / HWo);
+    const int r = (int)(e - (unsigned)n * HWo);
     const int i = r / Wo, j = r - i * Wo;
     float gv[OC];
 #pragma unroll
@@ -207,14 +209,18 @@ __global__ __launch_bounds__(256) void conv3x3_small_cin_wgrad_kernel(
   for (int oo = 0; oo < OC; ++oo)
 #pragma unroll
     for (int k = 0; k < T; ++k) {
-      const float s = wave_sum(acc[oo][k]);
-      if (lane == 0) sh[wave][oo * T + k] = s;
+      const float s = row16_sum(acc[oo][k]);
+      if ((lane & 15) == 0) sh[wave * 4 + (lane >> 4)][oo * T + k] = s;
     }
   __syncthreads();
   for (int q = threadIdx.x; q < OC * T; q += 256) {
     const int oo = q / T;
-    if (o0 + oo < Cout)
-      part[((size_t)chunk * Cout + o0 + oo) * T + (q - oo * T)] = (sh[0][q] + sh[1][q]) + (sh[2][q] + sh[3][q]);
+    if (o0 + oo < Cout) {
+      float s = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += sh[r][q];
+      part[((size_t)chunk * Cout + o0 + oo) * T + (q - oo * T)] = s;
+    }
   }
 }
 
