@@ -92,7 +92,9 @@ __global__ __launch_bounds__(256) void conv_mfma_f32_kernel(C3Args a) {
       ok = ok && xr >= 0 && xc >= 0;
     }
     ok = ok && xr < XH && xc < XW;
-    const float* xt = xn + xr * XW + xc;  // dereferenced only where ok
+    // branch-free operand loads: a tap outside the tensor reads pixel 0 and is replaced by zero, rows
+    // past Kdim read the last row (they meet zero weights in the packed copy)
+    const float* xt = xn + (ok ? xr * XW + xc : 0);
     const float4* wt = wl + (size_t)tap * a.tap_stride;
     for (int g0 = 0; g0 < KG; g0 += NCH * 4) {
       float4 av[MT][NCH * 4];
@@ -104,10 +106,9 @@ __global__ __launch_bounds__(256) void conv_mfma_f32_kernel(C3Args a) {
         if (MT > 1) av[MT - 1][g] = (gv && t1) ? wt[(size_t)(KG + g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int k = (g0 + g) * 8 + 2 * e + half;
-          float val = 0.f;
-          if (ok && k < Kdim) val = xt[(size_t)k * XHW];
-          b[4 * g + e] = val;
+          const int k = min((g0 + g) * 8 + 2 * e + half, Kdim - 1);
+          const float val = xt[(size_t)k * XHW];
+          b[4 * g + e] = ok ? val : 0.f;
         }
       }
 #pragma unroll
