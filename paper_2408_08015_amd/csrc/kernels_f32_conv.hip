@@ -131,8 +131,11 @@ __device__ __forceinline__ void pw_pk_body(const PwArgs& a, int bx, int by, floa
       a[g] = ok ? wl[(size_t)(g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int k = (g0 + g) * 8 + 2 * e + half;
-        b[4 * g + e] = (qv && k < Kdim) ? xq[(size_t)k * HW] : 0.f;
+        // branch-free: rows past Kdim read the last row (zero weights in the packed copy), pixels past
+        // NQ read pixel 0 and are replaced by zero (the statistics epilogue sums every column)
+        const int k = min((g0 + g) * 8 + 2 * e + half, Kdim - 1);
+        const float val = xq[(size_t)k * HW];
+        b[4 * g + e] = qv ? val : 0.f;
       }
     }
 #pragma unroll
@@ -218,8 +221,9 @@ __device__ __forceinline__ void pw_pkks_body(const PwArgs& a, int bx, int by, fl
       a[g] = ok ? wl[(size_t)(g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int k = (g0 + g) * 8 + 2 * e + half;
-        b[4 * g + e] = (ok && qv && k < Kdim) ? xq[(size_t)k * HW] : 0.f;
+        const int k = min((g0 + g) * 8 + 2 * e + half, Kdim - 1);  // branch-free, as above
+        const float val = xq[(size_t)k * HW];
+        b[4 * g + e] = qv ? val : 0.f;
       }
     }
 #pragma unroll
@@ -300,9 +304,9 @@ __device__ __forceinline__ void pw_pk4_body(const PwArgs& a, int bx, int by, flo
       a[g] = ok ? wl[(size_t)(g0 + g) * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int k = (g0 + g) * 8 + 2 * e + half;
-        b[4 * g + e] = (qv && k < Kdim) ? *reinterpret_cast<const float4*>(xq + (size_t)k * HW)
-                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int k = min((g0 + g) * 8 + 2 * e + half, Kdim - 1);  // branch-free, as above
+        const float4 val = *reinterpret_cast<const float4*>(xq + (size_t)k * HW);
+        b[4 * g + e] = qv ? val : make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
 #pragma unroll
