@@ -258,24 +258,29 @@ __global__ __launch_bounds__(256) void conv3x3_wgrad_vec_mfma_f32_kernel(C3WgArg
     for (int f = 0; f < 2; ++f) {
       const int b0 = p + 16 * f + 8 * half, b1 = b0 + 4;   // the fragment's two groups of four pixels
       const bool in0 = b0 < p1, in1 = b1 < p1;              // (p1 is a multiple of four)
-      float4 a0 = z4, a1 = z4;
-      if (av && in0) a0 = *reinterpret_cast<const float4*>(ga + b0);
-      if (av && in1) a1 = *reinterpret_cast<const float4*>(ga + b1);
+      // Branch-free loads: a pixel group past the chunk reads pixel 0 and gets a zero g operand (its x
+      // operand then does not matter); rows past Cout / Cin read channel 0 and land in rows / columns of
+      // the tile that are never stored; an x row outside the image reads pixel 0 and becomes zero.
+      float4 a0 = *reinterpret_cast<const float4*>(ga + (in0 ? b0 : 0));
+      float4 a1 = *reinterpret_cast<const float4*>(ga + (in1 ? b1 : 0));
+      if (!in0) a0 = z4;
+      if (!in1) a1 = z4;
       const int i0 = b0 / W, j0 = b0 - i0 * W;
       int i1 = i0, j1 = j0 + 4;
       if (j1 >= W) { j1 -= W; ++i1; }
 #pragma unroll
       for (int du = -1; du <= 1; ++du) {
-        const bool v0 = bv && in0 && (unsigned)(i0 + du) < (unsigned)H;
-        const bool v1 = bv && in1 && (unsigned)(i1 + du) < (unsigned)H;
-        const float* x0 = xb + b0 + du * W;  // read only where valid
-        const float* x1 = xb + b1 + du * W;
-        float4 f0 = z4, f1 = z4;
-        float l0 = 0.f, r1 = 0.f;
-        if (v0) f0 = *reinterpret_cast<const float4*>(x0);
-        if (v1) f1 = *reinterpret_cast<const float4*>(x1);
-        if (v0 && j0 > 0) l0 = x0[-1];
-        if (v1 && j1 + 4 < W) r1 = x1[4];
+        const bool v0 = in0 && (unsigned)(i0 + du) < (unsigned)H;
+        const bool v1 = in1 && (unsigned)(i1 + du) < (unsigned)H;
+        const bool vl = v0 && j0 > 0, vr = v1 && j1 + 4 < W;
+        float4 f0 = *reinterpret_cast<const float4*>(xb + (v0 ? b0 + du * W : 0));
+        float4 f1 = *reinterpret_cast<const float4*>(xb + (v1 ? b1 + du * W : 0));
+        float l0 = xb[vl ? b0 + du * W - 1 : 0];
+        float r1 = xb[vr ? b1 + du * W + 4 : 0];
+        if (!v0) f0 = z4;
+        if (!v1) f1 = z4;
+        if (!vl) l0 = 0.f;
+        if (!vr) r1 = 0.f;
         // neighbours across the two groups: only inside one image row
         const float r0 = (j0 + 4 < W) ? f1.x : 0.f;
         const float l1 = (j1 > 0) ? f0.w : 0.f;
