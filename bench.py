@@ -221,8 +221,8 @@ DOMINANT = {
 TRAFFIC_BYTES = {
     ("cfg2", "bn_bwd_apply_kernel"): int((17501.9 / 0.5012 + 17254.5) * 1024),
     ("cfg4", "gemm_bf16_kernel<128x128,im2col>"): int((49588.4 / 0.5005 + 45994.7) * 1024),
-    ("cfg6", "pw_bwd_dual_kernel<pk2>"): int((22452.4 / 0.5007 + 18610.3) * 1024),
-    ("cfg7", "pw_bwd_dual_kernel<pk4>"): int((108342.8 / 0.5003 + 54125.7) * 1024),
+    ("cfg6", "pw_bwd_dual_kernel<pk2>"): int((22454.4 / 0.5010 + 18547.2) * 1024),
+    ("cfg7", "pw_bwd_dual_kernel<pk4>"): int((109159.3 / 0.5005 + 54125.7) * 1024),
 }
 
 
