@@ -28,6 +28,13 @@ void conv_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh_fwd, const 
 // conv) dx is zeroed where relu_out <= 0: that ReLU's backward, folded into the epilogue.
 void conv_bf16_dgrad(hipStream_t st, const bf16_t* g, const bf16_t* sh_dgrad, bf16_t* dx, const bf16_t* relu_out,
                      int N, int H, int W, int Cin, int Cout, int k);
+// The same 3x3 product with the input tile and its halo staged in LDS once per 64-channel slice
+// (conv_bf16_halo.hip); conv_bf16_fwd / conv_bf16_dgrad use it for the shapes it supports.
+// w is [Cout][tap][Cin]; the output is zeroed where mask <= 0 (mask may be NULL).  Returns false,
+// with nothing launched, if the device refuses the kernel's LDS size.
+bool conv3x3_halo_supported(int N, int H, int W, int Cin, int Cout);
+bool conv3x3_halo_bf16(hipStream_t st, const bf16_t* x, const bf16_t* w, const float* bias, const bf16_t* mask,
+                       bf16_t* y, int N, int H, int W, int Cin, int Cout, int act);
 // Scratch layout of a weight-gradient call: `splits` partial copies of the weight gradient at
 // ws[0, ...), `bias_parts` partial bias gradients ([bias_parts][Cout]) from float offset bias_off.
 struct WgradParts { int splits; size_t bias_off; int bias_parts; };
