@@ -654,8 +654,10 @@ ast_status refresh_shadow(Stage& s, std::string& err) {
     } else if (!s.bf16) {
       continue;  // the remaining copies are bf16 layouts
     } else if (op.kind == OP_CONV_IGEMM) {
+      const Act& I = s.acts[op.in];  // the kernel each direction will run decides the layout of its copy
       conv_weight_shadow_bf16(s.stream, s.W + op.w_off, s.shadow + op.sh_off, s.shadow + op.sh2_off, op.cout,
-                              op.cin, op.k);
+                              op.cin, op.k, conv_bf16_uses_halo(I.n, I.h, I.w, op.cin, op.cout, op.k),
+                              conv_bf16_uses_halo(I.n, I.h, I.w, op.cout, op.cin, op.k));
     } else if (op.kind == OP_LINEAR) {
       linear_weight_shadow_bf16(s.stream, s.W + op.w_off, s.shadow + op.sh_off, s.shadow + op.sh2_off, op.cout,
                                 op.cin);

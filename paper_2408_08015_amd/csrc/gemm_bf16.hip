@@ -848,16 +848,17 @@ WgradParts conv_bf16_wgrad_parts(int N, int H, int W, int Cin, int Cout, int k) 
 }
 
 // experiment switch: ASTEROID_CONV_HALO=0 keeps the 3x3 products on the generic implicit-GEMM kernel
-static bool use_halo(int N, int H, int W, int Cin, int Cout, int k) {
+bool conv_bf16_uses_halo(int N, int H, int W, int Cin, int Cout, int k) {
   static const bool on = env_int("ASTEROID_CONV_HALO") != 0;
   return on && k == 3 && conv3x3_halo_supported(N, H, W, Cin, Cout);
 }
 
 void conv_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh_fwd, const float* bias, bf16_t* y, int N,
                    int H, int W, int Cin, int Cout, int k, int act) {
-  if ((act == ACT_NONE || act == ACT_RELU) && use_halo(N, H, W, Cin, Cout, k) &&
-      conv3x3_halo_bf16(st, x, sh_fwd, bias, nullptr, y, N, H, W, Cin, Cout, act))
+  if (conv_bf16_uses_halo(N, H, W, Cin, Cout, k)) {  // sh_fwd is the tiled copy then
+    conv3x3_halo_bf16(st, x, sh_fwd, bias, nullptr, y, N, H, W, Cin, Cout, act);
     return;
+  }
   GemmArgs g = {};
   g.A = x; g.B = sh_fwd;
   g.M = (long)N * H * W; g.N = Cout; g.K = (long)k * k * Cin;
@@ -870,8 +871,10 @@ void conv_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh_fwd, const 
 void conv_bf16_dgrad(hipStream_t st, const bf16_t* gy, const bf16_t* sh_dgrad, bf16_t* dx, const bf16_t* relu_out,
                      int N, int H, int W, int Cin, int Cout, int k) {
   // the input gradient is the same product with the roles of the channel counts exchanged
-  if (use_halo(N, H, W, Cout, Cin, k) && conv3x3_halo_bf16(st, gy, sh_dgrad, nullptr, relu_out, dx, N, H, W, Cout, Cin, 0))
+  if (conv_bf16_uses_halo(N, H, W, Cout, Cin, k)) {
+    conv3x3_halo_bf16(st, gy, sh_dgrad, nullptr, relu_out, dx, N, H, W, Cout, Cin, 0);
     return;
+  }
   GemmArgs g = {};
   g.gmul = relu_out;
   g.gmul_relu = 1;

@@ -12,9 +12,10 @@ typedef unsigned short bf16_t;
 
 // ---- weight copies (refreshed by the optimizer step from the fp32 master weights)
 // conv: master [Cout][Cin][k][k] -> fwd operand [Cout][tap][Cin] and input-gradient operand
-// [Cin][tap'][Cout] with tap' the point-reflected tap.
+// [Cin][tap'][Cout] with tap' the point-reflected tap.  With tiled_fwd / tiled_dgrad the copy is
+// laid out for the LDS-halo kernel instead: [Cin/64][tap][Cout][64] / [Cout/64][tap'][Cin][64].
 void conv_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh_fwd, bf16_t* sh_dgrad, int Cout,
-                             int Cin, int k);
+                             int Cin, int k, bool tiled_fwd, bool tiled_dgrad);
 // linear: master [Cout][Cin] -> copy [Cout][Cin] and transpose [Cin][Cout]
 void linear_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh, bf16_t* sh_t, int Cout,
                                int Cin);
@@ -29,11 +30,14 @@ void conv_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh_fwd, const 
 void conv_bf16_dgrad(hipStream_t st, const bf16_t* g, const bf16_t* sh_dgrad, bf16_t* dx, const bf16_t* relu_out,
                      int N, int H, int W, int Cin, int Cout, int k);
 // The same 3x3 product with the input tile and its halo staged in LDS once per 64-channel slice
-// (conv_bf16_halo.hip); conv_bf16_fwd / conv_bf16_dgrad use it for the shapes it supports.
-// w is [Cout][tap][Cin]; the output is zeroed where mask <= 0 (mask may be NULL).  Returns false,
-// with nothing launched, if the device refuses the kernel's LDS size.
+// (conv_bf16_halo.hip).  conv_bf16_uses_halo(N, H, W, Cin, Cout, k): conv_bf16_fwd takes that
+// kernel for this shape and expects the tiled weight copy [Cin/64][tap][Cout][64]; the input
+// gradient asks with Cin and Cout exchanged.  The answer is fixed for the life of the process
+// (it needs a device: the kernel's LDS size has to be granted).
+// conv3x3_halo_bf16: act is 0 or ReLU; the output is zeroed where mask <= 0 (mask may be NULL).
+bool conv_bf16_uses_halo(int N, int H, int W, int Cin, int Cout, int k);
 bool conv3x3_halo_supported(int N, int H, int W, int Cin, int Cout);
-bool conv3x3_halo_bf16(hipStream_t st, const bf16_t* x, const bf16_t* w, const float* bias, const bf16_t* mask,
+void conv3x3_halo_bf16(hipStream_t st, const bf16_t* x, const bf16_t* w, const float* bias, const bf16_t* mask,
                        bf16_t* y, int N, int H, int W, int Cin, int Cout, int act);
 // Scratch layout of a weight-gradient call: `splits` partial copies of the weight gradient at
 // ws[0, ...), `bias_parts` partial bias gradients ([bias_parts][Cout]) from float offset bias_off.

@@ -36,8 +36,8 @@ __device__ __forceinline__ float gelu_val(float x) { return 0.5f * x * (1.f + er
 
 // ------------------------------------------------------------------ weight copies
 __global__ void conv_shadow_kernel(const float* __restrict__ w, bf16_t* __restrict__ fwd,
-                                   bf16_t* __restrict__ dgr, int Cout, int Cin, int kk) {
-  // master [co][ci][t]; fwd [co][t][ci]; dgrad [ci][kk-1-t][co]
+                                   bf16_t* __restrict__ dgr, int Cout, int Cin, int kk, int tiled_fwd, int tiled_dgrad) {
+  // master [co][ci][t]; fwd [co][t][ci]; dgrad [ci][kk-1-t][co]; tiled: [slice of 64][tap][row][64]
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t total = (size_t)Cout * Cin * kk;
   if (i >= total) return;
@@ -46,13 +46,16 @@ __global__ void conv_shadow_kernel(const float* __restrict__ w, bf16_t* __restri
   int ci = (int)(r % Cin);
   int co = (int)(r / Cin);
   bf16_t v = f2bf(w[i]);
-  fwd[((size_t)co * kk + t) * Cin + ci] = v;
-  dgr[((size_t)ci * kk + (kk - 1 - t)) * Cout + co] = v;
+  if (tiled_fwd) fwd[(((size_t)(ci >> 6) * kk + t) * Cout + co) * 64 + (ci & 63)] = v;
+  else fwd[((size_t)co * kk + t) * Cin + ci] = v;
+  if (tiled_dgrad) dgr[(((size_t)(co >> 6) * kk + (kk - 1 - t)) * Cin + ci) * 64 + (co & 63)] = v;
+  else dgr[((size_t)ci * kk + (kk - 1 - t)) * Cout + co] = v;
 }
 void conv_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh_fwd, bf16_t* sh_dgrad, int Cout, int Cin,
-                             int k) {
+                             int k, bool tiled_fwd, bool tiled_dgrad) {
   size_t total = (size_t)Cout * Cin * k * k;
-  KLAUNCH(conv_shadow_kernel, dim3(cdivu(total, 256)), dim3(256), 0, st, w, sh_fwd, sh_dgrad, Cout, Cin, k * k);
+  KLAUNCH(conv_shadow_kernel, dim3(cdivu(total, 256)), dim3(256), 0, st, w, sh_fwd, sh_dgrad, Cout, Cin, k * k,
+          tiled_fwd ? 1 : 0, tiled_dgrad ? 1 : 0);
 }
 
 __global__ void linear_shadow_kernel(const float* __restrict__ w, bf16_t* __restrict__ sh,
