@@ -836,14 +836,28 @@ void set_geometry(GemmArgs& g, int H, int W, int C, int k) {
 }  // namespace
 
 // ------------------------------------------------------------------ public launchers
+// experiment switch: ASTEROID_WGRAD_TR=0 keeps the conv weight gradients on the generic kernel
+static bool conv_wgrad_uses_tr(int N, int H, int W, int Cin, int Cout, int k) {
+  static const bool on = env_int("ASTEROID_WGRAD_TR") != 0;
+  return on && conv_wgrad_tr_supported(N, H, W, Cin, Cout, k);
+}
+// floats of weight-gradient partials: room for whichever kernel runs (the choice needs a device,
+// the size must not)
+static size_t conv_wgrad_part_floats(int N, int H, int W, int Cin, int Cout, int k) {
+  const long P = (long)N * H * W;
+  const size_t a = wgrad_ws_floats(Cout, Cin, P, k * k);
+  const size_t b = (size_t)conv_wgrad_tr_splits(P, Cin, Cout, k * k) * k * k * Cout * Cin;
+  return a > b ? a : b;
+}
 size_t conv_bf16_ws_bytes(int N, int H, int W, int Cin, int Cout, int k) {
-  return (align64f(wgrad_ws_floats(Cout, Cin, (long)N * H * W, k * k)) + colsum_ws_floats(Cout)) * sizeof(float) + 256;
+  return (align64f(conv_wgrad_part_floats(N, H, W, Cin, Cout, k)) + colsum_ws_floats(Cout)) * sizeof(float) + 256;
 }
 WgradParts conv_bf16_wgrad_parts(int N, int H, int W, int Cin, int Cout, int k) {
   WgradParts p;
-  p.splits = wgrad_splits(Cout, Cin, (long)N * H * W, k * k);
-  p.bias_off = align64f(wgrad_ws_floats(Cout, Cin, (long)N * H * W, k * k));
-  p.bias_parts = (int)colsum_shape((long)N * H * W, Cout).blocks;
+  p.splits = conv_wgrad_uses_tr(N, H, W, Cin, Cout, k) ? conv_wgrad_tr_splits((long)N * H * W, Cin, Cout, k * k)
+                                                      : wgrad_splits(Cout, Cin, (long)N * H * W, k * k);
+  p.bias_off = align64f(conv_wgrad_part_floats(N, H, W, Cin, Cout, k));
+  p.bias_parts = conv_wgrad_uses_tr(N, H, W, Cin, Cout, k) ? p.splits : (int)colsum_shape((long)N * H * W, Cout).blocks;
   return p;
 }
 
@@ -888,15 +902,28 @@ void conv_bf16_dgrad(hipStream_t st, const bf16_t* gy, const bf16_t* sh_dgrad, b
 
 void conv_bf16_wgrad(hipStream_t st, const bf16_t* gy, const bf16_t* x, float* GW, float* Gb, bool has_bias,
                      bool defer, void* ws, int N, int H, int W, int Cin, int Cout, int k) {
-  GemmArgs g = {};
-  g.A = gy; g.B = x;
-  g.M = Cout; g.N = Cin; g.K = (long)N * H * W;
-  g.lda = Cout; g.ldb = Cin;
-  set_geometry(g, H, W, Cin, k);
-  launch_wgrad<B_T_SHIFT>(st, g, defer ? nullptr : GW, reinterpret_cast<float*>(ws), k * k);
+  if (conv_wgrad_uses_tr(N, H, W, Cin, Cout, k)) {  // the bias gradient's partials come from the same launch
+    float* bias_ws = reinterpret_cast<float*>(ws) + align64f(conv_wgrad_part_floats(N, H, W, Cin, Cout, k));
+    const int splits = conv_wgrad_tr_splits((long)N * H * W, Cin, Cout, k * k);
+    conv_wgrad_tr_bf16(st, gy, x, reinterpret_cast<float*>(ws), has_bias ? bias_ws : nullptr, N, H, W, Cin, Cout, k);
+    if (!defer) {
+      const long total = (long)k * k * Cout * Cin;
+      KLAUNCH(reduce_wgrad_kernel, dim3((unsigned)cdivl(total, 64)), dim3(256), 0, st, reinterpret_cast<const float*>(ws), GW,
+              (long)Cout, (long)Cin, k * k, splits);
+      if (has_bias) KLAUNCH(colsum_final_kernel, dim3((unsigned)cdivl(Cout, 16)), dim3(256), 0, st, bias_ws, Gb, Cout, splits);
+    }
+    return;
+  } else {
+    GemmArgs g = {};
+    g.A = gy; g.B = x;
+    g.M = Cout; g.N = Cin; g.K = (long)N * H * W;
+    g.lda = Cout; g.ldb = Cin;
+    set_geometry(g, H, W, Cin, k);
+    launch_wgrad<B_T_SHIFT>(st, g, defer ? nullptr : GW, reinterpret_cast<float*>(ws), k * k);
+  }
   if (has_bias)
     launch_colsum(st, gy, defer ? nullptr : Gb,
-                  reinterpret_cast<float*>(ws) + align64f(wgrad_ws_floats(Cout, Cin, (long)N * H * W, k * k)),
+                  reinterpret_cast<float*>(ws) + align64f(conv_wgrad_part_floats(N, H, W, Cin, Cout, k)),
                   (long)N * H * W, Cout);
 }
 

@@ -39,6 +39,14 @@ bool conv_bf16_uses_halo(int N, int H, int W, int Cin, int Cout, int k);
 bool conv3x3_halo_supported(int N, int H, int W, int Cin, int Cout);
 void conv3x3_halo_bf16(hipStream_t st, const bf16_t* x, const bf16_t* w, const float* bias, const bf16_t* mask,
                        bf16_t* y, int N, int H, int W, int Cin, int Cout, int act);
+// Weight gradient with both operands read transposed from LDS (conv_bf16_wgrad.hip): partials
+// part[split][tap][Cout][Cin], conv_wgrad_tr_splits() of them (a function of the shape alone), and,
+// with bias_part, the splits' column sums of dy [split][Cout] (the bias gradient's partials).
+// conv_bf16_wgrad uses it where conv_wgrad_tr_supported() (needs a device: LDS size granted).
+int conv_wgrad_tr_splits(long P, int Cin, int Cout, int taps);
+bool conv_wgrad_tr_supported(int N, int H, int W, int Cin, int Cout, int k);
+void conv_wgrad_tr_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* x, float* part, float* bias_part, int N, int H,
+                        int W, int Cin, int Cout, int k);
 // Scratch layout of a weight-gradient call: `splits` partial copies of the weight gradient at
 // ws[0, ...), `bias_parts` partial bias gradients ([bias_parts][Cout]) from float offset bias_off.
 struct WgradParts { int splits; size_t bias_off; int bias_parts; };
