@@ -138,6 +138,19 @@ ast_status asteroid_stage_forward(asteroid_stage* s, int32_t mb, const void* x_d
 ast_status asteroid_stage_backward(asteroid_stage* s, int32_t mb, const void* dy_dev,
                                    void* dx_dev);
 
+/* For callers that cannot allocate or let a library allocate on their behalf (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): asteroid_stage_backward with the
+ * stage's workspace - activation gradients, per-operator scratch, reduction partials - taken from
+ * a file-scope device array of AST_STATIC_SCRATCH_BYTES instead of the memory the stage allocated
+ * at create.  Same arguments, same results (bit-identical), same AST_ESTATE rules; the call itself
+ * allocates nothing and records no memset (the array's used part is cleared by a kernel).
+ * AST_EINVAL if the stage's workspace (asteroid_stage_memory) is larger than the array.  Every GPU
+ * the library runs on holds one such array until the process ends, and all stages on that GPU
+ * share it: calls that overlap in time on one GPU race; calls on one stream do not. */
+#define AST_STATIC_SCRATCH_BYTES (32u << 20)
+ast_status asteroid_stage_backward_static(asteroid_stage* s, int32_t mb, const void* dy_dev,
+                                          void* dx_dev);
+
 /* Weight update at the end of the HPP-Round (Sec. 3.2): v = momentum*v + G;
  * W = W - lr*v; G = 0; reduced-precision weight copies are refreshed.
  * AST_ESTATE unless all M micro-batches have been forwarded and backwarded. */

@@ -55,6 +55,7 @@ def load_library():
     lib.asteroid_stage_create.argtypes = [C.POINTER(ast_layer), i32, C.POINTER(ast_stage_cfg), vp, C.POINTER(vp)]
     lib.asteroid_stage_forward.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.asteroid_stage_backward.argtypes = [vp, i32, vp, vp]
+    lib.asteroid_stage_backward_static.argtypes = [vp, i32, vp, vp]
     lib.asteroid_stage_step.argtypes = [vp, C.c_float, C.c_float]
     lib.asteroid_stage_destroy.argtypes = [vp]
     lib.asteroid_stage_destroy.restype = None
@@ -161,6 +162,9 @@ class Stage:
 
     def backward(self, mb, dy=None, dx=None):
         _check(self.lib, self.lib.asteroid_stage_backward(self.h, mb, _ptr(dy), _ptr(dx)))
+
+    def backward_static(self, mb, dy=None, dx=None):
+        _check(self.lib, self.lib.asteroid_stage_backward_static(self.h, mb, _ptr(dy), _ptr(dx)))
 
     def step(self, lr, momentum):
         _check(self.lib, self.lib.asteroid_stage_step(self.h, lr, momentum))

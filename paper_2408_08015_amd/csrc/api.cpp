@@ -65,6 +65,8 @@ void free_stage(ast::Stage& s) {
   s.pack_block_task = nullptr;
   s.pack_nblocks = 0;
   if (s.red_tasks) (void)hipFree(s.red_tasks);
+  if (s.red_tasks_static) (void)hipFree(s.red_tasks_static);
+  s.red_tasks_static = nullptr;
   if (s.red_block_task) (void)hipFree(s.red_block_task);
   s.red_tasks = nullptr;
   s.red_block_task = nullptr;
@@ -213,7 +215,7 @@ ast_status asteroid_stage_forward(asteroid_stage* h, int32_t mb, const void* x_d
   return AST_OK;
 }
 
-ast_status asteroid_stage_backward(asteroid_stage* h, int32_t mb, const void* dy_dev, void* dx_dev) {
+static ast_status backward_impl(asteroid_stage* h, int32_t mb, const void* dy_dev, void* dx_dev, bool use_static) {
   if (!h) return fail(AST_EINVAL, "backward: NULL stage");
   ast::Stage& s = h->s;
   if (mb < 0 || mb >= s.cfg.M) return fail(AST_ESTATE, "backward: micro-batch index outside [0, M)");
@@ -224,15 +226,29 @@ ast_status asteroid_stage_backward(asteroid_stage* h, int32_t mb, const void* dy
   if (s.cfg.needs_input_grad && !dx_dev) return fail(AST_EINVAL, "backward: dx_dev is NULL");
   if (!s.cfg.needs_input_grad && dx_dev) return fail(AST_EINVAL, "backward: dx_dev must be NULL when needs_input_grad == 0");
   if (!aligned16(dy_dev) || !aligned16(dx_dev)) return fail(AST_EINVAL, "backward: buffers must be 16-byte aligned");
+  if (use_static) {
+    if (s.ws_bytes > (size_t)AST_STATIC_SCRATCH_BYTES)
+      return fail(AST_EINVAL, "backward_static: the stage's workspace (" + std::to_string(s.ws_bytes) +
+                                  " bytes) exceeds AST_STATIC_SCRATCH_BYTES (" + std::to_string((size_t)AST_STATIC_SCRATCH_BYTES) + ")");
+    if (!s.static_ws) return fail(AST_EHIP, "backward_static: the static workspace of this device could not be located at create");
+  }
   int slot = s.mb_slot[mb];
   std::string err;
   ProfGuard pg(h);
-  ast_status r = ast::run_backward(s, slot, dy_dev, dx_dev, err);
+  ast_status r = ast::run_backward(s, slot, dy_dev, dx_dev, use_static ? s.static_ws : nullptr, err);
   if (r != AST_OK) return fail(r, err);
   s.mb_slot[mb] = -1;
   s.free_slots.push_back(slot);  // the backward releases the stash
   s.next_bwd++;
   return AST_OK;
+}
+
+ast_status asteroid_stage_backward(asteroid_stage* h, int32_t mb, const void* dy_dev, void* dx_dev) {
+  return backward_impl(h, mb, dy_dev, dx_dev, false);
+}
+
+ast_status asteroid_stage_backward_static(asteroid_stage* h, int32_t mb, const void* dy_dev, void* dx_dev) {
+  return backward_impl(h, mb, dy_dev, dx_dev, true);
 }
 
 ast_status asteroid_stage_step(asteroid_stage* h, float lr, float momentum) {

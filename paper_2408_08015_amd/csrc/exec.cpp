@@ -7,6 +7,7 @@
 #include "kernels.h"
 #include "kernels_bf16.h"
 #include "stage.h"
+#include "static_scratch.h"
 
 namespace ast {
 
@@ -16,6 +17,7 @@ struct Ctx {
   Stage& s;
   char* slot;
   int final_act;
+  char* ws;  // workspace of this call: the stage's own, or the static array (backward_static)
   bool forked = false;
 };
 
@@ -29,9 +31,9 @@ inline void* grad_ptr(Ctx& c, int id) {
   while (c.s.acts[id].grad_alias >= 0) id = c.s.acts[id].grad_alias;
   if (id == 0) return c.s.cur_dx;  // may be NULL: the input gradient is not wanted
   if (id == c.final_act && !c.s.loss_tail) return const_cast<void*>(c.s.cur_dy);  // id != 0 here
-  return c.s.ws + c.s.acts[id].grad_off;
+  return c.ws + c.s.acts[id].grad_off;
 }
-inline char* scratch(Ctx& c, const Op& op) { return c.s.ws + c.s.scratch_off + op.sc_off; }
+inline char* scratch(Ctx& c, const Op& op) { return c.ws + c.s.scratch_off + op.sc_off; }
 // Stream for a weight-gradient kernel.  Nothing later in the same backward pass reads a
 // parameter gradient, so these kernels leave the dependency chain: they run on the stage's
 // second stream, ordered after all work enqueued so far on the main stream, and the pass
@@ -462,7 +464,7 @@ ast_status check_launch(std::string& err, const char* what) {
 
 ast_status run_forward(Stage& s, int slot, const void* x, const int32_t* labels, void* y, float* loss,
                        std::string& err) {
-  Ctx c{s, s.slots[slot], final_act_of(s)};
+  Ctx c{s, s.slots[slot], final_act_of(s), s.ws};
   s.cur_y = y;
   s.cur_dy = nullptr;
   s.cur_dx = nullptr;
@@ -473,14 +475,16 @@ ast_status run_forward(Stage& s, int slot, const void* x, const int32_t* labels,
   return check_launch(err, "forward");
 }
 
-ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, std::string& err) {
-  Ctx c{s, s.slots[slot], final_act_of(s)};
+ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, char* static_ws, std::string& err) {
+  Ctx c{s, s.slots[slot], final_act_of(s), static_ws ? static_ws : s.ws};
+  if (static_ws) static_scratch_zero(s.stream, static_ws, s.ws_bytes);  // what the stage's own workspace was at create
   s.cur_y = nullptr;
   s.cur_dy = dy;
   s.cur_dx = dx;
   for (int j = (int)s.ops.size() - 1; j >= 0; --j) bwd_op(c, s.ops[j]);
   if (s.red_nblocks)  // every layer's partials -> G, one launch (behind all of this pass's kernels)
-    reduce_tasks_f32(fork_side(c), static_cast<const RedTask*>(s.red_tasks), s.red_block_task, s.red_nblocks);
+    reduce_tasks_f32(fork_side(c), static_cast<const RedTask*>(static_ws ? s.red_tasks_static : s.red_tasks), s.red_block_task,
+                     s.red_nblocks);
   if (c.forked) {  // join: whatever follows on the main stream sees every gradient
     (void)hipEventRecord(s.join_ev, s.side);
     (void)hipStreamWaitEvent(s.stream, s.join_ev, 0);
@@ -536,8 +540,18 @@ static ast_status build_pack_tasks(Stage& s, std::string& err) {
 
 ast_status build_reduce_tasks(Stage& s, std::string& err) {
   if (ast_status r = build_pack_tasks(s, err)) return r;
+  char* static_ws = nullptr;
+  if (s.ws_bytes <= kStaticScratchBytes) {
+    std::string ignore;
+    (void)static_scratch_ptr(&static_ws, ignore);  // no static variant for this stage if this fails
+  }
+  s.static_ws = static_ws;
   if (const char* e = getenv("ASTEROID_BATCHED_REDUCE"))
     if (e[0] == '0') return AST_OK;  // per-layer reduction launches instead
+  // the table holds absolute addresses of the partials: one table per workspace the backward
+  // may run in (the stage's own; the static array, if the stage fits into it)
+  for (int pass = 0; pass < (static_ws ? 2 : 1); ++pass) {
+  char* const ws_base = pass == 0 ? s.ws : static_ws;
   std::vector<RedTask> tasks;
   std::vector<unsigned short> block_task;
   bool overflow = false;
@@ -561,7 +575,7 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
   };
   for (const Op& op : s.ops) {
     const Act& I = s.acts[op.in];
-    char* sc = s.ws + s.scratch_off + op.sc_off;
+    char* sc = ws_base + s.scratch_off + op.sc_off;
     float* scf = reinterpret_cast<float*>(sc);
     switch (op.kind) {
       case OP_CONV_PW: {
@@ -617,15 +631,18 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
   }
   if (tasks.empty() || overflow) return AST_OK;  // (absurdly long stage: per-layer launches)
   hipError_t e;
-  if ((e = hipMalloc(&s.red_tasks, tasks.size() * sizeof(RedTask))) != hipSuccess ||
-      (e = hipMalloc((void**)&s.red_block_task, block_task.size() * sizeof(unsigned short))) != hipSuccess ||
-      (e = hipMemcpy(s.red_tasks, tasks.data(), tasks.size() * sizeof(RedTask), hipMemcpyHostToDevice)) != hipSuccess ||
-      (e = hipMemcpy(s.red_block_task, block_task.data(), block_task.size() * sizeof(unsigned short),
-                     hipMemcpyHostToDevice)) != hipSuccess) {
+  void** table = pass == 0 ? &s.red_tasks : &s.red_tasks_static;
+  if ((e = hipMalloc(table, tasks.size() * sizeof(RedTask))) != hipSuccess ||
+      (e = hipMemcpy(*table, tasks.data(), tasks.size() * sizeof(RedTask), hipMemcpyHostToDevice)) != hipSuccess ||
+      (pass == 0 &&
+       ((e = hipMalloc((void**)&s.red_block_task, block_task.size() * sizeof(unsigned short))) != hipSuccess ||
+        (e = hipMemcpy(s.red_block_task, block_task.data(), block_task.size() * sizeof(unsigned short),
+                       hipMemcpyHostToDevice)) != hipSuccess))) {
     err = std::string("reduction task table: ") + hipGetErrorString(e);
     return e == hipErrorOutOfMemory ? AST_ENOMEM : AST_EHIP;
   }
-  s.red_nblocks = (int)block_task.size();
+  if (pass == 0) s.red_nblocks = (int)block_task.size();
+  }
   return AST_OK;
 }
 

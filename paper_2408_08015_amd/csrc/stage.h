@@ -129,6 +129,8 @@ struct Stage {
   unsigned short* pack_block_task = nullptr;
   int pack_nblocks = 0;
   void* red_tasks = nullptr;             // RedTask[]
+  void* red_tasks_static = nullptr;      // the same table with the partials' addresses in the static workspace
+  char* static_ws = nullptr;             // this device's static workspace, if the stage fits into it
   unsigned short* red_block_task = nullptr;
   int red_nblocks = 0;
 
@@ -156,7 +158,7 @@ ast_status build_plan(Stage& s, std::string& err);
 // exec.cpp
 ast_status run_forward(Stage& s, int slot, const void* x, const int32_t* labels, void* y, float* loss,
                        std::string& err);
-ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, std::string& err);
+ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, char* static_ws, std::string& err);
 ast_status run_step(Stage& s, float lr, float mu, std::string& err);
 ast_status refresh_shadow(Stage& s, std::string& err);
 ast_status build_reduce_tasks(Stage& s, std::string& err);  // after the workspace is allocated

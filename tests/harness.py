@@ -41,9 +41,10 @@ def run_oracle(cfg, inp, K=1, rounds=2, keep_acts=False):
     return res, st
 
 
-def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None):
+def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None, static_backward=False):
     """Returns the per-round results of the HIP stage (numpy fp32) and, if asked, the
-    activations of `debug_layers` for micro-batch 0 of round 0."""
+    activations of `debug_layers` for micro-batch 0 of round 0.  static_backward: the backward
+    passes go through asteroid_stage_backward_static."""
     import torch
     import paper_2408_08015_amd as A
     dev = torch.device("cuda:0")
@@ -83,7 +84,8 @@ def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None):
         for m in range(min(K, M)):
             fwd(m, r)
         for m in range(M):
-            st.backward(m, dys[m] if dys is not None else None, dxs[m] if dxs is not None else None)
+            (st.backward_static if static_backward else st.backward)(
+                m, dys[m] if dys is not None else None, dxs[m] if dxs is not None else None)
             if m + K < M:
                 fwd(m + K, r)
         torch.cuda.synchronize()
