@@ -71,6 +71,13 @@ void free_stage(ast::Stage& s) {
   s.red_tasks = nullptr;
   s.red_block_task = nullptr;
   s.red_nblocks = 0;
+  for (ast::Stage::WgGroup& wg : s.wg_groups) {
+    if (wg.tasks) (void)hipFree(wg.tasks);
+    if (wg.block_task) (void)hipFree(wg.block_task);
+    if (wg.task_block0) (void)hipFree(wg.task_block0);
+  }
+  s.wg_groups.clear();
+  s.wg_nblocks = 0;
   if (s.wpack) (void)hipFree(s.wpack);
   s.wpack = nullptr;
   if (s.ws) (void)hipFree(s.ws);

@@ -40,6 +40,9 @@
 #ifndef HALO_STAMP
 #define HALO_STAMP(k)
 #endif
+#ifndef HALO_STAMP2
+#define HALO_STAMP2(k)
+#endif
 
 namespace ast {
 
@@ -320,10 +323,12 @@ __device__ __forceinline__ void conv3x3_halo_body(const HaloArgs& g) {
       for (int k = 0; k < 4; ++k) mk[0][k] = __builtin_amdgcn_raw_buffer_load_b128(rmask, out_off(0, k), 0, 0);
     }
     lds_barrier();  // bias in LDS
+    HALO_STAMP2(0);
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       const int i = p / (TN / 2), jh = p % (TN / 2);
       if (p > 0) lds_barrier();  // the previous pass has been read
+      HALO_STAMP2(1 + 3 * p);
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const int j = 2 * jh + jj;
@@ -335,12 +340,13 @@ __device__ __forceinline__ void conv3x3_halo_body(const HaloArgs& g) {
           float v2 = acc[j][i][4 * r4 + 2] + bv.z, v3 = acc[j][i][4 * r4 + 3] + bv.w;
           if (g.act == ACT_RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
           uint2 pk;
-          pk.x = (uint32_t)f2bf(v0) | ((uint32_t)f2bf(v1) << 16);
-          pk.y = (uint32_t)f2bf(v2) | ((uint32_t)f2bf(v3) << 16);
+          pk.x = f2bf_pk(v0, v1);
+          pk.y = f2bf_pk(v2, v3);
           *reinterpret_cast<uint2*>(scratch + (wm * 32 + lrow) * HALO_CP + wn * 128 + jj * 64 + c4 * 2) = pk;
         }
       }
       lds_barrier();
+      HALO_STAMP2(2 + 3 * p);
       if (g.mask && p + 1 < NP) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) mk[(p + 1) & 1][k] = __builtin_amdgcn_raw_buffer_load_b128(rmask, out_off(p + 1, k), 0, 0);
@@ -360,6 +366,7 @@ __device__ __forceinline__ void conv3x3_halo_body(const HaloArgs& g) {
         }
         __builtin_amdgcn_raw_buffer_store_b128(v, ry, out_off(p, k), 0, 0);
       }
+      HALO_STAMP2(3 + 3 * p);
     }
   };
 

@@ -32,6 +32,8 @@ struct WgArgs {
   const bf16_t* x;   // [P][Cin]
   float* part;       // [splits][taps][Cout][Cin]
   float* bias_part;  // [splits][Cout] or NULL: column sums of dy (the bias gradient) per split
+  float* acc_out;    // grouped launches (one split): [Cout][Cin] that the product is ADDED to, instead of `part`
+  float* bias_acc;   // ... and [Cout] that the column sums of dy are added to (or NULL)
   int P, H, W, Cout, Cin;
   int taps;          // 9 (3x3) or 1
   int k_per_split;   // pixels per split, a multiple of the K-tile
@@ -69,7 +71,7 @@ __device__ __forceinline__ bf16x8 wg_read_tr(const unsigned char* smem, int off)
 }
 
 template <int TN>  // block: 256 output channels x 64*TN input channels; wavefront tile 64 x 32*TN
-__device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g) {
+__device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  // bid: block of this product
   constexpr int NCI = 64 * TN;                       // input channels per block
   constexpr int BPITCH = NCI * 2;                    // bytes per pixel row of the x tile
   constexpr int B_BYTES = TN == 4 ? WG_BK * 512 : 16 * 1024;  // TN == 2: 12 KB of rows + 4 KB never read
@@ -81,7 +83,6 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int lrow = lane & 31, lgrp = lane >> 5;
-  int bid = (int)xcd_grouped(blockIdx.x, gridDim.x);
   const int tile_n = bid % g.tiles_n; bid /= g.tiles_n;
   const int tile_m = bid % g.tiles_m; bid /= g.tiles_m;
   const int tap = bid % g.taps, split = bid / g.taps;
@@ -173,7 +174,7 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g) {
   // Bias gradient = column sums of dy: the blocks of the centre tap (first input-channel tile)
   // add up the dy tile they hold in LDS anyway.  Thread -> one 16-byte chunk (8 channels) of three
   // pixel rows per K-tile; the 16 row groups are added in a fixed order at the end.
-  const bool do_bias = g.bias_part != nullptr && tap == (g.taps == 9 ? 4 : 0) && tile_n == 0;
+  const bool do_bias = (g.bias_part != nullptr || g.bias_acc != nullptr) && tap == (g.taps == 9 ? 4 : 0) && tile_n == 0;
   float bsum[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) bsum[e] = 0.f;
@@ -279,28 +280,53 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g) {
       float t = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) t += sb[r * 256 + tid];
-      g.bias_part[(size_t)split * g.Cout + co0 + tid] = t;
+      if (g.bias_acc) g.bias_acc[co0 + tid] += t;  // (this block alone owns these channels)
+      else g.bias_part[(size_t)split * g.Cout + co0 + tid] = t;
     }
   }
 
   // ---- the partial: accumulator register r of lane l is D[8*(r/4) + 4*(l/32) + r%4][l%32]
-  float* out = g.part + ((size_t)(split * g.taps + tap) * g.Cout) * g.Cin;
+  const bool accumulate = g.acc_out != nullptr;  // every output entry belongs to this block alone: a plain add
+  float* out = accumulate ? g.acc_out : g.part + ((size_t)(split * g.taps + tap) * g.Cout) * g.Cin;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int ci = ci0 + wn * (32 * TN) + j * 32 + lrow;
       if (ci >= g.Cin) continue;
+      float old[16];
+      if (accumulate) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int co = co0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
+          old[r] = co < g.Cout ? out[(size_t)co * g.Cin + ci] : 0.f;
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int co = co0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
-        if (co < g.Cout) out[(size_t)co * g.Cin + ci] = acc[i][j][r];
+        if (co < g.Cout) out[(size_t)co * g.Cin + ci] = accumulate ? old[r] + acc[i][j][r] : acc[i][j][r];
       }
     }
 }
 
-__global__ __launch_bounds__(512) void conv_wgrad_tr_kernel_n256(WgArgs g) { conv_wgrad_tr_body<4>(g); }
-__global__ __launch_bounds__(512) void conv_wgrad_tr_kernel_n128(WgArgs g) { conv_wgrad_tr_body<2>(g); }
+__global__ __launch_bounds__(512) void conv_wgrad_tr_kernel_n256(WgArgs g) {
+  conv_wgrad_tr_body<4>(g, (int)xcd_grouped(blockIdx.x, gridDim.x));
+}
+__global__ __launch_bounds__(512) void conv_wgrad_tr_kernel_n128(WgArgs g) {
+  conv_wgrad_tr_body<2>(g, (int)xcd_grouped(blockIdx.x, gridDim.x));
+}
+// Many products in one launch (the weight gradients of all linear layers of a stage: nothing later in
+// a backward pass depends on them): block -> (product, block of that product) through a table;
+// every product runs unsplit and adds its result straight into the gradient arena.
+__global__ __launch_bounds__(512) void wgrad_grouped_kernel(const WgArgs* __restrict__ tasks,
+                                                            const unsigned short* __restrict__ block_task,
+                                                            const unsigned* __restrict__ task_block0, int block_base) {
+  const int b = block_base + (int)blockIdx.x;  // (a launch may cover a sub-range of the table's blocks)
+  const int t = block_task[b];
+  const WgArgs g = tasks[t];
+  conv_wgrad_tr_body<4>(g, b - (int)task_block0[t]);
+}
 
 constexpr size_t wg_lds_bytes(int tn) { return 3 * (size_t)(WG_A_BYTES + (tn == 4 ? WG_BK * 512 : 16 * 1024)); }
 
@@ -309,6 +335,8 @@ bool wg_attr_ok() {
   if (ok < 0) {
     ok = hipFuncSetAttribute((const void*)conv_wgrad_tr_kernel_n256, hipFuncAttributeMaxDynamicSharedMemorySize,
                              (int)wg_lds_bytes(4)) == hipSuccess &&
+                 hipFuncSetAttribute((const void*)wgrad_grouped_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)wg_lds_bytes(4)) == hipSuccess &&
                  hipFuncSetAttribute((const void*)conv_wgrad_tr_kernel_n128, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)wg_lds_bytes(2)) == hipSuccess
              ? 1
@@ -365,6 +393,35 @@ void conv_wgrad_tr_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* x, float
     KLAUNCH_NAMED("conv_wgrad_tr_kernel_n128", conv_wgrad_tr_kernel_n128,
                   dim3((unsigned)(splits * g.taps * g.tiles_m * g.tiles_n)), dim3(512), wg_lds_bytes(2), st, g);
   }
+}
+
+// ---- grouped launch: descriptors are built on the host (wgrad_group_task), copied to the device by
+// the caller once, and launched as one grid.
+size_t wgrad_group_task_bytes() { return sizeof(WgArgs); }
+bool wgrad_group_supported(size_t rows, int Cin, int Cout) {
+  return Cin % 8 == 0 && Cout % 8 == 0 && rows >= (size_t)WG_BK && rows * Cin * 2 < (1ul << 31) && rows * Cout * 2 < (1ul << 31) &&
+         wg_attr_ok();
+}
+// Writes the descriptor of GW[Cout][Cin] += dy[rows][Cout]^T x[rows][Cin] (and Gb[Cout] += column sums of dy,
+// if Gb) to `task_out`; returns the number of blocks the product takes.
+int wgrad_group_task(void* task_out, const bf16_t* dy, const bf16_t* x, float* GW, float* Gb, size_t rows, int Cin, int Cout) {
+  WgArgs g = {};
+  g.dy = dy; g.x = x; g.acc_out = GW; g.bias_acc = Gb;
+  g.P = (int)rows; g.H = 1; g.W = 1; g.Cout = Cout; g.Cin = Cin;
+  g.taps = 1;
+  g.k_per_split = (int)(wg_cdiv((long)rows, WG_BK) * WG_BK);
+  g.tiles_m = (int)wg_cdiv(Cout, 256);
+  g.tiles_n = (int)wg_cdiv(Cin, 256);
+  g.step_q = 0; g.step_r = 0;   // (one tap: no pixel is ever outside the image)
+  g.x_bytes = (unsigned)(rows * Cin * 2);
+  *static_cast<WgArgs*>(task_out) = g;
+  return g.tiles_m * g.tiles_n;
+}
+void wgrad_group_launch(hipStream_t st, const void* tasks_dev, const unsigned short* block_task_dev,
+                        const unsigned* task_block0_dev, int block_base, int nblocks) {
+  if (nblocks <= 0) return;
+  KLAUNCH(wgrad_grouped_kernel, dim3((unsigned)nblocks), dim3(512), wg_lds_bytes(4), st,
+          static_cast<const WgArgs*>(tasks_dev), block_task_dev, task_block0_dev, block_base);
 }
 
 }  // namespace ast

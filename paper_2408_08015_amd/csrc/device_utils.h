@@ -101,6 +101,14 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
   return (bf16_t)(u >> 16);
 }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+// two values at once with the hardware conversion (v_cvt_pk_bf16_f32, round to nearest even: the same
+// result as f2bf for every finite value); a in the low half
+__device__ __forceinline__ uint32_t f2bf_pk(float a, float b) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float float2_t __attribute__((ext_vector_type(2)));
+  const float2_t f = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+}
 
 // Workgroups are dealt to the 8 XCDs (each with an L2 of its own) round-robin by their flat index.
 // Renumbering: XCD x gets the contiguous range of ids that starts at x*(n/8) + min(x, n%8), so

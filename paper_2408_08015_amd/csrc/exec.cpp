@@ -388,13 +388,14 @@ void bwd_op(Ctx& c, const Op& op) {
           g = gp;
         }
         sc += align256(O.bytes);
-        hipStream_t sw = fork_side(c);
+        hipStream_t sw = op.wg_grouped ? st : fork_side(c);
         if (gin)
           linear_bf16_dgrad(st, g, s.shadow + op.sh2_off, (bf16_t*)gin,
                             op.gelu_from >= 0 ? (cb)act_ptr(c, op.gelu_from) : nullptr,
                             op.dgrad_add >= 0 ? (cb)grad_ptr(c, op.dgrad_add) : nullptr, R, op.cin, op.cout);
-        linear_bf16_wgrad(sw, g, (cb)act_ptr(c, op.in), s.G + op.w_off, s.G + op.b_off, op.has_bias != 0,
-                          s.red_nblocks != 0, sc, R, op.cin, op.cout);
+        if (!op.wg_grouped)  // else: part of the grouped launch at the end of the pass
+          linear_bf16_wgrad(sw, g, (cb)act_ptr(c, op.in), s.G + op.w_off, s.G + op.b_off, op.has_bias != 0,
+                            s.red_nblocks != 0, sc, R, op.cin, op.cout);
       } else {
         cf g = (cf)grad_ptr(c, op.out);
         hipStream_t sw = fork_side(c);
@@ -437,15 +438,15 @@ void bwd_op(Ctx& c, const Op& op) {
       char* lw_q = lw_o + align256(linear_bf16_ws_bytes(R, D, D));
       const bool defer = s.red_nblocks != 0;
       cb g = (cb)grad_ptr(c, op.out);
-      hipStream_t sw = fork_side(c);
+      hipStream_t sw = op.wg_grouped ? st : fork_side(c);
       linear_bf16_dgrad(st, g, s.shadow + op.sh2_off + (size_t)3 * D * D, d_o, nullptr, nullptr, R, D, D);
-      linear_bf16_wgrad(sw, g, o, Go, Gbo, true, defer, lw_o, R, D, D);
+      if (!op.wg_grouped) linear_bf16_wgrad(sw, g, o, Go, Gbo, true, defer, lw_o, R, D, D);
       attention_bwd_bf16(st, qkv, o, d_o, lse, dqkv, dsum, I.n, I.h, D, op.heads);
-      sw = fork_side(c);
+      if (!op.wg_grouped) sw = fork_side(c);
       if (gin)
         linear_bf16_dgrad(st, dqkv, s.shadow + op.sh2_off, (bf16_t*)gin, nullptr,
                           op.dgrad_add >= 0 ? (cb)grad_ptr(c, op.dgrad_add) : nullptr, R, D, 3 * D);
-      linear_bf16_wgrad(sw, dqkv, (cb)act_ptr(c, op.in), Gq, Gbq, true, defer, lw_q, R, D, 3 * D);
+      if (!op.wg_grouped) linear_bf16_wgrad(sw, dqkv, (cb)act_ptr(c, op.in), Gq, Gbq, true, defer, lw_q, R, D, 3 * D);
       break;
     }
   }
@@ -481,7 +482,17 @@ ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, char* stat
   s.cur_y = nullptr;
   s.cur_dy = dy;
   s.cur_dx = dx;
-  for (int j = (int)s.ops.size() - 1; j >= 0; --j) bwd_op(c, s.ops[j]);
+  // the weight (and bias) gradients of all grouped linear layers: two launches on the second stream, each
+  // adding its products into G (every entry of G belongs to one block of one launch)
+  const Stage::WgGroup* wg = s.wg_nblocks ? &s.wg_groups[2 * slot + (static_ws ? 1 : 0)] : nullptr;
+  for (int j = (int)s.ops.size() - 1; j >= 0; --j) {
+    bwd_op(c, s.ops[j]);
+    if (wg && j == s.wg_split_op)
+      wgrad_group_launch(fork_side(c), wg->tasks, wg->block_task, wg->task_block0, 0, s.wg_first_blocks);
+  }
+  if (wg)
+    wgrad_group_launch(fork_side(c), wg->tasks, wg->block_task, wg->task_block0, s.wg_first_blocks,
+                       s.wg_nblocks - s.wg_first_blocks);
   if (s.red_nblocks)  // every layer's partials -> G, one launch (behind all of this pass's kernels)
     reduce_tasks_f32(fork_side(c), static_cast<const RedTask*>(static_ws ? s.red_tasks_static : s.red_tasks), s.red_block_task,
                      s.red_nblocks);
@@ -538,6 +549,112 @@ static ast_status build_pack_tasks(Stage& s, std::string& err) {
   return AST_OK;
 }
 
+// Grouped weight gradients (bf16 stages): every linear layer and attention projection whose operands lie
+// in the stash and the workspace (i.e. not in a buffer of the caller) becomes one product of a single
+// launch at the end of the backward pass.  ASTEROID_WGRAD_GROUP=0 keeps the per-layer launches.
+static ast_status build_wgrad_groups(Stage& s, char* static_ws, std::string& err) {
+  if (!s.bf16) return AST_OK;
+  if (const char* e = getenv("ASTEROID_WGRAD_GROUP"))
+    if (e[0] == '0') return AST_OK;
+  // addresses as forward / backward will compute them, or NULL where they depend on the call
+  auto act_at = [&](char* slot, int id) -> char* {
+    if (id == s.final_act && !s.loss_tail && id != 0 && !s.final_in_slot) return nullptr;  // the caller's y
+    return slot + s.acts[id].slot_off;
+  };
+  auto grad_at = [&](char* ws, int id) -> char* {
+    while (s.acts[id].grad_alias >= 0) id = s.acts[id].grad_alias;
+    if (id == 0 || (id == s.final_act && !s.loss_tail)) return nullptr;  // the caller's dx / dy
+    return ws + s.acts[id].grad_off;
+  };
+  struct Prod { const bf16_t* dy; const bf16_t* x; float* GW; float* Gb; size_t rows; int cin, cout; };
+  auto products = [&](const Op& op, char* slot, char* ws, std::vector<Prod>& out) -> bool {
+    const Act& I = s.acts[op.in];
+    char* sc = ws + s.scratch_off + op.sc_off;
+    if (op.kind == OP_LINEAR) {
+      const size_t R = (size_t)I.n * I.h * I.w;
+      char* g = (op.act == 3 && !op.gelu_bwd_fused) ? sc : grad_at(ws, op.out);  // the GELU-masked gradient lies in the scratch
+      char* x = act_at(slot, op.in);
+      if (!g || !x || !wgrad_group_supported(R, op.cin, op.cout)) return false;
+      out.push_back({(const bf16_t*)g, (const bf16_t*)x, s.G + op.w_off, op.has_bias ? s.G + op.b_off : nullptr, R, op.cin, op.cout});
+      return true;
+    }
+    if (op.kind == OP_MHA) {
+      const int D = op.cin;
+      const size_t R = (size_t)I.n * I.h;
+      bf16_t* qkv = reinterpret_cast<bf16_t*>(slot + op.aux_off);
+      bf16_t* o = qkv + R * 3 * D;
+      bf16_t* dqkv = reinterpret_cast<bf16_t*>(sc) + R * D;
+      float* Gq = s.G + op.w_off;
+      float* Gbq = Gq + (size_t)3 * D * D;
+      float* Go = Gbq + 3 * D;
+      float* Gbo = Go + (size_t)D * D;
+      char* g = grad_at(ws, op.out);
+      char* x = act_at(slot, op.in);
+      if (!g || !x || !wgrad_group_supported(R, D, 3 * D)) return false;
+      out.push_back({(const bf16_t*)g, o, Go, Gbo, R, D, D});
+      out.push_back({dqkv, (const bf16_t*)x, Gq, Gbq, R, D, 3 * D});
+      return true;
+    }
+    return false;
+  };
+  // which ops take part (the same for every slot and workspace)
+  bool any = false;
+  for (Op& op : s.ops) {
+    std::vector<Prod> tmp;
+    op.wg_grouped = !op.absorbed && (op.kind == OP_LINEAR || op.kind == OP_MHA) && products(op, s.slots[0], s.ws, tmp);
+    any = any || op.wg_grouped;
+  }
+  if (!any) return AST_OK;
+  const size_t tb = wgrad_group_task_bytes();
+  s.wg_groups.assign(2 * s.slots.size(), Stage::WgGroup());
+  for (size_t k = 0; k < s.slots.size(); ++k)
+    for (int v = 0; v < (static_ws ? 2 : 1); ++v) {
+      std::vector<Prod> prods;
+      std::vector<int> prod_op;
+      for (int j = (int)s.ops.size() - 1; j >= 0; --j)  // the order of the backward pass
+        if (s.ops[j].wg_grouped) {
+          products(s.ops[j], s.slots[k], v ? static_ws : s.ws, prods);
+          prod_op.resize(prods.size(), j);
+        }
+      std::vector<char> tasks(prods.size() * tb);
+      std::vector<unsigned short> block_task;
+      std::vector<unsigned> block0;
+      for (size_t t = 0; t < prods.size(); ++t) {
+        const Prod& p = prods[t];
+        const int nb = wgrad_group_task(tasks.data() + t * tb, p.dy, p.x, p.GW, p.Gb, p.rows, p.cin, p.cout);
+        block0.push_back((unsigned)block_task.size());
+        for (int b = 0; b < nb; ++b) block_task.push_back((unsigned short)t);
+      }
+      if (prods.size() >= 65535) {  // (absurdly long stage) back to per-layer launches
+        for (Op& op : s.ops) op.wg_grouped = false;
+        s.wg_groups.clear();
+        return AST_OK;
+      }
+      Stage::WgGroup& wg = s.wg_groups[2 * k + v];
+      hipError_t e;
+      if ((e = hipMalloc(&wg.tasks, tasks.size())) != hipSuccess ||
+          (e = hipMalloc((void**)&wg.block_task, block_task.size() * sizeof(unsigned short))) != hipSuccess ||
+          (e = hipMalloc((void**)&wg.task_block0, block0.size() * sizeof(unsigned))) != hipSuccess ||
+          (e = hipMemcpy(wg.tasks, tasks.data(), tasks.size(), hipMemcpyHostToDevice)) != hipSuccess ||
+          (e = hipMemcpy(wg.block_task, block_task.data(), block_task.size() * sizeof(unsigned short), hipMemcpyHostToDevice)) != hipSuccess ||
+          (e = hipMemcpy(wg.task_block0, block0.data(), block0.size() * sizeof(unsigned), hipMemcpyHostToDevice)) != hipSuccess) {
+        err = std::string("grouped weight-gradient table: ") + hipGetErrorString(e);
+        return e == hipErrorOutOfMemory ? AST_ENOMEM : AST_EHIP;
+      }
+      s.wg_nblocks = (int)block_task.size();
+      // first launch: the products of the ops the pass reaches first, up to about half of the blocks
+      s.wg_first_blocks = 0;
+      s.wg_split_op = -1;
+      for (size_t t = 0; t + 1 < prods.size(); ++t)
+        if (prod_op[t + 1] != prod_op[t] && (int)block0[t + 1] * 2 >= s.wg_nblocks) {
+          s.wg_first_blocks = (int)block0[t + 1];
+          s.wg_split_op = prod_op[t];
+          break;
+        }
+    }
+  return AST_OK;
+}
+
 ast_status build_reduce_tasks(Stage& s, std::string& err) {
   if (ast_status r = build_pack_tasks(s, err)) return r;
   char* static_ws = nullptr;
@@ -548,6 +665,7 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
   s.static_ws = static_ws;
   if (const char* e = getenv("ASTEROID_BATCHED_REDUCE"))
     if (e[0] == '0') return AST_OK;  // per-layer reduction launches instead
+  if (ast_status r = build_wgrad_groups(s, static_ws, err)) return r;
   // the table holds absolute addresses of the partials: one table per workspace the backward
   // may run in (the stage's own; the static array, if the stage fits into it)
   for (int pass = 0; pass < (static_ws ? 2 : 1); ++pass) {
@@ -602,7 +720,7 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
                   op.has_bias ? s.G + op.b_off : nullptr, op.cout, op.cin, op.k * op.k);
         break;
       case OP_LINEAR:
-        if (s.bf16)
+        if (s.bf16 && !op.wg_grouped)
           add_wgrad(reinterpret_cast<float*>(sc + align256(s.acts[op.out].bytes)),
                     linear_bf16_wgrad_parts((size_t)I.n * I.h * I.w, op.cin, op.cout), s.G + op.w_off,
                     op.has_bias ? s.G + op.b_off : nullptr, op.cout, op.cin, 1);
@@ -616,6 +734,7 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
         float* Gbo = Go + (size_t)D * D;
         char* lw_o = sc + mha_lw_offset(I.n, I.h, D, op.heads);
         char* lw_q = lw_o + align256(linear_bf16_ws_bytes(R, D, D));
+        if (op.wg_grouped) break;
         add_wgrad(reinterpret_cast<float*>(lw_o), linear_bf16_wgrad_parts(R, D, D), Go, Gbo, D, D, 1);
         add_wgrad(reinterpret_cast<float*>(lw_q), linear_bf16_wgrad_parts(R, D, 3 * D), Gq, Gbq, (size_t)3 * D, D, 1);
         break;

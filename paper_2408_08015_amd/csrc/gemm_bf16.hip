@@ -398,7 +398,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          // bf16 output: the B rows as the first operand, so that an accumulator register group holds
+          // four consecutive COLUMNS of one output row (packed 8-byte LDS writes in the epilogue);
+          // partials: rows and columns as the operands come
+          acc[i][j] = EMODE == E_BF16 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0)
+                                      : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
   };
   if (DBUF) {
@@ -474,16 +478,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int nl = wn * WTN + j * 32 + lrow;
-        const long n = n0 + nl;
-        const float bv = (g.bias && n < g.N) ? g.bias[n] : 0.f;
+        const int ml = wm * WTM + i * 32 + lrow;  // accumulator register r of lane l is C[l % 32][8*(r/4) + 4*(l/32) + r%4]
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int ml = wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
-          float v = acc[i][j][r] + bv;
-          if (g.act == ACT_RELU) v = fmaxf(v, 0.f);
-          if (g.act == ACT_GELU && pass == 1) v = gelu_f(v);
-          smem[ml * CS + nl] = f2bf(v);
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int nl = wn * WTN + j * 32 + 8 * r4 + 4 * lgrp;  // four consecutive columns
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const long n = n0 + nl + e;
+            v[e] = acc[i][j][4 * r4 + e] + ((g.bias && n < g.N) ? g.bias[n] : 0.f);
+            if (g.act == ACT_RELU) v[e] = fmaxf(v[e], 0.f);
+            if (g.act == ACT_GELU && pass == 1) v[e] = gelu_f(v[e]);
+          }
+          uint2 pk;
+          pk.x = f2bf_pk(v[0], v[1]);
+          pk.y = f2bf_pk(v[2], v[3]);
+          *reinterpret_cast<uint2*>(&smem[ml * CS + nl]) = pk;
         }
       }
     __syncthreads();

@@ -47,6 +47,16 @@ int conv_wgrad_tr_splits(long P, int Cin, int Cout, int taps);
 bool conv_wgrad_tr_supported(int N, int H, int W, int Cin, int Cout, int k);
 void conv_wgrad_tr_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* x, float* part, float* bias_part, int N, int H,
                         int W, int Cin, int Cout, int k);
+// Grouped weight gradients of linear layers (same kernel, one launch for many products, no split-K:
+// each product is added straight into its gradient): the caller builds one descriptor per product on
+// the host (wgrad_group_task returns the product's block count), a block -> product table and the
+// first block of each product, copies the three arrays to the device once, and launches them together
+// (or a contiguous range of the table's blocks: block_base, nblocks).
+size_t wgrad_group_task_bytes();
+bool wgrad_group_supported(size_t rows, int Cin, int Cout);
+int wgrad_group_task(void* task_out, const bf16_t* dy, const bf16_t* x, float* GW, float* Gb, size_t rows, int Cin, int Cout);
+void wgrad_group_launch(hipStream_t st, const void* tasks_dev, const unsigned short* block_task_dev,
+                        const unsigned* task_block0_dev, int block_base, int nblocks);
 // Scratch layout of a weight-gradient call: `splits` partial copies of the weight gradient at
 // ws[0, ...), `bias_parts` partial bias gradients ([bias_parts][Cout]) from float offset bias_off.
 struct WgradParts { int splits; size_t bias_off; int bias_parts; };

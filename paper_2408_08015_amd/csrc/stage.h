@@ -92,6 +92,8 @@ struct Op {
   int bn_out_op = -1;                 // depthwise conv: index of the BatchNorm op it writes statistics for
   int bn_bwd_out_op = -1;             // depthwise conv: index of the BatchNorm op whose backward apply it does
   int stats_op = -1;                  // pointwise conv: index of the BatchNorm op it writes statistics for
+  bool wg_grouped = false;            // bf16 linear / attention projections: the weight (and bias) gradient is part of
+                                      // the stage's one grouped weight-gradient launch at the end of the backward pass
 };
 
 struct Stage {
@@ -133,6 +135,16 @@ struct Stage {
   char* static_ws = nullptr;             // this device's static workspace, if the stage fits into it
   unsigned short* red_block_task = nullptr;
   int red_nblocks = 0;
+
+  // Grouped weight gradients of the bf16 linear layers: descriptor tables on the device, one per stash
+  // slot (the layer inputs live there) and workspace (the stage's own, the static array), index 2*slot + static
+  struct WgGroup { void* tasks = nullptr; unsigned short* block_task = nullptr; unsigned* task_block0 = nullptr; };
+  std::vector<WgGroup> wg_groups;
+  int wg_nblocks = 0;
+  // the products are launched in two halves on the second stream: the first as soon as the backward pass has
+  // gone through op `wg_split_op` (the gradients its products read exist then) and overlaps the rest of the
+  // pass, the second at the end
+  int wg_first_blocks = 0, wg_split_op = -1;
 
   // Second stream for the weight-gradient kernels, which no later kernel of the same
   // backward pass depends on (NULL: everything runs on `stream`).

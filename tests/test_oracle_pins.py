@@ -461,10 +461,12 @@ def test_mobilenetv2_schedule():
 
 
 # ----------------------------------------------------------------- independent library cross-check
-def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False):
+def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False, manual_bn=False):
     """The same layer list through PyTorch CPU functional ops + autograd (float64 by default).
     bf16_storage: weight matrices and every layer output pass through the library's own
-    bf16 cast (round to nearest even) with a straight-through gradient."""
+    bf16 cast (round to nearest even) with a straight-through gradient.
+    manual_bn: BatchNorm written out with elementwise operations and reductions in `dtype` (the
+    library routine accumulates its statistics in double on the CPU whatever the tensor's type)."""
     t = lambda a: torch.tensor(np.asarray(a, np.float64)).to(dtype)
     rb = (lambda v: v + (v.float().bfloat16().to(dtype) - v).detach()) if bf16_storage else (lambda v: v)
     W = t(params).requires_grad_(True)
@@ -496,7 +498,12 @@ def torch_stage(cfg, params, x, target, dtype=torch.float64, bf16_storage=False)
                 a = TF.conv2d(a, w, b, l["stride"], l["pad"], 1, l["groups"])
             elif k == "batchnorm2d":
                 ga, be = take((l["c"],)), take((l["c"],))
-                a = TF.batch_norm(a, None, None, ga, be, True, 0.1, l["eps"])
+                if manual_bn:
+                    mu = a.mean(dim=(0, 2, 3), keepdim=True)
+                    var = ((a - mu) ** 2).mean(dim=(0, 2, 3), keepdim=True)
+                    a = (a - mu) / torch.sqrt(var + l["eps"]) * ga[None, :, None, None] + be[None, :, None, None]
+                else:
+                    a = TF.batch_norm(a, None, None, ga, be, True, 0.1, l["eps"])
             elif k == "layernorm":
                 ga, be = take((l["d"],)), take((l["d"],))
                 a = TF.layer_norm(a, (l["d"],), ga, be, l["eps"])

@@ -9,7 +9,9 @@ Tolerances (rel-L2 per tensor, oracle as reference):
         those stages are the derived ones stated at each test.
   bf16 operands / fp32 accumulation: 2e-2.
 """
+import json
 import math
+import os
 
 import numpy as np
 import pytest
@@ -22,6 +24,22 @@ from asteroid_workloads.configs import StageConfig, bn, conv, irb, linear, simpl
 pytestmark = pytest.mark.gpu
 
 TOL_ACT, TOL_GRAD = 1e-4, 1e-3
+# What an independent fp32 implementation (PyTorch CPU fp32 autograd) holds against the fp64 oracle on the
+# deep BatchNorm stacks, on these very inputs: tests/golden/fp32_reference.json, written by
+# tests/golden/make_fp32_reference.py and re-checked on the CPU by tests/test_reference_records.py.
+FP32_REF = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "fp32_reference.json")))
+
+
+def derived_bar(case, key, stated=1e-3, factor=1.5):
+    """Gradient bar of a workload on which fp32 itself cannot hold the stated tolerance: 1.5 x the
+    deviation of the fp32 reference, never below the stated tolerance."""
+    return max(stated, factor * FP32_REF[case][key])
+
+
+# The parameter kinds whose gradient can cancel: shifts (a constant added in front of a normalisation that
+# removes constants) and scales (a per-channel factor in front of a normalisation that removes per-channel
+# factors, through depthwise / positively homogeneous maps).
+SHIFT_PARAMS = ("beta", "gamma", "bias", "b_qkv", "b_o")
 
 
 @pytest.fixture(scope="module")
@@ -33,22 +51,31 @@ def A():
     return A
 
 
-def check(cfg, tol_y=TOL_ACT, tol_g=TOL_GRAD, K=1, rounds=2):
+def check(cfg, tol_y=TOL_ACT, tol_g=TOL_GRAD, K=1, rounds=2, tol_g_median=None):
     inp = gen.make_inputs(cfg, randomize_affine=True)
     ora, _ = harness.run_oracle(cfg, inp, K=1, rounds=rounds)
     hip, _, _ = harness.run_hip(cfg, inp, K=K, rounds=rounds)
     sc = harness.score(cfg, hip, ora)
-    # gradients that are exactly zero in exact arithmetic (a BatchNorm beta feeding another
-    # BatchNorm through a linear map) are scored against the overall gradient scale
+    # gradients that cancel (a BatchNorm beta feeding another BatchNorm through a linear map) are scored
+    # against the overall gradient scale, see harness.grad_error; every other tensor against its own norm
     for r in range(rounds):
         g_rms = float(np.sqrt(np.mean(ora[r]["G"] ** 2))) if ora[r]["G"].size else 0.0
-        worst = 0.0
+        floored, errs = [], []
         for (name, hv), (_, ov) in zip(harness.split_params(cfg.layers, hip[r]["G"]),
                                        harness.split_params(cfg.layers, ora[r]["G"])):
-            floor = 1e-2 * g_rms * math.sqrt(ov.size)
-            e = np.linalg.norm(hv - ov) / max(np.linalg.norm(ov), floor)
-            worst = max(worst, e)
+            e, fl = harness.grad_error(hv, ov, g_rms)
+            errs.append(e)
+            if fl:
+                floored.append(name)
             assert e <= tol_g, (cfg.name, r, name, e)
+        if tol_g_median is not None:
+            print("%s round %d: gradient error over the parameter tensors: median %.2e, max %.2e (bars %.2e / %.2e)" %
+                  (cfg.name, r, np.median(errs), max(errs), tol_g_median, tol_g))
+            assert np.median(errs) <= tol_g_median, (cfg.name, r, float(np.median(errs)))
+        if floored:
+            print("%s round %d: scored against the gradient-scale floor (cancelling gradient): %s" % (cfg.name, r, floored))
+            # only shifts have such a gradient: biases and BatchNorm / LayerNorm betas
+            assert all(n.rsplit(".", 1)[1] in SHIFT_PARAMS for n in floored), floored
         assert sc["r%d.y" % r] <= tol_y, (cfg.name, r, sc["r%d.y" % r])
         if cfg.needs_input_grad:
             assert sc["r%d.dx" % r] <= tol_g, (cfg.name, r, sc["r%d.dx" % r])
@@ -175,10 +202,13 @@ def test_cfg2_small(A, kw):
 
 
 def test_cfg3_small(A):
-    # 52 stacked BatchNorms over few elements: fp32 deviates from fp64 by ~1e-2 in the
-    # gradients whatever the implementation (PyTorch CPU fp32 shows 4e-3 median / 1.2e-2 max
-    # on this very input); the forward is well conditioned.
-    check(C.cfg3(B=8, M=2, hw=96, num_classes=24), tol_y=1e-4, tol_g=5e-2, rounds=1)
+    # 52 stacked BatchNorms over few elements: fp32 deviates from fp64 by ~1e-2 in the gradients
+    # whatever the implementation; the bars derive from the deviation of PyTorch CPU fp32 on this very
+    # input: 1.5 x for the worst parameter tensor; 2 x for the median, where this library measures 1.7 x
+    # the reference's figure (72 values per channel in the last blocks: the one bar that is not at 1.5 x).
+    # The forward is well conditioned.
+    check(C.cfg3(B=8, M=2, hw=96, num_classes=24), tol_y=1e-4, tol_g=derived_bar("cfg3_small", "G_max"),
+          tol_g_median=derived_bar("cfg3_small", "G_median", factor=2.0), rounds=1)
 
 
 # ------------------------------------------------------------------ EfficientNet blocks (Table 4 workload)
@@ -251,9 +281,10 @@ def test_cfg6_small(A):
 
 
 def test_efficientnet_b1_small(A):
-    # the whole model at a small resolution and batch: 69 stacked BatchNorms over few elements, bar as for
-    # the whole MobileNetV2 (fp32 statistics against fp64, see test_cfg3_small)
-    check(C.effnetb1(B=8, M=2, hw=96, num_classes=24), tol_y=1e-4, tol_g=5e-2, rounds=1)
+    # the whole model at a small resolution and batch: 69 stacked BatchNorms over few elements; bars derived
+    # from the fp32 reference on this input as in test_cfg3_small
+    check(C.effnetb1(B=8, M=2, hw=96, num_classes=24), tol_y=1e-4, tol_g=derived_bar("effnetb1_small", "G_max"),
+          tol_g_median=derived_bar("effnetb1_small", "G_median"), rounds=1)
 
 
 # ------------------------------------------------------------------ ResNet blocks (Table 4 workload)
@@ -348,8 +379,10 @@ def test_maxpool3x3s2(A, c, h, w, B):
 
 
 def test_resnet50_small(A):
-    # the whole model at a small resolution: 53 stacked BatchNorms over few elements (bar as for the other whole models)
-    check(C.resnet50(B=8, M=2, hw=64, num_classes=24), tol_y=1e-4, tol_g=5e-2, rounds=1)
+    # the whole model at a small resolution: 53 stacked BatchNorms over few elements; bars derived from the
+    # fp32 reference on this input as in test_cfg3_small
+    check(C.resnet50(B=8, M=2, hw=64, num_classes=24), tol_y=1e-4, tol_g=derived_bar("resnet50_small", "G_max"),
+          tol_g_median=derived_bar("resnet50_small", "G_median"), rounds=1)
 
 
 def test_cfg7_small(A):
@@ -519,9 +552,11 @@ def golden_check(name, tol_y, tol_dx, tol_g, tol_w):
     hip = harness.run_hip_one_round(cfg, inp, v0=harness.golden_velocity(cfg, inp["params"].size))
     sc = harness.score_golden(cfg, hip, gold)
     print(name, {k: v for k, v in sc.items() if k != "G_all"})
-    assert sc["y"] <= tol_y, sc["y"]
+    # tensors scored against the gradient-scale floor: only shifts, whose gradient cancels
+    assert all(n.rsplit(".", 1)[1] in SHIFT_PARAMS for n in sc["floored"]), sc["floored"]
+    assert sc["y"] <= tol_y and sc["ys"] <= tol_y, (sc["y"], sc["ys"])      # seeded sample; tile edges and borders
     if cfg.needs_input_grad:
-        assert sc["dx"] <= tol_dx, sc["dx"]
+        assert sc["dx"] <= tol_dx and sc["dxs"] <= tol_dx, (sc["dx"], sc["dxs"])
     if cfg.loss_tail:
         assert sc["loss"] <= 1e-5, sc["loss"]
     assert sc["G"][1] <= tol_g, sc["G"]
@@ -534,19 +569,21 @@ def test_cfg1_full_golden(A):
 
 
 def test_cfg2_full_golden(A):
-    # Derived bar: PyTorch CPU fp32 on this input deviates from the fp64 oracle by 6.3e-4
-    # (dx) and up to 2.0e-3 (BatchNorm affine gradients); 1e-3 holds for the activations'
-    # gradient, 5e-3 bounds every parameter tensor.
-    sc = golden_check("cfg2", 1e-4, 1e-3, 5e-3, 5e-3)
-    assert sc["G_median"] <= 1e-3
+    # Nine chained BatchNorms over 25 088 .. 100 352 values per channel: the stated 1e-3 holds for the input
+    # gradient and for the median parameter tensor; the worst tensors (BatchNorm affine gradients) get the
+    # derived bar, 1.5 x the deviation of the fp32 reference on this input.
+    bar = derived_bar("cfg2_full", "G_max")
+    sc = golden_check("cfg2", 1e-4, derived_bar("cfg2_full", "dx"), bar, bar)
+    assert sc["G_median"] <= derived_bar("cfg2_full", "G_median")
 
 
 def test_cfg7_full_golden(A):
-    # Derived bar: PyTorch CPU fp32 on this input deviates from the fp64 oracle by 1.6e-3 (dx), 1.5e-3 (median
-    # over the parameter tensors) and 2.1e-3 (worst tensor): nine BatchNorms over 100 352 values per channel
-    # under an unnormalised upstream gradient.  The forward holds 1e-4; 5e-3 bounds every gradient.
-    sc = golden_check("cfg7", 1e-4, 5e-3, 5e-3, 5e-3)
-    assert sc["G_median"] <= 3e-3
+    # Twelve BatchNorms over 100 352 values per channel under an unnormalised upstream gradient: derived
+    # bars (1.5 x the fp32 reference on this input) for the input gradient, the median and the worst
+    # parameter tensor.  The forward holds 1e-4.
+    bar = derived_bar("cfg7_full", "G_max")
+    sc = golden_check("cfg7", 1e-4, derived_bar("cfg7_full", "dx"), bar, bar)
+    assert sc["G_median"] <= derived_bar("cfg7_full", "G_median")
 
 
 def test_cfg6_full_golden(A):
@@ -554,9 +591,10 @@ def test_cfg6_full_golden(A):
 
 
 def test_cfg3_full_golden(A):
-    # Derived bar: PyTorch CPU fp32 deviates by 9e-3 (median over tensors) and 1.7e-2 (max).
-    sc = golden_check("cfg3", 1e-4, None, 5e-2, 5e-2)
-    assert sc["G_median"] <= 2e-2
+    # 52 chained BatchNorms: derived bars, 1.5 x the fp32 reference on this input (median, worst tensor)
+    bar = derived_bar("cfg3_full", "G_max")
+    sc = golden_check("cfg3", 1e-4, None, bar, bar)
+    assert sc["G_median"] <= derived_bar("cfg3_full", "G_median")
 
 
 # ------------------------------------------------------------------ bf16 operands / fp32 accumulation
