@@ -577,6 +577,25 @@ def test_cfg2_full_golden(A):
     assert sc["G_median"] <= derived_bar("cfg2_full", "G_median")
 
 
+def test_cfg2_full_whole_tensors(A):
+    # the same configuration with the oracle run here (half a minute of host time) and EVERY entry of y, dx,
+    # G and W compared, not the stored samples: nothing a sample could miss
+    cfg = get_config("cfg2")
+    inp = gen.make_inputs(cfg)
+    print("cfg2 at full size: running the oracle ...", flush=True)
+    ora, _ = harness.run_oracle(cfg, inp, K=1, rounds=1)
+    hip, _, _ = harness.run_hip(cfg, inp, K=1, rounds=1)
+    sc = harness.score(cfg, hip, ora)
+    g_rms = float(np.sqrt(np.mean(ora[0]["G"] ** 2)))
+    errs = [harness.grad_error(a, b, g_rms)[0] for (_, a), (_, b) in
+            zip(harness.split_params(cfg.layers, hip[0]["G"]), harness.split_params(cfg.layers, ora[0]["G"]))]
+    print("cfg2 whole tensors: y %.2e dx %.2e G median %.2e max %.2e W %.2e" %
+          (sc["r0.y"], sc["r0.dx"], np.median(errs), max(errs), sc["r0.W"][1]))
+    assert sc["r0.y"] <= 1e-4 and sc["r0.dx"] <= derived_bar("cfg2_full", "dx")
+    assert max(errs) <= derived_bar("cfg2_full", "G_max") and np.median(errs) <= derived_bar("cfg2_full", "G_median")
+    assert sc["r0.W"][1] <= derived_bar("cfg2_full", "G_max")
+
+
 def test_cfg7_full_golden(A):
     # Twelve BatchNorms over 100 352 values per channel under an unnormalised upstream gradient: derived
     # bars (1.5 x the fp32 reference on this input) for the input gradient, the median and the worst
