@@ -172,7 +172,9 @@ ast_status asteroid_stage_get_velocity(asteroid_stage* s, float* host_flat);
 /* Bytes held, in the terms of the memory model Eq. (3): mod = parameters + accumulated
  * gradients (+ derived weight copies: bf16 layouts, packed pointwise-conv operands); opt = optimizer state (velocity);
  * act_per_mb = activation stash of one micro-batch (the stage holds K of them);
- * workspace = activation-gradient and reduction scratch, independent of K.
+ * workspace = activation-gradient and reduction scratch, independent of K.  Eq. (3)'s sum
+ * MOD + OPT + K * ACT has no term for the workspace: a memory check against a device budget has to add
+ * it (the profiler tables of this library fold it into the per-sample activation bytes).
  * Any output pointer may be NULL. */
 ast_status asteroid_stage_memory(const asteroid_stage* s, size_t* mod, size_t* opt,
                                  size_t* act_per_mb, size_t* workspace);

@@ -34,6 +34,8 @@ extern "C" {
  *                     (equal to a_l when a "layer" is a single tensor-producing module)
  *   host_w    [L]     bytes of the layer's parameters
  *   host_u    [N]     memory budget of each device
+ *   host_fixed [L]    bytes the layer needs whatever K and beta are (workspace, derived weight copies);
+ *                     Eq. (3) has no such term: NULL = none, and the paper's formula is what is evaluated
  *   host_bw   [N][N]  bandwidth between devices (diagonal ignored)
  *   mod_factor, opt_factor: Mem^MOD = mod_factor * sum w_l (2: parameters + accumulated
  *                     gradients), Mem^OPT = opt_factor * sum w_l (1: momentum)   (Eq. (3))
@@ -50,10 +52,11 @@ typedef struct {
   const double* host_w;
   const double* host_u;
   const double* host_bw;
+  const double* host_fixed;
 } ast_plan_problem;
 
 /* Eq. (3): footprint in bytes of the stage of layers [lo, hi) with K resident micro-batches of
- * beta samples: mod_factor*W + opt_factor*W + K * beta * sum(act_l).
+ * beta samples: mod_factor*W + opt_factor*W + K * beta * sum(act_l) (+ sum(fixed_l) when host_fixed is given).
  * AST_EINVAL on a bad range, K < 1 or beta outside 0..B. */
 int32_t asteroid_plan_stage_memory(const ast_plan_problem* pr, int32_t lo, int32_t hi, int32_t K, int32_t beta,
                                    double* bytes);

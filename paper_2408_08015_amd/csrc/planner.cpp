@@ -30,7 +30,7 @@ struct Tables {
   const ast_plan_problem* pr;
   int L, N, B;
   std::vector<double> pf, pb;  // [N][B+1][L+1] prefix sums over layers of t_f, t_b
-  std::vector<double> pw, pact;  // [L+1]
+  std::vector<double> pw, pact, pfix;  // [L+1]
 
   explicit Tables(const ast_plan_problem* p) : pr(p), L(p->L), N(p->N), B(p->B) {
     const size_t row = (size_t)L + 1;
@@ -48,9 +48,11 @@ struct Tables {
       }
     pw.assign(row, 0.0);
     pact.assign(row, 0.0);
+    pfix.assign(row, 0.0);
     for (int l = 0; l < L; ++l) {
       pw[l + 1] = pw[l] + p->host_w[l];
       pact[l + 1] = pact[l] + p->host_act[l];
+      pfix[l + 1] = pfix[l] + (p->host_fixed ? p->host_fixed[l] : 0.0);
     }
   }
   double tf(int d, int lo, int hi, int beta) const {
@@ -65,7 +67,7 @@ struct Tables {
   // Eq. (3)
   double memory(int lo, int hi, int K, int beta) const {
     const double W = weights(lo, hi), A = pact[hi] - pact[lo];
-    return pr->mod_factor * W + pr->opt_factor * W + K * (beta * A);
+    return pr->mod_factor * W + pr->opt_factor * W + K * (beta * A) + (pfix[hi] - pfix[lo]);
   }
   // largest beta in 0..B that fits the budget of d; -1 when the replica alone does not
   int max_batch(int d, int lo, int hi, int K) const {
@@ -258,7 +260,10 @@ int32_t asteroid_plan_stage_memory(const ast_plan_problem* pr, int32_t lo, int32
   double W = 0.0, A = 0.0;
   for (int l = lo; l < hi; ++l) W += pr->host_w[l];
   for (int l = lo; l < hi; ++l) A += pr->host_act[l];
-  *bytes = pr->mod_factor * W + pr->opt_factor * W + K * (beta * A);
+  double F = 0.0;
+  if (pr->host_fixed)
+    for (int l = lo; l < hi; ++l) F += pr->host_fixed[l];
+  *bytes = pr->mod_factor * W + pr->opt_factor * W + K * (beta * A) + F;
   return AST_OK;
 }
 

@@ -14,7 +14,7 @@ class ast_plan_problem(C.Structure):
     _fields_ = [("L", C.c_int32), ("N", C.c_int32), ("B", C.c_int32), ("M", C.c_int32),
                 ("block", C.c_int32), ("mod_factor", C.c_double), ("opt_factor", C.c_double),
                 ("host_tf", _dp), ("host_tb", _dp), ("host_a", _dp), ("host_act", _dp),
-                ("host_w", _dp), ("host_u", _dp), ("host_bw", _dp)]
+                ("host_w", _dp), ("host_u", _dp), ("host_bw", _dp), ("host_fixed", _dp)]
 
 
 def _lib():
@@ -35,9 +35,10 @@ def _d(a):
 
 class Problem:
     """Profiler tables and device pool in the layout the C ABI takes.
-    tf, tb [N][L][B+1]; a, act, w [L]; u [N]; bw [N][N]."""
+    tf, tb [N][L][B+1]; a, act, w [L]; u [N]; bw [N][N]; fixed [L] or None (bytes per layer
+    outside Eq. (3): workspace, derived weight copies)."""
 
-    def __init__(self, tf, tb, a, act, w, u, bw, B, M, mod_factor=2.0, opt_factor=1.0, block=1):
+    def __init__(self, tf, tb, a, act, w, u, bw, B, M, mod_factor=2.0, opt_factor=1.0, block=1, fixed=None):
         self.tf, self.tb, self.a, self.act, self.w, self.u, self.bw = map(_d, (tf, tb, a, act, w, u, bw))
         self.N, self.L = int(self.u.shape[0]), int(self.a.shape[0])
         self.B, self.M = int(B), int(M)
@@ -50,6 +51,11 @@ class Problem:
         c.mod_factor, c.opt_factor = float(mod_factor), float(opt_factor)
         for name in ("tf", "tb", "a", "act", "w", "u", "bw"):
             setattr(c, "host_" + name, getattr(self, name).ctypes.data_as(_dp))
+        self.fixed = None if fixed is None else _d(fixed)
+        if self.fixed is not None:
+            if self.fixed.shape != (self.L,):
+                raise ValueError("fixed must be [L]")
+            c.host_fixed = self.fixed.ctypes.data_as(_dp)
         self.c = c
 
 

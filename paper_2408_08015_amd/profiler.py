@@ -121,6 +121,28 @@ def time_unit(layers, in_shape, beta, dtype, layout, needs_input_grad, reps=20, 
     return tf, tb
 
 
+def unit_memory(sub, bmax, shape, dtype, layout, grad_in, out_bytes=0.0):
+    """(act_l, w_l, fixed_l) of a unit for the planner's memory check, Eq. (3) plus a fixed term:
+    (2 + 1) w_l + K * beta * act_l + fixed_l.  w_l = fp32 parameter bytes.  Eq. (3) has no term for the
+    workspace (activation gradients, reduction partials: independent of K, growing with beta in steps) or
+    for the derived weight copies; both are fitted here as fixed_l + beta * (part of act_l) from what
+    asteroid_stage_plan_memory reports at beta = 1, 2, 4, ... and bmax: act_l is the slope between beta = 1
+    and bmax of stash + workspace, fixed_l the largest amount by which any of those batch sizes lies above
+    that line, plus the copies.  out_bytes (a_l, the unit's output per sample) is added to act_l: a unit
+    measured alone writes its output gradient into the caller's buffer, inside a longer stage that buffer
+    is part of the stage's workspace.  Charging the workspace slope once per stashed micro-batch
+    over-states it for K > 1: the check errs on the safe side, never below what the library reports.
+    No GPU needed."""
+    grid = sorted({bmax} | {b for b in (1 << i for i in range(31)) if b < bmax})
+    rows = {b: A.plan_memory(sub, b, 1, 1, shape, dtype, layout, grad_in) for b in grid}
+    mod, opt, _, _ = rows[bmax]
+    T = {b: rows[b][2] + rows[b][3] for b in grid}
+    slope = (T[bmax] - T[1]) / (bmax - 1) if bmax > 1 else 0.0
+    slope = max(slope, max(rows[b][2] / b for b in grid))      # never below the stash alone
+    fixed = max(0.0, max(T[b] - slope * b for b in grid)) + max(0, mod - 2 * opt)
+    return slope + out_bytes, opt, fixed
+
+
 def profile_model(layers, in_shape, dtype, layout, betas, needs_input_grad=False, reps=20, log=None):
     """Tables of a model: list of units, each {lo, hi, kinds, a, act, w, tf{beta}, tb{beta}};
     a, act in bytes per sample, w in bytes, times in ms."""
@@ -131,10 +153,10 @@ def profile_model(layers, in_shape, dtype, layout, betas, needs_input_grad=False
         sub = layers[lo:hi]
         out = _out_shape(sub, shape)
         grad_in = needs_input_grad or lo > 0
-        mod, opt, act, _ = A.plan_memory(sub, bmax, 1, 1, shape, dtype, layout, grad_in)
+        a_l = int(np.prod(out)) * (4 if sub[-1]["kind"] == "softmax_ce" else esz)
+        act_l, w_l, fixed_l = unit_memory(sub, bmax, shape, dtype, layout, grad_in, a_l)
         u = dict(lo=lo, hi=hi, kinds=[L["kind"] for L in sub], in_shape=list(shape), out_shape=list(out),
-                 a=int(np.prod(out)) * (4 if sub[-1]["kind"] == "softmax_ce" else esz),
-                 act=act / bmax, w=opt, tf={}, tb={})
+                 a=a_l, act=act_l, w=w_l, fixed=fixed_l, tf={}, tb={})
         for beta in betas:
             tf, tb = time_unit(sub, shape, beta, dtype, layout, grad_in, reps=reps)
             u["tf"][beta], u["tb"][beta] = tf, tb
@@ -147,7 +169,7 @@ def profile_model(layers, in_shape, dtype, layout, betas, needs_input_grad=False
 
 def tables_for_planner(units, B, n_devices=1):
     """tf, tb [n_devices][L][B+1] (piecewise linear between the measured batch sizes, 0 at 0,
-    the last slope beyond the largest one), a, act, w [L]: the planner's input for a pool of
+    the last slope beyond the largest one), a, act, w, fixed [L]: the planner's input for a pool of
     identical devices."""
     L = len(units)
     tf = np.zeros((n_devices, L, B + 1))
@@ -168,7 +190,8 @@ def tables_for_planner(units, B, n_devices=1):
     a = np.array([u["a"] for u in units], dtype=np.float64)
     act = np.array([u["act"] for u in units], dtype=np.float64)
     w = np.array([u["w"] for u in units], dtype=np.float64)
-    return tf, tb, a, act, w
+    fixed = np.array([u.get("fixed", 0.0) for u in units], dtype=np.float64)
+    return tf, tb, a, act, w, fixed
 
 
 def markdown(units, betas, title):
@@ -223,10 +246,10 @@ def main(argv=None):
         import time
         from . import planner as PL
         N, B, M = args.plan_devices, args.plan_B, args.plan_M
-        tf, tb, a, act, w = tables_for_planner(units, B, N)
+        tf, tb, a, act, w, fixed = tables_for_planner(units, B, N)
         bw = np.full((N, N), args.link_gbs * 1e6)          # bytes per millisecond
         u = np.full(N, args.budget_gb * 1e9)
-        pr = PL.Problem(tf, tb, a, act, w, u, bw, B, M, block=max(1, B // 16))
+        pr = PL.Problem(tf, tb, a, act, w, u, bw, B, M, block=max(1, B // 16), fixed=fixed)
         t0 = time.perf_counter()
         lat, stages, y = PL.plan_hpp(pr)
         dt = time.perf_counter() - t0

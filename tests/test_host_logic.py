@@ -146,8 +146,53 @@ def test_profiler_units_cut_only_where_a_stage_may_end():
 def test_profiler_table_interpolation():
     from paper_2408_08015_amd.profiler import tables_for_planner
     units = [dict(tf={1: 10.0, 4: 16.0}, tb={1: 20.0, 4: 32.0}, a=8, act=24.0, w=100)]
-    tf, tb, a, act, w = tables_for_planner(units, 6, n_devices=3)
+    tf, tb, a, act, w, fixed = tables_for_planner(units, 6, n_devices=3)
     assert tf.shape == (3, 1, 7)
     assert list(tf[2, 0]) == [0.0, 10.0, 12.0, 14.0, 16.0, 18.0, 20.0]      # last slope continues
     assert list(tb[0, 0]) == [0.0, 20.0, 24.0, 28.0, 32.0, 36.0, 40.0]
-    assert (a[0], act[0], w[0]) == (8.0, 24.0, 100.0)
+    assert (a[0], act[0], w[0], fixed[0]) == (8.0, 24.0, 100.0, 0.0)
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
+def test_profiler_memory_terms_cover_what_the_library_allocates(A, name):
+    """Eq. (3) has no term for the workspace or the derived weight copies.  What the profiler hands the
+    planner for a unit (w_l, act_l, fixed_l), put through the planner's memory check, must never fall below
+    the bytes asteroid_stage_plan_memory reports for a stage made of that unit - for K = 1 and K = 3, at the
+    power-of-two micro-batch sizes up to the profiled one - nor, summed over its units, for a stage of
+    several units, which at the profiled size with K = 1 it over-states by less than 30 %."""
+    from asteroid_workloads.gen import out_shape
+    from paper_2408_08015_amd import planner as PL
+    from paper_2408_08015_amd.profiler import split_units, unit_memory
+    cfg = get_config(name)
+    units = split_units(cfg.layers)[:6]
+    shape, bmax = list(cfg.in_shape), cfg.B
+    first_shape, rows = list(shape), []
+    for lo, hi in units:
+        sub = cfg.layers[lo:hi]
+        out = list(out_shape(sub, shape))
+        a_l = int(np.prod(out)) * (2 if cfg.dtype == "bf16" else 4)
+        rows.append(unit_memory(sub, bmax, shape, cfg.dtype, cfg.layout, cfg.needs_input_grad or lo > 0, a_l))
+        shape = out
+    L = len(units)
+    act, w, fixed = (np.array(c, dtype=np.float64) for c in zip(*rows))
+    z = np.zeros((1, L, bmax + 1))
+    pr = PL.Problem(z, z, [1.0] * L, act, w, [1e18], [[1.0]], bmax, 4, fixed=fixed)
+    betas = sorted({bmax} | {b for b in (1, 2, 4, 8, 16) if b < bmax})
+    shape = list(first_shape)
+    for u, (lo, hi) in enumerate(units):
+        sub = cfg.layers[lo:hi]
+        for K in (1, 3):
+            for beta in betas:
+                mod, opt, a_, ws = A.plan_memory(sub, beta, max(K, 4), K, shape, cfg.dtype, cfg.layout,
+                                                 cfg.needs_input_grad or lo > 0)
+                model = PL.stage_memory(pr, u, u + 1, K, beta)
+                assert mod + opt + K * a_ + ws <= model + 1e-6, (u, K, beta)
+        shape = list(out_shape(sub, shape))
+    sub = cfg.layers[units[0][0]:units[-1][1]]
+    for K in (1, 3):
+        mod, opt, a_, ws = A.plan_memory(sub, bmax, max(K, 4), K, first_shape, cfg.dtype, cfg.layout,
+                                         cfg.needs_input_grad)
+        model = PL.stage_memory(pr, 0, L, K, bmax)
+        assert mod + opt + K * a_ + ws <= model + 1e-6, K
+        if K == 1:
+            assert model <= 1.3 * (mod + opt + a_ + ws), (model, mod + opt + a_ + ws)

@@ -451,7 +451,8 @@ def test_profiler_tables(A):
     assert units[0]["w"] == 4 * gen.num_params(cfg.layers[:units[0]["hi"]])
     for u in units:
         assert all(u["tf"][b] > 0 and u["tb"][b] > 0 for b in (1, 2, 4))
-    tf, tb, a, act, w = profiler.tables_for_planner(units, 6, n_devices=2)
+    tf, tb, a, act, w, fixed = profiler.tables_for_planner(units, 6, n_devices=2)
+    assert np.all(fixed >= 0) and np.all(act >= a)      # act_l includes the output-gradient buffer
     assert tf.shape == (2, len(units), 7) and np.all(tf[:, :, 0] == 0)
     assert tf[1, 0, 4] == units[0]["tf"][4] and tb[0, 1, 2] == units[1]["tb"][2]
     assert abs(tf[0, 0, 3] - 0.5 * (units[0]["tf"][2] + units[0]["tf"][4])) < 1e-12
