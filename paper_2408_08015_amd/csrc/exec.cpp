@@ -795,15 +795,21 @@ ast_status refresh_shadow(Stage& s, std::string& err) {
                               op.cin, op.k, conv_bf16_uses_halo(I.n, I.h, I.w, op.cin, op.cout, op.k),
                               conv_bf16_uses_halo(I.n, I.h, I.w, op.cout, op.cin, op.k));
     } else if (op.kind == OP_LINEAR) {
+      const Act& I = s.acts[op.in];  // the kernel each direction will run decides the layout of its copy
+      const size_t R = (size_t)I.n * I.h * I.w;
       linear_weight_shadow_bf16(s.stream, s.W + op.w_off, s.shadow + op.sh_off, s.shadow + op.sh2_off, op.cout,
-                                op.cin);
+                                op.cin, linear_dl_supported(R, op.cin, op.cout), linear_dl_supported(R, op.cout, op.cin));
     } else if (op.kind == OP_MHA) {
       const int D = op.cin;
       const float* wq = s.W + op.w_off;
       const float* wo = wq + (size_t)3 * D * D + 3 * D;
-      linear_weight_shadow_bf16(s.stream, wq, s.shadow + op.sh_off, s.shadow + op.sh2_off, 3 * D, D);
+      const Act& I = s.acts[op.in];
+      const size_t R = (size_t)I.n * I.h;
+      linear_weight_shadow_bf16(s.stream, wq, s.shadow + op.sh_off, s.shadow + op.sh2_off, 3 * D, D,
+                                linear_dl_supported(R, D, 3 * D), linear_dl_supported(R, 3 * D, D));
       linear_weight_shadow_bf16(s.stream, wo, s.shadow + op.sh_off + (size_t)3 * D * D,
-                                s.shadow + op.sh2_off + (size_t)3 * D * D, D, D);
+                                s.shadow + op.sh2_off + (size_t)3 * D * D, D, D, linear_dl_supported(R, D, D),
+                                linear_dl_supported(R, D, D));
     }
   }
   return check_launch(err, "weight copy refresh");

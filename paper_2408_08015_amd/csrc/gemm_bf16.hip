@@ -87,11 +87,9 @@ __device__ __forceinline__ int lds_off(int row, int c16) {
   return row * BKT + ((c16 ^ (row & 15)) << 3);
 }
 
-__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_f(float x) { return gelu_fast(x); }
 // d/dx of the exact GELU: Phi(x) + x phi(x)
-__device__ __forceinline__ float gelu_grad_f(float x) {
-  return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
-}
+__device__ __forceinline__ float gelu_grad_f(float x) { return gelu_grad_fast(x); }
 
 template <int WTM, int WTN, int AMODE, int BMODE, int EMODE, bool DBUF, bool FASTC, int PF = 1, int BKT = 64>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
@@ -515,7 +513,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             if (g.add) { a0 += b0; a1 += b1; }
             else if (g.gmul_relu) { a0 = b0 > 0.f ? a0 : 0.f; a1 = b1 > 0.f ? a1 : 0.f; }
             else { a0 *= gelu_grad_f(b0); a1 *= gelu_grad_f(b1); }
-            vw[w] = (uint32_t)f2bf(a0) | ((uint32_t)f2bf(a1) << 16);
+            vw[w] = f2bf_pk(a0, a1);
           }
         }
         *reinterpret_cast<uint4*>(out + m * g.ldc + n) = v;
@@ -950,6 +948,10 @@ WgradParts linear_bf16_wgrad_parts(size_t R, int Cin, int Cout) {
 
 void linear_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh, const float* bias, bf16_t* y, bf16_t* pre,
                      const bf16_t* add, size_t R, int Cin, int Cout, int act) {
+  if (linear_dl_supported(R, Cin, Cout)) {
+    linear_dl_bf16(st, x, sh, bias, y, pre, add, nullptr, R, Cin, Cout, act);
+    return;
+  }
   GemmArgs g = {};
   g.add = add;
   g.A = x; g.B = sh;
@@ -960,6 +962,10 @@ void linear_bf16_fwd(hipStream_t st, const bf16_t* x, const bf16_t* sh, const fl
 
 void linear_bf16_dgrad(hipStream_t st, const bf16_t* gy, const bf16_t* sh_t, bf16_t* dx, const bf16_t* gelu_pre,
                        const bf16_t* add, size_t R, int Cin, int Cout) {
+  if (linear_dl_supported(R, Cout, Cin)) {
+    linear_dl_bf16(st, gy, sh_t, nullptr, dx, nullptr, add, gelu_pre, R, Cout, Cin, 0);
+    return;
+  }
   GemmArgs g = {};
   g.gmul = gelu_pre;  // at most one of the two is given
   g.add = add;

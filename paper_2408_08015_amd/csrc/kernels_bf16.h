@@ -17,8 +17,8 @@ typedef unsigned short bf16_t;
 void conv_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh_fwd, bf16_t* sh_dgrad, int Cout,
                              int Cin, int k, bool tiled_fwd, bool tiled_dgrad);
 // linear: master [Cout][Cin] -> copy [Cout][Cin] and transpose [Cin][Cout]
-void linear_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh, bf16_t* sh_t, int Cout,
-                               int Cin);
+void linear_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh, bf16_t* sh_t, int Cout, int Cin,
+                               bool tiled, bool tiled_t);
 
 // ---- dense 'same' convolution, stride 1, NHWC, k in {1,3}
 size_t conv_bf16_ws_bytes(int N, int H, int W, int Cin, int Cout, int k);
@@ -67,6 +67,12 @@ void conv_bf16_wgrad(hipStream_t st, const bf16_t* g, const bf16_t* x, float* GW
                      bool defer, void* ws, int N, int H, int W, int Cin, int Cout, int k);
 
 // ---- linear on [R][Cin] rows
+// Whether the product of [R][K] rows with an [N][K] weight matrix runs in the direct-to-LDS kernel,
+// which reads its weights from the tiled copy [K/64][N][64] (linear_weight_shadow_bf16: `tiled` for
+// the forward copy with K = Cin, N = Cout; `tiled_t` for the transposed one with K = Cout, N = Cin).
+bool linear_dl_supported(size_t R, int K, int N);
+void linear_dl_bf16(hipStream_t st, const bf16_t* a, const bf16_t* b, const float* bias, bf16_t* c, bf16_t* pre,
+                    const bf16_t* add, const bf16_t* gmul, size_t R, int K, int N, int act);
 size_t linear_bf16_ws_bytes(size_t R, int Cin, int Cout);
 // y = act(x W^T + b) (+ add); with act == GELU the pre-activation goes to `pre` as well
 // `add` (may be NULL): residual input [R][Cout] added to the rounded output.

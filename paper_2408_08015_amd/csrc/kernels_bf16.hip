@@ -26,12 +26,8 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
   for (int k = 0; k < 4; ++k) w[k] = (uint32_t)f2bf(f[2 * k]) | ((uint32_t)f2bf(f[2 * k + 1]) << 16);
   return v;
 }
-__device__ __forceinline__ float gelu_grad(float x) {
-  float cdf = 0.5f * (1.f + erff(x * 0.70710678118654752f));
-  float pdf = 0.3989422804014327f * __expf(-0.5f * x * x);
-  return cdf + x * pdf;
-}
-__device__ __forceinline__ float gelu_val(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad(float x) { return gelu_grad_fast(x); }
+__device__ __forceinline__ float gelu_val(float x) { return gelu_fast(x); }
 }  // namespace
 
 // ------------------------------------------------------------------ weight copies
@@ -58,8 +54,10 @@ void conv_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh_fwd, bf1
           tiled_fwd ? 1 : 0, tiled_dgrad ? 1 : 0);
 }
 
+// sh [Cout][Cin] and sht [Cin][Cout]; tiled: [K/64][rows][64] with K the contraction index of the
+// product that reads the copy (Cin for sh, Cout for sht) - the layout of the direct-to-LDS kernel
 __global__ void linear_shadow_kernel(const float* __restrict__ w, bf16_t* __restrict__ sh,
-                                     bf16_t* __restrict__ sht, int Cout, int Cin) {
+                                     bf16_t* __restrict__ sht, int Cout, int Cin, int tiled, int tiled_t) {
   __shared__ float tile[32][33];
   int bx = blockIdx.x * 32, by = blockIdx.y * 32;  // bx: ci, by: co
   int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
@@ -67,16 +65,20 @@ __global__ void linear_shadow_kernel(const float* __restrict__ w, bf16_t* __rest
     int co = by + r, ci = bx + tx;
     float v = (co < Cout && ci < Cin) ? w[(size_t)co * Cin + ci] : 0.f;
     tile[r][tx] = v;
-    if (co < Cout && ci < Cin) sh[(size_t)co * Cin + ci] = f2bf(v);
+    if (co < Cout && ci < Cin)
+      sh[tiled ? ((size_t)(ci >> 6) * Cout + co) * 64 + (ci & 63) : (size_t)co * Cin + ci] = f2bf(v);
   }
   __syncthreads();
   for (int r = ty; r < 32; r += 8) {
     int ci = bx + r, co = by + tx;
-    if (co < Cout && ci < Cin) sht[(size_t)ci * Cout + co] = f2bf(tile[tx][r]);
+    if (co < Cout && ci < Cin)
+      sht[tiled_t ? ((size_t)(co >> 6) * Cin + ci) * 64 + (co & 63) : (size_t)ci * Cout + co] = f2bf(tile[tx][r]);
   }
 }
-void linear_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh, bf16_t* sh_t, int Cout, int Cin) {
-  KLAUNCH(linear_shadow_kernel, dim3(cdivu(Cin, 32), cdivu(Cout, 32)), dim3(256), 0, st, w, sh, sh_t, Cout, Cin);
+void linear_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh, bf16_t* sh_t, int Cout, int Cin, bool tiled,
+                               bool tiled_t) {
+  KLAUNCH(linear_shadow_kernel, dim3(cdivu(Cin, 32), cdivu(Cout, 32)), dim3(256), 0, st, w, sh, sh_t, Cout, Cin,
+          tiled ? 1 : 0, tiled_t ? 1 : 0);
 }
 
 __global__ void f32_to_bf16_kernel(const float* __restrict__ s, bf16_t* __restrict__ d, size_t n) {
