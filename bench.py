@@ -190,14 +190,20 @@ def kernel_model(cfg):
         if cfg.dtype == "bf16" and k in ("linear", "mha"):
             rows = B * shape[0]
 
-            def lcls(mm, nn):
+            def lcls(mm, nn, kc):
+                if kc % 64 == 0 and nn % 8 == 0 and nn >= 64 and mm >= 64:      # the direct-to-LDS kernel's shapes
+                    if _cdiv(mm, 256) * _cdiv(nn, 128) >= 160:
+                        return "linear_dl_kernel_256x128"
+                    return "linear_dl_kernel_128x128" if _cdiv(mm, 128) * _cdiv(nn, 128) >= 160 else "linear_dl_kernel_128x64"
                 return "gemm_bf16_kernel<128x128,rows>" if _cdiv(mm, 128) * _cdiv(nn, 128) >= 256 \
                     else "gemm_bf16_kernel<64x64,rows>"
             mats = [(L["cin"], L["cout"])] if k == "linear" else [(L["d"], 3 * L["d"]), (L["d"], L["d"])]
             for cin, cout in mats:
-                out.setdefault(lcls(rows, cout), []).append(2 * rows * cin * cout)      # forward
-                out.setdefault(lcls(rows, cin), []).append(2 * rows * cin * cout)       # input gradient
-                out.setdefault("gemm_bf16_kernel<128x128,wgrad_rows>", []).append(2 * rows * cin * cout)
+                out.setdefault(lcls(rows, cout, cin), []).append(2 * rows * cin * cout)      # forward
+                out.setdefault(lcls(rows, cin, cout), []).append(2 * rows * cin * cout)      # input gradient
+                grouped = cin % 8 == 0 and cout % 8 == 0 and rows >= 48     # one launch for many layers' products
+                out.setdefault("wgrad_grouped_kernel" if grouped else "gemm_bf16_kernel<128x128,wgrad_rows>",
+                               []).append(2 * rows * cin * cout)
         if cfg.dtype == "bf16" and k == "mha":
             S, D = shape
             fl = 4 * S * D * B * S                                            # QK^T and PV
@@ -216,12 +222,12 @@ def kernel_model(cfg):
 
 
 def kernel_bound(name):
-    return "mfma" if name.startswith(("gemm_bf16", "attention", "conv3x3_", "conv_wgrad", "wgrad_grouped")) else "hbm"
+    return "mfma" if name.startswith(("gemm_bf16", "attention", "conv3x3_", "conv_wgrad", "wgrad_grouped", "linear_dl")) else "hbm"
 
 
 def family(name):
     """Kernel family of a profile name: template arguments and tile-size suffixes dropped."""
-    return re.sub(r"_n(128|256)$", "", name.split("<")[0])
+    return re.sub(r"_(n128|n256|256x128|128x128|128x64)$", "", name.split("<")[0])
 
 
 def committed_traffic(workload, fam):

@@ -37,13 +37,6 @@
 
 #include <type_traits>
 
-#ifndef HALO_STAMP
-#define HALO_STAMP(k)
-#endif
-#ifndef HALO_STAMP2
-#define HALO_STAMP2(k)
-#endif
-
 namespace ast {
 
 namespace {
@@ -59,9 +52,6 @@ struct HaloArgs {
   int tiles_n;         // channel tiles of BN
   int rows_per_block;  // pixels per block
   unsigned x_bytes, w_bytes;
-#ifdef HALO_DEBUG_FIELD
-  HALO_DEBUG_FIELD
-#endif
 };
 
 constexpr int HALO_BM = 256;             // pixels per tile
@@ -224,7 +214,6 @@ __device__ __forceinline__ void conv3x3_halo_body(const HaloArgs& g) {
   };
 
   // ---------------- prologue: halo of the first slice, weight tiles 0 and 1
-  HALO_STAMP(0);
   set_avoff(m_begin);  // (the first tile starts at m_begin in either order)
 #pragma unroll
   for (int q = 0; q < HALO_AQ; ++q) issue_A(q, 0, 0);
@@ -236,7 +225,6 @@ __device__ __forceinline__ void conv3x3_halo_body(const HaloArgs& g) {
   __builtin_amdgcn_s_barrier();
   fence();
   read_frags(both_groups{}, 0, a_base(arow0), 2 * HALO_A_BYTES + b_base, 0);
-  HALO_STAMP(1);
 
   // ---------------- one 64-channel slice: nine taps.  s: slice of the tile, sig: slices done by
   // the block so far (buffer parities), hn: another slice follows (of this tile or the next),
@@ -323,12 +311,10 @@ __device__ __forceinline__ void conv3x3_halo_body(const HaloArgs& g) {
       for (int k = 0; k < 4; ++k) mk[0][k] = __builtin_amdgcn_raw_buffer_load_b128(rmask, out_off(0, k), 0, 0);
     }
     lds_barrier();  // bias in LDS
-    HALO_STAMP2(0);
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       const int i = p / (TN / 2), jh = p % (TN / 2);
       if (p > 0) lds_barrier();  // the previous pass has been read
-      HALO_STAMP2(1 + 3 * p);
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const int j = 2 * jh + jj;
@@ -346,7 +332,6 @@ __device__ __forceinline__ void conv3x3_halo_body(const HaloArgs& g) {
         }
       }
       lds_barrier();
-      HALO_STAMP2(2 + 3 * p);
       if (g.mask && p + 1 < NP) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) mk[(p + 1) & 1][k] = __builtin_amdgcn_raw_buffer_load_b128(rmask, out_off(p + 1, k), 0, 0);
@@ -366,7 +351,6 @@ __device__ __forceinline__ void conv3x3_halo_body(const HaloArgs& g) {
         }
         __builtin_amdgcn_raw_buffer_store_b128(v, ry, out_off(p, k), 0, 0);
       }
-      HALO_STAMP2(3 + 3 * p);
     }
   };
 
@@ -396,11 +380,9 @@ __device__ __forceinline__ void conv3x3_halo_body(const HaloArgs& g) {
       if (mine > 32) slice_body(both_groups{}, s, sig, hn, s_next, fresh);
       else if (mine > 0) slice_body(std::integral_constant<int, 1>{}, s, sig, hn, s_next, fresh);
       else slice_body(std::integral_constant<int, 0>{}, s, sig, hn, s_next, fresh);
-      HALO_STAMP(2 + sig);
     }
     // sig counts this tile's last slice already: its halo buffer is the one before
     epilogue(m0, m0 + rows, sA + ((sig - 1) & 1) * HALO_A_BYTES);
-    HALO_STAMP(12 + tl);
     if (more) {
       zero_acc();
       set_valid(tile_begin(tl + 1));
