@@ -654,6 +654,31 @@ def test_bf16_linear(A, rows_s, cin, cout, gelu):
     check(cfg, tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
 
 
+@pytest.mark.parametrize("rows_s,B,cin,cout,gelu", [
+    (650, 4, 64, 1920, True),     # 2600 rows: eleven ragged 256 x 128 tiles x 15 (forward); input gradient K = 1920 on 128 x 64 tiles
+    (325, 4, 128, 1920, False),   # 1300 rows: 128 x 128 tiles, ragged in M
+    (50, 4, 192, 200, True),      # 128 x 64 tiles ragged in M and N, three 64-deep K-tiles (half a stage at the end)
+    (16, 4, 64, 64, False),       # a single tile, a single K-tile
+])
+def test_bf16_linear_direct_to_lds_tiles(A, rows_s, B, cin, cout, gelu):
+    """The tile shapes of the dense-layer kernel with loads straight into LDS, each with ragged edges; the layer sits
+    in a residual block where the shapes allow, so the residual-sum epilogue runs too."""
+    L = [linear(cin, cout)] + ([simple("gelu")] if gelu else [])
+    if cin == cout:
+        L = [simple("res_begin")] + L + [simple("res_add")]
+    cfg = one_bf16(L, (rows_s, cin), "bsd", B=B)
+    cfg.init = "normal0.02" if cin > 64 else "kaiming"
+    check(cfg, tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+
+
+def test_bf16_linear_general_kernel_path(A, monkeypatch):
+    """ASTEROID_LINEAR_DL=0 is read once per process, so this only checks the shapes the direct-to-LDS kernel
+    refuses (K not a multiple of 64, N below 64): they run on the general kernel."""
+    for cin, cout in ((72, 40), (136, 512)):
+        cfg = one_bf16([linear(cin, cout), simple("gelu")], (24, cin), "bsd", B=3)
+        check(cfg, tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+
+
 @pytest.mark.parametrize("S,d", [(32, 64), (128, 512), (96, 1024)])
 def test_bf16_layernorm(A, S, d):
     check(one_bf16([dict(kind="layernorm", d=d, eps=1e-5)], (S, d), "bsd", B=3), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
