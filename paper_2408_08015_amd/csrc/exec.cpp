@@ -371,7 +371,9 @@ void bwd_op(Ctx& c, const Op& op) {
       break;
     case OP_MAXPOOL:
       if (!gin) break;
-      if (s.bf16) maxpool_bwd_bf16(st, (cb)grad_ptr(c, op.out), (cb)act_ptr(c, op.in), (bf16_t*)gin, I.n, I.h, I.w, I.c);
+      if (s.bf16)
+        maxpool_bwd_bf16(st, (cb)grad_ptr(c, op.out), (cb)act_ptr(c, op.in), (bf16_t*)gin, I.n, I.h, I.w, I.c,
+                         op.relu_from >= 0);
       else if (op.k == 3)
         maxpool3x3s2_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), (float*)gin, I.n * I.c, I.h, I.w);
       else maxpool_bwd_f32(st, (cf)grad_ptr(c, op.out), (cf)act_ptr(c, op.in), (float*)gin, I.n * I.c, I.h, I.w);

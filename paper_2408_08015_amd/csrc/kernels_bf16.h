@@ -94,7 +94,7 @@ void act_fwd_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, size_t n, int act)
 void add_bf16(hipStream_t st, const bf16_t* a, const bf16_t* b, bf16_t* y, size_t n);
 void maxpool_fwd_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, int N, int H, int W, int C);
 void maxpool_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, bf16_t* dx, int N, int H, int W,
-                      int C);
+                      int C, bool relu_mask);
 
 // ---- LayerNorm over the last dimension of [R][D]
 size_t layernorm_bf16_ws_bytes(size_t R, int D);

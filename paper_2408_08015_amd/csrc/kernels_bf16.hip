@@ -159,7 +159,7 @@ __global__ void maxpool_fwd_bf16_kernel(const bf16_t* __restrict__ x, bf16_t* __
 // one thread per output window and 8 channels: writes the four input-gradient vectors
 __global__ void maxpool_bwd_bf16_kernel(const bf16_t* __restrict__ g, const bf16_t* __restrict__ x,
                                         bf16_t* __restrict__ dx, int H, int W, int C, int Ho, int Wo,
-                                        size_t total8) {
+                                        size_t total8, int relu_mask) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total8) return;
   int c8 = C / 8;
@@ -183,8 +183,10 @@ __global__ void maxpool_bwd_bf16_kernel(const bf16_t* __restrict__ g, const bf16
     if (v[1][k] > m) { m = v[1][k]; am = 1; }
     if (v[2][k] > m) { m = v[2][k]; am = 2; }
     if (v[3][k] > m) { m = v[3][k]; am = 3; }
+    // relu_mask: x is the output of a ReLU whose backward is applied here as well (gradient only where x > 0)
+    const float gk = (relu_mask && !(m > 0.f)) ? 0.f : gv[k];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) o[q][k] = q == am ? gv[k] : 0.f;
+    for (int q = 0; q < 4; ++q) o[q][k] = q == am ? gk : 0.f;
   }
   *reinterpret_cast<uint4*>(dx + off) = pack8(o[0]);
   *reinterpret_cast<uint4*>(dx + off + C) = pack8(o[1]);
@@ -209,10 +211,12 @@ void maxpool_fwd_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, int N, int H, 
   size_t total8 = (size_t)N * Ho * Wo * (C / 8);
   KLAUNCH(maxpool_fwd_bf16_kernel, dim3(cdivu(total8, 256)), dim3(256), 0, st, x, y, H, W, C, Ho, Wo, total8);
 }
-void maxpool_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, bf16_t* dx, int N, int H, int W, int C) {
+void maxpool_bwd_bf16(hipStream_t st, const bf16_t* g, const bf16_t* x, bf16_t* dx, int N, int H, int W, int C,
+                      bool relu_mask) {
   int Ho = H / 2, Wo = W / 2;
   size_t total8 = (size_t)N * Ho * Wo * (C / 8);
-  KLAUNCH(maxpool_bwd_bf16_kernel, dim3(cdivu(total8, 256)), dim3(256), 0, st, g, x, dx, H, W, C, Ho, Wo, total8);
+  KLAUNCH(maxpool_bwd_bf16_kernel, dim3(cdivu(total8, 256)), dim3(256), 0, st, g, x, dx, H, W, C, Ho, Wo, total8,
+          relu_mask ? 1 : 0);
   if ((H & 1) || (W & 1)) {
     size_t total = (size_t)N * H * W * C;
     KLAUNCH(maxpool_bwd_edge_kernel, dim3(cdivu(total, 256)), dim3(256), 0, st, dx, H, W, C, Ho, Wo, total);

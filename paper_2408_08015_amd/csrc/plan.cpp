@@ -369,6 +369,12 @@ ast_status build_plan(Stage& s, std::string& err) {
       nx.relu_from = pr.out;
       pr.relu_bwd_fused = true;
     }
+    // ... or a 2x2 max pool behind it: the pool's backward sees the ReLU output anyway (it is its input)
+    // and hands the gradient to a window's maximum only where that maximum is positive
+    if (s.bf16 && pr.kind == OP_CONV_IGEMM && pr.act == 1 && nx.kind == OP_MAXPOOL && nx.k == 2 && nx.in == pr.out) {
+      nx.relu_from = pr.out;
+      pr.relu_bwd_fused = true;
+    }
   }
 
   // Fuse the skip-gradient add of a residual block into the input-gradient kernel of the op
