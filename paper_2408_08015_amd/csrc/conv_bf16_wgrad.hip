@@ -21,6 +21,7 @@
 #include "kernels_bf16.h"
 #include "prof.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace ast {
@@ -70,14 +71,21 @@ __device__ __forceinline__ bf16x8 wg_read_tr(const unsigned char* smem, int off)
   return __builtin_bit_cast(bf16x8, v);
 }
 
-template <int TN>  // block: 256 output channels x 64*TN input channels; wavefront tile 64 x 32*TN
+// block: 256 output channels x 64*TN input channels, 8 wavefronts as 4 x 2; wavefront tile 64 x 32*TN.
+// (Four wavefronts of 128 x 128 with the accumulators in the accumulation registers - a third less LDS
+// read traffic per MFMA - were measured: 190-210 us against 137-149 us for the 256 -> 256 channel layer.)
+template <int TN>
 __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  // bid: block of this product
+  constexpr int NW = 8;
+  constexpr int TM = 16 / NW;
+  constexpr int NT = NW * 64;                        // threads
   constexpr int NCI = 64 * TN;                       // input channels per block
   constexpr int BPITCH = NCI * 2;                    // bytes per pixel row of the x tile
   constexpr int B_BYTES = TN == 4 ? WG_BK * 512 : 16 * 1024;  // TN == 2: 12 KB of rows + 4 KB never read
   constexpr int STAGE = WG_A_BYTES + B_BYTES;
-  constexpr int BQ = TN == 4 ? 3 : 2;                // x-tile load instructions per wavefront and K-tile
-  constexpr int NL = 3 + BQ;                         // loads per wavefront and K-tile
+  constexpr int AQ = 24 / NW;                        // dy-tile load instructions per wavefront and K-tile
+  constexpr int BQ = TN == 4 ? 24 / NW : 2;          // x-tile load instructions per wavefront and K-tile
+  constexpr int NL = AQ + BQ;                        // loads per wavefront and K-tile
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -98,10 +106,10 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
 
   // ---- what this lane copies.  dy tile: instruction q of the wavefront fills rows 2*(wave+8q),
   // +1 (512 bytes each); the lane's row and 16-byte chunk, un-swizzled, give its source address.
-  unsigned avoff[3];
+  unsigned avoff[AQ];
 #pragma unroll
-  for (int q = 0; q < 3; ++q) {
-    const int row = 2 * (wave + 8 * q) + (lane >> 5);
+  for (int q = 0; q < AQ; ++q) {
+    const int row = 2 * (wave + NW * q) + (lane >> 5);
     const int lc = (lane & 31) ^ ((row & 3) << 2);
     const int co = co0 + lc * 8;
     avoff[q] = co < g.Cout ? (unsigned)(((k_begin + row) * g.Cout + co) * 2) : WG_OOB;
@@ -113,7 +121,7 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
   bool b_on[BQ];
 #pragma unroll
   for (int q = 0; q < BQ; ++q) {
-    const int row = TN == 4 ? 2 * (wave + 8 * q) + (lane >> 5) : 4 * (wave + 8 * q) + (lane >> 4);
+    const int row = TN == 4 ? 2 * (wave + NW * q) + (lane >> 5) : 4 * (wave + NW * q) + (lane >> 4);
     const int pc = TN == 4 ? (lane & 31) : (lane & 15);
     const int lc = pc ^ ((row & 3) << 2);
     const int ci = ci0 + lc * 8;
@@ -126,15 +134,15 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
   }
   auto issue = [&](int stage_off) __attribute__((always_inline)) {
 #pragma unroll
-    for (int q = 0; q < 3; ++q) {
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rdy, (wg_lds_void*)(smem + stage_off + (wave + 8 * q) * 1024), 16,
+    for (int q = 0; q < AQ; ++q) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rdy, (wg_lds_void*)(smem + stage_off + (wave + NW * q) * 1024), 16,
                                                avoff[q], 0, 0, 0);
       avoff[q] += (unsigned)(WG_BK * 2) * (unsigned)g.Cout;  // (an offset beyond the extent stays beyond it)
     }
 #pragma unroll
     for (int q = 0; q < BQ; ++q) {
       const bool ok = b_on[q] && (unsigned)(b_y[q] + du) < (unsigned)H && (unsigned)(b_x[q] + dv) < (unsigned)W;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (wg_lds_void*)(smem + stage_off + WG_A_BYTES + (wave + 8 * q) * 1024),
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (wg_lds_void*)(smem + stage_off + WG_A_BYTES + (wave + NW * q) * 1024),
                                                16, ok ? b_lin[q] : WG_OOB, 0, 0, 0);
       b_lin[q] += (unsigned)(WG_BK * 2) * (unsigned)g.Cin;
       int nx = b_x[q] + g.step_r, ny = b_y[q] + g.step_q;
@@ -151,10 +159,10 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
   const int j16 = lane & 15, blk = lane >> 4;
   const int krow = 8 * (blk >> 1) + (j16 >> 2);
   const int swz = ((j16 >> 2) & 3) << 2;  // = (pixel & 3) << 2 for every step and half
-  int aoff[2], boff[TN];
+  int aoff[TM], boff[TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int col = wm * 64 + i * 32 + 16 * (blk & 1) + 4 * (j16 & 3);
+  for (int i = 0; i < TM; ++i) {
+    const int col = wm * (32 * TM) + i * 32 + 16 * (blk & 1) + 4 * (j16 & 3);
     aoff[i] = krow * 512 + (((col >> 3) ^ swz) << 4) + (col & 7) * 2;
   }
 #pragma unroll
@@ -163,9 +171,9 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
     boff[j] = WG_A_BYTES + krow * BPITCH + (((col >> 3) ^ swz) << 4) + (col & 7) * 2;
   }
 
-  floatx16 acc[2][TN];
+  floatx16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -173,16 +181,17 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
 
   // Bias gradient = column sums of dy: the blocks of the centre tap (first input-channel tile)
   // add up the dy tile they hold in LDS anyway.  Thread -> one 16-byte chunk (8 channels) of three
-  // pixel rows per K-tile; the 16 row groups are added in a fixed order at the end.
+  // (six) pixel rows per K-tile; the 16 (8) row groups are added in a fixed order at the end.
   const bool do_bias = (g.bias_part != nullptr || g.bias_acc != nullptr) && tap == (g.taps == 9 ? 4 : 0) && tile_n == 0;
   float bsum[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) bsum[e] = 0.f;
   auto bias_rows = [&](int stage_off) __attribute__((always_inline)) {
+    constexpr int RPT = WG_BK / (NT / 32);  // rows per thread
     const int c = tid & 31, rg = tid >> 5;
 #pragma unroll
-    for (int rr = 0; rr < 3; ++rr) {
-      const int row = rg * 3 + rr;
+    for (int rr = 0; rr < RPT; ++rr) {
+      const int row = rg * RPT + rr;
       const uint4 v = *reinterpret_cast<const uint4*>(smem + stage_off + row * 512 + ((c ^ ((row & 3) << 2)) << 4));
       const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -193,10 +202,10 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
     }
   };
 
-  bf16x8 fa[2][2], fb[2][TN];
+  bf16x8 fa[2][TM], fb[2][TN];
   auto read_frags = [&](int par, int stage_off, int ks) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) fa[par][i] = wg_read_tr(smem, stage_off + aoff[i] + ks * 16 * 512);
+    for (int i = 0; i < TM; ++i) fa[par][i] = wg_read_tr(smem, stage_off + aoff[i] + ks * 16 * 512);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       // (the second half of the pair is 4 rows further: wg_read_tr adds 4 * 512, the x tile's rows
@@ -211,26 +220,30 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
   };
   auto mma = [&](int par) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[par][i], fb[par][j], acc[i][j], 0, 0, 0);
   };
 
-  // ---- prologue: three K-tiles in flight
+  // ---- prologue: three K-tiles in flight.  Every wavefront issues the loads of every K-tile up to
+  // three beyond the (even) number the loop runs over - past the split's range they come back as
+  // zeros or are never multiplied - so the wait counts are the same in every step, and the loop body
+  // has no branch that carries an accumulator or an operand fragment (a conditional second half, or
+  // conditional operand reads, cost a register copy per accumulator and iteration).
+  const int nk2 = (nk + 1) & ~1;
   issue(0);
-  if (nk > 1) issue(STAGE);
-  if (nk > 2) issue(2 * STAGE);
-  if (nk > 2) { if (NL == 6) wg_wait_vmcnt12(); else wg_wait_vmcnt10(); }
-  else if (nk > 1) { if (NL == 6) wg_wait_vmcnt6(); else wg_wait_vmcnt5(); }
-  else wg_wait_vmcnt0();
+  issue(STAGE);
+  issue(2 * STAGE);
+  if (NL == 6) wg_wait_vmcnt12(); else wg_wait_vmcnt10();  // the first tile is in LDS
+  static_assert(NL == 5 || NL == 6, "wait counts");
   wg_fence();
   __builtin_amdgcn_s_barrier();
   wg_fence();
   read_frags(0, 0, 0);
 
   // ---- one K-tile: three 16-pixel steps; `par` = fragment set that holds step 0
-  auto tile_body = [&](auto par_t, int kt, int st, int st_next) __attribute__((always_inline)) {
+  auto tile_body = [&](auto par_t, int st, int st_next) __attribute__((always_inline)) {
     constexpr int P0 = decltype(par_t)::value;
     if (do_bias) bias_rows(st);
     read_frags(P0 ^ 1, st, 1);
@@ -241,30 +254,32 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
     __builtin_amdgcn_sched_barrier(0);
     mma(P0 ^ 1);
     __builtin_amdgcn_sched_barrier(0);
-    // every LDS read of this K-tile has returned; the next tile's loads were issued two sections ago,
-    // the one after it may still be in flight
+    // every LDS read of this K-tile has returned; of the two K-tiles in flight the older has to have landed
     wg_wait_lds();
-    if (kt + 2 < nk) { if (NL == 6) wg_wait_vmcnt6(); else wg_wait_vmcnt5(); }
-    else wg_wait_vmcnt0();
+    if (NL == 6) wg_wait_vmcnt6(); else wg_wait_vmcnt5();
     wg_fence();
     __builtin_amdgcn_s_barrier();
     wg_fence();
-    if (kt + 3 < nk) issue(st);  // into the stage this K-tile has released
-    if (kt + 1 < nk) read_frags(P0 ^ 1, st_next, 0);
+    issue(st);  // three K-tiles ahead, into the stage this K-tile has released
+    read_frags(P0 ^ 1, st_next, 0);
     __builtin_amdgcn_sched_barrier(0);
     mma(P0);
     __builtin_amdgcn_sched_barrier(0);
   };
   int st = 0;
-  for (int kt = 0; kt < nk; kt += 2) {
+  for (int kt = 0; kt < nk2; kt += 2) {
     const int st1 = st == 2 * STAGE ? 0 : st + STAGE;
-    tile_body(std::integral_constant<int, 0>{}, kt, st, st1);
-    if (kt + 1 < nk) {
-      const int st2 = st1 == 2 * STAGE ? 0 : st1 + STAGE;
-      tile_body(std::integral_constant<int, 1>{}, kt + 1, st1, st2);
-      st = st2;
-    }
+    const int st2 = st1 == 2 * STAGE ? 0 : st1 + STAGE;
+    tile_body(std::integral_constant<int, 0>{}, st, st1);
+    tile_body(std::integral_constant<int, 1>{}, st1, st2);
+    st = st2;
   }
+  // the loads issued past the last K-tile still target the stages
+  wg_wait_vmcnt0();
+  wg_wait_lds();
+  wg_fence();
+  __builtin_amdgcn_s_barrier();
+  wg_fence();
 
   if (do_bias) {  // (uniform over the block) [16 row groups][256 channels] through LDS, summed in order
     wg_wait_lds();
@@ -279,7 +294,7 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
     if (tid < 256 && co0 + tid < g.Cout) {
       float t = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) t += sb[r * 256 + tid];
+      for (int r = 0; r < NT / 32; ++r) t += sb[r * 256 + tid];
       if (g.bias_acc) g.bias_acc[co0 + tid] += t;  // (this block alone owns these channels)
       else g.bias_part[(size_t)split * g.Cout + co0 + tid] = t;
     }
@@ -289,22 +304,23 @@ __device__ __forceinline__ void conv_wgrad_tr_body(const WgArgs& g, int bid) {  
   const bool accumulate = g.acc_out != nullptr;  // every output entry belongs to this block alone: a plain add
   float* out = accumulate ? g.acc_out : g.part + ((size_t)(split * g.taps + tap) * g.Cout) * g.Cin;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int ci = ci0 + wn * (32 * TN) + j * 32 + lrow;
       if (ci >= g.Cin) continue;
+      wg_fence();  // one tile's loads and stores at a time (hoisted together they would not fit in registers)
       float old[16];
       if (accumulate) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int co = co0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
+          const int co = co0 + wm * (32 * TM) + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
           old[r] = co < g.Cout ? out[(size_t)co * g.Cin + ci] : 0.f;
         }
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int co = co0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
+        const int co = co0 + wm * (32 * TM) + i * 32 + 8 * (r >> 2) + 4 * lgrp + (r & 3);
         if (co < g.Cout) out[(size_t)co * g.Cin + ci] = accumulate ? old[r] + acc[i][j][r] : acc[i][j][r];
       }
     }
@@ -316,6 +332,7 @@ __global__ __launch_bounds__(512) void conv_wgrad_tr_kernel_n256(WgArgs g) {
 __global__ __launch_bounds__(512) void conv_wgrad_tr_kernel_n128(WgArgs g) {
   conv_wgrad_tr_body<2>(g, (int)xcd_grouped(blockIdx.x, gridDim.x));
 }
+
 // Many products in one launch (the weight gradients of all linear layers of a stage: nothing later in
 // a backward pass depends on them): block -> (product, block of that product) through a table;
 // every product runs unsplit and adds its result straight into the gradient arena.
@@ -327,7 +344,6 @@ __global__ __launch_bounds__(512) void wgrad_grouped_kernel(const WgArgs* __rest
   const WgArgs g = tasks[t];
   conv_wgrad_tr_body<4>(g, b - (int)task_block0[t]);
 }
-
 constexpr size_t wg_lds_bytes(int tn) { return 3 * (size_t)(WG_A_BYTES + (tn == 4 ? WG_BK * 512 : 16 * 1024)); }
 
 bool wg_attr_ok() {
@@ -337,6 +353,7 @@ bool wg_attr_ok() {
                              (int)wg_lds_bytes(4)) == hipSuccess &&
                  hipFuncSetAttribute((const void*)wgrad_grouped_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)wg_lds_bytes(4)) == hipSuccess &&
+
                  hipFuncSetAttribute((const void*)conv_wgrad_tr_kernel_n128, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)wg_lds_bytes(2)) == hipSuccess
              ? 1
