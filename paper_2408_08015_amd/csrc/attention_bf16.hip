@@ -161,39 +161,30 @@ __global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __rest
   if (g == 0) lse[((long)b * H + h) * S + q] = m_run + __logf(l_run);
 }
 
-// ------------------------------------------------------------------ backward helpers
-// Dsum[b][h][q] = sum_d dO[q][d] * O[q][d]
-__global__ void attn_dsum_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
-                                 float* __restrict__ dsum, int S, int D, int H, long total) {
-  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;  // (b, q, h)
-  if (i >= total) return;
-  int h = (int)(i % H);
-  long bq = i / H;
-  int q = (int)(bq % S);
-  long b = bq / S;
-  const bf16_t* po = o + bq * D + h * HD;
-  const bf16_t* pd = d_o + bq * D + h * HD;
+// ------------------------------------------------------------------ backward
+// Half of Dsum[q] = sum_d dO[q][d] * O[q][d]: the 32 elements d = 16 t + 8 g + e (t < 4, e < 8) of one row, in
+// that order; Dsum = half(g = 0) + half(g = 1).  Both backward roles form it this way (bitwise the same value).
+__device__ __forceinline__ float dsum_half(const bf16_t* __restrict__ po, const bf16_t* __restrict__ pd, int g) {
   float s = 0.f;
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    uint4 a = *reinterpret_cast<const uint4*>(po + c * 8);
-    uint4 d = *reinterpret_cast<const uint4*>(pd + c * 8);
-    const uint32_t* aw = reinterpret_cast<const uint32_t*>(&a);
-    const uint32_t* dw = reinterpret_cast<const uint32_t*>(&d);
+  for (int t = 0; t < 4; ++t) {
+    const uint4 a = *reinterpret_cast<const uint4*>(po + 16 * t + 8 * g);
+    const uint4 d = *reinterpret_cast<const uint4*>(pd + 16 * t + 8 * g);
+    const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, dw[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       s += __uint_as_float(aw[k] << 16) * __uint_as_float(dw[k] << 16);
       s += __uint_as_float(aw[k] & 0xffff0000u) * __uint_as_float(dw[k] & 0xffff0000u);
     }
   }
-  dsum[(b * H + h) * S + q] = s;
+  return s;
 }
 
 // dK, dV: a wavefront owns 32 keys (lane = key), loops over query tiles.
 __device__ __forceinline__ void attention_bwd_dkv_body(const bf16_t* __restrict__ qkv,
                                                        const bf16_t* __restrict__ d_o,
                                                        const float* __restrict__ lse,
-                                                       const float* __restrict__ dsum,
+                                                       const bf16_t* __restrict__ o,
                                                        bf16_t* __restrict__ dqkv, int S, int D, int H, int bx,
                                                        unsigned char* smem) {
   const int TS = S + 8;
@@ -213,9 +204,13 @@ __device__ __forceinline__ void attention_bwd_dkv_body(const bf16_t* __restrict_
   stage_rows(sdO, dobase, D, S);
   stage_rows_T(sQt, base, ld, S);
   stage_rows_T(sdOt, dobase, D, S);
-  for (int i = threadIdx.x; i < S; i += blockDim.x) {
-    sL[i] = lse[((long)b * H + h) * S + i];
-    sD[i] = dsum[((long)b * H + h) * S + i];
+  for (int i = threadIdx.x; i < S; i += blockDim.x) sL[i] = lse[((long)b * H + h) * S + i];
+  for (int i = threadIdx.x; i < 2 * S; i += blockDim.x) {  // thread -> (row, half): neighbouring lanes hold the two halves
+    const int row = i >> 1;
+    const long at = ((long)b * S + row) * D + h * HD;
+    const float half = dsum_half(o + at, d_o + at, i & 1);
+    const float other = __shfl_xor(half, 1);
+    if (!(i & 1)) sD[row] = half + other;
   }
   __syncthreads();
   const int k0 = bx * 128 + wave * 32;
@@ -281,7 +276,7 @@ __device__ __forceinline__ void attention_bwd_dkv_body(const bf16_t* __restrict_
 __device__ __forceinline__ void attention_bwd_dq_body(const bf16_t* __restrict__ qkv,
                                                       const bf16_t* __restrict__ d_o,
                                                       const float* __restrict__ lse,
-                                                      const float* __restrict__ dsum,
+                                                      const bf16_t* __restrict__ o,
                                                       bf16_t* __restrict__ dqkv, int S, int D, int H, int bx,
                                                       unsigned char* smem) {
   const int TS = S + 8;
@@ -307,7 +302,13 @@ __device__ __forceinline__ void attention_bwd_dq_body(const bf16_t* __restrict__
     dof[t] = ld_frag(d_o + ((long)b * S + q) * D + h * HD + 16 * t + 8 * g);
   }
   const float lq = lse[((long)b * H + h) * S + q];
-  const float dq_sum = dsum[((long)b * H + h) * S + q];
+  float dq_sum;
+  {
+    const long at = ((long)b * S + q) * D + h * HD;
+    const float half = dsum_half(o + at, d_o + at, g);
+    const float other = __shfl_xor(half, 32);
+    dq_sum = g == 0 ? half + other : other + half;  // half(0) + half(1) in both lanes
+  }
   floatx16 dq[2];
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
@@ -359,11 +360,11 @@ size_t lds_dq(int S) { return ((size_t)2 * S * RS + (size_t)HD * (S + 8)) * 2; }
 __global__ __launch_bounds__(256) void attention_bwd_kernel(const bf16_t* __restrict__ qkv,
                                                             const bf16_t* __restrict__ d_o,
                                                             const float* __restrict__ lse,
-                                                            const float* __restrict__ dsum,
+                                                            const bf16_t* __restrict__ o,
                                                             bf16_t* __restrict__ dqkv, int S, int D, int H, int nx) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  if ((int)blockIdx.x < nx) attention_bwd_dkv_body(qkv, d_o, lse, dsum, dqkv, S, D, H, (int)blockIdx.x, smem);  // uniform
-  else attention_bwd_dq_body(qkv, d_o, lse, dsum, dqkv, S, D, H, (int)blockIdx.x - nx, smem);
+  if ((int)blockIdx.x < nx) attention_bwd_dkv_body(qkv, d_o, lse, o, dqkv, S, D, H, (int)blockIdx.x, smem);  // uniform
+  else attention_bwd_dq_body(qkv, d_o, lse, o, dqkv, S, D, H, (int)blockIdx.x - nx, smem);
 }
 
 void allow_lds(const void* fn, size_t bytes) {
@@ -385,13 +386,12 @@ void attention_fwd_bf16(hipStream_t st, const bf16_t* qkv, bf16_t* o, float* lse
 
 void attention_bwd_bf16(hipStream_t st, const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o, const float* lse,
                         bf16_t* dqkv, float* dsum, int B, int S, int D, int heads) {
-  long total = (long)B * S * heads;
-  KLAUNCH(attn_dsum_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, o, d_o, dsum, S, D, heads, total);
+  (void)dsum;  // the row sums of dO * O are formed inside the kernel (they were a launch of their own)
   const size_t l1 = lds_dkv(S), l2 = lds_dq(S), lds = l1 > l2 ? l1 : l2;
   allow_lds((const void*)attention_bwd_kernel, lds);
   const int nx = (S + 127) / 128;
   dim3 grid(2 * nx, heads, B);
-  KLAUNCH(attention_bwd_kernel, grid, dim3(256), lds, st, qkv, d_o, lse, dsum, dqkv, S, D, heads, nx);
+  KLAUNCH(attention_bwd_kernel, grid, dim3(256), lds, st, qkv, d_o, lse, o, dqkv, S, D, heads, nx);
 }
 
 }  // namespace ast
