@@ -28,7 +28,7 @@ __device__ __forceinline__ bf16x8 pack_frag(const float* f) {
   uint4 v;
   uint32_t* w = reinterpret_cast<uint32_t*>(&v);
 #pragma unroll
-  for (int k = 0; k < 4; ++k) w[k] = (uint32_t)f2bf(f[2 * k]) | ((uint32_t)f2bf(f[2 * k + 1]) << 16);
+  for (int k = 0; k < 4; ++k) w[k] = f2bf_pk(f[2 * k], f[2 * k + 1]);
   return __builtin_bit_cast(bf16x8, v);
 }
 // two 8-byte reads -> one operand fragment (slots e = 0..3 and 4..7)
@@ -154,8 +154,8 @@ __global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __rest
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
       uint2 v;
-      v.x = (uint32_t)f2bf(oacc[dt][4 * r4] * inv) | ((uint32_t)f2bf(oacc[dt][4 * r4 + 1] * inv) << 16);
-      v.y = (uint32_t)f2bf(oacc[dt][4 * r4 + 2] * inv) | ((uint32_t)f2bf(oacc[dt][4 * r4 + 3] * inv) << 16);
+      v.x = f2bf_pk(oacc[dt][4 * r4] * inv, oacc[dt][4 * r4 + 1] * inv);
+      v.y = f2bf_pk(oacc[dt][4 * r4 + 2] * inv, oacc[dt][4 * r4 + 3] * inv);
       *reinterpret_cast<uint2*>(orow + dt * 32 + 8 * r4 + 4 * g) = v;
     }
   if (g == 0) lse[((long)b * H + h) * S + q] = m_run + __logf(l_run);
@@ -263,10 +263,10 @@ __device__ __forceinline__ void attention_bwd_dkv_body(const bf16_t* __restrict_
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
       uint2 a, c;
-      a.x = (uint32_t)f2bf(dk[dt][4 * r4] * scale) | ((uint32_t)f2bf(dk[dt][4 * r4 + 1] * scale) << 16);
-      a.y = (uint32_t)f2bf(dk[dt][4 * r4 + 2] * scale) | ((uint32_t)f2bf(dk[dt][4 * r4 + 3] * scale) << 16);
-      c.x = (uint32_t)f2bf(dv[dt][4 * r4]) | ((uint32_t)f2bf(dv[dt][4 * r4 + 1]) << 16);
-      c.y = (uint32_t)f2bf(dv[dt][4 * r4 + 2]) | ((uint32_t)f2bf(dv[dt][4 * r4 + 3]) << 16);
+      a.x = f2bf_pk(dk[dt][4 * r4] * scale, dk[dt][4 * r4 + 1] * scale);
+      a.y = f2bf_pk(dk[dt][4 * r4 + 2] * scale, dk[dt][4 * r4 + 3] * scale);
+      c.x = f2bf_pk(dv[dt][4 * r4], dv[dt][4 * r4 + 1]);
+      c.y = f2bf_pk(dv[dt][4 * r4 + 2], dv[dt][4 * r4 + 3]);
       *reinterpret_cast<uint2*>(krow + dt * 32 + 8 * r4 + 4 * g) = a;
       *reinterpret_cast<uint2*>(vrow + dt * 32 + 8 * r4 + 4 * g) = c;
     }
@@ -343,8 +343,8 @@ __device__ __forceinline__ void attention_bwd_dq_body(const bf16_t* __restrict__
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
       uint2 a;
-      a.x = (uint32_t)f2bf(dq[dt][4 * r4] * scale) | ((uint32_t)f2bf(dq[dt][4 * r4 + 1] * scale) << 16);
-      a.y = (uint32_t)f2bf(dq[dt][4 * r4 + 2] * scale) | ((uint32_t)f2bf(dq[dt][4 * r4 + 3] * scale) << 16);
+      a.x = f2bf_pk(dq[dt][4 * r4] * scale, dq[dt][4 * r4 + 1] * scale);
+      a.y = f2bf_pk(dq[dt][4 * r4 + 2] * scale, dq[dt][4 * r4 + 3] * scale);
       *reinterpret_cast<uint2*>(qrow + dt * 32 + 8 * r4 + 4 * g) = a;
     }
 }

@@ -23,7 +23,7 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
   uint4 v;
   uint32_t* w = reinterpret_cast<uint32_t*>(&v);
 #pragma unroll
-  for (int k = 0; k < 4; ++k) w[k] = (uint32_t)f2bf(f[2 * k]) | ((uint32_t)f2bf(f[2 * k + 1]) << 16);
+  for (int k = 0; k < 4; ++k) w[k] = f2bf_pk(f[2 * k], f[2 * k + 1]);
   return v;
 }
 __device__ __forceinline__ float gelu_grad(float x) { return gelu_grad_fast(x); }
