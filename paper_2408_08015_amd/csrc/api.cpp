@@ -64,6 +64,11 @@ void free_stage(ast::Stage& s) {
   s.pack_tasks = nullptr;
   s.pack_block_task = nullptr;
   s.pack_nblocks = 0;
+  if (s.lsh_tasks) (void)hipFree(s.lsh_tasks);
+  if (s.lsh_block_task) (void)hipFree(s.lsh_block_task);
+  s.lsh_tasks = nullptr;
+  s.lsh_block_task = nullptr;
+  s.lsh_nblocks = 0;
   if (s.red_tasks) (void)hipFree(s.red_tasks);
   if (s.red_tasks_static) (void)hipFree(s.red_tasks_static);
   s.red_tasks_static = nullptr;

@@ -551,6 +551,47 @@ static ast_status build_pack_tasks(Stage& s, std::string& err) {
   return AST_OK;
 }
 
+// The bf16 copies of all dense-layer weight matrices (linear layers, attention projections) in one launch.
+static ast_status build_linear_shadow_tasks(Stage& s, std::string& err) {
+  if (!s.bf16) return AST_OK;
+  std::vector<LinShadowTask> tasks;
+  std::vector<unsigned short> block_task;
+  auto add = [&](const float* w, size_t sh_off, size_t sh2_off, int Cout, int Cin, size_t R) {
+    LinShadowTask t = {};
+    t.w = w; t.sh = s.shadow + sh_off; t.sht = s.shadow + sh2_off; t.Cout = Cout; t.Cin = Cin;
+    t.tiled = linear_dl_supported(R, Cin, Cout) ? 1 : 0;   // the kernel each direction will run decides the layout
+    t.tiled_t = linear_dl_supported(R, Cout, Cin) ? 1 : 0;
+    t.block0 = (unsigned)block_task.size();
+    for (unsigned b = 0; b < linear_shadow_blocks(Cout, Cin); ++b) block_task.push_back((unsigned short)tasks.size());
+    tasks.push_back(t);
+  };
+  for (const Op& op : s.ops) {
+    if (tasks.size() + 2 >= 65535) return AST_OK;  // per-layer launches instead
+    const Act& I = s.acts[op.in];
+    if (op.kind == OP_LINEAR) {
+      add(s.W + op.w_off, op.sh_off, op.sh2_off, op.cout, op.cin, (size_t)I.n * I.h * I.w);
+    } else if (op.kind == OP_MHA) {
+      const int D = op.cin;
+      const size_t R = (size_t)I.n * I.h;
+      const float* wq = s.W + op.w_off;
+      add(wq, op.sh_off, op.sh2_off, 3 * D, D, R);
+      add(wq + (size_t)3 * D * D + 3 * D, op.sh_off + (size_t)3 * D * D, op.sh2_off + (size_t)3 * D * D, D, D, R);
+    }
+  }
+  if (tasks.size() < 2) return AST_OK;
+  hipError_t e;
+  if ((e = hipMalloc(&s.lsh_tasks, tasks.size() * sizeof(LinShadowTask))) != hipSuccess ||
+      (e = hipMalloc((void**)&s.lsh_block_task, block_task.size() * sizeof(unsigned short))) != hipSuccess ||
+      (e = hipMemcpy(s.lsh_tasks, tasks.data(), tasks.size() * sizeof(LinShadowTask), hipMemcpyHostToDevice)) != hipSuccess ||
+      (e = hipMemcpy(s.lsh_block_task, block_task.data(), block_task.size() * sizeof(unsigned short),
+                     hipMemcpyHostToDevice)) != hipSuccess) {
+    err = std::string("weight copy task table: ") + hipGetErrorString(e);
+    return e == hipErrorOutOfMemory ? AST_ENOMEM : AST_EHIP;
+  }
+  s.lsh_nblocks = (int)block_task.size();
+  return AST_OK;
+}
+
 // Grouped weight gradients (bf16 stages): every linear layer and attention projection whose operands lie
 // in the stash and the workspace (i.e. not in a buffer of the caller) becomes one product of a single
 // launch at the end of the backward pass.  ASTEROID_WGRAD_GROUP=0 keeps the per-layer launches.
@@ -659,6 +700,7 @@ static ast_status build_wgrad_groups(Stage& s, char* static_ws, std::string& err
 
 ast_status build_reduce_tasks(Stage& s, std::string& err) {
   if (ast_status r = build_pack_tasks(s, err)) return r;
+  if (ast_status r = build_linear_shadow_tasks(s, err)) return r;
   char* static_ws = nullptr;
   if (s.ws_bytes <= kStaticScratchBytes) {
     std::string ignore;
@@ -770,6 +812,8 @@ ast_status build_reduce_tasks(Stage& s, std::string& err) {
 ast_status refresh_shadow(Stage& s, std::string& err) {
   if (s.pack_nblocks)
     pw_pack_all_f32(s.stream, static_cast<const PackTask*>(s.pack_tasks), s.pack_block_task, s.wpack, s.pack_nblocks);
+  if (s.lsh_nblocks)
+    linear_weight_shadow_all_bf16(s.stream, static_cast<const LinShadowTask*>(s.lsh_tasks), s.lsh_block_task, s.lsh_nblocks);
   for (const Op& op : s.ops) {
     if (op.kind == OP_CONV_PW) {
       if (s.pack_nblocks) continue;
@@ -796,6 +840,8 @@ ast_status refresh_shadow(Stage& s, std::string& err) {
       conv_weight_shadow_bf16(s.stream, s.W + op.w_off, s.shadow + op.sh_off, s.shadow + op.sh2_off, op.cout,
                               op.cin, op.k, conv_bf16_uses_halo(I.n, I.h, I.w, op.cin, op.cout, op.k),
                               conv_bf16_uses_halo(I.n, I.h, I.w, op.cout, op.cin, op.k));
+    } else if (s.lsh_nblocks) {
+      continue;  // the dense-layer copies went out in one launch above
     } else if (op.kind == OP_LINEAR) {
       const Act& I = s.acts[op.in];  // the kernel each direction will run decides the layout of its copy
       const size_t R = (size_t)I.n * I.h * I.w;

@@ -19,6 +19,18 @@ void conv_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh_fwd, bf1
 // linear: master [Cout][Cin] -> copy [Cout][Cin] and transpose [Cin][Cout]
 void linear_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh, bf16_t* sh_t, int Cout, int Cin,
                                bool tiled, bool tiled_t);
+// ... and for all dense layers of a stage in one launch: the table lives in device memory, block_task maps a
+// block to its matrix, a matrix takes linear_shadow_blocks() consecutive blocks from block0.
+struct LinShadowTask {
+  const float* w;
+  bf16_t* sh;
+  bf16_t* sht;
+  int Cout, Cin, tiled, tiled_t;
+  unsigned block0;
+};
+unsigned linear_shadow_blocks(int Cout, int Cin);
+void linear_weight_shadow_all_bf16(hipStream_t st, const LinShadowTask* tasks_dev, const unsigned short* block_task_dev,
+                                   int nblocks);
 
 // ---- dense 'same' convolution, stride 1, NHWC, k in {1,3}
 size_t conv_bf16_ws_bytes(int N, int H, int W, int Cin, int Cout, int k);

@@ -55,11 +55,12 @@ void conv_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh_fwd, bf1
 }
 
 // sh [Cout][Cin] and sht [Cin][Cout]; tiled: [K/64][rows][64] with K the contraction index of the
-// product that reads the copy (Cin for sh, Cout for sht) - the layout of the direct-to-LDS kernel
-__global__ void linear_shadow_kernel(const float* __restrict__ w, bf16_t* __restrict__ sh,
-                                     bf16_t* __restrict__ sht, int Cout, int Cin, int tiled, int tiled_t) {
+// product that reads the copy (Cin for sh, Cout for sht) - the layout of the direct-to-LDS kernel.
+// One 32 x 32 tile (bx: ci, by: co) per block.
+__device__ __forceinline__ void linear_shadow_tile(const float* __restrict__ w, bf16_t* __restrict__ sh,
+                                                   bf16_t* __restrict__ sht, int Cout, int Cin, int tiled, int tiled_t,
+                                                   int bx, int by) {
   __shared__ float tile[32][33];
-  int bx = blockIdx.x * 32, by = blockIdx.y * 32;  // bx: ci, by: co
   int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
   for (int r = ty; r < 32; r += 8) {
     int co = by + r, ci = bx + tx;
@@ -75,10 +76,26 @@ __global__ void linear_shadow_kernel(const float* __restrict__ w, bf16_t* __rest
       sht[tiled_t ? ((size_t)(co >> 6) * Cin + ci) * 64 + (co & 63) : (size_t)ci * Cout + co] = f2bf(tile[tx][r]);
   }
 }
+__global__ void linear_shadow_kernel(const float* __restrict__ w, bf16_t* __restrict__ sh,
+                                     bf16_t* __restrict__ sht, int Cout, int Cin, int tiled, int tiled_t) {
+  linear_shadow_tile(w, sh, sht, Cout, Cin, tiled, tiled_t, blockIdx.x * 32, blockIdx.y * 32);
+}
 void linear_weight_shadow_bf16(hipStream_t st, const float* w, bf16_t* sh, bf16_t* sh_t, int Cout, int Cin, bool tiled,
                                bool tiled_t) {
   KLAUNCH(linear_shadow_kernel, dim3(cdivu(Cin, 32), cdivu(Cout, 32)), dim3(256), 0, st, w, sh, sh_t, Cout, Cin,
           tiled ? 1 : 0, tiled_t ? 1 : 0);
+}
+// the copies of every dense layer of a stage in one launch: block -> (matrix, tile) through a table
+__global__ void linear_shadow_all_kernel(const LinShadowTask* __restrict__ tasks, const unsigned short* __restrict__ block_task) {
+  const LinShadowTask t = tasks[block_task[blockIdx.x]];
+  const unsigned local = blockIdx.x - t.block0;
+  const unsigned nbx = (unsigned)(t.Cin + 31) / 32;
+  linear_shadow_tile(t.w, t.sh, t.sht, t.Cout, t.Cin, t.tiled, t.tiled_t, (int)(local % nbx) * 32, (int)(local / nbx) * 32);
+}
+unsigned linear_shadow_blocks(int Cout, int Cin) { return (unsigned)(cdivu(Cin, 32) * cdivu(Cout, 32)); }
+void linear_weight_shadow_all_bf16(hipStream_t st, const LinShadowTask* tasks_dev, const unsigned short* block_task_dev,
+                                   int nblocks) {
+  if (nblocks > 0) KLAUNCH(linear_shadow_all_kernel, dim3((unsigned)nblocks), dim3(256), 0, st, tasks_dev, block_task_dev);
 }
 
 __global__ void f32_to_bf16_kernel(const float* __restrict__ s, bf16_t* __restrict__ d, size_t n) {

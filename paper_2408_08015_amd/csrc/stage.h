@@ -130,6 +130,9 @@ struct Stage {
   void* pack_tasks = nullptr;            // PackTask[]: all packed pointwise-conv copies, one launch
   unsigned short* pack_block_task = nullptr;
   int pack_nblocks = 0;
+  void* lsh_tasks = nullptr;             // LinShadowTask[]: the bf16 copies of all dense-layer weights, one launch
+  unsigned short* lsh_block_task = nullptr;
+  int lsh_nblocks = 0;
   void* red_tasks = nullptr;             // RedTask[]
   void* red_tasks_static = nullptr;      // the same table with the partials' addresses in the static workspace
   char* static_ws = nullptr;             // this device's static workspace, if the stage fits into it
