@@ -157,3 +157,26 @@ def test_planning_time_at_the_papers_problem_size(PL):
     dt = time.time() - t0
     assert stages is not None and sum(y.values()) == 32 * len(stages)
     assert dt < 60.0
+
+
+def test_fixed_bytes_per_layer_enter_the_memory_check(PL):
+    """The optional fixed term (workspace, derived weight copies: outside Eq. (3)) adds its layer sum to the
+    stage footprint, NULL leaves the paper's formula, and Alg. 1 sees it: a micro-batch that fits without it
+    is cut down, and refused when the fixed bytes alone exceed the budget."""
+    L, N, B = 3, 1, 8
+    t = np.zeros((N, L, B + 1))
+    t[:, :, 1:] = np.arange(1, B + 1)[None, None, :]
+    act, w = [10.0, 20.0, 30.0], [100.0, 200.0, 400.0]
+    plain = PL.Problem(t, t, [1.0] * L, act, w, [3000.0], [[1.0]], B, 4)
+    fixed = PL.Problem(t, t, [1.0] * L, act, w, [3000.0], [[1.0]], B, 4, fixed=[5.0, 50.0, 500.0])
+    assert PL.stage_memory(plain, 1, 3, 3, 4) == 1200 + 600 + 3 * 200
+    assert PL.stage_memory(fixed, 1, 3, 3, 4) == 1200 + 600 + 3 * 200 + 550
+    assert PL.stage_memory(fixed, 0, 1, 1, 0) == 300 + 5
+    # whole model on the one device, K = 1: 2100 + 60 beta (+ 555) <= 3000
+    assert PL.allocate(plain, 0, 3, [0], 1)[0] == {0: 8}
+    tight = PL.Problem(t, t, [1.0] * L, act, w, [2100.0 + 60 * 8 + 100], [[1.0]], B, 4, fixed=[5.0, 50.0, 500.0])
+    assert PL.allocate(tight, 0, 3, [0], 1) is None                    # 2655 + 60 beta > 2680 for beta = 8: cannot hold B
+    none = PL.Problem(t, t, [1.0] * L, act, w, [2500.0], [[1.0]], B, 4, fixed=[5.0, 50.0, 500.0])
+    assert PL.allocate(none, 0, 3, [0], 1) is None                     # 2655 > 2500 even for an empty micro-batch
+    with pytest.raises(ValueError):
+        PL.Problem(t, t, [1.0] * L, act, w, [1.0], [[1.0]], B, 4, fixed=[1.0])
