@@ -640,6 +640,24 @@ def test_bf16_conv(A, cin, cout, k, hw, B):
     check(one_bf16(L, (cin, hw, hw), "nhwc", B=B), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
 
 
+@pytest.mark.parametrize("cin,cout,h,w,B,two", [
+    (64, 64, 5, 7, 1, False),       # one ragged tile, one 64-channel slice
+    (128, 72, 9, 13, 3, False),     # Cout neither a multiple of 64 nor of 128: ragged channel tile
+    (192, 320, 16, 16, 2, False),   # two 256-channel tiles, three slices
+    (64, 64, 63, 63, 2, False),     # the longest image row the halo buffer takes; 7938 pixels: ragged last tile
+    (64, 128, 40, 40, 3, True),     # 4800 pixels over persistent blocks; second conv: ReLU mask in the input gradient
+    (256, 256, 12, 10, 2, True),    # 256-channel weight-gradient tiles (splits over 240 pixels), masks, biases
+])
+def test_bf16_conv_halo_and_transposed_wgrad_shapes(A, cin, cout, h, w, B, two):
+    """Shapes chosen for the LDS-halo convolution (forward / input gradient) and the transposed-read weight
+    gradient: ragged pixel tiles and channel tiles, one to four channel slices, the row-length limit, image
+    borders inside a tile, and the ReLU mask of the layer in front applied in the input-gradient epilogue."""
+    L = [conv(cin, cout, 3, 1, 1, bias=True), simple("relu")]
+    if two:
+        L += [conv(cout, cout, 3, 1, 1, bias=True), simple("relu"), simple("maxpool2x2")]
+    check(one_bf16(L, (cin, h, w), "nhwc", B=B, M=2), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
+
+
 def test_bf16_conv_without_relu_and_maxpool(A):
     check(one_bf16([conv(16, 16, 3, 1, 1, bias=False)], (16, 6, 6), "nhwc"), tol_y=TOL_BF16, tol_g=TOL_BF16, rounds=1)
     L = [conv(8, 16, 3, 1, 1, bias=True), simple("relu"), simple("maxpool2x2")]
