@@ -243,8 +243,18 @@ def committed_traffic(workload, fam):
     return None
 
 
-def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3):
-    """One configuration: returns its record for the JSON line."""
+# Learning rate of the updates inside bench.py's loops.  The configurations state 0.01 for ONE update; the
+# bench runs tens of rounds back to back on the same unnormalised N(0,1) upstream gradients (|G| ~ 1e3), which
+# at 0.01 drives the bf16 stages' weights to inf / NaN within a few rounds - and a round of the VGG stage on
+# non-finite operands runs 6 % FASTER than on finite ones (3.65 against 3.89 ms: the matrix cores draw less
+# power, the clock rises).  The same kernels, bytes and flops run for any value of the scalar, so the timed
+# loop uses one that keeps every tensor finite over the whole run.  The parity tests use the stated 0.01.
+BENCH_LR = 1e-9
+
+
+def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3, K=1, forward_stream=False):
+    """One configuration: returns its record for the JSON line.  K = micro-batches in flight (stash
+    slots); forward_stream: the forward passes run on a second stream beside the backward passes."""
     import torch
     import paper_2408_08015_amd as A
     from asteroid_workloads import get_config, gen
@@ -254,9 +264,14 @@ def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3)
     dev = torch.device("cuda:0")
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     stream = torch.cuda.current_stream()
-    st = A.Stage(cfg.layers, cfg.B, cfg.M, 1, cfg.in_shape, cfg.dtype, cfg.layout, cfg.needs_input_grad,
+    K = min(K, cfg.M)
+    st = A.Stage(cfg.layers, cfg.B, cfg.M, K, cfg.in_shape, cfg.dtype, cfg.layout, cfg.needs_input_grad,
                  stream=stream.cuda_stream)
     st.set_params(inp["params"])
+    fwd_stream = None
+    if forward_stream:
+        fwd_stream = torch.cuda.Stream()   # default priority
+        st.set_forward_stream(fwd_stream.cuda_stream)
     B, M = cfg.B, cfg.M
     x = torch.from_numpy(inp["x"]).to(dev).to(tdt).contiguous()
     if cfg.loss_tail:
@@ -275,11 +290,14 @@ def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3)
     ls = [loss[4 * m:4 * m + 1] if cfg.loss_tail else None for m in range(M)]
 
     def one_round():
-        # K = 1: F0 B0 F1 B1 ... then the update
-        for m in range(M):
+        # K forward passes, then one backward / one forward (K = 1: F0 B0 F1 B1 ...), then the update
+        for m in range(K):
             st.forward(m, xs[m], labs[m], ys[m], ls[m])
+        for m in range(M):
             st.backward(m, dys[m], dxs[m])
-        st.step(cfg.lr, cfg.momentum)
+            if m + K < M:
+                st.forward(m + K, xs[m + K], labs[m + K], ys[m + K], ls[m + K])
+        st.step(BENCH_LR, cfg.momentum)
 
     for _ in range(warmup):
         one_round()
@@ -358,6 +376,38 @@ def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3)
             print(line, file=sys.stderr)
     mem = st.memory()
     st.close()
+    # ---- the same rounds with K = 3 stashes and the forward passes on a second stream (the forward of a later
+    # micro-batch runs beside the backward of an earlier one; bit-identical results): timed the same way,
+    # reported beside the headline figure, never in its place
+    two = None
+    if K == 1 and not forward_stream and cfg.M >= 2:
+        K2 = min(3, cfg.M)
+        st2 = A.Stage(cfg.layers, cfg.B, cfg.M, K2, cfg.in_shape, cfg.dtype, cfg.layout, cfg.needs_input_grad,
+                      stream=stream.cuda_stream)
+        st2.set_params(inp["params"])
+        fs2 = torch.cuda.Stream()   # default priority
+        st2.set_forward_stream(fs2.cuda_stream)
+
+        def round2():
+            for m in range(K2):
+                st2.forward(m, xs[m], labs[m], ys[m], ls[m])
+            for m in range(M):
+                st2.backward(m, dys[m], dxs[m])
+                if m + K2 < M:
+                    st2.forward(m + K2, xs[m + K2], labs[m + K2], ys[m + K2], ls[m + K2])
+            st2.step(BENCH_LR, cfg.momentum)
+
+        for _ in range(warmup):
+            round2()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(steps):
+            round2()
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t2) * 1e3 / steps
+        two = {"K": K2, "forward_stream": True, "ms_per_step": round(ms2, 4),
+               "value": round(M * B / (ms2 * 1e-3), 1), "unit": "samples/s", "act_stashes": K2}
+        st2.close()
     del xs, ys, dys, dxs, x, y, dy, dx
     torch.cuda.empty_cache()
     rec = {
@@ -368,6 +418,7 @@ def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3)
         "ms_per_step_median": round(statistics.median(per_round), 4), "ms_per_step_min": round(min(per_round), 4),
         "host_enqueue_ms_per_step": round((t_enq - t0) * 1e3 / steps, 4),
         "launches_per_step": round(launches_per_step, 1),
+        "K": K, "forward_stream": bool(forward_stream), "two_streams": two,
         "roofline": roofline, "step_roofline": step_roofline,
         "stage_bytes": {"mod": mem[0], "opt": mem[1], "act_per_mb": mem[2], "workspace": mem[3]},
         "cpu_baseline": cpu_baseline(cfg, inp) if cpu else None,
@@ -383,7 +434,8 @@ def run(args):
     head = args.workload or HEADLINE
     recs = {}
     for w in workloads:
-        recs[w], cfg = measure(w, args.steps, args.warmup, cpu=not args.no_cpu_baseline, profile_all=args.profile_all)
+        recs[w], cfg = measure(w, args.steps, args.warmup, cpu=not args.no_cpu_baseline, profile_all=args.profile_all,
+                               K=args.K, forward_stream=args.forward_stream)
         if w == head:
             head_cfg = cfg
     h = recs[head]
@@ -392,7 +444,7 @@ def run(args):
         "value": h["value"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": h["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": h["dtype"], "data": "synthetic",
-        "config": {"workload": h["workload"], "K": 1, "lr": head_cfg.lr, "momentum": head_cfg.momentum,
+        "config": {"workload": h["workload"], "K": h["K"], "forward_stream": h["forward_stream"], "lr": BENCH_LR, "lr_of_the_configuration": head_cfg.lr, "momentum": head_cfg.momentum,
                    "ms_per_step_median": h["ms_per_step_median"], "ms_per_step_min": h["ms_per_step_min"],
                    "host_enqueue_ms_per_step": h["host_enqueue_ms_per_step"],
                    "launches_per_step": h["launches_per_step"], "stage_bytes": h["stage_bytes"]},
@@ -448,6 +500,9 @@ def main():
     ap.add_argument("--workload", default=None, help="one configuration only (default: cfg1 .. cfg5, headline cfg4)")
     ap.add_argument("--profile-all", action="store_true", help="time every kernel, table on stderr")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--K", type=int, default=1, help="micro-batches in flight (stash slots): K forward passes, then 1F1B")
+    ap.add_argument("--forward-stream", action="store_true",
+                    help="forward passes on a second stream (needs --K 2 or more to overlap anything)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); "

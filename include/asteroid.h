@@ -138,6 +138,20 @@ ast_status asteroid_stage_forward(asteroid_stage* s, int32_t mb, const void* x_d
 ast_status asteroid_stage_backward(asteroid_stage* s, int32_t mb, const void* dy_dev,
                                    void* dx_dev);
 
+/* Optional second stream for the forward passes.  A stage that keeps K >= 2 micro-batches in flight
+ * (Sec. 3.2: K_p forward passes before one-forward-one-backward is enforced) is handed the forward of a
+ * later micro-batch before the backward of an earlier one; the two are independent (different stash
+ * slots, G is written by backward passes only, W changes in asteroid_stage_step only).  After this call
+ * asteroid_stage_forward enqueues on `hip_stream` (a hipStream_t of default priority) and
+ * asteroid_stage_backward / _step stay on the stream given to create, so the two passes may overlap on
+ * the GPU; the library orders what does depend through events: backward(mb) behind forward(mb), a
+ * forward that reuses a stash slot behind the backward that released it, the first forward of a round
+ * behind everything the main stream holds when it is called (the previous round's weight update).  Results are bit-identical to the one-stream execution.  The caller's part:
+ * x_dev / labels_dev are ready, and y_dev / loss_dev are read, in the order of `hip_stream`; dy_dev /
+ * dx_dev in the order of the main stream.  NULL (or the main stream) returns to one stream.  Waits for
+ * the stage's work.  AST_ESTATE inside a round (after a forward and before the step). */
+ast_status asteroid_stage_set_forward_stream(asteroid_stage* s, void* hip_stream);
+
 /* For callers that cannot allocate or let a library allocate on their behalf (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): asteroid_stage_backward with the
  * stage's workspace - activation gradients, per-operator scratch, reduction partials - taken from

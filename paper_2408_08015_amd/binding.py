@@ -54,6 +54,7 @@ def load_library():
     vp, i32, f32p, szp = C.c_void_p, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_size_t)
     lib.asteroid_stage_create.argtypes = [C.POINTER(ast_layer), i32, C.POINTER(ast_stage_cfg), vp, C.POINTER(vp)]
     lib.asteroid_stage_forward.argtypes = [vp, i32, vp, vp, vp, vp]
+    lib.asteroid_stage_set_forward_stream.argtypes = [vp, vp]
     lib.asteroid_stage_backward.argtypes = [vp, i32, vp, vp]
     lib.asteroid_stage_backward_static.argtypes = [vp, i32, vp, vp]
     lib.asteroid_stage_step.argtypes = [vp, C.c_float, C.c_float]
@@ -159,6 +160,9 @@ class Stage:
 
     def forward(self, mb, x, labels=None, y=None, loss=None):
         _check(self.lib, self.lib.asteroid_stage_forward(self.h, mb, _ptr(x), _ptr(labels), _ptr(y), _ptr(loss)))
+
+    def set_forward_stream(self, stream):
+        _check(self.lib, self.lib.asteroid_stage_set_forward_stream(self.h, C.c_void_p(stream or 0)))
 
     def backward(self, mb, dy=None, dx=None):
         _check(self.lib, self.lib.asteroid_stage_backward(self.h, mb, _ptr(dy), _ptr(dx)))

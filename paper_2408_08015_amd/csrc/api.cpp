@@ -91,6 +91,13 @@ void free_stage(ast::Stage& s) {
   s.slots.clear();
   for (hipEvent_t ev : s.fork_ev) (void)hipEventDestroy(ev);
   s.fork_ev.clear();
+  for (hipEvent_t ev : s.fwd_done) (void)hipEventDestroy(ev);
+  for (hipEvent_t ev : s.bwd_done) (void)hipEventDestroy(ev);
+  s.fwd_done.clear();
+  s.bwd_done.clear();
+  if (s.round_ev) (void)hipEventDestroy(s.round_ev);
+  s.round_ev = nullptr;
+  s.fwd_stream = nullptr;
   if (s.join_ev) (void)hipEventDestroy(s.join_ev);
   if (s.side) (void)hipStreamDestroy(s.side);
   s.join_ev = nullptr;
@@ -111,6 +118,15 @@ std::vector<float> initial_params(const ast::Stage& s) {
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// waits for everything the stage has enqueued: the forward stream (if any), then the main stream
+hipError_t sync_stage(ast::Stage& s) {
+  if (s.fwd_stream) {
+    hipError_t e = hipStreamSynchronize(s.fwd_stream);
+    if (e != hipSuccess) return e;
+  }
+  return hipStreamSynchronize(s.stream);
+}
 }  // namespace
 
 namespace ast {
@@ -205,6 +221,26 @@ ast_status asteroid_stage_create(const ast_layer* layers, int32_t n_layers, cons
   return AST_OK;
 }
 
+ast_status asteroid_stage_set_forward_stream(asteroid_stage* h, void* hip_stream) {
+  if (!h) return fail(AST_EINVAL, "set_forward_stream: NULL stage");
+  ast::Stage& s = h->s;
+  if (s.next_fwd != 0 || s.next_bwd != 0) return fail(AST_ESTATE, "set_forward_stream: only between rounds");
+  HIPCHK(sync_stage(s), "set_forward_stream");
+  hipStream_t f = static_cast<hipStream_t>(hip_stream);
+  if (f == s.stream) f = nullptr;
+  if (f && s.fwd_done.empty()) {
+    for (int k = 0; k < 2 * s.cfg.K + 1; ++k) {
+      hipEvent_t ev;
+      HIPCHK(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "set_forward_stream: event");
+      if (k == 2 * s.cfg.K) s.round_ev = ev;
+      else (k < s.cfg.K ? s.fwd_done : s.bwd_done).push_back(ev);
+    }
+  }
+  s.bwd_done_set.assign(s.cfg.K, 0);
+  s.fwd_stream = f;
+  return AST_OK;
+}
+
 ast_status asteroid_stage_forward(asteroid_stage* h, int32_t mb, const void* x_dev, const int32_t* labels_dev,
                                   void* y_dev, float* loss_dev) {
   if (!h) return fail(AST_EINVAL, "forward: NULL stage");
@@ -277,7 +313,7 @@ ast_status asteroid_stage_step(asteroid_stage* h, float lr, float momentum) {
 
 void asteroid_stage_destroy(asteroid_stage* h) {
   if (!h) return;
-  (void)hipStreamSynchronize(h->s.stream);
+  (void)sync_stage(h->s);
   for (hipEvent_t e : h->prof.events) (void)hipEventDestroy(e);
   free_stage(h->s);
   delete h;
@@ -288,7 +324,7 @@ size_t asteroid_stage_num_params(const asteroid_stage* h) { return h ? h->s.npar
 static ast_status copy_flat(asteroid_stage* h, float* dev, float* host_out, const float* host_in, const char* what) {
   if (!h || (!host_out && !host_in)) return fail(AST_EINVAL, std::string(what) + ": NULL argument");
   ast::Stage& s = h->s;
-  HIPCHK(hipStreamSynchronize(s.stream), what);
+  HIPCHK(sync_stage(s), what);
   if (host_in) HIPCHK(hipMemcpy(dev, host_in, s.nparams * sizeof(float), hipMemcpyHostToDevice), what);
   else HIPCHK(hipMemcpy(host_out, dev, s.nparams * sizeof(float), hipMemcpyDeviceToHost), what);
   return AST_OK;
@@ -352,7 +388,7 @@ ast_status asteroid_stage_debug_activation(asteroid_stage* h, int32_t mb, int32_
   if (id == s.final_act && !s.loss_tail && !s.final_in_slot) return fail(AST_EINVAL, "debug_activation: the stage output lives in the caller's buffer");
   if (n_out) *n_out = A.elems;
   if (!host_out) return AST_OK;
-  HIPCHK(hipStreamSynchronize(s.stream), "debug_activation");
+  HIPCHK(sync_stage(s), "debug_activation");
   const char* src = s.slots[s.mb_slot[mb]] + A.slot_off;
   if (A.esize == 4) {
     HIPCHK(hipMemcpy(host_out, src, A.bytes, hipMemcpyDeviceToHost), "debug_activation");
@@ -386,7 +422,7 @@ ast_status asteroid_stage_profile_begin(asteroid_stage* h, const char* filter, i
 ast_status asteroid_stage_profile_end(asteroid_stage* h) {
   if (!h) return fail(AST_EINVAL, "profile_end: NULL stage");
   h->prof_on = false;
-  HIPCHK(hipStreamSynchronize(h->s.stream), "profile_end");
+  HIPCHK(sync_stage(h->s), "profile_end");
   ast::Profiler& p = h->prof;
   h->prof_result.clear();
   for (size_t i = 0; i < p.used; ++i) {

@@ -18,6 +18,7 @@ struct Ctx {
   char* slot;
   int final_act;
   char* ws;  // workspace of this call: the stage's own, or the static array (backward_static)
+  hipStream_t st;  // stream of this pass
   bool forked = false;
 };
 
@@ -34,6 +35,8 @@ inline void* grad_ptr(Ctx& c, int id) {
   return c.ws + c.s.acts[id].grad_off;
 }
 inline char* scratch(Ctx& c, const Op& op) { return c.ws + c.s.scratch_off + op.sc_off; }
+// scratch of the forward pass (BatchNorm statistics partials): always in the stage's own workspace
+inline char* fscratch(Ctx& c, const Op& op) { return c.s.ws + c.s.fscratch_off + op.fsc_off; }
 // Stream for a weight-gradient kernel.  Nothing later in the same backward pass reads a
 // parameter gradient, so these kernels leave the dependency chain: they run on the stage's
 // second stream, ordered after all work enqueued so far on the main stream, and the pass
@@ -61,7 +64,7 @@ typedef const bf16_t* cb;
 
 void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
   Stage& s = c.s;
-  hipStream_t st = s.stream;
+  hipStream_t st = c.st;
   const Act& I = s.acts[op.in];
   const int HW = I.h * I.w;
   if (op.absorbed) return;
@@ -77,7 +80,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
     case OP_CONV_PW:
       pw_conv_f32(st, s.wpack + op.wp_off, (cf)act_ptr(c, op.in), (float*)act_ptr(c, op.out),
                   op.has_bias ? s.W + op.b_off : nullptr, nullptr, I.n, op.cin, op.cout, HW,
-                  op.stats_op >= 0 ? reinterpret_cast<double*>(scratch(c, s.ops[op.stats_op])) : nullptr);
+                  op.stats_op >= 0 ? reinterpret_cast<double*>(fscratch(c, s.ops[op.stats_op])) : nullptr);
       break;
     case OP_CONV_DW:
     {
@@ -88,7 +91,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
         const Act& BI = s.acts[bn.in];
         float* aux = reinterpret_cast<float*>(c.slot + bn.aux_off);
         x = (cf)act_ptr(c, bn.in);
-        bi.ws = reinterpret_cast<const double*>(scratch(c, bn));
+        bi.ws = reinterpret_cast<const double*>(fscratch(c, bn));
         bi.gamma = s.W + bn.w_off; bi.beta = s.W + bn.b_off;
         bi.stat = aux; bi.ss = aux + 2 * I.c; bi.running = s.running + bn.run_off;
         bi.count = (double)BI.n * BI.h * BI.w; bi.eps = bn.eps;
@@ -97,7 +100,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       }
       dw3x3_fwd_f32(st, x, s.W + op.w_off, (float*)act_ptr(c, op.out), I.n, I.c, I.h, I.w, op.stride,
                     op.bn_in_op >= 0 ? &bi : nullptr,
-                    op.bn_out_op >= 0 ? reinterpret_cast<double*>(scratch(c, s.ops[op.bn_out_op])) : nullptr);
+                    op.bn_out_op >= 0 ? reinterpret_cast<double*>(fscratch(c, s.ops[op.bn_out_op])) : nullptr);
       break;
     }
     case OP_CONV_GK:
@@ -123,7 +126,7 @@ void fwd_op(Ctx& c, const Op& op, const int32_t* labels, float* loss) {
       break;
     case OP_BN: {
       float* aux = reinterpret_cast<float*>(c.slot + op.aux_off);
-      double* ws = reinterpret_cast<double*>(scratch(c, op));
+      double* ws = reinterpret_cast<double*>(fscratch(c, op));
       cf x = (cf)act_ptr(c, op.in);
       if (!op.bn_stats_given && !op.bn_lazy && op.act != 4 && bn_onepass_fits(I.n, HW)) {  // small tensor: one launch
         bn_fwd_onepass_f32(st, x, s.W + op.w_off, s.W + op.b_off, op.skip >= 0 ? (cf)act_ptr(c, op.skip) : nullptr,
@@ -467,19 +470,33 @@ ast_status check_launch(std::string& err, const char* what) {
 
 ast_status run_forward(Stage& s, int slot, const void* x, const int32_t* labels, void* y, float* loss,
                        std::string& err) {
-  Ctx c{s, s.slots[slot], final_act_of(s), s.ws};
+  const bool two = s.fwd_stream != nullptr;
+  Ctx c{s, s.slots[slot], final_act_of(s), s.ws, two ? s.fwd_stream : s.stream};
   s.cur_y = y;
   s.cur_dy = nullptr;
   s.cur_dx = nullptr;
-  copy_bytes(s.stream, x, c.slot + s.acts[0].slot_off, s.acts[0].bytes);
+  if (two) {
+    if (s.next_fwd == 0) {
+      // a round's first forward starts behind whatever the main stream holds at this moment: the previous
+      // round's backward passes and weight update (a fork from the main stream, so a caller may also capture
+      // a whole round into a graph from there)
+      (void)hipEventRecord(s.round_ev, s.stream);
+      (void)hipStreamWaitEvent(c.st, s.round_ev, 0);
+      s.bwd_done_set.assign(s.bwd_done_set.size(), 0);
+    }
+    if (s.bwd_done_set[slot]) (void)hipStreamWaitEvent(c.st, s.bwd_done[slot], 0);  // the slot's previous reader
+  }
+  copy_bytes(c.st, x, c.slot + s.acts[0].slot_off, s.acts[0].bytes);
   for (const Op& op : s.ops) fwd_op(c, op, labels, loss);
   if (s.final_in_slot && !s.loss_tail)
-    copy_bytes(s.stream, c.slot + s.acts[s.final_act].slot_off, y, s.acts[s.final_act].bytes);
+    copy_bytes(c.st, c.slot + s.acts[s.final_act].slot_off, y, s.acts[s.final_act].bytes);
+  if (two) (void)hipEventRecord(s.fwd_done[slot], c.st);
   return check_launch(err, "forward");
 }
 
 ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, char* static_ws, std::string& err) {
-  Ctx c{s, s.slots[slot], final_act_of(s), static_ws ? static_ws : s.ws};
+  Ctx c{s, s.slots[slot], final_act_of(s), static_ws ? static_ws : s.ws, s.stream};
+  if (s.fwd_stream) (void)hipStreamWaitEvent(s.stream, s.fwd_done[slot], 0);  // the stash of this micro-batch
   if (static_ws) static_scratch_zero(s.stream, static_ws, s.ws_bytes);  // what the stage's own workspace was at create
   s.cur_y = nullptr;
   s.cur_dy = dy;
@@ -501,6 +518,10 @@ ast_status run_backward(Stage& s, int slot, const void* dy, void* dx, char* stat
   if (c.forked) {  // join: whatever follows on the main stream sees every gradient
     (void)hipEventRecord(s.join_ev, s.side);
     (void)hipStreamWaitEvent(s.stream, s.join_ev, 0);
+  }
+  if (s.fwd_stream) {  // the slot is free for a later forward from here on
+    (void)hipEventRecord(s.bwd_done[slot], s.stream);
+    s.bwd_done_set[slot] = 1;
   }
   return check_launch(err, "backward");
 }

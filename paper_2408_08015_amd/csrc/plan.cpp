@@ -531,9 +531,19 @@ ast_status build_plan(Stage& s, std::string& err) {
     op.sc_off = sc;
     sc += align_up(need, 256);
   }
+  // The forward pass has scratch of its own (BatchNorm statistics partials), so that the forward of one
+  // micro-batch may run beside the backward of another.
+  size_t fsc = 0;
+  for (Op& op : s.ops) {
+    if (op.kind != OP_BN) continue;
+    const Act& I = s.acts[op.in];
+    op.fsc_off = fsc;
+    fsc += align_up(std::max(bn_ws_doubles(I.c, I.n, I.h * I.w), (size_t)2 * I.c * op.given_parts) * sizeof(double), 256);
+  }
   s.scratch_off = align_up(goff, 256);
   s.scratch_bytes = align_up(sc, 256);
-  s.ws_bytes = s.scratch_off + s.scratch_bytes + 256;
+  s.fscratch_off = s.scratch_off + s.scratch_bytes;
+  s.ws_bytes = s.fscratch_off + align_up(fsc, 256) + 256;
   return AST_OK;
 }
 

@@ -79,6 +79,7 @@ struct Op {
   size_t sh_off = 0, sh2_off = 0;     // bf16 weight copies (elements) in the shadow arena
   size_t wp_off = 0, wp2_off = 0;     // fp32 pointwise conv: packed forward / dgrad operands (floats)
   size_t sc_off = 0;                  // this op's private scratch region (bytes past scratch_off)
+  size_t fsc_off = 0;                 // BatchNorm: its forward-pass scratch (bytes past fscratch_off)
   // fp32 BatchNorm passes taken over by the depthwise conv next to them:
   bool bn_lazy = false;               // BatchNorm(+act) feeding a depthwise conv: the output is never written; the
                                       // conv normalises on load (forward and backward) and finishes the statistics
@@ -124,6 +125,7 @@ struct Stage {
   char* ws = nullptr;        // workspace: activation gradients + scratch
   size_t ws_bytes = 0, grad_bytes = 0;
   size_t scratch_off = 0, scratch_bytes = 0;  // per-op scratch regions (masked gradients, partials)
+  size_t fscratch_off = 0;                    // per-op scratch of the forward pass (behind the backward's)
 
   // fp32 stages: the per-layer reductions of weight-gradient partials into G, batched into one
   // launch at the end of every backward pass (device-side task table, built at create)
@@ -155,6 +157,16 @@ struct Stage {
   std::vector<hipEvent_t> fork_ev;
   hipEvent_t join_ev = nullptr;
   unsigned fork_i = 0;
+
+  // Optional stream of the forward passes (NULL: they run on `stream`).  With K >= 2 the forward of a later
+  // micro-batch and the backward of an earlier one touch different stash slots and different scratch, so the
+  // two passes may overlap; the events order what does depend: backward(mb) behind forward(mb), a forward that
+  // reuses a slot behind the backward that released it, the first forward of a round behind the weight update
+  // (behind the main stream's position when that forward is called).
+  hipStream_t fwd_stream = nullptr;
+  std::vector<hipEvent_t> fwd_done, bwd_done;  // per slot
+  std::vector<char> bwd_done_set;              // the slot's bwd_done event has been recorded in this round
+  hipEvent_t round_ev = nullptr;
 
   // 1F1B state
   int next_fwd = 0, next_bwd = 0;

@@ -41,10 +41,11 @@ def run_oracle(cfg, inp, K=1, rounds=2, keep_acts=False):
     return res, st
 
 
-def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None, static_backward=False):
+def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None, static_backward=False, forward_stream=False):
     """Returns the per-round results of the HIP stage (numpy fp32) and, if asked, the
     activations of `debug_layers` for micro-batch 0 of round 0.  static_backward: the backward
-    passes go through asteroid_stage_backward_static."""
+    passes go through asteroid_stage_backward_static.  forward_stream: the forward passes run on
+    a second stream (asteroid_stage_set_forward_stream)."""
     import torch
     import paper_2408_08015_amd as A
     dev = torch.device("cuda:0")
@@ -52,6 +53,10 @@ def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None, static_backward=False):
     st = A.Stage(cfg.layers, cfg.B, cfg.M, K, cfg.in_shape, cfg.dtype, cfg.layout, cfg.needs_input_grad,
                  stream=torch.cuda.current_stream().cuda_stream)
     st.set_params(inp["params"])
+    fs = None
+    if forward_stream:
+        fs = torch.cuda.Stream()  # default priority
+        st.set_forward_stream(fs.cuda_stream)
     x = torch.from_numpy(inp["x"]).to(dev).to(tdt).contiguous()
     B, M = cfg.B, cfg.M
     if cfg.loss_tail:
@@ -80,6 +85,7 @@ def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None, static_backward=False):
                 except A.AsteroidError:
                     pass
 
+    torch.cuda.synchronize()  # the inputs exist before either stream reads them
     for r in range(rounds):
         for m in range(min(K, M)):
             fwd(m, r)
