@@ -252,7 +252,8 @@ def committed_traffic(workload, fam):
 BENCH_LR = 1e-9
 
 
-def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3, K=1, forward_stream=False):
+def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3, K=1, forward_stream=False,
+            two_streams=True):
     """One configuration: returns its record for the JSON line.  K = micro-batches in flight (stash
     slots); forward_stream: the forward passes run on a second stream beside the backward passes."""
     import torch
@@ -270,8 +271,8 @@ def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3,
     st.set_params(inp["params"])
     fwd_stream = None
     if forward_stream:
-        fwd_stream = torch.cuda.Stream()   # default priority
-        st.set_forward_stream(fwd_stream.cuda_stream)
+        fwd_stream = A.stream_create()     # not torch.cuda.Stream(): its pool holds 32 streams per priority, and
+        st.set_forward_stream(fwd_stream)  # the runtime deals all streams of a process onto four hardware queues
     B, M = cfg.B, cfg.M
     x = torch.from_numpy(inp["x"]).to(dev).to(tdt).contiguous()
     if cfg.loss_tail:
@@ -376,17 +377,19 @@ def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3,
             print(line, file=sys.stderr)
     mem = st.memory()
     st.close()
+    if fwd_stream:
+        A.stream_destroy(fwd_stream)
     # ---- the same rounds with K = 3 stashes and the forward passes on a second stream (the forward of a later
     # micro-batch runs beside the backward of an earlier one; bit-identical results): timed the same way,
     # reported beside the headline figure, never in its place
     two = None
-    if K == 1 and not forward_stream and cfg.M >= 2:
+    if two_streams and K == 1 and not forward_stream and cfg.M >= 2:
         K2 = min(3, cfg.M)
         st2 = A.Stage(cfg.layers, cfg.B, cfg.M, K2, cfg.in_shape, cfg.dtype, cfg.layout, cfg.needs_input_grad,
                       stream=stream.cuda_stream)
         st2.set_params(inp["params"])
-        fs2 = torch.cuda.Stream()   # default priority
-        st2.set_forward_stream(fs2.cuda_stream)
+        fs2 = A.stream_create()
+        st2.set_forward_stream(fs2)
 
         def round2():
             for m in range(K2):
@@ -408,6 +411,7 @@ def measure(workload, steps, warmup, cpu=True, profile_all=False, prof_rounds=3,
         two = {"K": K2, "forward_stream": True, "ms_per_step": round(ms2, 4),
                "value": round(M * B / (ms2 * 1e-3), 1), "unit": "samples/s", "act_stashes": K2}
         st2.close()
+        A.stream_destroy(fs2)
     del xs, ys, dys, dxs, x, y, dy, dx
     torch.cuda.empty_cache()
     rec = {
@@ -435,7 +439,7 @@ def run(args):
     recs = {}
     for w in workloads:
         recs[w], cfg = measure(w, args.steps, args.warmup, cpu=not args.no_cpu_baseline, profile_all=args.profile_all,
-                               K=args.K, forward_stream=args.forward_stream)
+                               K=args.K, forward_stream=args.forward_stream, two_streams=not args.no_two_streams)
         if w == head:
             head_cfg = cfg
     h = recs[head]
@@ -500,6 +504,7 @@ def main():
     ap.add_argument("--workload", default=None, help="one configuration only (default: cfg1 .. cfg5, headline cfg4)")
     ap.add_argument("--profile-all", action="store_true", help="time every kernel, table on stderr")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-two-streams", action="store_true", help="skip the extra K = 3 / forward-stream timing")
     ap.add_argument("--K", type=int, default=1, help="micro-batches in flight (stash slots): K forward passes, then 1F1B")
     ap.add_argument("--forward-stream", action="store_true",
                     help="forward passes on a second stream (needs --K 2 or more to overlap anything)")

@@ -152,6 +152,15 @@ ast_status asteroid_stage_backward(asteroid_stage* s, int32_t mb, const void* dy
  * the stage's work.  AST_ESTATE inside a round (after a forward and before the step). */
 ast_status asteroid_stage_set_forward_stream(asteroid_stage* s, void* hip_stream);
 
+/* A stream for the call above, for callers without a stream API of their own at hand: a new hipStream_t
+ * of default priority that does not synchronise with the NULL stream (*out; NULL on error), and its
+ * release (waits for nothing: the caller has synchronised; NULL is a no-op).  A process has few hardware
+ * queues (four by default) and the runtime deals streams onto them: two streams meant to overlap must not
+ * land on one queue, which is likelier the more streams the process holds - a framework's stream pool
+ * creates dozens.  Creating the few streams that are used, and destroying them after use, avoids that. */
+ast_status asteroid_stream_create(void** out);
+ast_status asteroid_stream_destroy(void* hip_stream);
+
 /* For callers that cannot allocate or let a library allocate on their behalf (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): asteroid_stage_backward with the
  * stage's workspace - activation gradients, per-operator scratch, reduction partials - taken from

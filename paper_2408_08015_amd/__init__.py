@@ -11,4 +11,6 @@ from .binding import (  # noqa: F401
     plan_memory,
     lib_path,
     load_library,
+    stream_create,
+    stream_destroy,
 )

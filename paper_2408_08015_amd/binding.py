@@ -55,6 +55,8 @@ def load_library():
     lib.asteroid_stage_create.argtypes = [C.POINTER(ast_layer), i32, C.POINTER(ast_stage_cfg), vp, C.POINTER(vp)]
     lib.asteroid_stage_forward.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.asteroid_stage_set_forward_stream.argtypes = [vp, vp]
+    lib.asteroid_stream_create.argtypes = [C.POINTER(vp)]
+    lib.asteroid_stream_destroy.argtypes = [vp]
     lib.asteroid_stage_backward.argtypes = [vp, i32, vp, vp]
     lib.asteroid_stage_backward_static.argtypes = [vp, i32, vp, vp]
     lib.asteroid_stage_step.argtypes = [vp, C.c_float, C.c_float]
@@ -114,6 +116,19 @@ def _marshal_cfg(B, M, K, in_shape, dtype, layout, needs_input_grad):
     cfg.layout = LAYOUTS[layout]
     cfg.needs_input_grad = int(bool(needs_input_grad))
     return cfg
+
+
+def stream_create():
+    """A new non-blocking HIP stream of default priority; returns its handle (an int)."""
+    lib = load_library()
+    h = C.c_void_p()
+    _check(lib, lib.asteroid_stream_create(C.byref(h)))
+    return h.value
+
+
+def stream_destroy(handle):
+    lib = load_library()
+    _check(lib, lib.asteroid_stream_destroy(C.c_void_p(handle or 0)))
 
 
 def kp(P, p):

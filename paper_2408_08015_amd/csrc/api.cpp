@@ -221,6 +221,21 @@ ast_status asteroid_stage_create(const ast_layer* layers, int32_t n_layers, cons
   return AST_OK;
 }
 
+ast_status asteroid_stream_create(void** out) {
+  if (!out) return fail(AST_EINVAL, "stream_create: NULL argument");
+  *out = nullptr;
+  hipStream_t st;
+  HIPCHK(hipStreamCreateWithFlags(&st, hipStreamNonBlocking), "stream_create");
+  *out = st;
+  return AST_OK;
+}
+
+ast_status asteroid_stream_destroy(void* hip_stream) {
+  if (!hip_stream) return AST_OK;
+  HIPCHK(hipStreamDestroy(static_cast<hipStream_t>(hip_stream)), "stream_destroy");
+  return AST_OK;
+}
+
 ast_status asteroid_stage_set_forward_stream(asteroid_stage* h, void* hip_stream) {
   if (!h) return fail(AST_EINVAL, "set_forward_stream: NULL stage");
   ast::Stage& s = h->s;

@@ -55,8 +55,8 @@ def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None, static_backward=False, f
     st.set_params(inp["params"])
     fs = None
     if forward_stream:
-        fs = torch.cuda.Stream()  # default priority
-        st.set_forward_stream(fs.cuda_stream)
+        fs = A.stream_create()
+        st.set_forward_stream(fs)
     x = torch.from_numpy(inp["x"]).to(dev).to(tdt).contiguous()
     B, M = cfg.B, cfg.M
     if cfg.loss_tail:
@@ -104,6 +104,8 @@ def run_hip(cfg, inp, K=1, rounds=2, debug_layers=None, static_backward=False, f
                         W=st.get_params()))
     mem = st.memory()
     st.close()
+    if fs:
+        A.stream_destroy(fs)
     return res, dbg, mem
 
 
