@@ -647,6 +647,10 @@ def test_bf16_conv(A, cin, cout, k, hw, B):
     (64, 64, 63, 63, 2, False),     # the longest image row the halo buffer takes; 7938 pixels: ragged last tile
     (64, 128, 40, 40, 3, True),     # 4800 pixels over persistent blocks; second conv: ReLU mask in the input gradient
     (256, 256, 12, 10, 2, True),    # 256-channel weight-gradient tiles (splits over 240 pixels), masks, biases
+    (256, 128, 20, 24, 2, False),   # 128-channel tiles with two taps per K-tile: four slices, ragged pixel tiles
+    (128, 256, 14, 14, 3, False),   # its input gradient is the 256 -> 128 product (four slices, 588 pixels)
+    (192, 96, 33, 17, 2, True),     # an odd number of slices, 96 of 128 channels live, mask in the second layer
+    (64, 64, 60, 62, 18, False),    # 66 960 pixels = 262 tiles over 256 blocks: a second, six-pixel tile per block
 ])
 def test_bf16_conv_halo_and_transposed_wgrad_shapes(A, cin, cout, h, w, B, two):
     """Shapes chosen for the LDS-halo convolution (forward / input gradient) and the transposed-read weight
