@@ -138,9 +138,10 @@ def golden_velocity(cfg, n):
     return (rng.standard_normal(n) * 0.05).astype(np.float32)
 
 
-def run_hip_one_round(cfg, inp, v0=None, K=1):
-    """One HPP-Round on the GPU at the launch configuration bench.py times (K = 1 by default).
-    Returns y, loss, dx, G (before the update), W (after it) as numpy arrays."""
+def run_hip_one_round(cfg, inp, v0=None, K=1, forward_stream=False):
+    """One HPP-Round on the GPU at the launch configurations bench.py times (K = 1 on one stream; K = 3
+    with the forward passes on a second stream).  Returns y, loss, dx, G (before the update), W (after
+    it) as numpy arrays."""
     import torch
     import paper_2408_08015_amd as A
     dev = torch.device("cuda:0")
@@ -150,6 +151,10 @@ def run_hip_one_round(cfg, inp, v0=None, K=1):
     st.set_params(inp["params"])
     if v0 is not None:
         st.set_velocity(v0)
+    fs = None
+    if forward_stream:
+        fs = A.stream_create()
+        st.set_forward_stream(fs)
     x = torch.from_numpy(inp["x"]).to(dev).to(tdt).contiguous()
     B, M = cfg.B, cfg.M
     if cfg.loss_tail:
@@ -169,6 +174,7 @@ def run_hip_one_round(cfg, inp, v0=None, K=1):
         st.forward(m, xs[m], labs[m] if labs is not None else None, ys[m],
                    losses[4 * m:4 * m + 1] if cfg.loss_tail else None)
 
+    torch.cuda.synchronize()  # the inputs exist before either stream reads them
     for m in range(min(K, M)):
         fwd(m)
     for m in range(M):
@@ -183,6 +189,8 @@ def run_hip_one_round(cfg, inp, v0=None, K=1):
                dx=torch.cat(dxs).float().cpu().numpy() if dxs is not None else None, G=G, W=st.get_params(),
                V=st.get_velocity())
     st.close()
+    if fs:
+        A.stream_destroy(fs)
     return out
 
 

@@ -51,6 +51,25 @@ def test_forward_stream_is_bit_identical(A, name, K):
             assert a["loss"] == b["loss"], (name, K, r)
 
 
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5"])
+def test_full_size_forward_stream_is_bit_identical(A, name):
+    """bench.py's second timing configuration (K = 3 stashes, forward passes on a second stream) at the
+    full size of the benchmark configurations: the same bits as the K = 1, one-stream round that the
+    full-size tests score against the stored oracle values."""
+    from asteroid_workloads import get_config
+    cfg = get_config(name)
+    inp = gen.make_inputs(cfg)
+    v0 = harness.golden_velocity(cfg, inp["params"].size)
+    one = harness.run_hip_one_round(cfg, inp, v0=v0, K=1)
+    two = harness.run_hip_one_round(cfg, inp, v0=v0, K=3, forward_stream=True)
+    for k in ("y", "dx", "G", "W", "V"):
+        if one[k] is None:
+            continue
+        assert np.isfinite(one[k]).all(), (name, k)
+        assert np.array_equal(one[k], two[k]), (name, k)
+    assert one["loss"] == two["loss"]
+
+
 def test_forward_stream_with_one_stash_and_switching_back(A):
     """K = 1 leaves nothing to overlap (every forward waits for the slot's backward) and must still be
     right; NULL returns to one stream; the call is refused inside a round."""
