@@ -51,6 +51,19 @@ def test_forward_stream_is_bit_identical(A, name, K):
             assert a["loss"] == b["loss"], (name, K, r)
 
 
+@pytest.mark.parametrize("name", ["cfg2", "cfg5"])
+def test_forward_stream_with_the_allocation_free_backward(A, name):
+    """asteroid_stage_backward_static beside forward passes on the second stream: the backward's workspace is
+    the static array, the forward's scratch stays in the stage's own workspace."""
+    cfg = CASES[name]()
+    inp = gen.make_inputs(cfg, randomize_affine=True)
+    one, _, _ = harness.run_hip(cfg, inp, K=2, rounds=2)
+    two, _, _ = harness.run_hip(cfg, inp, K=2, rounds=2, forward_stream=True, static_backward=True)
+    for r, (a, b) in enumerate(zip(one, two)):
+        for k in ("y", "dx", "G", "W"):
+            assert np.array_equal(a[k], b[k], equal_nan=True), (name, r, k)
+
+
 @pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5"])
 def test_full_size_forward_stream_is_bit_identical(A, name):
     """bench.py's second timing configuration (K = 3 stashes, forward passes on a second stream) at the
