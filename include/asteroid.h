@@ -18,8 +18,14 @@
  * weight copies, the activation stash and its workspace; all are allocated in
  * asteroid_stage_create and none in forward/backward/step.
  *
- * All work is enqueued on the HIP stream given at creation and is asynchronous to
- * the host.  Every function returns an ast_status; nothing throws or aborts.
+ * All work is enqueued on the HIP stream given at creation (the forward passes on a
+ * second one after asteroid_stage_set_forward_stream) and is asynchronous to the host.
+ * forward / backward / step consist of kernel launches and event waits only - no
+ * allocation, no memset, no host synchronisation - so the calls of a whole round may be
+ * recorded into a HIP graph by stream capture on the creation stream and replayed (the
+ * buffers, lr and momentum of the recording are then the graph's; the checks of the
+ * call discipline happen while recording).
+ * Every function returns an ast_status; nothing throws or aborts.
  * asteroid_last_error() gives a thread-local message for the last failure.
  */
 #ifndef ASTEROID_H
