@@ -40,36 +40,46 @@ __device__ __forceinline__ bf16x8 ld_frag_2x4(const bf16_t* p0, const bf16_t* p1
   return __builtin_bit_cast(bf16x8, v);
 }
 
-// copy S rows of 64 bf16 (row stride `ld` elements in global memory) into LDS [S][RS]
-__device__ __forceinline__ void stage_rows(bf16_t* dst, const bf16_t* src, long ld, int S) {
-  for (int c = threadIdx.x; c < S * 8; c += blockDim.x) {
-    int row = c >> 3, part = c & 7;
-    *reinterpret_cast<uint4*>(dst + row * RS + part * 8) =
-        *reinterpret_cast<const uint4*>(src + (long)row * ld + part * 8);
+// Staging of two [S][64] tensors (row strides ld0 / ld1 elements in global memory) into LDS, each as a row copy
+// [S][RS] (R0 / R1) and / or a transposed copy [64][S + 8] (T0 / T1), from ONE set of loads: a task is 4 rows x 8
+// columns of both tensors, and its eight 16-byte loads are requested before the first LDS write (loops with one
+// load, one wait and one write per trip made a block wait for a dozen memory round trips one after the other).
+__device__ __forceinline__ void write_rows4(bf16_t* dst, const uint4 (&v)[4], int rq, int cg) {
+#pragma unroll
+  for (int r = 0; r < 4; ++r) *reinterpret_cast<uint4*>(dst + (rq * 4 + r) * RS + cg * 8) = v[r];
+}
+__device__ __forceinline__ void write_T4(bf16_t* dst, const uint4 (&v)[4], int rq, int cg, int TS) {
+  const uint32_t* r0 = reinterpret_cast<const uint32_t*>(&v[0]);
+  const uint32_t* r1 = reinterpret_cast<const uint32_t*>(&v[1]);
+  const uint32_t* r2 = reinterpret_cast<const uint32_t*>(&v[2]);
+  const uint32_t* r3 = reinterpret_cast<const uint32_t*>(&v[3]);
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    uint2 lo, hi;
+    lo.x = (r0[w] & 0xffffu) | (r1[w] << 16);
+    lo.y = (r2[w] & 0xffffu) | (r3[w] << 16);
+    hi.x = (r0[w] >> 16) | (r1[w] & 0xffff0000u);
+    hi.y = (r2[w] >> 16) | (r3[w] & 0xffff0000u);
+    *reinterpret_cast<uint2*>(dst + (cg * 8 + 2 * w) * TS + rq * 4) = lo;
+    *reinterpret_cast<uint2*>(dst + (cg * 8 + 2 * w + 1) * TS + rq * 4) = hi;
   }
 }
-// transposed copy into LDS [64][S + 8]: tasks of 4 rows x 8 columns
-__device__ __forceinline__ void stage_rows_T(bf16_t* dst, const bf16_t* src, long ld, int S) {
+template <bool R0, bool T0, bool R1, bool T1>
+__device__ __forceinline__ void stage_pair(bf16_t* rows0, bf16_t* tr0, const bf16_t* src0, long ld0, bf16_t* rows1,
+                                           bf16_t* tr1, const bf16_t* src1, long ld1, int S) {
   const int TS = S + 8;
   for (int t = threadIdx.x; t < (S / 4) * 8; t += blockDim.x) {
-    int rq = t >> 3, cg = t & 7;
-    uint4 v[4];
+    const int rq = t >> 3, cg = t & 7;
+    uint4 a[4], c[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) v[r] = *reinterpret_cast<const uint4*>(src + (long)(rq * 4 + r) * ld + cg * 8);
-    const uint32_t* r0 = reinterpret_cast<const uint32_t*>(&v[0]);
-    const uint32_t* r1 = reinterpret_cast<const uint32_t*>(&v[1]);
-    const uint32_t* r2 = reinterpret_cast<const uint32_t*>(&v[2]);
-    const uint32_t* r3 = reinterpret_cast<const uint32_t*>(&v[3]);
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      uint2 lo, hi;
-      lo.x = (r0[w] & 0xffffu) | (r1[w] << 16);
-      lo.y = (r2[w] & 0xffffu) | (r3[w] << 16);
-      hi.x = (r0[w] >> 16) | (r1[w] & 0xffff0000u);
-      hi.y = (r2[w] >> 16) | (r3[w] & 0xffff0000u);
-      *reinterpret_cast<uint2*>(dst + (cg * 8 + 2 * w) * TS + rq * 4) = lo;
-      *reinterpret_cast<uint2*>(dst + (cg * 8 + 2 * w + 1) * TS + rq * 4) = hi;
+    for (int r = 0; r < 4; ++r) {
+      a[r] = *reinterpret_cast<const uint4*>(src0 + (long)(rq * 4 + r) * ld0 + cg * 8);
+      c[r] = *reinterpret_cast<const uint4*>(src1 + (long)(rq * 4 + r) * ld1 + cg * 8);
     }
+    if (R0) write_rows4(rows0, a, rq, cg);
+    if (R1) write_rows4(rows1, c, rq, cg);
+    if (T0) write_T4(tr0, a, rq, cg, TS);
+    if (T1) write_T4(tr1, c, rq, cg, TS);
   }
 }
 
@@ -89,16 +99,16 @@ __global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __rest
   const int col = lane & 31, g = lane >> 5;
   const long ld = 3L * D;
   const bf16_t* base = qkv + (long)b * S * ld + h * HD;
-  stage_rows(sK, base + D, ld, S);
-  stage_rows_T(sVt, base + 2 * D, ld, S);
-  __syncthreads();
+  // everything this wavefront reads from global memory is requested before the staging copies wait for theirs
   const int q0 = blockIdx.x * 128 + wave * 32;
-  if (q0 >= S) return;
-  const int q = q0 + col;
-
+  const bool live = q0 < S;
+  const int q = live ? q0 + col : 0;
   bf16x8 qf[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) qf[t] = ld_frag(base + (long)q * ld + 16 * t + 8 * g);
+  stage_pair<true, false, false, true>(sK, nullptr, base + D, ld, nullptr, sVt, base + 2 * D, ld, S);
+  __syncthreads();
+  if (!live) return;
 
   floatx16 oacc[2];
 #pragma unroll
@@ -164,13 +174,19 @@ __global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __rest
 // ------------------------------------------------------------------ backward
 // Half of Dsum[q] = sum_d dO[q][d] * O[q][d]: the 32 elements d = 16 t + 8 g + e (t < 4, e < 8) of one row, in
 // that order; Dsum = half(g = 0) + half(g = 1).  Both backward roles form it this way (bitwise the same value).
-__device__ __forceinline__ float dsum_half(const bf16_t* __restrict__ po, const bf16_t* __restrict__ pd, int g) {
+struct DsumWords { uint4 a[4], d[4]; };  // half a row of O and of dO
+__device__ __forceinline__ void dsum_load(const bf16_t* __restrict__ po, const bf16_t* __restrict__ pd, int g, DsumWords& w) {
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    w.a[t] = *reinterpret_cast<const uint4*>(po + 16 * t + 8 * g);
+    w.d[t] = *reinterpret_cast<const uint4*>(pd + 16 * t + 8 * g);
+  }
+}
+__device__ __forceinline__ float dsum_math(const DsumWords& w) {
   float s = 0.f;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    const uint4 a = *reinterpret_cast<const uint4*>(po + 16 * t + 8 * g);
-    const uint4 d = *reinterpret_cast<const uint4*>(pd + 16 * t + 8 * g);
-    const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, dw[4] = {d.x, d.y, d.z, d.w};
+    const uint32_t aw[4] = {w.a[t].x, w.a[t].y, w.a[t].z, w.a[t].w}, dw[4] = {w.d[t].x, w.d[t].y, w.d[t].z, w.d[t].w};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       s += __uint_as_float(aw[k] << 16) * __uint_as_float(dw[k] << 16);
@@ -178,6 +194,11 @@ __device__ __forceinline__ float dsum_half(const bf16_t* __restrict__ po, const 
     }
   }
   return s;
+}
+__device__ __forceinline__ float dsum_half(const bf16_t* __restrict__ po, const bf16_t* __restrict__ pd, int g) {
+  DsumWords w;
+  dsum_load(po, pd, g, w);
+  return dsum_math(w);
 }
 
 // dK, dV: a wavefront owns 32 keys (lane = key), loops over query tiles.
@@ -200,12 +221,33 @@ __device__ __forceinline__ void attention_bwd_dkv_body(const bf16_t* __restrict_
   const long ld = 3L * D;
   const bf16_t* base = qkv + (long)b * S * ld + h * HD;
   const bf16_t* dobase = d_o + (long)b * S * D + h * HD;
-  stage_rows(sQ, base, ld, S);
-  stage_rows(sdO, dobase, D, S);
-  stage_rows_T(sQt, base, ld, S);
-  stage_rows_T(sdOt, dobase, D, S);
-  for (int i = threadIdx.x; i < S; i += blockDim.x) sL[i] = lse[((long)b * H + h) * S + i];
-  for (int i = threadIdx.x; i < 2 * S; i += blockDim.x) {  // thread -> (row, half): neighbouring lanes hold the two halves
+  // Everything read from global memory is requested before the staging copies wait for theirs: this wavefront's
+  // K and V fragments, the log-sum-exp values, and the words of the first round of row sums of dO * O.
+  const int k0 = bx * 128 + wave * 32;
+  const bool live = k0 < S;
+  const int key = live ? k0 + col : 0;
+  bf16x8 kf[4], vf[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    kf[t] = ld_frag(base + D + (long)key * ld + 16 * t + 8 * g);
+    vf[t] = ld_frag(base + 2 * D + (long)key * ld + 16 * t + 8 * g);
+  }
+  const int tid = threadIdx.x;
+  const float lse_mine = tid < S ? lse[((long)b * H + h) * S + tid] : 0.f;  // blockDim.x = 256 >= S
+  DsumWords w0;
+  const bool has0 = tid < 2 * S;  // uniform per wavefront (2 S is a multiple of 64)
+  if (has0) {  // thread -> (row, half): neighbouring lanes hold the two halves
+    const long at = ((long)b * S + (tid >> 1)) * D + h * HD;
+    dsum_load(o + at, d_o + at, tid & 1, w0);
+  }
+  stage_pair<true, true, true, true>(sQ, sQt, base, ld, sdO, sdOt, dobase, D, S);
+  if (tid < S) sL[tid] = lse_mine;
+  if (has0) {
+    const float half = dsum_math(w0);
+    const float other = __shfl_xor(half, 1);
+    if (!(tid & 1)) sD[tid >> 1] = half + other;
+  }
+  for (int i = tid + (int)blockDim.x; i < 2 * S; i += blockDim.x) {  // S = 256: the second round
     const int row = i >> 1;
     const long at = ((long)b * S + row) * D + h * HD;
     const float half = dsum_half(o + at, d_o + at, i & 1);
@@ -213,15 +255,7 @@ __device__ __forceinline__ void attention_bwd_dkv_body(const bf16_t* __restrict_
     if (!(i & 1)) sD[row] = half + other;
   }
   __syncthreads();
-  const int k0 = bx * 128 + wave * 32;
-  if (k0 >= S) return;
-  const int key = k0 + col;
-  bf16x8 kf[4], vf[4];
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    kf[t] = ld_frag(base + D + (long)key * ld + 16 * t + 8 * g);
-    vf[t] = ld_frag(base + 2 * D + (long)key * ld + 16 * t + 8 * g);
-  }
+  if (!live) return;
   floatx16 dk[2], dv[2];
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
@@ -240,10 +274,17 @@ __device__ __forceinline__ void attention_bwd_dkv_body(const bf16_t* __restrict_
     }
     float p[16], ds[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      int qq = qt * 32 + acc_row(r, g);
-      p[r] = __expf(s[r] * scale - sL[qq]);
-      ds[r] = p[r] * (dp[r] - sD[qq]);
+    for (int r4 = 0; r4 < 4; ++r4) {  // registers 4 r4 .. 4 r4 + 3 are four consecutive queries: one 16-byte read each
+      const int qq = qt * 32 + acc_row(4 * r4, g);
+      const float4 l4 = *reinterpret_cast<const float4*>(sL + qq);
+      const float4 d4 = *reinterpret_cast<const float4*>(sD + qq);
+      const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = 4 * r4 + e;
+        p[r] = __expf(s[r] * scale - lv[e]);
+        ds[r] = p[r] * (dp[r] - dv4[e]);
+      }
     }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -288,13 +329,10 @@ __device__ __forceinline__ void attention_bwd_dq_body(const bf16_t* __restrict__
   const int col = lane & 31, g = lane >> 5;
   const long ld = 3L * D;
   const bf16_t* base = qkv + (long)b * S * ld + h * HD;
-  stage_rows(sK, base + D, ld, S);
-  stage_rows(sV, base + 2 * D, ld, S);
-  stage_rows_T(sKt, base + D, ld, S);
-  __syncthreads();
+  // (all global reads of this wavefront are requested before the staging copies wait for theirs)
   const int q0 = bx * 128 + wave * 32;
-  if (q0 >= S) return;
-  const int q = q0 + col;
+  const bool live = q0 < S;
+  const int q = live ? q0 + col : 0;
   bf16x8 qf[4], dof[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
@@ -302,10 +340,17 @@ __device__ __forceinline__ void attention_bwd_dq_body(const bf16_t* __restrict__
     dof[t] = ld_frag(d_o + ((long)b * S + q) * D + h * HD + 16 * t + 8 * g);
   }
   const float lq = lse[((long)b * H + h) * S + q];
-  float dq_sum;
+  DsumWords wq;
   {
     const long at = ((long)b * S + q) * D + h * HD;
-    const float half = dsum_half(o + at, d_o + at, g);
+    dsum_load(o + at, d_o + at, g, wq);
+  }
+  stage_pair<true, true, true, false>(sK, sKt, base + D, ld, sV, nullptr, base + 2 * D, ld, S);
+  __syncthreads();
+  if (!live) return;
+  float dq_sum;
+  {
+    const float half = dsum_math(wq);
     const float other = __shfl_xor(half, 32);
     dq_sum = g == 0 ? half + other : other + half;  // half(0) + half(1) in both lanes
   }
